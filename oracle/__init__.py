@@ -1,0 +1,131 @@
+"""fp64 CPU oracle of the semi-CRF forward-backward pass (TEST INFRASTRUCTURE).
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
+``bench.py`` may import this package.  It compiles ``semicrf_oracle.c`` with
+gcc (plain C, OpenMP) and calls it through ctypes; it imports nothing from the
+GPU package and the GPU package imports nothing from here.
+
+The C file's header states, passage by passage, which part of the paper each
+step follows (Eq. 1-2 prefix sums, Eq. 4 edge potential, Algorithm 1 and
+Algorithm 3 recurrences kept as full tables, the "Gradient Formulas" section).
+Every function here is pinned by ``tests/test_oracle_pins.py`` (brute-force
+enumeration, the K=1 linear-chain CRF, closed forms, finite differences,
+marginal invariants, the centring/duration-prior identity of Eq. 5, the toy
+baseline table).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "semicrf_oracle.c")
+_LIB = os.path.join(_HERE, "libsemicrf_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc; returns the path of the shared object."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True, cwd=_HERE)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        dp = ctypes.POINTER(ctypes.c_double)
+        ip = ctypes.POINTER(ctypes.c_int32)
+        lib.semicrf_oracle_fwd_bwd.restype = ctypes.c_int
+        lib.semicrf_oracle_fwd_bwd.argtypes = [dp, ip, dp, dp, dp] + [ctypes.c_int] * 6 + [dp] * 11
+        lib.semicrf_oracle_logz.restype = ctypes.c_int
+        lib.semicrf_oracle_logz.argtypes = [dp, ip, dp, dp] + [ctypes.c_int] * 6 + [dp]
+        _lib = lib
+    return _lib
+
+
+def _dptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _as_f64(a):
+    return np.ascontiguousarray(np.asarray(a), dtype=np.float64)
+
+
+@dataclass
+class OracleResult:
+    logz: np.ndarray          # [B]
+    grad_emis: np.ndarray     # [B,T,C]  d(sum_b w_b logZ_b)/d emis
+    pos_marg: np.ndarray      # [B,T,C]  P(label of token u is c)
+    grad_trans: np.ndarray    # [C,C]
+    grad_dur: np.ndarray      # [K,C]
+    grad_trans_b: np.ndarray  # [B,C,C]  per sequence (weighted by w_b)
+    grad_dur_b: np.ndarray    # [B,K,C]
+    threads: int
+    S: np.ndarray | None = None      # [B,T+1,C] centred prefix sums
+    alpha: np.ndarray | None = None  # [B,T+1,C]
+    beta: np.ndarray | None = None   # [B,T+1,C]
+    gS: np.ndarray | None = None     # [B,T+1,C] gradient w.r.t. the prefix sums
+
+
+def fwd_bwd(emis, lengths, trans, dur, grad_logz=None, center=True, threads=0,
+            tables=False) -> OracleResult:
+    """Run the oracle.  emis [B,T,C], lengths [B] or None, trans [C,C]
+    (source label first), dur [K,C] (row k-1), grad_logz [B] or None."""
+    lib = _load()
+    emis = _as_f64(emis)
+    B, T, C = emis.shape
+    trans = _as_f64(trans)
+    dur = _as_f64(dur)
+    K = dur.shape[0]
+    assert trans.shape == (C, C) and dur.shape == (K, C)
+    lp = None
+    if lengths is not None:
+        lengths = np.ascontiguousarray(np.asarray(lengths), dtype=np.int32)
+        assert lengths.shape == (B,)
+        lp = lengths.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    w = None if grad_logz is None else _as_f64(grad_logz)
+    logz = np.zeros(B)
+    gE = np.zeros((B, T, C))
+    pm = np.zeros((B, T, C))
+    gTr = np.zeros((C, C))
+    gD = np.zeros((K, C))
+    gTr_b = np.zeros((B, C, C))
+    gD_b = np.zeros((B, K, C))
+    S = np.zeros((B, T + 1, C)) if tables else None
+    al = np.zeros((B, T + 1, C)) if tables else None
+    be = np.zeros((B, T + 1, C)) if tables else None
+    gS = np.zeros((B, T + 1, C)) if tables else None
+    rc = lib.semicrf_oracle_fwd_bwd(_dptr(emis), lp, _dptr(trans), _dptr(dur), _dptr(w),
+                                    B, T, K, C, int(bool(center)), int(threads),
+                                    _dptr(logz), _dptr(gE), _dptr(pm), _dptr(gTr), _dptr(gD),
+                                    _dptr(gTr_b), _dptr(gD_b), _dptr(S), _dptr(al), _dptr(be), _dptr(gS))
+    if rc < 0:
+        raise ValueError("semicrf_oracle_fwd_bwd: bad arguments")
+    return OracleResult(logz, gE, pm, gTr, gD, gTr_b, gD_b, rc, S, al, be, gS)
+
+
+def logz(emis, lengths, trans, dur, center=True, threads=0) -> np.ndarray:
+    """Forward pass only: logZ [B]."""
+    lib = _load()
+    emis = _as_f64(emis)
+    B, T, C = emis.shape
+    trans = _as_f64(trans)
+    dur = _as_f64(dur)
+    K = dur.shape[0]
+    lp = None
+    if lengths is not None:
+        lengths = np.ascontiguousarray(np.asarray(lengths), dtype=np.int32)
+        lp = lengths.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    out = np.zeros(B)
+    rc = lib.semicrf_oracle_logz(_dptr(emis), lp, _dptr(trans), _dptr(dur),
+                                 B, T, K, C, int(bool(center)), int(threads), _dptr(out))
+    if rc < 0:
+        raise ValueError("semicrf_oracle_logz: bad arguments")
+    return out

@@ -1,0 +1,308 @@
+/*
+ * Plain fp64 CPU oracle of the semi-Markov CRF forward-backward pass.
+ *
+ * TEST INFRASTRUCTURE ONLY.  Nothing on the product path may call this file:
+ * it exists so that the GPU library can be checked against a slow, obviously
+ * correct implementation of the textbook O(T*K*C^2) recurrence.  It shares no
+ * code, tables or helpers with the HIP kernels.
+ *
+ * What it computes (per sequence b of true length L = lengths[b]):
+ *   - the emission baseline nu[c] and the centred prefix sums S[t,c]
+ *     (paper Eq. 1 and Eq. 2, masked mean over the L valid positions);
+ *   - the three-term edge potential psi(t,k,c,c') of Eq. 4 without the
+ *     optional boundary projections:
+ *         psi = S[t,c] - S[t-k,c] + dur[k-1,c] + trans[c',c];
+ *   - log-forward messages alpha[t,c] by the recurrence of Algorithm 1
+ *     (alpha[0,:] = 0, k <= min(K,t)) but with the FULL table kept: no ring
+ *     buffer, no checkpoints, no normalisation;
+ *   - logZ = LSE_c alpha[L,c]  (Algorithm 1, last line, with T -> L);
+ *   - log-backward messages beta[t,c'] (Algorithm 3: beta[L,:] = 0,
+ *     k <= min(K, L-t)), again as a full table;
+ *   - segment marginals mu(t,k,c,c') = exp(alpha[t,c'] + psi(t+k,k,c,c')
+ *     + beta[t+k,c] - logZ) ("Gradient Computation" section) and from them the
+ *     expected sufficient statistics of the "Gradient Formulas" section:
+ *         gS[t+k,c] += mu,  gS[t,c] -= mu,
+ *         gTr[c',c] += w*mu, gD[k-1,c] += w*mu       (w = upstream dL/dlogZ_b);
+ *   - the chain rule through Eq. 2 and Eq. 1 (the paper leaves this to
+ *     autograd): pm[u,c] = sum_{t>u} gS[t,c] is the gradient w.r.t. the centred
+ *     emission, i.e. the posterior that token u carries label c, and
+ *     gE[u,c] = w*(pm[u,c] - mean_u' pm[u',c]) is the gradient w.r.t. the raw
+ *     emission when centring is on (w*pm[u,c] when it is off).
+ *
+ * Logsumexp of an empty set is a true -inf; every LSE is max-shifted and
+ * guarded so that -inf inputs never produce NaN.  No clamps are applied.
+ *
+ * Threading: OpenMP over sequences; when there are fewer sequences than
+ * threads the destination-label loop inside a position is split as well.
+ * Neither changes the arithmetic or its order for any single output element.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+static double lse_pair_guard(double m, double s) {
+    /* m = running max, s = sum of exp(x - m); returns max + log(sum) */
+    if (m == -INFINITY) return -INFINITY;
+    return m + log(s);
+}
+
+#define PSI(t, k, c, cp) (S[(size_t)(t) * C + (c)] - S[(size_t)((t) - (k)) * C + (c)] \
+                          + dur[(size_t)((k) - 1) * C + (c)] + trans[(size_t)(cp) * C + (c)])
+
+/* Eq. 1 (masked mean over the L valid positions) and Eq. 2 (S[0,c] = 0,
+ * S[t,c] = sum_{u<t} (f[u,c] - nu[c])).  S must hold (L+1)*C zeros on entry. */
+static void oracle_prefix_sums(const double *f, int L, int C, int center, double *nu, double *S)
+{
+    for (int c = 0; c < C; ++c) nu[c] = 0.0;
+    if (center && L > 0) {
+        for (int c = 0; c < C; ++c) {
+            double acc = 0.0;
+            for (int u = 0; u < L; ++u) acc += f[(size_t)u * C + c];
+            nu[c] = acc / (double)L;
+        }
+    }
+    for (int t = 1; t <= L; ++t)
+        for (int c = 0; c < C; ++c)
+            S[(size_t)t * C + c] = S[(size_t)(t - 1) * C + c] + (f[(size_t)(t - 1) * C + c] - nu[c]);
+}
+
+/* Algorithm 1 with the whole table kept (alpha[0,:] = 0); returns
+ * logZ = LSE_c alpha[L,c]. */
+static double oracle_forward(const double *S, const double *trans, const double *dur,
+                             int L, int K, int C, int inner_threads, double *alpha)
+{
+    (void)inner_threads;
+    for (int c = 0; c < C; ++c) alpha[c] = 0.0;
+    for (int t = 1; t <= L; ++t) {
+        int kmax = K < t ? K : t;
+#pragma omp parallel for num_threads(inner_threads) if (inner_threads > 1) schedule(static)
+        for (int c = 0; c < C; ++c) {
+            double m = -INFINITY;
+            for (int k = 1; k <= kmax; ++k)
+                for (int cp = 0; cp < C; ++cp) {
+                    double x = alpha[(size_t)(t - k) * C + cp] + PSI(t, k, c, cp);
+                    if (x > m) m = x;
+                }
+            double s = 0.0;
+            if (m != -INFINITY)
+                for (int k = 1; k <= kmax; ++k)
+                    for (int cp = 0; cp < C; ++cp)
+                        s += exp(alpha[(size_t)(t - k) * C + cp] + PSI(t, k, c, cp) - m);
+            alpha[(size_t)t * C + c] = lse_pair_guard(m, s);
+        }
+    }
+    double m = -INFINITY, s = 0.0;
+    for (int c = 0; c < C; ++c)
+        if (alpha[(size_t)L * C + c] > m) m = alpha[(size_t)L * C + c];
+    if (m != -INFINITY)
+        for (int c = 0; c < C; ++c) s += exp(alpha[(size_t)L * C + c] - m);
+    return lse_pair_guard(m, s);
+}
+
+/* One sequence.  All arrays are fp64.  Optional outputs may be NULL. */
+static void oracle_sequence(const double *f,      /* [T,C] emissions of this sequence */
+                            int L, int T, int K, int C, int center, double w,
+                            const double *trans,  /* [C,C] source-major: trans[c'*C+c] */
+                            const double *dur,    /* [K,C] row k-1 */
+                            int inner_threads,
+                            double *logz_out,
+                            double *gE,           /* [T,C] */
+                            double *pm,           /* [T,C] */
+                            double *gTr,          /* [C,C]   this sequence only, weighted by w */
+                            double *gD,           /* [K,C]   this sequence only, weighted by w */
+                            double *S_out,        /* [T+1,C] or NULL */
+                            double *alpha_out,    /* [T+1,C] or NULL */
+                            double *beta_out,     /* [T+1,C] or NULL */
+                            double *gS_out)       /* [T+1,C] or NULL */
+{
+    (void)inner_threads;
+    size_t n1 = (size_t)(L + 1) * C;
+    double *nu = (double *)calloc((size_t)C, sizeof(double));
+    double *S = (double *)calloc(n1, sizeof(double));
+    double *alpha = (double *)malloc(n1 * sizeof(double));
+    double *beta = (double *)malloc(n1 * sizeof(double));
+    double *gS = (double *)calloc(n1, sizeof(double));
+
+    oracle_prefix_sums(f, L, C, center, nu, S);
+    double logz = oracle_forward(S, trans, dur, L, K, C, inner_threads, alpha);
+    *logz_out = logz;
+
+    /* Algorithm 3 recurrence with the whole table kept: beta[L,:] = 0. */
+    for (int c = 0; c < C; ++c) beta[(size_t)L * C + c] = 0.0;
+    for (int t = L - 1; t >= 0; --t) {
+        int kmax = K < (L - t) ? K : (L - t);
+#pragma omp parallel for num_threads(inner_threads) if (inner_threads > 1) schedule(static)
+        for (int cp = 0; cp < C; ++cp) {
+            double m = -INFINITY;
+            for (int k = 1; k <= kmax; ++k)
+                for (int c = 0; c < C; ++c) {
+                    double x = PSI(t + k, k, c, cp) + beta[(size_t)(t + k) * C + c];
+                    if (x > m) m = x;
+                }
+            double s = 0.0;
+            if (m != -INFINITY)
+                for (int k = 1; k <= kmax; ++k)
+                    for (int c = 0; c < C; ++c)
+                        s += exp(PSI(t + k, k, c, cp) + beta[(size_t)(t + k) * C + c] - m);
+            beta[(size_t)t * C + cp] = lse_pair_guard(m, s);
+        }
+    }
+
+    /* Marginals and expected sufficient statistics.  The destination label c
+     * is the outer loop so that every accumulator element is owned by one c. */
+    memset(gTr, 0, sizeof(double) * (size_t)C * C);
+    memset(gD, 0, sizeof(double) * (size_t)K * C);
+#pragma omp parallel for num_threads(inner_threads) if (inner_threads > 1) schedule(static)
+    for (int c = 0; c < C; ++c) {
+        for (int t = 0; t < L; ++t) {
+            int kmax = K < (L - t) ? K : (L - t);
+            for (int k = 1; k <= kmax; ++k)
+                for (int cp = 0; cp < C; ++cp) {
+                    double lm = alpha[(size_t)t * C + cp] + PSI(t + k, k, c, cp)
+                                + beta[(size_t)(t + k) * C + c] - logz;
+                    double mu = exp(lm);
+                    gTr[(size_t)cp * C + c] += w * mu;
+                    gD[(size_t)(k - 1) * C + c] += w * mu;
+                    gS[(size_t)(t + k) * C + c] += mu;
+                    gS[(size_t)t * C + c] -= mu;
+                }
+        }
+    }
+
+    /* Chain rule through the prefix sum (Eq. 2) and the centring (Eq. 1). */
+    for (int c = 0; c < C; ++c) {
+        double run = 0.0, tot = 0.0;
+        for (int u = L - 1; u >= 0; --u) {
+            run += gS[(size_t)(u + 1) * C + c];
+            pm[(size_t)u * C + c] = run;
+            tot += run;
+        }
+        double mean = (center && L > 0) ? tot / (double)L : 0.0;
+        for (int u = 0; u < L; ++u) gE[(size_t)u * C + c] = w * (pm[(size_t)u * C + c] - mean);
+        for (int u = L; u < T; ++u) {
+            pm[(size_t)u * C + c] = 0.0;
+            gE[(size_t)u * C + c] = 0.0;
+        }
+    }
+
+    if (S_out) {
+        memcpy(S_out, S, n1 * sizeof(double));
+        for (size_t i = n1; i < (size_t)(T + 1) * C; ++i) S_out[i] = 0.0;
+    }
+    if (alpha_out) {
+        memcpy(alpha_out, alpha, n1 * sizeof(double));
+        for (size_t i = n1; i < (size_t)(T + 1) * C; ++i) alpha_out[i] = 0.0;
+    }
+    if (beta_out) {
+        memcpy(beta_out, beta, n1 * sizeof(double));
+        for (size_t i = n1; i < (size_t)(T + 1) * C; ++i) beta_out[i] = 0.0;
+    }
+    if (gS_out) {
+        memcpy(gS_out, gS, n1 * sizeof(double));
+        for (size_t i = n1; i < (size_t)(T + 1) * C; ++i) gS_out[i] = 0.0;
+    }
+    free(nu); free(S); free(alpha); free(beta); free(gS);
+}
+
+/*
+ * Batched entry point.  Returns the number of OpenMP threads it used
+ * (outer * inner), or a negative value on bad arguments.
+ *
+ *   emis      [B,T,C]   raw emissions (rows u >= lengths[b] are never read)
+ *   lengths   [B]       true lengths, each in [0,T]; NULL means all T
+ *   trans     [C,C]     trans[c'*C + c], source label first
+ *   dur       [K,C]     dur[(k-1)*C + c]
+ *   grad_logz [B]       upstream weights w_b; NULL means all ones
+ * Outputs (caller-allocated, fp64):
+ *   logz [B]; grad_emis [B,T,C]; pos_marg [B,T,C]; grad_trans [C,C];
+ *   grad_dur [K,C]; optional per-sequence grad_trans_b [B,C,C], grad_dur_b
+ *   [B,K,C]; optional tables S, alpha, beta, gS each [B,T+1,C].
+ */
+int semicrf_oracle_fwd_bwd(const double *emis, const int32_t *lengths,
+                           const double *trans, const double *dur, const double *grad_logz,
+                           int B, int T, int K, int C, int center, int threads,
+                           double *logz, double *grad_emis, double *pos_marg,
+                           double *grad_trans, double *grad_dur,
+                           double *grad_trans_b, double *grad_dur_b,
+                           double *S_out, double *alpha_out, double *beta_out, double *gS_out)
+{
+    if (B < 1 || T < 1 || K < 1 || C < 1) return -1;
+    int nthreads = 1;
+#ifdef _OPENMP
+    nthreads = threads > 0 ? threads : omp_get_max_threads();
+#endif
+    int outer = B < nthreads ? B : nthreads;
+    int inner = nthreads / outer;
+    if (inner < 1) inner = 1;
+    if (inner > C) inner = C;
+#ifdef _OPENMP
+    omp_set_max_active_levels(2);
+#endif
+    size_t cc = (size_t)C * C, kc = (size_t)K * C, tc = (size_t)T * C, t1c = (size_t)(T + 1) * C;
+    double *gTr_b = grad_trans_b ? grad_trans_b : (double *)malloc(sizeof(double) * cc * B);
+    double *gD_b = grad_dur_b ? grad_dur_b : (double *)malloc(sizeof(double) * kc * B);
+
+#pragma omp parallel for num_threads(outer) schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        int L = lengths ? lengths[b] : T;
+        if (L < 0) L = 0;
+        if (L > T) L = T;
+        double w = grad_logz ? grad_logz[b] : 1.0;
+        oracle_sequence(emis + tc * b, L, T, K, C, center, w, trans, dur, inner,
+                        logz + b, grad_emis + tc * b, pos_marg + tc * b,
+                        gTr_b + cc * b, gD_b + kc * b,
+                        S_out ? S_out + t1c * b : NULL,
+                        alpha_out ? alpha_out + t1c * b : NULL,
+                        beta_out ? beta_out + t1c * b : NULL,
+                        gS_out ? gS_out + t1c * b : NULL);
+    }
+    /* Fixed-order sum over sequences. */
+    for (size_t i = 0; i < cc; ++i) {
+        double a = 0.0;
+        for (int b = 0; b < B; ++b) a += gTr_b[cc * b + i];
+        grad_trans[i] = a;
+    }
+    for (size_t i = 0; i < kc; ++i) {
+        double a = 0.0;
+        for (int b = 0; b < B; ++b) a += gD_b[kc * b + i];
+        grad_dur[i] = a;
+    }
+    if (!grad_trans_b) free(gTr_b);
+    if (!grad_dur_b) free(gD_b);
+    return outer * inner;
+}
+
+/*
+ * Forward only: logZ per sequence (same recurrence, same arithmetic).
+ * Used for finite-difference checks, where the backward pass is not wanted.
+ */
+int semicrf_oracle_logz(const double *emis, const int32_t *lengths,
+                        const double *trans, const double *dur,
+                        int B, int T, int K, int C, int center, int threads, double *logz)
+{
+    if (B < 1 || T < 1 || K < 1 || C < 1) return -1;
+    int nthreads = 1;
+#ifdef _OPENMP
+    nthreads = threads > 0 ? threads : omp_get_max_threads();
+#endif
+    int outer = B < nthreads ? B : nthreads;
+#pragma omp parallel for num_threads(outer) schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        int L = lengths ? lengths[b] : T;
+        if (L < 0) L = 0;
+        if (L > T) L = T;
+        const double *f = emis + (size_t)T * C * b;
+        size_t n1 = (size_t)(L + 1) * C;
+        double *nu = (double *)calloc((size_t)C, sizeof(double));
+        double *S = (double *)calloc(n1, sizeof(double));
+        double *alpha = (double *)malloc(n1 * sizeof(double));
+        oracle_prefix_sums(f, L, C, center, nu, S);
+        logz[b] = oracle_forward(S, trans, dur, L, K, C, 1, alpha);
+        free(nu); free(S); free(alpha);
+    }
+    return outer;
+}

@@ -1,0 +1,400 @@
+"""Pins of the fp64 CPU oracle against things other than itself (CPU only).
+
+Each test fixes part of ``oracle/`` to something the paper or the mathematics
+determines: a printed table, brute-force enumeration of every segmentation, the
+textbook linear-chain CRF at K=1, the explicit two-term recurrence at K=2,
+closed forms for all-zero potentials, central finite differences, marginal
+invariants, the centring = effective-duration-prior identity (Eq. 5), shift
+identities and padding independence.
+"""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+from scipy.special import logsumexp
+
+import oracle
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def rand_case(seed, B, T, K, C, ragged=False, scale=1.0):
+    rng = np.random.default_rng(seed)
+    emis = scale * rng.standard_normal((B, T, C))
+    trans = 0.7 * rng.standard_normal((C, C))
+    dur = 0.7 * rng.standard_normal((K, C))
+    lengths = rng.integers(1, T + 1, size=B).astype(np.int32) if ragged else np.full(B, T, np.int32)
+    return emis, lengths, trans, dur
+
+
+# --------------------------------------------------------------------------
+# P1  baseline arithmetic of Eq. 1 against the printed toy table
+# --------------------------------------------------------------------------
+def test_baseline_matches_printed_toy_table():
+    rows = []
+    with open(os.path.join(GOLDEN, "toy_centering_table1.txt")) as fh:
+        for line in fh:
+            if line.startswith("#") or not line.strip():
+                continue
+            p = line.split()
+            rows.append([float(x) for x in p[1:]])
+    rows = np.array(rows)
+    act, inact, prev, nu_print, pen_print, cen_print = rows.T
+    T, C = 10000, 3
+    counts = np.round(prev * T).astype(int)
+    assert counts.sum() == T
+    labels = np.repeat(np.arange(C), counts)
+    np.random.default_rng(0).shuffle(labels)
+    emis = np.tile(inact, (T, 1))
+    emis[np.arange(T), labels] = act[labels]
+    r = oracle.fwd_bwd(emis[None], None, np.zeros((C, C)), np.zeros((2, C)), tables=True)
+    S = r.S[0]
+    # Eq. 2: S[t] = sum_{u<t} f[u] - t*nu  =>  nu = (cumsum(f)[t-1] - S[t]) / t
+    nu = (emis.cumsum(0)[-1] - S[T]) / T
+    nu1 = (emis[0] - S[1])
+    assert np.allclose(nu, nu1, atol=1e-9)
+    assert np.all(np.abs(nu - nu_print) <= 0.005 + 1e-12), nu          # printed to 2 decimals
+    assert np.all(np.abs(-100 * nu - pen_print) <= 0.5 + 1e-9)
+    assert np.all(np.abs((act - nu) - cen_print) <= 0.005 + 1e-9)
+    # S ends at zero when every position is valid (zero-mean walk)
+    assert np.allclose(S[T], 0.0, atol=1e-7)
+    # no centring: S is the raw prefix sum
+    r0 = oracle.fwd_bwd(emis[None], None, np.zeros((C, C)), np.zeros((2, C)), center=False, tables=True)
+    assert np.allclose(r0.S[0][1:], emis.cumsum(0), atol=1e-9)
+
+
+# --------------------------------------------------------------------------
+# P2  brute force over every segmentation (independent pure-Python code)
+# --------------------------------------------------------------------------
+def compositions(n, K):
+    if n == 0:
+        yield ()
+        return
+    for first in range(1, min(K, n) + 1):
+        for rest in compositions(n - first, K):
+            yield (first,) + rest
+
+
+def brute_force(emis, L, trans, dur, center):
+    """Z and expected statistics by explicit enumeration.  The first segment
+    pays a transition from a virtual initial label c0 that ranges over all
+    labels with weight 1 (alpha_0 = 0 for every label)."""
+    T, C = emis.shape
+    K = dur.shape[0]
+    nu = emis[:L].mean(0) if (center and L > 0) else np.zeros(C)
+    fbar = emis - nu
+    Z = 0.0
+    gTr = np.zeros((C, C))
+    gD = np.zeros((K, C))
+    pm = np.zeros((T, C))
+    gS = np.zeros((T + 1, C))
+    for comp in compositions(L, K):
+        n = len(comp)
+        for c0 in range(C):
+            for labs in itertools.product(range(C), repeat=n):
+                score = 0.0
+                prev = c0
+                s = 0
+                for k, c in zip(comp, labs):
+                    score += trans[prev, c] + dur[k - 1, c] + fbar[s:s + k, c].sum()
+                    prev = c
+                    s += k
+                wgt = math.exp(score)
+                Z += wgt
+                prev = c0
+                s = 0
+                for k, c in zip(comp, labs):
+                    gTr[prev, c] += wgt
+                    gD[k - 1, c] += wgt
+                    pm[s:s + k, c] += wgt
+                    gS[s + k, c] += wgt
+                    gS[s, c] -= wgt
+                    prev = c
+                    s += k
+    return math.log(Z), gTr / Z, gD / Z, pm / Z, gS / Z
+
+
+@pytest.mark.parametrize("T,K,C,center", [(5, 3, 2, True), (6, 4, 2, False), (4, 2, 3, True),
+                                          (7, 7, 2, True), (5, 1, 3, True), (3, 5, 3, False)])
+def test_brute_force_enumeration(T, K, C, center):
+    emis, _, trans, dur = rand_case(100 + T * 10 + K, 1, T, K, C)
+    r = oracle.fwd_bwd(emis, None, trans, dur, center=center, tables=True)
+    lz, gTr, gD, pm, gS = brute_force(emis[0], T, trans, dur, center)
+    assert abs(r.logz[0] - lz) < 1e-12 * max(1, abs(lz))
+    assert np.allclose(r.grad_trans, gTr, atol=1e-10)
+    assert np.allclose(r.grad_dur, gD, atol=1e-10)
+    assert np.allclose(r.pos_marg[0], pm, atol=1e-10)
+    assert np.allclose(r.gS[0], gS, atol=1e-10)
+    # gradient w.r.t. raw emissions through the centring Jacobian
+    gE = pm - (pm.mean(0) if center else 0.0)
+    assert np.allclose(r.grad_emis[0], gE, atol=1e-10)
+
+
+def test_brute_force_ragged_and_weighted():
+    T, K, C = 6, 3, 2
+    emis, _, trans, dur = rand_case(7, 3, T, K, C)
+    lengths = np.array([6, 3, 1], np.int32)
+    w = np.array([0.5, -2.0, 3.0])
+    r = oracle.fwd_bwd(emis, lengths, trans, dur, grad_logz=w)
+    gTr = np.zeros((C, C))
+    gD = np.zeros((K, C))
+    for b in range(3):
+        L = int(lengths[b])
+        lz, tr_b, d_b, pm, _ = brute_force(emis[b], L, trans, dur, True)
+        assert abs(r.logz[b] - lz) < 1e-12
+        assert np.allclose(r.pos_marg[b], pm, atol=1e-10)
+        assert np.all(r.pos_marg[b, L:] == 0) and np.all(r.grad_emis[b, L:] == 0)
+        gE = w[b] * (pm[:L] - pm[:L].mean(0))
+        assert np.allclose(r.grad_emis[b, :L], gE, atol=1e-10)
+        gTr += w[b] * tr_b
+        gD += w[b] * d_b
+    assert np.allclose(r.grad_trans, gTr, atol=1e-10)
+    assert np.allclose(r.grad_dur, gD, atol=1e-10)
+
+
+# --------------------------------------------------------------------------
+# P3  K=1 is the textbook linear-chain CRF; K=2 is the explicit recurrence
+# --------------------------------------------------------------------------
+def test_k1_is_linear_chain_crf():
+    T, C = 300, 5
+    emis, _, trans, dur = rand_case(11, 2, T, 1, C)
+    r = oracle.fwd_bwd(emis, None, trans, dur, center=True)
+    for b in range(2):
+        fbar = emis[b] - emis[b].mean(0)
+        a = np.ones(C)
+        log_scale = 0.0
+        E = np.exp(trans)
+        for t in range(T):
+            a = (a @ E) * np.exp(fbar[t] + dur[0])
+            s = a.sum()
+            a /= s
+            log_scale += math.log(s)
+        assert abs(r.logz[b] - log_scale) < 1e-9
+    # every boundary is certain at K=1: expected number of segments = T per sequence
+    assert abs(r.grad_dur.sum() - 2 * T) < 1e-8
+
+
+def test_k2_explicit_recurrence():
+    T, C = 120, 4
+    emis, _, trans, dur = rand_case(12, 1, T, 2, C)
+    lz = oracle.logz(emis, None, trans, dur, center=False)[0]
+    S = np.vstack([np.zeros(C), emis[0].cumsum(0)])
+    a1 = np.zeros(C)               # alpha[t-1]
+    a2 = np.full(C, -np.inf)       # alpha[t-2]
+    for t in range(1, T + 1):
+        s1 = S[t] - S[t - 1] + dur[0] + logsumexp(a1[:, None] + trans, axis=0)
+        if t >= 2:
+            s2 = S[t] - S[t - 2] + dur[1] + logsumexp(a2[:, None] + trans, axis=0)
+            new = np.logaddexp(s1, s2)
+        else:
+            new = s1
+        a2, a1 = a1, new
+    assert abs(lz - logsumexp(a1)) < 1e-9
+
+
+# --------------------------------------------------------------------------
+# P4  closed forms for all-zero potentials
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("T,C", [(1, 3), (7, 2), (12, 5)])
+def test_closed_forms_zero_potentials(T, C):
+    z = np.zeros((1, T, C))
+    # K >= T: A_t = C * sum_{s<t} A_s, A_0 = C  =>  logZ = 2 ln C + (T-1) ln(C+1)
+    lz = oracle.logz(z, None, np.zeros((C, C)), np.zeros((T + 3, C)))[0]
+    assert abs(lz - (2 * math.log(C) + (T - 1) * math.log(C + 1))) < 1e-10
+    # K = 1: A_t = C * A_{t-1}  =>  logZ = (T+1) ln C
+    lz1 = oracle.logz(z, None, np.zeros((C, C)), np.zeros((1, C)))[0]
+    assert abs(lz1 - (T + 1) * math.log(C)) < 1e-10
+    # general K by the integer recurrence
+    K = 3
+    A = [C]
+    for t in range(1, T + 1):
+        A.append(C * sum(A[max(0, t - K):t]))
+    lzk = oracle.logz(z, None, np.zeros((C, C)), np.zeros((K, C)))[0]
+    assert abs(lzk - math.log(A[T])) < 1e-10
+    # empty sequence: logZ = ln C (alpha_0 = 0 for all labels)
+    lz0 = oracle.logz(z, np.array([0], np.int32), np.zeros((C, C)), np.zeros((K, C)))[0]
+    assert abs(lz0 - math.log(C)) < 1e-12
+
+
+# --------------------------------------------------------------------------
+# P5  central finite differences on every input element
+# --------------------------------------------------------------------------
+def test_finite_differences_all_inputs():
+    B, T, K, C = 2, 9, 4, 3
+    emis, _, trans, dur = rand_case(21, B, T, K, C)
+    lengths = np.array([9, 6], np.int32)
+    w = np.array([1.3, -0.7])
+    r = oracle.fwd_bwd(emis, lengths, trans, dur, grad_logz=w, center=True)
+
+    def loss(e, tr, d):
+        return float((w * oracle.logz(e, lengths, tr, d, center=True)).sum())
+
+    eps = 1e-6
+    g = np.zeros_like(emis)
+    for idx in np.ndindex(*emis.shape):
+        ep, em = emis.copy(), emis.copy()
+        ep[idx] += eps
+        em[idx] -= eps
+        g[idx] = (loss(ep, trans, dur) - loss(em, trans, dur)) / (2 * eps)
+    assert np.allclose(r.grad_emis, g, atol=2e-8)
+    g = np.zeros_like(trans)
+    for idx in np.ndindex(*trans.shape):
+        p, m = trans.copy(), trans.copy()
+        p[idx] += eps
+        m[idx] -= eps
+        g[idx] = (loss(emis, p, dur) - loss(emis, m, dur)) / (2 * eps)
+    assert np.allclose(r.grad_trans, g, atol=2e-8)
+    g = np.zeros_like(dur)
+    for idx in np.ndindex(*dur.shape):
+        p, m = dur.copy(), dur.copy()
+        p[idx] += eps
+        m[idx] -= eps
+        g[idx] = (loss(emis, trans, p) - loss(emis, trans, m)) / (2 * eps)
+    assert np.allclose(r.grad_dur, g, atol=2e-8)
+
+
+def test_finite_differences_paper_protocol_sizes():
+    """The paper's own check: B=1, T=100, C=16, K=25 (sampled elements here)."""
+    B, T, K, C = 1, 100, 25, 16
+    emis, _, trans, dur = rand_case(22, B, T, K, C)
+    r = oracle.fwd_bwd(emis, None, trans, dur, center=False)
+    rng = np.random.default_rng(0)
+    eps = 1e-5
+    for _ in range(6):
+        i, j = rng.integers(0, C, 2)
+        p, m = trans.copy(), trans.copy()
+        p[i, j] += eps
+        m[i, j] -= eps
+        fd = (oracle.logz(emis, None, p, dur, center=False)[0] - oracle.logz(emis, None, m, dur, center=False)[0]) / (2 * eps)
+        assert abs(fd - r.grad_trans[i, j]) < 1e-6
+        k, c = rng.integers(0, K), rng.integers(0, C)
+        p, m = dur.copy(), dur.copy()
+        p[k, c] += eps
+        m[k, c] -= eps
+        fd = (oracle.logz(emis, None, trans, p, center=False)[0] - oracle.logz(emis, None, trans, m, center=False)[0]) / (2 * eps)
+        assert abs(fd - r.grad_dur[k, c]) < 1e-6
+        u, c = rng.integers(0, T), rng.integers(0, C)
+        p, m = emis.copy(), emis.copy()
+        p[0, u, c] += eps
+        m[0, u, c] -= eps
+        fd = (oracle.logz(p, None, trans, dur, center=False)[0] - oracle.logz(m, None, trans, dur, center=False)[0]) / (2 * eps)
+        assert abs(fd - r.pos_marg[0, u, c]) < 1e-6
+
+
+# --------------------------------------------------------------------------
+# P6  invariants of the marginals
+# --------------------------------------------------------------------------
+def test_marginal_invariants():
+    B, T, K, C = 3, 200, 12, 6
+    emis, lengths, trans, dur = rand_case(31, B, T, K, C, ragged=True)
+    lengths[0] = T
+    r = oracle.fwd_bwd(emis, lengths, trans, dur, tables=True)
+    for b in range(B):
+        L = int(lengths[b])
+        pm = r.pos_marg[b]
+        assert np.all(pm >= -1e-12) and np.all(pm <= 1 + 1e-12)
+        assert np.allclose(pm[:L].sum(1), 1.0, atol=1e-10)
+        assert np.all(pm[L:] == 0)
+        assert abs(pm.sum() - L) < 1e-8
+        gD, gTr = r.grad_dur_b[b], r.grad_trans_b[b]
+        ks = np.arange(1, K + 1)[:, None]
+        assert abs((ks * gD).sum() - L) < 1e-8                     # durations tile the sequence
+        nseg = gD.sum()
+        assert abs(gTr.sum() - nseg) < 1e-8                         # one transition per segment
+        assert math.ceil(L / K) - 1e-9 <= nseg <= L + 1e-9
+        gS = r.gS[b]
+        assert np.allclose(gS[1:L].sum(1), 0.0, atol=1e-10)
+        assert abs(gS[0].sum() + 1) < 1e-10 and abs(gS[L].sum() - 1) < 1e-10
+        bdy = np.exp(r.alpha[b, :L + 1] + r.beta[b, :L + 1] - r.logz[b]).sum(1)
+        assert np.all(bdy[1:] <= 1 + 1e-10) and abs(bdy[L] - 1) < 1e-10
+        assert abs(bdy[1:L + 1].sum() - nseg) < 1e-8
+        # beta at the origin carries the partition function (alpha_0 = 0)
+        assert abs(logsumexp(r.beta[b, 0]) - r.logz[b]) < 1e-9
+        # centred gradient sums to zero over valid positions for each label
+        assert np.allclose(r.grad_emis[b, :L].sum(0), 0.0, atol=1e-9)
+
+
+# --------------------------------------------------------------------------
+# P7  centring == per-sequence effective duration prior (Eq. 5)
+# --------------------------------------------------------------------------
+def test_centering_equals_effective_duration_prior():
+    B, T, K, C = 1, 40, 7, 4
+    emis, _, trans, dur = rand_case(41, B, T, K, C)
+    emis += np.array([2.0, -1.0, 0.3, 0.0])     # non-zero per-label means
+    L = 33
+    lengths = np.array([L], np.int32)
+    nu = emis[0, :L].mean(0)
+    dur_eff = dur - nu[None, :] * np.arange(1, K + 1)[:, None]
+    a = oracle.fwd_bwd(emis, lengths, trans, dur, center=True)
+    b = oracle.fwd_bwd(emis, lengths, trans, dur_eff, center=False)
+    assert abs(a.logz[0] - b.logz[0]) < 1e-9
+    assert np.allclose(a.pos_marg, b.pos_marg, atol=1e-10)
+    assert np.allclose(a.grad_trans, b.grad_trans, atol=1e-10)
+    assert np.allclose(a.grad_dur, b.grad_dur, atol=1e-10)
+    # and centring is NOT path-invariant: it changes logZ
+    c = oracle.fwd_bwd(emis, lengths, trans, dur, center=False)
+    assert abs(a.logz[0] - c.logz[0]) > 1e-3
+
+
+# --------------------------------------------------------------------------
+# P8  shift identities
+# --------------------------------------------------------------------------
+def test_shift_identities():
+    B, T, K, C = 1, 30, 5, 3
+    emis, _, trans, dur = rand_case(51, B, T, K, C)
+    shift = np.random.default_rng(3).standard_normal(T)
+    e2 = emis + shift[None, :, None]
+    # without centring a per-position scalar is path-invariant: logZ moves by its sum
+    l0 = oracle.logz(emis, None, trans, dur, center=False)[0]
+    l1 = oracle.logz(e2, None, trans, dur, center=False)[0]
+    assert abs((l1 - l0) - shift.sum()) < 1e-9
+    # with centring a constant per-label offset is removed exactly
+    e3 = emis + np.array([5.0, -3.0, 0.5])[None, None, :]
+    l2 = oracle.logz(emis, None, trans, dur, center=True)[0]
+    l3 = oracle.logz(e3, None, trans, dur, center=True)[0]
+    assert abs(l2 - l3) < 1e-9
+    # marginals are untouched by the path-invariant shift
+    a = oracle.fwd_bwd(emis, None, trans, dur, center=False)
+    b = oracle.fwd_bwd(e2, None, trans, dur, center=False)
+    assert np.allclose(a.pos_marg, b.pos_marg, atol=1e-10)
+
+
+# --------------------------------------------------------------------------
+# P10  padding independence
+# --------------------------------------------------------------------------
+def test_padding_independence():
+    T, K, C = 25, 6, 3
+    emis, _, trans, dur = rand_case(61, 1, T, K, C)
+    L = 17
+    alone = oracle.fwd_bwd(emis[:, :L], None, trans, dur)
+    padded = emis.copy()
+    padded[0, L:] = np.nan                       # must never be read
+    other = np.random.default_rng(9).standard_normal((1, T, C))
+    batch = np.concatenate([other, padded], 0)
+    r = oracle.fwd_bwd(batch, np.array([T, L], np.int32), trans, dur, grad_logz=np.array([0.0, 1.0]))
+    assert r.logz[1] == alone.logz[0]
+    assert np.array_equal(r.pos_marg[1, :L], alone.pos_marg[0])
+    assert np.all(r.pos_marg[1, L:] == 0)
+    assert np.allclose(r.grad_trans, alone.grad_trans, atol=1e-12)
+    assert np.allclose(r.grad_dur, alone.grad_dur, atol=1e-12)
+
+
+# --------------------------------------------------------------------------
+# transposition / index sensitivity: the pins above must be able to see a
+# swapped transition matrix or a shifted duration row
+# --------------------------------------------------------------------------
+def test_pins_can_see_transposed_or_shifted_operands():
+    T, K, C = 5, 3, 2
+    emis, _, trans, dur = rand_case(150 + 3, 1, T, K, C)
+    lz, *_ = brute_force(emis[0], T, trans, dur, True)
+    assert abs(oracle.logz(emis, None, trans.T.copy(), dur)[0] - lz) > 1e-4
+    assert abs(oracle.logz(emis, None, trans, np.roll(dur, 1, axis=0))[0] - lz) > 1e-4
+
+
+def test_forward_only_entry_matches_full_entry():
+    emis, lengths, trans, dur = rand_case(71, 3, 50, 9, 4, ragged=True)
+    a = oracle.logz(emis, lengths, trans, dur)
+    b = oracle.fwd_bwd(emis, lengths, trans, dur).logz
+    assert np.array_equal(a, b)
