@@ -1,0 +1,137 @@
+/*
+ * semicrf.h - C ABI of the MI355X (gfx950) streaming semi-Markov CRF library.
+ *
+ * The library computes, for a batch of sequences, the log-partition function
+ * logZ of a semi-Markov CRF whose edge potential is the three-term form of the
+ * paper's Eq. 4 (centred content score from prefix sums, duration bias,
+ * transition), and the exact gradients of sum_b w_b*logZ_b with respect to the
+ * emissions, the duration bias and the transition matrix (the expected
+ * sufficient statistics of the paper's "Gradient Formulas" section).  Edge
+ * potentials are never stored; working memory beyond the O(T*C) prefix arrays
+ * is a K-deep ring per sequence plus checkpoints every `ckpt_interval`
+ * positions (Algorithm 1 / Algorithm 3).
+ *
+ * Conventions common to every entry point
+ *   - Every array pointer is a DEVICE pointer owned by the caller, except where
+ *     "host" is stated.  The library allocates nothing and frees nothing; all
+ *     scratch comes from the caller's `workspace`.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
+ *     default stream).  No entry point synchronises with the host.
+ *   - Return value: SEMICRF_OK or a negative semicrf_status.  On any error no
+ *     kernel has been launched and the outputs are untouched.
+ *   - Layouts are row-major with the label index fastest:
+ *       emis   [B,T,C]  float   raw emissions f(t,c); rows t >= lengths[b] are never read
+ *       lengths[B]      int32   true lengths L_b, clamped on the device to [0,T]; NULL = all T
+ *       trans  [C,C]    float   trans[c_src*C + c_dst]         (source label first)
+ *       dur    [K,C]    float   dur[(k-1)*C + c], k = 1..K     (durations are 1-based)
+ *   - Positions t in 0..T are boundaries between tokens; a segment [s,s+k)
+ *     covers tokens s..s+k-1 and its content score is S[s+k,c]-S[s,c]
+ *     ("Indexing conventions").  alpha_0(c) = 0 for every label, so the first
+ *     segment pays LSE over the source label of trans[.,c]; there is no end
+ *     term: logZ = LSE_c alpha_L(c).  K may exceed T.  An empty sequence
+ *     (L_b = 0) has logZ = ln C and zero gradients.
+ *   - Supported sizes: 1 <= C <= 256, and K*C small enough for the ring, the
+ *     duration table and the per-interval accumulators to fit the 160 KB LDS of
+ *     one compute unit (see semicrf_workspace_bytes, which reports
+ *     SEMICRF_EUNSUPPORTED otherwise).
+ */
+#ifndef SEMICRF_H
+#define SEMICRF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SEMICRF_OK = 0,
+    SEMICRF_EINVAL = -1,       /* bad size, null required pointer, negative interval */
+    SEMICRF_EWORKSPACE = -2,   /* workspace_bytes too small or workspace misaligned (256 B) */
+    SEMICRF_EUNSUPPORTED = -3, /* (K,C) does not fit the LDS budget of the kernels */
+    SEMICRF_ELAUNCH = -4       /* a HIP call or kernel launch reported an error */
+} semicrf_status;
+
+/* flags bit 0: subtract the per-sequence emission baseline nu[b,c] before the
+ * prefix sum (Eq. 1).  Without it S is the raw prefix sum. */
+#define SEMICRF_CENTER 1u
+
+int semicrf_version(void);
+
+/* Host only.  Text for a status code; the pointer is static storage. */
+const char *semicrf_strerror(int status);
+
+/*
+ * Host only, pure.  Bytes of device workspace the calls below need for these
+ * sizes.  ckpt_interval = 0 selects the automatic interval
+ * ceil(sqrt(T*K*B/256)) clamped to [1,T] (the paper's sqrt(T*K) spacing scaled
+ * so that checkpoint memory and per-interval recompute buffers balance when the
+ * B*T/interval recompute tasks are spread over the 256 compute units).
+ * want_grad = 0 sizes for semicrf_logz_fwd / semicrf_cum_scores only.
+ * `bytes` is a host pointer.
+ */
+int semicrf_workspace_bytes(int B, int T, int K, int C, int ckpt_interval, int want_grad,
+                            size_t *bytes);
+
+/*
+ * Eq. 1 and Eq. 2: per-sequence baseline and centred prefix sums.
+ *   cum [B,T+1,C] double: cum[b,0,c] = 0, cum[b,t,c] = sum_{u<t} (emis[b,u,c] - nu[b,c])
+ *   for t <= L_b; rows t > L_b are written as 0.
+ * Workspace: as for want_grad = 0 with K = 1.
+ */
+int semicrf_cum_scores(const float *emis, const int32_t *lengths, int B, int T, int C,
+                       unsigned flags, void *workspace, size_t workspace_bytes,
+                       double *cum, void *stream);
+
+/*
+ * Algorithm 1 (streaming forward scan): logz[b] = log partition function of
+ * sequence b.  logz [B] float.  The result does not depend on ckpt_interval.
+ */
+int semicrf_logz_fwd(const float *emis, const int32_t *lengths, const float *trans,
+                     const float *dur, int B, int T, int K, int C, int ckpt_interval,
+                     unsigned flags, void *workspace, size_t workspace_bytes,
+                     float *logz, void *stream);
+
+/*
+ * Algorithm 1 + Algorithm 3 (forward scan, checkpointed backward pass) and the
+ * gradient formulas.
+ *   grad_logz [B] float or NULL: upstream weights w_b = dLoss/dlogZ_b (NULL = ones)
+ * Outputs (all fully overwritten):
+ *   logz       [B]     float
+ *   grad_emis  [B,T,C] float  w_b * d logZ_b / d emis[b,u,c]; with SEMICRF_CENTER this
+ *                             includes the Jacobian of the baseline subtraction; rows
+ *                             u >= L_b are 0.  (Also used as scratch during the call.)
+ *   grad_trans [C,C]   float  sum_b w_b * sum_{t,k} mu_b(t,k,c,c')   at [c'*C + c]
+ *   grad_dur   [K,C]   float  sum_b w_b * sum_{t,c'} mu_b(t,k,c,c')  at [(k-1)*C + c]
+ *   pos_marg   [B,T,C] float or NULL: posterior P(token u has label c), which is the
+ *                             gradient of logZ_b w.r.t. the centred emission; rows
+ *                             u >= L_b are 0.
+ */
+int semicrf_fwd_bwd(const float *emis, const int32_t *lengths, const float *trans,
+                    const float *dur, const float *grad_logz, int B, int T, int K, int C,
+                    int ckpt_interval, unsigned flags, void *workspace, size_t workspace_bytes,
+                    float *logz, float *grad_emis, float *grad_trans, float *grad_dur,
+                    float *pos_marg, void *stream);
+
+/*
+ * Measurement aid: semicrf_fwd_bwd with HIP events recorded on `stream` around
+ * its four stages.  Unlike every other entry point this one creates events,
+ * waits for the stream to finish and then fills the HOST array
+ *   stage_ms[4] = { prefix sums (Eq. 1-2 kernels), the two sequential scans
+ *                   (Algorithm 1 and the beta recurrence of Algorithm 3),
+ *                   per-interval recompute + marginals (Algorithm 3 body),
+ *                   fixed-order reductions of the gradient formulas }
+ * in milliseconds.  Results are identical to semicrf_fwd_bwd.
+ */
+int semicrf_fwd_bwd_profiled(const float *emis, const int32_t *lengths, const float *trans,
+                             const float *dur, const float *grad_logz, int B, int T, int K, int C,
+                             int ckpt_interval, unsigned flags, void *workspace,
+                             size_t workspace_bytes, float *logz, float *grad_emis,
+                             float *grad_trans, float *grad_dur, float *pos_marg, void *stream,
+                             float *stage_ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SEMICRF_H */

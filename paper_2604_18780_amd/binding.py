@@ -1,0 +1,174 @@
+"""Thin ctypes binding of ``libsemicrf.so`` (argument marshalling only).
+
+Every function mirrors the C entry point of the same name in
+``include/semicrf.h``: tensors are passed as device pointers, the work is
+enqueued on torch's current HIP stream and nothing is computed here.  The
+library must have been built (``python -m paper_2604_18780_amd.build``); a
+missing library is an error, there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsemicrf.so")
+EXPORTS = ("semicrf_version", "semicrf_strerror", "semicrf_workspace_bytes",
+           "semicrf_cum_scores", "semicrf_logz_fwd", "semicrf_fwd_bwd", "semicrf_fwd_bwd_profiled")
+SEMICRF_CENTER = 1
+_lib = None
+
+
+class SemiCRFError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"semicrf status {status}: {msg}")
+        self.status = status
+
+
+def load():
+    """Load the shared library (once) and declare the prototypes."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2604_18780_amd.build` "
+            "(there is no CPU fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, ci, cu, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_uint, ctypes.c_size_t
+    lib.semicrf_version.restype = ci
+    lib.semicrf_version.argtypes = []
+    lib.semicrf_strerror.restype = ctypes.c_char_p
+    lib.semicrf_strerror.argtypes = [ci]
+    lib.semicrf_workspace_bytes.restype = ci
+    lib.semicrf_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci, ctypes.POINTER(sz)]
+    lib.semicrf_cum_scores.restype = ci
+    lib.semicrf_cum_scores.argtypes = [vp, vp, ci, ci, ci, cu, vp, sz, vp, vp]
+    lib.semicrf_logz_fwd.restype = ci
+    lib.semicrf_logz_fwd.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, cu, vp, sz, vp, vp]
+    lib.semicrf_fwd_bwd.restype = ci
+    lib.semicrf_fwd_bwd.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, cu, vp, sz,
+                                    vp, vp, vp, vp, vp, vp]
+    lib.semicrf_fwd_bwd_profiled.restype = ci
+    lib.semicrf_fwd_bwd_profiled.argtypes = lib.semicrf_fwd_bwd.argtypes + [ctypes.POINTER(ctypes.c_float)]
+    _lib = lib
+    return lib
+
+
+def _check(status: int):
+    if status != 0:
+        raise SemiCRFError(status, load().semicrf_strerror(status).decode())
+
+
+def semicrf_version() -> int:
+    return load().semicrf_version()
+
+
+def semicrf_strerror(status: int) -> str:
+    return load().semicrf_strerror(status).decode()
+
+
+def semicrf_workspace_bytes(B, T, K, C, ckpt_interval=0, want_grad=True) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().semicrf_workspace_bytes(B, T, K, C, ckpt_interval, int(bool(want_grad)),
+                                          ctypes.byref(out)))
+    return out.value
+
+
+def _ptr(t, dtype):
+    if t is None:
+        return None
+    if not (t.is_cuda and t.is_contiguous() and t.dtype == dtype):
+        raise ValueError(f"expected a contiguous {dtype} device tensor")
+    return t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def alloc_workspace(B, T, K, C, ckpt_interval=0, want_grad=True, device="cuda:0"):
+    n = semicrf_workspace_bytes(B, T, K, C, ckpt_interval, want_grad)
+    ws = torch.empty(n + 256, dtype=torch.uint8, device=device)
+    off = (-ws.data_ptr()) % 256
+    return ws[off:off + n]
+
+
+def semicrf_cum_scores(emis, lengths, flags=SEMICRF_CENTER, workspace=None):
+    B, T, C = emis.shape
+    if workspace is None:
+        workspace = alloc_workspace(B, T, 1, C, 0, False, emis.device)
+    cum = torch.empty((B, T + 1, C), dtype=torch.float64, device=emis.device)
+    _check(load().semicrf_cum_scores(_ptr(emis, torch.float32), _ptr(lengths, torch.int32),
+                                     B, T, C, flags, workspace.data_ptr(), workspace.numel(),
+                                     cum.data_ptr(), _stream()))
+    return cum
+
+
+def semicrf_logz_fwd(emis, lengths, trans, dur, ckpt_interval=0, flags=SEMICRF_CENTER,
+                     workspace=None, logz=None):
+    B, T, C = emis.shape
+    K = dur.shape[0]
+    if workspace is None:
+        workspace = alloc_workspace(B, T, K, C, ckpt_interval, False, emis.device)
+    if logz is None:
+        logz = torch.empty(B, dtype=torch.float32, device=emis.device)
+    _check(load().semicrf_logz_fwd(_ptr(emis, torch.float32), _ptr(lengths, torch.int32),
+                                   _ptr(trans, torch.float32), _ptr(dur, torch.float32),
+                                   B, T, K, C, ckpt_interval, flags,
+                                   workspace.data_ptr(), workspace.numel(),
+                                   _ptr(logz, torch.float32), _stream()))
+    return logz
+
+
+def semicrf_fwd_bwd(emis, lengths, trans, dur, grad_logz=None, ckpt_interval=0,
+                    flags=SEMICRF_CENTER, workspace=None, want_pos_marg=True, out=None):
+    """Returns (logz, grad_emis, grad_trans, grad_dur, pos_marg or None)."""
+    B, T, C = emis.shape
+    K = dur.shape[0]
+    dev = emis.device
+    if workspace is None:
+        workspace = alloc_workspace(B, T, K, C, ckpt_interval, True, dev)
+    if out is None:
+        logz = torch.empty(B, dtype=torch.float32, device=dev)
+        g_e = torch.empty((B, T, C), dtype=torch.float32, device=dev)
+        g_t = torch.empty((C, C), dtype=torch.float32, device=dev)
+        g_d = torch.empty((K, C), dtype=torch.float32, device=dev)
+        pm = torch.empty((B, T, C), dtype=torch.float32, device=dev) if want_pos_marg else None
+    else:
+        logz, g_e, g_t, g_d, pm = out
+    _check(load().semicrf_fwd_bwd(_ptr(emis, torch.float32), _ptr(lengths, torch.int32),
+                                  _ptr(trans, torch.float32), _ptr(dur, torch.float32),
+                                  _ptr(grad_logz, torch.float32), B, T, K, C, ckpt_interval, flags,
+                                  workspace.data_ptr(), workspace.numel(),
+                                  _ptr(logz, torch.float32), _ptr(g_e, torch.float32),
+                                  _ptr(g_t, torch.float32), _ptr(g_d, torch.float32),
+                                  _ptr(pm, torch.float32), _stream()))
+    return logz, g_e, g_t, g_d, pm
+
+
+def semicrf_fwd_bwd_profiled(emis, lengths, trans, dur, grad_logz=None, ckpt_interval=0,
+                             flags=SEMICRF_CENTER, workspace=None, out=None):
+    """semicrf_fwd_bwd plus per-stage HIP-event times; returns (outputs, [ms x 4])."""
+    B, T, C = emis.shape
+    K = dur.shape[0]
+    dev = emis.device
+    if workspace is None:
+        workspace = alloc_workspace(B, T, K, C, ckpt_interval, True, dev)
+    if out is None:
+        out = (torch.empty(B, dtype=torch.float32, device=dev),
+               torch.empty((B, T, C), dtype=torch.float32, device=dev),
+               torch.empty((C, C), dtype=torch.float32, device=dev),
+               torch.empty((K, C), dtype=torch.float32, device=dev),
+               torch.empty((B, T, C), dtype=torch.float32, device=dev))
+    logz, g_e, g_t, g_d, pm = out
+    ms = (ctypes.c_float * 4)()
+    _check(load().semicrf_fwd_bwd_profiled(
+        _ptr(emis, torch.float32), _ptr(lengths, torch.int32), _ptr(trans, torch.float32),
+        _ptr(dur, torch.float32), _ptr(grad_logz, torch.float32), B, T, K, C, ckpt_interval, flags,
+        workspace.data_ptr(), workspace.numel(), _ptr(logz, torch.float32),
+        _ptr(g_e, torch.float32), _ptr(g_t, torch.float32), _ptr(g_d, torch.float32),
+        _ptr(pm, torch.float32), _stream(), ms))
+    return out, [float(x) for x in ms]

@@ -1,0 +1,1012 @@
+// Streaming semi-Markov CRF forward-backward for gfx950 (MI355X).
+//
+// Numerical design.  The paper runs the recurrences of Algorithm 1 / Algorithm 3
+// in the log domain in fp32 and renormalises at checkpoints.  CDNA issues fp64
+// FMA at the same rate as unpacked fp32 FMA, so here the recurrences run in the
+// LINEAR (probability) domain in fp64 with explicit power-of-two scaling; there
+// is no exp/log inside any scan.  With a = exp(alpha), the factorised form of
+// Eq. 4 (the transition does not depend on k, the rest not on the source label)
+// reads, for a sequence with centred prefix sums S (Eq. 2):
+//
+//   forward   x_t(c) = sum_k W[k,c] q_{t-k}(c)            W = exp(dur)
+//             a_t(c) = E_t(c) x_t(c)                       E_t(c) = exp(S[t,c])
+//             z_t(c) = sum_c' a_t(c') Etr[c',c]            Etr = exp(trans)
+//             q_t(c) = z_t(c) / E_t(c)                     (K-deep ring of q)
+//   backward  p_t(c) = (1/E_t(c)) sum_k W[k,c] v_{t+k}(c)
+//             b_t(c') = sum_c Etr[c',c] p_t(c)             b = exp(beta)
+//             v_t(c') = b_t(c') E_t(c')                    (K-deep ring of v)
+//   marginal  sum_c' mu(t,k,c,c') = q_t(c) W[k,c] v_{t+k}(c) / Z
+//
+// exp(S) would overflow, so positions are grouped in blocks of J positions and
+// E is stored relative to a per-block, per-label power of two:
+// ES_t(c) = exp(S[t,c] - n_j(c) ln 2), n_j(c) = round(S[jJ,c]/ln 2).  Rings are kept
+// relative to the block of the position last processed and to one global
+// power-of-two scale Y per direction; both are changed only by exact
+// multiplications by powers of two at block boundaries.  logZ = Y ln 2 +
+// log(sum_c a_L(c)).
+//
+// Kernels: k_tables, k_colsum, k_prep_seq, k_prefix (Eq. 1-2), k_scan (Algorithm 1
+// and the beta recurrence of Algorithm 3 as two concurrent scans that write ring
+// checkpoints every Delta positions), k_interval (per checkpoint interval:
+// recompute the forward messages, run beta across the interval, accumulate the
+// expected sufficient statistics in registers/LDS, no global atomics),
+// k_fin_seq / k_fin_emis / k_fin_params (fixed-order reductions).
+#include <hip/hip_runtime.h>
+#include <float.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "semicrf.h"
+
+namespace {
+
+constexpr int NT = 256;          // threads per workgroup in the scan kernels
+constexpr int PREP_CH = 256;     // positions per prefix-sum chunk (multiple of JMAX)
+constexpr int JMAX = 32;         // largest scaling block
+constexpr int NSLOT_MAX = 512;   // persistent workgroups of the interval kernel
+constexpr int GRAD_CMAX = 64;    // most labels the gradient path holds transition accumulators for
+constexpr double LN2 = 0.6931471805599453094;
+constexpr double LOG2E = 1.4426950408889634074;
+constexpr double RANGE_NATS = 250.0;  // growth allowed inside one scaling block
+constexpr size_t LDS_LIMIT = 160 * 1024;
+
+struct SeqHdr {
+    int L;          // clamped length
+    int J;          // scaling block length (power of two <= JMAX)
+    int flags;      // bit 0: scores exceed the supported per-position range
+    int pad;
+    double logZ;    // from the forward scan
+    double logZb;   // from the backward scan (diagnostic: must equal logZ)
+};
+
+struct Params {
+    // problem
+    const float *emis;
+    const int32_t *lengths;
+    const float *trans;
+    const float *dur;
+    const float *grad_logz;
+    int B, T, K, C;
+    int Delta, N;       // checkpoint interval and intervals per padded sequence
+    int NCH;            // prefix-sum chunks per sequence (covers t = 0..T)
+    int center;
+    int want_grad;
+    int nslot;
+    // workspace
+    SeqHdr *hdr;        // [B]
+    double *nu;         // [B][C]
+    double *chsum;      // [B][NCH][C] chunk sums, then exclusive chunk offsets
+    double *chmax;      // [B][NCH]
+    double *tabmax;     // [2]: max dur, max trans
+    double *W;          // [K][C]
+    double *Etr;        // [C][C]
+    double *ES;         // [B][T+1][C]
+    double *IES;        // [B][T+1][C]
+    int *nbase;         // [B][T+1][C] (row j = scaling block j)
+    double *ckA;        // [B][N+1][K*C + C]
+    double *ckB;        // [B][N+1][K*C + C]
+    double *ckYA;       // [B][N+1]
+    double *ckYB;       // [B][N+1]
+    double *aloc;       // [nslot][Delta][2C]
+    double *alocY;      // [nslot][Delta]
+    double *partD;      // [B][N][K][C]
+    double *partTr;     // [B][N][C][C]
+    double *tot;        // [B][N][C]
+    double *sumR;       // [B][N][C]
+    double *carry;      // [B][N][C]
+    double *mean;       // [B][C]
+    // outputs
+    double *cum;        // optional [B][T+1][C]
+    float *logz;
+    float *grad_emis;
+    float *grad_trans;
+    float *grad_dur;
+    float *pos_marg;
+};
+
+__device__ __forceinline__ int seq_len(const Params &p, int b)
+{
+    int L = p.lengths ? p.lengths[b] : p.T;
+    L = L < 0 ? 0 : L;
+    return L > p.T ? p.T : L;
+}
+
+// ---------------------------------------------------------------------------
+// exp(dur), exp(trans) in fp64 and the maxima that bound per-step growth.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(NT) void k_tables(Params p)
+{
+    __shared__ double red[NT];
+    const int tid = threadIdx.x;
+    const int KC = p.K * p.C, CC = p.C * p.C;
+    if (!p.dur || !p.trans) {  // prefix sums only: growth is bounded by the emissions alone
+        if (tid < 2) p.tabmax[tid] = 0.0;
+        return;
+    }
+    double mxd = -DBL_MAX, mxt = -DBL_MAX;
+    for (int i = tid; i < KC; i += NT) {
+        double v = (double)p.dur[i];
+        p.W[i] = exp(v);
+        mxd = fmax(mxd, v);
+    }
+    for (int i = tid; i < CC; i += NT) {
+        double v = (double)p.trans[i];
+        p.Etr[i] = exp(v);
+        mxt = fmax(mxt, v);
+    }
+    red[tid] = mxd;
+    __syncthreads();
+    if (tid == 0) {
+        double m = red[0];
+        for (int i = 1; i < NT; ++i) m = fmax(m, red[i]);
+        p.tabmax[0] = m;
+    }
+    __syncthreads();
+    red[tid] = mxt;
+    __syncthreads();
+    if (tid == 0) {
+        double m = red[0];
+        for (int i = 1; i < NT; ++i) m = fmax(m, red[i]);
+        p.tabmax[1] = m;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Eq. 1, stage 1: per-chunk column sums (fp64) and |f| maxima.  grid (NCH, B).
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(NT) void k_colsum(Params p)
+{
+    __shared__ double red[NT];
+    __shared__ double redm[NT];
+    const int b = blockIdx.y, ch = blockIdx.x, tid = threadIdx.x;
+    const int C = p.C, L = seq_len(p, b);
+    const int u0 = ch * PREP_CH;
+    const int u1 = min(u0 + PREP_CH, L);
+    const int R = NT / C;  // rows handled per pass
+    const int r = tid / C, c = tid % C;
+    double acc = 0.0, mx = 0.0;
+    if (r < R) {
+        const float *f = p.emis + ((size_t)b * p.T) * C;
+        for (int u = u0 + r; u < u1; u += R) {
+            double v = (double)f[(size_t)u * C + c];
+            acc += v;
+            mx = fmax(mx, fabs(v));
+        }
+    }
+    red[tid] = acc;
+    redm[tid] = mx;
+    __syncthreads();
+    if (tid < C) {
+        double s = 0.0;
+        for (int i = 0; i < R; ++i) s += red[i * C + tid];
+        p.chsum[((size_t)b * p.NCH + ch) * C + tid] = s;
+    }
+    if (tid == 0) {
+        double m = 0.0;
+        for (int i = 0; i < R * C; ++i) m = fmax(m, redm[i]);
+        p.chmax[(size_t)b * p.NCH + ch] = m;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Eq. 1, stage 2: nu = mean over valid positions; chunk sums -> exclusive
+// offsets of the centred prefix sum; scaling block length J.  grid B.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(NT) void k_prep_seq(Params p)
+{
+    __shared__ double numax[NT];
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int C = p.C, L = seq_len(p, b);
+    double mynu = 0.0;
+    if (tid < C) {
+        double *cs = p.chsum + ((size_t)b * p.NCH) * C + tid;
+        double total = 0.0;
+        for (int ch = 0; ch < p.NCH; ++ch) total += cs[(size_t)ch * C];
+        mynu = (p.center && L > 0) ? total / (double)L : 0.0;
+        p.nu[(size_t)b * C + tid] = mynu;
+        double pref = 0.0;  // raw prefix sum at the chunk start
+        for (int ch = 0; ch < p.NCH; ++ch) {
+            double s = cs[(size_t)ch * C];
+            int u0 = ch * PREP_CH;
+            int nvalid = min(u0, L);
+            cs[(size_t)ch * C] = pref - (double)nvalid * mynu;
+            pref += s;
+        }
+    }
+    numax[tid] = tid < C ? fabs(mynu) : 0.0;
+    __syncthreads();
+    if (tid == 0) {
+        double fm = 0.0;
+        for (int ch = 0; ch < p.NCH; ++ch) fm = fmax(fm, p.chmax[(size_t)b * p.NCH + ch]);
+        double nm = 0.0;
+        for (int i = 0; i < C; ++i) nm = fmax(nm, numax[i]);
+        fm += nm;  // bound on |f - nu|
+        double dmax = p.tabmax[0], tmax = p.tabmax[1];
+        double grow = fm + fmax(dmax, 0.0) + fmax(tmax, 0.0) + log((double)p.K * (double)C);
+        double shrink = fm + fmax(-dmax, 0.0) + fmax(-tmax, 0.0);
+        double r = fmax(fmax(grow, shrink), 1e-9);
+        int J = 1, flags = 0;
+        if (!(r <= RANGE_NATS)) flags = 1;  // also catches NaN
+        while (J < JMAX && (double)(2 * J) * r <= RANGE_NATS) J *= 2;
+        SeqHdr h;
+        h.L = L; h.J = J; h.flags = flags; h.pad = 0; h.logZ = 0.0; h.logZb = 0.0;
+        p.hdr[b] = h;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Eq. 2: centred prefix sums S[t,c] (fp64, sequential inside a chunk), the
+// per-block exponents n_j(c) and ES = exp(S - n ln2), IES = 1/ES.  grid (NCH,B),
+// one thread per label.
+// ---------------------------------------------------------------------------
+__global__ void k_prefix(Params p)
+{
+    const int b = blockIdx.y, ch = blockIdx.x;
+    const int C = p.C;
+    const SeqHdr h = p.hdr[b];
+    const int L = h.L, J = h.J;
+    const int t0 = ch * PREP_CH;
+    for (int c = threadIdx.x; c < C; c += blockDim.x) {
+        const float *f = p.emis + ((size_t)b * p.T) * C + c;
+        const double nu = p.nu[(size_t)b * C + c];
+        double S = p.chsum[((size_t)b * p.NCH + ch) * C + c];
+        double base = 0.0;
+        const size_t row0 = (size_t)b * (p.T + 1);
+        const int tend = min(t0 + PREP_CH, p.T + 1);
+        for (int t = t0; t < tend; ++t) {
+            if (t <= L) {
+                if ((t % J) == 0) {
+                    double n = rint(S * LOG2E);
+                    p.nbase[(row0 + (size_t)(t / J)) * C + c] = (int)n;
+                    base = n * LN2;
+                }
+                double x = S - base;
+                p.ES[(row0 + t) * C + c] = exp(x);
+                p.IES[(row0 + t) * C + c] = exp(-x);
+                if (p.cum) p.cum[(row0 + t) * C + c] = S;
+                if (t < L) S += (double)f[(size_t)t * C] - nu;
+            } else if (p.cum) {
+                p.cum[(row0 + t) * C + c] = 0.0;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Shared pieces of the scans.  LDS layout (doubles), CP1 = C|1 (odd row stride
+// so that both orientations of the transition product are bank-conflict free):
+//   ring[K*C]  Wl[K*C]  El[C*CP1]  red[G*C]  yv[C]  zv[C]  av[C]  qv[C]  sc[C](int)
+//   (interval kernel only) accD[K*C]
+// ---------------------------------------------------------------------------
+struct Lds {
+    double *ring, *Wl, *El, *red, *yv, *zv, *av, *qv, *accD;
+    int *sc;
+};
+
+__host__ __device__ inline size_t lds_doubles(int K, int C, int G, bool interval)
+{
+    size_t CP1 = (size_t)(C | 1);
+    size_t n = 2 * (size_t)K * C + (size_t)C * CP1 + (size_t)G * C + 5 * (size_t)C;
+    if (interval) n += (size_t)K * C;
+    return n;
+}
+
+__device__ __forceinline__ Lds carve(double *base, int K, int C, int G, bool interval)
+{
+    Lds l;
+    const int CP1 = C | 1;
+    double *q = base;
+    l.ring = q; q += K * C;
+    l.Wl = q;   q += K * C;
+    l.El = q;   q += C * CP1;
+    l.red = q;  q += G * C;
+    l.yv = q;   q += C;
+    l.zv = q;   q += C;
+    l.av = q;   q += C;
+    l.qv = q;   q += C;
+    l.sc = (int *)q; q += C;
+    l.accD = interval ? q : nullptr;
+    return l;
+}
+
+__device__ __forceinline__ void load_tables(const Params &p, const Lds &l, int tid)
+{
+    const int KC = p.K * p.C, C = p.C, CP1 = C | 1;
+    for (int i = tid; i < KC; i += NT) l.Wl[i] = p.W[i];
+    for (int i = tid; i < C * C; i += NT) l.El[(i / C) * CP1 + (i % C)] = p.Etr[i];
+}
+
+// max of a C-vector in LDS, computed redundantly by every thread (uniform result)
+__device__ __forceinline__ double vec_max(const double *v, int C)
+{
+    double m = 0.0;
+    for (int i = 0; i < C; ++i) m = fmax(m, v[i]);
+    return m;
+}
+
+__device__ __forceinline__ int safe_exponent(double m)
+{
+    if (!(m > 0.0) || !(m < DBL_MAX)) return 0;
+    int e;
+    (void)frexp(m, &e);
+    return e;
+}
+
+// Rescale the ring when the scan enters scaling block jnew from block jold:
+// every entry of label c is multiplied by 2^(sgn*(n_new-n_old) - e), e being the
+// exponent of the largest entry of the previous message vector.  Returns e.
+__device__ __forceinline__ int rebase_ring(const Params &p, const Lds &l, const int *nb,
+                                           int jnew, int jold, int sgn, double prevmax, int tid)
+{
+    const int C = p.C, KC = p.K * p.C;
+    const int e = safe_exponent(prevmax);
+    if (tid < C) l.sc[tid] = sgn * (nb[(size_t)jnew * C + tid] - nb[(size_t)jold * C + tid]) - e;
+    __syncthreads();
+    for (int i = tid; i < KC; i += NT) {
+        double v = ldexp(l.ring[i], l.sc[i % C]);
+        l.ring[i] = fmin(v, DBL_MAX);
+    }
+    __syncthreads();
+    return e;
+}
+
+// sum_k W[k,c] * ring[(t -/+ k) mod K][c] over this thread's strip of k.
+template <bool BWD>
+__device__ __forceinline__ double strip_sum(const Lds &l, int K, int C, int G, int g, int c, int s0)
+{
+    double acc = 0.0;
+    for (int k = g + 1; k <= K; k += G) {
+        int slot = BWD ? s0 + k : s0 - k;
+        if (BWD) { if (slot >= K) slot -= K; } else { if (slot < 0) slot += K; }
+        acc = fma(l.Wl[(k - 1) * C + c], l.ring[slot * C + c], acc);
+    }
+    return acc;
+}
+
+// One forward step at position t (Algorithm 1 body in the linear domain).
+// On exit yv = a_t (scaled), ring[t mod K] = q_t.  Two barriers inside, one at exit.
+__device__ __forceinline__ void fwd_step(const Params &p, const Lds &l, int G, int tid, int t,
+                                         const double *ESrow, const double *IESrow)
+{
+    const int K = p.K, C = p.C, CP1 = C | 1;
+    const int g = tid / C, c = tid % C;
+    const int s0 = t % K;
+    if (g < G) l.red[g * C + c] = strip_sum<false>(l, K, C, G, g, c, s0);
+    __syncthreads();
+    if (tid < C) {
+        double x = 0.0;
+        for (int i = 0; i < G; ++i) x += l.red[i * C + tid];
+        l.yv[tid] = x * ESrow[tid];
+    }
+    __syncthreads();
+    if (tid < C) {
+        double z = 0.0;
+        for (int cp = 0; cp < C; ++cp) z = fma(l.yv[cp], l.El[cp * CP1 + tid], z);
+        l.ring[s0 * C + tid] = z * IESrow[tid];
+    }
+    __syncthreads();
+}
+
+// ---------------------------------------------------------------------------
+// The two sequential scans.  grid = B (forward only) or 2B (blockIdx&1 = direction).
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(NT) void k_scan(Params p, int both)
+{
+    extern __shared__ double lds_raw[];
+    const int tid = threadIdx.x;
+    const int b = both ? (int)(blockIdx.x >> 1) : (int)blockIdx.x;
+    const int dir = both ? (int)(blockIdx.x & 1) : 0;
+    const int K = p.K, C = p.C, KC = K * C, CP1 = C | 1;
+    const int G = min(NT / C, K);
+    const Lds l = carve(lds_raw, K, C, G, false);
+    const SeqHdr h = p.hdr[b];
+    const int L = h.L, J = h.J, Delta = p.Delta;
+    const size_t row0 = (size_t)b * (p.T + 1);
+    const double *ES = p.ES + row0 * C;
+    const double *IES = p.IES + row0 * C;
+    const int *nb = p.nbase + row0 * C;
+    const size_t ckstride = (size_t)KC + C;
+
+    load_tables(p, l, tid);
+    for (int i = tid; i < KC; i += NT) l.ring[i] = 0.0;
+    __syncthreads();
+
+    double Y = 0.0;
+    if (dir == 0) {
+        // ---- t = 0: a_0 = 1, q_0 = (sum_c' Etr[c',c]) / E_0(c)
+        if (tid < C) {
+            l.yv[tid] = 1.0;
+            double z = 0.0;
+            for (int cp = 0; cp < C; ++cp) z += l.El[cp * CP1 + tid];
+            l.ring[tid] = z * IES[tid];
+        }
+        __syncthreads();
+        if (p.want_grad) {
+            double *ck = p.ckA + ((size_t)b * (p.N + 1)) * ckstride;
+            for (int i = tid; i < KC; i += NT) ck[i] = l.ring[i];
+            if (tid < C) ck[KC + tid] = l.yv[tid];
+            if (tid == 0) p.ckYA[(size_t)b * (p.N + 1)] = 0.0;
+        }
+        for (int t = 1; t <= L; ++t) {
+            if ((t % J) == 0) {
+                double pm = vec_max(l.yv, C);
+                Y += (double)rebase_ring(p, l, nb, t / J, t / J - 1, +1, pm, tid);
+            }
+            fwd_step(p, l, G, tid, t, ES + (size_t)t * C, IES + (size_t)t * C);
+            if (p.want_grad && (t % Delta) == 0) {
+                const int i = t / Delta;
+                double *ck = p.ckA + ((size_t)b * (p.N + 1) + i) * ckstride;
+                for (int j = tid; j < KC; j += NT) ck[j] = l.ring[j];
+                if (tid < C) ck[KC + tid] = l.yv[tid];
+                if (tid == 0) p.ckYA[(size_t)b * (p.N + 1) + i] = Y;
+            }
+        }
+        if (tid == 0) {
+            double s = 0.0;
+            for (int c = 0; c < C; ++c) s += l.yv[c];
+            double lz = Y * LN2 + log(s);
+            p.hdr[b].logZ = lz;
+            p.logz[b] = (float)lz;
+        }
+    } else {
+        // ---- t = L: b_L = 1, v_L = E_L
+        if (tid < C) {
+            l.zv[tid] = 1.0;
+            if (L > 0) l.ring[(L % K) * C + tid] = ES[(size_t)L * C + tid];
+        }
+        __syncthreads();
+        for (int t = L - 1; t >= 0; --t) {
+            if (((t + 1) % J) == 0) {
+                double pm = vec_max(l.zv, C);
+                Y += (double)rebase_ring(p, l, nb, t / J, t / J + 1, -1, pm, tid);
+            }
+            const int g = tid / C, c = tid % C;
+            const int s0 = t % K;
+            if (g < G) l.red[g * C + c] = strip_sum<true>(l, K, C, G, g, c, s0);
+            __syncthreads();
+            if (tid < C) {
+                double x = 0.0;
+                for (int i = 0; i < G; ++i) x += l.red[i * C + tid];
+                l.yv[tid] = x * IES[(size_t)t * C + tid];
+            }
+            __syncthreads();
+            if (tid < C) {
+                double z = 0.0;
+                for (int cc = 0; cc < C; ++cc) z = fma(l.El[tid * CP1 + cc], l.yv[cc], z);
+                l.zv[tid] = z;
+                l.ring[s0 * C + tid] = z * ES[(size_t)t * C + tid];
+            }
+            __syncthreads();
+            if (t > 0 && (t % Delta) == 0) {
+                const int i = t / Delta;
+                double *ck = p.ckB + ((size_t)b * (p.N + 1) + i) * ckstride;
+                for (int j = tid; j < KC; j += NT) ck[j] = l.ring[j];
+                if (tid < C) ck[KC + tid] = l.zv[tid];
+                if (tid == 0) p.ckYB[(size_t)b * (p.N + 1) + i] = Y;
+            }
+        }
+        if (tid == 0) {
+            double s = 0.0;
+            for (int c = 0; c < C; ++c) s += l.zv[c];
+            p.hdr[b].logZb = Y * LN2 + log(s);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Per-interval backward work (Algorithm 3 body for one checkpoint interval):
+// restore the forward ring from the checkpoint, recompute a_t and q_t for the
+// interval, then run the backward recurrence across it from the backward
+// checkpoint, accumulating
+//   partD[k,c]  += q_t(c) W[k,c] v_{t+k}(c) / Z                (duration bias)
+//   partTr[c',c] += a_t(c') p_t(c) / Z     (times Etr at the end; transitions)
+//   d_t(c) = out_t(c) - in_t(c), out = z_t p_t / Z (a c-segment starts at t),
+//            in = a_t b_t / Z (a c-segment ends at t); the running sum of d over
+//            positions is the position marginal.
+// Persistent workgroups: task = (sequence, interval).
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(NT) void k_interval(Params p)
+{
+    extern __shared__ double lds_raw[];
+    const int tid = threadIdx.x;
+    const int K = p.K, C = p.C, KC = K * C, CP1 = C | 1, CC = C * C;
+    const int G = min(NT / C, K);
+    const Lds l = carve(lds_raw, K, C, G, true);
+    const int Delta = p.Delta, N = p.N;
+    const size_t ckstride = (size_t)KC + C;
+    double *aloc = p.aloc + (size_t)blockIdx.x * Delta * 2 * C;
+    double *alocY = p.alocY + (size_t)blockIdx.x * Delta;
+    constexpr int TRP = GRAD_CMAX * GRAD_CMAX / NT;  // transition pairs per thread
+    load_tables(p, l, tid);
+    __syncthreads();
+
+    const int ntask = p.B * N;
+    for (int task = blockIdx.x; task < ntask; task += gridDim.x) {
+        const int b = task / N, iv = task % N;
+        const SeqHdr h = p.hdr[b];
+        const int L = h.L, J = h.J;
+        const int t0 = iv * Delta;
+        if (t0 >= L) continue;  // uniform
+        const int t1 = min(t0 + Delta, L);
+        const size_t row0 = (size_t)b * (p.T + 1);
+        const double *ES = p.ES + row0 * C;
+        const double *IES = p.IES + row0 * C;
+        const int *nb = p.nbase + row0 * C;
+        const double logZ = h.logZ;
+
+        // ------------------------------------------------ forward recompute
+        {
+            const double *ck = p.ckA + ((size_t)b * (N + 1) + iv) * ckstride;
+            for (int i = tid; i < KC; i += NT) l.ring[i] = ck[i];
+            if (tid < C) l.yv[tid] = ck[KC + tid];
+        }
+        double Y = p.ckYA[(size_t)b * (N + 1) + iv];
+        __syncthreads();
+        if (tid < C) {
+            aloc[tid] = l.yv[tid];
+            aloc[C + tid] = l.ring[(t0 % K) * C + tid];
+        }
+        if (tid == 0) alocY[0] = Y;
+        for (int t = t0 + 1; t < t1; ++t) {
+            if ((t % J) == 0) {
+                double pm = vec_max(l.yv, C);
+                Y += (double)rebase_ring(p, l, nb, t / J, t / J - 1, +1, pm, tid);
+            }
+            fwd_step(p, l, G, tid, t, ES + (size_t)t * C, IES + (size_t)t * C);
+            if (tid < C) {
+                double *row = aloc + (size_t)(t - t0) * 2 * C;
+                row[tid] = l.yv[tid];
+                row[C + tid] = l.ring[(t % K) * C + tid];
+            }
+            if (tid == 0) alocY[t - t0] = Y;
+        }
+        __syncthreads();
+
+        // ------------------------------------------------ backward across the interval
+        double Yb;
+        if (t1 == L) {
+            for (int i = tid; i < KC; i += NT) l.ring[i] = 0.0;
+            __syncthreads();
+            if (tid < C) {
+                l.zv[tid] = 1.0;
+                l.ring[(L % K) * C + tid] = ES[(size_t)L * C + tid];
+            }
+            Yb = 0.0;
+        } else {
+            const int ci = t1 / Delta;
+            const double *ck = p.ckB + ((size_t)b * (N + 1) + ci) * ckstride;
+            for (int i = tid; i < KC; i += NT) l.ring[i] = ck[i];
+            if (tid < C) l.zv[tid] = ck[KC + tid];
+            Yb = p.ckYB[(size_t)b * (N + 1) + ci];
+        }
+        for (int i = tid; i < KC; i += NT) l.accD[i] = 0.0;
+        double accTr[TRP];
+#pragma unroll
+        for (int j = 0; j < TRP; ++j) accTr[j] = 0.0;
+        double R = 0.0, sR = 0.0;  // running suffix sum of d and its sum (threads < C)
+        double kappa = 0.0, kY = -1.0e300;
+        __syncthreads();
+
+        for (int t = t1 - 1; t >= t0; --t) {
+            if (((t + 1) % J) == 0) {
+                double pm = vec_max(l.zv, C);
+                Yb += (double)rebase_ring(p, l, nb, t / J, t / J + 1, -1, pm, tid);
+            }
+            const double *row = aloc + (size_t)(t - t0) * 2 * C;
+            if (tid < C) {
+                l.av[tid] = row[tid];
+                l.qv[tid] = row[C + tid];
+            }
+            const double ysum = alocY[t - t0] + Yb;
+            if (ysum != kY) {  // uniform
+                kY = ysum;
+                kappa = exp(ysum * LN2 - logZ);
+            }
+            __syncthreads();
+            const int g = tid / C, c = tid % C;
+            const int s0 = t % K;
+            if (g < G) {
+                const double coef = l.qv[c] * kappa;
+                double acc = 0.0;
+                for (int k = g + 1; k <= K; k += G) {
+                    int slot = s0 + k;
+                    if (slot >= K) slot -= K;
+                    double prod = l.Wl[(k - 1) * C + c] * l.ring[slot * C + c];
+                    acc += prod;
+                    l.accD[(k - 1) * C + c] = fma(coef, prod, l.accD[(k - 1) * C + c]);
+                }
+                l.red[g * C + c] = acc;
+            }
+            __syncthreads();
+            double outv = 0.0;
+            if (tid < C) {
+                double x = 0.0;
+                for (int i = 0; i < G; ++i) x += l.red[i * C + tid];
+                l.yv[tid] = x * IES[(size_t)t * C + tid];
+                outv = l.qv[tid] * x * kappa;
+            }
+            __syncthreads();
+            if (tid < C) {
+                double z = 0.0;
+                for (int cc = 0; cc < C; ++cc) z = fma(l.El[tid * CP1 + cc], l.yv[cc], z);
+                l.zv[tid] = z;
+                l.ring[s0 * C + tid] = z * ES[(size_t)t * C + tid];
+                const double inv = t >= 1 ? l.av[tid] * z * kappa : 0.0;
+                p.grad_emis[((size_t)b * p.T + t) * C + tid] = (float)R;
+                sR += R;
+                R += outv - inv;
+            }
+#pragma unroll
+            for (int j = 0; j < TRP; ++j) {
+                const int idx = tid + j * NT;
+                if (idx < CC) accTr[j] = fma(l.av[idx / C] * kappa, l.yv[idx % C], accTr[j]);
+            }
+            __syncthreads();
+        }
+
+        double *pD = p.partD + ((size_t)b * N + iv) * KC;
+        for (int i = tid; i < KC; i += NT) pD[i] = l.accD[i];
+        double *pT = p.partTr + ((size_t)b * N + iv) * CC;
+#pragma unroll
+        for (int j = 0; j < TRP; ++j) {
+            const int idx = tid + j * NT;
+            if (idx < CC) pT[idx] = accTr[j];
+        }
+        if (tid < C) {
+            p.tot[((size_t)b * N + iv) * C + tid] = R;
+            p.sumR[((size_t)b * N + iv) * C + tid] = sR;
+        }
+        __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Finalisation (fixed-order reductions).
+// ---------------------------------------------------------------------------
+// carry[b,i,c] = sum_{i'<=i} tot[b,i',c];  mean[b,c] = (1/L) sum_u pm[b,u,c].  grid B.
+__global__ void k_fin_seq(Params p)
+{
+    const int b = blockIdx.x, C = p.C, N = p.N;
+    const int L = p.hdr[b].L;
+    const int nint = (L + p.Delta - 1) / p.Delta;
+    for (int c = threadIdx.x; c < C; c += blockDim.x) {
+        double run = 0.0, total = 0.0;
+        for (int i = 0; i < nint; ++i) {
+            const size_t o = ((size_t)b * N + i) * C + c;
+            run += p.tot[o];
+            p.carry[o] = run;
+            const int n = min(p.Delta, L - i * p.Delta);
+            total += (double)n * run - p.sumR[o];
+        }
+        p.mean[(size_t)b * C + c] = (p.center && L > 0) ? total / (double)L : 0.0;
+    }
+}
+
+// grad_emis / pos_marg, elementwise over (b,u,c).
+__global__ __launch_bounds__(NT) void k_fin_emis(Params p)
+{
+    const size_t n = (size_t)p.B * p.T * p.C;
+    const int C = p.C;
+    for (size_t idx = (size_t)blockIdx.x * NT + threadIdx.x; idx < n; idx += (size_t)gridDim.x * NT) {
+        const int c = (int)(idx % C);
+        const size_t bu = idx / C;
+        const int u = (int)(bu % p.T);
+        const int b = (int)(bu / p.T);
+        const int L = p.hdr[b].L;
+        float ge = 0.f, pmv = 0.f;
+        if (u < L) {
+            const int i = u / p.Delta;
+            const double pm = p.carry[((size_t)b * p.N + i) * C + c] - (double)p.grad_emis[idx];
+            const double w = p.grad_logz ? (double)p.grad_logz[b] : 1.0;
+            ge = (float)(w * (pm - p.mean[(size_t)b * C + c]));
+            pmv = (float)pm;
+        }
+        p.grad_emis[idx] = ge;
+        if (p.pos_marg) p.pos_marg[idx] = pmv;
+    }
+}
+
+// grad_trans[c',c] = Etr[c',c] * sum_b w_b sum_i partTr;  grad_dur[k,c] = sum_b w_b sum_i partD.
+__global__ __launch_bounds__(NT) void k_fin_params(Params p)
+{
+    const int C = p.C, CC = C * C, KC = p.K * C, N = p.N;
+    const int idx = blockIdx.x * NT + threadIdx.x;
+    if (idx >= CC + KC) return;
+    double acc = 0.0;
+    for (int b = 0; b < p.B; ++b) {
+        const int L = p.hdr[b].L;
+        const int nint = (L + p.Delta - 1) / p.Delta;
+        const double w = p.grad_logz ? (double)p.grad_logz[b] : 1.0;
+        double s = 0.0;
+        if (idx < CC) {
+            const double *q = p.partTr + ((size_t)b * N) * CC + idx;
+            for (int i = 0; i < nint; ++i) s += q[(size_t)i * CC];
+        } else {
+            const double *q = p.partD + ((size_t)b * N) * KC + (idx - CC);
+            for (int i = 0; i < nint; ++i) s += q[(size_t)i * KC];
+        }
+        acc = fma(w, s, acc);
+    }
+    if (idx < CC) p.grad_trans[idx] = (float)(acc * p.Etr[idx]);
+    else p.grad_dur[idx - CC] = (float)acc;
+}
+
+// ---------------------------------------------------------------------------
+// Host side: sizing, workspace carving, launches.
+// ---------------------------------------------------------------------------
+inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+int auto_interval(int B, int T, int K)
+{
+    double d = ceil(sqrt((double)T * (double)K * (double)B / 256.0));
+    if (d < 1.0) d = 1.0;
+    if (d > (double)T) d = (double)T;
+    return (int)d;
+}
+
+struct Plan {
+    int Delta, N, NCH, nslot, G;
+    size_t lds_scan, lds_interval;
+    size_t total;
+    size_t off[24];
+};
+
+int make_plan(int B, int T, int K, int C, int ckpt_interval, int want_grad, Plan *pl)
+{
+    if (B < 1 || T < 1 || K < 1 || C < 1 || ckpt_interval < 0) return SEMICRF_EINVAL;
+    if (C > 256) return SEMICRF_EUNSUPPORTED;
+    if ((double)B * ((double)T + 1.0) * (double)C > 2.0e10) return SEMICRF_EUNSUPPORTED;
+    pl->Delta = ckpt_interval > 0 ? (ckpt_interval > T ? T : ckpt_interval) : auto_interval(B, T, K);
+    pl->N = (T + pl->Delta - 1) / pl->Delta;
+    pl->NCH = T / PREP_CH + 1;
+    pl->G = (NT / C) < K ? (NT / C) : K;
+    pl->lds_scan = lds_doubles(K, C, pl->G, false) * sizeof(double);
+    pl->lds_interval = lds_doubles(K, C, pl->G, true) * sizeof(double);
+    if (pl->lds_scan > LDS_LIMIT) return SEMICRF_EUNSUPPORTED;
+    if (want_grad && (pl->lds_interval > LDS_LIMIT || C > GRAD_CMAX)) return SEMICRF_EUNSUPPORTED;
+    size_t ntask = (size_t)B * pl->N;
+    pl->nslot = (int)(ntask < (size_t)NSLOT_MAX ? ntask : (size_t)NSLOT_MAX);
+    const size_t b = (size_t)B, t1 = (size_t)T + 1, c = (size_t)C, k = (size_t)K, n = (size_t)pl->N;
+    size_t sz[24];
+    int i = 0;
+    sz[i++] = b * sizeof(SeqHdr);                 // 0 hdr
+    sz[i++] = b * c * 8;                          // 1 nu
+    sz[i++] = b * pl->NCH * c * 8;                // 2 chsum
+    sz[i++] = b * pl->NCH * 8;                    // 3 chmax
+    sz[i++] = 2 * 8;                              // 4 tabmax
+    sz[i++] = k * c * 8;                          // 5 W
+    sz[i++] = c * c * 8;                          // 6 Etr
+    sz[i++] = b * t1 * c * 8;                     // 7 ES
+    sz[i++] = b * t1 * c * 8;                     // 8 IES
+    sz[i++] = b * t1 * c * 4;                     // 9 nbase
+    const size_t g = want_grad ? 1 : 0;
+    sz[i++] = g * b * (n + 1) * (k * c + c) * 8;  // 10 ckA
+    sz[i++] = g * b * (n + 1) * (k * c + c) * 8;  // 11 ckB
+    sz[i++] = g * b * (n + 1) * 8;                // 12 ckYA
+    sz[i++] = g * b * (n + 1) * 8;                // 13 ckYB
+    sz[i++] = g * (size_t)pl->nslot * pl->Delta * 2 * c * 8;  // 14 aloc
+    sz[i++] = g * (size_t)pl->nslot * pl->Delta * 8;          // 15 alocY
+    sz[i++] = g * b * n * k * c * 8;              // 16 partD
+    sz[i++] = g * b * n * c * c * 8;              // 17 partTr
+    sz[i++] = g * b * n * c * 8;                  // 18 tot
+    sz[i++] = g * b * n * c * 8;                  // 19 sumR
+    sz[i++] = g * b * n * c * 8;                  // 20 carry
+    sz[i++] = g * b * c * 8;                      // 21 mean
+    size_t off = 0;
+    for (int j = 0; j < i; ++j) {
+        pl->off[j] = off;
+        off += align_up(sz[j]);
+    }
+    pl->total = off;
+    return SEMICRF_OK;
+}
+
+void bind_workspace(Params &p, const Plan &pl, void *ws)
+{
+    char *w = (char *)ws;
+    p.hdr = (SeqHdr *)(w + pl.off[0]);
+    p.nu = (double *)(w + pl.off[1]);
+    p.chsum = (double *)(w + pl.off[2]);
+    p.chmax = (double *)(w + pl.off[3]);
+    p.tabmax = (double *)(w + pl.off[4]);
+    p.W = (double *)(w + pl.off[5]);
+    p.Etr = (double *)(w + pl.off[6]);
+    p.ES = (double *)(w + pl.off[7]);
+    p.IES = (double *)(w + pl.off[8]);
+    p.nbase = (int *)(w + pl.off[9]);
+    p.ckA = (double *)(w + pl.off[10]);
+    p.ckB = (double *)(w + pl.off[11]);
+    p.ckYA = (double *)(w + pl.off[12]);
+    p.ckYB = (double *)(w + pl.off[13]);
+    p.aloc = (double *)(w + pl.off[14]);
+    p.alocY = (double *)(w + pl.off[15]);
+    p.partD = (double *)(w + pl.off[16]);
+    p.partTr = (double *)(w + pl.off[17]);
+    p.tot = (double *)(w + pl.off[18]);
+    p.sumR = (double *)(w + pl.off[19]);
+    p.carry = (double *)(w + pl.off[20]);
+    p.mean = (double *)(w + pl.off[21]);
+}
+
+int check_launch()
+{
+    return hipGetLastError() == hipSuccess ? SEMICRF_OK : SEMICRF_ELAUNCH;
+}
+
+// prefix stage shared by all entry points
+int launch_prep(const Params &p, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_tables, dim3(1), dim3(NT), 0, st, p);
+    hipLaunchKernelGGL(k_colsum, dim3(p.NCH, p.B), dim3(NT), 0, st, p);
+    hipLaunchKernelGGL(k_prep_seq, dim3(p.B), dim3(NT), 0, st, p);
+    int pt = p.C <= 64 ? 64 : (p.C <= 128 ? 128 : 256);
+    hipLaunchKernelGGL(k_prefix, dim3(p.NCH, p.B), dim3(pt), 0, st, p);
+    return check_launch();
+}
+
+// Optional per-stage timing: events are recorded on the caller's stream around
+// the four stages (prefix sums, scans, intervals, finalisation).
+struct StageTimer {
+    hipEvent_t ev[5];
+    int n = 0;
+    bool on = false;
+    hipStream_t st = nullptr;
+    void mark()
+    {
+        if (on && n < 5) hipEventRecord(ev[n++], st);
+    }
+};
+
+int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hipStream_t st,
+        int mode /*0 cum, 1 logz, 2 fwd_bwd*/, StageTimer *tm = nullptr)
+{
+    StageTimer none;
+    StageTimer &T = tm ? *tm : none;
+    Plan pl;
+    int rc = make_plan(p.B, p.T, p.K, p.C, ckpt_interval, mode == 2, &pl);
+    if (rc != SEMICRF_OK) return rc;
+    if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < pl.total)
+        return SEMICRF_EWORKSPACE;
+    p.Delta = pl.Delta;
+    p.N = pl.N;
+    p.NCH = pl.NCH;
+    p.nslot = pl.nslot;
+    p.want_grad = mode == 2;
+    bind_workspace(p, pl, workspace);
+    T.mark();
+    rc = launch_prep(p, st);
+    T.mark();
+    if (rc != SEMICRF_OK || mode == 0) return rc;
+    if (hipFuncSetAttribute((const void *)k_scan, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)pl.lds_scan) != hipSuccess)
+        return SEMICRF_ELAUNCH;
+    hipLaunchKernelGGL(k_scan, dim3(mode == 2 ? 2 * p.B : p.B), dim3(NT), pl.lds_scan, st, p,
+                       mode == 2 ? 1 : 0);
+    T.mark();
+    rc = check_launch();
+    if (rc != SEMICRF_OK || mode == 1) return rc;
+    if (hipFuncSetAttribute((const void *)k_interval, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)pl.lds_interval) != hipSuccess)
+        return SEMICRF_ELAUNCH;
+    hipLaunchKernelGGL(k_interval, dim3(pl.nslot), dim3(NT), pl.lds_interval, st, p);
+    T.mark();
+    hipLaunchKernelGGL(k_fin_seq, dim3(p.B), dim3(64), 0, st, p);
+    {
+        size_t n = (size_t)p.B * p.T * p.C;
+        size_t blocks = (n + NT - 1) / NT;
+        if (blocks > 65536) blocks = 65536;
+        hipLaunchKernelGGL(k_fin_emis, dim3((unsigned)blocks), dim3(NT), 0, st, p);
+    }
+    {
+        int n = p.C * p.C + p.K * p.C;
+        hipLaunchKernelGGL(k_fin_params, dim3((n + NT - 1) / NT), dim3(NT), 0, st, p);
+    }
+    T.mark();
+    return check_launch();
+}
+
+}  // namespace
+
+extern "C" {
+
+int semicrf_version(void) { return 1; }
+
+const char *semicrf_strerror(int status)
+{
+    switch (status) {
+        case SEMICRF_OK: return "ok";
+        case SEMICRF_EINVAL: return "invalid argument";
+        case SEMICRF_EWORKSPACE: return "workspace too small or misaligned";
+        case SEMICRF_EUNSUPPORTED: return "sizes not supported (C > 256, C > 64 with gradients, or K*C exceeds the LDS budget)";
+        case SEMICRF_ELAUNCH: return "HIP launch failure";
+        default: return "unknown status";
+    }
+}
+
+int semicrf_workspace_bytes(int B, int T, int K, int C, int ckpt_interval, int want_grad,
+                            size_t *bytes)
+{
+    if (!bytes) return SEMICRF_EINVAL;
+    Plan pl;
+    int rc = make_plan(B, T, K, C, ckpt_interval, want_grad, &pl);
+    if (rc != SEMICRF_OK) return rc;
+    *bytes = pl.total;
+    return SEMICRF_OK;
+}
+
+int semicrf_cum_scores(const float *emis, const int32_t *lengths, int B, int T, int C,
+                       unsigned flags, void *workspace, size_t workspace_bytes, double *cum,
+                       void *stream)
+{
+    if (!emis || !cum) return SEMICRF_EINVAL;
+    Params p = {};
+    p.emis = emis; p.lengths = lengths;
+    p.B = B; p.T = T; p.K = 1; p.C = C;
+    p.center = (flags & SEMICRF_CENTER) ? 1 : 0;
+    p.cum = cum;
+    return run(p, 0, workspace, workspace_bytes, (hipStream_t)stream, 0);
+}
+
+int semicrf_logz_fwd(const float *emis, const int32_t *lengths, const float *trans,
+                     const float *dur, int B, int T, int K, int C, int ckpt_interval,
+                     unsigned flags, void *workspace, size_t workspace_bytes, float *logz,
+                     void *stream)
+{
+    if (!emis || !trans || !dur || !logz) return SEMICRF_EINVAL;
+    Params p = {};
+    p.emis = emis; p.lengths = lengths; p.trans = trans; p.dur = dur;
+    p.B = B; p.T = T; p.K = K; p.C = C;
+    p.center = (flags & SEMICRF_CENTER) ? 1 : 0;
+    p.logz = logz;
+    return run(p, ckpt_interval, workspace, workspace_bytes, (hipStream_t)stream, 1);
+}
+
+int semicrf_fwd_bwd(const float *emis, const int32_t *lengths, const float *trans,
+                    const float *dur, const float *grad_logz, int B, int T, int K, int C,
+                    int ckpt_interval, unsigned flags, void *workspace, size_t workspace_bytes,
+                    float *logz, float *grad_emis, float *grad_trans, float *grad_dur,
+                    float *pos_marg, void *stream)
+{
+    if (!emis || !trans || !dur || !logz || !grad_emis || !grad_trans || !grad_dur)
+        return SEMICRF_EINVAL;
+    Params p = {};
+    p.emis = emis; p.lengths = lengths; p.trans = trans; p.dur = dur; p.grad_logz = grad_logz;
+    p.B = B; p.T = T; p.K = K; p.C = C;
+    p.center = (flags & SEMICRF_CENTER) ? 1 : 0;
+    p.logz = logz; p.grad_emis = grad_emis; p.grad_trans = grad_trans; p.grad_dur = grad_dur;
+    p.pos_marg = pos_marg;
+    return run(p, ckpt_interval, workspace, workspace_bytes, (hipStream_t)stream, 2);
+}
+
+int semicrf_fwd_bwd_profiled(const float *emis, const int32_t *lengths, const float *trans,
+                             const float *dur, const float *grad_logz, int B, int T, int K, int C,
+                             int ckpt_interval, unsigned flags, void *workspace,
+                             size_t workspace_bytes, float *logz, float *grad_emis,
+                             float *grad_trans, float *grad_dur, float *pos_marg, void *stream,
+                             float *stage_ms)
+{
+    if (!emis || !trans || !dur || !logz || !grad_emis || !grad_trans || !grad_dur || !stage_ms)
+        return SEMICRF_EINVAL;
+    Params p = {};
+    p.emis = emis; p.lengths = lengths; p.trans = trans; p.dur = dur; p.grad_logz = grad_logz;
+    p.B = B; p.T = T; p.K = K; p.C = C;
+    p.center = (flags & SEMICRF_CENTER) ? 1 : 0;
+    p.logz = logz; p.grad_emis = grad_emis; p.grad_trans = grad_trans; p.grad_dur = grad_dur;
+    p.pos_marg = pos_marg;
+    StageTimer tm;
+    tm.on = true;
+    tm.st = (hipStream_t)stream;
+    for (int i = 0; i < 5; ++i)
+        if (hipEventCreate(&tm.ev[i]) != hipSuccess) return SEMICRF_ELAUNCH;
+    int rc = run(p, ckpt_interval, workspace, workspace_bytes, tm.st, 2, &tm);
+    if (rc == SEMICRF_OK && tm.n == 5) {
+        if (hipEventSynchronize(tm.ev[4]) != hipSuccess) rc = SEMICRF_ELAUNCH;
+        for (int i = 0; i < 4 && rc == SEMICRF_OK; ++i)
+            if (hipEventElapsedTime(&stage_ms[i], tm.ev[i], tm.ev[i + 1]) != hipSuccess)
+                rc = SEMICRF_ELAUNCH;
+    }
+    for (int i = 0; i < 5; ++i) hipEventDestroy(tm.ev[i]);
+    return rc;
+}
+
+}  // extern "C"

@@ -1,0 +1,163 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 CPU oracle.
+
+Tolerances (from the stated target): relative 1e-5 on logZ, absolute 1e-4 on
+per-position gradients (grad_emis, pos_marg, all in [-1,1] up to the upstream
+weight); the accumulated gradients grad_trans / grad_dur are sums of up to
+sum_b L_b marginals, so they are held to 1e-4 * max(1, max|g|) and the raw
+maximum error is printed.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2604_18780_amd import binding as sb
+from paper_2604_18780_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def to_dev(w, nan_pad=True):
+    emis = w.emis.copy()
+    if nan_pad:
+        for b in range(w.B):
+            emis[b, int(w.lengths[b]):] = np.nan      # padding must never be read
+    return (torch.from_numpy(emis).to(DEV), torch.from_numpy(w.lengths).to(DEV),
+            torch.from_numpy(w.trans).to(DEV), torch.from_numpy(w.dur).to(DEV))
+
+
+def check_against_oracle(w, center=True, grad_logz=None, ckpt_interval=0, label=""):
+    emis, lengths, trans, dur = to_dev(w)
+    flags = sb.SEMICRF_CENTER if center else 0
+    gl = None if grad_logz is None else torch.from_numpy(grad_logz.astype(np.float32)).to(DEV)
+    print(f"[case] {label or w.name} B={w.B} T={w.T} K={w.K} C={w.C} center={center} "
+          f"delta={ckpt_interval}", flush=True)
+    logz, g_e, g_t, g_d, pm = sb.semicrf_fwd_bwd(emis, lengths, trans, dur, gl, ckpt_interval, flags)
+    logz_f = sb.semicrf_logz_fwd(emis, lengths, trans, dur, ckpt_interval, flags)
+    torch.cuda.synchronize()
+    r = oracle.fwd_bwd(w.emis, w.lengths, w.trans, w.dur, grad_logz=grad_logz, center=center)
+    lz = logz.double().cpu().numpy()
+    assert np.all(np.isfinite(lz))
+    rel = np.abs(lz - r.logz) / np.maximum(1.0, np.abs(r.logz))
+    assert rel.max() <= 1e-5, (rel.max(), lz, r.logz)
+    assert np.array_equal(lz, logz_f.double().cpu().numpy())       # forward-only entry agrees bit for bit
+    e_pm = np.abs(pm.double().cpu().numpy() - r.pos_marg).max()
+    e_ge = np.abs(g_e.double().cpu().numpy() - r.grad_emis).max()
+    wmax = 1.0 if grad_logz is None else max(1.0, float(np.abs(grad_logz).max()))
+    assert e_pm <= 1e-4, e_pm
+    assert e_ge <= 1e-4 * wmax, e_ge
+    e_t = np.abs(g_t.double().cpu().numpy() - r.grad_trans).max()
+    e_d = np.abs(g_d.double().cpu().numpy() - r.grad_dur).max()
+    print(f"       max err: logz rel {rel.max():.2e} pos_marg {e_pm:.2e} grad_emis {e_ge:.2e} "
+          f"grad_trans {e_t:.2e} (max|g| {np.abs(r.grad_trans).max():.3g}) "
+          f"grad_dur {e_d:.2e} (max|g| {np.abs(r.grad_dur).max():.3g})", flush=True)
+    assert e_t <= 1e-4 * max(1.0, np.abs(r.grad_trans).max()), e_t
+    assert e_d <= 1e-4 * max(1.0, np.abs(r.grad_dur).max()), e_d
+    return r
+
+
+def test_tiny_config_exact():
+    check_against_oracle(synth.make("tiny"))
+
+
+def test_tiny_config_no_centering():
+    check_against_oracle(synth.make("tiny"), center=False)
+
+
+@pytest.mark.parametrize("seed,B,T,K,C", [
+    (1, 3, 40, 5, 3), (2, 4, 300, 8, 6), (3, 2, 700, 33, 24), (4, 5, 130, 1, 7),
+    (5, 3, 90, 2, 5), (6, 2, 50, 80, 4), (7, 3, 257, 16, 64), (8, 6, 33, 7, 1),
+    (9, 2, 513, 3, 17), (10, 1, 1, 1, 1),
+])
+def test_random_ragged_cases(seed, B, T, K, C):
+    w = synth.small_random(seed, B, T, K, C, ragged=True)
+    if seed == 2:
+        w.lengths[0] = 0          # empty sequence
+        w.lengths[1] = T          # full sequence
+    rng = np.random.default_rng(seed)
+    check_against_oracle(w, grad_logz=rng.standard_normal(B))
+
+
+def test_large_emission_scale_changes_block_length():
+    # emissions of scale 8 shorten the power-of-two scaling block
+    check_against_oracle(synth.small_random(21, 2, 400, 12, 5, ragged=False, scale=8.0))
+    check_against_oracle(synth.small_random(22, 2, 200, 6, 4, ragged=False, scale=30.0))
+
+
+def test_checkpoint_interval_invariance():
+    w = synth.small_random(31, 2, 210, 9, 5, ragged=True)
+    w.lengths[:] = [210, 100]
+    emis, lengths, trans, dur = to_dev(w)
+    ref = None
+    for delta in [1, 8, 9, 10, 15, 46, 210, 0]:
+        out = sb.semicrf_fwd_bwd(emis, lengths, trans, dur, None, delta)
+        torch.cuda.synchronize()
+        cur = [o.double().cpu().numpy() for o in out]
+        if ref is None:
+            ref = cur
+            check_against_oracle(w, ckpt_interval=delta)
+        else:
+            assert np.array_equal(cur[0], ref[0])                    # logZ does not depend on delta
+            for a, b in zip(cur[1:], ref[1:]):
+                assert np.abs(a - b).max() <= 2e-6
+
+
+def test_padding_independence_and_determinism():
+    w = synth.small_random(41, 3, 120, 10, 6, ragged=True)
+    w.lengths[:] = [120, 77, 5]
+    emis, lengths, trans, dur = to_dev(w)
+    a = sb.semicrf_fwd_bwd(emis, lengths, trans, dur)
+    b = sb.semicrf_fwd_bwd(emis, lengths, trans, dur)
+    torch.cuda.synchronize()
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)                                     # no atomics: bit-reproducible
+    # sequence 1 alone, unpadded
+    L = 77
+    e1 = torch.from_numpy(w.emis[1:2, :L].copy()).to(DEV)
+    l1 = torch.tensor([L], dtype=torch.int32, device=DEV)
+    c = sb.semicrf_fwd_bwd(e1, l1, trans, dur, ckpt_interval=int(0))
+    torch.cuda.synchronize()
+    assert abs(float(c[0][0]) - float(a[0][1])) <= 1e-5 * abs(float(a[0][1]))
+    assert (c[4][0] - a[4][1, :L]).abs().max().item() <= 2e-6
+    assert torch.all(a[4][1, L:] == 0) and torch.all(a[1][1, L:] == 0)
+
+
+def test_cum_scores_matches_oracle_prefix_sums():
+    w = synth.small_random(51, 3, 700, 4, 9, ragged=True)
+    w.lengths[:] = [700, 256, 0]
+    emis, lengths, _, _ = to_dev(w)
+    for center in (True, False):
+        cum = sb.semicrf_cum_scores(emis, lengths, sb.SEMICRF_CENTER if center else 0)
+        torch.cuda.synchronize()
+        r = oracle.fwd_bwd(w.emis, w.lengths, w.trans, w.dur, center=center, tables=True)
+        assert np.abs(cum.cpu().numpy() - r.S).max() <= 1e-9
+
+
+def test_nlp_config():
+    check_against_oracle(synth.make("nlp"))
+
+
+def test_speech_config_reduced_batch():
+    # the speech shape (K=32, C=64, lengths in [T/2, T]) on 6 sequences of T=600
+    check_against_oracle(synth.make("speech", B=6, T=600))
+
+
+def test_genomic_shape_reduced_length():
+    check_against_oracle(synth.make("genomic", T=6000, B=2))
+
+
+def test_longgen_shape_reduced_length():
+    check_against_oracle(synth.make("longgen", T=3000))
+
+
+def test_unsupported_and_invalid_arguments_are_rejected():
+    w = synth.small_random(61, 1, 8, 2, 3, ragged=False)
+    emis, lengths, trans, dur = to_dev(w, nan_pad=False)
+    with pytest.raises(sb.SemiCRFError) as ei:
+        sb.semicrf_fwd_bwd(emis, lengths, trans, dur, workspace=torch.empty(256, dtype=torch.uint8, device=DEV))
+    assert ei.value.status == -2
+    with pytest.raises(sb.SemiCRFError) as ei:
+        sb.semicrf_logz_fwd(emis, lengths, trans, dur, ckpt_interval=-1)
+    assert ei.value.status == -1
