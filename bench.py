@@ -1,0 +1,148 @@
+#!/usr/bin/env python3
+"""Benchmark of the semi-CRF forward-backward hot path on one MI355X.
+
+A step is one whole pass (prefix sums -> forward/backward scans -> per-interval
+marginals -> finalisation) of ``semicrf_fwd_bwd`` over one synthetic batch that
+is already resident in HBM.  The default workload is the genomic configuration
+(B=4, T=100 000, K=64, C=24), the one the metric's positions/s figure is quoted
+on.  Prints ONE JSON line on stdout.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+FP64_VECTOR_PEAK_TFLOPS = 78.6   # MI355X published fp64 vector peak (256 CU x 64 FMA lanes x 2 x 2.4 GHz)
+
+
+def cpu_baseline(name: str, sample_T: int):
+    """The oracle as it stands, timed on the host cores on a bounded prefix-shaped sample."""
+    import oracle
+    from paper_2604_18780_amd import synth
+    w = synth.make(name, T=sample_T)
+    t0 = time.perf_counter()
+    r = oracle.fwd_bwd(w.emis, w.lengths, w.trans, w.dur)
+    dt = time.perf_counter() - t0
+    return {
+        "value": w.nominal_edges / dt,
+        "unit": "edge evals/s",
+        "cores": int(r.threads),
+        "kind": "oracle",
+        "sample": f"{name} workload with T cut to {sample_T} (B={w.B}, K={w.K}, C={w.C}); "
+                  f"{w.nominal_edges:.3g} nominal edges in {dt:.1f} s; "
+                  f"{w.positions / dt:.3g} positions/s",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="genomic",
+                    choices=["tiny", "nlp", "speech", "genomic", "longgen"])
+    ap.add_argument("--ckpt-interval", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-T", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (sequences shard across GPUs with a "
+              "single small all-reduce of the parameter gradients; that path is not built)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2604_18780_amd import binding as sb
+    from paper_2604_18780_amd import synth
+
+    dev = "cuda:0"
+    w = synth.make(args.workload)
+    emis = torch.from_numpy(w.emis).to(dev)
+    lengths = torch.from_numpy(w.lengths).to(dev)
+    trans = torch.from_numpy(w.trans).to(dev)
+    dur = torch.from_numpy(w.dur).to(dev)
+    B, T, K, C = w.B, w.T, w.K, w.C
+    ws_bytes = sb.semicrf_workspace_bytes(B, T, K, C, args.ckpt_interval, True)
+    ws = sb.alloc_workspace(B, T, K, C, args.ckpt_interval, True, dev)
+    out = (torch.empty(B, dtype=torch.float32, device=dev),
+           torch.empty((B, T, C), dtype=torch.float32, device=dev),
+           torch.empty((C, C), dtype=torch.float32, device=dev),
+           torch.empty((K, C), dtype=torch.float32, device=dev),
+           torch.empty((B, T, C), dtype=torch.float32, device=dev))
+    events = [sb.StageEvents() for _ in range(args.steps)]
+
+    for _ in range(args.warmup):
+        sb.semicrf_fwd_bwd(emis, lengths, trans, dur, None, args.ckpt_interval, workspace=ws, out=out)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        sb.semicrf_fwd_bwd_profiled(emis, lengths, trans, dur, events[i], None, args.ckpt_interval,
+                                    workspace=ws, out=out)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_step = 1e3 * dt / args.steps
+
+    stage = [0.0, 0.0, 0.0, 0.0]
+    for ev in events:
+        for j, ms in enumerate(ev.stage_ms()):
+            stage[j] += ms / args.steps
+        ev.destroy()
+
+    positions = w.positions
+    edges = w.nominal_edges
+    # dominant kernel: the two sequential scans (one launch).  Algorithmic work per
+    # position and scan: K*C multiply-adds for the duration sum + C*C for the transition
+    # product, 2 flop each, in fp64.
+    scan_flop = 2.0 * 2.0 * (K * C + C * C) * positions
+    scan_s = stage[1] * 1e-3
+    achieved = scan_flop / scan_s / 1e12
+    logz = out[0].double().cpu().numpy()
+
+    rec = {
+        "metric": "semi-CRF fwd+bwd edge evals/sec (B*T*K*C^2/s) + positions/sec at T=100k",
+        "value": edges / (ms_step * 1e-3),
+        "unit": "edge evals/s",
+        "positions_per_s": positions / (ms_step * 1e-3),
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f64",
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: B={B} T={T} K={K} C={C}, fp32 emissions, "
+                               f"sum of lengths {positions}",
+                   "ckpt_interval": args.ckpt_interval, "workspace_bytes": ws_bytes,
+                   "nominal_edges_per_step": edges},
+        "stage_ms": {"prefix": stage[0], "scans": stage[1], "intervals": stage[2], "finalise": stage[3]},
+        "roofline": {
+            "bound": "alu",
+            "kernel": "k_scan (forward + backward sequential scans, one launch)",
+            "achieved": achieved,
+            "peak": FP64_VECTOR_PEAK_TFLOPS,
+            "unit": "TFLOP/s",
+            "frac": achieved / FP64_VECTOR_PEAK_TFLOPS,
+            "traffic": None,
+            "occupied_cus": min(2 * B, 256),
+            "frac_of_occupied_cus": achieved / (FP64_VECTOR_PEAK_TFLOPS * min(2 * B, 256) / 256.0),
+        },
+        "logz_mean": float(logz.mean()),
+    }
+    if not args.no_cpu_baseline:
+        sample_T = args.cpu_sample_T or {"tiny": 512, "nlp": 256, "speech": 500,
+                                         "genomic": 16000, "longgen": 8000}[args.workload]
+        rec["cpu_baseline"] = cpu_baseline(args.workload, sample_T)
+    print(json.dumps(rec))
+
+
+if __name__ == "__main__":
+    main()

@@ -115,21 +115,24 @@ int semicrf_fwd_bwd(const float *emis, const int32_t *lengths, const float *tran
                     float *pos_marg, void *stream);
 
 /*
- * Measurement aid: semicrf_fwd_bwd with HIP events recorded on `stream` around
- * its four stages.  Unlike every other entry point this one creates events,
- * waits for the stream to finish and then fills the HOST array
- *   stage_ms[4] = { prefix sums (Eq. 1-2 kernels), the two sequential scans
- *                   (Algorithm 1 and the beta recurrence of Algorithm 3),
- *                   per-interval recompute + marginals (Algorithm 3 body),
- *                   fixed-order reductions of the gradient formulas }
- * in milliseconds.  Results are identical to semicrf_fwd_bwd.
+ * Measurement aid: semicrf_fwd_bwd with five caller-owned HIP events recorded on
+ * `stream`: stage_events[0] before the first kernel and stage_events[1..4] after
+ * each of the four stages
+ *   1 prefix sums (Eq. 1-2 kernels),
+ *   2 the two sequential scans (Algorithm 1 and the beta recurrence of Algorithm 3),
+ *   3 per-interval recompute + marginals (Algorithm 3 body),
+ *   4 fixed-order reductions of the gradient formulas.
+ * stage_events is a HOST array of 5 hipEvent_t handles created by the caller
+ * with timing enabled; the library neither creates, waits on nor destroys them
+ * (the caller synchronises and calls hipEventElapsedTime).  Results are
+ * identical to semicrf_fwd_bwd.
  */
 int semicrf_fwd_bwd_profiled(const float *emis, const int32_t *lengths, const float *trans,
                              const float *dur, const float *grad_logz, int B, int T, int K, int C,
                              int ckpt_interval, unsigned flags, void *workspace,
                              size_t workspace_bytes, float *logz, float *grad_emis,
                              float *grad_trans, float *grad_dur, float *pos_marg, void *stream,
-                             float *stage_ms);
+                             void *const *stage_events);
 
 #ifdef __cplusplus
 }

@@ -52,7 +52,7 @@ def load():
     lib.semicrf_fwd_bwd.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, cu, vp, sz,
                                     vp, vp, vp, vp, vp, vp]
     lib.semicrf_fwd_bwd_profiled.restype = ci
-    lib.semicrf_fwd_bwd_profiled.argtypes = lib.semicrf_fwd_bwd.argtypes + [ctypes.POINTER(ctypes.c_float)]
+    lib.semicrf_fwd_bwd_profiled.argtypes = lib.semicrf_fwd_bwd.argtypes + [ctypes.POINTER(vp)]
     _lib = lib
     return lib
 
@@ -149,9 +149,53 @@ def semicrf_fwd_bwd(emis, lengths, trans, dur, grad_logz=None, ckpt_interval=0,
     return logz, g_e, g_t, g_d, pm
 
 
-def semicrf_fwd_bwd_profiled(emis, lengths, trans, dur, grad_logz=None, ckpt_interval=0,
+_hip = None
+
+
+def _hiprt():
+    """The HIP runtime, for the event handles the profiled entry point records."""
+    global _hip
+    if _hip is None:
+        hip = ctypes.CDLL("libamdhip64.so")
+        hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        _hip = hip
+    return _hip
+
+
+class StageEvents:
+    """Five HIP events for one call of semicrf_fwd_bwd_profiled."""
+
+    def __init__(self):
+        hip = _hiprt()
+        self.arr = (ctypes.c_void_p * 5)()
+        for i in range(5):
+            ev = ctypes.c_void_p()
+            if hip.hipEventCreate(ctypes.byref(ev)) != 0:
+                raise RuntimeError("hipEventCreate failed")
+            self.arr[i] = ev
+
+    def stage_ms(self):
+        """Elapsed ms of the four stages; the stream must have been synchronised."""
+        hip = _hiprt()
+        out = []
+        for i in range(4):
+            ms = ctypes.c_float(0)
+            if hip.hipEventElapsedTime(ctypes.byref(ms), self.arr[i], self.arr[i + 1]) != 0:
+                raise RuntimeError("hipEventElapsedTime failed")
+            out.append(ms.value)
+        return out
+
+    def destroy(self):
+        hip = _hiprt()
+        for i in range(5):
+            hip.hipEventDestroy(self.arr[i])
+
+
+def semicrf_fwd_bwd_profiled(emis, lengths, trans, dur, events, grad_logz=None, ckpt_interval=0,
                              flags=SEMICRF_CENTER, workspace=None, out=None):
-    """semicrf_fwd_bwd plus per-stage HIP-event times; returns (outputs, [ms x 4])."""
+    """semicrf_fwd_bwd that also records `events` (a StageEvents) on the stream."""
     B, T, C = emis.shape
     K = dur.shape[0]
     dev = emis.device
@@ -164,11 +208,10 @@ def semicrf_fwd_bwd_profiled(emis, lengths, trans, dur, grad_logz=None, ckpt_int
                torch.empty((K, C), dtype=torch.float32, device=dev),
                torch.empty((B, T, C), dtype=torch.float32, device=dev))
     logz, g_e, g_t, g_d, pm = out
-    ms = (ctypes.c_float * 4)()
     _check(load().semicrf_fwd_bwd_profiled(
         _ptr(emis, torch.float32), _ptr(lengths, torch.int32), _ptr(trans, torch.float32),
         _ptr(dur, torch.float32), _ptr(grad_logz, torch.float32), B, T, K, C, ckpt_interval, flags,
         workspace.data_ptr(), workspace.numel(), _ptr(logz, torch.float32),
         _ptr(g_e, torch.float32), _ptr(g_t, torch.float32), _ptr(g_d, torch.float32),
-        _ptr(pm, torch.float32), _stream(), ms))
-    return out, [float(x) for x in ms]
+        _ptr(pm, torch.float32), _stream(), events.arr))
+    return out

@@ -316,11 +316,12 @@ __device__ __forceinline__ void load_tables(const Params &p, const Lds &l, int t
     for (int i = tid; i < C * C; i += NT) l.El[(i / C) * CP1 + (i % C)] = p.Etr[i];
 }
 
-// max of a C-vector in LDS, computed redundantly by every thread (uniform result)
-__device__ __forceinline__ double vec_max(const double *v, int C)
+// sum of a C-vector in LDS, computed redundantly by every thread in index order
+// (uniform result).  Its exponent is the power-of-two scale reference of the scans.
+__device__ __forceinline__ double vec_sum(const double *v, int C)
 {
     double m = 0.0;
-    for (int i = 0; i < C; ++i) m = fmax(m, v[i]);
+    for (int i = 0; i < C; ++i) m += v[i];
     return m;
 }
 
@@ -334,12 +335,13 @@ __device__ __forceinline__ int safe_exponent(double m)
 
 // Rescale the ring when the scan enters scaling block jnew from block jold:
 // every entry of label c is multiplied by 2^(sgn*(n_new-n_old) - e), e being the
-// exponent of the largest entry of the previous message vector.  Returns e.
+// exponent of the sum of the previous step's message vector (a_t going forward,
+// p_t going backward).  Returns e.
 __device__ __forceinline__ int rebase_ring(const Params &p, const Lds &l, const int *nb,
-                                           int jnew, int jold, int sgn, double prevmax, int tid)
+                                           int jnew, int jold, int sgn, double prevsum, int tid)
 {
     const int C = p.C, KC = p.K * p.C;
-    const int e = safe_exponent(prevmax);
+    const int e = safe_exponent(prevsum);
     if (tid < C) l.sc[tid] = sgn * (nb[(size_t)jnew * C + tid] - nb[(size_t)jold * C + tid]) - e;
     __syncthreads();
     for (int i = tid; i < KC; i += NT) {
@@ -429,7 +431,7 @@ __global__ __launch_bounds__(NT) void k_scan(Params p, int both)
         }
         for (int t = 1; t <= L; ++t) {
             if ((t % J) == 0) {
-                double pm = vec_max(l.yv, C);
+                double pm = vec_sum(l.yv, C);
                 Y += (double)rebase_ring(p, l, nb, t / J, t / J - 1, +1, pm, tid);
             }
             fwd_step(p, l, G, tid, t, ES + (size_t)t * C, IES + (size_t)t * C);
@@ -449,15 +451,16 @@ __global__ __launch_bounds__(NT) void k_scan(Params p, int both)
             p.logz[b] = (float)lz;
         }
     } else {
-        // ---- t = L: b_L = 1, v_L = E_L
+        // ---- t = L: b_L = 1, v_L = E_L; the scale reference starts at sum = 1
         if (tid < C) {
             l.zv[tid] = 1.0;
-            if (L > 0) l.ring[(L % K) * C + tid] = ES[(size_t)L * C + tid];
+            l.yv[tid] = tid == 0 ? 1.0 : 0.0;
+            l.ring[(L % K) * C + tid] = ES[(size_t)L * C + tid];
         }
         __syncthreads();
         for (int t = L - 1; t >= 0; --t) {
             if (((t + 1) % J) == 0) {
-                double pm = vec_max(l.zv, C);
+                double pm = vec_sum(l.yv, C);
                 Y += (double)rebase_ring(p, l, nb, t / J, t / J + 1, -1, pm, tid);
             }
             const int g = tid / C, c = tid % C;
@@ -481,7 +484,7 @@ __global__ __launch_bounds__(NT) void k_scan(Params p, int both)
                 const int i = t / Delta;
                 double *ck = p.ckB + ((size_t)b * (p.N + 1) + i) * ckstride;
                 for (int j = tid; j < KC; j += NT) ck[j] = l.ring[j];
-                if (tid < C) ck[KC + tid] = l.zv[tid];
+                if (tid < C) ck[KC + tid] = l.yv[tid];
                 if (tid == 0) p.ckYB[(size_t)b * (p.N + 1) + i] = Y;
             }
         }
@@ -491,6 +494,289 @@ __global__ __launch_bounds__(NT) void k_scan(Params p, int both)
             p.hdr[b].logZb = Y * LN2 + log(s);
         }
     }
+}
+
+// ---------------------------------------------------------------------------
+// Latency-oriented scan (C <= 64).  One workgroup per (sequence, direction):
+//   wave 0 ("tip") owns the dependent chain of a step: the k = 1 and k = 2 terms
+//     (its last two ring entries stay in registers), the emission factor, the
+//     transition product (its Etr row/column lives in registers, the message
+//     vector is broadcast through LDS inside the wave) and the ring write;
+//   waves 1.. ("helpers") pre-reduce, two steps ahead, the k >= 3 terms of a
+//     later position from the LDS ring (their W strip lives in registers) and
+//     leave one partial per wave and label; the tip adds them in wave order one
+//     step before it needs them, so the partials are off the dependent chain.
+// One LDS-only barrier per step (outstanding global prefetches are not drained);
+// the tip prefetches ES/IES rows PF steps ahead into registers.
+// ---------------------------------------------------------------------------
+constexpr int PF = 8;        // prefetch distance of the emission factors, in steps
+constexpr int NH_MAX = 7;    // most helper waves
+
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// orders LDS accesses of one wave (LDS executes a wave's instructions in order)
+__device__ __forceinline__ void lds_wave_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+}
+
+__host__ __device__ inline size_t fast_lds_doubles(int K, int C, int CT)
+{
+    return (size_t)K * C + 2 * (size_t)NH_MAX * CT + 2 * (size_t)CT;
+}
+
+template <int CT, int NKL, bool BWD>
+__device__ __forceinline__ void scan_fast_body(const Params &p, double *lds, const int b)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nthreads = blockDim.x;
+    const int NH = (nthreads >> 6) - 1;
+    constexpr int GW = 64 / CT;
+    const int K = p.K, C = p.C, KC = K * C;
+    double *ring = lds;                           // [K*C]
+    double *part = ring + KC;                     // [2][NH_MAX][CT], rows >= NH stay zero
+    double *yv = part + 2 * (size_t)NH_MAX * CT;  // [CT]
+    int *sc = (int *)(yv + CT);                   // [CT]
+    const SeqHdr h = p.hdr[b];
+    const int L = h.L, J = h.J, Delta = p.Delta;
+    const size_t row0 = (size_t)b * (p.T + 1);
+    const double *ES = p.ES + row0 * C;
+    const double *IES = p.IES + row0 * C;
+    const int *nb = p.nbase + row0 * C;
+    const size_t ckstride = (size_t)KC + C;
+    double *ckbase = (BWD ? p.ckB : p.ckA) + ((size_t)b * (p.N + 1)) * ckstride;
+    double *ckY = (BWD ? p.ckYB : p.ckYA) + (size_t)b * (p.N + 1);
+    const bool tip = wave == 0;
+    const int c = tip ? lane : (lane % CT);
+    const bool cval = c < C;
+    const int cc = cval ? c : 0;  // in-bounds label index for address arithmetic
+
+    // ---- one register array, two meanings: the tip's Etr row/column, a helper's W strip
+    constexpr int NREG = CT > NKL ? CT : NKL;
+    double treg[NREG];
+    double *const Ereg = treg;
+    double *const wreg = treg;
+    double W1 = 0.0, W2 = 0.0;
+    const int g = lane / CT;
+    const int NG = NH * GW;
+    const int kfirst = 3 + (wave - 1) * GW + g;  // this helper lane's first duration
+#pragma unroll
+    for (int i = 0; i < NREG; ++i) treg[i] = 0.0;
+    if (tip) {
+        if (cval) {
+#pragma unroll
+            for (int i = 0; i < CT; ++i)
+                if (i < C) Ereg[i] = BWD ? p.Etr[(size_t)c * C + i] : p.Etr[(size_t)i * C + c];
+            W1 = p.W[c];
+            if (K >= 2) W2 = p.W[(size_t)C + c];
+        }
+    } else if (cval) {
+#pragma unroll
+        for (int j = 0; j < NKL; ++j) {
+            const int k = kfirst + j * NG;
+            if (k <= K) wreg[j] = p.W[(size_t)(k - 1) * C + c];
+        }
+    }
+    for (int i = tid; i < KC; i += nthreads) ring[i] = 0.0;
+    for (int i = tid; i < 2 * NH_MAX * CT; i += nthreads) part[i] = 0.0;
+    if (tid < CT) yv[tid] = 0.0;
+    lds_barrier();
+
+    // ---- first position (t = 0 forward, t = L backward)
+    double q1 = 0.0, q2 = 0.0, Y = 0.0, prevsum = 1.0;
+    int slot = BWD ? L % K : 0;  // ring slot of the position just processed
+    int nb_cur = 0, nb_nxt = 0;  // scaling exponents of the current / next block (tip lanes)
+    if (tip && cval) {
+        if (!BWD) {
+            yv[c] = 1.0;
+            double z = 0.0;
+#pragma unroll
+            for (int i = 0; i < CT; ++i) z += Ereg[i];
+            q1 = z * IES[c];
+        } else {
+            yv[c] = c == 0 ? 1.0 : 0.0;
+            q1 = ES[(size_t)L * C + c];
+        }
+        ring[slot * C + c] = q1;
+        const int j0 = BWD ? L / J : 0;
+        const int j1 = BWD ? max(j0 - 1, 0) : min(j0 + 1, L / J);
+        nb_cur = nb[(size_t)j0 * C + c];
+        nb_nxt = nb[(size_t)j1 * C + c];
+    }
+    if (!BWD) prevsum = (double)C;
+    lds_barrier();
+    if (!BWD && p.want_grad) {
+        for (int i = tid; i < KC; i += nthreads) ckbase[i] = ring[i];
+        if (tid < C) ckbase[KC + tid] = yv[tid];
+        if (tid == 0) ckY[0] = 0.0;
+    }
+
+    auto step_slot = [&](int sl, int by) {  // slot of the position `by` steps further along the scan
+        int r = BWD ? sl - by : sl + by;
+        while (r < 0) r += K;
+        while (r >= K) r -= K;
+        return r;
+    };
+    // helper: partial of sum_{k>=3} W[k,c] ring[pos -/+ k] for the position whose slot is ps.
+    // Every load is unconditional (invalid terms carry weight 0 and a clamped duration).
+    auto helper_partial = [&](int ps, int buf) {
+        double v[NKL];
+#pragma unroll
+        for (int j = 0; j < NKL; ++j) {
+            int k = kfirst + j * NG;
+            k = k > K ? K : k;
+            int sl = BWD ? ps + k : ps - k;
+            if (BWD) sl = sl >= K ? sl - K : sl;
+            else sl = sl < 0 ? sl + K : sl;
+            v[j] = ring[sl * C + cc];
+        }
+        double a0 = 0.0, a1 = 0.0;
+#pragma unroll
+        for (int j = 0; j < NKL; j += 2) {
+            a0 = fma(wreg[j], v[j], a0);
+            a1 = fma(wreg[j + 1], v[j + 1], a1);
+        }
+        double acc = a0 + a1;
+#pragma unroll
+        for (int off = CT; off < 64; off <<= 1) acc += __shfl_xor(acc, off);
+        if (lane < CT) part[((size_t)buf * NH_MAX + (wave - 1)) * CT + lane] = cval ? acc : 0.0;
+    };
+    auto read_partials = [&](int buf) {
+        double v[NH_MAX];
+#pragma unroll
+        for (int w = 0; w < NH_MAX; ++w) v[w] = part[((size_t)buf * NH_MAX + w) * CT + cc];
+        double s = 0.0;
+#pragma unroll
+        for (int w = 0; w < NH_MAX; ++w) s += v[w];
+        return s;
+    };
+
+    // ---- emission-factor prefetch queue (tip lanes)
+    double qa[PF], qb[PF];
+#pragma unroll
+    for (int j = 0; j < PF; ++j) {
+        qa[j] = 0.0;
+        qb[j] = 0.0;
+        if (tip && cval) {
+            int n = 1 + j;
+            if (n > L) n = L;
+            const int t = BWD ? L - n : n;
+            qa[j] = ES[(size_t)t * C + c];
+            qb[j] = IES[(size_t)t * C + c];
+        }
+    }
+
+    // Nothing lies k >= 3 behind steps 1 and 2, so their partials are the zeros
+    // already in `part`.  psum is the partial of the step about to run.
+    double psum = 0.0;
+    for (int nbase = 1; nbase <= L; nbase += PF) {
+#pragma unroll
+        for (int j = 0; j < PF; ++j) {
+            const int n = nbase + j;
+            if (n <= L) {  // uniform
+                const int t = BWD ? L - n : n;
+                const double es = qa[j], ies = qb[j];
+                if (tip && cval) {
+                    int n2 = n + PF;
+                    if (n2 > L) n2 = L;
+                    const int t2 = BWD ? L - n2 : n2;
+                    qa[j] = ES[(size_t)t2 * C + c];
+                    qb[j] = IES[(size_t)t2 * C + c];
+                }
+                const bool boundary = BWD ? ((t + 1) % J) == 0 : (t % J) == 0;
+                int scl = 0;
+                if (boundary) {  // uniform: rescale ring, tip registers and the pending partials
+                    if (tip) {
+                        const int e = safe_exponent(prevsum);
+                        Y += (double)e;
+                        if (cval) {
+                            const int sft = (BWD ? -(nb_nxt - nb_cur) : (nb_nxt - nb_cur)) - e;
+                            sc[c] = sft;
+                            scl = sft;
+                            q1 = fmin(ldexp(q1, sft), DBL_MAX);
+                            q2 = fmin(ldexp(q2, sft), DBL_MAX);
+                            psum = fmin(ldexp(psum, sft), DBL_MAX);
+                            nb_cur = nb_nxt;
+                            const int jn = t / J;
+                            const int j2 = BWD ? max(jn - 1, 0) : min(jn + 1, L / J);
+                            nb_nxt = nb[(size_t)j2 * C + c];
+                        }
+                    }
+                    lds_barrier();
+                    for (int i = tid; i < KC; i += nthreads)
+                        ring[i] = fmin(ldexp(ring[i], sc[i % C]), DBL_MAX);
+                    lds_barrier();
+                }
+                slot = step_slot(slot, 1);
+                if (tip) {
+                    // partial of the NEXT step (finished by the helpers one barrier ago)
+                    double pnext = read_partials((n + 1) & 1);
+                    if (scl != 0) pnext = fmin(ldexp(pnext, scl), DBL_MAX);
+                    const double x = fma(W1, q1, fma(W2, q2, psum));
+                    const double y = x * (BWD ? ies : es);
+                    if (cval) yv[c] = y;
+                    lds_wave_fence();
+                    double z0 = 0.0, z1 = 0.0, ysum = 0.0;
+                    const bool want_sum = BWD ? (t % J) == 0 : ((t + 1) % J) == 0;
+#pragma unroll
+                    for (int i = 0; i < CT; i += 2) {
+                        const double v0 = yv[i], v1 = yv[i + 1];
+                        z0 = fma(v0, Ereg[i], z0);
+                        z1 = fma(v1, Ereg[i + 1], z1);
+                        if (want_sum) ysum += v0 + v1;
+                    }
+                    if (want_sum) prevsum = ysum;
+                    const double z = z0 + z1;
+                    q2 = q1;
+                    q1 = z * (BWD ? es : ies);
+                    if (cval) ring[slot * C + c] = q1;
+                    psum = pnext;
+                    if (BWD && n == L) {  // beta_0: diagnostic partition function
+                        lds_wave_fence();
+                        if (cval) yv[c] = z;
+                    }
+                } else if (n + 2 <= L) {
+                    helper_partial(step_slot(slot, 2), n & 1);
+                }
+                lds_barrier();
+                if (p.want_grad && (t % Delta) == 0 && t > 0) {  // uniform
+                    const int i = t / Delta;
+                    double *ck = ckbase + (size_t)i * ckstride;
+                    for (int q = tid; q < KC; q += nthreads) ck[q] = ring[q];
+                    if (tid < C) ck[KC + tid] = yv[tid];
+                    if (tid == 0) ckY[i] = Y;
+                    lds_barrier();
+                }
+            }
+        }
+    }
+    if (tid == 0) {
+        double s = 0.0;
+        for (int i = 0; i < C; ++i) s += (BWD && L == 0) ? 1.0 : yv[i];
+        const double lz = Y * LN2 + log(s);
+        if (BWD) {
+            p.hdr[b].logZb = lz;
+        } else {
+            p.hdr[b].logZ = lz;
+            p.logz[b] = (float)lz;
+        }
+    }
+}
+
+template <int CT, int NKL>
+__global__ __launch_bounds__(CT == 64 ? 256 : 512) void k_scan_fast(Params p, int both)
+{
+    extern __shared__ double lds_raw[];
+    const int b = both ? (int)(blockIdx.x >> 1) : (int)blockIdx.x;
+    const int dir = both ? (int)(blockIdx.x & 1) : 0;
+    if (dir == 0) scan_fast_body<CT, NKL, false>(p, lds_raw, b);
+    else scan_fast_body<CT, NKL, true>(p, lds_raw, b);
 }
 
 // ---------------------------------------------------------------------------
@@ -549,7 +835,7 @@ __global__ __launch_bounds__(NT) void k_interval(Params p)
         if (tid == 0) alocY[0] = Y;
         for (int t = t0 + 1; t < t1; ++t) {
             if ((t % J) == 0) {
-                double pm = vec_max(l.yv, C);
+                double pm = vec_sum(l.yv, C);
                 Y += (double)rebase_ring(p, l, nb, t / J, t / J - 1, +1, pm, tid);
             }
             fwd_step(p, l, G, tid, t, ES + (size_t)t * C, IES + (size_t)t * C);
@@ -568,7 +854,7 @@ __global__ __launch_bounds__(NT) void k_interval(Params p)
             for (int i = tid; i < KC; i += NT) l.ring[i] = 0.0;
             __syncthreads();
             if (tid < C) {
-                l.zv[tid] = 1.0;
+                l.yv[tid] = tid == 0 ? 1.0 : 0.0;
                 l.ring[(L % K) * C + tid] = ES[(size_t)L * C + tid];
             }
             Yb = 0.0;
@@ -576,7 +862,7 @@ __global__ __launch_bounds__(NT) void k_interval(Params p)
             const int ci = t1 / Delta;
             const double *ck = p.ckB + ((size_t)b * (N + 1) + ci) * ckstride;
             for (int i = tid; i < KC; i += NT) l.ring[i] = ck[i];
-            if (tid < C) l.zv[tid] = ck[KC + tid];
+            if (tid < C) l.yv[tid] = ck[KC + tid];
             Yb = p.ckYB[(size_t)b * (N + 1) + ci];
         }
         for (int i = tid; i < KC; i += NT) l.accD[i] = 0.0;
@@ -589,7 +875,7 @@ __global__ __launch_bounds__(NT) void k_interval(Params p)
 
         for (int t = t1 - 1; t >= t0; --t) {
             if (((t + 1) % J) == 0) {
-                double pm = vec_max(l.zv, C);
+                double pm = vec_sum(l.yv, C);
                 Yb += (double)rebase_ring(p, l, nb, t / J, t / J + 1, -1, pm, tid);
             }
             const double *row = aloc + (size_t)(t - t0) * 2 * C;
@@ -844,6 +1130,50 @@ int launch_prep(const Params &p, hipStream_t st)
     return check_launch();
 }
 
+// Chooses the latency-oriented scan when the helper lanes can hold the duration
+// strips in registers, else the generic one.
+template <int CT, int NKL>
+int launch_scan_fast(const Params &p, hipStream_t st, bool both, int NH)
+{
+    const size_t lds = fast_lds_doubles(p.K, p.C, CT) * sizeof(double);
+    if (hipFuncSetAttribute((const void *)k_scan_fast<CT, NKL>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+        return SEMICRF_ELAUNCH;
+    hipLaunchKernelGGL((k_scan_fast<CT, NKL>), dim3(both ? 2 * p.B : p.B), dim3(64 * (NH + 1)), lds,
+                       st, p, both ? 1 : 0);
+    return check_launch();
+}
+
+template <int CT>
+int launch_scan_ct(const Params &p, hipStream_t st, bool both)
+{
+    constexpr int GW = 64 / CT;
+    constexpr int NHcap = CT == 64 ? 3 : NH_MAX;
+    const int terms = p.K > 2 ? p.K - 2 : 0;           // durations k >= 3 go to the helpers
+    int NH = (terms + 4 * GW - 1) / (4 * GW);           // aim at <= 4 terms per helper lane
+    NH = NH < 1 ? 1 : (NH > NHcap ? NHcap : NH);
+    const int per_lane = (terms + NH * GW - 1) / (NH * GW);
+    if (per_lane > 16 || fast_lds_doubles(p.K, p.C, CT) * sizeof(double) > LDS_LIMIT) return 1;
+    if (per_lane <= 8) return launch_scan_fast<CT, 8>(p, st, both, NH);
+    return launch_scan_fast<CT, 16>(p, st, both, NH);
+}
+
+int launch_scan(const Params &p, const Plan &pl, hipStream_t st, bool both)
+{
+    const int C = p.C;
+    int rc = 1;  // 1 = fast path not applicable
+    if (C <= 8) rc = launch_scan_ct<8>(p, st, both);
+    else if (C <= 16) rc = launch_scan_ct<16>(p, st, both);
+    else if (C <= 32) rc = launch_scan_ct<32>(p, st, both);
+    else if (C <= 64) rc = launch_scan_ct<64>(p, st, both);
+    if (rc != 1) return rc;
+    if (hipFuncSetAttribute((const void *)k_scan, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)pl.lds_scan) != hipSuccess)
+        return SEMICRF_ELAUNCH;
+    hipLaunchKernelGGL(k_scan, dim3(both ? 2 * p.B : p.B), dim3(NT), pl.lds_scan, st, p, both ? 1 : 0);
+    return check_launch();
+}
+
 // Optional per-stage timing: events are recorded on the caller's stream around
 // the four stages (prefix sums, scans, intervals, finalisation).
 struct StageTimer {
@@ -877,11 +1207,8 @@ int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hi
     rc = launch_prep(p, st);
     T.mark();
     if (rc != SEMICRF_OK || mode == 0) return rc;
-    if (hipFuncSetAttribute((const void *)k_scan, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)pl.lds_scan) != hipSuccess)
-        return SEMICRF_ELAUNCH;
-    hipLaunchKernelGGL(k_scan, dim3(mode == 2 ? 2 * p.B : p.B), dim3(NT), pl.lds_scan, st, p,
-                       mode == 2 ? 1 : 0);
+    rc = launch_scan(p, pl, st, mode == 2);
+    if (rc != SEMICRF_OK) return rc;
     T.mark();
     rc = check_launch();
     if (rc != SEMICRF_OK || mode == 1) return rc;
@@ -983,9 +1310,9 @@ int semicrf_fwd_bwd_profiled(const float *emis, const int32_t *lengths, const fl
                              int ckpt_interval, unsigned flags, void *workspace,
                              size_t workspace_bytes, float *logz, float *grad_emis,
                              float *grad_trans, float *grad_dur, float *pos_marg, void *stream,
-                             float *stage_ms)
+                             void *const *stage_events)
 {
-    if (!emis || !trans || !dur || !logz || !grad_emis || !grad_trans || !grad_dur || !stage_ms)
+    if (!emis || !trans || !dur || !logz || !grad_emis || !grad_trans || !grad_dur || !stage_events)
         return SEMICRF_EINVAL;
     Params p = {};
     p.emis = emis; p.lengths = lengths; p.trans = trans; p.dur = dur; p.grad_logz = grad_logz;
@@ -996,17 +1323,11 @@ int semicrf_fwd_bwd_profiled(const float *emis, const int32_t *lengths, const fl
     StageTimer tm;
     tm.on = true;
     tm.st = (hipStream_t)stream;
-    for (int i = 0; i < 5; ++i)
-        if (hipEventCreate(&tm.ev[i]) != hipSuccess) return SEMICRF_ELAUNCH;
-    int rc = run(p, ckpt_interval, workspace, workspace_bytes, tm.st, 2, &tm);
-    if (rc == SEMICRF_OK && tm.n == 5) {
-        if (hipEventSynchronize(tm.ev[4]) != hipSuccess) rc = SEMICRF_ELAUNCH;
-        for (int i = 0; i < 4 && rc == SEMICRF_OK; ++i)
-            if (hipEventElapsedTime(&stage_ms[i], tm.ev[i], tm.ev[i + 1]) != hipSuccess)
-                rc = SEMICRF_ELAUNCH;
+    for (int i = 0; i < 5; ++i) {
+        if (!stage_events[i]) return SEMICRF_EINVAL;
+        tm.ev[i] = (hipEvent_t)stage_events[i];
     }
-    for (int i = 0; i < 5; ++i) hipEventDestroy(tm.ev[i]);
-    return rc;
+    return run(p, ckpt_interval, workspace, workspace_bytes, tm.st, 2, &tm);
 }
 
 }  // extern "C"
