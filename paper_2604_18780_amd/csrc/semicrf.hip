@@ -80,8 +80,7 @@ struct Params {
     double *tabmax;     // [2]: max dur, max trans
     double *W;          // [K][C]
     double *Etr;        // [C][C]
-    double *ES;         // [B][T+1][C]
-    double *IES;        // [B][T+1][C]
+    double2 *EI;        // [B][T+1][C]  .x = ES = exp(S - n ln2), .y = 1/ES
     int *nbase;         // [B][T+1][C] (row j = scaling block j)
     double *ckA;        // [B][N+1][K*C + C]
     double *ckB;        // [B][N+1][K*C + C]
@@ -236,7 +235,7 @@ __global__ __launch_bounds__(NT) void k_prep_seq(Params p)
 
 // ---------------------------------------------------------------------------
 // Eq. 2: centred prefix sums S[t,c] (fp64, sequential inside a chunk), the
-// per-block exponents n_j(c) and ES = exp(S - n ln2), IES = 1/ES.  grid (NCH,B),
+// per-block exponents n_j(c) and the pair (ES, 1/ES), ES = exp(S - n ln2).  grid (NCH,B),
 // one thread per label.
 // ---------------------------------------------------------------------------
 __global__ void k_prefix(Params p)
@@ -261,8 +260,7 @@ __global__ void k_prefix(Params p)
                     base = n * LN2;
                 }
                 double x = S - base;
-                p.ES[(row0 + t) * C + c] = exp(x);
-                p.IES[(row0 + t) * C + c] = exp(-x);
+                p.EI[(row0 + t) * C + c] = make_double2(exp(x), exp(-x));
                 if (p.cum) p.cum[(row0 + t) * C + c] = S;
                 if (t < L) S += (double)f[(size_t)t * C] - nu;
             } else if (p.cum) {
@@ -368,7 +366,7 @@ __device__ __forceinline__ double strip_sum(const Lds &l, int K, int C, int G, i
 // One forward step at position t (Algorithm 1 body in the linear domain).
 // On exit yv = a_t (scaled), ring[t mod K] = q_t.  Two barriers inside, one at exit.
 __device__ __forceinline__ void fwd_step(const Params &p, const Lds &l, int G, int tid, int t,
-                                         const double *ESrow, const double *IESrow)
+                                         const double2 *EIrow)
 {
     const int K = p.K, C = p.C, CP1 = C | 1;
     const int g = tid / C, c = tid % C;
@@ -378,13 +376,13 @@ __device__ __forceinline__ void fwd_step(const Params &p, const Lds &l, int G, i
     if (tid < C) {
         double x = 0.0;
         for (int i = 0; i < G; ++i) x += l.red[i * C + tid];
-        l.yv[tid] = x * ESrow[tid];
+        l.yv[tid] = x * EIrow[tid].x;
     }
     __syncthreads();
     if (tid < C) {
         double z = 0.0;
         for (int cp = 0; cp < C; ++cp) z = fma(l.yv[cp], l.El[cp * CP1 + tid], z);
-        l.ring[s0 * C + tid] = z * IESrow[tid];
+        l.ring[s0 * C + tid] = z * EIrow[tid].y;
     }
     __syncthreads();
 }
@@ -404,8 +402,7 @@ __global__ __launch_bounds__(NT) void k_scan(Params p, int both)
     const SeqHdr h = p.hdr[b];
     const int L = h.L, J = h.J, Delta = p.Delta;
     const size_t row0 = (size_t)b * (p.T + 1);
-    const double *ES = p.ES + row0 * C;
-    const double *IES = p.IES + row0 * C;
+    const double2 *EI = p.EI + row0 * C;
     const int *nb = p.nbase + row0 * C;
     const size_t ckstride = (size_t)KC + C;
 
@@ -420,7 +417,7 @@ __global__ __launch_bounds__(NT) void k_scan(Params p, int both)
             l.yv[tid] = 1.0;
             double z = 0.0;
             for (int cp = 0; cp < C; ++cp) z += l.El[cp * CP1 + tid];
-            l.ring[tid] = z * IES[tid];
+            l.ring[tid] = z * EI[tid].y;
         }
         __syncthreads();
         if (p.want_grad) {
@@ -434,7 +431,7 @@ __global__ __launch_bounds__(NT) void k_scan(Params p, int both)
                 double pm = vec_sum(l.yv, C);
                 Y += (double)rebase_ring(p, l, nb, t / J, t / J - 1, +1, pm, tid);
             }
-            fwd_step(p, l, G, tid, t, ES + (size_t)t * C, IES + (size_t)t * C);
+            fwd_step(p, l, G, tid, t, EI + (size_t)t * C);
             if (p.want_grad && (t % Delta) == 0) {
                 const int i = t / Delta;
                 double *ck = p.ckA + ((size_t)b * (p.N + 1) + i) * ckstride;
@@ -455,7 +452,7 @@ __global__ __launch_bounds__(NT) void k_scan(Params p, int both)
         if (tid < C) {
             l.zv[tid] = 1.0;
             l.yv[tid] = tid == 0 ? 1.0 : 0.0;
-            l.ring[(L % K) * C + tid] = ES[(size_t)L * C + tid];
+            l.ring[(L % K) * C + tid] = EI[(size_t)L * C + tid].x;
         }
         __syncthreads();
         for (int t = L - 1; t >= 0; --t) {
@@ -470,14 +467,14 @@ __global__ __launch_bounds__(NT) void k_scan(Params p, int both)
             if (tid < C) {
                 double x = 0.0;
                 for (int i = 0; i < G; ++i) x += l.red[i * C + tid];
-                l.yv[tid] = x * IES[(size_t)t * C + tid];
+                l.yv[tid] = x * EI[(size_t)t * C + tid].y;
             }
             __syncthreads();
             if (tid < C) {
                 double z = 0.0;
                 for (int cc = 0; cc < C; ++cc) z = fma(l.El[tid * CP1 + cc], l.yv[cc], z);
                 l.zv[tid] = z;
-                l.ring[s0 * C + tid] = z * ES[(size_t)t * C + tid];
+                l.ring[s0 * C + tid] = z * EI[(size_t)t * C + tid].x;
             }
             __syncthreads();
             if (t > 0 && (t % Delta) == 0) {
@@ -497,20 +494,34 @@ __global__ __launch_bounds__(NT) void k_scan(Params p, int both)
 }
 
 // ---------------------------------------------------------------------------
-// Latency-oriented scan (C <= 64).  One workgroup per (sequence, direction):
+// Latency-oriented scan (C <= 64).  A lone wave issues about one VALU/LDS
+// instruction per 8 clocks on this hardware, so the time of a step is the number
+// of instructions on the dependent chain; the kernel is organised to keep that
+// number small.  One workgroup per (sequence, direction):
 //   wave 0 ("tip") owns the dependent chain of a step: the k = 1 and k = 2 terms
 //     (its last two ring entries stay in registers), the emission factor, the
-//     transition product (its Etr row/column lives in registers, the message
-//     vector is broadcast through LDS inside the wave) and the ring write;
+//     transition product (its part of the Etr row/column lives in registers; for
+//     C <= 32 the two 32-lane halves of the wave each take half of the source
+//     labels and are combined with one lane-swap) and the ring write;
 //   waves 1.. ("helpers") pre-reduce, two steps ahead, the k >= 3 terms of a
-//     later position from the LDS ring (their W strip lives in registers) and
-//     leave one partial per wave and label; the tip adds them in wave order one
-//     step before it needs them, so the partials are off the dependent chain.
+//     later position from the LDS ring and leave one partial per wave and label;
+//     the tip adds them in wave order one step before it needs them.
+// The LDS ring is stored twice (slots s and s+K) with a compile-time row stride,
+// so a helper lane reads its NKL consecutive durations at immediate offsets from
+// one base address, without wrap-around arithmetic.
 // One LDS-only barrier per step (outstanding global prefetches are not drained);
-// the tip prefetches ES/IES rows PF steps ahead into registers.
+// the tip prefetches the (ES, 1/ES) rows PF steps ahead into registers.
 // ---------------------------------------------------------------------------
 constexpr int PF = 8;        // prefetch distance of the emission factors, in steps
-constexpr int NH_MAX = 7;    // most helper waves
+constexpr int NH_MAX = 4;    // most helper waves
+constexpr int NKL = 16;      // consecutive durations per helper lane
+
+__host__ __device__ constexpr int pow2_ge8(int x)
+{
+    int r = 8;
+    while (r < x) r <<= 1;
+    return r;
+}
 
 __device__ __forceinline__ void lds_barrier()
 {
@@ -526,257 +537,332 @@ __device__ __forceinline__ void lds_wave_fence()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
 }
 
-__host__ __device__ inline size_t fast_lds_doubles(int K, int C, int CT)
+// v + (v of the lane 32 away), in every lane: rows 2,3 of one copy are swapped with
+// rows 0,1 of the other (a row is 16 lanes), then the copies are added.
+__device__ __forceinline__ double add_across_32(double v)
 {
-    return (size_t)K * C + 2 * (size_t)NH_MAX * CT + 2 * (size_t)CT;
+    const unsigned lo = (unsigned)__double2loint(v), hi = (unsigned)__double2hiint(v);
+    const auto a = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
+    const auto b = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
+    return __hiloint2double((int)b[0], (int)a[0]) + __hiloint2double((int)b[1], (int)a[1]);
 }
 
-template <int CT, int NKL, bool BWD>
+// v + (v of the lane 16 away): odd rows of one copy are swapped with even rows of the other
+__device__ __forceinline__ double add_across_16(double v)
+{
+    const unsigned lo = (unsigned)__double2loint(v), hi = (unsigned)__double2hiint(v);
+    const auto a = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
+    const auto b = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
+    return __hiloint2double((int)b[0], (int)a[0]) + __hiloint2double((int)b[1], (int)a[1]);
+}
+
+// v + (v of the lane 8 away inside a row of 16): DPP row rotate by 8
+__device__ __forceinline__ double add_across_8(double v)
+{
+    const int lo = __double2loint(v), hi = __double2hiint(v);
+    const int lo2 = __builtin_amdgcn_update_dpp(0, lo, 0x128, 0xf, 0xf, false);
+    const int hi2 = __builtin_amdgcn_update_dpp(0, hi, 0x128, 0xf, 0xf, false);
+    return v + __hiloint2double(hi2, lo2);
+}
+
+// sum over the 64/CTP lanes of a wave that share lane % CTP; every lane gets the total
+template <int CTP>
+__device__ __forceinline__ double group_sum(double v)
+{
+    if (CTP <= 8) v = add_across_8(v);
+    if (CTP <= 16) v = add_across_16(v);
+    if (CTP <= 32) v = add_across_32(v);
+    return v;
+}
+
+struct FastGeom {
+    int RSLOTS;  // ring slots: both copies plus front padding
+    int XP;      // front padding slots (forward direction only)
+};
+
+__host__ __device__ inline FastGeom fast_geom(int K, int CTP, int NH)
+{
+    const int GW = 64 / CTP;
+    const int kmaxpad = 2 + NH * GW * NKL;  // largest duration index any helper lane touches
+    FastGeom g;
+    g.XP = kmaxpad > K ? kmaxpad - K : 0;
+    g.RSLOTS = 2 * K + g.XP;
+    return g;
+}
+
+__host__ __device__ inline size_t fast_lds_doubles(int K, int CTP, int NH)
+{
+    return (size_t)fast_geom(K, CTP, NH).RSLOTS * CTP + 2 * (size_t)NH_MAX * CTP + 2 * (size_t)CTP;
+}
+
+template <int CT, int NHR, bool BWD>
 __device__ __forceinline__ void scan_fast_body(const Params &p, double *lds, const int b)
 {
+    constexpr int CTP = pow2_ge8(CT);       // lanes per label group in a helper wave, LDS row stride
+    constexpr int RS = CTP;
+    constexpr int GW = 64 / CTP;
+    constexpr int H = CT <= 32 ? 2 : 1;     // tip: lane halves sharing the transition product
+    constexpr int HC = CT / H;              // source labels per tip lane
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nthreads = blockDim.x;
     const int NH = (nthreads >> 6) - 1;
-    constexpr int GW = 64 / CT;
     const int K = p.K, C = p.C, KC = K * C;
-    double *ring = lds;                           // [K*C]
-    double *part = ring + KC;                     // [2][NH_MAX][CT], rows >= NH stay zero
-    double *yv = part + 2 * (size_t)NH_MAX * CT;  // [CT]
-    int *sc = (int *)(yv + CT);                   // [CT]
+    const FastGeom geo = fast_geom(K, CTP, NH);
+    const int XPf = BWD ? 0 : geo.XP;
+    const int RTOT = geo.RSLOTS * RS;
+    double *ring = lds;                           // [RSLOTS][RS]
+    double *part = ring + RTOT;                   // [2][NH_MAX][CTP]
+    double *yv = part + 2 * (size_t)NH_MAX * CTP; // [CTP]
+    int *sc = (int *)(yv + CTP);                  // [CTP]
     const SeqHdr h = p.hdr[b];
-    const int L = h.L, J = h.J, Delta = p.Delta;
+    const int L = h.L, J = h.J, Jm = J - 1, Delta = p.Delta;
     const size_t row0 = (size_t)b * (p.T + 1);
-    const double *ES = p.ES + row0 * C;
-    const double *IES = p.IES + row0 * C;
+    const double2 *EI = p.EI + row0 * C;
     const int *nb = p.nbase + row0 * C;
     const size_t ckstride = (size_t)KC + C;
     double *ckbase = (BWD ? p.ckB : p.ckA) + ((size_t)b * (p.N + 1)) * ckstride;
     double *ckY = (BWD ? p.ckYB : p.ckYA) + (size_t)b * (p.N + 1);
     const bool tip = wave == 0;
-    const int c = tip ? lane : (lane % CT);
+    const int hh = H == 2 ? (lane >> 5) : 0;                    // tip: which half of the source labels
+    const int c = lane % CTP;  // label of this lane (tip: both halves; helper: every lane group)
     const bool cval = c < C;
-    const int cc = cval ? c : 0;  // in-bounds label index for address arithmetic
+    const int cc = cval ? c : 0;
 
-    // ---- one register array, two meanings: the tip's Etr row/column, a helper's W strip
-    constexpr int NREG = CT > NKL ? CT : NKL;
+    // ---- one register array, two meanings: the tip's part of Etr, a helper's W strip
+    constexpr int NREG = HC > NKL ? HC : NKL;
     double treg[NREG];
     double *const Ereg = treg;
     double *const wreg = treg;
     double W1 = 0.0, W2 = 0.0;
-    const int g = lane / CT;
-    const int NG = NH * GW;
-    const int kfirst = 3 + (wave - 1) * GW + g;  // this helper lane's first duration
+    const int g = lane / CTP;
+    // helper lane (wave, g): durations k0, k0 + GW, k0 + 2 GW, ... so that the 64 lanes of a
+    // wave read 64 consecutive doubles of the ring for every term (no LDS bank conflicts)
+    const int k0 = 3 + (wave - 1) * GW * NKL + g;
 #pragma unroll
     for (int i = 0; i < NREG; ++i) treg[i] = 0.0;
     if (tip) {
         if (cval) {
 #pragma unroll
-            for (int i = 0; i < CT; ++i)
-                if (i < C) Ereg[i] = BWD ? p.Etr[(size_t)c * C + i] : p.Etr[(size_t)i * C + c];
+            for (int i = 0; i < HC; ++i) {
+                const int o = hh * HC + i;  // the other label of the transition
+                if (o < C) Ereg[i] = BWD ? p.Etr[(size_t)c * C + o] : p.Etr[(size_t)o * C + c];
+            }
             W1 = p.W[c];
             if (K >= 2) W2 = p.W[(size_t)C + c];
         }
     } else if (cval) {
 #pragma unroll
         for (int j = 0; j < NKL; ++j) {
-            const int k = kfirst + j * NG;
+            // forward lanes read their strip from the lowest address up, i.e. longest duration first
+            const int k = BWD ? k0 + j * GW : k0 + (NKL - 1 - j) * GW;
             if (k <= K) wreg[j] = p.W[(size_t)(k - 1) * C + c];
         }
     }
-    for (int i = tid; i < KC; i += nthreads) ring[i] = 0.0;
-    for (int i = tid; i < 2 * NH_MAX * CT; i += nthreads) part[i] = 0.0;
-    if (tid < CT) yv[tid] = 0.0;
+    for (int i = tid; i < RTOT; i += nthreads) ring[i] = 0.0;
+    for (int i = tid; i < 2 * NH_MAX * CTP; i += nthreads) part[i] = 0.0;
+    if (tid < CTP) {
+        yv[tid] = 0.0;
+        sc[tid] = 0;
+    }
     lds_barrier();
 
     // ---- first position (t = 0 forward, t = L backward)
-    double q1 = 0.0, q2 = 0.0, Y = 0.0, prevsum = 1.0;
-    int slot = BWD ? L % K : 0;  // ring slot of the position just processed
+    double q1 = 0.0, q2 = 0.0, Y = 0.0, prevsum = BWD ? 1.0 : (double)C;
+    int slot = BWD ? L % K : 0;  // ring slot (lower copy) of the position just processed
     int nb_cur = 0, nb_nxt = 0;  // scaling exponents of the current / next block (tip lanes)
     if (tip && cval) {
         if (!BWD) {
             yv[c] = 1.0;
             double z = 0.0;
 #pragma unroll
-            for (int i = 0; i < CT; ++i) z += Ereg[i];
-            q1 = z * IES[c];
+            for (int i = 0; i < HC; ++i) z += Ereg[i];
+            if (H == 2) z = add_across_32(z);
+            q1 = z * EI[c].y;
         } else {
             yv[c] = c == 0 ? 1.0 : 0.0;
-            q1 = ES[(size_t)L * C + c];
+            q1 = EI[(size_t)L * C + c].x;
         }
-        ring[slot * C + c] = q1;
+        ring[(XPf + slot) * RS + c] = q1;
+        ring[(XPf + slot + K) * RS + c] = q1;
         const int j0 = BWD ? L / J : 0;
         const int j1 = BWD ? max(j0 - 1, 0) : min(j0 + 1, L / J);
         nb_cur = nb[(size_t)j0 * C + c];
         nb_nxt = nb[(size_t)j1 * C + c];
     }
-    if (!BWD) prevsum = (double)C;
     lds_barrier();
-    if (!BWD && p.want_grad) {
-        for (int i = tid; i < KC; i += nthreads) ckbase[i] = ring[i];
-        if (tid < C) ckbase[KC + tid] = yv[tid];
-        if (tid == 0) ckY[0] = 0.0;
-    }
-
-    auto step_slot = [&](int sl, int by) {  // slot of the position `by` steps further along the scan
-        int r = BWD ? sl - by : sl + by;
-        while (r < 0) r += K;
-        while (r >= K) r -= K;
-        return r;
+    auto write_checkpoint = [&](int i) {
+        double *ck = ckbase + (size_t)i * ckstride;
+        for (int q = tid; q < KC; q += nthreads) ck[q] = ring[(XPf + q / C) * RS + (q % C)];
+        if (tid < C) ck[KC + tid] = yv[tid];
+        if (tid == 0) ckY[i] = Y;
     };
-    // helper: partial of sum_{k>=3} W[k,c] ring[pos -/+ k] for the position whose slot is ps.
-    // Every load is unconditional (invalid terms carry weight 0 and a clamped duration).
+    if (!BWD && p.want_grad) write_checkpoint(0);
+
+    // helper: partial of sum_{k>=3} W[k,c] ring[pos -/+ k] over this lane's NKL consecutive
+    // durations, for the position whose lower-copy slot is ps.
     auto helper_partial = [&](int ps, int buf) {
+        const double *base = BWD ? ring + (size_t)(ps + k0) * RS + c
+                                 : ring + (size_t)(XPf + ps + K - k0 - (NKL - 1) * GW) * RS + c;
         double v[NKL];
 #pragma unroll
-        for (int j = 0; j < NKL; ++j) {
-            int k = kfirst + j * NG;
-            k = k > K ? K : k;
-            int sl = BWD ? ps + k : ps - k;
-            if (BWD) sl = sl >= K ? sl - K : sl;
-            else sl = sl < 0 ? sl + K : sl;
-            v[j] = ring[sl * C + cc];
-        }
+        for (int j = 0; j < NKL; ++j) v[j] = base[j * GW * RS];
         double a0 = 0.0, a1 = 0.0;
 #pragma unroll
         for (int j = 0; j < NKL; j += 2) {
             a0 = fma(wreg[j], v[j], a0);
             a1 = fma(wreg[j + 1], v[j + 1], a1);
         }
-        double acc = a0 + a1;
-#pragma unroll
-        for (int off = CT; off < 64; off <<= 1) acc += __shfl_xor(acc, off);
-        if (lane < CT) part[((size_t)buf * NH_MAX + (wave - 1)) * CT + lane] = cval ? acc : 0.0;
+        const double acc = group_sum<CTP>(a0 + a1);
+        if (lane < CTP) part[((size_t)buf * NH_MAX + (wave - 1)) * CTP + lane] = acc;
     };
-    auto read_partials = [&](int buf) {
-        double v[NH_MAX];
-#pragma unroll
-        for (int w = 0; w < NH_MAX; ++w) v[w] = part[((size_t)buf * NH_MAX + w) * CT + cc];
-        double s = 0.0;
-#pragma unroll
-        for (int w = 0; w < NH_MAX; ++w) s += v[w];
-        return s;
-    };
-
-    // ---- emission-factor prefetch queue (tip lanes)
-    double qa[PF], qb[PF];
-#pragma unroll
-    for (int j = 0; j < PF; ++j) {
-        qa[j] = 0.0;
-        qb[j] = 0.0;
-        if (tip && cval) {
-            int n = 1 + j;
-            if (n > L) n = L;
-            const int t = BWD ? L - n : n;
-            qa[j] = ES[(size_t)t * C + c];
-            qb[j] = IES[(size_t)t * C + c];
+    auto step_slot = [&](int sl, int by) {  // slot of the position `by` steps further along the scan
+        int r = BWD ? sl - by : sl + by;  // by <= 2, so two conditional wraps suffice for any K >= 1
+        if (BWD) {
+            if (r < 0) r += K;
+            if (r < 0) r += K;
+        } else {
+            if (r >= K) r -= K;
+            if (r >= K) r -= K;
         }
-    }
+        return r;
+    };
 
-    // Nothing lies k >= 3 behind steps 1 and 2, so their partials are the zeros
-    // already in `part`.  psum is the partial of the step about to run.
-    double psum = 0.0;
-    for (int nbase = 1; nbase <= L; nbase += PF) {
-#pragma unroll
-        for (int j = 0; j < PF; ++j) {
-            const int n = nbase + j;
-            if (n <= L) {  // uniform
-                const int t = BWD ? L - n : n;
-                const double es = qa[j], ies = qb[j];
-                if (tip && cval) {
-                    int n2 = n + PF;
-                    if (n2 > L) n2 = L;
-                    const int t2 = BWD ? L - n2 : n2;
-                    qa[j] = ES[(size_t)t2 * C + c];
-                    qb[j] = IES[(size_t)t2 * C + c];
-                }
-                const bool boundary = BWD ? ((t + 1) % J) == 0 : (t % J) == 0;
-                int scl = 0;
-                if (boundary) {  // uniform: rescale ring, tip registers and the pending partials
-                    if (tip) {
-                        const int e = safe_exponent(prevsum);
-                        Y += (double)e;
-                        if (cval) {
-                            const int sft = (BWD ? -(nb_nxt - nb_cur) : (nb_nxt - nb_cur)) - e;
-                            sc[c] = sft;
-                            scl = sft;
-                            q1 = fmin(ldexp(q1, sft), DBL_MAX);
-                            q2 = fmin(ldexp(q2, sft), DBL_MAX);
-                            psum = fmin(ldexp(psum, sft), DBL_MAX);
-                            nb_cur = nb_nxt;
-                            const int jn = t / J;
-                            const int j2 = BWD ? max(jn - 1, 0) : min(jn + 1, L / J);
-                            nb_nxt = nb[(size_t)j2 * C + c];
-                        }
-                    }
-                    lds_barrier();
-                    for (int i = tid; i < KC; i += nthreads)
-                        ring[i] = fmin(ldexp(ring[i], sc[i % C]), DBL_MAX);
-                    lds_barrier();
-                }
-                slot = step_slot(slot, 1);
-                if (tip) {
-                    // partial of the NEXT step (finished by the helpers one barrier ago)
-                    double pnext = read_partials((n + 1) & 1);
-                    if (scl != 0) pnext = fmin(ldexp(pnext, scl), DBL_MAX);
-                    const double x = fma(W1, q1, fma(W2, q2, psum));
-                    const double y = x * (BWD ? ies : es);
-                    if (cval) yv[c] = y;
-                    lds_wave_fence();
-                    double z0 = 0.0, z1 = 0.0, ysum = 0.0;
-                    const bool want_sum = BWD ? (t % J) == 0 : ((t + 1) % J) == 0;
-#pragma unroll
-                    for (int i = 0; i < CT; i += 2) {
-                        const double v0 = yv[i], v1 = yv[i + 1];
-                        z0 = fma(v0, Ereg[i], z0);
-                        z1 = fma(v1, Ereg[i + 1], z1);
-                        if (want_sum) ysum += v0 + v1;
-                    }
-                    if (want_sum) prevsum = ysum;
-                    const double z = z0 + z1;
-                    q2 = q1;
-                    q1 = z * (BWD ? es : ies);
-                    if (cval) ring[slot * C + c] = q1;
-                    psum = pnext;
-                    if (BWD && n == L) {  // beta_0: diagnostic partition function
-                        lds_wave_fence();
-                        if (cval) yv[c] = z;
-                    }
-                } else if (n + 2 <= L) {
-                    helper_partial(step_slot(slot, 2), n & 1);
-                }
+    // ---- pieces of a step that every wave runs (uniform control flow, same barriers)
+    auto rescale_ring = [&]() {  // sc[] was written by the tip before the first barrier
+        lds_barrier();
+        for (int i = tid; i < RTOT; i += nthreads)
+            ring[i] = fmin(ldexp(ring[i], sc[i % RS]), DBL_MAX);
+        lds_barrier();
+    };
+    // steps left until the next checkpoint position (a positive multiple of Delta)
+    int dleft = BWD ? L - ((L - 1) / Delta) * Delta : Delta;
+    auto after_step = [&](int t) {
+        if (--dleft == 0) {
+            dleft = Delta;
+            if (p.want_grad && t > 0) {
+                write_checkpoint(t / Delta);
                 lds_barrier();
-                if (p.want_grad && (t % Delta) == 0 && t > 0) {  // uniform
-                    const int i = t / Delta;
-                    double *ck = ckbase + (size_t)i * ckstride;
-                    for (int q = tid; q < KC; q += nthreads) ck[q] = ring[q];
-                    if (tid < C) ck[KC + tid] = yv[tid];
-                    if (tid == 0) ckY[i] = Y;
-                    lds_barrier();
-                }
             }
         }
-    }
-    if (tid == 0) {
-        double s = 0.0;
-        for (int i = 0; i < C; ++i) s += (BWD && L == 0) ? 1.0 : yv[i];
-        const double lz = Y * LN2 + log(s);
-        if (BWD) {
-            p.hdr[b].logZb = lz;
-        } else {
-            p.hdr[b].logZ = lz;
-            p.logz[b] = (float)lz;
+    };
+
+    if (tip) {
+        // All 64 lanes run the same instruction stream without masks: lanes whose label
+        // index is >= C carry zeros (W1 = W2 = 0, Ereg = 0, their partials are 0).
+        const double2 *EIc = EI + cc;  // this lane's column; rows are addressed by a uniform offset
+        double2 qe[PF];                // emission factors of the next PF steps
+#pragma unroll
+        for (int j = 0; j < PF; ++j) {
+            int n = 1 + j;
+            if (n > L) n = L;
+            qe[j] = EIc[(size_t)(BWD ? L - n : n) * C];
+        }
+        // Nothing lies k >= 3 behind steps 1 and 2, so their partials are the zeros
+        // already in `part`.  psum is the partial of the step about to run.
+        double psum = 0.0, zlast = 1.0;
+        const double2 *ys = (const double2 *)__builtin_assume_aligned(yv + hh * HC, 16);
+        auto tip_step = [&](const int n, const double2 e) {
+            const int t = BWD ? L - n : n;
+            const bool boundary = BWD ? ((t + 1) & Jm) == 0 : (t & Jm) == 0;
+            int sft = 0;
+            if (boundary) {  // uniform: rescale ring, tip registers and the pending partials
+                const int ex = safe_exponent(prevsum);
+                Y += (double)ex;
+                sft = (cval ? (BWD ? -(nb_nxt - nb_cur) : (nb_nxt - nb_cur)) : 0) - ex;
+                sc[c] = sft;
+                q1 = fmin(ldexp(q1, sft), DBL_MAX);
+                q2 = fmin(ldexp(q2, sft), DBL_MAX);
+                psum = fmin(ldexp(psum, sft), DBL_MAX);
+                nb_cur = nb_nxt;
+                const int jn = t / J;
+                const int j2 = BWD ? max(jn - 1, 0) : min(jn + 1, L / J);
+                nb_nxt = nb[(size_t)j2 * C + cc];
+                rescale_ring();
+            }
+            slot = step_slot(slot, 1);
+            // partial of the NEXT step (finished by the helpers one barrier ago)
+            const double *pp = part + (size_t)((n + 1) & 1) * NH_MAX * CTP + c;
+            double pv[NHR];
+#pragma unroll
+            for (int w = 0; w < NHR; ++w) pv[w] = pp[w * CTP];
+            const double x = fma(W1, q1, fma(W2, q2, psum));
+            yv[c] = x * (BWD ? e.y : e.x);
+            lds_wave_fence();
+            double z0 = 0.0, z1 = 0.0;
+#pragma unroll
+            for (int i = 0; i < HC; i += 2) {
+                const double2 vv = ys[i >> 1];
+                z0 = fma(vv.x, Ereg[i], z0);
+                z1 = fma(vv.y, Ereg[i + 1], z1);
+            }
+            double z = z0 + z1;
+            if (H == 2) z = add_across_32(z);
+            q2 = q1;
+            q1 = z * (BWD ? e.x : e.y);
+            double *rw = ring + (size_t)(XPf + slot) * RS + c;
+            rw[0] = q1;
+            rw[(size_t)K * RS] = q1;
+            double pn = pv[0];
+#pragma unroll
+            for (int w = 1; w < NHR; ++w) pn += pv[w];
+            if (boundary) pn = fmin(ldexp(pn, sft), DBL_MAX);  // computed before the rescale
+            psum = pn;
+            zlast = z;
+            const bool want_sum = BWD ? (t & Jm) == 0 : ((t + 1) & Jm) == 0;
+            if (want_sum) {  // uniform: scale reference for the boundary that follows
+                double sum = 0.0;
+                for (int i = 0; i < CT; ++i) sum += yv[i];
+                prevsum = sum;
+            }
+            lds_barrier();
+            after_step(t);
+        };
+        int n = 1;
+        for (; n + PF - 1 <= L; n += PF) {
+#pragma unroll
+            for (int j = 0; j < PF; ++j) {
+                const double2 e = qe[j];
+                int n2 = n + j + PF;
+                if (n2 > L) n2 = L;
+                qe[j] = EIc[__builtin_amdgcn_readfirstlane((BWD ? L - n2 : n2) * C)];
+                tip_step(n + j, e);
+            }
+        }
+        for (; n <= L; ++n) tip_step(n, EIc[(size_t)(BWD ? L - n : n) * C]);
+        if (BWD && L > 0) yv[c] = zlast;  // beta_0: diagnostic partition function
+        lds_wave_fence();
+        if (tid == 0) {
+            double s = 0.0;
+            for (int i = 0; i < C; ++i) s += (BWD && L == 0) ? 1.0 : yv[i];
+            const double lz = Y * LN2 + log(s);
+            if (BWD) {
+                p.hdr[b].logZb = lz;
+            } else {
+                p.hdr[b].logZ = lz;
+                p.logz[b] = (float)lz;
+            }
+        }
+    } else {
+        for (int n = 1; n <= L; ++n) {
+            const int t = BWD ? L - n : n;
+            const bool boundary = BWD ? ((t + 1) & Jm) == 0 : (t & Jm) == 0;
+            if (boundary) rescale_ring();
+            slot = step_slot(slot, 1);
+            if (n + 2 <= L) helper_partial(step_slot(slot, 2), n & 1);
+            lds_barrier();
+            after_step(t);
         }
     }
 }
 
-template <int CT, int NKL>
-__global__ __launch_bounds__(CT == 64 ? 256 : 512) void k_scan_fast(Params p, int both)
+template <int CT, int NHR>
+__global__ __launch_bounds__(CT == 64 ? 64 * (NHR + 1) : 320) void k_scan_fast(Params p, int both)
 {
     extern __shared__ double lds_raw[];
     const int b = both ? (int)(blockIdx.x >> 1) : (int)blockIdx.x;
     const int dir = both ? (int)(blockIdx.x & 1) : 0;
-    if (dir == 0) scan_fast_body<CT, NKL, false>(p, lds_raw, b);
-    else scan_fast_body<CT, NKL, true>(p, lds_raw, b);
+    if (dir == 0) scan_fast_body<CT, NHR, false>(p, lds_raw, b);
+    else scan_fast_body<CT, NHR, true>(p, lds_raw, b);
 }
 
 // ---------------------------------------------------------------------------
@@ -815,8 +901,7 @@ __global__ __launch_bounds__(NT) void k_interval(Params p)
         if (t0 >= L) continue;  // uniform
         const int t1 = min(t0 + Delta, L);
         const size_t row0 = (size_t)b * (p.T + 1);
-        const double *ES = p.ES + row0 * C;
-        const double *IES = p.IES + row0 * C;
+        const double2 *EI = p.EI + row0 * C;
         const int *nb = p.nbase + row0 * C;
         const double logZ = h.logZ;
 
@@ -838,7 +923,7 @@ __global__ __launch_bounds__(NT) void k_interval(Params p)
                 double pm = vec_sum(l.yv, C);
                 Y += (double)rebase_ring(p, l, nb, t / J, t / J - 1, +1, pm, tid);
             }
-            fwd_step(p, l, G, tid, t, ES + (size_t)t * C, IES + (size_t)t * C);
+            fwd_step(p, l, G, tid, t, EI + (size_t)t * C);
             if (tid < C) {
                 double *row = aloc + (size_t)(t - t0) * 2 * C;
                 row[tid] = l.yv[tid];
@@ -855,7 +940,7 @@ __global__ __launch_bounds__(NT) void k_interval(Params p)
             __syncthreads();
             if (tid < C) {
                 l.yv[tid] = tid == 0 ? 1.0 : 0.0;
-                l.ring[(L % K) * C + tid] = ES[(size_t)L * C + tid];
+                l.ring[(L % K) * C + tid] = EI[(size_t)L * C + tid].x;
             }
             Yb = 0.0;
         } else {
@@ -908,7 +993,7 @@ __global__ __launch_bounds__(NT) void k_interval(Params p)
             if (tid < C) {
                 double x = 0.0;
                 for (int i = 0; i < G; ++i) x += l.red[i * C + tid];
-                l.yv[tid] = x * IES[(size_t)t * C + tid];
+                l.yv[tid] = x * EI[(size_t)t * C + tid].y;
                 outv = l.qv[tid] * x * kappa;
             }
             __syncthreads();
@@ -916,7 +1001,7 @@ __global__ __launch_bounds__(NT) void k_interval(Params p)
                 double z = 0.0;
                 for (int cc = 0; cc < C; ++cc) z = fma(l.El[tid * CP1 + cc], l.yv[cc], z);
                 l.zv[tid] = z;
-                l.ring[s0 * C + tid] = z * ES[(size_t)t * C + tid];
+                l.ring[s0 * C + tid] = z * EI[(size_t)t * C + tid].x;
                 const double inv = t >= 1 ? l.av[tid] * z * kappa : 0.0;
                 p.grad_emis[((size_t)b * p.T + t) * C + tid] = (float)R;
                 sR += R;
@@ -1062,8 +1147,8 @@ int make_plan(int B, int T, int K, int C, int ckpt_interval, int want_grad, Plan
     sz[i++] = 2 * 8;                              // 4 tabmax
     sz[i++] = k * c * 8;                          // 5 W
     sz[i++] = c * c * 8;                          // 6 Etr
-    sz[i++] = b * t1 * c * 8;                     // 7 ES
-    sz[i++] = b * t1 * c * 8;                     // 8 IES
+    sz[i++] = b * t1 * c * 16;                    // 7 EI
+    sz[i++] = 0;                                  // 8 (unused)
     sz[i++] = b * t1 * c * 4;                     // 9 nbase
     const size_t g = want_grad ? 1 : 0;
     sz[i++] = g * b * (n + 1) * (k * c + c) * 8;  // 10 ckA
@@ -1097,8 +1182,7 @@ void bind_workspace(Params &p, const Plan &pl, void *ws)
     p.tabmax = (double *)(w + pl.off[4]);
     p.W = (double *)(w + pl.off[5]);
     p.Etr = (double *)(w + pl.off[6]);
-    p.ES = (double *)(w + pl.off[7]);
-    p.IES = (double *)(w + pl.off[8]);
+    p.EI = (double2 *)(w + pl.off[7]);
     p.nbase = (int *)(w + pl.off[9]);
     p.ckA = (double *)(w + pl.off[10]);
     p.ckB = (double *)(w + pl.off[11]);
@@ -1130,16 +1214,17 @@ int launch_prep(const Params &p, hipStream_t st)
     return check_launch();
 }
 
-// Chooses the latency-oriented scan when the helper lanes can hold the duration
-// strips in registers, else the generic one.
-template <int CT, int NKL>
-int launch_scan_fast(const Params &p, hipStream_t st, bool both, int NH)
+// Chooses the latency-oriented scan when the helper lanes can cover the durations,
+// else the generic one.  Returns 1 when the fast path does not apply.
+template <int CT, int NHR>
+int launch_scan_fast(const Params &p, hipStream_t st, bool both)
 {
-    const size_t lds = fast_lds_doubles(p.K, p.C, CT) * sizeof(double);
-    if (hipFuncSetAttribute((const void *)k_scan_fast<CT, NKL>,
+    const size_t lds = fast_lds_doubles(p.K, pow2_ge8(CT), NHR) * sizeof(double);
+    if (lds > LDS_LIMIT) return 1;
+    if (hipFuncSetAttribute((const void *)k_scan_fast<CT, NHR>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return SEMICRF_ELAUNCH;
-    hipLaunchKernelGGL((k_scan_fast<CT, NKL>), dim3(both ? 2 * p.B : p.B), dim3(64 * (NH + 1)), lds,
+    hipLaunchKernelGGL((k_scan_fast<CT, NHR>), dim3(both ? 2 * p.B : p.B), dim3(64 * (NHR + 1)), lds,
                        st, p, both ? 1 : 0);
     return check_launch();
 }
@@ -1147,23 +1232,22 @@ int launch_scan_fast(const Params &p, hipStream_t st, bool both, int NH)
 template <int CT>
 int launch_scan_ct(const Params &p, hipStream_t st, bool both)
 {
-    constexpr int GW = 64 / CT;
-    constexpr int NHcap = CT == 64 ? 3 : NH_MAX;
-    const int terms = p.K > 2 ? p.K - 2 : 0;           // durations k >= 3 go to the helpers
-    int NH = (terms + 4 * GW - 1) / (4 * GW);           // aim at <= 4 terms per helper lane
-    NH = NH < 1 ? 1 : (NH > NHcap ? NHcap : NH);
-    const int per_lane = (terms + NH * GW - 1) / (NH * GW);
-    if (per_lane > 16 || fast_lds_doubles(p.K, p.C, CT) * sizeof(double) > LDS_LIMIT) return 1;
-    if (per_lane <= 8) return launch_scan_fast<CT, 8>(p, st, both, NH);
-    return launch_scan_fast<CT, 16>(p, st, both, NH);
+    constexpr int GW = 64 / pow2_ge8(CT);
+    const int terms = p.K > 2 ? p.K - 2 : 0;  // durations k >= 3 go to the helpers
+    if (terms <= 1 * GW * NKL) return launch_scan_fast<CT, 1>(p, st, both);
+    if (terms <= 2 * GW * NKL) return launch_scan_fast<CT, 2>(p, st, both);
+    if (CT < 64 && terms <= 4 * GW * NKL)
+        return launch_scan_fast<CT, (CT < 64 ? 4 : 2)>(p, st, both);
+    return 1;
 }
 
 int launch_scan(const Params &p, const Plan &pl, hipStream_t st, bool both)
 {
     const int C = p.C;
-    int rc = 1;  // 1 = fast path not applicable
+    int rc = 1;
     if (C <= 8) rc = launch_scan_ct<8>(p, st, both);
     else if (C <= 16) rc = launch_scan_ct<16>(p, st, both);
+    else if (C <= 24) rc = launch_scan_ct<24>(p, st, both);
     else if (C <= 32) rc = launch_scan_ct<32>(p, st, both);
     else if (C <= 64) rc = launch_scan_ct<64>(p, st, both);
     if (rc != 1) return rc;
