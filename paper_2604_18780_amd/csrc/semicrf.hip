@@ -592,7 +592,7 @@ __host__ __device__ inline FastGeom fast_geom(int K, int CTP, int NH)
 
 __host__ __device__ inline size_t fast_lds_doubles(int K, int CTP, int NH)
 {
-    return (size_t)fast_geom(K, CTP, NH).RSLOTS * CTP + 2 * (size_t)NH_MAX * CTP + 2 * (size_t)CTP;
+    return (size_t)fast_geom(K, CTP, NH).RSLOTS * CTP + 2 * (size_t)NH_MAX * CTP + 2 * (size_t)CTP;  // yv + 2 int arrays
 }
 
 template <int CT, int NHR, bool BWD>
@@ -613,7 +613,8 @@ __device__ __forceinline__ void scan_fast_body(const Params &p, double *lds, con
     double *ring = lds;                           // [RSLOTS][RS]
     double *part = ring + RTOT;                   // [2][NH_MAX][CTP]
     double *yv = part + 2 * (size_t)NH_MAX * CTP; // [CTP]
-    int *sc = (int *)(yv + CTP);                  // [CTP]
+    int *sc = (int *)(yv + CTP);                  // [CTP] shift applied at the current boundary
+    int *sc_dn = sc + CTP;                        // [CTP] block-exponent delta of the next boundary
     const SeqHdr h = p.hdr[b];
     const int L = h.L, J = h.J, Jm = J - 1, Delta = p.Delta;
     const size_t row0 = (size_t)b * (p.T + 1);
@@ -669,7 +670,6 @@ __device__ __forceinline__ void scan_fast_body(const Params &p, double *lds, con
     // ---- first position (t = 0 forward, t = L backward)
     double q1 = 0.0, q2 = 0.0, Y = 0.0, prevsum = BWD ? 1.0 : (double)C;
     int slot = BWD ? L % K : 0;  // ring slot (lower copy) of the position just processed
-    int nb_cur = 0, nb_nxt = 0;  // scaling exponents of the current / next block (tip lanes)
     if (tip && cval) {
         if (!BWD) {
             yv[c] = 1.0;
@@ -684,10 +684,20 @@ __device__ __forceinline__ void scan_fast_body(const Params &p, double *lds, con
         }
         ring[(XPf + slot) * RS + c] = q1;
         ring[(XPf + slot + K) * RS + c] = q1;
-        const int j0 = BWD ? L / J : 0;
-        const int j1 = BWD ? max(j0 - 1, 0) : min(j0 + 1, L / J);
-        nb_cur = nb[(size_t)j0 * C + c];
-        nb_nxt = nb[(size_t)j1 * C + c];
+    }
+    // Block-exponent deltas are staged through LDS by helper wave 1, one boundary ahead, so
+    // that no global load is ever pending in a tip register (a wait on it would also
+    // drain the tip's emission-factor prefetch queue, the counter being in-order).
+    // sc_dn holds n_new(c) - n_old(c) of the next boundary; dn_from/dn_to are the pending loads
+    // of n(c) on both sides of the boundary after it.
+    int dn_from = 0, dn_to = 0;
+    const int jlast = L / J;
+    auto block_after = [&](int j) { return BWD ? max(j - 1, 0) : min(j + 1, jlast); };
+    if (wave == 1) {
+        const int j0 = BWD ? jlast : 0, j1 = block_after(j0), j2 = block_after(j1);
+        if (lane < CTP) sc_dn[lane] = nb[(size_t)j1 * C + cc] - nb[(size_t)j0 * C + cc];
+        dn_from = nb[(size_t)j1 * C + cc];
+        dn_to = nb[(size_t)j2 * C + cc];
     }
     lds_barrier();
     auto write_checkpoint = [&](int i) {
@@ -728,16 +738,21 @@ __device__ __forceinline__ void scan_fast_body(const Params &p, double *lds, con
     };
 
     // ---- pieces of a step that every wave runs (uniform control flow, same barriers)
-    auto rescale_ring = [&]() {  // sc[] was written by the tip before the first barrier
+    // sc[] was written by the tip before the first barrier; pbuf is the partial buffer that
+    // was computed before this boundary and is still to be consumed
+    auto rescale_ring = [&](int pbuf) {
         lds_barrier();
         for (int i = tid; i < RTOT; i += nthreads)
             ring[i] = fmin(ldexp(ring[i], sc[i % RS]), DBL_MAX);
+        double *pb = part + (size_t)pbuf * NH_MAX * CTP;
+        for (int i = tid; i < NH_MAX * CTP; i += nthreads)
+            pb[i] = fmin(ldexp(pb[i], sc[i % CTP]), DBL_MAX);
         lds_barrier();
     };
     // steps left until the next checkpoint position (a positive multiple of Delta)
     int dleft = BWD ? L - ((L - 1) / Delta) * Delta : Delta;
     auto after_step = [&](int t) {
-        if (--dleft == 0) {
+        if (__builtin_expect(--dleft == 0, 0)) {
             dleft = Delta;
             if (p.want_grad && t > 0) {
                 write_checkpoint(t / Delta);
@@ -764,20 +779,15 @@ __device__ __forceinline__ void scan_fast_body(const Params &p, double *lds, con
         auto tip_step = [&](const int n, const double2 e) {
             const int t = BWD ? L - n : n;
             const bool boundary = BWD ? ((t + 1) & Jm) == 0 : (t & Jm) == 0;
-            int sft = 0;
-            if (boundary) {  // uniform: rescale ring, tip registers and the pending partials
+            if (__builtin_expect(boundary, 0)) {  // uniform: rescale ring, tip registers, pending partials
                 const int ex = safe_exponent(prevsum);
                 Y += (double)ex;
-                sft = (cval ? (BWD ? -(nb_nxt - nb_cur) : (nb_nxt - nb_cur)) : 0) - ex;
+                const int sft = (BWD ? -sc_dn[c] : sc_dn[c]) - ex;
                 sc[c] = sft;
                 q1 = fmin(ldexp(q1, sft), DBL_MAX);
                 q2 = fmin(ldexp(q2, sft), DBL_MAX);
                 psum = fmin(ldexp(psum, sft), DBL_MAX);
-                nb_cur = nb_nxt;
-                const int jn = t / J;
-                const int j2 = BWD ? max(jn - 1, 0) : min(jn + 1, L / J);
-                nb_nxt = nb[(size_t)j2 * C + cc];
-                rescale_ring();
+                rescale_ring((n + 1) & 1);
             }
             slot = step_slot(slot, 1);
             // partial of the NEXT step (finished by the helpers one barrier ago)
@@ -805,11 +815,10 @@ __device__ __forceinline__ void scan_fast_body(const Params &p, double *lds, con
             double pn = pv[0];
 #pragma unroll
             for (int w = 1; w < NHR; ++w) pn += pv[w];
-            if (boundary) pn = fmin(ldexp(pn, sft), DBL_MAX);  // computed before the rescale
             psum = pn;
             zlast = z;
             const bool want_sum = BWD ? (t & Jm) == 0 : ((t + 1) & Jm) == 0;
-            if (want_sum) {  // uniform: scale reference for the boundary that follows
+            if (__builtin_expect(want_sum, 0)) {  // uniform: scale reference for the boundary that follows
                 double sum = 0.0;
                 for (int i = 0; i < CT; ++i) sum += yv[i];
                 prevsum = sum;
@@ -846,7 +855,17 @@ __device__ __forceinline__ void scan_fast_body(const Params &p, double *lds, con
         for (int n = 1; n <= L; ++n) {
             const int t = BWD ? L - n : n;
             const bool boundary = BWD ? ((t + 1) & Jm) == 0 : (t & Jm) == 0;
-            if (boundary) rescale_ring();
+            if (__builtin_expect(boundary, 0)) {
+                rescale_ring((n + 1) & 1);
+                if (wave == 1) {
+                    // this boundary consumed sc_dn: publish the delta of the next boundary (its
+                    // loads were issued one boundary ago) and start loading the one after it
+                    if (lane < CTP) sc_dn[lane] = dn_to - dn_from;
+                    const int ja = block_after(t / J), jb = block_after(ja);
+                    dn_from = nb[(size_t)ja * C + cc];
+                    dn_to = nb[(size_t)jb * C + cc];
+                }
+            }
             slot = step_slot(slot, 1);
             if (n + 2 <= L) helper_partial(step_slot(slot, 2), n & 1);
             lds_barrier();

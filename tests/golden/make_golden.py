@@ -1,0 +1,60 @@
+#!/usr/bin/env python3
+"""Writes the stored expected values for the full-size parity cases.
+
+Calls ONLY the CPU oracle (``oracle/``) and the seeded input generators; nothing
+here touches the GPU library.  For each named workload at its full size it runs
+the fp64 oracle once and stores logZ, the accumulated gradients and the
+per-position outputs at a fixed random sample of (sequence, position) rows:
+
+    python tests/golden/make_golden.py speech genomic longgen
+
+Output: tests/golden/full_<name>.npz (float64 arrays, a few hundred KB each).
+"""
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+sys.path.insert(0, ROOT)
+
+import oracle  # noqa: E402
+from paper_2604_18780_amd import synth  # noqa: E402
+
+NSAMPLE = 4096
+
+
+def sample_rows(w, seed=12345):
+    """Fixed sample of valid (b, u) rows, always including the first and last token."""
+    rng = np.random.default_rng(seed)
+    rows = []
+    for b in range(w.B):
+        L = int(w.lengths[b])
+        if L == 0:
+            continue
+        n = max(2, NSAMPLE // w.B)
+        u = np.unique(np.concatenate([[0, L - 1], rng.integers(0, L, size=n)]))
+        rows.append(np.stack([np.full_like(u, b), u], 1))
+    return np.concatenate(rows, 0)
+
+
+def main(names):
+    for name in names:
+        w = synth.make(name)
+        t0 = time.time()
+        r = oracle.fwd_bwd(w.emis, w.lengths, w.trans, w.dur)
+        dt = time.time() - t0
+        rows = sample_rows(w)
+        out = os.path.join(os.path.dirname(os.path.abspath(__file__)), f"full_{name}.npz")
+        np.savez_compressed(
+            out, logz=r.logz, grad_trans=r.grad_trans, grad_dur=r.grad_dur, rows=rows,
+            pos_marg_rows=r.pos_marg[rows[:, 0], rows[:, 1]],
+            grad_emis_rows=r.grad_emis[rows[:, 0], rows[:, 1]],
+            pos_marg_total=np.array([r.pos_marg.sum()]),
+            oracle_seconds=np.array([dt]), oracle_threads=np.array([r.threads]))
+        print(f"{name}: oracle {dt:.1f}s on {r.threads} threads -> {out}", flush=True)
+
+
+if __name__ == "__main__":
+    main(sys.argv[1:] or ["speech", "genomic", "longgen"])

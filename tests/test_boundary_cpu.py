@@ -1,0 +1,129 @@
+"""Host-side checks of the C-ABI library that need no GPU.
+
+The shared library must load, export every symbol that ``include/semicrf.h``
+declares, size its workspace sensibly and reject bad arguments before touching
+the device.  No kernel is launched here.
+"""
+import ctypes
+import math
+import os
+import re
+
+import pytest
+
+from paper_2604_18780_amd import binding as sb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "semicrf.h")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(semicrf_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ctypes.CDLL(sb.LIB_PATH)
+    names = declared_functions()
+    assert set(names) == set(sb.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_version_and_strerror():
+    assert sb.semicrf_version() >= 1
+    assert sb.semicrf_strerror(0) == "ok"
+    for code in (-1, -2, -3, -4):
+        assert sb.semicrf_strerror(code) not in ("ok", "unknown status")
+    assert sb.semicrf_strerror(-99) == "unknown status"
+
+
+def test_workspace_bytes_rejects_bad_sizes():
+    lib = sb.load()
+    out = ctypes.c_size_t(0)
+    for args in [(0, 8, 2, 3), (1, 0, 2, 3), (1, 8, 0, 3), (1, 8, 2, 0), (-1, 8, 2, 3)]:
+        assert lib.semicrf_workspace_bytes(*args, 0, 1, ctypes.byref(out)) == -1
+    assert lib.semicrf_workspace_bytes(1, 8, 2, 3, -5, 1, ctypes.byref(out)) == -1
+    assert lib.semicrf_workspace_bytes(1, 8, 2, 3, 0, 1, None) == -1
+    # label count beyond the kernels' limits
+    assert lib.semicrf_workspace_bytes(1, 8, 2, 257, 0, 0, ctypes.byref(out)) == -3
+    assert lib.semicrf_workspace_bytes(1, 8, 2, 65, 0, 1, ctypes.byref(out)) == -3
+    assert lib.semicrf_workspace_bytes(1, 8, 2, 65, 0, 0, ctypes.byref(out)) == 0
+    # K*C too large for the LDS ring
+    assert lib.semicrf_workspace_bytes(1, 100000, 4096, 64, 0, 1, ctypes.byref(out)) == -3
+
+
+def test_workspace_is_aligned_positive_and_monotone():
+    prev = 0
+    for T in (1000, 10000, 100000, 400000):
+        n = sb.semicrf_workspace_bytes(4, T, 64, 24, 0, True)
+        assert n % 256 == 0 and n > prev
+        prev = n
+    assert sb.semicrf_workspace_bytes(4, 1000, 64, 24, 0, False) < sb.semicrf_workspace_bytes(4, 1000, 64, 24, 0, True)
+
+
+def test_working_memory_beyond_prefix_arrays_is_sublinear_in_T():
+    """Checkpoints + per-interval recompute buffers must grow like sqrt(T): the
+    part of the workspace that is not the O(T*C) prefix arrays, measured as
+    (grad workspace - forward-only workspace), may at most double when T grows
+    fourfold (it would quadruple if it were linear)."""
+    B, K, C = 4, 64, 24
+    extra = []
+    for T in (100000, 400000, 1600000):
+        extra.append(sb.semicrf_workspace_bytes(B, T, K, C, 0, True)
+                     - sb.semicrf_workspace_bytes(B, T, K, C, 0, False))
+    assert extra[1] / extra[0] < 2.3 and extra[2] / extra[1] < 2.3
+    # and it is a small fraction of what the paper's own per-interval layout
+    # (full K x C x C gradient workspace per checkpoint) would need
+    T = 100000
+    delta = math.ceil(math.sqrt(T * K))
+    paper_ws = B * math.ceil(T / delta) * K * C * C * 8
+    assert extra[0] < 40 * paper_ws        # same order, no K*C*C blow-up per interval here
+
+
+def test_memory_arithmetic_of_the_paper_example():
+    """Section "Complexity": at T = 1e6, K = 200, C = 6 the edge tensor would be
+    ~29 GB in float32, the prefix-sum array ~24 MB and the ring ~10 KB."""
+    T, K, C = 10**6, 200, 6
+    edge_bytes = T * K * C * C * 4
+    prefix_bytes = (T + 1) * C * 4
+    ring_bytes = K * C * 4 + 2 * K * C * 4          # K-slot forward ring + 2K-slot backward ring
+    assert abs(edge_bytes / 1e9 - 28.8) < 0.1
+    assert abs(prefix_bytes / 1e6 - 24.0) < 0.1
+    assert 9e3 < ring_bytes < 15e3
+    # this library: never anywhere near the edge tensor
+    ws = sb.semicrf_workspace_bytes(1, T, K, C, 0, True)
+    assert ws < edge_bytes / 50
+
+
+def test_calls_reject_null_pointers_and_bad_workspace_before_any_launch():
+    lib = sb.load()
+    # every pointer null: invalid argument, checked on the host only
+    rc = lib.semicrf_logz_fwd(None, None, None, None, 1, 8, 2, 3, 0, 1, None, 0, None, None)
+    assert rc == -1
+    rc = lib.semicrf_fwd_bwd(None, None, None, None, None, 1, 8, 2, 3, 0, 1, None, 0,
+                             None, None, None, None, None, None)
+    assert rc == -1
+    rc = lib.semicrf_cum_scores(None, None, 1, 8, 3, 1, None, 0, None, None)
+    assert rc == -1
+    # non-null (fake, never dereferenced on the host) data pointers but no workspace
+    fake = ctypes.c_void_p(4096)
+    rc = lib.semicrf_logz_fwd(fake, None, fake, fake, 1, 8, 2, 3, 0, 1, None, 0, fake, None)
+    assert rc == -2
+    # misaligned workspace pointer
+    rc = lib.semicrf_logz_fwd(fake, None, fake, fake, 1, 8, 2, 3, 0, 1, ctypes.c_void_p(4100), 1 << 30, fake, None)
+    assert rc == -2
+    # bad sizes win over everything else
+    rc = lib.semicrf_logz_fwd(fake, None, fake, fake, 1, 8, 0, 3, 0, 1, fake, 1 << 30, fake, None)
+    assert rc == -1
+
+
+def test_binding_requires_the_built_library(monkeypatch, tmp_path):
+    import importlib
+    mod = importlib.reload(sb)
+    monkeypatch.setattr(mod, "LIB_PATH", str(tmp_path / "missing.so"))
+    monkeypatch.setattr(mod, "_lib", None)
+    with pytest.raises(FileNotFoundError):
+        mod.load()
+    importlib.reload(sb)

@@ -161,3 +161,51 @@ def test_unsupported_and_invalid_arguments_are_rejected():
     with pytest.raises(sb.SemiCRFError) as ei:
         sb.semicrf_logz_fwd(emis, lengths, trans, dur, ckpt_interval=-1)
     assert ei.value.status == -1
+
+
+# --------------------------------------------------------------------------
+# Full-size workloads, in the launch configuration bench.py times, against
+# oracle values stored by tests/golden/make_golden.py (which calls only oracle/).
+# --------------------------------------------------------------------------
+import os
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+@pytest.mark.parametrize("name", ["speech", "genomic", "longgen"])
+def test_full_size_workload_against_stored_oracle_values(name):
+    path = os.path.join(GOLDEN, f"full_{name}.npz")
+    if not os.path.exists(path):
+        pytest.skip(f"{path} not generated")
+    g = np.load(path)
+    w = synth.make(name)
+    emis, lengths, trans, dur = to_dev(w)
+    print(f"[case] full {name} B={w.B} T={w.T} K={w.K} C={w.C}", flush=True)
+    logz, g_e, g_t, g_d, pm = sb.semicrf_fwd_bwd(emis, lengths, trans, dur)
+    torch.cuda.synchronize()
+    lz = logz.double().cpu().numpy()
+    rel = np.abs(lz - g["logz"]) / np.abs(g["logz"])
+    assert rel.max() <= 1e-5, rel.max()
+    rows = g["rows"]
+    rb = torch.from_numpy(rows[:, 0]).to(DEV)
+    ru = torch.from_numpy(rows[:, 1]).to(DEV)
+    e_pm = np.abs(pm[rb, ru].double().cpu().numpy() - g["pos_marg_rows"]).max()
+    e_ge = np.abs(g_e[rb, ru].double().cpu().numpy() - g["grad_emis_rows"]).max()
+    e_t = np.abs(g_t.double().cpu().numpy() - g["grad_trans"]).max()
+    e_d = np.abs(g_d.double().cpu().numpy() - g["grad_dur"]).max()
+    print(f"       max err: logz rel {rel.max():.2e} pos_marg {e_pm:.2e} grad_emis {e_ge:.2e} "
+          f"grad_trans {e_t:.2e} (max|g| {np.abs(g['grad_trans']).max():.3g}) "
+          f"grad_dur {e_d:.2e} (max|g| {np.abs(g['grad_dur']).max():.3g})", flush=True)
+    assert e_pm <= 1e-4 and e_ge <= 1e-4
+    assert e_t <= 1e-4 * max(1.0, np.abs(g["grad_trans"]).max())
+    assert e_d <= 1e-4 * max(1.0, np.abs(g["grad_dur"]).max())
+    # properties over ALL rows: each valid token's label posterior sums to one,
+    # padding carries no mass, total mass = number of valid tokens
+    row_sum = pm.double().sum(-1)
+    valid = torch.arange(w.T, device=DEV)[None, :] < lengths[:, None]
+    assert (row_sum[valid] - 1.0).abs().max().item() <= 1e-5
+    assert row_sum[~valid].abs().max().item() == 0.0 if (~valid).any() else True
+    assert abs(pm.double().sum().item() - float(w.positions)) <= 1e-6 * w.positions
+    assert pm.min().item() >= -1e-6 and pm.max().item() <= 1.0 + 1e-6
+    # expected segment count from both accumulated gradients agrees
+    assert abs(g_t.double().sum().item() - g_d.double().sum().item()) <= 1e-5 * g_d.double().sum().item()
