@@ -51,6 +51,9 @@ def main():
     ap.add_argument("--ckpt-interval", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-T", type=int, default=0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device-to-device copy so that a rocprofv3 --pmc run of this "
+                         "command holds a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (sequences shard across GPUs with a "
@@ -78,6 +81,12 @@ def main():
            torch.empty((B, T, C), dtype=torch.float32, device=dev))
     events = [sb.StageEvents() for _ in range(args.steps)]
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)          # 1 GiB read + 1 GiB written
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         sb.semicrf_fwd_bwd(emis, lengths, trans, dur, None, args.ckpt_interval, workspace=ws, out=out)
     torch.cuda.synchronize()
