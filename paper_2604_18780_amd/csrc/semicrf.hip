@@ -43,11 +43,11 @@ namespace {
 constexpr int NT = 256;          // threads per workgroup in the scan kernels
 constexpr int PREP_CH = 256;     // positions per prefix-sum chunk (multiple of JMAX)
 constexpr int JMAX = 32;         // largest scaling block
-constexpr int NSLOT_MAX = 512;   // persistent workgroups of the interval kernel
+constexpr int NSLOT_MAX = 1280;  // persistent workgroups of the interval kernel (5 per compute unit)
 constexpr int GRAD_CMAX = 64;    // most labels the gradient path holds transition accumulators for
 constexpr double LN2 = 0.6931471805599453094;
 constexpr double LOG2E = 1.4426950408889634074;
-constexpr double RANGE_NATS = 250.0;  // growth allowed inside one scaling block
+constexpr double RANGE_NATS = 300.0;  // growth allowed inside one scaling block (2x this < ln DBL_MAX)
 constexpr size_t LDS_LIMIT = 160 * 1024;
 
 struct SeqHdr {
@@ -1051,6 +1051,316 @@ __global__ __launch_bounds__(NT) void k_interval(Params p)
 }
 
 // ---------------------------------------------------------------------------
+// Per-interval backward work, throughput-oriented variant (C <= 64): ONE WAVE per
+// task, no barriers.  The interval stage has hundreds of independent tasks, so
+// unlike the scans it is bound by instruction throughput, which several
+// independent single-wave workgroups per compute unit fill better than one
+// multi-wave workgroup that synchronises every step.  A lane (g, c) owns the
+// durations k = 1+g, 1+g+GW, ... of label c (its W strip and its grad_dur
+// accumulators stay in registers for the whole task) and, as in the scan's tip,
+// its part of the transition row (Etr) plus the matching grad_trans accumulators.
+// The ring is stored twice with a compile-time row stride (immediate offsets).
+// ---------------------------------------------------------------------------
+constexpr int PFW = 4;  // prefetch distance (steps) of the per-position rows
+
+__host__ __device__ inline int wave_ring_pad(int K, int CTP, int NKW)
+{
+    const int kmax = (64 / CTP) * NKW;
+    return kmax > K ? kmax - K : 0;
+}
+
+__host__ __device__ inline size_t wave_lds_doubles(int K, int CTP, int NKW)
+{
+    return (size_t)(2 * K + wave_ring_pad(K, CTP, NKW)) * CTP + 2 * (size_t)CTP;
+}
+
+template <int CT, int NKW>
+__global__ __launch_bounds__(64) void k_interval_wave(Params p)
+{
+    constexpr int CTP = pow2_ge8(CT);
+    constexpr int RS = CTP;
+    constexpr int GW = 64 / CTP;
+    constexpr int H = CT <= 32 ? 2 : 1;
+    constexpr int HC = CT / H;
+    extern __shared__ double lds_raw[];
+    const int lane = threadIdx.x;
+    const int K = p.K, C = p.C, KC = K * C, CC = C * C;
+    const int XP = wave_ring_pad(K, CTP, NKW);
+    const int RTOT = (2 * K + XP) * RS;
+    double *ring = lds_raw;          // [2K+XP][RS]
+    double *yv = ring + RTOT;        // [CTP]
+    int *sc = (int *)(yv + CTP);     // [CTP]
+    const int Delta = p.Delta, N = p.N;
+    const size_t ckstride = (size_t)KC + C;
+    const int c = lane % CTP, g = lane / CTP;
+    const int hh = H == 2 ? (lane >> 5) : 0;
+    const bool cval = c < C;
+    const int cc = cval ? c : 0;
+    double2 *aloc = (double2 *)p.aloc + (size_t)blockIdx.x * Delta * C;
+    double *alocY = p.alocY + (size_t)blockIdx.x * Delta;
+
+    // task-invariant registers
+    double wreg[NKW];   // W[k,c], k = 1 + g + j*GW in backward order; reversed for the forward phase
+    double Ereg[HC];    // this lane's part of the transition column (forward) / row (backward)
+#pragma unroll
+    for (int j = 0; j < NKW; ++j) {
+        const int k = 1 + g + j * GW;
+        wreg[j] = (cval && k <= K) ? p.W[(size_t)(k - 1) * C + c] : 0.0;
+    }
+    auto load_etr = [&](bool backward) {
+#pragma unroll
+        for (int i = 0; i < HC; ++i) {
+            const int o = hh * HC + i;
+            const bool ok = cval && o < C;
+            // forward: z(c) = sum_o a(o) Etr[o,c];  backward: b(c) = sum_o Etr[c,o] p(o)
+            Ereg[i] = ok ? (backward ? p.Etr[(size_t)c * C + o] : p.Etr[(size_t)o * C + c]) : 0.0;
+        }
+    };
+    const double2 *ys = (const double2 *)__builtin_assume_aligned(yv + hh * HC, 16);
+
+    auto rescale = [&](int sft) {  // every ring entry of label c times 2^sc[c]
+        sc[c] = sft;
+        lds_wave_fence();
+        for (int i = lane; i < RTOT; i += 64) ring[i] = fmin(ldexp(ring[i], sc[i % RS]), DBL_MAX);
+        lds_wave_fence();
+    };
+
+    const int ntask = p.B * N;
+    for (int task = blockIdx.x; task < ntask; task += gridDim.x) {
+        const int b = task / N, iv = task % N;
+        const SeqHdr h = p.hdr[b];
+        const int L = h.L, J = h.J, Jm = J - 1;
+        const int t0 = iv * Delta;
+        if (t0 >= L) continue;
+        const int t1 = min(t0 + Delta, L);
+        const size_t row0 = (size_t)b * (p.T + 1);
+        const double2 *EIc = p.EI + row0 * C + cc;
+        const int *nbc = p.nbase + row0 * C + cc;
+        const double logZ = h.logZ;
+
+        // ============================ forward recompute over (t0, t1) ============================
+        load_etr(false);
+        for (int i = lane; i < RTOT; i += 64) ring[i] = 0.0;
+        if (lane < CTP) yv[lane] = 0.0;
+        lds_wave_fence();
+        {
+            const double *ck = p.ckA + ((size_t)b * (N + 1) + iv) * ckstride;
+            for (int i = lane; i < KC; i += 64) {
+                const double v = ck[i];
+                const int sl = i / C, col = i % C;
+                ring[(XP + sl) * RS + col] = v;
+                ring[(XP + sl + K) * RS + col] = v;
+            }
+            if (lane < C) yv[lane] = ck[KC + lane];
+        }
+        lds_wave_fence();
+        double Y = p.ckYA[(size_t)b * (N + 1) + iv];
+        double prevsum = 0.0;
+        for (int i = 0; i < CT; ++i) prevsum += yv[i];
+        int slot = t0 % K;
+        if (g == 0 && hh == 0 && cval)
+            aloc[c] = make_double2(yv[c], ring[(size_t)(XP + slot) * RS + c]);
+        if (lane == 0) alocY[0] = Y;
+        {
+            double2 qe[PFW];
+#pragma unroll
+            for (int j = 0; j < PFW; ++j) qe[j] = EIc[(size_t)min(t0 + 1 + j, L) * C];
+            auto fwd_one = [&](const int t, const double2 e) {
+                if (__builtin_expect((t & Jm) == 0, 0)) {
+                    const int ex = safe_exponent(prevsum);
+                    Y += (double)ex;
+                    const int jn = t / J;
+                    rescale(nbc[(size_t)jn * C] - nbc[(size_t)(jn - 1) * C] - ex);
+                }
+                const int ps = slot + 1 == K ? 0 : slot + 1;
+                // x(c) = sum_k W[k,c] q_{t-k}(c); this lane's strip, longest duration first
+                const double *base = ring + (size_t)(XP + ps + K - (1 + g) - (NKW - 1) * GW) * RS + c;
+                double v[NKW];
+#pragma unroll
+                for (int j = 0; j < NKW; ++j) v[j] = base[j * GW * RS];
+                double a0 = 0.0, a1 = 0.0;
+#pragma unroll
+                for (int j = 0; j < NKW; j += 2) {
+                    a0 = fma(wreg[NKW - 1 - j], v[j], a0);
+                    a1 = fma(wreg[NKW - 2 - j], v[j + 1], a1);
+                }
+                const double x = group_sum<CTP>(a0 + a1);
+                const double y = x * e.x;
+                yv[c] = y;
+                lds_wave_fence();
+                double z0 = 0.0, z1 = 0.0, ysum = 0.0;
+#pragma unroll
+                for (int i = 0; i < HC; i += 2) {
+                    const double2 vv = ys[i >> 1];
+                    z0 = fma(vv.x, Ereg[i], z0);
+                    z1 = fma(vv.y, Ereg[i + 1], z1);
+                    ysum += vv.x + vv.y;
+                }
+                double z = z0 + z1;
+                if (H == 2) {
+                    z = add_across_32(z);
+                    ysum = add_across_32(ysum);
+                }
+                prevsum = ysum;
+                const double q = z * e.y;
+                double *rw = ring + (size_t)(XP + ps) * RS + c;
+                rw[0] = q;
+                rw[(size_t)K * RS] = q;
+                lds_wave_fence();
+                slot = ps;
+                if (g == 0 && hh == 0 && cval) aloc[(size_t)(t - t0) * C + c] = make_double2(y, q);
+                if (lane == 0) alocY[t - t0] = Y;
+            };
+            int t = t0 + 1;
+            for (; t + PFW - 1 < t1; t += PFW) {
+#pragma unroll
+                for (int j = 0; j < PFW; ++j) {
+                    const double2 e = qe[j];
+                    qe[j] = EIc[(size_t)min(t + j + PFW, L) * C];
+                    fwd_one(t + j, e);
+                }
+            }
+            for (; t < t1; ++t) fwd_one(t, EIc[(size_t)t * C]);
+        }
+
+        // ============================ backward pass over [t0, t1) ============================
+        __threadfence_block();  // this wave's aloc / alocY rows are read back by all of its lanes
+        load_etr(true);
+        for (int i = lane; i < RTOT; i += 64) ring[i] = 0.0;
+        lds_wave_fence();
+        double Yb;
+        if (t1 == L) {  // beta_L = 1: v_L = E_L, scale reference sum = 1
+            if (g == 0 && hh == 0 && cval) {
+                const double v = EIc[(size_t)L * C].x;
+                ring[(size_t)(L % K) * RS + c] = v;
+                ring[(size_t)(L % K + K) * RS + c] = v;
+            }
+            prevsum = 1.0;
+            Yb = 0.0;
+        } else {
+            const int ci = t1 / Delta;
+            const double *ck = p.ckB + ((size_t)b * (N + 1) + ci) * ckstride;
+            for (int i = lane; i < KC; i += 64) {
+                const double v = ck[i];
+                const int sl = i / C, col = i % C;
+                ring[sl * RS + col] = v;
+                ring[(sl + K) * RS + col] = v;
+            }
+            prevsum = 0.0;
+            for (int i = 0; i < C; ++i) prevsum += ck[KC + i];
+            Yb = p.ckYB[(size_t)b * (N + 1) + ci];
+        }
+        lds_wave_fence();
+        slot = t1 % K;
+        double accD[NKW], accT[HC];
+#pragma unroll
+        for (int j = 0; j < NKW; ++j) accD[j] = 0.0;
+#pragma unroll
+        for (int i = 0; i < HC; ++i) accT[i] = 0.0;
+        double R = 0.0, sR = 0.0;
+        double kappa = exp((alocY[t1 - 1 - t0] + Yb) * LN2 - logZ);
+        {
+            double2 qe[PFW], qa[PFW];
+#pragma unroll
+            for (int j = 0; j < PFW; ++j) {
+                const int t = max(t1 - 1 - j, t0);
+                qe[j] = EIc[(size_t)t * C];
+                qa[j] = aloc[(size_t)(t - t0) * C + cc];
+            }
+            float *gout = p.grad_emis + ((size_t)b * p.T) * C + cc;
+            auto bwd_one = [&](const int t, const double2 e, const double2 aq) {
+                if (__builtin_expect(((t + 1) & Jm) == 0, 0)) {
+                    const int ex = safe_exponent(prevsum);
+                    Yb += (double)ex;
+                    const int jn = t / J;
+                    rescale(-(nbc[(size_t)jn * C] - nbc[(size_t)(jn + 1) * C]) - ex);
+                    kappa = exp((alocY[t - t0] + Yb) * LN2 - logZ);
+                }
+                const int ps = slot == 0 ? K - 1 : slot - 1;
+                const double ahat = cval ? aq.x : 0.0, qhat = cval ? aq.y : 0.0;
+                const double coef = qhat * kappa;
+                // S(c) = sum_k W[k,c] v_{t+k}(c); every product is also a duration marginal
+                const double *base = ring + (size_t)(ps + 1 + g) * RS + c;
+                double v[NKW];
+#pragma unroll
+                for (int j = 0; j < NKW; ++j) v[j] = base[j * GW * RS];
+                double a0 = 0.0, a1 = 0.0;
+#pragma unroll
+                for (int j = 0; j < NKW; j += 2) {
+                    const double p0 = wreg[j] * v[j], p1 = wreg[j + 1] * v[j + 1];
+                    a0 += p0;
+                    a1 += p1;
+                    accD[j] = fma(coef, p0, accD[j]);
+                    accD[j + 1] = fma(coef, p1, accD[j + 1]);
+                }
+                const double x = group_sum<CTP>(a0 + a1);
+                const double y = x * e.y;  // p_t(c)
+                yv[c] = y;
+                lds_wave_fence();
+                const double ak = ahat * kappa;
+                double z0 = 0.0, z1 = 0.0, ysum = 0.0;
+#pragma unroll
+                for (int i = 0; i < HC; i += 2) {
+                    const double2 vv = ys[i >> 1];
+                    z0 = fma(vv.x, Ereg[i], z0);
+                    z1 = fma(vv.y, Ereg[i + 1], z1);
+                    ysum += vv.x + vv.y;
+                    accT[i] = fma(ak, vv.x, accT[i]);
+                    accT[i + 1] = fma(ak, vv.y, accT[i + 1]);
+                }
+                double z = z0 + z1;
+                if (H == 2) {
+                    z = add_across_32(z);
+                    ysum = add_across_32(ysum);
+                }
+                prevsum = ysum;
+                const double q = z * e.x;  // v_t(c) = b_t(c) E_t(c)
+                double *rw = ring + (size_t)ps * RS + c;
+                rw[0] = q;
+                rw[(size_t)K * RS] = q;
+                lds_wave_fence();
+                slot = ps;
+                const double outv = coef * x;
+                const double inv = t >= 1 ? ak * z : 0.0;
+                if (g == 0 && hh == 0 && cval) gout[(size_t)t * C] = (float)R;
+                sR += R;
+                R += outv - inv;
+            };
+            int t = t1 - 1;
+            for (; t - (PFW - 1) >= t0; t -= PFW) {
+#pragma unroll
+                for (int j = 0; j < PFW; ++j) {
+                    const double2 e = qe[j], aq = qa[j];
+                    const int tn = max(t - j - PFW, t0);
+                    qe[j] = EIc[(size_t)tn * C];
+                    qa[j] = aloc[(size_t)(tn - t0) * C + cc];
+                    bwd_one(t - j, e, aq);
+                }
+            }
+            for (; t >= t0; --t) bwd_one(t, EIc[(size_t)t * C], aloc[(size_t)(t - t0) * C + cc]);
+        }
+        // ---- partials of this task
+        double *pD = p.partD + ((size_t)b * N + iv) * KC;
+#pragma unroll
+        for (int j = 0; j < NKW; ++j) {
+            const int k = 1 + g + j * GW;
+            if (cval && k <= K) pD[(size_t)(k - 1) * C + c] = accD[j];
+        }
+        double *pT = p.partTr + ((size_t)b * N + iv) * CC;
+#pragma unroll
+        for (int i = 0; i < HC; ++i) {
+            const int o = hh * HC + i;
+            const bool owner = H == 2 ? lane == hh * 32 + c : true;  // one lane per (label, half)
+            if (cval && owner && o < C) pT[(size_t)c * C + o] = accT[i];
+        }
+        if (lane < C) {
+            p.tot[((size_t)b * N + iv) * C + lane] = R;
+            p.sumR[((size_t)b * N + iv) * C + lane] = sR;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Finalisation (fixed-order reductions).
 // ---------------------------------------------------------------------------
 // carry[b,i,c] = sum_{i'<=i} tot[b,i',c];  mean[b,c] = (1/L) sum_u pm[b,u,c].  grid B.
@@ -1277,6 +1587,46 @@ int launch_scan(const Params &p, const Plan &pl, hipStream_t st, bool both)
     return check_launch();
 }
 
+// One wave per task when the duration strips fit the registers, else the generic kernel.
+template <int CT, int NKW>
+int launch_interval_wave(const Params &p, const Plan &pl, hipStream_t st)
+{
+    const size_t lds = wave_lds_doubles(p.K, pow2_ge8(CT), NKW) * sizeof(double);
+    if (lds > LDS_LIMIT) return 1;
+    if (hipFuncSetAttribute((const void *)k_interval_wave<CT, NKW>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+        return SEMICRF_ELAUNCH;
+    hipLaunchKernelGGL((k_interval_wave<CT, NKW>), dim3(pl.nslot), dim3(64), lds, st, p);
+    return check_launch();
+}
+
+template <int CT>
+int launch_interval_ct(const Params &p, const Plan &pl, hipStream_t st)
+{
+    constexpr int GW = 64 / pow2_ge8(CT);
+    const int per_lane = (p.K + GW - 1) / GW;
+    // longer strips (or C > 32) would not fit the register file of one wave
+    if (per_lane <= 16) return launch_interval_wave<CT, 16>(p, pl, st);
+    if (per_lane <= 32) return launch_interval_wave<CT, 32>(p, pl, st);
+    return 1;
+}
+
+int launch_interval(const Params &p, const Plan &pl, hipStream_t st)
+{
+    const int C = p.C;
+    int rc = 1;
+    if (C <= 8) rc = launch_interval_ct<8>(p, pl, st);
+    else if (C <= 16) rc = launch_interval_ct<16>(p, pl, st);
+    else if (C <= 24) rc = launch_interval_ct<24>(p, pl, st);
+    else if (C <= 32) rc = launch_interval_ct<32>(p, pl, st);
+    if (rc != 1) return rc;
+    if (hipFuncSetAttribute((const void *)k_interval, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)pl.lds_interval) != hipSuccess)
+        return SEMICRF_ELAUNCH;
+    hipLaunchKernelGGL(k_interval, dim3(pl.nslot), dim3(NT), pl.lds_interval, st, p);
+    return check_launch();
+}
+
 // Optional per-stage timing: events are recorded on the caller's stream around
 // the four stages (prefix sums, scans, intervals, finalisation).
 struct StageTimer {
@@ -1315,10 +1665,8 @@ int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hi
     T.mark();
     rc = check_launch();
     if (rc != SEMICRF_OK || mode == 1) return rc;
-    if (hipFuncSetAttribute((const void *)k_interval, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)pl.lds_interval) != hipSuccess)
-        return SEMICRF_ELAUNCH;
-    hipLaunchKernelGGL(k_interval, dim3(pl.nslot), dim3(NT), pl.lds_interval, st, p);
+    rc = launch_interval(p, pl, st);
+    if (rc != SEMICRF_OK) return rc;
     T.mark();
     hipLaunchKernelGGL(k_fin_seq, dim3(p.B), dim3(64), 0, st, p);
     {
