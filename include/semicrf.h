@@ -65,7 +65,7 @@ const char *semicrf_strerror(int status);
 /*
  * Host only, pure.  Bytes of device workspace the calls below need for these
  * sizes.  ckpt_interval = 0 selects the automatic interval
- * ceil(sqrt(T*K*B/256)) clamped to [1,T] (the paper's sqrt(T*K) spacing scaled
+ * ceil(sqrt(T*K*B/256)), rounded up to a multiple of 8 and clamped to [1,T] (the paper's sqrt(T*K) spacing scaled
  * so that checkpoint memory and per-interval recompute buffers balance when the
  * B*T/interval recompute tasks are spread over the 256 compute units).
  * want_grad = 0 sizes for semicrf_logz_fwd / semicrf_cum_scores only.

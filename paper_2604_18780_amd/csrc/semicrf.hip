@@ -35,6 +35,7 @@
 #include <float.h>
 #include <math.h>
 #include <stdint.h>
+#include <type_traits>
 
 #include "semicrf.h"
 
@@ -193,33 +194,54 @@ __global__ __launch_bounds__(NT) void k_colsum(Params p)
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(NT) void k_prep_seq(Params p)
 {
-    __shared__ double numax[NT];
+    // The chunks are split into G = NT/C contiguous ranges, one per thread group; range sums
+    // are combined in range order (a fixed order for a given problem).
+    __shared__ double gsum[NT];
+    __shared__ double red[NT];
+    __shared__ double nu_s[NT];
     const int b = blockIdx.x, tid = threadIdx.x;
-    const int C = p.C, L = seq_len(p, b);
-    double mynu = 0.0;
+    const int C = p.C, L = seq_len(p, b), NCH = p.NCH;
+    const int G = NT / C;
+    const int g = tid / C, c = tid % C;
+    const bool act = g < G;
+    const int per = (NCH + G - 1) / G;
+    const int c0 = min(g * per, NCH), c1 = min(c0 + per, NCH);
+    double *cs = p.chsum + ((size_t)b * NCH) * C + c;
+    double loc = 0.0;
+    if (act)
+        for (int ch = c0; ch < c1; ++ch) loc += cs[(size_t)ch * C];
+    gsum[tid] = loc;
+    __syncthreads();
     if (tid < C) {
-        double *cs = p.chsum + ((size_t)b * p.NCH) * C + tid;
         double total = 0.0;
-        for (int ch = 0; ch < p.NCH; ++ch) total += cs[(size_t)ch * C];
-        mynu = (p.center && L > 0) ? total / (double)L : 0.0;
-        p.nu[(size_t)b * C + tid] = mynu;
-        double pref = 0.0;  // raw prefix sum at the chunk start
-        for (int ch = 0; ch < p.NCH; ++ch) {
-            double s = cs[(size_t)ch * C];
-            int u0 = ch * PREP_CH;
-            int nvalid = min(u0, L);
+        for (int gg = 0; gg < G; ++gg) total += gsum[gg * C + tid];
+        const double nu = (p.center && L > 0) ? total / (double)L : 0.0;
+        p.nu[(size_t)b * C + tid] = nu;
+        nu_s[tid] = nu;
+    }
+    __syncthreads();
+    if (act) {
+        const double mynu = nu_s[c];
+        double pref = 0.0;  // raw prefix sum at the start of this range
+        for (int gg = 0; gg < g; ++gg) pref += gsum[gg * C + c];
+        for (int ch = c0; ch < c1; ++ch) {
+            const double sum = cs[(size_t)ch * C];
+            const int nvalid = min(ch * PREP_CH, L);
             cs[(size_t)ch * C] = pref - (double)nvalid * mynu;
-            pref += s;
+            pref += sum;
         }
     }
-    numax[tid] = tid < C ? fabs(mynu) : 0.0;
+    // bound on |f - nu|
+    double fm = 0.0;
+    for (int ch = tid; ch < NCH; ch += NT) fm = fmax(fm, p.chmax[(size_t)b * NCH + ch]);
+    red[tid] = fm;
     __syncthreads();
     if (tid == 0) {
-        double fm = 0.0;
-        for (int ch = 0; ch < p.NCH; ++ch) fm = fmax(fm, p.chmax[(size_t)b * p.NCH + ch]);
+        fm = 0.0;
+        for (int i = 0; i < NT; ++i) fm = fmax(fm, red[i]);
         double nm = 0.0;
-        for (int i = 0; i < C; ++i) nm = fmax(nm, numax[i]);
-        fm += nm;  // bound on |f - nu|
+        for (int i = 0; i < C; ++i) nm = fmax(nm, fabs(nu_s[i]));
+        fm += nm;
         double dmax = p.tabmax[0], tmax = p.tabmax[1];
         double grow = fm + fmax(dmax, 0.0) + fmax(tmax, 0.0) + log((double)p.K * (double)C);
         double shrink = fm + fmax(-dmax, 0.0) + fmax(-tmax, 0.0);
@@ -765,20 +787,23 @@ __device__ __forceinline__ void scan_fast_body(const Params &p, double *lds, con
         // All 64 lanes run the same instruction stream without masks: lanes whose label
         // index is >= C carry zeros (W1 = W2 = 0, Ereg = 0, their partials are 0).
         const double2 *EIc = EI + cc;  // this lane's column; rows are addressed by a uniform offset
-        double2 qe[PF];                // emission factors of the next PF steps
+        double2 qe[PF];                // emission factors of the next PF steps (aligned groups)
 #pragma unroll
-        for (int j = 0; j < PF; ++j) {
-            int n = 1 + j;
-            if (n > L) n = L;
-            qe[j] = EIc[(size_t)(BWD ? L - n : n) * C];
-        }
+        for (int j = 0; j < PF; ++j) qe[j] = make_double2(0.0, 0.0);
         // Nothing lies k >= 3 behind steps 1 and 2, so their partials are the zeros
         // already in `part`.  psum is the partial of the step about to run.
         double psum = 0.0, zlast = 1.0;
         const double2 *ys = (const double2 *)__builtin_assume_aligned(yv + hh * HC, 16);
-        auto tip_step = [&](const int n, const double2 e) {
+        // `kind` says which rare events a step has to look for.  Steps run in groups of 8
+        // aligned on t = 0 mod 8 whenever J and Delta are multiples of 8: then a scaling
+        // boundary can only precede the first step of a group and its scale reference is
+        // only needed after the last one, and most steps carry no branch at all.
+        //   0: any step (all checks)      1: first of a group
+        //   2: middle of a group          3: last of a group
+        auto tip_step = [&](auto kind_tag, const int n, const double2 e) {
+            constexpr int kind = decltype(kind_tag)::value;
             const int t = BWD ? L - n : n;
-            const bool boundary = BWD ? ((t + 1) & Jm) == 0 : (t & Jm) == 0;
+            const bool boundary = kind == 0 || kind == 1 ? (BWD ? ((t + 1) & Jm) == 0 : (t & Jm) == 0) : false;
             if (__builtin_expect(boundary, 0)) {  // uniform: rescale ring, tip registers, pending partials
                 const int ex = safe_exponent(prevsum);
                 Y += (double)ex;
@@ -817,27 +842,74 @@ __device__ __forceinline__ void scan_fast_body(const Params &p, double *lds, con
             for (int w = 1; w < NHR; ++w) pn += pv[w];
             psum = pn;
             zlast = z;
-            const bool want_sum = BWD ? (t & Jm) == 0 : ((t + 1) & Jm) == 0;
+            const bool want_sum = kind == 0 || kind == 3 ? (BWD ? (t & Jm) == 0 : ((t + 1) & Jm) == 0) : false;
             if (__builtin_expect(want_sum, 0)) {  // uniform: scale reference for the boundary that follows
                 double sum = 0.0;
                 for (int i = 0; i < CT; ++i) sum += yv[i];
                 prevsum = sum;
             }
             lds_barrier();
-            after_step(t);
+            if (kind == 0) {
+                after_step(t);
+            } else if (BWD ? kind == 3 : kind == 1) {
+                // the only step of a group that can sit on a checkpoint position (t = 0 mod 8);
+                // dleft is brought up to date for the whole group by the caller
+                const int due = BWD ? 8 : 1;
+                if (__builtin_expect(dleft == due, 0)) {
+                    dleft = Delta + due;
+                    if (p.want_grad && t > 0) {
+                        write_checkpoint(t / Delta);
+                        lds_barrier();
+                    }
+                }
+            }
         };
+        using K0 = std::integral_constant<int, 0>;
+        using K1 = std::integral_constant<int, 1>;
+        using K2 = std::integral_constant<int, 2>;
+        using K3 = std::integral_constant<int, 3>;
+        static_assert(PF == 8, "the aligned groups are 8 steps long");
+        const bool grouped = (J % 8) == 0 && (Delta % 8) == 0;
         int n = 1;
-        for (; n + PF - 1 <= L; n += PF) {
+        if (grouped) {
+            // single steps until the next position is the first of an aligned group
+            while (n <= L && ((BWD ? L - n : n) & 7) != (BWD ? 7 : 0)) {
+                tip_step(K0{}, n, EIc[(size_t)(BWD ? L - n : n) * C]);
+                ++n;
+            }
+            if (n + 7 <= L) {
 #pragma unroll
-            for (int j = 0; j < PF; ++j) {
-                const double2 e = qe[j];
-                int n2 = n + j + PF;
-                if (n2 > L) n2 = L;
-                qe[j] = EIc[__builtin_amdgcn_readfirstlane((BWD ? L - n2 : n2) * C)];
-                tip_step(n + j, e);
+                for (int j = 0; j < PF; ++j) qe[j] = EIc[(size_t)(BWD ? L - (n + j) : n + j) * C];
+            }
+            for (; n + 7 <= L; n += 8) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const double2 e = qe[j];
+                    int n2 = n + j + 8;
+                    if (n2 > L) n2 = L;
+                    qe[j] = EIc[__builtin_amdgcn_readfirstlane((BWD ? L - n2 : n2) * C)];
+                    if (j == 0) tip_step(K1{}, n + j, e);
+                    else if (j == 7) tip_step(K3{}, n + j, e);
+                    else tip_step(K2{}, n + j, e);
+                }
+                dleft -= 8;
+            }
+        } else if (n + 7 <= L) {
+            // J or Delta is not a multiple of 8: same prefetch queue, every step checks everything
+#pragma unroll
+            for (int j = 0; j < PF; ++j) qe[j] = EIc[(size_t)(BWD ? L - (n + j) : n + j) * C];
+            for (; n + 7 <= L; n += 8) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const double2 e = qe[j];
+                    int n2 = n + j + 8;
+                    if (n2 > L) n2 = L;
+                    qe[j] = EIc[__builtin_amdgcn_readfirstlane((BWD ? L - n2 : n2) * C)];
+                    tip_step(K0{}, n + j, e);
+                }
             }
         }
-        for (; n <= L; ++n) tip_step(n, EIc[(size_t)(BWD ? L - n : n) * C]);
+        for (; n <= L; ++n) tip_step(K0{}, n, EIc[(size_t)(BWD ? L - n : n) * C]);
         if (BWD && L > 0) yv[c] = zlast;  // beta_0: diagnostic partition function
         lds_wave_fence();
         if (tid == 0) {
@@ -1363,22 +1435,43 @@ __global__ __launch_bounds__(64) void k_interval_wave(Params p)
 // ---------------------------------------------------------------------------
 // Finalisation (fixed-order reductions).
 // ---------------------------------------------------------------------------
-// carry[b,i,c] = sum_{i'<=i} tot[b,i',c];  mean[b,c] = (1/L) sum_u pm[b,u,c].  grid B.
-__global__ void k_fin_seq(Params p)
+// carry[b,i,c] = sum_{i'<=i} tot[b,i',c];  mean[b,c] = (1/L) sum_u pm[b,u,c].  grid B, NT threads:
+// the intervals are split into G = NT/C contiguous chunks, one per thread group; chunk sums are
+// combined in chunk order, so the result does not depend on the launch shape.
+__global__ __launch_bounds__(NT) void k_fin_seq(Params p)
 {
-    const int b = blockIdx.x, C = p.C, N = p.N;
+    __shared__ double gsum[NT];
+    __shared__ double gtot[NT];
+    const int b = blockIdx.x, C = p.C, N = p.N, tid = threadIdx.x;
     const int L = p.hdr[b].L;
     const int nint = (L + p.Delta - 1) / p.Delta;
-    for (int c = threadIdx.x; c < C; c += blockDim.x) {
-        double run = 0.0, total = 0.0;
-        for (int i = 0; i < nint; ++i) {
+    const int G = NT / C;
+    const int g = tid / C, c = tid % C;
+    const int per = (nint + G - 1) / G;
+    const int i0 = min(g * per, nint), i1 = min(i0 + per, nint);
+    const bool act = g < G;
+    double loc = 0.0;
+    if (act)
+        for (int i = i0; i < i1; ++i) loc += p.tot[((size_t)b * N + i) * C + c];
+    gsum[tid] = loc;
+    __syncthreads();
+    double run = 0.0, total = 0.0;
+    if (act) {
+        for (int gg = 0; gg < g; ++gg) run += gsum[gg * C + c];
+        for (int i = i0; i < i1; ++i) {
             const size_t o = ((size_t)b * N + i) * C + c;
             run += p.tot[o];
             p.carry[o] = run;
             const int n = min(p.Delta, L - i * p.Delta);
             total += (double)n * run - p.sumR[o];
         }
-        p.mean[(size_t)b * C + c] = (p.center && L > 0) ? total / (double)L : 0.0;
+    }
+    gtot[tid] = total;
+    __syncthreads();
+    if (tid < C) {
+        double t = 0.0;
+        for (int gg = 0; gg < G; ++gg) t += gtot[gg * C + tid];
+        p.mean[(size_t)b * C + tid] = (p.center && L > 0) ? t / (double)L : 0.0;
     }
 }
 
@@ -1407,28 +1500,42 @@ __global__ __launch_bounds__(NT) void k_fin_emis(Params p)
 }
 
 // grad_trans[c',c] = Etr[c',c] * sum_b w_b sum_i partTr;  grad_dur[k,c] = sum_b w_b sum_i partD.
+// One workgroup per 32 outputs; 8 thread groups take the intervals i = g, g+8, ... and their
+// sums are combined in group order (fixed order for a given problem).
 __global__ __launch_bounds__(NT) void k_fin_params(Params p)
 {
-    const int C = p.C, CC = C * C, KC = p.K * C, N = p.N;
-    const int idx = blockIdx.x * NT + threadIdx.x;
-    if (idx >= CC + KC) return;
+    __shared__ double red[NT];
+    const int C = p.C, CC = C * C, KC = p.K * C, N = p.N, tid = threadIdx.x;
+    const int o = tid & 31, g = tid >> 5;
+    const int idx = blockIdx.x * 32 + o;
+    const bool ok = idx < CC + KC;
     double acc = 0.0;
-    for (int b = 0; b < p.B; ++b) {
-        const int L = p.hdr[b].L;
-        const int nint = (L + p.Delta - 1) / p.Delta;
-        const double w = p.grad_logz ? (double)p.grad_logz[b] : 1.0;
-        double s = 0.0;
-        if (idx < CC) {
-            const double *q = p.partTr + ((size_t)b * N) * CC + idx;
-            for (int i = 0; i < nint; ++i) s += q[(size_t)i * CC];
-        } else {
-            const double *q = p.partD + ((size_t)b * N) * KC + (idx - CC);
-            for (int i = 0; i < nint; ++i) s += q[(size_t)i * KC];
+    if (ok) {
+        for (int b = 0; b < p.B; ++b) {
+            const int L = p.hdr[b].L;
+            const int nint = (L + p.Delta - 1) / p.Delta;
+            const double w = p.grad_logz ? (double)p.grad_logz[b] : 1.0;
+            const size_t stride = idx < CC ? (size_t)CC : (size_t)KC;
+            const double *q = idx < CC ? p.partTr + ((size_t)b * N) * CC + idx
+                                       : p.partD + ((size_t)b * N) * KC + (idx - CC);
+            double s0 = 0.0, s1 = 0.0;
+            int i = g;
+            for (; i + 8 < nint; i += 16) {
+                s0 += q[(size_t)i * stride];
+                s1 += q[(size_t)(i + 8) * stride];
+            }
+            if (i < nint) s0 += q[(size_t)i * stride];
+            acc = fma(w, s0 + s1, acc);
         }
-        acc = fma(w, s, acc);
     }
-    if (idx < CC) p.grad_trans[idx] = (float)(acc * p.Etr[idx]);
-    else p.grad_dur[idx - CC] = (float)acc;
+    red[tid] = acc;
+    __syncthreads();
+    if (ok && g == 0) {
+        double t = 0.0;
+        for (int gg = 0; gg < 8; ++gg) t += red[gg * 32 + o];
+        if (idx < CC) p.grad_trans[idx] = (float)(t * p.Etr[idx]);
+        else p.grad_dur[idx - CC] = (float)t;
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -1440,8 +1547,10 @@ int auto_interval(int B, int T, int K)
 {
     double d = ceil(sqrt((double)T * (double)K * (double)B / 256.0));
     if (d < 1.0) d = 1.0;
-    if (d > (double)T) d = (double)T;
-    return (int)d;
+    int di = (int)d;
+    if (di >= 8) di = (di + 7) & ~7;  // lets the scan run its steps in aligned groups of 8
+    if (di > T) di = T;
+    return di;
 }
 
 struct Plan {
@@ -1668,7 +1777,7 @@ int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hi
     rc = launch_interval(p, pl, st);
     if (rc != SEMICRF_OK) return rc;
     T.mark();
-    hipLaunchKernelGGL(k_fin_seq, dim3(p.B), dim3(64), 0, st, p);
+    hipLaunchKernelGGL(k_fin_seq, dim3(p.B), dim3(NT), 0, st, p);
     {
         size_t n = (size_t)p.B * p.T * p.C;
         size_t blocks = (n + NT - 1) / NT;
@@ -1677,7 +1786,7 @@ int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hi
     }
     {
         int n = p.C * p.C + p.K * p.C;
-        hipLaunchKernelGGL(k_fin_params, dim3((n + NT - 1) / NT), dim3(NT), 0, st, p);
+        hipLaunchKernelGGL(k_fin_params, dim3((n + 31) / 32), dim3(NT), 0, st, p);
     }
     T.mark();
     return check_launch();
