@@ -520,14 +520,18 @@ __global__ __launch_bounds__(NT) void k_scan(Params p, int both)
 // instruction per 8 clocks on this hardware, so the time of a step is the number
 // of instructions on the dependent chain; the kernel is organised to keep that
 // number small.  One workgroup per (sequence, direction):
-//   wave 0 ("tip") owns the dependent chain of a step: the k = 1 and k = 2 terms
-//     (its last two ring entries stay in registers), the emission factor, the
+//   wave 0 ("tip") owns the dependent chain of a step: the k = 1, 2, 3 terms
+//     (its last three ring entries stay in registers), the emission factor, the
 //     transition product (its part of the Etr row/column lives in registers; for
 //     C <= 32 the two 32-lane halves of the wave each take half of the source
 //     labels and are combined with one lane-swap) and the ring write;
-//   waves 1.. ("helpers") pre-reduce, two steps ahead, the k >= 3 terms of a
+//   waves 1.. ("helpers") pre-reduce, two steps ahead, the k >= 4 terms of a
 //     later position from the LDS ring and leave one partial per wave and label;
-//     the tip adds them in wave order one step before it needs them.
+//     the tip adds them in wave order one step before it needs them.  Because the
+//     helpers never touch the entry the tip wrote in the step just finished, the
+//     tip does not have to wait for its ring write before the step barrier: the
+//     write is known to have landed one barrier later (LDS serves a wave in order
+//     and the tip has since waited on younger reads).
 // The LDS ring is stored twice (slots s and s+K) with a compile-time row stride,
 // so a helper lane reads its NKL consecutive durations at immediate offsets from
 // one base address, without wrap-around arithmetic.
@@ -550,6 +554,13 @@ __device__ __forceinline__ void lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// The tip's end-of-step barrier: no s_waitcnt.  The only LDS write of the step that
+// other waves read (the ring entry) is not read by them before the NEXT barrier.
+__device__ __forceinline__ void tip_step_barrier()
+{
+    asm volatile("s_barrier" ::: "memory");
 }
 
 // orders LDS accesses of one wave (LDS executes a wave's instructions in order)
@@ -605,7 +616,7 @@ struct FastGeom {
 __host__ __device__ inline FastGeom fast_geom(int K, int CTP, int NH)
 {
     const int GW = 64 / CTP;
-    const int kmaxpad = 2 + NH * GW * NKL;  // largest duration index any helper lane touches
+    const int kmaxpad = 3 + NH * GW * NKL;  // largest duration index any helper lane touches
     FastGeom g;
     g.XP = kmaxpad > K ? kmaxpad - K : 0;
     g.RSLOTS = 2 * K + g.XP;
@@ -656,11 +667,11 @@ __device__ __forceinline__ void scan_fast_body(const Params &p, double *lds, con
     double treg[NREG];
     double *const Ereg = treg;
     double *const wreg = treg;
-    double W1 = 0.0, W2 = 0.0;
+    double W1 = 0.0, W2 = 0.0, W3 = 0.0;
     const int g = lane / CTP;
     // helper lane (wave, g): durations k0, k0 + GW, k0 + 2 GW, ... so that the 64 lanes of a
     // wave read 64 consecutive doubles of the ring for every term (no LDS bank conflicts)
-    const int k0 = 3 + (wave - 1) * GW * NKL + g;
+    const int k0 = 4 + (wave - 1) * GW * NKL + g;
 #pragma unroll
     for (int i = 0; i < NREG; ++i) treg[i] = 0.0;
     if (tip) {
@@ -672,6 +683,7 @@ __device__ __forceinline__ void scan_fast_body(const Params &p, double *lds, con
             }
             W1 = p.W[c];
             if (K >= 2) W2 = p.W[(size_t)C + c];
+            if (K >= 3) W3 = p.W[(size_t)2 * C + c];
         }
     } else if (cval) {
 #pragma unroll
@@ -690,7 +702,7 @@ __device__ __forceinline__ void scan_fast_body(const Params &p, double *lds, con
     lds_barrier();
 
     // ---- first position (t = 0 forward, t = L backward)
-    double q1 = 0.0, q2 = 0.0, Y = 0.0, prevsum = BWD ? 1.0 : (double)C;
+    double q1 = 0.0, q2 = 0.0, q3 = 0.0, Y = 0.0, prevsum = BWD ? 1.0 : (double)C;
     int slot = BWD ? L % K : 0;  // ring slot (lower copy) of the position just processed
     if (tip && cval) {
         if (!BWD) {
@@ -730,8 +742,8 @@ __device__ __forceinline__ void scan_fast_body(const Params &p, double *lds, con
     };
     if (!BWD && p.want_grad) write_checkpoint(0);
 
-    // helper: partial of sum_{k>=3} W[k,c] ring[pos -/+ k] over this lane's NKL consecutive
-    // durations, for the position whose lower-copy slot is ps.
+    // helper: partial of sum_{k>=4} W[k,c] ring[pos -/+ k] over this lane's NKL durations,
+    // for the position whose lower-copy slot is ps.
     auto helper_partial = [&](int ps, int buf) {
         const double *base = BWD ? ring + (size_t)(ps + k0) * RS + c
                                  : ring + (size_t)(XPf + ps + K - k0 - (NKL - 1) * GW) * RS + c;
@@ -777,6 +789,7 @@ __device__ __forceinline__ void scan_fast_body(const Params &p, double *lds, con
         if (__builtin_expect(--dleft == 0, 0)) {
             dleft = Delta;
             if (p.want_grad && t > 0) {
+                lds_barrier();  // the tip's newest ring entry has landed (its step barrier does not wait)
                 write_checkpoint(t / Delta);
                 lds_barrier();
             }
@@ -790,7 +803,7 @@ __device__ __forceinline__ void scan_fast_body(const Params &p, double *lds, con
         double2 qe[PF];                // emission factors of the next PF steps (aligned groups)
 #pragma unroll
         for (int j = 0; j < PF; ++j) qe[j] = make_double2(0.0, 0.0);
-        // Nothing lies k >= 3 behind steps 1 and 2, so their partials are the zeros
+        // Nothing lies k >= 4 behind steps 1 and 2, so their partials are the zeros
         // already in `part`.  psum is the partial of the step about to run.
         double psum = 0.0, zlast = 1.0;
         const double2 *ys = (const double2 *)__builtin_assume_aligned(yv + hh * HC, 16);
@@ -811,6 +824,7 @@ __device__ __forceinline__ void scan_fast_body(const Params &p, double *lds, con
                 sc[c] = sft;
                 q1 = fmin(ldexp(q1, sft), DBL_MAX);
                 q2 = fmin(ldexp(q2, sft), DBL_MAX);
+                q3 = fmin(ldexp(q3, sft), DBL_MAX);
                 psum = fmin(ldexp(psum, sft), DBL_MAX);
                 rescale_ring((n + 1) & 1);
             }
@@ -820,7 +834,7 @@ __device__ __forceinline__ void scan_fast_body(const Params &p, double *lds, con
             double pv[NHR];
 #pragma unroll
             for (int w = 0; w < NHR; ++w) pv[w] = pp[w * CTP];
-            const double x = fma(W1, q1, fma(W2, q2, psum));
+            const double x = fma(W1, q1, fma(W2, q2, fma(W3, q3, psum)));
             yv[c] = x * (BWD ? e.y : e.x);
             lds_wave_fence();
             double z0 = 0.0, z1 = 0.0;
@@ -832,6 +846,7 @@ __device__ __forceinline__ void scan_fast_body(const Params &p, double *lds, con
             }
             double z = z0 + z1;
             if (H == 2) z = add_across_32(z);
+            q3 = q2;
             q2 = q1;
             q1 = z * (BWD ? e.x : e.y);
             double *rw = ring + (size_t)(XPf + slot) * RS + c;
@@ -848,7 +863,9 @@ __device__ __forceinline__ void scan_fast_body(const Params &p, double *lds, con
                 for (int i = 0; i < CT; ++i) sum += yv[i];
                 prevsum = sum;
             }
-            lds_barrier();
+            // no wait for the ring write here (see the kernel comment); the tip's other LDS
+            // traffic of this step has been consumed by itself already
+            tip_step_barrier();
             if (kind == 0) {
                 after_step(t);
             } else if (BWD ? kind == 3 : kind == 1) {
@@ -858,6 +875,7 @@ __device__ __forceinline__ void scan_fast_body(const Params &p, double *lds, con
                 if (__builtin_expect(dleft == due, 0)) {
                     dleft = Delta + due;
                     if (p.want_grad && t > 0) {
+                        lds_barrier();
                         write_checkpoint(t / Delta);
                         lds_barrier();
                     }
@@ -1671,7 +1689,7 @@ template <int CT>
 int launch_scan_ct(const Params &p, hipStream_t st, bool both)
 {
     constexpr int GW = 64 / pow2_ge8(CT);
-    const int terms = p.K > 2 ? p.K - 2 : 0;  // durations k >= 3 go to the helpers
+    const int terms = p.K > 3 ? p.K - 3 : 0;  // durations k >= 4 go to the helpers
     if (terms <= 1 * GW * NKL) return launch_scan_fast<CT, 1>(p, st, both);
     if (terms <= 2 * GW * NKL) return launch_scan_fast<CT, 2>(p, st, both);
     if (CT < 64 && terms <= 4 * GW * NKL)
