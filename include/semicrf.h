@@ -56,6 +56,18 @@ typedef enum {
 /* flags bit 0: subtract the per-sequence emission baseline nu[b,c] before the
  * prefix sum (Eq. 1).  Without it S is the raw prefix sum. */
 #define SEMICRF_CENTER 1u
+/* flags bit 1: run the forward scan of Algorithm 1 and the backward scan of Algorithm 3
+ * strictly sequentially.  By default both are run chunk-parallel: every checkpoint interval
+ * is scanned as an independent task that first warms its ring up over the max(4K,32)
+ * positions before the interval, starting from the state of a sequence that begins there.
+ * The state each task reaches at its end is then compared, entry by entry and up to the
+ * common scale factor, with the warmed-up state its neighbour started from; a (sequence,
+ * direction) is accepted only if every one of its boundaries agrees to 1e-10 (relative),
+ * which bounds the deviation from the sequential scan by 2e-10 per boundary crossed.  A
+ * rejected (sequence, direction) is rescanned sequentially inside the same call, so the
+ * results are those of the sequential scan either way; only the time differs.
+ * semicrf_scan_report tells which happened. */
+#define SEMICRF_SEQUENTIAL_SCAN 2u
 
 int semicrf_version(void);
 
@@ -86,7 +98,8 @@ int semicrf_cum_scores(const float *emis, const int32_t *lengths, int B, int T, 
 
 /*
  * Algorithm 1 (streaming forward scan): logz[b] = log partition function of
- * sequence b.  logz [B] float.  The result does not depend on ckpt_interval.
+ * sequence b.  logz [B] float.  The result does not depend on ckpt_interval (beyond
+ * rounding order and the 1e-10 acceptance bound of the chunk-parallel scan).
  */
 int semicrf_logz_fwd(const float *emis, const int32_t *lengths, const float *trans,
                      const float *dur, int B, int T, int K, int C, int ckpt_interval,
@@ -133,6 +146,23 @@ int semicrf_fwd_bwd_profiled(const float *emis, const int32_t *lengths, const fl
                              size_t workspace_bytes, float *logz, float *grad_emis,
                              float *grad_trans, float *grad_dur, float *pos_marg, void *stream,
                              void *const *stage_events);
+
+/*
+ * Diagnostics of the scans of the LAST semicrf_logz_fwd / semicrf_fwd_bwd call that used
+ * this workspace with these sizes (same B, T, K, C, ckpt_interval and want_grad: they
+ * locate the fields in the workspace).  Enqueued on `stream` after that call.
+ *   accepted [B,2] int32 device, or NULL: [b,0] forward scan (Algorithm 1), [b,1] backward
+ *             scan (Algorithm 3): 1 = the chunk-parallel result was verified and used,
+ *             0 = the sequential scan computed it (flag SEMICRF_SEQUENTIAL_SCAN, sizes the
+ *             chunk-parallel kernels do not cover, a direction that call did not run, or
+ *             a boundary that did not agree).
+ *   mismatch [B,2] double device, or NULL: largest relative disagreement over the chunk
+ *             boundaries of that scan; -1 where the chunk-parallel scan was not attempted.
+ * At least one of the two must be given.
+ */
+int semicrf_scan_report(const void *workspace, size_t workspace_bytes, int B, int T, int K, int C,
+                        int ckpt_interval, int want_grad, int32_t *accepted, double *mismatch,
+                        void *stream);
 
 #ifdef __cplusplus
 }

@@ -16,8 +16,10 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsemicrf.so")
 EXPORTS = ("semicrf_version", "semicrf_strerror", "semicrf_workspace_bytes",
-           "semicrf_cum_scores", "semicrf_logz_fwd", "semicrf_fwd_bwd", "semicrf_fwd_bwd_profiled")
+           "semicrf_cum_scores", "semicrf_logz_fwd", "semicrf_fwd_bwd", "semicrf_fwd_bwd_profiled",
+           "semicrf_scan_report")
 SEMICRF_CENTER = 1
+SEMICRF_SEQUENTIAL_SCAN = 2
 _lib = None
 
 
@@ -53,6 +55,8 @@ def load():
                                     vp, vp, vp, vp, vp, vp]
     lib.semicrf_fwd_bwd_profiled.restype = ci
     lib.semicrf_fwd_bwd_profiled.argtypes = lib.semicrf_fwd_bwd.argtypes + [ctypes.POINTER(vp)]
+    lib.semicrf_scan_report.restype = ci
+    lib.semicrf_scan_report.argtypes = [vp, sz, ci, ci, ci, ci, ci, ci, vp, vp, vp]
     _lib = lib
     return lib
 
@@ -147,6 +151,16 @@ def semicrf_fwd_bwd(emis, lengths, trans, dur, grad_logz=None, ckpt_interval=0,
                                   _ptr(g_t, torch.float32), _ptr(g_d, torch.float32),
                                   _ptr(pm, torch.float32), _stream()))
     return logz, g_e, g_t, g_d, pm
+
+
+def semicrf_scan_report(workspace, B, T, K, C, ckpt_interval=0, want_grad=True):
+    """Returns (accepted [B,2] int32, mismatch [B,2] float64) of the last call on `workspace`."""
+    acc = torch.empty((B, 2), dtype=torch.int32, device=workspace.device)
+    mis = torch.empty((B, 2), dtype=torch.float64, device=workspace.device)
+    _check(load().semicrf_scan_report(workspace.data_ptr(), workspace.numel(), B, T, K, C,
+                                      ckpt_interval, int(bool(want_grad)), acc.data_ptr(),
+                                      mis.data_ptr(), _stream()))
+    return acc, mis
 
 
 _hip = None

@@ -35,6 +35,7 @@
 #include <float.h>
 #include <math.h>
 #include <stdint.h>
+#include <stdlib.h>
 #include <type_traits>
 
 #include "semicrf.h"
@@ -87,6 +88,16 @@ struct Params {
     double *ckB;        // [B][N+1][K*C + C]
     double *ckYA;       // [B][N+1]
     double *ckYB;       // [B][N+1]
+    // chunk-parallel scan: states reached at the END of a chunk (compared with the next
+    // chunk's warm-up state), their scales, per-boundary log2 scale ratios and mismatches
+    double *ckA2;       // [B][N+1][K*C + C]
+    double *ckB2;       // [B][N+1][K*C + C]
+    double *ckYA2;      // [B][N+1]
+    double *ckYB2;      // [B][N+1]
+    double *spec_lr;    // [B][2][N+1]
+    double *spec_err;   // [B][2][N+1]
+    int *spec_ok;       // [B][2]  1: the chunk-parallel scan of (sequence, direction) was accepted
+    int spec;           // chunk-parallel scan enabled for this call
     double *aloc;       // [nslot][Delta][2C]
     double *alocY;      // [nslot][Delta]
     double *partD;      // [B][N][K][C]
@@ -418,6 +429,7 @@ __global__ __launch_bounds__(NT) void k_scan(Params p, int both)
     const int tid = threadIdx.x;
     const int b = both ? (int)(blockIdx.x >> 1) : (int)blockIdx.x;
     const int dir = both ? (int)(blockIdx.x & 1) : 0;
+    if (p.spec && p.spec_ok[b * 2 + dir]) return;  // the chunk-parallel scan was accepted
     const int K = p.K, C = p.C, KC = K * C, CP1 = C | 1;
     const int G = min(NT / C, K);
     const Lds l = carve(lds_raw, K, C, G, false);
@@ -970,6 +982,7 @@ __global__ __launch_bounds__(CT == 64 ? 64 * (NHR + 1) : 320) void k_scan_fast(P
     extern __shared__ double lds_raw[];
     const int b = both ? (int)(blockIdx.x >> 1) : (int)blockIdx.x;
     const int dir = both ? (int)(blockIdx.x & 1) : 0;
+    if (p.spec && p.spec_ok[b * 2 + dir]) return;  // the chunk-parallel scan was accepted
     if (dir == 0) scan_fast_body<CT, NHR, false>(p, lds_raw, b);
     else scan_fast_body<CT, NHR, true>(p, lds_raw, b);
 }
@@ -1451,6 +1464,343 @@ __global__ __launch_bounds__(64) void k_interval_wave(Params p)
 }
 
 // ---------------------------------------------------------------------------
+// Chunk-parallel scan.  A sequential scan of one sequence occupies one compute unit
+// for T dependent steps.  The recurrences are positive linear maps, and products of
+// positive maps forget their starting vector (up to scale) geometrically fast, so the
+// ring state at a checkpoint position can instead be obtained by a short WARM-UP: start
+// W positions earlier from the state a sequence beginning there would have, and run.
+// Every checkpoint interval ("chunk") is then an independent task:
+//   forward task j:  warm up over (j*Delta - W, j*Delta], record the state at j*Delta
+//                    (-> ckA[j]), run the chunk, record the state at its end (-> ckA2[j+1]);
+//   backward task j: the mirror image from above (-> ckB[j+1], ckB2[j]).
+// Nothing is taken on trust: k_spec_cmp compares, for every chunk boundary, the state
+// the previous chunk actually reached with the warm-up state the next chunk started
+// from, entry by entry, after removing their common scale factor.  If all boundaries of
+// a (sequence, direction) agree to SPEC_TOL the warm-up states ARE the sequential
+// states to that relative accuracy (perturbations of the start do not grow: the maps
+// are non-expansive in the projective metric); k_spec_fix then chains the scale
+// factors into the checkpoint scales and logZ.  Otherwise the flag stays 0 and the
+// sequential scan kernel, which is launched afterwards and returns at once for
+// accepted (sequence, direction) pairs, recomputes that pair from scratch.
+// One wave per task, no barriers, same register/LDS organisation as k_interval_wave.
+// ---------------------------------------------------------------------------
+constexpr double SPEC_TOL = 1e-10;
+
+// Rows of slack behind the sliding window of the chunk-parallel scan (see spec_task).
+__host__ __device__ constexpr int lin_slack(int KW)
+{
+    return KW / 4 < 8 ? 8 : ((KW / 4 + 3) & ~3);
+}
+
+__host__ __device__ constexpr size_t spec_lds_doubles(int CT, int NKW)
+{
+    const int KW = NKW * (64 / pow2_ge8(CT));
+    return (size_t)(KW + lin_slack(KW)) * CT + 2 * (size_t)pow2_ge8(CT);
+}
+
+// The window of the last KW = NKW*GW >= K messages lives in a LINEAR buffer of KW + M
+// rows of exactly CT doubles: the newest row moves up (forward) or down (backward) by one
+// per step, every read is base + compile-time offset, and when the newest row reaches the
+// end of the buffer the window is moved back by M rows (KW*CT/64 loads and stores per
+// lane every M steps).  This needs a third of the LDS of a doubled ring with padded rows,
+// which is what bounds the number of resident waves per compute unit.
+template <int CT, int NKW, bool BWD>
+__device__ __forceinline__ void spec_task(const Params &p, double *lds_raw, const int b, const int j,
+                                          const int warm)
+{
+    constexpr int CTP = pow2_ge8(CT);
+    constexpr int RS = CT;
+    constexpr int GW = 64 / CTP;
+    constexpr int KW = NKW * GW;
+    constexpr int M = lin_slack(KW);
+    constexpr int ROWS = KW + M;
+    constexpr int RTOT = ROWS * RS;
+    constexpr int H = CT <= 32 ? 2 : 1;
+    constexpr int HC = CT / H;
+    const int lane = threadIdx.x;
+    const int K = p.K, C = p.C, KC = K * C;
+    double *ring = lds_raw;          // [ROWS][RS]
+    double *yv = ring + RTOT;        // [CTP]
+    int *sc = (int *)(yv + CTP);     // [CTP]
+    const int Delta = p.Delta, N = p.N;
+    const size_t ckstride = (size_t)KC + C;
+    const int c = lane % CTP, g = lane / CTP;
+    const int hh = H == 2 ? (lane >> 5) : 0;
+    const bool cval = c < C;
+    const int cc = cval ? c : 0;
+    const SeqHdr h = p.hdr[b];
+    const int L = h.L, J = h.J, Jm = J - 1;
+    const int lo = j * Delta;
+    if (lo >= L) return;
+    const int hi = min(lo + Delta, L);
+    const size_t row0 = (size_t)b * (p.T + 1);
+    const double2 *EIc = p.EI + row0 * C + cc;
+    const int *nbc = p.nbase + row0 * C + cc;
+
+    // strip of W in the order in which this direction reads the window (lowest row first)
+    double wreg[NKW];
+#pragma unroll
+    for (int jj = 0; jj < NKW; ++jj) {
+        const int k = 1 + g + (BWD ? jj : NKW - 1 - jj) * GW;
+        wreg[jj] = (cval && k <= K) ? p.W[(size_t)(k - 1) * C + c] : 0.0;
+    }
+    double Ereg[HC];
+#pragma unroll
+    for (int i = 0; i < HC; ++i) {
+        const int o = hh * HC + i;
+        const bool ok = cval && o < C;
+        Ereg[i] = ok ? (BWD ? p.Etr[(size_t)c * C + o] : p.Etr[(size_t)o * C + c]) : 0.0;
+    }
+    const double2 *ys = (const double2 *)__builtin_assume_aligned(yv + hh * HC, 16);
+
+    // ---- start: the state of a sequence that begins (forward) / ends (backward) at s0
+    const int s0 = BWD ? min(hi + warm, L) : max(lo - warm, 0);
+    for (int i = lane; i < RTOT; i += 64) ring[i] = 0.0;
+    if (lane < CTP) yv[lane] = 0.0;
+    lds_wave_fence();
+    int r = BWD ? M : KW - 1;  // row of the newest message
+    double Y = 0.0, prevsum;
+    {
+        double q;
+        if (!BWD) {
+            double z = 0.0;
+#pragma unroll
+            for (int i = 0; i < HC; ++i) z += Ereg[i];
+            if (H == 2) z = add_across_32(z);
+            q = z * EIc[(size_t)s0 * C].y;
+            if (lane < C) yv[lane] = 1.0;
+            prevsum = (double)C;
+        } else {
+            q = EIc[(size_t)s0 * C].x;
+            if (lane == 0) yv[0] = 1.0;
+            prevsum = 1.0;
+        }
+        if (cval && g == 0) ring[r * RS + c] = q;
+    }
+    lds_wave_fence();
+    // checkpoint layout: message of position t' at slot t' mod K
+    auto record = [&](const int t, double *ck, double *ckY) {
+        const int tm = t % K;
+        for (int i = lane; i < KC; i += 64) {
+            const int sl = i / C, col = i % C;
+            int d = BWD ? sl - tm : tm - sl;
+            if (d < 0) d += K;
+            ck[i] = ring[(BWD ? r + d : r - d) * RS + col];
+        }
+        if (lane < C) ck[KC + lane] = yv[lane];
+        if (lane == 0) *ckY = Y;
+    };
+    double *ck1 = (BWD ? p.ckB : p.ckA) + ((size_t)b * (N + 1)) * ckstride;
+    double *ck2 = (BWD ? p.ckB2 : p.ckA2) + ((size_t)b * (N + 1)) * ckstride;
+    double *ckY1 = (BWD ? p.ckYB : p.ckYA) + (size_t)b * (N + 1);
+    double *ckY2 = (BWD ? p.ckYB2 : p.ckYA2) + (size_t)b * (N + 1);
+    const int tstart = BWD ? hi : lo;   // where the chunk proper begins (state -> ck1)
+    const int istart = BWD ? j + 1 : j, iend = BWD ? j : j + 1;
+    if (s0 == tstart && !(BWD && tstart == L)) record(s0, ck1 + (size_t)istart * ckstride, ckY1 + istart);
+
+    // this lane's lowest read address relative to the newest row
+    const int rdoff = BWD ? g * RS + cc : -(g + (NKW - 1) * GW) * RS + cc;
+    auto one = [&](const int t, const double2 e) {
+        const bool boundary = BWD ? ((t + 1) & Jm) == 0 : (t & Jm) == 0;
+        if (__builtin_expect(boundary, 0)) {
+            const int ex = safe_exponent(prevsum);
+            Y += (double)ex;
+            const int jn = t / J;
+            const int sft = BWD ? -(nbc[(size_t)jn * C] - nbc[(size_t)(jn + 1) * C]) - ex
+                                : nbc[(size_t)jn * C] - nbc[(size_t)(jn - 1) * C] - ex;
+            sc[c] = sft;
+            lds_wave_fence();
+            for (int i = lane; i < RTOT; i += 64) ring[i] = fmin(ldexp(ring[i], sc[i % RS]), DBL_MAX);
+            lds_wave_fence();
+        }
+        if (__builtin_expect(BWD ? r == 0 : r == ROWS - 1, 0)) {
+            // move the window back by M rows; chunk order keeps sources ahead of the stores
+            constexpr int NCP = (KW * RS + 63) / 64;
+            for (int u = 0; u < NCP; ++u) {
+                const int i = (BWD ? NCP - 1 - u : u) * 64 + lane;
+                double v = 0.0;
+                if (i < KW * RS) v = ring[BWD ? i : i + M * RS];
+                lds_wave_fence();
+                if (i < KW * RS) ring[BWD ? i + M * RS : i] = v;
+                lds_wave_fence();
+            }
+            r = BWD ? M : KW - 1;
+        }
+        const double *base = ring + r * RS + rdoff;  // rows r+g.. (backward) / r-g-(NKW-1)GW.. (forward)
+        double a0 = 0.0, a1 = 0.0;
+#pragma unroll
+        for (int jj = 0; jj < NKW; jj += 2) {
+            a0 = fma(wreg[jj], base[jj * GW * RS], a0);
+            a1 = fma(wreg[jj + 1], base[(jj + 1) * GW * RS], a1);
+        }
+        const double x = group_sum<CTP>(a0 + a1);
+        const double y = x * (BWD ? e.y : e.x);
+        if (cval) yv[c] = y;
+        lds_wave_fence();
+        double z0 = 0.0, z1 = 0.0, ysum = 0.0;
+#pragma unroll
+        for (int i = 0; i < HC; i += 2) {
+            const double2 vv = ys[i >> 1];
+            z0 = fma(vv.x, Ereg[i], z0);
+            z1 = fma(vv.y, Ereg[i + 1], z1);
+            ysum += vv.x + vv.y;
+        }
+        double z = z0 + z1;
+        if (H == 2) {
+            z = add_across_32(z);
+            ysum = add_across_32(ysum);
+        }
+        prevsum = ysum;
+        const double q = z * (BWD ? e.x : e.y);
+        r += BWD ? -1 : 1;
+        if (cval && g == 0) ring[r * RS + c] = q;
+        lds_wave_fence();
+        if (__builtin_expect(t == tstart, 0)) record(t, ck1 + (size_t)istart * ckstride, ckY1 + istart);
+    };
+    // positions s0+1 .. hi (forward) or s0-1 .. lo (backward), PFW rows prefetched ahead
+    const int nsteps = BWD ? s0 - lo : hi - s0;
+    double2 qe[PFW];
+#pragma unroll
+    for (int u = 0; u < PFW; ++u) {
+        const int n = min(1 + u, nsteps);
+        qe[u] = EIc[(size_t)(BWD ? s0 - n : s0 + n) * C];
+    }
+    int n = 1;
+    for (; n + PFW - 1 <= nsteps; n += PFW) {
+#pragma unroll
+        for (int u = 0; u < PFW; ++u) {
+            const double2 e = qe[u];
+            const int n2 = min(n + u + PFW, nsteps);
+            qe[u] = EIc[(size_t)(BWD ? s0 - n2 : s0 + n2) * C];
+            one(BWD ? s0 - (n + u) : s0 + (n + u), e);
+        }
+    }
+    for (; n <= nsteps; ++n) {
+        const int t = BWD ? s0 - n : s0 + n;
+        one(t, EIc[(size_t)t * C]);
+    }
+    record(BWD ? lo : hi, ck2 + (size_t)iend * ckstride, ckY2 + iend);
+}
+
+template <int CT, int NKW>
+__global__ __launch_bounds__(64) void k_spec(Params p, int both, int warm, int tier)
+{
+    extern __shared__ double lds_raw[];
+    const int ndir = both ? 2 : 1;
+    const int dir = blockIdx.x % ndir;
+    const int task = blockIdx.x / ndir;
+    const int b = task / p.N, j = task % p.N;
+    if (tier > 0 && p.spec_ok[b * 2 + dir]) return;  // accepted with the shorter warm-up
+    if (dir == 0) spec_task<CT, NKW, false>(p, lds_raw, b, j, warm);
+    else spec_task<CT, NKW, true>(p, lds_raw, b, j, warm);
+}
+
+// One wave per (chunk boundary j, sequence, direction): compare the state chunk j-1
+// (forward) / chunk j (backward) reached at position j*Delta with the warm-up state the
+// neighbouring chunk started from.
+__global__ __launch_bounds__(64) void k_spec_cmp(Params p, int tier)
+{
+    const int j = blockIdx.x, b = blockIdx.y, dir = blockIdx.z, lane = threadIdx.x;
+    if (tier > 0 && p.spec_ok[b * 2 + dir]) return;
+    const int L = p.hdr[b].L;
+    const int nint = (L + p.Delta - 1) / p.Delta;
+    if (j < 1 || j >= nint) return;
+    const int KC = p.K * p.C, C = p.C, N = p.N;
+    const size_t ckstride = (size_t)KC + C;
+    const double *A = (dir ? p.ckB : p.ckA) + ((size_t)b * (N + 1) + j) * ckstride;    // warm-up state
+    const double *A2 = (dir ? p.ckB2 : p.ckA2) + ((size_t)b * (N + 1) + j) * ckstride;  // reached state
+    const double Y = (dir ? p.ckYB : p.ckYA)[(size_t)b * (N + 1) + j];
+    const double Y2 = (dir ? p.ckYB2 : p.ckYA2)[(size_t)b * (N + 1) + j];
+    double s1 = 0.0, s2 = 0.0;
+    for (int i = 0; i < C; ++i) {
+        s1 += A[KC + i];
+        s2 += A2[KC + i];
+    }
+    const double f = s2 / s1;  // reached = f * 2^(Y2-Y) * warm-up, entry by entry, if they agree
+    double err = 0.0;
+    if (!(s1 > 0.0) || !(s2 > 0.0) || !(f > 0.0) || !(f < DBL_MAX)) err = DBL_MAX;
+    for (int i = lane; i < KC + C; i += 64) {
+        const double x = A2[i], y = A[i] * f;
+        const double m = fmax(fabs(x), fabs(y));
+        if (m > 1e-290) err = fmax(err, fabs(x - y) / m);
+        if (!(m < DBL_MAX)) err = DBL_MAX;
+    }
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) err = fmax(err, __shfl_xor(err, off));
+    if (lane == 0) {
+        const size_t o = ((size_t)b * 2 + dir) * (N + 1) + j;
+        p.spec_err[o] = err;
+        p.spec_lr[o] = (Y2 - Y) + log2(f);
+    }
+}
+
+// Accept or reject each (sequence, direction); chain the scale factors.  grid (B, ndir).
+__global__ void k_spec_fix(Params p, int ndir, int tier)
+{
+    if (threadIdx.x != 0) return;
+    const int b = blockIdx.x, dir = blockIdx.y;
+    if (tier > 0 && p.spec_ok[b * 2 + dir]) return;
+    const int L = p.hdr[b].L, N = p.N, C = p.C, KC = p.K * C;
+    const int nint = (L + p.Delta - 1) / p.Delta;
+    const size_t so = ((size_t)b * 2 + dir) * (N + 1);
+    if (dir >= ndir) {  // direction not run in this call
+        p.spec_ok[b * 2 + dir] = 0;
+        p.spec_err[so] = -1.0;
+        return;
+    }
+    bool ok = true;
+    double worst = 0.0;
+    for (int j = 1; j < nint; ++j) worst = fmax(worst, p.spec_err[so + j]);
+    ok = worst <= SPEC_TOL;
+    p.spec_err[so] = worst;  // entry 0 is no boundary: it carries the report value
+    if (dir == 0) {
+        double acc = 0.0;  // log2 of the factor between the true state and the warm-up state
+        for (int j = 1; j < nint; ++j) {
+            acc += p.spec_lr[so + j];
+            p.ckYA[(size_t)b * (N + 1) + j] += acc;
+        }
+        double lz;
+        if (nint == 0) {
+            lz = log((double)C);
+        } else {
+            const double *e = p.ckA2 + ((size_t)b * (N + 1) + nint) * ((size_t)KC + C);
+            double s = 0.0;
+            for (int i = 0; i < C; ++i) s += e[KC + i];
+            lz = (p.ckYA2[(size_t)b * (N + 1) + nint] + acc) * LN2 + log(s);
+            ok = ok && s > 0.0 && lz == lz;
+        }
+        if (ok) {
+            p.hdr[b].logZ = lz;
+            p.logz[b] = (float)lz;
+        }
+    } else {
+        double acc = 0.0;
+        for (int j = nint - 1; j >= 1; --j) {
+            acc += p.spec_lr[so + j];
+            p.ckYB[(size_t)b * (N + 1) + j] += acc;
+        }
+    }
+    p.spec_ok[b * 2 + dir] = ok ? 1 : 0;
+}
+
+// The chunk-parallel scan was not attempted: say so in the report fields.
+__global__ void k_spec_clear(Params p)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= 2 * p.B) return;
+    p.spec_ok[i] = 0;
+    p.spec_err[(size_t)i * (p.N + 1)] = -1.0;
+}
+
+__global__ void k_spec_report(Params p, int32_t *accepted, double *mismatch)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= 2 * p.B) return;
+    if (accepted) accepted[i] = p.spec_ok[i];
+    if (mismatch) mismatch[i] = p.spec_err[(size_t)i * (p.N + 1)];
+}
+
+// ---------------------------------------------------------------------------
 // Finalisation (fixed-order reductions).
 // ---------------------------------------------------------------------------
 // carry[b,i,c] = sum_{i'<=i} tot[b,i',c];  mean[b,c] = (1/L) sum_u pm[b,u,c].  grid B, NT threads:
@@ -1575,7 +1925,7 @@ struct Plan {
     int Delta, N, NCH, nslot, G;
     size_t lds_scan, lds_interval;
     size_t total;
-    size_t off[24];
+    size_t off[32];
 };
 
 int make_plan(int B, int T, int K, int C, int ckpt_interval, int want_grad, Plan *pl)
@@ -1594,7 +1944,8 @@ int make_plan(int B, int T, int K, int C, int ckpt_interval, int want_grad, Plan
     size_t ntask = (size_t)B * pl->N;
     pl->nslot = (int)(ntask < (size_t)NSLOT_MAX ? ntask : (size_t)NSLOT_MAX);
     const size_t b = (size_t)B, t1 = (size_t)T + 1, c = (size_t)C, k = (size_t)K, n = (size_t)pl->N;
-    size_t sz[24];
+    const size_t n1 = n;
+    size_t sz[32];
     int i = 0;
     sz[i++] = b * sizeof(SeqHdr);                 // 0 hdr
     sz[i++] = b * c * 8;                          // 1 nu
@@ -1604,12 +1955,12 @@ int make_plan(int B, int T, int K, int C, int ckpt_interval, int want_grad, Plan
     sz[i++] = k * c * 8;                          // 5 W
     sz[i++] = c * c * 8;                          // 6 Etr
     sz[i++] = b * t1 * c * 16;                    // 7 EI
-    sz[i++] = 0;                                  // 8 (unused)
+    sz[i++] = 2 * b * 2 * (n1 + 1) * 8 + b * 2 * 4 + 256;  // 8 spec_lr, spec_err, spec_ok
     sz[i++] = b * t1 * c * 4;                     // 9 nbase
     const size_t g = want_grad ? 1 : 0;
-    sz[i++] = g * b * (n + 1) * (k * c + c) * 8;  // 10 ckA
+    sz[i++] = b * (n + 1) * (k * c + c) * 8;      // 10 ckA
     sz[i++] = g * b * (n + 1) * (k * c + c) * 8;  // 11 ckB
-    sz[i++] = g * b * (n + 1) * 8;                // 12 ckYA
+    sz[i++] = b * (n + 1) * 8;                    // 12 ckYA
     sz[i++] = g * b * (n + 1) * 8;                // 13 ckYB
     sz[i++] = g * (size_t)pl->nslot * pl->Delta * 2 * c * 8;  // 14 aloc
     sz[i++] = g * (size_t)pl->nslot * pl->Delta * 8;          // 15 alocY
@@ -1619,6 +1970,10 @@ int make_plan(int B, int T, int K, int C, int ckpt_interval, int want_grad, Plan
     sz[i++] = g * b * n * c * 8;                  // 19 sumR
     sz[i++] = g * b * n * c * 8;                  // 20 carry
     sz[i++] = g * b * c * 8;                      // 21 mean
+    sz[i++] = b * (n + 1) * (k * c + c) * 8;      // 22 ckA2
+    sz[i++] = g * b * (n + 1) * (k * c + c) * 8;  // 23 ckB2
+    sz[i++] = b * (n + 1) * 8;                    // 24 ckYA2
+    sz[i++] = g * b * (n + 1) * 8;                // 25 ckYB2
     size_t off = 0;
     for (int j = 0; j < i; ++j) {
         pl->off[j] = off;
@@ -1652,6 +2007,13 @@ void bind_workspace(Params &p, const Plan &pl, void *ws)
     p.sumR = (double *)(w + pl.off[19]);
     p.carry = (double *)(w + pl.off[20]);
     p.mean = (double *)(w + pl.off[21]);
+    p.ckA2 = (double *)(w + pl.off[22]);
+    p.ckB2 = (double *)(w + pl.off[23]);
+    p.ckYA2 = (double *)(w + pl.off[24]);
+    p.ckYB2 = (double *)(w + pl.off[25]);
+    p.spec_lr = (double *)(w + pl.off[8]);
+    p.spec_err = p.spec_lr + (size_t)p.B * 2 * (pl.N + 1);
+    p.spec_ok = (int *)(p.spec_err + (size_t)p.B * 2 * (pl.N + 1));
 }
 
 int check_launch()
@@ -1754,6 +2116,61 @@ int launch_interval(const Params &p, const Plan &pl, hipStream_t st)
     return check_launch();
 }
 
+// Chunk-parallel scan: returns 1 when it does not apply to these sizes.
+template <int CT, int NKW>
+int launch_spec_k(const Params &p, hipStream_t st, bool both, int warm, int tier)
+{
+    const size_t lds = spec_lds_doubles(CT, NKW) * sizeof(double);
+    if (lds > LDS_LIMIT) return 1;
+    if (hipFuncSetAttribute((const void *)k_spec<CT, NKW>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds) != hipSuccess)
+        return SEMICRF_ELAUNCH;
+    const int ndir = both ? 2 : 1;
+    hipLaunchKernelGGL((k_spec<CT, NKW>), dim3(p.B * p.N * ndir), dim3(64), lds, st, p, both ? 1 : 0,
+                       warm, tier);
+    hipLaunchKernelGGL(k_spec_cmp, dim3(p.N, p.B, ndir), dim3(64), 0, st, p, tier);
+    hipLaunchKernelGGL(k_spec_fix, dim3(p.B, 2), dim3(64), 0, st, p, ndir, tier);
+    return check_launch();
+}
+
+template <int CT>
+int launch_spec_ct(const Params &p, hipStream_t st, bool both, int warm, int tier)
+{
+    constexpr int GW = 64 / pow2_ge8(CT);
+    const int per_lane = (p.K + GW - 1) / GW;
+    if (per_lane <= 16) return launch_spec_k<CT, 16>(p, st, both, warm, tier);
+    if (per_lane <= 32) return launch_spec_k<CT, 32>(p, st, both, warm, tier);
+    if (per_lane <= 64) return launch_spec_k<CT, 64>(p, st, both, warm, tier);
+    return 1;
+}
+
+constexpr int spec_ct_of(int C)
+{
+    return C <= 8 ? 8 : (C <= 16 ? 16 : (C <= 24 ? 24 : (C <= 32 ? 32 : 64)));
+}
+
+bool spec_applies(int K, int C)
+{
+    if (C > 64) return false;
+    const int CT = spec_ct_of(C);
+    const int GW = 64 / pow2_ge8(CT);
+    const int per_lane = (K + GW - 1) / GW;
+    if (per_lane > 64) return false;
+    const int NKW = per_lane <= 16 ? 16 : (per_lane <= 32 ? 32 : 64);
+    return spec_lds_doubles(CT, NKW) * sizeof(double) <= LDS_LIMIT;
+}
+
+int launch_spec(const Params &p, hipStream_t st, bool both, int warm, int tier)
+{
+    const int C = p.C;
+    if (C <= 8) return launch_spec_ct<8>(p, st, both, warm, tier);
+    if (C <= 16) return launch_spec_ct<16>(p, st, both, warm, tier);
+    if (C <= 24) return launch_spec_ct<24>(p, st, both, warm, tier);
+    if (C <= 32) return launch_spec_ct<32>(p, st, both, warm, tier);
+    if (C <= 64) return launch_spec_ct<64>(p, st, both, warm, tier);
+    return 1;
+}
+
 // Optional per-stage timing: events are recorded on the caller's stream around
 // the four stages (prefix sums, scans, intervals, finalisation).
 struct StageTimer {
@@ -1783,10 +2200,28 @@ int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hi
     p.nslot = pl.nslot;
     p.want_grad = mode == 2;
     bind_workspace(p, pl, workspace);
+    // warm-up lengths of the chunk-parallel scan: two maximal segment lengths first, eight
+    // for the (sequence, direction) pairs that fails for, the sequential scan for the rest
+    int warm[2] = {2 * p.K < 32 ? 32 : 2 * p.K, 8 * p.K < 64 ? 64 : 8 * p.K};
+    if (const char *e = getenv("SEMICRF_WARMUP")) {  // tuning knob: first warm-up length
+        const int w = atoi(e);
+        if (w > 0) warm[0] = w, warm[1] = 4 * w;
+    }
+    p.spec = p.spec && mode != 0 && spec_applies(p.K, p.C);
     T.mark();
     rc = launch_prep(p, st);
     T.mark();
     if (rc != SEMICRF_OK || mode == 0) return rc;
+    if (p.spec) {
+        for (int tier = 0; tier < 2; ++tier) {
+            rc = launch_spec(p, st, mode == 2, warm[tier], tier);
+            if (rc != SEMICRF_OK) return rc;
+        }
+    } else {
+        hipLaunchKernelGGL(k_spec_clear, dim3((2 * p.B + 63) / 64), dim3(64), 0, st, p);
+    }
+    // sequential scans: the whole job without the chunk-parallel scan, else only the
+    // (sequence, direction) pairs it rejected (the others return at once)
     rc = launch_scan(p, pl, st, mode == 2);
     if (rc != SEMICRF_OK) return rc;
     T.mark();
@@ -1862,6 +2297,7 @@ int semicrf_logz_fwd(const float *emis, const int32_t *lengths, const float *tra
     p.emis = emis; p.lengths = lengths; p.trans = trans; p.dur = dur;
     p.B = B; p.T = T; p.K = K; p.C = C;
     p.center = (flags & SEMICRF_CENTER) ? 1 : 0;
+    p.spec = (flags & SEMICRF_SEQUENTIAL_SCAN) ? 0 : 1;
     p.logz = logz;
     return run(p, ckpt_interval, workspace, workspace_bytes, (hipStream_t)stream, 1);
 }
@@ -1878,6 +2314,7 @@ int semicrf_fwd_bwd(const float *emis, const int32_t *lengths, const float *tran
     p.emis = emis; p.lengths = lengths; p.trans = trans; p.dur = dur; p.grad_logz = grad_logz;
     p.B = B; p.T = T; p.K = K; p.C = C;
     p.center = (flags & SEMICRF_CENTER) ? 1 : 0;
+    p.spec = (flags & SEMICRF_SEQUENTIAL_SCAN) ? 0 : 1;
     p.logz = logz; p.grad_emis = grad_emis; p.grad_trans = grad_trans; p.grad_dur = grad_dur;
     p.pos_marg = pos_marg;
     return run(p, ckpt_interval, workspace, workspace_bytes, (hipStream_t)stream, 2);
@@ -1896,6 +2333,7 @@ int semicrf_fwd_bwd_profiled(const float *emis, const int32_t *lengths, const fl
     p.emis = emis; p.lengths = lengths; p.trans = trans; p.dur = dur; p.grad_logz = grad_logz;
     p.B = B; p.T = T; p.K = K; p.C = C;
     p.center = (flags & SEMICRF_CENTER) ? 1 : 0;
+    p.spec = (flags & SEMICRF_SEQUENTIAL_SCAN) ? 0 : 1;
     p.logz = logz; p.grad_emis = grad_emis; p.grad_trans = grad_trans; p.grad_dur = grad_dur;
     p.pos_marg = pos_marg;
     StageTimer tm;
@@ -1906,6 +2344,25 @@ int semicrf_fwd_bwd_profiled(const float *emis, const int32_t *lengths, const fl
         tm.ev[i] = (hipEvent_t)stage_events[i];
     }
     return run(p, ckpt_interval, workspace, workspace_bytes, tm.st, 2, &tm);
+}
+
+int semicrf_scan_report(const void *workspace, size_t workspace_bytes, int B, int T, int K, int C,
+                        int ckpt_interval, int want_grad, int32_t *accepted, double *mismatch,
+                        void *stream)
+{
+    Plan pl;
+    int rc = make_plan(B, T, K, C, ckpt_interval, want_grad, &pl);
+    if (rc != SEMICRF_OK) return rc;
+    if (!accepted && !mismatch) return SEMICRF_EINVAL;
+    if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < pl.total)
+        return SEMICRF_EWORKSPACE;
+    Params p = {};
+    p.B = B; p.T = T; p.K = K; p.C = C;
+    p.N = pl.N;
+    bind_workspace(p, pl, const_cast<void *>(workspace));
+    hipLaunchKernelGGL(k_spec_report, dim3((2 * B + 63) / 64), dim3(64), 0, (hipStream_t)stream, p,
+                       accepted, mismatch);
+    return check_launch();
 }
 
 }  // extern "C"

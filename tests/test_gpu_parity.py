@@ -6,6 +6,8 @@ weight); the accumulated gradients grad_trans / grad_dur are sums of up to
 sum_b L_b marginals, so they are held to 1e-4 * max(1, max|g|) and the raw
 maximum error is printed.
 """
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -122,6 +124,76 @@ def test_padding_independence_and_determinism():
     assert abs(float(c[0][0]) - float(a[0][1])) <= 1e-5 * abs(float(a[0][1]))
     assert (c[4][0] - a[4][1, :L]).abs().max().item() <= 2e-6
     assert torch.all(a[4][1, L:] == 0) and torch.all(a[1][1, L:] == 0)
+
+
+def run_with_report(w, flags, ckpt_interval, warm_env=None):
+    emis, lengths, trans, dur = to_dev(w)
+    ws = sb.alloc_workspace(w.B, w.T, w.K, w.C, ckpt_interval, True, DEV)
+    old = os.environ.pop("SEMICRF_WARMUP", None)
+    if warm_env is not None:
+        os.environ["SEMICRF_WARMUP"] = str(warm_env)
+    try:
+        out = sb.semicrf_fwd_bwd(emis, lengths, trans, dur, None, ckpt_interval, flags, workspace=ws)
+    finally:
+        os.environ.pop("SEMICRF_WARMUP", None)
+        if old is not None:
+            os.environ["SEMICRF_WARMUP"] = old
+    acc, mis = sb.semicrf_scan_report(ws, w.B, w.T, w.K, w.C, ckpt_interval, True)
+    torch.cuda.synchronize()
+    return [o.double().cpu().numpy() for o in out], acc.cpu().numpy(), mis.cpu().numpy()
+
+
+def assert_outputs_match_oracle(out, r):
+    assert np.abs(out[0] - r.logz).max() <= 1e-5 * max(1.0, np.abs(r.logz).max())
+    assert np.abs(out[1] - r.grad_emis).max() <= 1e-4
+    assert np.abs(out[4] - r.pos_marg).max() <= 1e-4
+    assert np.abs(out[2] - r.grad_trans).max() <= 1e-4 * max(1.0, np.abs(r.grad_trans).max())
+    assert np.abs(out[3] - r.grad_dur).max() <= 1e-4 * max(1.0, np.abs(r.grad_dur).max())
+
+
+def test_chunk_parallel_and_sequential_scans_agree():
+    """Default (chunk-parallel, verified) against SEMICRF_SEQUENTIAL_SCAN on a case with
+    many chunks and a ragged batch; both against the oracle."""
+    w = synth.small_random(71, 4, 1500, 12, 10, ragged=True)
+    w.lengths[:] = [1500, 1499, 64, 3]
+    r = oracle.fwd_bwd(w.emis, w.lengths, w.trans, w.dur)
+    par, acc, mis = run_with_report(w, sb.SEMICRF_CENTER, 64)
+    seq, acc_s, mis_s = run_with_report(w, sb.SEMICRF_CENTER | sb.SEMICRF_SEQUENTIAL_SCAN, 64)
+    print(f"       boundary mismatch per (sequence, direction): {mis.ravel()}", flush=True)
+    assert np.all(acc == 1) and np.all(mis >= 0) and np.all(mis <= 1e-10)
+    assert np.all(acc_s == 0) and np.all(mis_s == -1)
+    assert_outputs_match_oracle(par, r)
+    assert_outputs_match_oracle(seq, r)
+    assert np.abs(par[0] - seq[0]).max() <= 1e-6 * np.abs(seq[0]).max()
+    for a, b in zip(par[1:], seq[1:]):
+        assert np.abs(a - b).max() <= 2e-6 * max(1.0, np.abs(b).max())
+
+
+def test_short_warm_up_is_rejected_then_longer_one_accepted():
+    """First warm-up of K/2 positions cannot reproduce the ring state (it does not even fill
+    the ring); the second attempt (four times as long) does.  Results as the oracle's."""
+    w = synth.small_random(72, 2, 900, 16, 6, ragged=False)
+    r = oracle.fwd_bwd(w.emis, w.lengths, w.trans, w.dur)
+    out, acc, mis = run_with_report(w, sb.SEMICRF_CENTER, 48, warm_env=8)
+    assert np.all(acc == 1) and np.all(mis <= 1e-10)
+    assert_outputs_match_oracle(out, r)
+
+
+def test_slow_mixing_input_falls_back_to_the_sequential_scan():
+    """A nearly deterministic two-label chain with weak emissions remembers its start for
+    thousands of positions, so no warm-up of a few K reproduces the state: every boundary
+    check must fail and the sequential scan must deliver the (oracle's) result."""
+    rng = np.random.default_rng(73)
+    B, T, K, C = 2, 2000, 2, 2
+    w = synth.small_random(73, B, T, K, C, ragged=False)
+    w.emis[:] = (0.05 * rng.standard_normal((B, T, C))).astype(np.float32)
+    w.trans[:] = np.array([[0.0, -40.0], [-40.0, 0.0]], dtype=np.float32)
+    w.dur[:] = 0.0
+    r = oracle.fwd_bwd(w.emis, w.lengths, w.trans, w.dur)
+    out, acc, mis = run_with_report(w, sb.SEMICRF_CENTER, 64)
+    print(f"       boundary mismatch per (sequence, direction): {mis.ravel()}", flush=True)
+    assert np.all(acc == 0) and np.all(mis > 1e-10)
+    assert_outputs_match_oracle(out, r)
 
 
 def test_cum_scores_matches_oracle_prefix_sums():
