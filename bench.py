@@ -106,13 +106,23 @@ def main():
 
     positions = w.positions
     edges = w.nominal_edges
-    # dominant kernel: the two sequential scans (one launch).  Algorithmic work per
-    # position and scan: K*C multiply-adds for the duration sum + C*C for the transition
-    # product, 2 flop each, in fp64.
-    scan_flop = 2.0 * 2.0 * (K * C + C * C) * positions
-    scan_s = stage[1] * 1e-3
-    achieved = scan_flop / scan_s / 1e12
+    # fp64 flops the method needs per position (one multiply-add = 2 flop): each of the
+    # forward scan, the per-interval forward recompute, the backward scan and the backward
+    # recompute is K*C (duration sum) + C*C (transition product) multiply-adds, and the marginal
+    # accumulation another K*C + C*C.  Warm-up positions of the chunk-parallel scans are overhead
+    # and are not counted.
+    unit = 2.0 * (K * C + C * C) * positions
+    stage_flop = {"scans": 2 * unit, "intervals": 3 * unit}
+    kernels = {"scans": "k_spec (chunk-parallel forward + backward scans, one launch; stage time "
+                        "includes its two small verification kernels)",
+               "intervals": "k_interval_wave / k_interval (per-interval recompute + marginals, one launch)"}
+    dom = "scans" if stage[1] >= stage[2] else "intervals"
+    dom_s = (stage[1] if dom == "scans" else stage[2]) * 1e-3
+    achieved = stage_flop[dom] / dom_s / 1e12
+    whole = 5 * unit / (ms_step * 1e-3) / 1e12
     logz = out[0].double().cpu().numpy()
+    acc, mis = sb.semicrf_scan_report(ws, B, T, K, C, args.ckpt_interval, True)
+    torch.cuda.synchronize()
 
     rec = {
         "metric": "semi-CRF fwd+bwd edge evals/sec (B*T*K*C^2/s) + positions/sec at T=100k",
@@ -135,15 +145,20 @@ def main():
         "stage_ms": {"prefix": stage[0], "scans": stage[1], "intervals": stage[2], "finalise": stage[3]},
         "roofline": {
             "bound": "alu",
-            "kernel": "k_scan (forward + backward sequential scans, one launch)",
+            "kernel": kernels[dom],
             "achieved": achieved,
             "peak": FP64_VECTOR_PEAK_TFLOPS,
             "unit": "TFLOP/s",
             "frac": achieved / FP64_VECTOR_PEAK_TFLOPS,
             "traffic": None,
-            "occupied_cus": min(2 * B, 256),
-            "frac_of_occupied_cus": achieved / (FP64_VECTOR_PEAK_TFLOPS * min(2 * B, 256) / 256.0),
+            "flop_per_launch": stage_flop[dom],
+            "launch_ms": dom_s * 1e3,
+            "whole_path_achieved": whole,
+            "whole_path_frac": whole / FP64_VECTOR_PEAK_TFLOPS,
         },
+        "scans_accepted_chunk_parallel": int(acc.sum().item()),
+        "scans_total": 2 * B,
+        "scan_boundary_mismatch_max": float(mis.max().item()),
         "logz_mean": float(logz.mean()),
     }
     if not args.no_cpu_baseline:

@@ -1486,7 +1486,16 @@ __global__ __launch_bounds__(64) void k_interval_wave(Params p)
 // ---------------------------------------------------------------------------
 constexpr double SPEC_TOL = 1e-10;
 
-// Rows of slack behind the sliding window of the chunk-parallel scan (see spec_task).
+constexpr int MB = 4;  // positions per time block of the one-wave scan
+
+// Entries of the message window per lane: NKW, plus one when a half-wave holds several lane
+// groups, so that the groups' rows fall into different LDS banks.
+__host__ __device__ constexpr int spec_nk(int CT, int NKW)
+{
+    return NKW + ((64 / pow2_ge8(CT)) > 2 ? 1 : 0);
+}
+
+// Rows of slack behind the sliding window.
 __host__ __device__ constexpr int lin_slack(int KW)
 {
     return KW / 4 < 8 ? 8 : ((KW / 4 + 3) & ~3);
@@ -1494,16 +1503,25 @@ __host__ __device__ constexpr int lin_slack(int KW)
 
 __host__ __device__ constexpr size_t spec_lds_doubles(int CT, int NKW)
 {
-    const int KW = NKW * (64 / pow2_ge8(CT));
-    return (size_t)(KW + lin_slack(KW)) * CT + 2 * (size_t)pow2_ge8(CT);
+    const int CTP = pow2_ge8(CT);
+    const int KW = spec_nk(CT, NKW) * (64 / CTP);
+    return (size_t)(KW + lin_slack(KW)) * CT + (size_t)(CTP - CT) + 2 * (size_t)CTP;
 }
 
-// The window of the last KW = NKW*GW >= K messages lives in a LINEAR buffer of KW + M
-// rows of exactly CT doubles: the newest row moves up (forward) or down (backward) by one
-// per step, every read is base + compile-time offset, and when the newest row reaches the
-// end of the buffer the window is moved back by M rows (KW*CT/64 loads and stores per
-// lane every M steps).  This needs a third of the LDS of a doubled ring with padded rows,
-// which is what bounds the number of resident waves per compute unit.
+// One scan task of the chunk-parallel scan, one wave.
+//
+// Window.  The last KW >= K messages live in a LINEAR buffer of KW + M rows of exactly CT
+// doubles: the newest row moves up (forward) or down (backward) by one per position, every
+// read is base + compile-time offset, and when the buffer's end is reached the window is
+// moved back (KW*CT/64 loads and stores per lane every ~M positions).
+//
+// Time blocking.  LDS bandwidth, not arithmetic, bounds a scan that re-reads its whole
+// window at every position (8 bytes per multiply-add).  Positions are therefore taken in
+// blocks of MB: lane (g, c) owns the window entries at distances d = g*NK .. g*NK+NK-1 from
+// the newest message, reads each ONCE per block and uses it for all MB positions of the
+// block (weights W[d+1] .. W[d+MB], a register strip of NK+MB-1 values).  What the block's
+// own new messages contribute to its later positions (durations 1..MB-1) is added from
+// registers while the positions are finished one after the other.
 template <int CT, int NKW, bool BWD>
 __device__ __forceinline__ void spec_task(const Params &p, double *lds_raw, const int b, const int j,
                                           const int warm)
@@ -1511,15 +1529,16 @@ __device__ __forceinline__ void spec_task(const Params &p, double *lds_raw, cons
     constexpr int CTP = pow2_ge8(CT);
     constexpr int RS = CT;
     constexpr int GW = 64 / CTP;
-    constexpr int KW = NKW * GW;
+    constexpr int NK = spec_nk(CT, NKW);
+    constexpr int KW = NK * GW;
     constexpr int M = lin_slack(KW);
     constexpr int ROWS = KW + M;
-    constexpr int RTOT = ROWS * RS;
+    constexpr int RTOT = ROWS * RS + (CTP - CT);  // lanes c >= C read (and ignore) past a row's end
     constexpr int H = CT <= 32 ? 2 : 1;
     constexpr int HC = CT / H;
     const int lane = threadIdx.x;
     const int K = p.K, C = p.C, KC = K * C;
-    double *ring = lds_raw;          // [ROWS][RS]
+    double *ring = lds_raw;          // [ROWS][RS] (+ pad)
     double *yv = ring + RTOT;        // [CTP]
     int *sc = (int *)(yv + CTP);     // [CTP]
     const int Delta = p.Delta, N = p.N;
@@ -1537,13 +1556,15 @@ __device__ __forceinline__ void spec_task(const Params &p, double *lds_raw, cons
     const double2 *EIc = p.EI + row0 * C + cc;
     const int *nbc = p.nbase + row0 * C + cc;
 
-    // strip of W in the order in which this direction reads the window (lowest row first)
-    double wreg[NKW];
+    double wx[NK + MB - 1];  // W[g*NK + jj + 1, c]
 #pragma unroll
-    for (int jj = 0; jj < NKW; ++jj) {
-        const int k = 1 + g + (BWD ? jj : NKW - 1 - jj) * GW;
-        wreg[jj] = (cval && k <= K) ? p.W[(size_t)(k - 1) * C + c] : 0.0;
+    for (int jj = 0; jj < NK + MB - 1; ++jj) {
+        const int k = g * NK + jj + 1;
+        wx[jj] = (cval && k <= K) ? p.W[(size_t)(k - 1) * C + c] : 0.0;
     }
+    double wn[MB - 1];       // W[1..MB-1, c]: durations inside a block
+#pragma unroll
+    for (int jj = 0; jj < MB - 1; ++jj) wn[jj] = (cval && jj + 1 <= K) ? p.W[(size_t)jj * C + c] : 0.0;
     double Ereg[HC];
 #pragma unroll
     for (int i = 0; i < HC; ++i) {
@@ -1559,7 +1580,7 @@ __device__ __forceinline__ void spec_task(const Params &p, double *lds_raw, cons
     if (lane < CTP) yv[lane] = 0.0;
     lds_wave_fence();
     int r = BWD ? M : KW - 1;  // row of the newest message
-    double Y = 0.0, prevsum;
+    double Y = 0.0;
     {
         double q;
         if (!BWD) {
@@ -1569,11 +1590,9 @@ __device__ __forceinline__ void spec_task(const Params &p, double *lds_raw, cons
             if (H == 2) z = add_across_32(z);
             q = z * EIc[(size_t)s0 * C].y;
             if (lane < C) yv[lane] = 1.0;
-            prevsum = (double)C;
         } else {
             q = EIc[(size_t)s0 * C].x;
             if (lane == 0) yv[0] = 1.0;
-            prevsum = 1.0;
         }
         if (cval && g == 0) ring[r * RS + c] = q;
     }
@@ -1595,91 +1614,114 @@ __device__ __forceinline__ void spec_task(const Params &p, double *lds_raw, cons
     double *ckY1 = (BWD ? p.ckYB : p.ckYA) + (size_t)b * (N + 1);
     double *ckY2 = (BWD ? p.ckYB2 : p.ckYA2) + (size_t)b * (N + 1);
     const int tstart = BWD ? hi : lo;   // where the chunk proper begins (state -> ck1)
+    const int tend = BWD ? lo : hi;
     const int istart = BWD ? j + 1 : j, iend = BWD ? j : j + 1;
     if (s0 == tstart && !(BWD && tstart == L)) record(s0, ck1 + (size_t)istart * ckstride, ckY1 + istart);
 
-    // this lane's lowest read address relative to the newest row
-    const int rdoff = BWD ? g * RS + cc : -(g + (NKW - 1) * GW) * RS + cc;
-    auto one = [&](const int t, const double2 e) {
-        const bool boundary = BWD ? ((t + 1) & Jm) == 0 : (t & Jm) == 0;
+    // this lane's lowest window address relative to the newest row
+    const int rdoff = BWD ? g * NK * RS + c : -(g * NK + NK - 1) * RS + c;
+    int t = s0;
+    auto load_rows = [&](double2 (&e)[MB], const int tfrom) {  // rows of the MB positions after tfrom
+#pragma unroll
+        for (int i = 0; i < MB; ++i) {
+            const int tt = BWD ? max(tfrom - 1 - i, tend) : min(tfrom + 1 + i, tend);
+            e[i] = EIc[(size_t)tt * C];
+        }
+    };
+    auto block_len = [&](const int tcur) {  // positions the block starting after tcur may take
+        int nb = BWD ? tcur - tend : tend - tcur;
+        nb = min(nb, MB);
+        // only the first position of a block may cross a scaling-block boundary
+        nb = min(nb, BWD ? ((tcur - 1) & Jm) + 1 : J - ((tcur + 1) & Jm));
+        // the position where the chunk proper starts ends its block (its state is recorded)
+        if (BWD ? tcur > tstart : tcur < tstart) nb = min(nb, BWD ? tcur - tstart : tstart - tcur);
+        return nb;
+    };
+    double2 e[MB];
+    load_rows(e, t);
+    while (t != tend) {
+        const int nb = block_len(t);
+        const int tn = BWD ? t - nb : t + nb;
+        double2 en[MB];
+        load_rows(en, tn);  // the next block's rows, a block ahead
+        const int t1 = BWD ? t - 1 : t + 1;
+        const bool boundary = BWD ? (t & Jm) == 0 : (t1 & Jm) == 0;
         if (__builtin_expect(boundary, 0)) {
+            double prevsum = 0.0;
+            for (int i = 0; i < CT; ++i) prevsum += yv[i];
             const int ex = safe_exponent(prevsum);
             Y += (double)ex;
-            const int jn = t / J;
+            const int jn = t1 / J;
             const int sft = BWD ? -(nbc[(size_t)jn * C] - nbc[(size_t)(jn + 1) * C]) - ex
                                 : nbc[(size_t)jn * C] - nbc[(size_t)(jn - 1) * C] - ex;
             sc[c] = sft;
             lds_wave_fence();
-            for (int i = lane; i < RTOT; i += 64) ring[i] = fmin(ldexp(ring[i], sc[i % RS]), DBL_MAX);
+            for (int i = lane; i < ROWS * RS; i += 64) ring[i] = fmin(ldexp(ring[i], sc[i % RS]), DBL_MAX);
             lds_wave_fence();
         }
-        if (__builtin_expect(BWD ? r == 0 : r == ROWS - 1, 0)) {
-            // move the window back by M rows; chunk order keeps sources ahead of the stores
+        if (__builtin_expect(BWD ? r < MB : r + MB > ROWS - 1, 0)) {
+            // move the window back to the start; chunk order keeps sources ahead of the stores
             constexpr int NCP = (KW * RS + 63) / 64;
+            const int shift = (BWD ? M - r : r - (KW - 1)) * RS;  // doubles, > 0
+            const int first = (BWD ? r : r - (KW - 1)) * RS;      // lowest double of the live window
             for (int u = 0; u < NCP; ++u) {
                 const int i = (BWD ? NCP - 1 - u : u) * 64 + lane;
                 double v = 0.0;
-                if (i < KW * RS) v = ring[BWD ? i : i + M * RS];
+                if (i < KW * RS) v = ring[first + i];
                 lds_wave_fence();
-                if (i < KW * RS) ring[BWD ? i + M * RS : i] = v;
+                if (i < KW * RS) ring[first + i + (BWD ? shift : -shift)] = v;
                 lds_wave_fence();
             }
             r = BWD ? M : KW - 1;
         }
-        const double *base = ring + r * RS + rdoff;  // rows r+g.. (backward) / r-g-(NKW-1)GW.. (forward)
-        double a0 = 0.0, a1 = 0.0;
+        // ---- what the window contributes to the MB positions of the block
+        const double *base = ring + r * RS + rdoff;
+        double acc[MB];
 #pragma unroll
-        for (int jj = 0; jj < NKW; jj += 2) {
-            a0 = fma(wreg[jj], base[jj * GW * RS], a0);
-            a1 = fma(wreg[jj + 1], base[(jj + 1) * GW * RS], a1);
-        }
-        const double x = group_sum<CTP>(a0 + a1);
-        const double y = x * (BWD ? e.y : e.x);
-        if (cval) yv[c] = y;
-        lds_wave_fence();
-        double z0 = 0.0, z1 = 0.0, ysum = 0.0;
+        for (int i = 0; i < MB; ++i) acc[i] = 0.0;
 #pragma unroll
-        for (int i = 0; i < HC; i += 2) {
-            const double2 vv = ys[i >> 1];
-            z0 = fma(vv.x, Ereg[i], z0);
-            z1 = fma(vv.y, Ereg[i + 1], z1);
-            ysum += vv.x + vv.y;
+        for (int jj = 0; jj < NK; ++jj) {
+            const double v = base[(BWD ? jj : NK - 1 - jj) * RS];  // distance g*NK + jj from the newest
+#pragma unroll
+            for (int i = 0; i < MB; ++i) acc[i] = fma(wx[jj + i], v, acc[i]);
         }
-        double z = z0 + z1;
-        if (H == 2) {
-            z = add_across_32(z);
-            ysum = add_across_32(ysum);
+#pragma unroll
+        for (int i = 0; i < MB; ++i) acc[i] = group_sum<CTP>(acc[i]);
+        // ---- the positions one after the other
+        double qn[MB];
+#pragma unroll
+        for (int i = 0; i < MB; ++i) {
+            if (i < nb) {
+                double x = acc[i];
+#pragma unroll
+                for (int jn = 0; jn < i; ++jn) x = fma(wn[i - 1 - jn], qn[jn], x);
+                const double y = x * (BWD ? e[i].y : e[i].x);
+                if (cval) yv[c] = y;
+                lds_wave_fence();
+                double z0 = 0.0, z1 = 0.0;
+#pragma unroll
+                for (int o = 0; o < HC; o += 2) {
+                    const double2 vv = ys[o >> 1];
+                    z0 = fma(vv.x, Ereg[o], z0);
+                    z1 = fma(vv.y, Ereg[o + 1], z1);
+                }
+                double z = z0 + z1;
+                if (H == 2) z = add_across_32(z);
+                const double q = z * (BWD ? e[i].x : e[i].y);
+                qn[i] = q;
+                r += BWD ? -1 : 1;
+                if (cval && g == 0) ring[r * RS + c] = q;
+                lds_wave_fence();
+            } else {
+                qn[i] = 0.0;
+            }
         }
-        prevsum = ysum;
-        const double q = z * (BWD ? e.x : e.y);
-        r += BWD ? -1 : 1;
-        if (cval && g == 0) ring[r * RS + c] = q;
-        lds_wave_fence();
+        t = tn;
+#pragma unroll
+        for (int i = 0; i < MB; ++i) e[i] = en[i];
         if (__builtin_expect(t == tstart, 0)) record(t, ck1 + (size_t)istart * ckstride, ckY1 + istart);
-    };
-    // positions s0+1 .. hi (forward) or s0-1 .. lo (backward), PFW rows prefetched ahead
-    const int nsteps = BWD ? s0 - lo : hi - s0;
-    double2 qe[PFW];
-#pragma unroll
-    for (int u = 0; u < PFW; ++u) {
-        const int n = min(1 + u, nsteps);
-        qe[u] = EIc[(size_t)(BWD ? s0 - n : s0 + n) * C];
     }
-    int n = 1;
-    for (; n + PFW - 1 <= nsteps; n += PFW) {
-#pragma unroll
-        for (int u = 0; u < PFW; ++u) {
-            const double2 e = qe[u];
-            const int n2 = min(n + u + PFW, nsteps);
-            qe[u] = EIc[(size_t)(BWD ? s0 - n2 : s0 + n2) * C];
-            one(BWD ? s0 - (n + u) : s0 + (n + u), e);
-        }
-    }
-    for (; n <= nsteps; ++n) {
-        const int t = BWD ? s0 - n : s0 + n;
-        one(t, EIc[(size_t)t * C]);
-    }
-    record(BWD ? lo : hi, ck2 + (size_t)iend * ckstride, ckY2 + iend);
+    record(tend, ck2 + (size_t)iend * ckstride, ckY2 + iend);
 }
 
 template <int CT, int NKW>
@@ -1734,50 +1776,65 @@ __global__ __launch_bounds__(64) void k_spec_cmp(Params p, int tier)
     }
 }
 
-// Accept or reject each (sequence, direction); chain the scale factors.  grid (B, ndir).
-__global__ void k_spec_fix(Params p, int ndir, int tier)
+// Accept or reject each (sequence, direction); chain the scale factors.  grid (B, 2), one
+// wave: lane l owns a contiguous run of boundaries in scan order, the running log2 factor
+// is a fixed-order prefix sum (per lane, then across lanes).
+__global__ __launch_bounds__(64) void k_spec_fix(Params p, int ndir, int tier)
 {
-    if (threadIdx.x != 0) return;
-    const int b = blockIdx.x, dir = blockIdx.y;
+    const int b = blockIdx.x, dir = blockIdx.y, lane = threadIdx.x;
     if (tier > 0 && p.spec_ok[b * 2 + dir]) return;
     const int L = p.hdr[b].L, N = p.N, C = p.C, KC = p.K * C;
     const int nint = (L + p.Delta - 1) / p.Delta;
     const size_t so = ((size_t)b * 2 + dir) * (N + 1);
     if (dir >= ndir) {  // direction not run in this call
-        p.spec_ok[b * 2 + dir] = 0;
-        p.spec_err[so] = -1.0;
+        if (lane == 0) {
+            p.spec_ok[b * 2 + dir] = 0;
+            p.spec_err[so] = -1.0;
+        }
         return;
     }
-    bool ok = true;
-    double worst = 0.0;
-    for (int j = 1; j < nint; ++j) worst = fmax(worst, p.spec_err[so + j]);
-    ok = worst <= SPEC_TOL;
+    const int nb = nint > 1 ? nint - 1 : 0;  // boundaries 1 .. nint-1
+    const int per = (nb + 63) / 64;
+    const int i0 = min(lane * per, nb), i1 = min(i0 + per, nb);
+    // i-th boundary in scan order: ascending for the forward scan, descending for the backward one
+    auto jof = [&](int i) { return dir == 0 ? 1 + i : nint - 1 - i; };
+    double s = 0.0, worst = 0.0;
+    for (int i = i0; i < i1; ++i) {
+        s += p.spec_lr[so + jof(i)];
+        worst = fmax(worst, p.spec_err[so + jof(i)]);
+    }
+    double inc = s;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const double v = __shfl_up(inc, off);
+        if (lane >= off) inc += v;
+    }
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) worst = fmax(worst, __shfl_xor(worst, off));
+    const double total = __shfl(inc, 63);
+    double *ckY = (dir ? p.ckYB : p.ckYA) + (size_t)b * (N + 1);
+    double acc = inc - s;  // log2 of the factor between the true state and the warm-up state
+    for (int i = i0; i < i1; ++i) {
+        acc += p.spec_lr[so + jof(i)];
+        ckY[jof(i)] += acc;
+    }
+    if (lane != 0) return;
+    bool ok = worst <= SPEC_TOL;
     p.spec_err[so] = worst;  // entry 0 is no boundary: it carries the report value
     if (dir == 0) {
-        double acc = 0.0;  // log2 of the factor between the true state and the warm-up state
-        for (int j = 1; j < nint; ++j) {
-            acc += p.spec_lr[so + j];
-            p.ckYA[(size_t)b * (N + 1) + j] += acc;
-        }
         double lz;
         if (nint == 0) {
             lz = log((double)C);
         } else {
             const double *e = p.ckA2 + ((size_t)b * (N + 1) + nint) * ((size_t)KC + C);
-            double s = 0.0;
-            for (int i = 0; i < C; ++i) s += e[KC + i];
-            lz = (p.ckYA2[(size_t)b * (N + 1) + nint] + acc) * LN2 + log(s);
-            ok = ok && s > 0.0 && lz == lz;
+            double sum = 0.0;
+            for (int i = 0; i < C; ++i) sum += e[KC + i];
+            lz = (p.ckYA2[(size_t)b * (N + 1) + nint] + total) * LN2 + log(sum);
+            ok = ok && sum > 0.0 && lz == lz;
         }
         if (ok) {
             p.hdr[b].logZ = lz;
             p.logz[b] = (float)lz;
-        }
-    } else {
-        double acc = 0.0;
-        for (int j = nint - 1; j >= 1; --j) {
-            acc += p.spec_lr[so + j];
-            p.ckYB[(size_t)b * (N + 1) + j] += acc;
         }
     }
     p.spec_ok[b * 2 + dir] = ok ? 1 : 0;
