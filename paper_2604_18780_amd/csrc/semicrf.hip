@@ -1154,62 +1154,139 @@ __global__ __launch_bounds__(NT) void k_interval(Params p)
 }
 
 // ---------------------------------------------------------------------------
-// Per-interval backward work, throughput-oriented variant (C <= 64): ONE WAVE per
-// task, no barriers.  The interval stage has hundreds of independent tasks, so
-// unlike the scans it is bound by instruction throughput, which several
-// independent single-wave workgroups per compute unit fill better than one
-// multi-wave workgroup that synchronises every step.  A lane (g, c) owns the
-// durations k = 1+g, 1+g+GW, ... of label c (its W strip and its grad_dur
-// accumulators stay in registers for the whole task) and, as in the scan's tip,
-// its part of the transition row (Etr) plus the matching grad_trans accumulators.
-// The ring is stored twice with a compile-time row stride (immediate offsets).
+// One-wave kernels (interval stage and chunk-parallel scan): shared geometry.
+//
+// Window.  The last KW >= K messages of a scan live in a LINEAR LDS buffer of KW + M rows
+// of exactly CT doubles: the newest row moves up (forward) or down (backward) by one per
+// position, every read is base + compile-time offset, and when the buffer's end is
+// reached the window is moved back (KW*CT/64 loads and stores per lane every ~M positions).
+//
+// Time blocking.  LDS bandwidth, not arithmetic, bounds a scan that re-reads its whole
+// window at every position (8 bytes per multiply-add).  Positions are therefore taken in
+// blocks of MB: lane (g, c) owns the window entries at distances d = g*NK .. g*NK+NK-1 from
+// the newest message of label c, reads each ONCE per block and uses it for all MB positions
+// of the block (weights W[d+1] .. W[d+MB]: a register strip of NK+MB-1 values).  What the
+// block's own new messages contribute to its later positions (durations 1..MB-1) is added
+// from registers while the positions are finished one after the other.
 // ---------------------------------------------------------------------------
-constexpr int PFW = 4;  // prefetch distance (steps) of the per-position rows
+constexpr int MB = 4;  // positions per time block
 
-__host__ __device__ inline int wave_ring_pad(int K, int CTP, int NKW)
+// Window entries per lane: NKW, plus one when a half-wave holds several lane groups, so
+// that the groups' rows fall into different LDS banks.
+__host__ __device__ constexpr int wave_nk(int CT, int NKW)
 {
-    const int kmax = (64 / CTP) * NKW;
-    return kmax > K ? kmax - K : 0;
+    return NKW + ((64 / pow2_ge8(CT)) > 2 ? 1 : 0);
 }
 
-__host__ __device__ inline size_t wave_lds_doubles(int K, int CTP, int NKW)
+// Rows of slack behind the sliding window.
+__host__ __device__ constexpr int lin_slack(int KW)
 {
-    return (size_t)(2 * K + wave_ring_pad(K, CTP, NKW)) * CTP + 2 * (size_t)CTP;
+    return KW / 4 < 8 ? 8 : ((KW / 4 + 3) & ~3);
 }
 
+__host__ __device__ constexpr size_t wave_lds_doubles(int CT, int NKW)
+{
+    const int CTP = pow2_ge8(CT);
+    const int KW = wave_nk(CT, NKW) * (64 / CTP);
+    return (size_t)(KW + lin_slack(KW)) * CT + (size_t)(CTP - CT) + 2 * (size_t)CTP;
+}
+
+// Geometry and the window operations shared by the one-wave kernels.
+template <int CT, int NKW>
+struct WaveWin {
+    static constexpr int CTP = pow2_ge8(CT);
+    static constexpr int RS = CT;
+    static constexpr int GW = 64 / CTP;
+    static constexpr int NK = wave_nk(CT, NKW);
+    static constexpr int KW = NK * GW;
+    static constexpr int M = lin_slack(KW);
+    static constexpr int ROWS = KW + M;
+    static constexpr int RTOT = ROWS * RS + (CTP - CT);  // lanes c >= C read (and ignore) past a row's end
+    static constexpr int H = CT <= 32 ? 2 : 1;
+    static constexpr int HC = CT / H;
+
+    // every entry of label c times 2^sft (each lane scales its own label's column)
+    static __device__ __forceinline__ void rescale(double *ring, int g, int c, bool cval, int sft)
+    {
+        if (cval) {
+            double *q = ring + g * RS + c;
+#pragma unroll 8
+            for (int row = g; row < ROWS; row += GW, q += GW * RS) *q = fmin(ldexp(*q, sft), DBL_MAX);
+        }
+        lds_wave_fence();
+    }
+
+    // Move the live window (newest row r) back to the start of the buffer; returns the new r.
+    // Chunk order keeps the sources ahead of the stores.
+    template <bool BWD>
+    static __device__ __forceinline__ int move(double *ring, int lane, int r)
+    {
+        constexpr int NCP = (KW * RS + 63) / 64;
+        const int shift = (BWD ? M - r : r - (KW - 1)) * RS;  // doubles, > 0
+        const int first = (BWD ? r : r - (KW - 1)) * RS;      // lowest double of the live window
+        for (int u = 0; u < NCP; ++u) {
+            const int i = (BWD ? NCP - 1 - u : u) * 64 + lane;
+            double v = 0.0;
+            if (i < KW * RS) v = ring[first + i];
+            lds_wave_fence();
+            if (i < KW * RS) ring[first + i + (BWD ? shift : -shift)] = v;
+            lds_wave_fence();
+        }
+        return BWD ? M : KW - 1;
+    }
+
+    // Checkpoint layout: message of position t' at slot t' mod K.  d = distance of slot sl
+    // from the newest position t.
+    template <bool BWD>
+    static __device__ __forceinline__ int slot_dist(int sl, int tm, int K)
+    {
+        int d = BWD ? sl - tm : tm - sl;
+        if (d < 0) d += K;
+        return d;
+    }
+};
+
+// ---------------------------------------------------------------------------
+// Per-interval backward work (Algorithm 3 body), throughput-oriented variant: ONE WAVE per
+// task, no barriers.  The interval stage has hundreds of independent tasks, so unlike a
+// sequential scan it is bound by instruction and LDS throughput, which several independent
+// single-wave workgroups per compute unit fill better than one multi-wave workgroup that
+// synchronises every step.  A lane (g, c) keeps its strip of W, the matching grad_dur
+// accumulators, its part of the transition row/column and the matching grad_trans
+// accumulators in registers for the whole task.
+// ---------------------------------------------------------------------------
 template <int CT, int NKW>
 __global__ __launch_bounds__(64) void k_interval_wave(Params p)
 {
-    constexpr int CTP = pow2_ge8(CT);
-    constexpr int RS = CTP;
-    constexpr int GW = 64 / CTP;
-    constexpr int H = CT <= 32 ? 2 : 1;
-    constexpr int HC = CT / H;
+    using G = WaveWin<CT, NKW>;
+    constexpr int CTP = G::CTP, RS = G::RS, NK = G::NK, KW = G::KW, M = G::M, ROWS = G::ROWS;
+    constexpr int RTOT = G::RTOT, H = G::H, HC = G::HC;
     extern __shared__ double lds_raw[];
     const int lane = threadIdx.x;
     const int K = p.K, C = p.C, KC = K * C, CC = C * C;
-    const int XP = wave_ring_pad(K, CTP, NKW);
-    const int RTOT = (2 * K + XP) * RS;
-    double *ring = lds_raw;          // [2K+XP][RS]
+    double *ring = lds_raw;          // [ROWS][RS] (+ pad)
     double *yv = ring + RTOT;        // [CTP]
-    int *sc = (int *)(yv + CTP);     // [CTP]
     const int Delta = p.Delta, N = p.N;
     const size_t ckstride = (size_t)KC + C;
     const int c = lane % CTP, g = lane / CTP;
     const int hh = H == 2 ? (lane >> 5) : 0;
     const bool cval = c < C;
     const int cc = cval ? c : 0;
+    const bool writer = cval && g == 0;  // one lane per label
     double2 *aloc = (double2 *)p.aloc + (size_t)blockIdx.x * Delta * C;
     double *alocY = p.alocY + (size_t)blockIdx.x * Delta;
 
     // task-invariant registers
-    double wreg[NKW];   // W[k,c], k = 1 + g + j*GW in backward order; reversed for the forward phase
-    double Ereg[HC];    // this lane's part of the transition column (forward) / row (backward)
+    double wx[NK + MB - 1];  // W[g*NK + jj + 1, c]
 #pragma unroll
-    for (int j = 0; j < NKW; ++j) {
-        const int k = 1 + g + j * GW;
-        wreg[j] = (cval && k <= K) ? p.W[(size_t)(k - 1) * C + c] : 0.0;
+    for (int jj = 0; jj < NK + MB - 1; ++jj) {
+        const int k = g * NK + jj + 1;
+        wx[jj] = (cval && k <= K) ? p.W[(size_t)(k - 1) * C + c] : 0.0;
     }
+    double wn[MB - 1];       // W[1..MB-1, c]: durations inside a block
+#pragma unroll
+    for (int jj = 0; jj < MB - 1; ++jj) wn[jj] = (cval && jj + 1 <= K) ? p.W[(size_t)jj * C + c] : 0.0;
+    double Ereg[HC];         // this lane's part of the transition column (forward) / row (backward)
     auto load_etr = [&](bool backward) {
 #pragma unroll
         for (int i = 0; i < HC; ++i) {
@@ -1220,12 +1297,10 @@ __global__ __launch_bounds__(64) void k_interval_wave(Params p)
         }
     };
     const double2 *ys = (const double2 *)__builtin_assume_aligned(yv + hh * HC, 16);
-
-    auto rescale = [&](int sft) {  // every ring entry of label c times 2^sc[c]
-        sc[c] = sft;
-        lds_wave_fence();
-        for (int i = lane; i < RTOT; i += 64) ring[i] = fmin(ldexp(ring[i], sc[i % RS]), DBL_MAX);
-        lds_wave_fence();
+    auto yv_sum = [&]() {
+        double s = 0.0;
+        for (int i = 0; i < CT; ++i) s += yv[i];
+        return s;
     };
 
     const int ntask = p.B * N;
@@ -1246,214 +1321,252 @@ __global__ __launch_bounds__(64) void k_interval_wave(Params p)
         for (int i = lane; i < RTOT; i += 64) ring[i] = 0.0;
         if (lane < CTP) yv[lane] = 0.0;
         lds_wave_fence();
+        int r = KW - 1;  // row of the newest message
         {
             const double *ck = p.ckA + ((size_t)b * (N + 1) + iv) * ckstride;
+            const int tm = t0 % K;
             for (int i = lane; i < KC; i += 64) {
-                const double v = ck[i];
                 const int sl = i / C, col = i % C;
-                ring[(XP + sl) * RS + col] = v;
-                ring[(XP + sl + K) * RS + col] = v;
+                ring[(r - G::template slot_dist<false>(sl, tm, K)) * RS + col] = ck[i];
             }
             if (lane < C) yv[lane] = ck[KC + lane];
         }
         lds_wave_fence();
         double Y = p.ckYA[(size_t)b * (N + 1) + iv];
-        double prevsum = 0.0;
-        for (int i = 0; i < CT; ++i) prevsum += yv[i];
-        int slot = t0 % K;
-        if (g == 0 && hh == 0 && cval)
-            aloc[c] = make_double2(yv[c], ring[(size_t)(XP + slot) * RS + c]);
+        if (writer) aloc[c] = make_double2(yv[c], ring[r * RS + c]);
         if (lane == 0) alocY[0] = Y;
         {
-            double2 qe[PFW];
+            const int tend = t1 - 1;  // alpha of position t1 belongs to the next interval
+            const int rdoff = -(g * NK + NK - 1) * RS + c;
+            int t = t0;
+            auto load_rows = [&](double2 (&e)[MB], const int tfrom) {
 #pragma unroll
-            for (int j = 0; j < PFW; ++j) qe[j] = EIc[(size_t)min(t0 + 1 + j, L) * C];
-            auto fwd_one = [&](const int t, const double2 e) {
-                if (__builtin_expect((t & Jm) == 0, 0)) {
-                    const int ex = safe_exponent(prevsum);
-                    Y += (double)ex;
-                    const int jn = t / J;
-                    rescale(nbc[(size_t)jn * C] - nbc[(size_t)(jn - 1) * C] - ex);
-                }
-                const int ps = slot + 1 == K ? 0 : slot + 1;
-                // x(c) = sum_k W[k,c] q_{t-k}(c); this lane's strip, longest duration first
-                const double *base = ring + (size_t)(XP + ps + K - (1 + g) - (NKW - 1) * GW) * RS + c;
-                double v[NKW];
-#pragma unroll
-                for (int j = 0; j < NKW; ++j) v[j] = base[j * GW * RS];
-                double a0 = 0.0, a1 = 0.0;
-#pragma unroll
-                for (int j = 0; j < NKW; j += 2) {
-                    a0 = fma(wreg[NKW - 1 - j], v[j], a0);
-                    a1 = fma(wreg[NKW - 2 - j], v[j + 1], a1);
-                }
-                const double x = group_sum<CTP>(a0 + a1);
-                const double y = x * e.x;
-                yv[c] = y;
-                lds_wave_fence();
-                double z0 = 0.0, z1 = 0.0, ysum = 0.0;
-#pragma unroll
-                for (int i = 0; i < HC; i += 2) {
-                    const double2 vv = ys[i >> 1];
-                    z0 = fma(vv.x, Ereg[i], z0);
-                    z1 = fma(vv.y, Ereg[i + 1], z1);
-                    ysum += vv.x + vv.y;
-                }
-                double z = z0 + z1;
-                if (H == 2) {
-                    z = add_across_32(z);
-                    ysum = add_across_32(ysum);
-                }
-                prevsum = ysum;
-                const double q = z * e.y;
-                double *rw = ring + (size_t)(XP + ps) * RS + c;
-                rw[0] = q;
-                rw[(size_t)K * RS] = q;
-                lds_wave_fence();
-                slot = ps;
-                if (g == 0 && hh == 0 && cval) aloc[(size_t)(t - t0) * C + c] = make_double2(y, q);
-                if (lane == 0) alocY[t - t0] = Y;
+                for (int i = 0; i < MB; ++i) e[i] = EIc[(size_t)min(tfrom + 1 + i, L) * C];
             };
-            int t = t0 + 1;
-            for (; t + PFW - 1 < t1; t += PFW) {
-#pragma unroll
-                for (int j = 0; j < PFW; ++j) {
-                    const double2 e = qe[j];
-                    qe[j] = EIc[(size_t)min(t + j + PFW, L) * C];
-                    fwd_one(t + j, e);
+            double2 e[MB];
+            load_rows(e, t);
+            while (t < tend) {
+                int nb = min(tend - t, MB);
+                nb = min(nb, J - ((t + 1) & Jm));  // only a block's first position may cross a scaling boundary
+                if (__builtin_expect(((t + 1) & Jm) == 0, 0)) {
+                    const int ex = safe_exponent(yv_sum());
+                    Y += (double)ex;
+                    const int jn = (t + 1) / J;
+                    G::rescale(ring, g, c, cval, nbc[(size_t)jn * C] - nbc[(size_t)(jn - 1) * C] - ex);
                 }
+                if (__builtin_expect(r + MB > ROWS - 1, 0)) r = G::template move<false>(ring, lane, r);
+                const double *base = ring + r * RS + rdoff;
+                double acc[MB];
+#pragma unroll
+                for (int i = 0; i < MB; ++i) acc[i] = 0.0;
+#pragma unroll
+                for (int jj = 0; jj < NK; ++jj) {
+                    const double v = base[(NK - 1 - jj) * RS];  // distance g*NK + jj from the newest
+#pragma unroll
+                    for (int i = 0; i < MB; ++i) acc[i] = fma(wx[jj + i], v, acc[i]);
+                }
+#pragma unroll
+                for (int i = 0; i < MB; ++i) acc[i] = group_sum<CTP>(acc[i]);
+                double qn[MB];
+#pragma unroll
+                for (int i = 0; i < MB; ++i) {
+                    if (i < nb) {
+                        double x = acc[i];
+#pragma unroll
+                        for (int jn = 0; jn < i; ++jn) x = fma(wn[i - 1 - jn], qn[jn], x);
+                        const double y = x * e[i].x;
+                        if (cval) yv[c] = y;
+                        lds_wave_fence();
+                        double z0 = 0.0, z1 = 0.0;
+#pragma unroll
+                        for (int o = 0; o < HC; o += 2) {
+                            const double2 vv = ys[o >> 1];
+                            z0 = fma(vv.x, Ereg[o], z0);
+                            z1 = fma(vv.y, Ereg[o + 1], z1);
+                        }
+                        double z = z0 + z1;
+                        if (H == 2) z = add_across_32(z);
+                        const double q = z * e[i].y;
+                        qn[i] = q;
+                        ++r;
+                        if (writer) {
+                            ring[r * RS + c] = q;
+                            aloc[(size_t)(t + 1 + i - t0) * C + c] = make_double2(y, q);
+                        }
+                        if (lane == 0) alocY[t + 1 + i - t0] = Y;
+                        lds_wave_fence();
+                    } else {
+                        qn[i] = 0.0;
+                    }
+                }
+                t += nb;
+                load_rows(e, t);  // the next block's rows (first use a block's window pass later)
             }
-            for (; t < t1; ++t) fwd_one(t, EIc[(size_t)t * C]);
         }
 
         // ============================ backward pass over [t0, t1) ============================
         __threadfence_block();  // this wave's aloc / alocY rows are read back by all of its lanes
         load_etr(true);
         for (int i = lane; i < RTOT; i += 64) ring[i] = 0.0;
+        if (lane < CTP) yv[lane] = 0.0;
         lds_wave_fence();
+        r = M;
         double Yb;
         if (t1 == L) {  // beta_L = 1: v_L = E_L, scale reference sum = 1
-            if (g == 0 && hh == 0 && cval) {
-                const double v = EIc[(size_t)L * C].x;
-                ring[(size_t)(L % K) * RS + c] = v;
-                ring[(size_t)(L % K + K) * RS + c] = v;
-            }
-            prevsum = 1.0;
+            if (writer) ring[r * RS + c] = EIc[(size_t)L * C].x;
+            if (lane == 0) yv[0] = 1.0;
             Yb = 0.0;
         } else {
             const int ci = t1 / Delta;
             const double *ck = p.ckB + ((size_t)b * (N + 1) + ci) * ckstride;
+            const int tm = t1 % K;
             for (int i = lane; i < KC; i += 64) {
-                const double v = ck[i];
                 const int sl = i / C, col = i % C;
-                ring[sl * RS + col] = v;
-                ring[(sl + K) * RS + col] = v;
+                ring[(r + G::template slot_dist<true>(sl, tm, K)) * RS + col] = ck[i];
             }
-            prevsum = 0.0;
-            for (int i = 0; i < C; ++i) prevsum += ck[KC + i];
+            if (lane < C) yv[lane] = ck[KC + lane];
             Yb = p.ckYB[(size_t)b * (N + 1) + ci];
         }
         lds_wave_fence();
-        slot = t1 % K;
-        double accD[NKW], accT[HC];
+        double dx[NK + MB - 1];  // sum_t coef_t(c) v_{t+k}(c), k = g*NK + jj + 1 (times W[k,c] at the end)
+        double dn[MB - 1];       // the same for k = 1..MB-1 from inside the blocks (lanes g == 0)
+        double accT[HC];
 #pragma unroll
-        for (int j = 0; j < NKW; ++j) accD[j] = 0.0;
+        for (int jj = 0; jj < NK + MB - 1; ++jj) dx[jj] = 0.0;
+#pragma unroll
+        for (int jj = 0; jj < MB - 1; ++jj) dn[jj] = 0.0;
 #pragma unroll
         for (int i = 0; i < HC; ++i) accT[i] = 0.0;
         double R = 0.0, sR = 0.0;
         double kappa = exp((alocY[t1 - 1 - t0] + Yb) * LN2 - logZ);
         {
-            double2 qe[PFW], qa[PFW];
-#pragma unroll
-            for (int j = 0; j < PFW; ++j) {
-                const int t = max(t1 - 1 - j, t0);
-                qe[j] = EIc[(size_t)t * C];
-                qa[j] = aloc[(size_t)(t - t0) * C + cc];
-            }
+            const int rdoff = g * NK * RS + c;
             float *gout = p.grad_emis + ((size_t)b * p.T) * C + cc;
-            auto bwd_one = [&](const int t, const double2 e, const double2 aq) {
-                if (__builtin_expect(((t + 1) & Jm) == 0, 0)) {
-                    const int ex = safe_exponent(prevsum);
-                    Yb += (double)ex;
-                    const int jn = t / J;
-                    rescale(-(nbc[(size_t)jn * C] - nbc[(size_t)(jn + 1) * C]) - ex);
-                    kappa = exp((alocY[t - t0] + Yb) * LN2 - logZ);
-                }
-                const int ps = slot == 0 ? K - 1 : slot - 1;
-                const double ahat = cval ? aq.x : 0.0, qhat = cval ? aq.y : 0.0;
-                const double coef = qhat * kappa;
-                // S(c) = sum_k W[k,c] v_{t+k}(c); every product is also a duration marginal
-                const double *base = ring + (size_t)(ps + 1 + g) * RS + c;
-                double v[NKW];
+            int t = t1;
+            auto load_rows = [&](double2 (&e)[MB], double2 (&aq)[MB], const int tfrom) {
 #pragma unroll
-                for (int j = 0; j < NKW; ++j) v[j] = base[j * GW * RS];
-                double a0 = 0.0, a1 = 0.0;
-#pragma unroll
-                for (int j = 0; j < NKW; j += 2) {
-                    const double p0 = wreg[j] * v[j], p1 = wreg[j + 1] * v[j + 1];
-                    a0 += p0;
-                    a1 += p1;
-                    accD[j] = fma(coef, p0, accD[j]);
-                    accD[j + 1] = fma(coef, p1, accD[j + 1]);
+                for (int i = 0; i < MB; ++i) {
+                    const int tt = max(tfrom - 1 - i, t0);
+                    e[i] = EIc[(size_t)tt * C];
+                    aq[i] = aloc[(size_t)(tt - t0) * C + cc];
                 }
-                const double x = group_sum<CTP>(a0 + a1);
-                const double y = x * e.y;  // p_t(c)
-                yv[c] = y;
-                lds_wave_fence();
-                const double ak = ahat * kappa;
-                double z0 = 0.0, z1 = 0.0, ysum = 0.0;
-#pragma unroll
-                for (int i = 0; i < HC; i += 2) {
-                    const double2 vv = ys[i >> 1];
-                    z0 = fma(vv.x, Ereg[i], z0);
-                    z1 = fma(vv.y, Ereg[i + 1], z1);
-                    ysum += vv.x + vv.y;
-                    accT[i] = fma(ak, vv.x, accT[i]);
-                    accT[i + 1] = fma(ak, vv.y, accT[i + 1]);
-                }
-                double z = z0 + z1;
-                if (H == 2) {
-                    z = add_across_32(z);
-                    ysum = add_across_32(ysum);
-                }
-                prevsum = ysum;
-                const double q = z * e.x;  // v_t(c) = b_t(c) E_t(c)
-                double *rw = ring + (size_t)ps * RS + c;
-                rw[0] = q;
-                rw[(size_t)K * RS] = q;
-                lds_wave_fence();
-                slot = ps;
-                const double outv = coef * x;
-                const double inv = t >= 1 ? ak * z : 0.0;
-                if (g == 0 && hh == 0 && cval) gout[(size_t)t * C] = (float)R;
-                sR += R;
-                R += outv - inv;
             };
-            int t = t1 - 1;
-            for (; t - (PFW - 1) >= t0; t -= PFW) {
-#pragma unroll
-                for (int j = 0; j < PFW; ++j) {
-                    const double2 e = qe[j], aq = qa[j];
-                    const int tn = max(t - j - PFW, t0);
-                    qe[j] = EIc[(size_t)tn * C];
-                    qa[j] = aloc[(size_t)(tn - t0) * C + cc];
-                    bwd_one(t - j, e, aq);
+            double2 e[MB], aq[MB];
+            load_rows(e, aq, t);
+            while (t > t0) {
+                int nb = min(t - t0, MB);
+                nb = min(nb, ((t - 1) & Jm) + 1);
+                if (__builtin_expect((t & Jm) == 0, 0)) {
+                    const int ex = safe_exponent(yv_sum());
+                    Yb += (double)ex;
+                    const int jn = (t - 1) / J;
+                    G::rescale(ring, g, c, cval, -(nbc[(size_t)jn * C] - nbc[(size_t)(jn + 1) * C]) - ex);
+                    kappa = exp((alocY[t - 1 - t0] + Yb) * LN2 - logZ);
                 }
+                if (__builtin_expect(r < MB, 0)) r = G::template move<true>(ring, lane, r);
+                double coef[MB], ak[MB];
+#pragma unroll
+                for (int i = 0; i < MB; ++i) {
+                    const bool on = cval && i < nb;
+                    coef[i] = on ? aq[i].y * kappa : 0.0;  // q_t(c) kappa
+                    ak[i] = on ? aq[i].x * kappa : 0.0;    // a_t(c) kappa
+                }
+                // x_i(c) = sum_k W[k,c] v_{t_i+k}(c); every product is also a duration marginal
+                const double *base = ring + r * RS + rdoff;
+                double acc[MB];
+#pragma unroll
+                for (int i = 0; i < MB; ++i) acc[i] = 0.0;
+#pragma unroll
+                for (int jj = 0; jj < NK; ++jj) {
+                    const double v = base[jj * RS];  // distance g*NK + jj from the newest
+#pragma unroll
+                    for (int i = 0; i < MB; ++i) {
+                        acc[i] = fma(wx[jj + i], v, acc[i]);
+                        dx[jj + i] = fma(coef[i], v, dx[jj + i]);
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < MB; ++i) acc[i] = group_sum<CTP>(acc[i]);
+                double qn[MB];
+#pragma unroll
+                for (int i = 0; i < MB; ++i) {
+                    if (i < nb) {
+                        const int tt = t - 1 - i;
+                        double x = acc[i];
+                        const double cg = g == 0 ? coef[i] : 0.0;
+#pragma unroll
+                        for (int jn = 0; jn < i; ++jn) {
+                            x = fma(wn[i - 1 - jn], qn[jn], x);
+                            dn[i - 1 - jn] = fma(cg, qn[jn], dn[i - 1 - jn]);
+                        }
+                        const double y = x * e[i].y;  // p_t(c)
+                        if (cval) yv[c] = y;
+                        lds_wave_fence();
+                        double z0 = 0.0, z1 = 0.0;
+#pragma unroll
+                        for (int o = 0; o < HC; o += 2) {
+                            const double2 vv = ys[o >> 1];
+                            z0 = fma(vv.x, Ereg[o], z0);
+                            z1 = fma(vv.y, Ereg[o + 1], z1);
+                            accT[o] = fma(ak[i], vv.x, accT[o]);
+                            accT[o + 1] = fma(ak[i], vv.y, accT[o + 1]);
+                        }
+                        double z = z0 + z1;
+                        if (H == 2) z = add_across_32(z);
+                        const double q = z * e[i].x;  // v_t(c) = b_t(c) E_t(c)
+                        qn[i] = q;
+                        --r;
+                        if (writer) {
+                            ring[r * RS + c] = q;
+                            gout[(size_t)tt * C] = (float)R;
+                        }
+                        lds_wave_fence();
+                        const double outv = coef[i] * x;
+                        const double inv = tt >= 1 ? ak[i] * z : 0.0;
+                        sR += R;
+                        R += outv - inv;
+                    } else {
+                        qn[i] = 0.0;
+                    }
+                }
+                t -= nb;
+                load_rows(e, aq, t);
             }
-            for (; t >= t0; --t) bwd_one(t, EIc[(size_t)t * C], aloc[(size_t)(t - t0) * C + cc]);
         }
-        // ---- partials of this task
+        // ---- partials of this task.  Duration sums: the strips of neighbouring lane groups
+        // overlap by MB-1 durations; they are combined through LDS in a fixed order.
+        lds_wave_fence();
+        double *tmp = ring;  // [K][CT]
+        for (int i = lane; i < K * CT; i += 64) tmp[i] = 0.0;
+        lds_wave_fence();
+#pragma unroll
+        for (int jj = 0; jj < NK; ++jj) {
+            const int k = g * NK + jj + 1;
+            if (cval && k <= K) tmp[(k - 1) * CT + c] = dx[jj];
+        }
+        lds_wave_fence();
+#pragma unroll
+        for (int jj = NK; jj < NK + MB - 1; ++jj) {
+            const int k = g * NK + jj + 1;
+            if (cval && k <= K) tmp[(k - 1) * CT + c] += dx[jj];
+        }
+        lds_wave_fence();
+#pragma unroll
+        for (int jj = 0; jj < MB - 1; ++jj)
+            if (writer && jj + 1 <= K) tmp[jj * CT + c] += dn[jj];
+        lds_wave_fence();
         double *pD = p.partD + ((size_t)b * N + iv) * KC;
 #pragma unroll
-        for (int j = 0; j < NKW; ++j) {
-            const int k = 1 + g + j * GW;
-            if (cval && k <= K) pD[(size_t)(k - 1) * C + c] = accD[j];
+        for (int jj = 0; jj < NK; ++jj) {
+            const int k = g * NK + jj + 1;
+            if (cval && k <= K) pD[(size_t)(k - 1) * C + c] = wx[jj] * tmp[(k - 1) * CT + c];
         }
+        lds_wave_fence();
         double *pT = p.partTr + ((size_t)b * N + iv) * CC;
 #pragma unroll
         for (int i = 0; i < HC; ++i) {
             const int o = hh * HC + i;
-            const bool owner = H == 2 ? lane == hh * 32 + c : true;  // one lane per (label, half)
+            const bool owner = H == 2 ? lane == hh * 32 + c : g == 0;  // one lane per (label, half)
             if (cval && owner && o < C) pT[(size_t)c * C + o] = accT[i];
         }
         if (lane < C) {
@@ -1486,61 +1599,18 @@ __global__ __launch_bounds__(64) void k_interval_wave(Params p)
 // ---------------------------------------------------------------------------
 constexpr double SPEC_TOL = 1e-10;
 
-constexpr int MB = 4;  // positions per time block of the one-wave scan
-
-// Entries of the message window per lane: NKW, plus one when a half-wave holds several lane
-// groups, so that the groups' rows fall into different LDS banks.
-__host__ __device__ constexpr int spec_nk(int CT, int NKW)
-{
-    return NKW + ((64 / pow2_ge8(CT)) > 2 ? 1 : 0);
-}
-
-// Rows of slack behind the sliding window.
-__host__ __device__ constexpr int lin_slack(int KW)
-{
-    return KW / 4 < 8 ? 8 : ((KW / 4 + 3) & ~3);
-}
-
-__host__ __device__ constexpr size_t spec_lds_doubles(int CT, int NKW)
-{
-    const int CTP = pow2_ge8(CT);
-    const int KW = spec_nk(CT, NKW) * (64 / CTP);
-    return (size_t)(KW + lin_slack(KW)) * CT + (size_t)(CTP - CT) + 2 * (size_t)CTP;
-}
-
-// One scan task of the chunk-parallel scan, one wave.
-//
-// Window.  The last KW >= K messages live in a LINEAR buffer of KW + M rows of exactly CT
-// doubles: the newest row moves up (forward) or down (backward) by one per position, every
-// read is base + compile-time offset, and when the buffer's end is reached the window is
-// moved back (KW*CT/64 loads and stores per lane every ~M positions).
-//
-// Time blocking.  LDS bandwidth, not arithmetic, bounds a scan that re-reads its whole
-// window at every position (8 bytes per multiply-add).  Positions are therefore taken in
-// blocks of MB: lane (g, c) owns the window entries at distances d = g*NK .. g*NK+NK-1 from
-// the newest message, reads each ONCE per block and uses it for all MB positions of the
-// block (weights W[d+1] .. W[d+MB], a register strip of NK+MB-1 values).  What the block's
-// own new messages contribute to its later positions (durations 1..MB-1) is added from
-// registers while the positions are finished one after the other.
+// One scan task of the chunk-parallel scan, one wave (window and time blocking as above).
 template <int CT, int NKW, bool BWD>
 __device__ __forceinline__ void spec_task(const Params &p, double *lds_raw, const int b, const int j,
                                           const int warm)
 {
-    constexpr int CTP = pow2_ge8(CT);
-    constexpr int RS = CT;
-    constexpr int GW = 64 / CTP;
-    constexpr int NK = spec_nk(CT, NKW);
-    constexpr int KW = NK * GW;
-    constexpr int M = lin_slack(KW);
-    constexpr int ROWS = KW + M;
-    constexpr int RTOT = ROWS * RS + (CTP - CT);  // lanes c >= C read (and ignore) past a row's end
-    constexpr int H = CT <= 32 ? 2 : 1;
-    constexpr int HC = CT / H;
+    using G = WaveWin<CT, NKW>;
+    constexpr int CTP = G::CTP, RS = G::RS, NK = G::NK, KW = G::KW, M = G::M, ROWS = G::ROWS;
+    constexpr int RTOT = G::RTOT, H = G::H, HC = G::HC;
     const int lane = threadIdx.x;
     const int K = p.K, C = p.C, KC = K * C;
     double *ring = lds_raw;          // [ROWS][RS] (+ pad)
     double *yv = ring + RTOT;        // [CTP]
-    int *sc = (int *)(yv + CTP);     // [CTP]
     const int Delta = p.Delta, N = p.N;
     const size_t ckstride = (size_t)KC + C;
     const int c = lane % CTP, g = lane / CTP;
@@ -1602,8 +1672,7 @@ __device__ __forceinline__ void spec_task(const Params &p, double *lds_raw, cons
         const int tm = t % K;
         for (int i = lane; i < KC; i += 64) {
             const int sl = i / C, col = i % C;
-            int d = BWD ? sl - tm : tm - sl;
-            if (d < 0) d += K;
+            const int d = G::template slot_dist<BWD>(sl, tm, K);
             ck[i] = ring[(BWD ? r + d : r - d) * RS + col];
         }
         if (lane < C) ck[KC + lane] = yv[lane];
@@ -1642,8 +1711,6 @@ __device__ __forceinline__ void spec_task(const Params &p, double *lds_raw, cons
     while (t != tend) {
         const int nb = block_len(t);
         const int tn = BWD ? t - nb : t + nb;
-        double2 en[MB];
-        load_rows(en, tn);  // the next block's rows, a block ahead
         const int t1 = BWD ? t - 1 : t + 1;
         const bool boundary = BWD ? (t & Jm) == 0 : (t1 & Jm) == 0;
         if (__builtin_expect(boundary, 0)) {
@@ -1654,26 +1721,9 @@ __device__ __forceinline__ void spec_task(const Params &p, double *lds_raw, cons
             const int jn = t1 / J;
             const int sft = BWD ? -(nbc[(size_t)jn * C] - nbc[(size_t)(jn + 1) * C]) - ex
                                 : nbc[(size_t)jn * C] - nbc[(size_t)(jn - 1) * C] - ex;
-            sc[c] = sft;
-            lds_wave_fence();
-            for (int i = lane; i < ROWS * RS; i += 64) ring[i] = fmin(ldexp(ring[i], sc[i % RS]), DBL_MAX);
-            lds_wave_fence();
+            G::rescale(ring, g, c, cval, sft);
         }
-        if (__builtin_expect(BWD ? r < MB : r + MB > ROWS - 1, 0)) {
-            // move the window back to the start; chunk order keeps sources ahead of the stores
-            constexpr int NCP = (KW * RS + 63) / 64;
-            const int shift = (BWD ? M - r : r - (KW - 1)) * RS;  // doubles, > 0
-            const int first = (BWD ? r : r - (KW - 1)) * RS;      // lowest double of the live window
-            for (int u = 0; u < NCP; ++u) {
-                const int i = (BWD ? NCP - 1 - u : u) * 64 + lane;
-                double v = 0.0;
-                if (i < KW * RS) v = ring[first + i];
-                lds_wave_fence();
-                if (i < KW * RS) ring[first + i + (BWD ? shift : -shift)] = v;
-                lds_wave_fence();
-            }
-            r = BWD ? M : KW - 1;
-        }
+        if (__builtin_expect(BWD ? r < MB : r + MB > ROWS - 1, 0)) r = G::template move<BWD>(ring, lane, r);
         // ---- what the window contributes to the MB positions of the block
         const double *base = ring + r * RS + rdoff;
         double acc[MB];
@@ -1717,8 +1767,7 @@ __device__ __forceinline__ void spec_task(const Params &p, double *lds_raw, cons
             }
         }
         t = tn;
-#pragma unroll
-        for (int i = 0; i < MB; ++i) e[i] = en[i];
+        load_rows(e, t);  // the next block's rows (first use a block's window pass later)
         if (__builtin_expect(t == tstart, 0)) record(t, ck1 + (size_t)istart * ckstride, ckY1 + istart);
     }
     record(tend, ck2 + (size_t)iend * ckstride, ckY2 + iend);
@@ -2137,7 +2186,7 @@ int launch_scan(const Params &p, const Plan &pl, hipStream_t st, bool both)
 template <int CT, int NKW>
 int launch_interval_wave(const Params &p, const Plan &pl, hipStream_t st)
 {
-    const size_t lds = wave_lds_doubles(p.K, pow2_ge8(CT), NKW) * sizeof(double);
+    const size_t lds = wave_lds_doubles(CT, NKW) * sizeof(double);
     if (lds > LDS_LIMIT) return 1;
     if (hipFuncSetAttribute((const void *)k_interval_wave<CT, NKW>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
@@ -2151,9 +2200,10 @@ int launch_interval_ct(const Params &p, const Plan &pl, hipStream_t st)
 {
     constexpr int GW = 64 / pow2_ge8(CT);
     const int per_lane = (p.K + GW - 1) / GW;
-    // longer strips (or C > 32) would not fit the register file of one wave
+    // longer strips would not fit the register file of one wave
     if (per_lane <= 16) return launch_interval_wave<CT, 16>(p, pl, st);
     if (per_lane <= 32) return launch_interval_wave<CT, 32>(p, pl, st);
+    if (per_lane <= 64) return launch_interval_wave<CT, 64>(p, pl, st);
     return 1;
 }
 
@@ -2165,6 +2215,7 @@ int launch_interval(const Params &p, const Plan &pl, hipStream_t st)
     else if (C <= 16) rc = launch_interval_ct<16>(p, pl, st);
     else if (C <= 24) rc = launch_interval_ct<24>(p, pl, st);
     else if (C <= 32) rc = launch_interval_ct<32>(p, pl, st);
+    else if (C <= 64) rc = launch_interval_ct<64>(p, pl, st);
     if (rc != 1) return rc;
     if (hipFuncSetAttribute((const void *)k_interval, hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)pl.lds_interval) != hipSuccess)
@@ -2177,7 +2228,7 @@ int launch_interval(const Params &p, const Plan &pl, hipStream_t st)
 template <int CT, int NKW>
 int launch_spec_k(const Params &p, hipStream_t st, bool both, int warm, int tier)
 {
-    const size_t lds = spec_lds_doubles(CT, NKW) * sizeof(double);
+    const size_t lds = wave_lds_doubles(CT, NKW) * sizeof(double);
     if (lds > LDS_LIMIT) return 1;
     if (hipFuncSetAttribute((const void *)k_spec<CT, NKW>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)lds) != hipSuccess)
@@ -2214,7 +2265,7 @@ bool spec_applies(int K, int C)
     const int per_lane = (K + GW - 1) / GW;
     if (per_lane > 64) return false;
     const int NKW = per_lane <= 16 ? 16 : (per_lane <= 32 ? 32 : 64);
-    return spec_lds_doubles(CT, NKW) * sizeof(double) <= LDS_LIMIT;
+    return wave_lds_doubles(CT, NKW) * sizeof(double) <= LDS_LIMIT;
 }
 
 int launch_spec(const Params &p, hipStream_t st, bool both, int warm, int tier)
