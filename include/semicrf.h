@@ -76,15 +76,22 @@ const char *semicrf_strerror(int status);
 
 /*
  * Host only, pure.  Bytes of device workspace the calls below need for these
- * sizes.  ckpt_interval = 0 selects the automatic interval
- * ceil(sqrt(T*K*B/256)), rounded up to a multiple of 8 and clamped to [1,T] (the paper's sqrt(T*K) spacing scaled
- * so that checkpoint memory and per-interval recompute buffers balance when the
- * B*T/interval recompute tasks are spread over the 256 compute units).
+ * sizes.  ckpt_interval = 0 selects the automatic interval: the multiple of 8 within
+ * [max(8, K/2), sqrt(T*K)] (the upper end is the spacing of Algorithm 1) that minimises
+ * the modelled time of the (sequence, interval) tasks, which run in rounds of about one
+ * task per SIMD of the chip; roughly ceil(B*T/1024) when the K-deep window is small.
  * want_grad = 0 sizes for semicrf_logz_fwd / semicrf_cum_scores only.
  * `bytes` is a host pointer.
  */
 int semicrf_workspace_bytes(int B, int T, int K, int C, int ckpt_interval, int want_grad,
                             size_t *bytes);
+
+/*
+ * Host only, pure.  The checkpoint interval (the Delta of Algorithm 1) the calls below
+ * use for these sizes: ckpt_interval itself (clamped to T) when positive, else the
+ * automatic choice described above.  `interval` is a host pointer.
+ */
+int semicrf_ckpt_interval(int B, int T, int K, int C, int ckpt_interval, int *interval);
 
 /*
  * Eq. 1 and Eq. 2: per-sequence baseline and centred prefix sums.

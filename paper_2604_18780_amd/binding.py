@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsemicrf.so")
 EXPORTS = ("semicrf_version", "semicrf_strerror", "semicrf_workspace_bytes",
            "semicrf_cum_scores", "semicrf_logz_fwd", "semicrf_fwd_bwd", "semicrf_fwd_bwd_profiled",
-           "semicrf_scan_report")
+           "semicrf_scan_report", "semicrf_ckpt_interval")
 SEMICRF_CENTER = 1
 SEMICRF_SEQUENTIAL_SCAN = 2
 _lib = None
@@ -55,6 +55,8 @@ def load():
                                     vp, vp, vp, vp, vp, vp]
     lib.semicrf_fwd_bwd_profiled.restype = ci
     lib.semicrf_fwd_bwd_profiled.argtypes = lib.semicrf_fwd_bwd.argtypes + [ctypes.POINTER(vp)]
+    lib.semicrf_ckpt_interval.restype = ci
+    lib.semicrf_ckpt_interval.argtypes = [ci, ci, ci, ci, ci, ctypes.POINTER(ci)]
     lib.semicrf_scan_report.restype = ci
     lib.semicrf_scan_report.argtypes = [vp, sz, ci, ci, ci, ci, ci, ci, vp, vp, vp]
     _lib = lib
@@ -78,6 +80,12 @@ def semicrf_workspace_bytes(B, T, K, C, ckpt_interval=0, want_grad=True) -> int:
     out = ctypes.c_size_t(0)
     _check(load().semicrf_workspace_bytes(B, T, K, C, ckpt_interval, int(bool(want_grad)),
                                           ctypes.byref(out)))
+    return out.value
+
+
+def semicrf_ckpt_interval(B, T, K, C, ckpt_interval=0) -> int:
+    out = ctypes.c_int(0)
+    _check(load().semicrf_ckpt_interval(B, T, K, C, ckpt_interval, ctypes.byref(out)))
     return out.value
 
 

@@ -45,7 +45,7 @@ namespace {
 constexpr int NT = 256;          // threads per workgroup in the scan kernels
 constexpr int PREP_CH = 256;     // positions per prefix-sum chunk (multiple of JMAX)
 constexpr int JMAX = 32;         // largest scaling block
-constexpr int NSLOT_MAX = 1280;  // persistent workgroups of the interval kernel (5 per compute unit)
+constexpr int NSLOT_MAX = 1024;  // resident tasks of the interval kernel (one wave per SIMD)
 constexpr int GRAD_CMAX = 64;    // most labels the gradient path holds transition accumulators for
 constexpr double LN2 = 0.6931471805599453094;
 constexpr double LOG2E = 1.4426950408889634074;
@@ -1170,6 +1170,7 @@ __global__ __launch_bounds__(NT) void k_interval(Params p)
 // from registers while the positions are finished one after the other.
 // ---------------------------------------------------------------------------
 constexpr int MB = 4;  // positions per time block
+constexpr int WCH = 8; // window entries loaded per group in the register-heavy beta pass
 
 // Window entries per lane: NKW, plus one when a half-wave holds several lane groups, so
 // that the groups' rows fall into different LDS banks.
@@ -1188,7 +1189,8 @@ __host__ __device__ constexpr size_t wave_lds_doubles(int CT, int NKW)
 {
     const int CTP = pow2_ge8(CT);
     const int KW = wave_nk(CT, NKW) * (64 / CTP);
-    return (size_t)(KW + lin_slack(KW)) * CT + (size_t)(CTP - CT) + 2 * (size_t)CTP;
+    const int YS = CTP < 16 ? 16 : CTP;
+    return (size_t)(KW + lin_slack(KW)) * CT + (size_t)(CTP - CT) + (size_t)MB * YS;
 }
 
 // Geometry and the window operations shared by the one-wave kernels.
@@ -1204,6 +1206,8 @@ struct WaveWin {
     static constexpr int RTOT = ROWS * RS + (CTP - CT);  // lanes c >= C read (and ignore) past a row's end
     static constexpr int H = CT <= 32 ? 2 : 1;
     static constexpr int HC = CT / H;
+    static constexpr int YS = CTP < 16 ? 16 : CTP;  // row stride of the MB message-vector rows
+    static constexpr int TRN = (CT + 15) / 16;       // 16-label tiles of the transition gradient
 
     // every entry of label c times 2^sft (each lane scales its own label's column)
     static __device__ __forceinline__ void rescale(double *ring, int g, int c, bool cval, int sft)
@@ -1260,12 +1264,13 @@ __global__ __launch_bounds__(64) void k_interval_wave(Params p)
 {
     using G = WaveWin<CT, NKW>;
     constexpr int CTP = G::CTP, RS = G::RS, NK = G::NK, KW = G::KW, M = G::M, ROWS = G::ROWS;
-    constexpr int RTOT = G::RTOT, H = G::H, HC = G::HC;
+    constexpr int RTOT = G::RTOT, H = G::H, HC = G::HC, YS = G::YS, TRN = G::TRN;
+    typedef double double4_t __attribute__((ext_vector_type(4)));
     extern __shared__ double lds_raw[];
     const int lane = threadIdx.x;
     const int K = p.K, C = p.C, KC = K * C, CC = C * C;
     double *ring = lds_raw;          // [ROWS][RS] (+ pad)
-    double *yv = ring + RTOT;        // [CTP]
+    double *yv = ring + RTOT;        // [MB][YS]: message vector of each position of a block (row 0 outside the beta pass)
     const int Delta = p.Delta, N = p.N;
     const size_t ckstride = (size_t)KC + C;
     const int c = lane % CTP, g = lane / CTP;
@@ -1297,9 +1302,9 @@ __global__ __launch_bounds__(64) void k_interval_wave(Params p)
         }
     };
     const double2 *ys = (const double2 *)__builtin_assume_aligned(yv + hh * HC, 16);
-    auto yv_sum = [&]() {
+    auto yv_sum = [&](const int row) {
         double s = 0.0;
-        for (int i = 0; i < CT; ++i) s += yv[i];
+        for (int i = 0; i < CT; ++i) s += yv[row * YS + i];
         return s;
     };
 
@@ -1319,7 +1324,7 @@ __global__ __launch_bounds__(64) void k_interval_wave(Params p)
         // ============================ forward recompute over (t0, t1) ============================
         load_etr(false);
         for (int i = lane; i < RTOT; i += 64) ring[i] = 0.0;
-        if (lane < CTP) yv[lane] = 0.0;
+        for (int i = lane; i < MB * YS; i += 64) yv[i] = 0.0;
         lds_wave_fence();
         int r = KW - 1;  // row of the newest message
         {
@@ -1349,7 +1354,7 @@ __global__ __launch_bounds__(64) void k_interval_wave(Params p)
                 int nb = min(tend - t, MB);
                 nb = min(nb, J - ((t + 1) & Jm));  // only a block's first position may cross a scaling boundary
                 if (__builtin_expect(((t + 1) & Jm) == 0, 0)) {
-                    const int ex = safe_exponent(yv_sum());
+                    const int ex = safe_exponent(yv_sum(0));
                     Y += (double)ex;
                     const int jn = (t + 1) / J;
                     G::rescale(ring, g, c, cval, nbc[(size_t)jn * C] - nbc[(size_t)(jn - 1) * C] - ex);
@@ -1408,7 +1413,7 @@ __global__ __launch_bounds__(64) void k_interval_wave(Params p)
         __threadfence_block();  // this wave's aloc / alocY rows are read back by all of its lanes
         load_etr(true);
         for (int i = lane; i < RTOT; i += 64) ring[i] = 0.0;
-        if (lane < CTP) yv[lane] = 0.0;
+        for (int i = lane; i < MB * YS; i += 64) yv[i] = 0.0;
         lds_wave_fence();
         r = M;
         double Yb;
@@ -1430,25 +1435,40 @@ __global__ __launch_bounds__(64) void k_interval_wave(Params p)
         lds_wave_fence();
         double dx[NK + MB - 1];  // sum_t coef_t(c) v_{t+k}(c), k = g*NK + jj + 1 (times W[k,c] at the end)
         double dn[MB - 1];       // the same for k = 1..MB-1 from inside the blocks (lanes g == 0)
-        double accT[HC];
+        // grad_trans[c',c] = Etr[c',c] sum_t a_t(c') kappa_t p_t(c) is a dense [C x T][T x C] product:
+        // accumulated on the matrix cores, four positions (one block) per instruction, in
+        // 16x16 tiles.  Operand A (a_t kappa) is loaded from the stored forward rows directly in
+        // the instruction's layout (lane l: label l mod 16 of the tile, position l/16 of the
+        // block); operand B (p_t) is read back from the block's message-vector rows in LDS.
+        double4_t accT[TRN][TRN];
 #pragma unroll
         for (int jj = 0; jj < NK + MB - 1; ++jj) dx[jj] = 0.0;
 #pragma unroll
         for (int jj = 0; jj < MB - 1; ++jj) dn[jj] = 0.0;
 #pragma unroll
-        for (int i = 0; i < HC; ++i) accT[i] = 0.0;
+        for (int i = 0; i < TRN; ++i)
+#pragma unroll
+            for (int o = 0; o < TRN; ++o) accT[i][o] = double4_t{0.0, 0.0, 0.0, 0.0};
+        int yrow = 0;  // row of yv that holds the newest message vector
         double R = 0.0, sR = 0.0;
         double kappa = exp((alocY[t1 - 1 - t0] + Yb) * LN2 - logZ);
         {
             const int rdoff = g * NK * RS + c;
             float *gout = p.grad_emis + ((size_t)b * p.T) * C + cc;
             int t = t1;
+            double aA[TRN];  // a of (position block index lane/16, label 16*tile + lane%16)
             auto load_rows = [&](double2 (&e)[MB], double2 (&aq)[MB], const int tfrom) {
 #pragma unroll
                 for (int i = 0; i < MB; ++i) {
                     const int tt = max(tfrom - 1 - i, t0);
                     e[i] = EIc[(size_t)tt * C];
                     aq[i] = aloc[(size_t)(tt - t0) * C + cc];
+                }
+                const int tt = max(tfrom - 1 - (lane >> 4), t0);
+#pragma unroll
+                for (int tr = 0; tr < TRN; ++tr) {
+                    const int cp = tr * 16 + (lane & 15);
+                    aA[tr] = cp < C ? aloc[(size_t)(tt - t0) * C + cp].x : 0.0;
                 }
             };
             double2 e[MB], aq[MB];
@@ -1457,7 +1477,7 @@ __global__ __launch_bounds__(64) void k_interval_wave(Params p)
                 int nb = min(t - t0, MB);
                 nb = min(nb, ((t - 1) & Jm) + 1);
                 if (__builtin_expect((t & Jm) == 0, 0)) {
-                    const int ex = safe_exponent(yv_sum());
+                    const int ex = safe_exponent(yv_sum(yrow));
                     Yb += (double)ex;
                     const int jn = (t - 1) / J;
                     G::rescale(ring, g, c, cval, -(nbc[(size_t)jn * C] - nbc[(size_t)(jn + 1) * C]) - ex);
@@ -1476,13 +1496,23 @@ __global__ __launch_bounds__(64) void k_interval_wave(Params p)
                 double acc[MB];
 #pragma unroll
                 for (int i = 0; i < MB; ++i) acc[i] = 0.0;
+                // in groups of WCH entries, so that the loaded values do not all sit in registers at once
 #pragma unroll
-                for (int jj = 0; jj < NK; ++jj) {
-                    const double v = base[jj * RS];  // distance g*NK + jj from the newest
+                for (int j0 = 0; j0 < NK; j0 += WCH) {
+                    double v[WCH];
 #pragma unroll
-                    for (int i = 0; i < MB; ++i) {
-                        acc[i] = fma(wx[jj + i], v, acc[i]);
-                        dx[jj + i] = fma(coef[i], v, dx[jj + i]);
+                    for (int u = 0; u < WCH; ++u)
+                        if (j0 + u < NK) v[u] = base[(j0 + u) * RS];  // distance g*NK + j0 + u from the newest
+                    asm volatile("" ::: "memory");
+#pragma unroll
+                    for (int u = 0; u < WCH; ++u) {
+                        if (j0 + u < NK) {
+#pragma unroll
+                            for (int i = 0; i < MB; ++i) {
+                                acc[i] = fma(wx[j0 + u + i], v[u], acc[i]);
+                                dx[j0 + u + i] = fma(coef[i], v[u], dx[j0 + u + i]);
+                            }
+                        }
                     }
                 }
 #pragma unroll
@@ -1500,16 +1530,14 @@ __global__ __launch_bounds__(64) void k_interval_wave(Params p)
                             dn[i - 1 - jn] = fma(cg, qn[jn], dn[i - 1 - jn]);
                         }
                         const double y = x * e[i].y;  // p_t(c)
-                        if (cval) yv[c] = y;
+                        if (cval) yv[i * YS + c] = y;
                         lds_wave_fence();
                         double z0 = 0.0, z1 = 0.0;
 #pragma unroll
                         for (int o = 0; o < HC; o += 2) {
-                            const double2 vv = ys[o >> 1];
+                            const double2 vv = ys[(i * YS + o) >> 1];
                             z0 = fma(vv.x, Ereg[o], z0);
                             z1 = fma(vv.y, Ereg[o + 1], z1);
-                            accT[o] = fma(ak[i], vv.x, accT[o]);
-                            accT[o + 1] = fma(ak[i], vv.y, accT[o + 1]);
                         }
                         double z = z0 + z1;
                         if (H == 2) z = add_across_32(z);
@@ -1529,6 +1557,21 @@ __global__ __launch_bounds__(64) void k_interval_wave(Params p)
                         qn[i] = 0.0;
                     }
                 }
+                // transition-gradient tiles of this block (rows of yv beyond nb are stale: A is 0 there)
+                {
+                    const bool on = (lane >> 4) < nb;
+                    double bB[TRN];
+#pragma unroll
+                    for (int tc = 0; tc < TRN; ++tc) bB[tc] = yv[(lane >> 4) * YS + tc * 16 + (lane & 15)];
+#pragma unroll
+                    for (int tr = 0; tr < TRN; ++tr) {
+                        const double a = on ? aA[tr] * kappa : 0.0;
+#pragma unroll
+                        for (int tc = 0; tc < TRN; ++tc)
+                            accT[tr][tc] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, bB[tc], accT[tr][tc], 0, 0, 0);
+                    }
+                }
+                yrow = nb - 1;
                 t -= nb;
                 load_rows(e, aq, t);
             }
@@ -1564,11 +1607,14 @@ __global__ __launch_bounds__(64) void k_interval_wave(Params p)
         lds_wave_fence();
         double *pT = p.partTr + ((size_t)b * N + iv) * CC;
 #pragma unroll
-        for (int i = 0; i < HC; ++i) {
-            const int o = hh * HC + i;
-            const bool owner = H == 2 ? lane == hh * 32 + c : g == 0;  // one lane per (label, half)
-            if (cval && owner && o < C) pT[(size_t)c * C + o] = accT[i];
-        }
+        for (int tr = 0; tr < TRN; ++tr)
+#pragma unroll
+            for (int tc = 0; tc < TRN; ++tc)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {  // tile element (4v + lane/16, lane%16)
+                    const int src = tr * 16 + 4 * v + (lane >> 4), dst = tc * 16 + (lane & 15);
+                    if (src < C && dst < C) pT[(size_t)src * C + dst] = accT[tr][tc][v];
+                }
         if (lane < C) {
             p.tot[((size_t)b * N + iv) * C + lane] = R;
             p.sumR[((size_t)b * N + iv) * C + lane] = sR;
@@ -2017,14 +2063,61 @@ __global__ __launch_bounds__(NT) void k_fin_params(Params p)
 // ---------------------------------------------------------------------------
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
-int auto_interval(int B, int T, int K)
+// LDS bytes of one single-wave task for these sizes, 0 when the one-wave kernels do not apply.
+size_t wave_task_lds(int K, int C)
 {
-    double d = ceil(sqrt((double)T * (double)K * (double)B / 256.0));
-    if (d < 1.0) d = 1.0;
-    int di = (int)d;
-    if (di >= 8) di = (di + 7) & ~7;  // lets the scan run its steps in aligned groups of 8
-    if (di > T) di = T;
-    return di;
+    if (C > 64) return 0;
+    const int CT = C <= 8 ? 8 : (C <= 16 ? 16 : (C <= 24 ? 24 : (C <= 32 ? 32 : 64)));
+    const int GW = 64 / pow2_ge8(CT);
+    const int per_lane = (K + GW - 1) / GW;
+    if (per_lane > 64) return 0;
+    const int NKW = per_lane <= 16 ? 16 : (per_lane <= 32 ? 32 : 64);
+    const size_t lds = wave_lds_doubles(CT, NKW) * sizeof(double);
+    return lds <= LDS_LIMIT ? lds : 0;
+}
+
+// Automatic checkpoint interval.  Every (sequence, interval) is one single-wave task of the
+// chunk-parallel scans (both directions, interval + warm-up positions each) and of the
+// interval stage (interval positions, about 2.2x the cost per position).  Tasks run in
+// rounds of as many as fit the chip at once (256 compute units; per compute unit 8 scan
+// waves or 4 interval waves by registers, fewer when the K-deep LDS window is large), and
+// a partly filled round costs a full one.  The interval is the multiple of 8 that
+// minimises that cost, within [max(8, K/2), sqrt(T*K)]: below the lower end warm-ups and
+// K-deep checkpoints dominate work and memory; the upper end is the spacing of Algorithm 1,
+// so checkpoints and per-task buffers still grow like sqrt(T) for very long sequences.
+int auto_interval(int B, int T, int K, int C)
+{
+    const size_t lds = wave_task_lds(K, C);
+    if (lds == 0) {  // generic kernels: sqrt(T*K) spacing scaled to spread B*T/interval tasks over 256 units
+        double d = ceil(sqrt((double)T * (double)K * (double)B / 256.0));
+        int di = d < 1.0 ? 1 : (int)d;
+        if (di >= 8) di = (di + 7) & ~7;
+        return di > T ? T : di;
+    }
+    const long per_cu = (long)(LDS_LIMIT / lds);
+    const double slots_scan = 256.0 * (double)(per_cu < 8 ? per_cu : 8);
+    const double slots_int = 256.0 * (double)(per_cu < 4 ? per_cu : 4);
+    const double warm = 2 * K < 32 ? 32.0 : 2.0 * K;
+    const int dlo = K / 2 < 8 ? 8 : K / 2;
+    int dhi = (int)ceil(sqrt((double)T * (double)K));
+    if (dhi < dlo) dhi = dlo;
+    int best = 0;
+    double best_cost = 0.0;
+    for (int n = 1; n <= 8192; ++n) {
+        int d = ((T + n - 1) / n + 7) & ~7;
+        if (d > T) d = T;
+        if (d > dhi && d != T) continue;
+        if (d > dhi && n > 1) continue;
+        if (d < dlo && best) break;
+        const double tasks = (double)B * (double)((T + d - 1) / d);
+        const double cost = ceil(2.0 * tasks / slots_scan) * (warm + d) + 2.2 * ceil(tasks / slots_int) * d;
+        if (!best || cost < best_cost) {
+            best = d;
+            best_cost = cost;
+        }
+        if (d <= dlo) break;
+    }
+    return best;
 }
 
 struct Plan {
@@ -2039,7 +2132,7 @@ int make_plan(int B, int T, int K, int C, int ckpt_interval, int want_grad, Plan
     if (B < 1 || T < 1 || K < 1 || C < 1 || ckpt_interval < 0) return SEMICRF_EINVAL;
     if (C > 256) return SEMICRF_EUNSUPPORTED;
     if ((double)B * ((double)T + 1.0) * (double)C > 2.0e10) return SEMICRF_EUNSUPPORTED;
-    pl->Delta = ckpt_interval > 0 ? (ckpt_interval > T ? T : ckpt_interval) : auto_interval(B, T, K);
+    pl->Delta = ckpt_interval > 0 ? (ckpt_interval > T ? T : ckpt_interval) : auto_interval(B, T, K, C);
     pl->N = (T + pl->Delta - 1) / pl->Delta;
     pl->NCH = T / PREP_CH + 1;
     pl->G = (NT / C) < K ? (NT / C) : K;
@@ -2379,6 +2472,16 @@ int semicrf_workspace_bytes(int B, int T, int K, int C, int ckpt_interval, int w
     int rc = make_plan(B, T, K, C, ckpt_interval, want_grad, &pl);
     if (rc != SEMICRF_OK) return rc;
     *bytes = pl.total;
+    return SEMICRF_OK;
+}
+
+int semicrf_ckpt_interval(int B, int T, int K, int C, int ckpt_interval, int *interval)
+{
+    if (!interval) return SEMICRF_EINVAL;
+    Plan pl;
+    int rc = make_plan(B, T, K, C, ckpt_interval, 0, &pl);
+    if (rc != SEMICRF_OK) return rc;
+    *interval = pl.Delta;
     return SEMICRF_OK;
 }
 

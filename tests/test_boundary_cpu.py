@@ -63,23 +63,42 @@ def test_workspace_is_aligned_positive_and_monotone():
     assert sb.semicrf_workspace_bytes(4, 1000, 64, 24, 0, False) < sb.semicrf_workspace_bytes(4, 1000, 64, 24, 0, True)
 
 
-def test_working_memory_beyond_prefix_arrays_is_sublinear_in_T():
-    """Checkpoints + per-interval recompute buffers must grow like sqrt(T): the
-    part of the workspace that is not the O(T*C) prefix arrays, measured as
-    (grad workspace - forward-only workspace), may at most double when T grows
-    fourfold (it would quadruple if it were linear)."""
+def test_working_memory_beyond_prefix_arrays_is_bounded_then_sublinear_in_T():
+    """Checkpoints + per-interval recompute buffers (grad workspace - forward-only workspace).
+    The automatic interval gives one task per SIMD, so up to T ~ 1024*sqrt(T*K)/B this part
+    is about one more O(T*C) array (never more than 1.5x the prefix arrays); beyond that the
+    interval is capped at sqrt(T*K) and it must grow like sqrt(T)."""
     B, K, C = 4, 64, 24
-    extra = []
+    extra = lambda T: (sb.semicrf_workspace_bytes(B, T, K, C, 0, True)
+                       - sb.semicrf_workspace_bytes(B, T, K, C, 0, False))
     for T in (100000, 400000, 1600000):
-        extra.append(sb.semicrf_workspace_bytes(B, T, K, C, 0, True)
-                     - sb.semicrf_workspace_bytes(B, T, K, C, 0, False))
-    assert extra[1] / extra[0] < 2.3 and extra[2] / extra[1] < 2.3
-    # and it is a small fraction of what the paper's own per-interval layout
-    # (full K x C x C gradient workspace per checkpoint) would need
+        assert extra(T) < 1.5 * B * (T + 1) * C * 20
+    # 16x longer sequences: sqrt growth is 4x (the number of rounds is an integer, hence the slack), linear 16x
+    assert extra(204800000) / extra(12800000) < 6.0
+    # and it is of the order of what the paper's own per-interval layout (full K x C x C
+    # gradient workspace per checkpoint) would need, without the K*C*C blow-up per interval
     T = 100000
     delta = math.ceil(math.sqrt(T * K))
     paper_ws = B * math.ceil(T / delta) * K * C * C * 8
-    assert extra[0] < 40 * paper_ws        # same order, no K*C*C blow-up per interval here
+    assert extra(T) < 40 * paper_ws
+
+
+def test_checkpoint_interval_choice():
+    """Explicit intervals are clamped to T; the automatic one is a multiple of 8 (or T),
+    at least max(8, K/2) and at most the sqrt(T*K) spacing of Algorithm 1 rounded up."""
+    assert sb.semicrf_ckpt_interval(2, 100, 4, 3, 7) == 7
+    assert sb.semicrf_ckpt_interval(2, 100, 4, 3, 1000) == 100
+    for (B, T, K, C) in [(2, 512, 8, 4), (64, 256, 16, 24), (32, 2000, 32, 64), (4, 100000, 64, 24),
+                         (1, 400000, 512, 8), (1, 3000, 512, 8), (1, 1, 1, 1), (4, 25600000, 64, 24)]:
+        d = sb.semicrf_ckpt_interval(B, T, K, C)
+        assert 1 <= d <= T
+        assert d == T or d % 8 == 0
+        if d < T:
+            assert d >= max(8, K // 2)
+            assert d <= math.ceil(math.sqrt(T * K)) + 7 or d <= max(8, K // 2) + 7
+    # the genomic shape gets one task per SIMD
+    d = sb.semicrf_ckpt_interval(4, 100000, 64, 24)
+    assert 4 * math.ceil(100000 / d) == 1024
 
 
 def test_memory_arithmetic_of_the_paper_example():
