@@ -267,32 +267,49 @@ __global__ __launch_bounds__(NT) void k_prep_seq(Params p)
 }
 
 // ---------------------------------------------------------------------------
-// Eq. 2: centred prefix sums S[t,c] (fp64, sequential inside a chunk), the
-// per-block exponents n_j(c) and the pair (ES, 1/ES), ES = exp(S - n ln2).  grid (NCH,B),
-// one thread per label.
+// Eq. 2: centred prefix sums S[t,c] (fp64), the per-block exponents n_j(c) and the pair
+// (ES, 1/ES), ES = exp(S - n ln2).  grid (NCH,B), 256 threads: a chunk of PREP_CH
+// positions is cut into 8 segments of 32 (a multiple of every scaling block length), thread
+// (segment, label) first sums its segment, the segment sums are combined in segment order,
+// then the thread walks its segment again and writes.  Labels beyond 32 take further turns.
 // ---------------------------------------------------------------------------
-__global__ void k_prefix(Params p)
+constexpr int PREP_SEG = 32;
+static_assert(PREP_CH == 8 * PREP_SEG && JMAX <= PREP_SEG && NT == 256, "k_prefix geometry");
+
+__global__ __launch_bounds__(NT) void k_prefix(Params p)
 {
+    __shared__ double segsum[8][PREP_SEG + 1];
     const int b = blockIdx.y, ch = blockIdx.x;
+    const int seg = threadIdx.x >> 5, cl = threadIdx.x & 31;
     const int C = p.C;
     const SeqHdr h = p.hdr[b];
     const int L = h.L, J = h.J;
-    const int t0 = ch * PREP_CH;
-    for (int c = threadIdx.x; c < C; c += blockDim.x) {
-        const float *f = p.emis + ((size_t)b * p.T) * C + c;
-        const double nu = p.nu[(size_t)b * C + c];
-        double S = p.chsum[((size_t)b * p.NCH + ch) * C + c];
+    const int t0 = ch * PREP_CH + seg * PREP_SEG;
+    const int tend = min(t0 + PREP_SEG, p.T + 1);
+    const size_t row0 = (size_t)b * (p.T + 1);
+    for (int cb = 0; cb < C; cb += 32) {
+        const int c = cb + cl;
+        const bool valid = c < C;
+        const float *f = p.emis + ((size_t)b * p.T) * C + (valid ? c : 0);
+        const double nu = valid ? p.nu[(size_t)b * C + c] : 0.0;
+        double sum = 0.0;
+        if (valid)
+            for (int t = t0; t < min(tend, L); ++t) sum += (double)f[(size_t)t * C] - nu;
+        segsum[seg][cl] = sum;
+        __syncthreads();
+        double S = valid ? p.chsum[((size_t)b * p.NCH + ch) * C + c] : 0.0;
+        for (int s2 = 0; s2 < seg; ++s2) S += segsum[s2][cl];
+        __syncthreads();
+        if (!valid) continue;
         double base = 0.0;
-        const size_t row0 = (size_t)b * (p.T + 1);
-        const int tend = min(t0 + PREP_CH, p.T + 1);
         for (int t = t0; t < tend; ++t) {
             if (t <= L) {
                 if ((t % J) == 0) {
-                    double n = rint(S * LOG2E);
+                    const double n = rint(S * LOG2E);
                     p.nbase[(row0 + (size_t)(t / J)) * C + c] = (int)n;
                     base = n * LN2;
                 }
-                double x = S - base;
+                const double x = S - base;
                 p.EI[(row0 + t) * C + c] = make_double2(exp(x), exp(-x));
                 if (p.cum) p.cum[(row0 + t) * C + c] = S;
                 if (t < L) S += (double)f[(size_t)t * C] - nu;
@@ -2226,8 +2243,7 @@ int launch_prep(const Params &p, hipStream_t st)
     hipLaunchKernelGGL(k_tables, dim3(1), dim3(NT), 0, st, p);
     hipLaunchKernelGGL(k_colsum, dim3(p.NCH, p.B), dim3(NT), 0, st, p);
     hipLaunchKernelGGL(k_prep_seq, dim3(p.B), dim3(NT), 0, st, p);
-    int pt = p.C <= 64 ? 64 : (p.C <= 128 ? 128 : 256);
-    hipLaunchKernelGGL(k_prefix, dim3(p.NCH, p.B), dim3(pt), 0, st, p);
+    hipLaunchKernelGGL(k_prefix, dim3(p.NCH, p.B), dim3(NT), 0, st, p);
     return check_launch();
 }
 
