@@ -116,6 +116,10 @@ def main():
     kernels = {"scans": "k_spec (chunk-parallel forward + backward scans, one launch; stage time "
                         "includes its two small verification kernels)",
                "intervals": "k_interval_wave / k_interval (per-interval recompute + marginals, one launch)"}
+    # HBM bytes per launch of the two big kernels at the genomic workload with the automatic
+    # interval, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by a 1 GiB copy
+    # (profiles/hot_path_genomic_hbm_traffic_pmc.txt); unknown for other workloads.
+    measured_traffic = {("genomic", "intervals"): 731.3e6, ("genomic", "scans"): 466.6e6 + 53.5e6}
     dom = "scans" if stage[1] >= stage[2] else "intervals"
     dom_s = (stage[1] if dom == "scans" else stage[2]) * 1e-3
     achieved = stage_flop[dom] / dom_s / 1e12
@@ -150,7 +154,7 @@ def main():
             "peak": FP64_VECTOR_PEAK_TFLOPS,
             "unit": "TFLOP/s",
             "frac": achieved / FP64_VECTOR_PEAK_TFLOPS,
-            "traffic": None,
+            "traffic": measured_traffic.get((args.workload, dom)) if args.ckpt_interval == 0 else None,
             "flop_per_launch": stage_flop[dom],
             "launch_ms": dom_s * 1e3,
             "whole_path_achieved": whole,
