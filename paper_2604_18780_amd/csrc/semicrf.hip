@@ -98,6 +98,7 @@ struct Params {
     double *spec_err;   // [B][2][N+1]
     int *spec_ok;       // [B][2]  1: the chunk-parallel scan of (sequence, direction) was accepted
     int spec;           // chunk-parallel scan enabled for this call
+    int fuse;           // its forward tasks also store the interval stage's forward rows (one slot per task)
     double *aloc;       // [nslot][Delta][2C]
     double *alocY;      // [nslot][Delta]
     double *partD;      // [B][N][K][C]
@@ -1337,13 +1338,22 @@ __global__ __launch_bounds__(64) void k_interval_wave(Params p)
         const double2 *EIc = p.EI + row0 * C + cc;
         const int *nbc = p.nbase + row0 * C + cc;
         const double logZ = h.logZ;
+        // exponent step n_j(c) - n_{j-1}(c) of the lane's label at the scaling-block boundary j*J
+        auto nbdelta = [&](const int j) {
+            return (j >= 1 && (long)j * J <= (long)L) ? nbc[(size_t)j * C] - nbc[(size_t)(j - 1) * C] : 0;
+        };
 
         // ============================ forward recompute over (t0, t1) ============================
+        // Scale of the interval's first position; the stored per-position scales are relative to it.
+        const double Y0 = p.ckYA[(size_t)b * (N + 1) + iv];
+        // An accepted chunk-parallel forward scan has already stored this interval's rows.
+        const bool stored = p.fuse && p.spec_ok[b * 2];
+        int r = KW - 1;  // row of the newest message
+        if (!stored) {
         load_etr(false);
         for (int i = lane; i < RTOT; i += 64) ring[i] = 0.0;
         for (int i = lane; i < MB * YS; i += 64) yv[i] = 0.0;
         lds_wave_fence();
-        int r = KW - 1;  // row of the newest message
         {
             const double *ck = p.ckA + ((size_t)b * (N + 1) + iv) * ckstride;
             const int tm = t0 % K;
@@ -1354,7 +1364,7 @@ __global__ __launch_bounds__(64) void k_interval_wave(Params p)
             if (lane < C) yv[lane] = ck[KC + lane];
         }
         lds_wave_fence();
-        double Y = p.ckYA[(size_t)b * (N + 1) + iv];
+        double Y = 0.0;
         if (writer) aloc[c] = make_double2(yv[c], ring[r * RS + c]);
         if (lane == 0) alocY[0] = Y;
         {
@@ -1367,14 +1377,16 @@ __global__ __launch_bounds__(64) void k_interval_wave(Params p)
             };
             double2 e[MB];
             load_rows(e, t);
+            int jnx = t0 / J + 1;      // next scaling-block boundary ahead (position jnx*J) ...
+            int dnx = nbdelta(jnx);    // ... and its exponent step, loaded one block of J early
             while (t < tend) {
                 int nb = min(tend - t, MB);
                 nb = min(nb, J - ((t + 1) & Jm));  // only a block's first position may cross a scaling boundary
                 if (__builtin_expect(((t + 1) & Jm) == 0, 0)) {
                     const int ex = safe_exponent(yv_sum(0));
                     Y += (double)ex;
-                    const int jn = (t + 1) / J;
-                    G::rescale(ring, g, c, cval, nbc[(size_t)jn * C] - nbc[(size_t)(jn - 1) * C] - ex);
+                    G::rescale(ring, g, c, cval, dnx - ex);
+                    dnx = nbdelta(++jnx);
                 }
                 if (__builtin_expect(r + MB > ROWS - 1, 0)) r = G::template move<false>(ring, lane, r);
                 const double *base = ring + r * RS + rdoff;
@@ -1425,6 +1437,7 @@ __global__ __launch_bounds__(64) void k_interval_wave(Params p)
                 load_rows(e, t);  // the next block's rows (first use a block's window pass later)
             }
         }
+        }  // !stored
 
         // ============================ backward pass over [t0, t1) ============================
         __threadfence_block();  // this wave's aloc / alocY rows are read back by all of its lanes
@@ -1468,7 +1481,7 @@ __global__ __launch_bounds__(64) void k_interval_wave(Params p)
             for (int o = 0; o < TRN; ++o) accT[i][o] = double4_t{0.0, 0.0, 0.0, 0.0};
         int yrow = 0;  // row of yv that holds the newest message vector
         double R = 0.0, sR = 0.0;
-        double kappa = exp((alocY[t1 - 1 - t0] + Yb) * LN2 - logZ);
+        double kappa = exp((Y0 + alocY[t1 - 1 - t0] + Yb) * LN2 - logZ);
         {
             const int rdoff = g * NK * RS + c;
             float *gout = p.grad_emis + ((size_t)b * p.T) * C + cc;
@@ -1490,15 +1503,23 @@ __global__ __launch_bounds__(64) void k_interval_wave(Params p)
             };
             double2 e[MB], aq[MB];
             load_rows(e, aq, t);
+            // next scaling-block boundary below (position jnx*J), its exponent step and the forward
+            // scale just below it, loaded one block of J early
+            auto ybelow = [&](const int j) { return (long)j * J - 1 >= (long)t0 ? alocY[j * J - 1 - t0] : 0.0; };
+            int jnx = t1 / J;
+            int dnx = nbdelta(jnx);
+            double aynx = ybelow(jnx);
             while (t > t0) {
                 int nb = min(t - t0, MB);
                 nb = min(nb, ((t - 1) & Jm) + 1);
                 if (__builtin_expect((t & Jm) == 0, 0)) {
                     const int ex = safe_exponent(yv_sum(yrow));
                     Yb += (double)ex;
-                    const int jn = (t - 1) / J;
-                    G::rescale(ring, g, c, cval, -(nbc[(size_t)jn * C] - nbc[(size_t)(jn + 1) * C]) - ex);
-                    kappa = exp((alocY[t - 1 - t0] + Yb) * LN2 - logZ);
+                    G::rescale(ring, g, c, cval, dnx - ex);
+                    kappa = exp((Y0 + aynx + Yb) * LN2 - logZ);
+                    --jnx;
+                    dnx = nbdelta(jnx);
+                    aynx = ybelow(jnx);
                 }
                 if (__builtin_expect(r < MB, 0)) r = G::template move<true>(ring, lane, r);
                 double coef[MB], ak[MB];
@@ -1748,7 +1769,23 @@ __device__ __forceinline__ void spec_task(const Params &p, double *lds_raw, cons
     const int tstart = BWD ? hi : lo;   // where the chunk proper begins (state -> ck1)
     const int tend = BWD ? lo : hi;
     const int istart = BWD ? j + 1 : j, iend = BWD ? j : j + 1;
-    if (s0 == tstart && !(BWD && tstart == L)) record(s0, ck1 + (size_t)istart * ckstride, ckY1 + istart);
+    // Forward tasks also leave the rows the interval stage needs, (a_t, q_t) and the scale relative
+    // to the chunk's first position, for t = lo .. hi-1, in the task's own slot (the interval
+    // stage then skips its forward recompute for accepted sequences).
+    const bool keep = !BWD && p.fuse;
+    const bool writer = cval && g == 0;
+    double2 *aloc = (double2 *)p.aloc + ((size_t)b * N + j) * Delta * C;
+    double *alocY = p.alocY + ((size_t)b * N + j) * Delta;
+    double Yrec = 0.0;  // scale at the chunk's first position
+    auto start_rows = [&]() {
+        Yrec = Y;
+        if (keep && writer) aloc[c] = make_double2(yv[c], ring[r * RS + c]);
+        if (keep && lane == 0) alocY[0] = 0.0;
+    };
+    if (s0 == tstart && !(BWD && tstart == L)) {
+        record(s0, ck1 + (size_t)istart * ckstride, ckY1 + istart);
+        start_rows();
+    }
 
     // this lane's lowest window address relative to the newest row
     const int rdoff = BWD ? g * NK * RS + c : -(g * NK + NK - 1) * RS + c;
@@ -1771,20 +1808,27 @@ __device__ __forceinline__ void spec_task(const Params &p, double *lds_raw, cons
     };
     double2 e[MB];
     load_rows(e, t);
+    // exponent step n_j(c) - n_{j-1}(c) of the lane's label at the scaling-block boundary j*J; the
+    // one of the next boundary in the scan's direction is loaded one block of J early
+    auto nbdelta = [&](const int jb) {
+        return (jb >= 1 && (long)jb * J <= (long)L) ? nbc[(size_t)jb * C] - nbc[(size_t)(jb - 1) * C] : 0;
+    };
+    int jnx = BWD ? s0 / J : s0 / J + 1;
+    int dnx = nbdelta(jnx);
     while (t != tend) {
         const int nb = block_len(t);
         const int tn = BWD ? t - nb : t + nb;
         const int t1 = BWD ? t - 1 : t + 1;
+        const bool inchunk = keep && t >= tstart;  // blocks end at tstart, so this holds for the whole block
         const bool boundary = BWD ? (t & Jm) == 0 : (t1 & Jm) == 0;
         if (__builtin_expect(boundary, 0)) {
             double prevsum = 0.0;
             for (int i = 0; i < CT; ++i) prevsum += yv[i];
             const int ex = safe_exponent(prevsum);
             Y += (double)ex;
-            const int jn = t1 / J;
-            const int sft = BWD ? -(nbc[(size_t)jn * C] - nbc[(size_t)(jn + 1) * C]) - ex
-                                : nbc[(size_t)jn * C] - nbc[(size_t)(jn - 1) * C] - ex;
-            G::rescale(ring, g, c, cval, sft);
+            G::rescale(ring, g, c, cval, dnx - ex);
+            jnx += BWD ? -1 : 1;
+            dnx = nbdelta(jnx);
         }
         if (__builtin_expect(BWD ? r < MB : r + MB > ROWS - 1, 0)) r = G::template move<BWD>(ring, lane, r);
         // ---- what the window contributes to the MB positions of the block
@@ -1823,7 +1867,11 @@ __device__ __forceinline__ void spec_task(const Params &p, double *lds_raw, cons
                 const double q = z * (BWD ? e[i].x : e[i].y);
                 qn[i] = q;
                 r += BWD ? -1 : 1;
-                if (cval && g == 0) ring[r * RS + c] = q;
+                if (writer) ring[r * RS + c] = q;
+                if (!BWD && inchunk && t + 1 + i < hi) {
+                    if (writer) aloc[(size_t)(t + 1 + i - lo) * C + c] = make_double2(y, q);
+                    if (lane == 0) alocY[t + 1 + i - lo] = Y - Yrec;
+                }
                 lds_wave_fence();
             } else {
                 qn[i] = 0.0;
@@ -1831,7 +1879,10 @@ __device__ __forceinline__ void spec_task(const Params &p, double *lds_raw, cons
         }
         t = tn;
         load_rows(e, t);  // the next block's rows (first use a block's window pass later)
-        if (__builtin_expect(t == tstart, 0)) record(t, ck1 + (size_t)istart * ckstride, ckY1 + istart);
+        if (__builtin_expect(t == tstart, 0)) {
+            record(t, ck1 + (size_t)istart * ckstride, ckY1 + istart);
+            start_rows();
+        }
     }
     record(tend, ck2 + (size_t)iend * ckstride, ckY2 + iend);
 }
@@ -2425,6 +2476,7 @@ int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hi
         if (w > 0) warm[0] = w, warm[1] = 4 * w;
     }
     p.spec = p.spec && mode != 0 && spec_applies(p.K, p.C);
+    p.fuse = p.spec && mode == 2 && (size_t)p.B * pl.N <= (size_t)pl.nslot;  // one slot per task
     T.mark();
     rc = launch_prep(p, st);
     T.mark();
