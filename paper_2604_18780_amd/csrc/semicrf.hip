@@ -179,6 +179,7 @@ __global__ __launch_bounds__(NT) void k_colsum(Params p)
     double acc = 0.0, mx = 0.0;
     if (r < R) {
         const float *f = p.emis + ((size_t)b * p.T) * C;
+#pragma unroll 8
         for (int u = u0 + r; u < u1; u += R) {
             double v = (double)f[(size_t)u * C + c];
             acc += v;
@@ -220,8 +221,10 @@ __global__ __launch_bounds__(NT) void k_prep_seq(Params p)
     const int c0 = min(g * per, NCH), c1 = min(c0 + per, NCH);
     double *cs = p.chsum + ((size_t)b * NCH) * C + c;
     double loc = 0.0;
-    if (act)
+    if (act) {
+#pragma unroll 8
         for (int ch = c0; ch < c1; ++ch) loc += cs[(size_t)ch * C];
+    }
     gsum[tid] = loc;
     __syncthreads();
     if (tid < C) {
@@ -236,6 +239,7 @@ __global__ __launch_bounds__(NT) void k_prep_seq(Params p)
         const double mynu = nu_s[c];
         double pref = 0.0;  // raw prefix sum at the start of this range
         for (int gg = 0; gg < g; ++gg) pref += gsum[gg * C + c];
+#pragma unroll 8
         for (int ch = c0; ch < c1; ++ch) {
             const double sum = cs[(size_t)ch * C];
             const int nvalid = min(ch * PREP_CH, L);
@@ -245,6 +249,7 @@ __global__ __launch_bounds__(NT) void k_prep_seq(Params p)
     }
     // bound on |f - nu|
     double fm = 0.0;
+#pragma unroll 4
     for (int ch = tid; ch < NCH; ch += NT) fm = fmax(fm, p.chmax[(size_t)b * NCH + ch]);
     red[tid] = fm;
     __syncthreads();
@@ -310,8 +315,8 @@ __global__ __launch_bounds__(NT) void k_prefix(Params p)
                     p.nbase[(row0 + (size_t)(t / J)) * C + c] = (int)n;
                     base = n * LN2;
                 }
-                const double x = S - base;
-                p.EI[(row0 + t) * C + c] = make_double2(exp(x), exp(-x));
+                const double es = exp(S - base);
+                p.EI[(row0 + t) * C + c] = make_double2(es, 1.0 / es);
                 if (p.cum) p.cum[(row0 + t) * C + c] = S;
                 if (t < L) S += (double)f[(size_t)t * C] - nu;
             } else if (p.cum) {
@@ -2039,13 +2044,16 @@ __global__ __launch_bounds__(NT) void k_fin_seq(Params p)
     const int i0 = min(g * per, nint), i1 = min(i0 + per, nint);
     const bool act = g < G;
     double loc = 0.0;
-    if (act)
+    if (act) {
+#pragma unroll 8
         for (int i = i0; i < i1; ++i) loc += p.tot[((size_t)b * N + i) * C + c];
+    }
     gsum[tid] = loc;
     __syncthreads();
     double run = 0.0, total = 0.0;
     if (act) {
         for (int gg = 0; gg < g; ++gg) run += gsum[gg * C + c];
+#pragma unroll 8
         for (int i = i0; i < i1; ++i) {
             const size_t o = ((size_t)b * N + i) * C + c;
             run += p.tot[o];
@@ -2063,27 +2071,36 @@ __global__ __launch_bounds__(NT) void k_fin_seq(Params p)
     }
 }
 
-// grad_emis / pos_marg, elementwise over (b,u,c).
+// grad_emis / pos_marg, elementwise over (u,c) of one sequence.  grid (blocks, B).
 __global__ __launch_bounds__(NT) void k_fin_emis(Params p)
 {
-    const size_t n = (size_t)p.B * p.T * p.C;
-    const int C = p.C;
-    for (size_t idx = (size_t)blockIdx.x * NT + threadIdx.x; idx < n; idx += (size_t)gridDim.x * NT) {
-        const int c = (int)(idx % C);
-        const size_t bu = idx / C;
-        const int u = (int)(bu % p.T);
-        const int b = (int)(bu / p.T);
-        const int L = p.hdr[b].L;
+    const int b = blockIdx.y, C = p.C;
+    const int L = p.hdr[b].L;
+    const double w = p.grad_logz ? (double)p.grad_logz[b] : 1.0;
+    const size_t n = (size_t)p.T * C;  // elements of one sequence
+    const size_t base = (size_t)b * n;
+    const double *carry = p.carry + ((size_t)b * p.N) * C;
+    const double *mean = p.mean + (size_t)b * C;
+    auto one = [&](const size_t idx, const int u, const int c) {
         float ge = 0.f, pmv = 0.f;
         if (u < L) {
             const int i = u / p.Delta;
-            const double pm = p.carry[((size_t)b * p.N + i) * C + c] - (double)p.grad_emis[idx];
-            const double w = p.grad_logz ? (double)p.grad_logz[b] : 1.0;
-            ge = (float)(w * (pm - p.mean[(size_t)b * C + c]));
+            const double pm = carry[(size_t)i * C + c] - (double)p.grad_emis[base + idx];
+            ge = (float)(w * (pm - mean[c]));
             pmv = (float)pm;
         }
-        p.grad_emis[idx] = ge;
-        if (p.pos_marg) p.pos_marg[idx] = pmv;
+        p.grad_emis[base + idx] = ge;
+        if (p.pos_marg) p.pos_marg[base + idx] = pmv;
+    };
+    if (n < ((size_t)1 << 31)) {  // 32-bit index arithmetic
+        const unsigned n32 = (unsigned)n, step = gridDim.x * NT;
+        for (unsigned idx = blockIdx.x * NT + threadIdx.x; idx < n32; idx += step) {
+            const unsigned u = idx / (unsigned)C;
+            one(idx, (int)u, (int)(idx - u * (unsigned)C));
+        }
+    } else {
+        for (size_t idx = (size_t)blockIdx.x * NT + threadIdx.x; idx < n; idx += (size_t)gridDim.x * NT)
+            one(idx, (int)(idx / C), (int)(idx % C));
     }
 }
 
@@ -2106,14 +2123,16 @@ __global__ __launch_bounds__(NT) void k_fin_params(Params p)
             const size_t stride = idx < CC ? (size_t)CC : (size_t)KC;
             const double *q = idx < CC ? p.partTr + ((size_t)b * N) * CC + idx
                                        : p.partD + ((size_t)b * N) * KC + (idx - CC);
-            double s0 = 0.0, s1 = 0.0;
+            double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
             int i = g;
-            for (; i + 8 < nint; i += 16) {
+            for (; i + 24 < nint; i += 32) {
                 s0 += q[(size_t)i * stride];
                 s1 += q[(size_t)(i + 8) * stride];
+                s2 += q[(size_t)(i + 16) * stride];
+                s3 += q[(size_t)(i + 24) * stride];
             }
-            if (i < nint) s0 += q[(size_t)i * stride];
-            acc = fma(w, s0 + s1, acc);
+            for (; i < nint; i += 8) s0 += q[(size_t)i * stride];
+            acc = fma(w, (s0 + s1) + (s2 + s3), acc);
         }
     }
     red[tid] = acc;
@@ -2501,10 +2520,10 @@ int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hi
     T.mark();
     hipLaunchKernelGGL(k_fin_seq, dim3(p.B), dim3(NT), 0, st, p);
     {
-        size_t n = (size_t)p.B * p.T * p.C;
+        size_t n = (size_t)p.T * p.C;
         size_t blocks = (n + NT - 1) / NT;
-        if (blocks > 65536) blocks = 65536;
-        hipLaunchKernelGGL(k_fin_emis, dim3((unsigned)blocks), dim3(NT), 0, st, p);
+        if (blocks > 16384) blocks = 16384;
+        hipLaunchKernelGGL(k_fin_emis, dim3((unsigned)blocks, p.B), dim3(NT), 0, st, p);
     }
     {
         int n = p.C * p.C + p.K * p.C;
