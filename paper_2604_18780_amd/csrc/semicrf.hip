@@ -1823,6 +1823,10 @@ __device__ __forceinline__ void spec_task(const Params &p, double *lds_raw, cons
     while (t != tend) {
         const int nb = block_len(t);
         const int tn = BWD ? t - nb : t + nb;
+        // the next block's rows, requested before this block's stores: loads and stores retire in
+        // order, so a load issued after a store could not be waited for without the store
+        double2 en[MB];
+        load_rows(en, tn);
         const int t1 = BWD ? t - 1 : t + 1;
         const bool inchunk = keep && t >= tstart;  // blocks end at tstart, so this holds for the whole block
         const bool boundary = BWD ? (t & Jm) == 0 : (t1 & Jm) == 0;
@@ -1883,7 +1887,8 @@ __device__ __forceinline__ void spec_task(const Params &p, double *lds_raw, cons
             }
         }
         t = tn;
-        load_rows(e, t);  // the next block's rows (first use a block's window pass later)
+#pragma unroll
+        for (int i = 0; i < MB; ++i) e[i] = en[i];
         if (__builtin_expect(t == tstart, 0)) {
             record(t, ck1 + (size_t)istart * ckstride, ckY1 + istart);
             start_rows();
@@ -1921,14 +1926,17 @@ __global__ __launch_bounds__(64) void k_spec_cmp(Params p, int tier)
     const double *A2 = (dir ? p.ckB2 : p.ckA2) + ((size_t)b * (N + 1) + j) * ckstride;  // reached state
     const double Y = (dir ? p.ckYB : p.ckYA)[(size_t)b * (N + 1) + j];
     const double Y2 = (dir ? p.ckYB2 : p.ckYA2)[(size_t)b * (N + 1) + j];
-    double s1 = 0.0, s2 = 0.0;
-    for (int i = 0; i < C; ++i) {
-        s1 += A[KC + i];
-        s2 += A2[KC + i];
+    // sums of the two message vectors (their ratio is the common scale factor); C <= 64 here
+    double s1 = lane < C ? A[KC + lane] : 0.0, s2 = lane < C ? A2[KC + lane] : 0.0;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        s1 += __shfl_xor(s1, off);
+        s2 += __shfl_xor(s2, off);
     }
     const double f = s2 / s1;  // reached = f * 2^(Y2-Y) * warm-up, entry by entry, if they agree
     double err = 0.0;
     if (!(s1 > 0.0) || !(s2 > 0.0) || !(f > 0.0) || !(f < DBL_MAX)) err = DBL_MAX;
+#pragma unroll 4
     for (int i = lane; i < KC + C; i += 64) {
         const double x = A2[i], y = A[i] * f;
         const double m = fmax(fabs(x), fabs(y));

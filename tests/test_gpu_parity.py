@@ -196,6 +196,28 @@ def test_slow_mixing_input_falls_back_to_the_sequential_scan():
     assert_outputs_match_oracle(out, r)
 
 
+def test_sizes_beyond_the_one_wave_kernels_use_the_generic_kernels():
+    """K too long for the register strips of the one-wave kernels (C=24: K > 128): the generic
+    scan and interval kernels compute the result, sequentially."""
+    w = synth.small_random(81, 2, 300, 200, 24, ragged=True)
+    r = oracle.fwd_bwd(w.emis, w.lengths, w.trans, w.dur)
+    out, acc, mis = run_with_report(w, sb.SEMICRF_CENTER, 0)
+    assert np.all(acc == 0) and np.all(mis == -1)
+    assert_outputs_match_oracle(out, r)
+
+
+def test_more_than_64_labels_forward_only():
+    """C > 64 is supported for logZ only (generic scan kernel); gradients are refused."""
+    w = synth.small_random(82, 2, 120, 6, 100, ragged=True)
+    emis, lengths, trans, dur = to_dev(w)
+    lz = sb.semicrf_logz_fwd(emis, lengths, trans, dur).double().cpu().numpy()
+    ref = oracle.logz(w.emis, w.lengths, w.trans, w.dur)
+    assert np.abs(lz - ref).max() <= 1e-5 * np.abs(ref).max()
+    with pytest.raises(sb.SemiCRFError) as ei:
+        sb.semicrf_fwd_bwd(emis, lengths, trans, dur)
+    assert ei.value.status == -3
+
+
 def test_cum_scores_matches_oracle_prefix_sums():
     w = synth.small_random(51, 3, 700, 4, 9, ragged=True)
     w.lengths[:] = [700, 256, 0]
