@@ -1282,17 +1282,41 @@ struct WaveWin {
 // accumulators, its part of the transition row/column and the matching grad_trans
 // accumulators in registers for the whole task.
 // ---------------------------------------------------------------------------
-template <int CT, int NKW>
-__global__ __launch_bounds__(64) void k_interval_wave(Params p)
+// With 64 labels a lane owns a whole 64-entry row or column of the transition matrix, which
+// does not fit the registers next to the duration strips.  Both orientations of the matrix
+// then live in LDS ([source][lane] order, conflict-free), shared by the IWAVES independent
+// single-wave tasks of a workgroup.
+__host__ __device__ constexpr int interval_waves(int CT) { return CT == 64 ? 4 : 1; }
+
+__host__ __device__ constexpr size_t interval_lds_doubles(int CT, int NKW)
 {
+    return (CT == 64 ? 2 * (size_t)CT * CT : 0) + (size_t)interval_waves(CT) * wave_lds_doubles(CT, NKW);
+}
+
+template <int CT, int NKW>
+__global__ __launch_bounds__(64 * interval_waves(CT)) void k_interval_wave(Params p)
+{
+    constexpr bool ELDS = CT == 64;
+    constexpr int IW = interval_waves(CT);
     using G = WaveWin<CT, NKW>;
     constexpr int CTP = G::CTP, RS = G::RS, NK = G::NK, KW = G::KW, M = G::M, ROWS = G::ROWS;
     constexpr int RTOT = G::RTOT, H = G::H, HC = G::HC, YS = G::YS, TRN = G::TRN;
     typedef double double4_t __attribute__((ext_vector_type(4)));
     extern __shared__ double lds_raw[];
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int K = p.K, C = p.C, KC = K * C, CC = C * C;
-    double *ring = lds_raw;          // [ROWS][RS] (+ pad)
+    double *EtF = lds_raw;                        // [o][c] = Etr[o,c]   (forward:  z(c) = sum_o a(o) Etr[o,c])
+    double *EtB = lds_raw + (ELDS ? CT * CT : 0);  // [o][c] = Etr[c,o]   (backward: b(c) = sum_o Etr[c,o] p(o))
+    if (ELDS) {
+        for (int i = threadIdx.x; i < CT * CT; i += 64 * IW) {
+            const int o = i / CT, cl = i % CT;
+            const bool ok = o < C && cl < C;
+            EtF[i] = ok ? p.Etr[(size_t)o * C + cl] : 0.0;
+            EtB[i] = ok ? p.Etr[(size_t)cl * C + o] : 0.0;
+        }
+        __syncthreads();  // the only workgroup-wide synchronisation: the waves are independent from here
+    }
+    double *ring = lds_raw + (ELDS ? 2 * CT * CT : 0) + (size_t)wave * (RTOT + MB * YS);  // [ROWS][RS] (+ pad)
     double *yv = ring + RTOT;        // [MB][YS]: message vector of each position of a block (row 0 outside the beta pass)
     const int Delta = p.Delta, N = p.N;
     const size_t ckstride = (size_t)KC + C;
@@ -1301,8 +1325,9 @@ __global__ __launch_bounds__(64) void k_interval_wave(Params p)
     const bool cval = c < C;
     const int cc = cval ? c : 0;
     const bool writer = cval && g == 0;  // one lane per label
-    double2 *aloc = (double2 *)p.aloc + (size_t)blockIdx.x * Delta * C;
-    double *alocY = p.alocY + (size_t)blockIdx.x * Delta;
+    const int slot = blockIdx.x * IW + wave;
+    double2 *aloc = (double2 *)p.aloc + (size_t)slot * Delta * C;
+    double *alocY = p.alocY + (size_t)slot * Delta;
 
     // task-invariant registers
     double wx[NK + MB - 1];  // W[g*NK + jj + 1, c]
@@ -1314,8 +1339,13 @@ __global__ __launch_bounds__(64) void k_interval_wave(Params p)
     double wn[MB - 1];       // W[1..MB-1, c]: durations inside a block
 #pragma unroll
     for (int jj = 0; jj < MB - 1; ++jj) wn[jj] = (cval && jj + 1 <= K) ? p.W[(size_t)jj * C + c] : 0.0;
-    double Ereg[HC];         // this lane's part of the transition column (forward) / row (backward)
+    double Ereg[ELDS ? 2 : HC];  // this lane's part of the transition column (forward) / row (backward)
+    const double *et = EtF + c;  // LDS variant: coefficient of source o at et[o * CT]
     auto load_etr = [&](bool backward) {
+        if (ELDS) {
+            et = (backward ? EtB : EtF) + c;
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < HC; ++i) {
             const int o = hh * HC + i;
@@ -1332,7 +1362,7 @@ __global__ __launch_bounds__(64) void k_interval_wave(Params p)
     };
 
     const int ntask = p.B * N;
-    for (int task = blockIdx.x; task < ntask; task += gridDim.x) {
+    for (int task = slot; task < ntask; task += gridDim.x * IW) {
         const int b = task / N, iv = task % N;
         const SeqHdr h = p.hdr[b];
         const int L = h.L, J = h.J, Jm = J - 1;
@@ -1420,8 +1450,8 @@ __global__ __launch_bounds__(64) void k_interval_wave(Params p)
 #pragma unroll
                         for (int o = 0; o < HC; o += 2) {
                             const double2 vv = ys[o >> 1];
-                            z0 = fma(vv.x, Ereg[o], z0);
-                            z1 = fma(vv.y, Ereg[o + 1], z1);
+                            z0 = fma(vv.x, ELDS ? et[o * CT] : Ereg[ELDS ? 0 : o], z0);
+                            z1 = fma(vv.y, ELDS ? et[(o + 1) * CT] : Ereg[ELDS ? 1 : o + 1], z1);
                         }
                         double z = z0 + z1;
                         if (H == 2) z = add_across_32(z);
@@ -1579,8 +1609,8 @@ __global__ __launch_bounds__(64) void k_interval_wave(Params p)
 #pragma unroll
                         for (int o = 0; o < HC; o += 2) {
                             const double2 vv = ys[(i * YS + o) >> 1];
-                            z0 = fma(vv.x, Ereg[o], z0);
-                            z1 = fma(vv.y, Ereg[o + 1], z1);
+                            z0 = fma(vv.x, ELDS ? et[o * CT] : Ereg[ELDS ? 0 : o], z0);
+                            z1 = fma(vv.y, ELDS ? et[(o + 1) * CT] : Ereg[ELDS ? 1 : o + 1], z1);
                         }
                         double z = z0 + z1;
                         if (H == 2) z = add_across_32(z);
@@ -2237,6 +2267,7 @@ int make_plan(int B, int T, int K, int C, int ckpt_interval, int want_grad, Plan
     if (want_grad && (pl->lds_interval > LDS_LIMIT || C > GRAD_CMAX)) return SEMICRF_EUNSUPPORTED;
     size_t ntask = (size_t)B * pl->N;
     pl->nslot = (int)(ntask < (size_t)NSLOT_MAX ? ntask : (size_t)NSLOT_MAX);
+    pl->nslot = (pl->nslot + 3) & ~3;  // whole workgroups of four single-wave tasks (64 labels)
     const size_t b = (size_t)B, t1 = (size_t)T + 1, c = (size_t)C, k = (size_t)K, n = (size_t)pl->N;
     const size_t n1 = n;
     size_t sz[32];
@@ -2373,12 +2404,13 @@ int launch_scan(const Params &p, const Plan &pl, hipStream_t st, bool both)
 template <int CT, int NKW>
 int launch_interval_wave(const Params &p, const Plan &pl, hipStream_t st)
 {
-    const size_t lds = wave_lds_doubles(CT, NKW) * sizeof(double);
+    constexpr int IW = interval_waves(CT);
+    const size_t lds = interval_lds_doubles(CT, NKW) * sizeof(double);
     if (lds > LDS_LIMIT) return 1;
     if (hipFuncSetAttribute((const void *)k_interval_wave<CT, NKW>,
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return SEMICRF_ELAUNCH;
-    hipLaunchKernelGGL((k_interval_wave<CT, NKW>), dim3(pl.nslot), dim3(64), lds, st, p);
+    hipLaunchKernelGGL((k_interval_wave<CT, NKW>), dim3((pl.nslot + IW - 1) / IW), dim3(64 * IW), lds, st, p);
     return check_launch();
 }
 
