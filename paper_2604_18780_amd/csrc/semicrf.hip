@@ -1193,7 +1193,6 @@ __global__ __launch_bounds__(NT) void k_interval(Params p)
 // from registers while the positions are finished one after the other.
 // ---------------------------------------------------------------------------
 constexpr int MB = 4;  // positions per time block
-constexpr int WCH = 8; // window entries loaded per group in the register-heavy beta pass
 
 // Window entries per lane: NKW, plus one when a half-wave holds several lane groups, so
 // that the groups' rows fall into different LDS banks.
@@ -1286,18 +1285,28 @@ struct WaveWin {
 // does not fit the registers next to the duration strips.  Both orientations of the matrix
 // then live in LDS ([source][lane] order, conflict-free), shared by the IWAVES independent
 // single-wave tasks of a workgroup.
-__host__ __device__ constexpr int interval_waves(int CT) { return CT == 64 ? 4 : 1; }
+// With the longest duration strips (NKW = 64) the strip of weights and the strip of grad_dur
+// accumulators do not both fit the registers; the weights then live in LDS as well, W[m+1, c]
+// at [m*CT + c] (zero beyond K), and are read once per block like the window.
+__host__ __device__ constexpr int interval_waves(int CT, int NKW) { return CT == 64 ? 4 : (NKW == 64 ? 3 : 1); }
+
+__host__ __device__ constexpr size_t interval_wtab_doubles(int CT, int NKW)
+{
+    return NKW == 64 ? (size_t)(wave_nk(CT, NKW) * (64 / pow2_ge8(CT)) + MB) * CT + (size_t)(pow2_ge8(CT) - CT) : 0;
+}
 
 __host__ __device__ constexpr size_t interval_lds_doubles(int CT, int NKW)
 {
-    return (CT == 64 ? 2 * (size_t)CT * CT : 0) + (size_t)interval_waves(CT) * wave_lds_doubles(CT, NKW);
+    return (CT == 64 ? 2 * (size_t)CT * CT : 0) + interval_wtab_doubles(CT, NKW) +
+           (size_t)interval_waves(CT, NKW) * wave_lds_doubles(CT, NKW);
 }
 
 template <int CT, int NKW>
-__global__ __launch_bounds__(64 * interval_waves(CT)) void k_interval_wave(Params p)
+__global__ __launch_bounds__(64 * interval_waves(CT, NKW)) void k_interval_wave(Params p)
 {
     constexpr bool ELDS = CT == 64;
-    constexpr int IW = interval_waves(CT);
+    constexpr bool WLDS = NKW == 64;
+    constexpr int IW = interval_waves(CT, NKW);
     using G = WaveWin<CT, NKW>;
     constexpr int CTP = G::CTP, RS = G::RS, NK = G::NK, KW = G::KW, M = G::M, ROWS = G::ROWS;
     constexpr int RTOT = G::RTOT, H = G::H, HC = G::HC, YS = G::YS, TRN = G::TRN;
@@ -1314,9 +1323,17 @@ __global__ __launch_bounds__(64 * interval_waves(CT)) void k_interval_wave(Param
             EtF[i] = ok ? p.Etr[(size_t)o * C + cl] : 0.0;
             EtB[i] = ok ? p.Etr[(size_t)cl * C + o] : 0.0;
         }
-        __syncthreads();  // the only workgroup-wide synchronisation: the waves are independent from here
     }
-    double *ring = lds_raw + (ELDS ? 2 * CT * CT : 0) + (size_t)wave * (RTOT + MB * YS);  // [ROWS][RS] (+ pad)
+    double *Wl = lds_raw + (ELDS ? 2 * CT * CT : 0);
+    constexpr int WTAB = (int)interval_wtab_doubles(CT, NKW);
+    if (WLDS) {
+        for (int i = threadIdx.x; i < WTAB; i += 64 * IW) {
+            const int m = i / CT, col = i % CT;
+            Wl[i] = (m < K && col < C) ? p.W[(size_t)m * C + col] : 0.0;
+        }
+    }
+    if (ELDS || WLDS) __syncthreads();  // the only workgroup-wide synchronisation: the waves are independent from here
+    double *ring = Wl + WTAB + (size_t)wave * (RTOT + MB * YS);  // [ROWS][RS] (+ pad)
     double *yv = ring + RTOT;        // [MB][YS]: message vector of each position of a block (row 0 outside the beta pass)
     const int Delta = p.Delta, N = p.N;
     const size_t ckstride = (size_t)KC + C;
@@ -1330,12 +1347,15 @@ __global__ __launch_bounds__(64 * interval_waves(CT)) void k_interval_wave(Param
     double *alocY = p.alocY + (size_t)slot * Delta;
 
     // task-invariant registers
-    double wx[NK + MB - 1];  // W[g*NK + jj + 1, c]
+    double wx[WLDS ? 1 : NK + MB - 1];  // W[g*NK + jj + 1, c] (register variant)
+    if (!WLDS) {
 #pragma unroll
-    for (int jj = 0; jj < NK + MB - 1; ++jj) {
-        const int k = g * NK + jj + 1;
-        wx[jj] = (cval && k <= K) ? p.W[(size_t)(k - 1) * C + c] : 0.0;
+        for (int jj = 0; jj < NK + MB - 1; ++jj) {
+            const int k = g * NK + jj + 1;
+            wx[WLDS ? 0 : jj] = (cval && k <= K) ? p.W[(size_t)(k - 1) * C + c] : 0.0;
+        }
     }
+    const double *wl = Wl + g * NK * CT + c;  // LDS variant: W[g*NK + m + 1, c] at wl[m*CT]
     double wn[MB - 1];       // W[1..MB-1, c]: durations inside a block
 #pragma unroll
     for (int jj = 0; jj < MB - 1; ++jj) wn[jj] = (cval && jj + 1 <= K) ? p.W[(size_t)jj * C + c] : 0.0;
@@ -1428,11 +1448,23 @@ __global__ __launch_bounds__(64 * interval_waves(CT)) void k_interval_wave(Param
                 double acc[MB];
 #pragma unroll
                 for (int i = 0; i < MB; ++i) acc[i] = 0.0;
+                if (WLDS) {
+                    double v[NK];
 #pragma unroll
-                for (int jj = 0; jj < NK; ++jj) {
-                    const double v = base[(NK - 1 - jj) * RS];  // distance g*NK + jj from the newest
+                    for (int m = 0; m < NK + MB - 1; ++m) {
+                        const double w = wl[m * CT];
+                        if (m < NK) v[m] = base[(NK - 1 - m) * RS];
 #pragma unroll
-                    for (int i = 0; i < MB; ++i) acc[i] = fma(wx[jj + i], v, acc[i]);
+                        for (int i = 0; i < MB; ++i)
+                            if (m - i >= 0 && m - i < NK) acc[i] = fma(w, v[m - i], acc[i]);
+                    }
+                } else {
+#pragma unroll
+                    for (int jj = 0; jj < NK; ++jj) {
+                        const double v = base[(NK - 1 - jj) * RS];  // distance g*NK + jj from the newest
+#pragma unroll
+                        for (int i = 0; i < MB; ++i) acc[i] = fma(wx[WLDS ? 0 : jj + i], v, acc[i]);
+                    }
                 }
 #pragma unroll
                 for (int i = 0; i < MB; ++i) acc[i] = group_sum<CTP>(acc[i]);
@@ -1569,22 +1601,28 @@ __global__ __launch_bounds__(64 * interval_waves(CT)) void k_interval_wave(Param
                 double acc[MB];
 #pragma unroll
                 for (int i = 0; i < MB; ++i) acc[i] = 0.0;
-                // in groups of WCH entries, so that the loaded values do not all sit in registers at once
+                if (WLDS) {
+                    double v[NK];
 #pragma unroll
-                for (int j0 = 0; j0 < NK; j0 += WCH) {
-                    double v[WCH];
+                    for (int m = 0; m < NK + MB - 1; ++m) {
+                        const double w = wl[m * CT];
+                        if (m < NK) v[m] = base[m * RS];  // distance g*NK + m from the newest
 #pragma unroll
-                    for (int u = 0; u < WCH; ++u)
-                        if (j0 + u < NK) v[u] = base[(j0 + u) * RS];  // distance g*NK + j0 + u from the newest
-                    asm volatile("" ::: "memory");
-#pragma unroll
-                    for (int u = 0; u < WCH; ++u) {
-                        if (j0 + u < NK) {
-#pragma unroll
-                            for (int i = 0; i < MB; ++i) {
-                                acc[i] = fma(wx[j0 + u + i], v[u], acc[i]);
-                                dx[j0 + u + i] = fma(coef[i], v[u], dx[j0 + u + i]);
+                        for (int i = 0; i < MB; ++i) {
+                            if (m - i >= 0 && m - i < NK) {
+                                acc[i] = fma(w, v[m - i], acc[i]);
+                                dx[m] = fma(coef[i], v[m - i], dx[m]);
                             }
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int jj = 0; jj < NK; ++jj) {
+                        const double v = base[jj * RS];  // distance g*NK + jj from the newest
+#pragma unroll
+                        for (int i = 0; i < MB; ++i) {
+                            acc[i] = fma(wx[WLDS ? 0 : jj + i], v, acc[i]);
+                            dx[jj + i] = fma(coef[i], v, dx[jj + i]);
                         }
                     }
                 }
@@ -1675,7 +1713,8 @@ __global__ __launch_bounds__(64 * interval_waves(CT)) void k_interval_wave(Param
 #pragma unroll
         for (int jj = 0; jj < NK; ++jj) {
             const int k = g * NK + jj + 1;
-            if (cval && k <= K) pD[(size_t)(k - 1) * C + c] = wx[jj] * tmp[(k - 1) * CT + c];
+            if (cval && k <= K)
+                pD[(size_t)(k - 1) * C + c] = (WLDS ? wl[jj * CT] : wx[WLDS ? 0 : jj]) * tmp[(k - 1) * CT + c];
         }
         lds_wave_fence();
         double *pT = p.partTr + ((size_t)b * N + iv) * CC;
@@ -2188,17 +2227,27 @@ __global__ __launch_bounds__(NT) void k_fin_params(Params p)
 // ---------------------------------------------------------------------------
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
-// LDS bytes of one single-wave task for these sizes, 0 when the one-wave kernels do not apply.
-size_t wave_task_lds(int K, int C)
+// Single-wave tasks a compute unit holds at once for these sizes (scan kernel, interval
+// kernel): bounded by the LDS windows and by registers (two scan waves per SIMD, one where
+// the kernel needs more than 256 registers; one interval wave per SIMD).  False when the
+// one-wave kernels do not apply.
+bool wave_tasks_per_cu(int K, int C, int *scan, int *interval)
 {
-    if (C > 64) return 0;
+    if (C > 64) return false;
     const int CT = C <= 8 ? 8 : (C <= 16 ? 16 : (C <= 24 ? 24 : (C <= 32 ? 32 : 64)));
     const int GW = 64 / pow2_ge8(CT);
     const int per_lane = (K + GW - 1) / GW;
-    if (per_lane > 64) return 0;
+    if (per_lane > 64) return false;
     const int NKW = per_lane <= 16 ? 16 : (per_lane <= 32 ? 32 : 64);
     const size_t lds = wave_lds_doubles(CT, NKW) * sizeof(double);
-    return lds <= LDS_LIMIT ? lds : 0;
+    if (lds > LDS_LIMIT) return false;
+    const int fit = (int)(LDS_LIMIT / lds);
+    const int scan_regs = (CT == 64 || (CT == 32 && NKW == 64)) ? 4 : 8;
+    *scan = fit < scan_regs ? fit : scan_regs;
+    const size_t ilds = interval_lds_doubles(CT, NKW) * sizeof(double);
+    int iw = ilds <= LDS_LIMIT ? (int)(LDS_LIMIT / ilds) * interval_waves(CT, NKW) : 1;  // else the generic kernel
+    *interval = iw < 4 ? iw : 4;
+    return true;
 }
 
 // Automatic checkpoint interval.  Every (sequence, interval) is one single-wave task of the
@@ -2212,16 +2261,16 @@ size_t wave_task_lds(int K, int C)
 // so checkpoints and per-task buffers still grow like sqrt(T) for very long sequences.
 int auto_interval(int B, int T, int K, int C)
 {
-    const size_t lds = wave_task_lds(K, C);
-    if (lds == 0) {  // generic kernels: sqrt(T*K) spacing scaled to spread B*T/interval tasks over 256 units
+    int per_scan = 0, per_int = 0;
+    if (!wave_tasks_per_cu(K, C, &per_scan, &per_int)) {
+        // generic kernels: sqrt(T*K) spacing scaled to spread B*T/interval tasks over 256 units
         double d = ceil(sqrt((double)T * (double)K * (double)B / 256.0));
         int di = d < 1.0 ? 1 : (int)d;
         if (di >= 8) di = (di + 7) & ~7;
         return di > T ? T : di;
     }
-    const long per_cu = (long)(LDS_LIMIT / lds);
-    const double slots_scan = 256.0 * (double)(per_cu < 8 ? per_cu : 8);
-    const double slots_int = 256.0 * (double)(per_cu < 4 ? per_cu : 4);
+    const double slots_scan = 256.0 * per_scan;
+    const double slots_int = 256.0 * per_int;
     const double warm = 2 * K < 32 ? 32.0 : 2.0 * K;
     const int dlo = K / 2 < 8 ? 8 : K / 2;
     int dhi = (int)ceil(sqrt((double)T * (double)K));
@@ -2267,7 +2316,7 @@ int make_plan(int B, int T, int K, int C, int ckpt_interval, int want_grad, Plan
     if (want_grad && (pl->lds_interval > LDS_LIMIT || C > GRAD_CMAX)) return SEMICRF_EUNSUPPORTED;
     size_t ntask = (size_t)B * pl->N;
     pl->nslot = (int)(ntask < (size_t)NSLOT_MAX ? ntask : (size_t)NSLOT_MAX);
-    pl->nslot = (pl->nslot + 3) & ~3;  // whole workgroups of four single-wave tasks (64 labels)
+    pl->nslot = (pl->nslot + 11) / 12 * 12;  // whole workgroups of three or four single-wave tasks
     const size_t b = (size_t)B, t1 = (size_t)T + 1, c = (size_t)C, k = (size_t)K, n = (size_t)pl->N;
     const size_t n1 = n;
     size_t sz[32];
@@ -2404,7 +2453,7 @@ int launch_scan(const Params &p, const Plan &pl, hipStream_t st, bool both)
 template <int CT, int NKW>
 int launch_interval_wave(const Params &p, const Plan &pl, hipStream_t st)
 {
-    constexpr int IW = interval_waves(CT);
+    constexpr int IW = interval_waves(CT, NKW);
     const size_t lds = interval_lds_doubles(CT, NKW) * sizeof(double);
     if (lds > LDS_LIMIT) return 1;
     if (hipFuncSetAttribute((const void *)k_interval_wave<CT, NKW>,
