@@ -2252,7 +2252,7 @@ bool wave_tasks_per_cu(int K, int C, int *scan, int *interval)
 
 // Automatic checkpoint interval.  Every (sequence, interval) is one single-wave task of the
 // chunk-parallel scans (both directions, interval + warm-up positions each) and of the
-// interval stage (interval positions, about 2.2x the cost per position).  Tasks run in
+// interval stage (interval positions, about 1.2x the cost per position and round).  Tasks run in
 // rounds of as many as fit the chip at once (256 compute units; per compute unit 8 scan
 // waves or 4 interval waves by registers, fewer when the K-deep LDS window is large), and
 // a partly filled round costs a full one.  The interval is the multiple of 8 that
@@ -2284,7 +2284,7 @@ int auto_interval(int B, int T, int K, int C)
         if (d > dhi && n > 1) continue;
         if (d < dlo && best) break;
         const double tasks = (double)B * (double)((T + d - 1) / d);
-        const double cost = ceil(2.0 * tasks / slots_scan) * (warm + d) + 2.2 * ceil(tasks / slots_int) * d;
+        const double cost = ceil(2.0 * tasks / slots_scan) * (warm + d) + 1.2 * ceil(tasks / slots_int) * d;
         if (!best || cost < best_cost) {
             best = d;
             best_cost = cost;
