@@ -25,12 +25,14 @@
 // multiplications by powers of two at block boundaries.  logZ = Y ln 2 +
 // log(sum_c a_L(c)).
 //
-// Kernels: k_tables, k_colsum, k_prep_seq, k_prefix (Eq. 1-2), k_scan (Algorithm 1
-// and the beta recurrence of Algorithm 3 as two concurrent scans that write ring
-// checkpoints every Delta positions), k_interval (per checkpoint interval:
-// recompute the forward messages, run beta across the interval, accumulate the
-// expected sufficient statistics in registers/LDS, no global atomics),
-// k_fin_seq / k_fin_emis / k_fin_params (fixed-order reductions).
+// Kernels: k_colsum (+ the exp tables), k_prep_seq, k_prefix (Eq. 1-2); k_spec, k_spec_cmp,
+// k_spec_fix (Algorithm 1 and the beta recurrence of Algorithm 3 as chunk-parallel scans
+// that are verified at every chunk boundary and write ring checkpoints every Delta
+// positions); k_scan_fast / k_scan (the same scans sequentially, for what the verification
+// rejects); k_interval_wave / k_interval (per checkpoint interval: recompute the forward
+// messages unless the scan stored them, run beta across the interval, accumulate the
+// expected sufficient statistics in registers/LDS, no global atomics); k_fin_seq (+ the
+// parameter gradients), k_fin_emis (fixed-order reductions).
 #include <hip/hip_runtime.h>
 #include <float.h>
 #include <math.h>
@@ -126,7 +128,7 @@ __device__ __forceinline__ int seq_len(const Params &p, int b)
 // ---------------------------------------------------------------------------
 // exp(dur), exp(trans) in fp64 and the maxima that bound per-step growth.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(NT) void k_tables(Params p)
+__device__ __forceinline__ void tables_body(const Params &p)
 {
     __shared__ double red[NT];
     const int tid = threadIdx.x;
@@ -166,11 +168,11 @@ __global__ __launch_bounds__(NT) void k_tables(Params p)
 // ---------------------------------------------------------------------------
 // Eq. 1, stage 1: per-chunk column sums (fp64) and |f| maxima.  grid (NCH, B).
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(NT) void k_colsum(Params p)
+__device__ __forceinline__ void colsum_body(const Params &p, const int b, const int ch)
 {
     __shared__ double red[NT];
     __shared__ double redm[NT];
-    const int b = blockIdx.y, ch = blockIdx.x, tid = threadIdx.x;
+    const int tid = threadIdx.x;
     const int C = p.C, L = seq_len(p, b);
     const int u0 = ch * PREP_CH;
     const int u1 = min(u0 + PREP_CH, L);
@@ -199,6 +201,17 @@ __global__ __launch_bounds__(NT) void k_colsum(Params p)
         for (int i = 0; i < R * C; ++i) m = fmax(m, redm[i]);
         p.chmax[(size_t)b * p.NCH + ch] = m;
     }
+}
+
+// One launch for both: workgroup 0 builds the tables, workgroup 1 + b*NCH + ch sums a chunk.
+__global__ __launch_bounds__(NT) void k_colsum(Params p)
+{
+    if (blockIdx.x == 0) {
+        tables_body(p);
+        return;
+    }
+    const int id = blockIdx.x - 1;
+    colsum_body(p, id / p.NCH, id % p.NCH);
 }
 
 // ---------------------------------------------------------------------------
@@ -2108,11 +2121,11 @@ __global__ void k_spec_report(Params p, int32_t *accepted, double *mismatch)
 // carry[b,i,c] = sum_{i'<=i} tot[b,i',c];  mean[b,c] = (1/L) sum_u pm[b,u,c].  grid B, NT threads:
 // the intervals are split into G = NT/C contiguous chunks, one per thread group; chunk sums are
 // combined in chunk order, so the result does not depend on the launch shape.
-__global__ __launch_bounds__(NT) void k_fin_seq(Params p)
+__device__ __forceinline__ void fin_seq_body(const Params &p, const int b)
 {
     __shared__ double gsum[NT];
     __shared__ double gtot[NT];
-    const int b = blockIdx.x, C = p.C, N = p.N, tid = threadIdx.x;
+    const int C = p.C, N = p.N, tid = threadIdx.x;
     const int L = p.hdr[b].L;
     const int nint = (L + p.Delta - 1) / p.Delta;
     const int G = NT / C;
@@ -2184,12 +2197,12 @@ __global__ __launch_bounds__(NT) void k_fin_emis(Params p)
 // grad_trans[c',c] = Etr[c',c] * sum_b w_b sum_i partTr;  grad_dur[k,c] = sum_b w_b sum_i partD.
 // One workgroup per 32 outputs; 8 thread groups take the intervals i = g, g+8, ... and their
 // sums are combined in group order (fixed order for a given problem).
-__global__ __launch_bounds__(NT) void k_fin_params(Params p)
+__device__ __forceinline__ void fin_params_body(const Params &p, const int blk)
 {
     __shared__ double red[NT];
     const int C = p.C, CC = C * C, KC = p.K * C, N = p.N, tid = threadIdx.x;
     const int o = tid & 31, g = tid >> 5;
-    const int idx = blockIdx.x * 32 + o;
+    const int idx = blk * 32 + o;
     const bool ok = idx < CC + KC;
     double acc = 0.0;
     if (ok) {
@@ -2220,6 +2233,14 @@ __global__ __launch_bounds__(NT) void k_fin_params(Params p)
         if (idx < CC) p.grad_trans[idx] = (float)(t * p.Etr[idx]);
         else p.grad_dur[idx - CC] = (float)t;
     }
+}
+
+// One launch for the two independent reductions: workgroups 0..B-1 per sequence, the rest
+// per 32 parameter gradients.
+__global__ __launch_bounds__(NT) void k_fin_seq(Params p)
+{
+    if ((int)blockIdx.x < p.B) fin_seq_body(p, blockIdx.x);
+    else fin_params_body(p, blockIdx.x - p.B);
 }
 
 // ---------------------------------------------------------------------------
@@ -2398,8 +2419,7 @@ int check_launch()
 // prefix stage shared by all entry points
 int launch_prep(const Params &p, hipStream_t st)
 {
-    hipLaunchKernelGGL(k_tables, dim3(1), dim3(NT), 0, st, p);
-    hipLaunchKernelGGL(k_colsum, dim3(p.NCH, p.B), dim3(NT), 0, st, p);
+    hipLaunchKernelGGL(k_colsum, dim3(1 + p.NCH * p.B), dim3(NT), 0, st, p);
     hipLaunchKernelGGL(k_prep_seq, dim3(p.B), dim3(NT), 0, st, p);
     hipLaunchKernelGGL(k_prefix, dim3(p.NCH, p.B), dim3(NT), 0, st, p);
     return check_launch();
@@ -2607,16 +2627,12 @@ int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hi
     rc = launch_interval(p, pl, st);
     if (rc != SEMICRF_OK) return rc;
     T.mark();
-    hipLaunchKernelGGL(k_fin_seq, dim3(p.B), dim3(NT), 0, st, p);
+    hipLaunchKernelGGL(k_fin_seq, dim3(p.B + (p.C * p.C + p.K * p.C + 31) / 32), dim3(NT), 0, st, p);
     {
         size_t n = (size_t)p.T * p.C;
         size_t blocks = (n + NT - 1) / NT;
         if (blocks > 16384) blocks = 16384;
         hipLaunchKernelGGL(k_fin_emis, dim3((unsigned)blocks, p.B), dim3(NT), 0, st, p);
-    }
-    {
-        int n = p.C * p.C + p.K * p.C;
-        hipLaunchKernelGGL(k_fin_params, dim3((n + 31) / 32), dim3(NT), 0, st, p);
     }
     T.mark();
     return check_launch();
