@@ -1701,34 +1701,34 @@ __global__ __launch_bounds__(64 * interval_waves(CT, NKW)) void k_interval_wave(
             }
         }
         // ---- partials of this task.  Duration sums: the strips of neighbouring lane groups
-        // overlap by MB-1 durations; they are combined through LDS in a fixed order.
+        // overlap by MB-1 durations; they are combined through LDS in a fixed order (own strip,
+        // then the neighbour's overlap, then the in-block terms) and scaled by W[k,c].
         lds_wave_fence();
-        double *tmp = ring;  // [K][CT]
-        for (int i = lane; i < K * CT; i += 64) tmp[i] = 0.0;
-        lds_wave_fence();
+        double *tmp = ring;  // [KW + MB - 1][CT], row m = duration m + 1
+        {
+            double *tl = tmp + g * NK * CT + c;
+            if (cval) {
 #pragma unroll
-        for (int jj = 0; jj < NK; ++jj) {
-            const int k = g * NK + jj + 1;
-            if (cval && k <= K) tmp[(k - 1) * CT + c] = dx[jj];
+                for (int jj = 0; jj < NK; ++jj) tl[jj * CT] = dx[jj];
+            }
+            if (cval && g == G::GW - 1) {
+#pragma unroll
+                for (int jj = NK; jj < NK + MB - 1; ++jj) tl[jj * CT] = 0.0;
+            }
+            lds_wave_fence();
+            if (cval) {
+#pragma unroll
+                for (int jj = NK; jj < NK + MB - 1; ++jj) tl[jj * CT] += dx[jj];
+            }
+            lds_wave_fence();
+            if (writer) {
+#pragma unroll
+                for (int jj = 0; jj < MB - 1; ++jj) tl[jj * CT] += dn[jj];
+            }
+            lds_wave_fence();
         }
-        lds_wave_fence();
-#pragma unroll
-        for (int jj = NK; jj < NK + MB - 1; ++jj) {
-            const int k = g * NK + jj + 1;
-            if (cval && k <= K) tmp[(k - 1) * CT + c] += dx[jj];
-        }
-        lds_wave_fence();
-#pragma unroll
-        for (int jj = 0; jj < MB - 1; ++jj)
-            if (writer && jj + 1 <= K) tmp[jj * CT + c] += dn[jj];
-        lds_wave_fence();
         double *pD = p.partD + ((size_t)b * N + iv) * KC;
-#pragma unroll
-        for (int jj = 0; jj < NK; ++jj) {
-            const int k = g * NK + jj + 1;
-            if (cval && k <= K)
-                pD[(size_t)(k - 1) * C + c] = (WLDS ? wl[jj * CT] : wx[WLDS ? 0 : jj]) * tmp[(k - 1) * CT + c];
-        }
+        for (int i = lane; i < KC; i += 64) pD[i] = p.W[i] * tmp[(i / C) * CT + i % C];
         lds_wave_fence();
         double *pT = p.partTr + ((size_t)b * N + iv) * CC;
 #pragma unroll
