@@ -218,6 +218,18 @@ def test_more_than_64_labels_forward_only():
     assert ei.value.status == -3
 
 
+def test_more_tasks_than_buffer_slots():
+    """An explicit interval of 2 positions gives 2250 (sequence, interval) tasks, more than the
+    2048 task buffers: the interval kernel then loops over tasks and recomputes its forward rows
+    instead of taking them from the chunk-parallel scan."""
+    w = synth.small_random(91, 3, 1500, 6, 5, ragged=True)
+    w.lengths[:] = [1500, 1500, 1497]
+    r = oracle.fwd_bwd(w.emis, w.lengths, w.trans, w.dur)
+    out, acc, mis = run_with_report(w, sb.SEMICRF_CENTER, 2)
+    assert np.all(acc == 1)
+    assert_outputs_match_oracle(out, r)
+
+
 def test_cum_scores_matches_oracle_prefix_sums():
     w = synth.small_random(51, 3, 700, 4, 9, ragged=True)
     w.lengths[:] = [700, 256, 0]
