@@ -11,7 +11,9 @@ Algorithm 3 recurrences kept as full tables, the "Gradient Formulas" section).
 Every function here is pinned by ``tests/test_oracle_pins.py`` (brute-force
 enumeration, the K=1 linear-chain CRF, closed forms, finite differences,
 marginal invariants, the centring/duration-prior identity of Eq. 5, the toy
-baseline table).
+baseline table; the boundary terms of Eq. 4 by enumeration with those terms, by
+finite differences, by the K=1 chain with start/end scores and by the identity
+between scalar boundaries and projections at the first/last token).
 """
 from __future__ import annotations
 
@@ -46,6 +48,11 @@ def _load():
         lib.semicrf_oracle_fwd_bwd.argtypes = [dp, ip, dp, dp, dp] + [ctypes.c_int] * 6 + [dp] * 11
         lib.semicrf_oracle_logz.restype = ctypes.c_int
         lib.semicrf_oracle_logz.argtypes = [dp, ip, dp, dp] + [ctypes.c_int] * 6 + [dp]
+        lib.semicrf_oracle_fwd_bwd_boundary.restype = ctypes.c_int
+        lib.semicrf_oracle_fwd_bwd_boundary.argtypes = ([dp, ip, dp, dp, dp] + [dp] * 4 + [ctypes.c_int] * 6
+                                                        + [dp] * 16)
+        lib.semicrf_oracle_logz_boundary.restype = ctypes.c_int
+        lib.semicrf_oracle_logz_boundary.argtypes = [dp, ip, dp, dp] + [dp] * 4 + [ctypes.c_int] * 6 + [dp]
         _lib = lib
     return _lib
 
@@ -72,12 +79,21 @@ class OracleResult:
     alpha: np.ndarray | None = None  # [B,T+1,C]
     beta: np.ndarray | None = None   # [B,T+1,C]
     gS: np.ndarray | None = None     # [B,T+1,C] gradient w.r.t. the prefix sums
+    grad_proj_start: np.ndarray | None = None  # [B,T,C] gradient w.r.t. the start projections
+    grad_proj_end: np.ndarray | None = None    # [B,T,C] gradient w.r.t. the end projections
+    grad_pi_start: np.ndarray | None = None    # [C] gradient w.r.t. the scalar start boundary
+    grad_pi_end: np.ndarray | None = None      # [C] gradient w.r.t. the scalar end boundary
+    bdy_post: np.ndarray | None = None         # [B,T+1] posterior of a segment boundary at position t
 
 
 def fwd_bwd(emis, lengths, trans, dur, grad_logz=None, center=True, threads=0,
-            tables=False) -> OracleResult:
+            tables=False, proj_start=None, proj_end=None, pi_start=None, pi_end=None,
+            boundary=False) -> OracleResult:
     """Run the oracle.  emis [B,T,C], lengths [B] or None, trans [C,C]
-    (source label first), dur [K,C] (row k-1), grad_logz [B] or None."""
+    (source label first), dur [K,C] (row k-1), grad_logz [B] or None.
+    proj_start / proj_end [B,T,C] and pi_start / pi_end [C] are the optional boundary
+    terms of Eq. 4; with any of them (or boundary=True) the result also carries their
+    gradients and the boundary posterior."""
     lib = _load()
     emis = _as_f64(emis)
     B, T, C = emis.shape
@@ -102,6 +118,29 @@ def fwd_bwd(emis, lengths, trans, dur, grad_logz=None, center=True, threads=0,
     al = np.zeros((B, T + 1, C)) if tables else None
     be = np.zeros((B, T + 1, C)) if tables else None
     gS = np.zeros((B, T + 1, C)) if tables else None
+    if boundary or any(x is not None for x in (proj_start, proj_end, pi_start, pi_end)):
+        ps = None if proj_start is None else _as_f64(proj_start)
+        pe = None if proj_end is None else _as_f64(proj_end)
+        pis = None if pi_start is None else _as_f64(pi_start)
+        pie = None if pi_end is None else _as_f64(pi_end)
+        for a in (ps, pe):
+            assert a is None or a.shape == (B, T, C)
+        for a in (pis, pie):
+            assert a is None or a.shape == (C,)
+        gPs = np.zeros((B, T, C))
+        gPe = np.zeros((B, T, C))
+        gPis = np.zeros(C)
+        gPie = np.zeros(C)
+        bdy = np.zeros((B, T + 1))
+        rc = lib.semicrf_oracle_fwd_bwd_boundary(
+            _dptr(emis), lp, _dptr(trans), _dptr(dur), _dptr(w), _dptr(ps), _dptr(pe), _dptr(pis), _dptr(pie),
+            B, T, K, C, int(bool(center)), int(threads),
+            _dptr(logz), _dptr(gE), _dptr(pm), _dptr(gTr), _dptr(gD), _dptr(gTr_b), _dptr(gD_b),
+            _dptr(S), _dptr(al), _dptr(be), _dptr(gS), _dptr(gPs), _dptr(gPe), _dptr(gPis), _dptr(gPie),
+            _dptr(bdy))
+        if rc < 0:
+            raise ValueError("semicrf_oracle_fwd_bwd_boundary: bad arguments")
+        return OracleResult(logz, gE, pm, gTr, gD, gTr_b, gD_b, rc, S, al, be, gS, gPs, gPe, gPis, gPie, bdy)
     rc = lib.semicrf_oracle_fwd_bwd(_dptr(emis), lp, _dptr(trans), _dptr(dur), _dptr(w),
                                     B, T, K, C, int(bool(center)), int(threads),
                                     _dptr(logz), _dptr(gE), _dptr(pm), _dptr(gTr), _dptr(gD),
@@ -111,8 +150,9 @@ def fwd_bwd(emis, lengths, trans, dur, grad_logz=None, center=True, threads=0,
     return OracleResult(logz, gE, pm, gTr, gD, gTr_b, gD_b, rc, S, al, be, gS)
 
 
-def logz(emis, lengths, trans, dur, center=True, threads=0) -> np.ndarray:
-    """Forward pass only: logZ [B]."""
+def logz(emis, lengths, trans, dur, center=True, threads=0, proj_start=None, proj_end=None,
+         pi_start=None, pi_end=None) -> np.ndarray:
+    """Forward pass only: logZ [B] (optional boundary terms as in fwd_bwd)."""
     lib = _load()
     emis = _as_f64(emis)
     B, T, C = emis.shape
@@ -124,8 +164,17 @@ def logz(emis, lengths, trans, dur, center=True, threads=0) -> np.ndarray:
         lengths = np.ascontiguousarray(np.asarray(lengths), dtype=np.int32)
         lp = lengths.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
     out = np.zeros(B)
-    rc = lib.semicrf_oracle_logz(_dptr(emis), lp, _dptr(trans), _dptr(dur),
-                                 B, T, K, C, int(bool(center)), int(threads), _dptr(out))
+    if any(x is not None for x in (proj_start, proj_end, pi_start, pi_end)):
+        ps = None if proj_start is None else _as_f64(proj_start)
+        pe = None if proj_end is None else _as_f64(proj_end)
+        pis = None if pi_start is None else _as_f64(pi_start)
+        pie = None if pi_end is None else _as_f64(pi_end)
+        rc = lib.semicrf_oracle_logz_boundary(_dptr(emis), lp, _dptr(trans), _dptr(dur), _dptr(ps), _dptr(pe),
+                                              _dptr(pis), _dptr(pie), B, T, K, C, int(bool(center)),
+                                              int(threads), _dptr(out))
+    else:
+        rc = lib.semicrf_oracle_logz(_dptr(emis), lp, _dptr(trans), _dptr(dur),
+                                     B, T, K, C, int(bool(center)), int(threads), _dptr(out))
     if rc < 0:
         raise ValueError("semicrf_oracle_logz: bad arguments")
     return out

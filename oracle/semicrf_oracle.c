@@ -9,9 +9,13 @@
  * What it computes (per sequence b of true length L = lengths[b]):
  *   - the emission baseline nu[c] and the centred prefix sums S[t,c]
  *     (paper Eq. 1 and Eq. 2, masked mean over the L valid positions);
- *   - the three-term edge potential psi(t,k,c,c') of Eq. 4 without the
- *     optional boundary projections:
- *         psi = S[t,c] - S[t-k,c] + dur[k-1,c] + trans[c',c];
+ *   - the edge potential psi(t,k,c,c') of Eq. 4,
+ *         psi = S[t,c] - S[t-k,c] + dur[k-1,c] + trans[c',c] + bs[t-k,c] + be[t-1,c],
+ *     where bs / be are the optional boundary projections of the "Boundary
+ *     Projections" section (start score of the segment's first token, end score of
+ *     its last token; zero when absent), to which the optional scalar sequence
+ *     boundaries pi_start[c] / pi_end[c] are added at token 0 / token L-1
+ *     (appendix on boundary handling, composition rule);
  *   - log-forward messages alpha[t,c] by the recurrence of Algorithm 1
  *     (alpha[0,:] = 0, k <= min(K,t)) but with the FULL table kept: no ring
  *     buffer, no checkpoints, no normalisation;
@@ -22,7 +26,11 @@
  *     + beta[t+k,c] - logZ) ("Gradient Computation" section) and from them the
  *     expected sufficient statistics of the "Gradient Formulas" section:
  *         gS[t+k,c] += mu,  gS[t,c] -= mu,
- *         gTr[c',c] += w*mu, gD[k-1,c] += w*mu       (w = upstream dL/dlogZ_b);
+ *         gTr[c',c] += w*mu, gD[k-1,c] += w*mu       (w = upstream dL/dlogZ_b),
+ *     and, since psi is linear in them, gPs[t,c] += w*mu, gPe[t+k-1,c] += w*mu for the
+ *     boundary projections (gradients of the scalar boundaries: the rows of token 0 /
+ *     token L-1 summed over sequences); the posterior that a segment boundary falls at
+ *     position t, sum_c exp(alpha[t,c] + beta[t,c] - logZ);
  *   - the chain rule through Eq. 2 and Eq. 1 (the paper leaves this to
  *     autograd): pm[u,c] = sum_{t>u} gS[t,c] is the gradient w.r.t. the centred
  *     emission, i.e. the posterior that token u carries label c, and
@@ -51,7 +59,8 @@ static double lse_pair_guard(double m, double s) {
 }
 
 #define PSI(t, k, c, cp) (S[(size_t)(t) * C + (c)] - S[(size_t)((t) - (k)) * C + (c)] \
-                          + dur[(size_t)((k) - 1) * C + (c)] + trans[(size_t)(cp) * C + (c)])
+                          + dur[(size_t)((k) - 1) * C + (c)] + trans[(size_t)(cp) * C + (c)] \
+                          + bs[(size_t)((t) - (k)) * C + (c)] + be[(size_t)((t) - 1) * C + (c)])
 
 /* Eq. 1 (masked mean over the L valid positions) and Eq. 2 (S[0,c] = 0,
  * S[t,c] = sum_{u<t} (f[u,c] - nu[c])).  S must hold (L+1)*C zeros on entry. */
@@ -73,6 +82,7 @@ static void oracle_prefix_sums(const double *f, int L, int C, int center, double
 /* Algorithm 1 with the whole table kept (alpha[0,:] = 0); returns
  * logZ = LSE_c alpha[L,c]. */
 static double oracle_forward(const double *S, const double *trans, const double *dur,
+                             const double *bs, const double *be,
                              int L, int K, int C, int inner_threads, double *alpha)
 {
     (void)inner_threads;
@@ -103,11 +113,38 @@ static double oracle_forward(const double *S, const double *trans, const double 
     return lse_pair_guard(m, s);
 }
 
-/* One sequence.  All arrays are fp64.  Optional outputs may be NULL. */
+/* Start / end scores per token for one sequence: the boundary projections (or zeros)
+ * plus the scalar sequence boundaries at token 0 / token L-1.  Rows 0..L-1 (at least one
+ * row is allocated so that the arrays are never empty). */
+static void oracle_boundary_scores(const double *ps, const double *pe, const double *pis,
+                                   const double *pie, int L, int C, double **bs_out, double **be_out)
+{
+    size_t n = (size_t)(L > 0 ? L : 1) * C;
+    double *bs = (double *)calloc(n, sizeof(double));
+    double *be = (double *)calloc(n, sizeof(double));
+    for (int t = 0; t < L; ++t)
+        for (int c = 0; c < C; ++c) {
+            if (ps) bs[(size_t)t * C + c] = ps[(size_t)t * C + c];
+            if (pe) be[(size_t)t * C + c] = pe[(size_t)t * C + c];
+        }
+    if (L > 0)
+        for (int c = 0; c < C; ++c) {
+            if (pis) bs[c] += pis[c];
+            if (pie) be[(size_t)(L - 1) * C + c] += pie[c];
+        }
+    *bs_out = bs;
+    *be_out = be;
+}
+
+/* One sequence.  All arrays are fp64.  Optional inputs and outputs may be NULL. */
 static void oracle_sequence(const double *f,      /* [T,C] emissions of this sequence */
                             int L, int T, int K, int C, int center, double w,
                             const double *trans,  /* [C,C] source-major: trans[c'*C+c] */
                             const double *dur,    /* [K,C] row k-1 */
+                            const double *ps,     /* [T,C] start projections or NULL */
+                            const double *pe,     /* [T,C] end projections or NULL */
+                            const double *pis,    /* [C] scalar start boundary or NULL */
+                            const double *pie,    /* [C] scalar end boundary or NULL */
                             int inner_threads,
                             double *logz_out,
                             double *gE,           /* [T,C] */
@@ -117,7 +154,10 @@ static void oracle_sequence(const double *f,      /* [T,C] emissions of this seq
                             double *S_out,        /* [T+1,C] or NULL */
                             double *alpha_out,    /* [T+1,C] or NULL */
                             double *beta_out,     /* [T+1,C] or NULL */
-                            double *gS_out)       /* [T+1,C] or NULL */
+                            double *gS_out,       /* [T+1,C] or NULL */
+                            double *gPs,          /* [T,C] or NULL, weighted by w */
+                            double *gPe,          /* [T,C] or NULL, weighted by w */
+                            double *bdy)          /* [T+1] or NULL: boundary posterior */
 {
     (void)inner_threads;
     size_t n1 = (size_t)(L + 1) * C;
@@ -127,8 +167,11 @@ static void oracle_sequence(const double *f,      /* [T,C] emissions of this seq
     double *beta = (double *)malloc(n1 * sizeof(double));
     double *gS = (double *)calloc(n1, sizeof(double));
 
+    double *bs, *be;
+    oracle_boundary_scores(ps, pe, pis, pie, L, C, &bs, &be);
+
     oracle_prefix_sums(f, L, C, center, nu, S);
-    double logz = oracle_forward(S, trans, dur, L, K, C, inner_threads, alpha);
+    double logz = oracle_forward(S, trans, dur, bs, be, L, K, C, inner_threads, alpha);
     *logz_out = logz;
 
     /* Algorithm 3 recurrence with the whole table kept: beta[L,:] = 0. */
@@ -156,6 +199,8 @@ static void oracle_sequence(const double *f,      /* [T,C] emissions of this seq
      * is the outer loop so that every accumulator element is owned by one c. */
     memset(gTr, 0, sizeof(double) * (size_t)C * C);
     memset(gD, 0, sizeof(double) * (size_t)K * C);
+    if (gPs) memset(gPs, 0, sizeof(double) * (size_t)T * C);
+    if (gPe) memset(gPe, 0, sizeof(double) * (size_t)T * C);
 #pragma omp parallel for num_threads(inner_threads) if (inner_threads > 1) schedule(static)
     for (int c = 0; c < C; ++c) {
         for (int t = 0; t < L; ++t) {
@@ -169,6 +214,8 @@ static void oracle_sequence(const double *f,      /* [T,C] emissions of this seq
                     gD[(size_t)(k - 1) * C + c] += w * mu;
                     gS[(size_t)(t + k) * C + c] += mu;
                     gS[(size_t)t * C + c] -= mu;
+                    if (gPs) gPs[(size_t)t * C + c] += w * mu;
+                    if (gPe) gPe[(size_t)(t + k - 1) * C + c] += w * mu;
                 }
         }
     }
@@ -189,6 +236,16 @@ static void oracle_sequence(const double *f,      /* [T,C] emissions of this seq
         }
     }
 
+    /* Posterior that a segment boundary falls at position t (1 at t = 0 and t = L). */
+    if (bdy) {
+        for (int t = 0; t <= T; ++t) bdy[t] = 0.0;
+        for (int t = 0; t <= L; ++t) {
+            double a = 0.0;
+            for (int c = 0; c < C; ++c) a += exp(alpha[(size_t)t * C + c] + beta[(size_t)t * C + c] - logz);
+            bdy[t] = a;
+        }
+    }
+
     if (S_out) {
         memcpy(S_out, S, n1 * sizeof(double));
         for (size_t i = n1; i < (size_t)(T + 1) * C; ++i) S_out[i] = 0.0;
@@ -205,7 +262,7 @@ static void oracle_sequence(const double *f,      /* [T,C] emissions of this seq
         memcpy(gS_out, gS, n1 * sizeof(double));
         for (size_t i = n1; i < (size_t)(T + 1) * C; ++i) gS_out[i] = 0.0;
     }
-    free(nu); free(S); free(alpha); free(beta); free(gS);
+    free(nu); free(S); free(alpha); free(beta); free(gS); free(bs); free(be);
 }
 
 /*
@@ -222,13 +279,17 @@ static void oracle_sequence(const double *f,      /* [T,C] emissions of this seq
  *   grad_dur [K,C]; optional per-sequence grad_trans_b [B,C,C], grad_dur_b
  *   [B,K,C]; optional tables S, alpha, beta, gS each [B,T+1,C].
  */
-int semicrf_oracle_fwd_bwd(const double *emis, const int32_t *lengths,
-                           const double *trans, const double *dur, const double *grad_logz,
-                           int B, int T, int K, int C, int center, int threads,
-                           double *logz, double *grad_emis, double *pos_marg,
-                           double *grad_trans, double *grad_dur,
-                           double *grad_trans_b, double *grad_dur_b,
-                           double *S_out, double *alpha_out, double *beta_out, double *gS_out)
+int semicrf_oracle_fwd_bwd_boundary(const double *emis, const int32_t *lengths,
+                                    const double *trans, const double *dur, const double *grad_logz,
+                                    const double *proj_start, const double *proj_end,
+                                    const double *pi_start, const double *pi_end,
+                                    int B, int T, int K, int C, int center, int threads,
+                                    double *logz, double *grad_emis, double *pos_marg,
+                                    double *grad_trans, double *grad_dur,
+                                    double *grad_trans_b, double *grad_dur_b,
+                                    double *S_out, double *alpha_out, double *beta_out, double *gS_out,
+                                    double *grad_proj_start, double *grad_proj_end,
+                                    double *grad_pi_start, double *grad_pi_end, double *bdy_post)
 {
     if (B < 1 || T < 1 || K < 1 || C < 1) return -1;
     int nthreads = 1;
@@ -245,6 +306,10 @@ int semicrf_oracle_fwd_bwd(const double *emis, const int32_t *lengths,
     size_t cc = (size_t)C * C, kc = (size_t)K * C, tc = (size_t)T * C, t1c = (size_t)(T + 1) * C;
     double *gTr_b = grad_trans_b ? grad_trans_b : (double *)malloc(sizeof(double) * cc * B);
     double *gD_b = grad_dur_b ? grad_dur_b : (double *)malloc(sizeof(double) * kc * B);
+    /* the scalar-boundary gradients are read off the projection gradients */
+    int own_ps = !grad_proj_start && grad_pi_start, own_pe = !grad_proj_end && grad_pi_end;
+    double *gPs = own_ps ? (double *)malloc(sizeof(double) * tc * B) : grad_proj_start;
+    double *gPe = own_pe ? (double *)malloc(sizeof(double) * tc * B) : grad_proj_end;
 
 #pragma omp parallel for num_threads(outer) schedule(dynamic, 1)
     for (int b = 0; b < B; ++b) {
@@ -252,13 +317,17 @@ int semicrf_oracle_fwd_bwd(const double *emis, const int32_t *lengths,
         if (L < 0) L = 0;
         if (L > T) L = T;
         double w = grad_logz ? grad_logz[b] : 1.0;
-        oracle_sequence(emis + tc * b, L, T, K, C, center, w, trans, dur, inner,
+        oracle_sequence(emis + tc * b, L, T, K, C, center, w, trans, dur,
+                        proj_start ? proj_start + tc * b : NULL, proj_end ? proj_end + tc * b : NULL,
+                        pi_start, pi_end, inner,
                         logz + b, grad_emis + tc * b, pos_marg + tc * b,
                         gTr_b + cc * b, gD_b + kc * b,
                         S_out ? S_out + t1c * b : NULL,
                         alpha_out ? alpha_out + t1c * b : NULL,
                         beta_out ? beta_out + t1c * b : NULL,
-                        gS_out ? gS_out + t1c * b : NULL);
+                        gS_out ? gS_out + t1c * b : NULL,
+                        gPs ? gPs + tc * b : NULL, gPe ? gPe + tc * b : NULL,
+                        bdy_post ? bdy_post + (size_t)(T + 1) * b : NULL);
     }
     /* Fixed-order sum over sequences. */
     for (size_t i = 0; i < cc; ++i) {
@@ -271,18 +340,49 @@ int semicrf_oracle_fwd_bwd(const double *emis, const int32_t *lengths,
         for (int b = 0; b < B; ++b) a += gD_b[kc * b + i];
         grad_dur[i] = a;
     }
+    for (int c = 0; c < C; ++c) {
+        double as = 0.0, ae = 0.0;
+        for (int b = 0; b < B; ++b) {
+            int L = lengths ? lengths[b] : T;
+            if (L > T) L = T;
+            if (L < 1) continue;
+            if (grad_pi_start) as += gPs[tc * b + c];
+            if (grad_pi_end) ae += gPe[tc * b + (size_t)(L - 1) * C + c];
+        }
+        if (grad_pi_start) grad_pi_start[c] = as;
+        if (grad_pi_end) grad_pi_end[c] = ae;
+    }
     if (!grad_trans_b) free(gTr_b);
     if (!grad_dur_b) free(gD_b);
+    if (own_ps) free(gPs);
+    if (own_pe) free(gPe);
     return outer * inner;
+}
+
+/* The three-term form of Eq. 4 (no boundary terms). */
+int semicrf_oracle_fwd_bwd(const double *emis, const int32_t *lengths,
+                           const double *trans, const double *dur, const double *grad_logz,
+                           int B, int T, int K, int C, int center, int threads,
+                           double *logz, double *grad_emis, double *pos_marg,
+                           double *grad_trans, double *grad_dur,
+                           double *grad_trans_b, double *grad_dur_b,
+                           double *S_out, double *alpha_out, double *beta_out, double *gS_out)
+{
+    return semicrf_oracle_fwd_bwd_boundary(emis, lengths, trans, dur, grad_logz, NULL, NULL, NULL, NULL,
+                                           B, T, K, C, center, threads, logz, grad_emis, pos_marg,
+                                           grad_trans, grad_dur, grad_trans_b, grad_dur_b,
+                                           S_out, alpha_out, beta_out, gS_out, NULL, NULL, NULL, NULL, NULL);
 }
 
 /*
  * Forward only: logZ per sequence (same recurrence, same arithmetic).
  * Used for finite-difference checks, where the backward pass is not wanted.
  */
-int semicrf_oracle_logz(const double *emis, const int32_t *lengths,
-                        const double *trans, const double *dur,
-                        int B, int T, int K, int C, int center, int threads, double *logz)
+int semicrf_oracle_logz_boundary(const double *emis, const int32_t *lengths,
+                                 const double *trans, const double *dur,
+                                 const double *proj_start, const double *proj_end,
+                                 const double *pi_start, const double *pi_end,
+                                 int B, int T, int K, int C, int center, int threads, double *logz)
 {
     if (B < 1 || T < 1 || K < 1 || C < 1) return -1;
     int nthreads = 1;
@@ -300,9 +400,20 @@ int semicrf_oracle_logz(const double *emis, const int32_t *lengths,
         double *nu = (double *)calloc((size_t)C, sizeof(double));
         double *S = (double *)calloc(n1, sizeof(double));
         double *alpha = (double *)malloc(n1 * sizeof(double));
+        double *bs, *be;
+        oracle_boundary_scores(proj_start ? proj_start + (size_t)T * C * b : NULL,
+                               proj_end ? proj_end + (size_t)T * C * b : NULL, pi_start, pi_end, L, C, &bs, &be);
         oracle_prefix_sums(f, L, C, center, nu, S);
-        logz[b] = oracle_forward(S, trans, dur, L, K, C, 1, alpha);
-        free(nu); free(S); free(alpha);
+        logz[b] = oracle_forward(S, trans, dur, bs, be, L, K, C, 1, alpha);
+        free(nu); free(S); free(alpha); free(bs); free(be);
     }
     return outer;
+}
+
+int semicrf_oracle_logz(const double *emis, const int32_t *lengths,
+                        const double *trans, const double *dur,
+                        int B, int T, int K, int C, int center, int threads, double *logz)
+{
+    return semicrf_oracle_logz_boundary(emis, lengths, trans, dur, NULL, NULL, NULL, NULL,
+                                        B, T, K, C, center, threads, logz);
 }

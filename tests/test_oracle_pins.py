@@ -398,3 +398,164 @@ def test_forward_only_entry_matches_full_entry():
     a = oracle.logz(emis, lengths, trans, dur)
     b = oracle.fwd_bwd(emis, lengths, trans, dur).logz
     assert np.array_equal(a, b)
+
+
+# --------------------------------------------------------------------------
+# P11  boundary terms of Eq. 4: start/end projections and scalar sequence boundaries
+# --------------------------------------------------------------------------
+def brute_force_boundary(emis, L, trans, dur, ps, pe, pis, pie, center):
+    """Enumeration with the two boundary terms: a segment [s, s+k) with label c also pays
+    ps[s,c] + pe[s+k-1,c]; the scalar boundaries are paid by the segment that starts at
+    token 0 / ends at token L-1.  Returns logZ and the expected counts that are the gradients
+    with respect to ps, pe, pis, pie, and the boundary posterior."""
+    T, C = emis.shape
+    K = dur.shape[0]
+    nu = emis[:L].mean(0) if (center and L > 0) else np.zeros(C)
+    fbar = emis - nu
+    Z = 0.0
+    gPs = np.zeros((T, C))
+    gPe = np.zeros((T, C))
+    gPis = np.zeros(C)
+    gPie = np.zeros(C)
+    pm = np.zeros((T, C))
+    bdy = np.zeros(T + 1)
+    for comp in compositions(L, K):
+        n = len(comp)
+        for c0 in range(C):
+            for labs in itertools.product(range(C), repeat=n):
+                score, prev, s = 0.0, c0, 0
+                for k, c in zip(comp, labs):
+                    score += trans[prev, c] + dur[k - 1, c] + fbar[s:s + k, c].sum() + ps[s, c] + pe[s + k - 1, c]
+                    if s == 0:
+                        score += pis[c]
+                    if s + k == L:
+                        score += pie[c]
+                    prev, s = c, s + k
+                wgt = math.exp(score)
+                Z += wgt
+                s = 0
+                bdy[0] += wgt
+                for k, c in zip(comp, labs):
+                    gPs[s, c] += wgt
+                    gPe[s + k - 1, c] += wgt
+                    pm[s:s + k, c] += wgt
+                    if s == 0:
+                        gPis[c] += wgt
+                    if s + k == L:
+                        gPie[c] += wgt
+                    s += k
+                    bdy[s] += wgt
+    return math.log(Z), gPs / Z, gPe / Z, gPis / Z, gPie / Z, pm / Z, bdy / Z
+
+
+@pytest.mark.parametrize("T,K,C,center", [(5, 3, 2, True), (6, 4, 2, False), (4, 2, 3, True), (5, 1, 3, True)])
+def test_brute_force_with_boundary_terms(T, K, C, center):
+    rng = np.random.default_rng(500 + T * 10 + K)
+    emis, _, trans, dur = rand_case(300 + T * 10 + K, 1, T, K, C)
+    ps, pe = rng.standard_normal((1, T, C)), rng.standard_normal((1, T, C))
+    pis, pie = rng.standard_normal(C), rng.standard_normal(C)
+    r = oracle.fwd_bwd(emis, None, trans, dur, center=center, proj_start=ps, proj_end=pe, pi_start=pis, pi_end=pie)
+    lz, gPs, gPe, gPis, gPie, pm, bdy = brute_force_boundary(emis[0], T, trans, dur, ps[0], pe[0], pis, pie, center)
+    assert abs(r.logz[0] - lz) < 1e-12 * max(1, abs(lz))
+    assert np.allclose(r.grad_proj_start[0], gPs, atol=1e-10)
+    assert np.allclose(r.grad_proj_end[0], gPe, atol=1e-10)
+    assert np.allclose(r.grad_pi_start, gPis, atol=1e-10)
+    assert np.allclose(r.grad_pi_end, gPie, atol=1e-10)
+    assert np.allclose(r.pos_marg[0], pm, atol=1e-10)
+    assert np.allclose(r.bdy_post[0], bdy, atol=1e-10)
+    # with all boundary terms zero the enumeration of P2 is recovered
+    z = np.zeros((1, T, C))
+    r0 = oracle.fwd_bwd(emis, None, trans, dur, center=center, proj_start=z, proj_end=z)
+    r1 = oracle.fwd_bwd(emis, None, trans, dur, center=center)
+    assert np.array_equal(r0.logz, r1.logz) and np.array_equal(r0.grad_dur, r1.grad_dur)
+
+
+def test_boundary_terms_ragged_weighted_and_scalar_composition():
+    """Ragged batch with upstream weights.  Scalar boundaries are the projections' rows of token 0
+    and token L_b - 1 (composition rule of the boundary appendix): folding them into the
+    projections by hand must give the same logZ, and their gradients are those rows summed."""
+    rng = np.random.default_rng(77)
+    B, T, K, C = 3, 9, 4, 3
+    emis, _, trans, dur = rand_case(78, B, T, K, C)
+    lengths = np.array([9, 6, 1], dtype=np.int32)
+    w = np.array([1.0, -0.7, 2.5])
+    ps, pe = rng.standard_normal((B, T, C)), rng.standard_normal((B, T, C))
+    pis, pie = rng.standard_normal(C), rng.standard_normal(C)
+    r = oracle.fwd_bwd(emis, lengths, trans, dur, grad_logz=w, proj_start=ps, proj_end=pe, pi_start=pis, pi_end=pie)
+    ps2, pe2 = ps.copy(), pe.copy()
+    for b in range(B):
+        ps2[b, 0] += pis
+        pe2[b, lengths[b] - 1] += pie
+    r2 = oracle.fwd_bwd(emis, lengths, trans, dur, grad_logz=w, proj_start=ps2, proj_end=pe2)
+    assert np.allclose(r.logz, r2.logz, rtol=0, atol=1e-12)
+    assert np.allclose(r.grad_proj_start, r2.grad_proj_start, atol=1e-12)
+    assert np.allclose(r.grad_pi_start, r.grad_proj_start[:, 0].sum(0), atol=1e-12)
+    assert np.allclose(r.grad_pi_end, sum(r.grad_proj_end[b, lengths[b] - 1] for b in range(B)), atol=1e-12)
+    # per sequence against the enumeration (weights scale the gradients)
+    for b in range(B):
+        L = int(lengths[b])
+        lz, gPs, gPe, gPis, gPie, pm, bdy = brute_force_boundary(emis[b], L, trans, dur, ps[b], pe[b], pis, pie, True)
+        assert abs(r.logz[b] - lz) < 1e-12 * max(1, abs(lz))
+        assert np.allclose(r.grad_proj_start[b], w[b] * gPs, atol=1e-10)
+        assert np.allclose(r.grad_proj_end[b], w[b] * gPe, atol=1e-10)
+        assert np.allclose(r.bdy_post[b], bdy, atol=1e-10)
+        assert np.all(r.grad_proj_start[b, L:] == 0) and np.all(r.grad_proj_end[b, L:] == 0)
+    # every segment has one start and one end: both gradients sum to the expected number of segments
+    for b in range(B):
+        nseg = r.grad_dur_b[b].sum()
+        assert abs(r.grad_proj_start[b].sum() - nseg) < 1e-10 and abs(r.grad_proj_end[b].sum() - nseg) < 1e-10
+
+
+def test_k1_with_scalar_boundaries_is_the_chain_crf_with_start_and_end_scores():
+    """K = 1 with scalar boundaries is the textbook linear-chain CRF with start and end
+    scores: a_1 = (1 E) * exp(f_0 + dur + pi_start), ..., Z = sum_c a_T(c) exp(pi_end[c])
+    (the transition from the free initial label is kept, as in the K=1 pin above)."""
+    T, C = 200, 4
+    rng = np.random.default_rng(13)
+    emis, _, trans, dur = rand_case(14, 1, T, 1, C)
+    pis, pie = rng.standard_normal(C), rng.standard_normal(C)
+    lz = oracle.logz(emis, None, trans, dur, center=True, pi_start=pis, pi_end=pie)[0]
+    fbar = emis[0] - emis[0].mean(0)
+    a = np.ones(C)
+    log_scale = 0.0
+    E = np.exp(trans)
+    for t in range(T):
+        a = (a @ E) * np.exp(fbar[t] + dur[0] + (pis if t == 0 else 0.0) + (pie if t == T - 1 else 0.0))
+        s = a.sum()
+        a /= s
+        log_scale += math.log(s)
+    assert abs(lz - log_scale) < 1e-9
+
+
+def test_finite_differences_boundary_terms():
+    rng = np.random.default_rng(15)
+    B, T, K, C = 2, 7, 3, 3
+    emis, _, trans, dur = rand_case(16, B, T, K, C)
+    lengths = np.array([7, 5], dtype=np.int32)
+    w = np.array([0.8, -1.3])
+    ps, pe = 0.5 * rng.standard_normal((B, T, C)), 0.5 * rng.standard_normal((B, T, C))
+    pis, pie = rng.standard_normal(C), rng.standard_normal(C)
+    r = oracle.fwd_bwd(emis, lengths, trans, dur, grad_logz=w, proj_start=ps, proj_end=pe, pi_start=pis, pi_end=pie)
+    loss = lambda **kw: float(w @ oracle.logz(emis, lengths, trans, dur, **{**dict(proj_start=ps, proj_end=pe,
+                                                                            pi_start=pis, pi_end=pie), **kw}))
+    eps = 1e-6
+    for name, arr, grad in (("proj_start", ps, r.grad_proj_start), ("proj_end", pe, r.grad_proj_end),
+                            ("pi_start", pis, r.grad_pi_start), ("pi_end", pie, r.grad_pi_end)):
+        for idx in np.ndindex(arr.shape):
+            hi, lo = arr.copy(), arr.copy()
+            hi[idx] += eps
+            lo[idx] -= eps
+            fd = (loss(**{name: hi}) - loss(**{name: lo})) / (2 * eps)
+            assert abs(fd - grad[idx]) < 2e-7, (name, idx, fd, grad[idx])
+
+
+def test_boundary_posterior_invariants():
+    emis, lengths, trans, dur = rand_case(17, 3, 40, 6, 4, ragged=True)
+    r = oracle.fwd_bwd(emis, lengths, trans, dur, boundary=True)
+    for b in range(3):
+        L = int(lengths[b])
+        p = r.bdy_post[b]
+        assert abs(p[0] - 1) < 1e-10 and abs(p[L] - 1) < 1e-10 and np.all(p[L + 1:] == 0)
+        assert np.all(p[:L + 1] > 0) and np.all(p[:L + 1] <= 1 + 1e-12)
+        # expected number of boundaries = expected number of segments + 1
+        assert abs(p.sum() - (r.grad_dur_b[b].sum() + 1)) < 1e-9
