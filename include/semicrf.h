@@ -135,6 +135,41 @@ int semicrf_fwd_bwd(const float *emis, const int32_t *lengths, const float *tran
                     float *pos_marg, void *stream);
 
 /*
+ * The full edge potential of Eq. 4: the three terms above plus the optional boundary terms
+ * of the "Boundary Projections" section and the scalar sequence boundaries of the appendix on
+ * boundary handling.  A segment [s, s+k) with label c additionally scores
+ *     proj_start[b, s, c] + proj_end[b, s+k-1, c]
+ * (first and last TOKEN of the segment), plus pi_start[c] if s = 0 and pi_end[c] if
+ * s+k = L_b (the scalars are added to the projections at token 0 / token L_b-1).
+ *   proj_start, proj_end [B,T,C] float or NULL (= zeros); rows u >= L_b are never read
+ *   pi_start, pi_end     [C]     float or NULL (= zeros)
+ * With all four NULL these calls are semicrf_logz_fwd / semicrf_fwd_bwd.  Additional
+ * outputs of the gradient call, each optional (NULL = not wanted), fully overwritten:
+ *   grad_proj_start [B,T,C] float  w_b * P(a segment with label c starts at token u); rows u >= L_b are 0
+ *   grad_proj_end   [B,T,C] float  w_b * P(a segment with label c ends with token u);  rows u >= L_b are 0
+ *   grad_pi_start   [C]     float  sum_b w_b * P(first segment of b has label c)
+ *   grad_pi_end     [C]     float  sum_b w_b * P(last segment of b has label c)
+ *   bdy_post        [B,T+1] float  P(a segment boundary falls at position t): 1 at t = 0 and
+ *                                  t = L_b, 0 for t > L_b (the boundary posterior of the paper's
+ *                                  analysis; independent of grad_logz)
+ * The score range bound of the header comment includes max|proj_start| + max|proj_end| + the
+ * scalars.  Everything else as for semicrf_logz_fwd / semicrf_fwd_bwd.
+ */
+int semicrf_logz_fwd_boundary(const float *emis, const int32_t *lengths, const float *trans,
+                              const float *dur, const float *proj_start, const float *proj_end,
+                              const float *pi_start, const float *pi_end, int B, int T, int K, int C,
+                              int ckpt_interval, unsigned flags, void *workspace, size_t workspace_bytes,
+                              float *logz, void *stream);
+
+int semicrf_fwd_bwd_boundary(const float *emis, const int32_t *lengths, const float *trans,
+                             const float *dur, const float *grad_logz, const float *proj_start,
+                             const float *proj_end, const float *pi_start, const float *pi_end, int B, int T,
+                             int K, int C, int ckpt_interval, unsigned flags, void *workspace,
+                             size_t workspace_bytes, float *logz, float *grad_emis, float *grad_trans,
+                             float *grad_dur, float *pos_marg, float *grad_proj_start, float *grad_proj_end,
+                             float *grad_pi_start, float *grad_pi_end, float *bdy_post, void *stream);
+
+/*
  * Measurement aid: semicrf_fwd_bwd with five caller-owned HIP events recorded on
  * `stream`: stage_events[0] before the first kernel and stage_events[1..4] after
  * each of the four stages

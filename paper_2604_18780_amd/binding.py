@@ -17,7 +17,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsemicrf.so")
 EXPORTS = ("semicrf_version", "semicrf_strerror", "semicrf_workspace_bytes",
            "semicrf_cum_scores", "semicrf_logz_fwd", "semicrf_fwd_bwd", "semicrf_fwd_bwd_profiled",
-           "semicrf_scan_report", "semicrf_ckpt_interval")
+           "semicrf_scan_report", "semicrf_ckpt_interval", "semicrf_logz_fwd_boundary",
+           "semicrf_fwd_bwd_boundary")
 SEMICRF_CENTER = 1
 SEMICRF_SEQUENTIAL_SCAN = 2
 _lib = None
@@ -57,6 +58,10 @@ def load():
     lib.semicrf_fwd_bwd_profiled.argtypes = lib.semicrf_fwd_bwd.argtypes + [ctypes.POINTER(vp)]
     lib.semicrf_ckpt_interval.restype = ci
     lib.semicrf_ckpt_interval.argtypes = [ci, ci, ci, ci, ci, ctypes.POINTER(ci)]
+    lib.semicrf_logz_fwd_boundary.restype = ci
+    lib.semicrf_logz_fwd_boundary.argtypes = [vp] * 8 + [ci, ci, ci, ci, ci, cu, vp, sz, vp, vp]
+    lib.semicrf_fwd_bwd_boundary.restype = ci
+    lib.semicrf_fwd_bwd_boundary.argtypes = [vp] * 9 + [ci, ci, ci, ci, ci, cu, vp, sz] + [vp] * 11
     lib.semicrf_scan_report.restype = ci
     lib.semicrf_scan_report.argtypes = [vp, sz, ci, ci, ci, ci, ci, ci, vp, vp, vp]
     _lib = lib
@@ -159,6 +164,48 @@ def semicrf_fwd_bwd(emis, lengths, trans, dur, grad_logz=None, ckpt_interval=0,
                                   _ptr(g_t, torch.float32), _ptr(g_d, torch.float32),
                                   _ptr(pm, torch.float32), _stream()))
     return logz, g_e, g_t, g_d, pm
+
+
+def semicrf_logz_fwd_boundary(emis, lengths, trans, dur, proj_start=None, proj_end=None, pi_start=None,
+                              pi_end=None, ckpt_interval=0, flags=SEMICRF_CENTER, workspace=None):
+    B, T, C = emis.shape
+    K = dur.shape[0]
+    if workspace is None:
+        workspace = alloc_workspace(B, T, K, C, ckpt_interval, False, emis.device)
+    logz = torch.empty(B, dtype=torch.float32, device=emis.device)
+    f32 = torch.float32
+    _check(load().semicrf_logz_fwd_boundary(_ptr(emis, f32), _ptr(lengths, torch.int32), _ptr(trans, f32),
+                                            _ptr(dur, f32), _ptr(proj_start, f32), _ptr(proj_end, f32),
+                                            _ptr(pi_start, f32), _ptr(pi_end, f32), B, T, K, C, ckpt_interval,
+                                            flags, workspace.data_ptr(), workspace.numel(), _ptr(logz, f32),
+                                            _stream()))
+    return logz
+
+
+def semicrf_fwd_bwd_boundary(emis, lengths, trans, dur, grad_logz=None, proj_start=None, proj_end=None,
+                             pi_start=None, pi_end=None, ckpt_interval=0, flags=SEMICRF_CENTER, workspace=None):
+    """Returns a dict with logz, grad_emis, grad_trans, grad_dur, pos_marg, grad_proj_start,
+    grad_proj_end, grad_pi_start, grad_pi_end, bdy_post."""
+    B, T, C = emis.shape
+    K = dur.shape[0]
+    dev = emis.device
+    if workspace is None:
+        workspace = alloc_workspace(B, T, K, C, ckpt_interval, True, dev)
+    f32 = torch.float32
+    new = lambda *shape: torch.empty(shape, dtype=f32, device=dev)
+    o = dict(logz=new(B), grad_emis=new(B, T, C), grad_trans=new(C, C), grad_dur=new(K, C), pos_marg=new(B, T, C),
+             grad_proj_start=new(B, T, C), grad_proj_end=new(B, T, C), grad_pi_start=new(C), grad_pi_end=new(C),
+             bdy_post=new(B, T + 1))
+    _check(load().semicrf_fwd_bwd_boundary(_ptr(emis, f32), _ptr(lengths, torch.int32), _ptr(trans, f32),
+                                           _ptr(dur, f32), _ptr(grad_logz, f32), _ptr(proj_start, f32),
+                                           _ptr(proj_end, f32), _ptr(pi_start, f32), _ptr(pi_end, f32),
+                                           B, T, K, C, ckpt_interval, flags, workspace.data_ptr(),
+                                           workspace.numel(), *[_ptr(o[k], f32) for k in
+                                                                ("logz", "grad_emis", "grad_trans", "grad_dur",
+                                                                 "pos_marg", "grad_proj_start", "grad_proj_end",
+                                                                 "grad_pi_start", "grad_pi_end", "bdy_post")],
+                                           _stream()))
+    return o
 
 
 def semicrf_scan_report(workspace, B, T, K, C, ckpt_interval=0, want_grad=True):

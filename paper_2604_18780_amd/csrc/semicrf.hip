@@ -70,6 +70,11 @@ struct Params {
     const float *trans;
     const float *dur;
     const float *grad_logz;
+    // optional boundary terms of Eq. 4 (any of them may be null)
+    const float *proj_start;  // [B][T][C]  start score of a segment whose first token is t
+    const float *proj_end;    // [B][T][C]  end score of a segment whose last token is t
+    const float *pi_start;    // [C]        scalar boundary of the sequence's first segment
+    const float *pi_end;      // [C]        scalar boundary of the sequence's last segment
     int B, T, K, C;
     int Delta, N;       // checkpoint interval and intervals per padded sequence
     int NCH;            // prefix-sum chunks per sequence (covers t = 0..T)
@@ -109,6 +114,8 @@ struct Params {
     double *sumR;       // [B][N][C]
     double *carry;      // [B][N][C]
     double *mean;       // [B][C]
+    double *out0;       // [B][C]  mass of the segments that start at position 0, per label
+    double *inL;        // [B][C]  mass of the segments that end at position L, per label
     // outputs
     double *cum;        // optional [B][T+1][C]
     float *logz;
@@ -116,6 +123,11 @@ struct Params {
     float *grad_trans;
     float *grad_dur;
     float *pos_marg;
+    float *g_proj_start;  // optional [B][T][C]
+    float *g_proj_end;    // optional [B][T][C]
+    float *g_pi_start;    // optional [C]
+    float *g_pi_end;      // optional [C]
+    float *bdy_post;      // optional [B][T+1]
 };
 
 __device__ __forceinline__ int seq_len(const Params &p, int b)
@@ -188,8 +200,19 @@ __device__ __forceinline__ void colsum_body(const Params &p, const int b, const 
             mx = fmax(mx, fabs(v));
         }
     }
+    // the boundary projections move a message like an emission does: their maxima are added
+    double mps = 0.0, mpe = 0.0;
+    if (r < R && (p.proj_start || p.proj_end)) {
+        const size_t o = ((size_t)b * p.T) * C;
+        for (int u = u0 + r; u < u1; u += R) {
+            if (p.proj_start) mps = fmax(mps, fabs((double)p.proj_start[o + (size_t)u * C + c]));
+            if (p.proj_end) mpe = fmax(mpe, fabs((double)p.proj_end[o + (size_t)u * C + c]));
+        }
+    }
+    __shared__ double redp[NT];
     red[tid] = acc;
     redm[tid] = mx;
+    redp[tid] = mps + mpe;
     __syncthreads();
     if (tid < C) {
         double s = 0.0;
@@ -197,9 +220,11 @@ __device__ __forceinline__ void colsum_body(const Params &p, const int b, const 
         p.chsum[((size_t)b * p.NCH + ch) * C + tid] = s;
     }
     if (tid == 0) {
-        double m = 0.0;
+        double m = 0.0, mp = 0.0;
         for (int i = 0; i < R * C; ++i) m = fmax(m, redm[i]);
-        p.chmax[(size_t)b * p.NCH + ch] = m;
+        if (p.proj_start || p.proj_end)
+            for (int i = 0; i < R * C; ++i) mp = fmax(mp, redp[i]);
+        p.chmax[(size_t)b * p.NCH + ch] = m + 2.0 * mp;  // |start| + |end| bounded by twice the larger sum
     }
 }
 
@@ -269,9 +294,13 @@ __global__ __launch_bounds__(NT) void k_prep_seq(Params p)
     if (tid == 0) {
         fm = 0.0;
         for (int i = 0; i < NT; ++i) fm = fmax(fm, red[i]);
-        double nm = 0.0;
-        for (int i = 0; i < C; ++i) nm = fmax(nm, fabs(nu_s[i]));
-        fm += nm;
+        double nm = 0.0, npi = 0.0;
+        for (int i = 0; i < C; ++i) {
+            nm = fmax(nm, fabs(nu_s[i]));
+            if (p.pi_start) npi = fmax(npi, fabs((double)p.pi_start[i]));
+            if (p.pi_end) npi = fmax(npi, fabs((double)p.pi_end[i]));
+        }
+        fm += nm + 2.0 * npi;
         double dmax = p.tabmax[0], tmax = p.tabmax[1];
         double grow = fm + fmax(dmax, 0.0) + fmax(tmax, 0.0) + log((double)p.K * (double)C);
         double shrink = fm + fmax(-dmax, 0.0) + fmax(-tmax, 0.0);
@@ -295,6 +324,7 @@ __global__ __launch_bounds__(NT) void k_prep_seq(Params p)
 constexpr int PREP_SEG = 32;
 static_assert(PREP_CH == 8 * PREP_SEG && JMAX <= PREP_SEG && NT == 256, "k_prefix geometry");
 
+template <bool BTERMS>  // any boundary term of Eq. 4 present
 __global__ __launch_bounds__(NT) void k_prefix(Params p)
 {
     __shared__ double segsum[8][PREP_SEG + 1];
@@ -328,8 +358,26 @@ __global__ __launch_bounds__(NT) void k_prefix(Params p)
                     p.nbase[(row0 + (size_t)(t / J)) * C + c] = (int)n;
                     base = n * LN2;
                 }
-                const double es = exp(S - base);
-                p.EI[(row0 + t) * C + c] = make_double2(es, 1.0 / es);
+                const double x = S - base;
+                double2 pr;
+                if (!BTERMS) {
+                    const double es = exp(x);
+                    pr = make_double2(es, 1.0 / es);
+                } else {
+                    // (ES * exp(end score of token t-1), exp(start score of token t) / ES): every message
+                    // that arrives at position t is multiplied by the first, every one that leaves by the second
+                    double xs = 0.0, xe = 0.0;
+                    if (t < L) {
+                        if (p.proj_start) xs = (double)p.proj_start[((size_t)b * p.T + t) * C + c];
+                        if (t == 0 && p.pi_start) xs += (double)p.pi_start[c];
+                    }
+                    if (t >= 1) {
+                        if (p.proj_end) xe = (double)p.proj_end[((size_t)b * p.T + t - 1) * C + c];
+                        if (t == L && p.pi_end) xe += (double)p.pi_end[c];
+                    }
+                    pr = make_double2(exp(x + xe), exp(xs - x));
+                }
+                p.EI[(row0 + t) * C + c] = pr;
                 if (p.cum) p.cum[(row0 + t) * C + c] = S;
                 if (t < L) S += (double)f[(size_t)t * C] - nu;
             } else if (p.cum) {
@@ -516,6 +564,7 @@ __global__ __launch_bounds__(NT) void k_scan(Params p, int both)
             double lz = Y * LN2 + log(s);
             p.hdr[b].logZ = lz;
             p.logz[b] = (float)lz;
+            for (int c = 0; c < C; ++c) p.inL[(size_t)b * C + c] = l.yv[c] / s;  // a_L(c) / Z
         }
     } else {
         // ---- t = L: b_L = 1, v_L = E_L; the scale reference starts at sum = 1
@@ -987,6 +1036,7 @@ __device__ __forceinline__ void scan_fast_body(const Params &p, double *lds, con
             } else {
                 p.hdr[b].logZ = lz;
                 p.logz[b] = (float)lz;
+                for (int i = 0; i < C; ++i) p.inL[(size_t)b * C + i] = yv[i] / s;  // a_L(c) / Z
             }
         }
     } else {
@@ -1164,6 +1214,21 @@ __global__ __launch_bounds__(NT) void k_interval(Params p)
                 p.grad_emis[((size_t)b * p.T + t) * C + tid] = (float)R;
                 sR += R;
                 R += outv - inv;
+                // gradients of the boundary terms: a segment starts at t (first token t), ends at t (last token t-1)
+                const double wb = p.grad_logz ? (double)p.grad_logz[b] : 1.0;
+                if (p.g_proj_start) p.g_proj_start[((size_t)b * p.T + t) * C + tid] = (float)(wb * outv);
+                if (p.g_proj_end && t >= 1) p.g_proj_end[((size_t)b * p.T + t - 1) * C + tid] = (float)(wb * inv);
+                if (t == 0) p.out0[(size_t)b * C + tid] = outv;
+                if (p.bdy_post) l.red[tid] = inv;
+            }
+            if (p.bdy_post) {  // posterior of a boundary at t: total mass of the segments that end there
+                __syncthreads();
+                if (tid == 0 && t >= 1) {
+                    double sb = 0.0;
+                    for (int i = 0; i < C; ++i) sb += l.red[i];
+                    p.bdy_post[(size_t)b * (p.T + 1) + t] = (float)sb;
+                }
+                __syncthreads();
             }
 #pragma unroll
             for (int j = 0; j < TRP; ++j) {
@@ -1561,6 +1626,8 @@ __global__ __launch_bounds__(64 * interval_waves(CT, NKW)) void k_interval_wave(
             for (int o = 0; o < TRN; ++o) accT[i][o] = double4_t{0.0, 0.0, 0.0, 0.0};
         int yrow = 0;  // row of yv that holds the newest message vector
         double R = 0.0, sR = 0.0;
+        const bool bterms = p.g_proj_start || p.g_proj_end || p.bdy_post;
+        const double wb = p.grad_logz ? (double)p.grad_logz[b] : 1.0;
         double kappa = exp((Y0 + alocY[t1 - 1 - t0] + Yb) * LN2 - logZ);
         {
             const int rdoff = g * NK * RS + c;
@@ -1677,6 +1744,21 @@ __global__ __launch_bounds__(64 * interval_waves(CT, NKW)) void k_interval_wave(
                         const double inv = tt >= 1 ? ak[i] * z : 0.0;
                         sR += R;
                         R += outv - inv;
+                        // gradients of the boundary terms: a segment starts at tt (first token tt) / ends at tt (last token tt-1)
+                        if (__builtin_expect(bterms, 0)) {
+                            if (writer) {
+                                if (p.g_proj_start) p.g_proj_start[((size_t)b * p.T + tt) * C + c] = (float)(wb * outv);
+                                if (p.g_proj_end && tt >= 1)
+                                    p.g_proj_end[((size_t)b * p.T + tt - 1) * C + c] = (float)(wb * inv);
+                            }
+                            if (p.bdy_post) {  // posterior of a boundary at tt: total mass of the segments that end there
+                                double sb = writer ? inv : 0.0;
+#pragma unroll
+                                for (int off = 1; off < 64; off <<= 1) sb += __shfl_xor(sb, off);
+                                if (lane == 0 && tt >= 1) p.bdy_post[(size_t)b * (p.T + 1) + tt] = (float)sb;
+                            }
+                        }
+                        if (tt == 0 && writer) p.out0[(size_t)b * C + c] = outv;
                     } else {
                         qn[i] = 0.0;
                     }
@@ -2076,6 +2158,16 @@ __global__ __launch_bounds__(64) void k_spec_fix(Params p, int ndir, int tier)
         acc += p.spec_lr[so + jof(i)];
         ckY[jof(i)] += acc;
     }
+    if (dir == 0 && nint > 0) {
+        // a_L(c) / Z: mass of the segments that end at L with label c (the sequential scan
+        // overwrites it if this scan is rejected)
+        const double *e = p.ckA2 + ((size_t)b * (N + 1) + nint) * ((size_t)KC + C);
+        const double v = lane < C ? e[KC + lane] : 0.0;
+        double sum = v;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) sum += __shfl_xor(sum, off);
+        if (lane < C) p.inL[(size_t)b * C + lane] = v / sum;
+    }
     if (lane != 0) return;
     bool ok = worst <= SPEC_TOL;
     p.spec_err[so] = worst;  // entry 0 is no boundary: it carries the report value
@@ -2159,6 +2251,30 @@ __device__ __forceinline__ void fin_seq_body(const Params &p, const int b)
         for (int gg = 0; gg < G; ++gg) t += gtot[gg * C + tid];
         p.mean[(size_t)b * C + tid] = (p.center && L > 0) ? t / (double)L : 0.0;
     }
+    // boundary posterior: certain at both ends of the sequence, nothing beyond it (the interval
+    // kernels wrote positions 1 .. L-1)
+    if (p.bdy_post) {
+        float *bd = p.bdy_post + (size_t)b * (p.T + 1);
+        for (int t = tid; t <= p.T; t += NT)
+            if (t == 0 || t >= L) bd[t] = (t == 0 || t == L) ? 1.f : 0.f;
+    }
+}
+
+// Gradients of the scalar sequence boundaries: sums over sequences, in sequence order, of the
+// mass of the segments that start at position 0 / end at position L.  One workgroup.
+__device__ __forceinline__ void fin_pi_body(const Params &p)
+{
+    const int c = threadIdx.x;
+    if (c >= p.C) return;
+    double gs = 0.0, ge = 0.0;
+    for (int b = 0; b < p.B; ++b) {
+        if (p.hdr[b].L < 1) continue;
+        const double w = p.grad_logz ? (double)p.grad_logz[b] : 1.0;
+        gs = fma(w, p.out0[(size_t)b * p.C + c], gs);
+        ge = fma(w, p.inL[(size_t)b * p.C + c], ge);
+    }
+    if (p.g_pi_start) p.g_pi_start[c] = (float)gs;
+    if (p.g_pi_end) p.g_pi_end[c] = (float)ge;
 }
 
 // grad_emis / pos_marg, elementwise over (u,c) of one sequence.  grid (blocks, B).
@@ -2181,6 +2297,11 @@ __global__ __launch_bounds__(NT) void k_fin_emis(Params p)
         }
         p.grad_emis[base + idx] = ge;
         if (p.pos_marg) p.pos_marg[base + idx] = pmv;
+        // boundary projections: rows beyond the sequence are zero; the last token's end score
+        // belongs to the segments that end at position L
+        if (p.g_proj_start && u >= L) p.g_proj_start[base + idx] = 0.f;
+        if (p.g_proj_end && u >= L - 1)
+            p.g_proj_end[base + idx] = u == L - 1 ? (float)(w * p.inL[(size_t)b * C + c]) : 0.f;
     };
     if (n < ((size_t)1 << 31)) {  // 32-bit index arithmetic
         const unsigned n32 = (unsigned)n, step = gridDim.x * NT;
@@ -2239,8 +2360,10 @@ __device__ __forceinline__ void fin_params_body(const Params &p, const int blk)
 // per 32 parameter gradients.
 __global__ __launch_bounds__(NT) void k_fin_seq(Params p)
 {
+    const int nparam = (p.C * p.C + p.K * p.C + 31) / 32;
     if ((int)blockIdx.x < p.B) fin_seq_body(p, blockIdx.x);
-    else fin_params_body(p, blockIdx.x - p.B);
+    else if ((int)blockIdx.x < p.B + nparam) fin_params_body(p, blockIdx.x - p.B);
+    else fin_pi_body(p);
 }
 
 // ---------------------------------------------------------------------------
@@ -2369,6 +2492,8 @@ int make_plan(int B, int T, int K, int C, int ckpt_interval, int want_grad, Plan
     sz[i++] = g * b * (n + 1) * (k * c + c) * 8;  // 23 ckB2
     sz[i++] = b * (n + 1) * 8;                    // 24 ckYA2
     sz[i++] = g * b * (n + 1) * 8;                // 25 ckYB2
+    sz[i++] = b * c * 8;                          // 26 out0
+    sz[i++] = b * c * 8;                          // 27 inL
     size_t off = 0;
     for (int j = 0; j < i; ++j) {
         pl->off[j] = off;
@@ -2406,6 +2531,8 @@ void bind_workspace(Params &p, const Plan &pl, void *ws)
     p.ckB2 = (double *)(w + pl.off[23]);
     p.ckYA2 = (double *)(w + pl.off[24]);
     p.ckYB2 = (double *)(w + pl.off[25]);
+    p.out0 = (double *)(w + pl.off[26]);
+    p.inL = (double *)(w + pl.off[27]);
     p.spec_lr = (double *)(w + pl.off[8]);
     p.spec_err = p.spec_lr + (size_t)p.B * 2 * (pl.N + 1);
     p.spec_ok = (int *)(p.spec_err + (size_t)p.B * 2 * (pl.N + 1));
@@ -2421,7 +2548,10 @@ int launch_prep(const Params &p, hipStream_t st)
 {
     hipLaunchKernelGGL(k_colsum, dim3(1 + p.NCH * p.B), dim3(NT), 0, st, p);
     hipLaunchKernelGGL(k_prep_seq, dim3(p.B), dim3(NT), 0, st, p);
-    hipLaunchKernelGGL(k_prefix, dim3(p.NCH, p.B), dim3(NT), 0, st, p);
+    if (p.proj_start || p.proj_end || p.pi_start || p.pi_end)
+        hipLaunchKernelGGL(k_prefix<true>, dim3(p.NCH, p.B), dim3(NT), 0, st, p);
+    else
+        hipLaunchKernelGGL(k_prefix<false>, dim3(p.NCH, p.B), dim3(NT), 0, st, p);
     return check_launch();
 }
 
@@ -2627,7 +2757,8 @@ int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hi
     rc = launch_interval(p, pl, st);
     if (rc != SEMICRF_OK) return rc;
     T.mark();
-    hipLaunchKernelGGL(k_fin_seq, dim3(p.B + (p.C * p.C + p.K * p.C + 31) / 32), dim3(NT), 0, st, p);
+    hipLaunchKernelGGL(k_fin_seq, dim3(p.B + (p.C * p.C + p.K * p.C + 31) / 32 + ((p.g_pi_start || p.g_pi_end) ? 1 : 0)),
+                       dim3(NT), 0, st, p);
     {
         size_t n = (size_t)p.T * p.C;
         size_t blocks = (n + NT - 1) / NT;
@@ -2747,6 +2878,46 @@ int semicrf_fwd_bwd_profiled(const float *emis, const int32_t *lengths, const fl
         tm.ev[i] = (hipEvent_t)stage_events[i];
     }
     return run(p, ckpt_interval, workspace, workspace_bytes, tm.st, 2, &tm);
+}
+
+int semicrf_logz_fwd_boundary(const float *emis, const int32_t *lengths, const float *trans,
+                              const float *dur, const float *proj_start, const float *proj_end,
+                              const float *pi_start, const float *pi_end, int B, int T, int K, int C,
+                              int ckpt_interval, unsigned flags, void *workspace, size_t workspace_bytes,
+                              float *logz, void *stream)
+{
+    if (!emis || !trans || !dur || !logz) return SEMICRF_EINVAL;
+    Params p = {};
+    p.emis = emis; p.lengths = lengths; p.trans = trans; p.dur = dur;
+    p.proj_start = proj_start; p.proj_end = proj_end; p.pi_start = pi_start; p.pi_end = pi_end;
+    p.B = B; p.T = T; p.K = K; p.C = C;
+    p.center = (flags & SEMICRF_CENTER) ? 1 : 0;
+    p.spec = (flags & SEMICRF_SEQUENTIAL_SCAN) ? 0 : 1;
+    p.logz = logz;
+    return run(p, ckpt_interval, workspace, workspace_bytes, (hipStream_t)stream, 1);
+}
+
+int semicrf_fwd_bwd_boundary(const float *emis, const int32_t *lengths, const float *trans,
+                             const float *dur, const float *grad_logz, const float *proj_start,
+                             const float *proj_end, const float *pi_start, const float *pi_end, int B, int T,
+                             int K, int C, int ckpt_interval, unsigned flags, void *workspace,
+                             size_t workspace_bytes, float *logz, float *grad_emis, float *grad_trans,
+                             float *grad_dur, float *pos_marg, float *grad_proj_start, float *grad_proj_end,
+                             float *grad_pi_start, float *grad_pi_end, float *bdy_post, void *stream)
+{
+    if (!emis || !trans || !dur || !logz || !grad_emis || !grad_trans || !grad_dur)
+        return SEMICRF_EINVAL;
+    Params p = {};
+    p.emis = emis; p.lengths = lengths; p.trans = trans; p.dur = dur; p.grad_logz = grad_logz;
+    p.proj_start = proj_start; p.proj_end = proj_end; p.pi_start = pi_start; p.pi_end = pi_end;
+    p.B = B; p.T = T; p.K = K; p.C = C;
+    p.center = (flags & SEMICRF_CENTER) ? 1 : 0;
+    p.spec = (flags & SEMICRF_SEQUENTIAL_SCAN) ? 0 : 1;
+    p.logz = logz; p.grad_emis = grad_emis; p.grad_trans = grad_trans; p.grad_dur = grad_dur;
+    p.pos_marg = pos_marg;
+    p.g_proj_start = grad_proj_start; p.g_proj_end = grad_proj_end;
+    p.g_pi_start = grad_pi_start; p.g_pi_end = grad_pi_end; p.bdy_post = bdy_post;
+    return run(p, ckpt_interval, workspace, workspace_bytes, (hipStream_t)stream, 2);
 }
 
 int semicrf_scan_report(const void *workspace, size_t workspace_bytes, int B, int T, int K, int C,

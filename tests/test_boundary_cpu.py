@@ -133,6 +133,13 @@ def test_calls_reject_null_pointers_and_bad_workspace_before_any_launch():
     # misaligned workspace pointer
     rc = lib.semicrf_logz_fwd(fake, None, fake, fake, 1, 8, 2, 3, 0, 1, ctypes.c_void_p(4100), 1 << 30, fake, None)
     assert rc == -2
+    # the entry points with the boundary terms of Eq. 4 check the same things
+    rc = lib.semicrf_logz_fwd_boundary(None, None, None, None, None, None, None, None, 1, 8, 2, 3, 0, 1,
+                                       None, 0, None, None)
+    assert rc == -1
+    rc = lib.semicrf_fwd_bwd_boundary(fake, None, fake, fake, None, None, None, None, None, 1, 8, 2, 3, 0, 1,
+                                      None, 0, fake, fake, fake, fake, None, None, None, None, None, None, None)
+    assert rc == -2
     # bad sizes win over everything else
     rc = lib.semicrf_logz_fwd(fake, None, fake, fake, 1, 8, 0, 3, 0, 1, fake, 1 << 30, fake, None)
     assert rc == -1

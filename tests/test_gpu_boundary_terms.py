@@ -1,0 +1,125 @@
+"""GPU parity of the boundary terms of Eq. 4 (start/end projections, scalar sequence
+boundaries), their gradients and the boundary posterior, against the fp64 CPU oracle.
+
+Tolerances as in test_gpu_parity.py: logZ relative 1e-5; per-position outputs (grad_emis,
+pos_marg, grad_proj_start, grad_proj_end, bdy_post: probabilities times the upstream weight)
+absolute 1e-4 * max(1, |w|); accumulated gradients 1e-4 * max(1, max|g|).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2604_18780_amd import binding as sb
+from paper_2604_18780_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def dev(a, dtype=np.float32):
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a, dtype=dtype)).to(DEV)
+
+
+def make_terms(seed, w, scale=0.5):
+    rng = np.random.default_rng(seed)
+    ps = (scale * rng.standard_normal((w.B, w.T, w.C))).astype(np.float32)
+    pe = (scale * rng.standard_normal((w.B, w.T, w.C))).astype(np.float32)
+    pis = rng.standard_normal(w.C).astype(np.float32)
+    pie = rng.standard_normal(w.C).astype(np.float32)
+    return ps, pe, pis, pie
+
+
+def nan_pad(a, lengths):
+    a = a.copy()
+    for b in range(a.shape[0]):
+        a[b, int(lengths[b]):] = np.nan       # rows beyond the sequence must never be read
+    return a
+
+
+def check(w, ps, pe, pis, pie, grad_logz=None, ckpt_interval=0, flags=sb.SEMICRF_CENTER, label=""):
+    print(f"[case] {label} B={w.B} T={w.T} K={w.K} C={w.C} delta={ckpt_interval} flags={flags}", flush=True)
+    emis = dev(nan_pad(w.emis, w.lengths))
+    out = sb.semicrf_fwd_bwd_boundary(
+        emis, dev(w.lengths, np.int32), dev(w.trans), dev(w.dur), dev(grad_logz),
+        dev(None if ps is None else nan_pad(ps, w.lengths)), dev(None if pe is None else nan_pad(pe, w.lengths)),
+        dev(pis), dev(pie), ckpt_interval, flags)
+    lz_f = sb.semicrf_logz_fwd_boundary(emis, dev(w.lengths, np.int32), dev(w.trans), dev(w.dur),
+                                        dev(None if ps is None else nan_pad(ps, w.lengths)),
+                                        dev(None if pe is None else nan_pad(pe, w.lengths)), dev(pis), dev(pie),
+                                        ckpt_interval, flags)
+    torch.cuda.synchronize()
+    o = {k: v.double().cpu().numpy() for k, v in out.items()}
+    r = oracle.fwd_bwd(w.emis, w.lengths, w.trans, w.dur, grad_logz=grad_logz, proj_start=ps, proj_end=pe,
+                       pi_start=pis, pi_end=pie, boundary=True, center=bool(flags & sb.SEMICRF_CENTER))
+    wmax = 1.0 if grad_logz is None else max(1.0, float(np.abs(grad_logz).max()))
+    assert np.all(np.isfinite(o["logz"]))
+    assert np.abs(o["logz"] - r.logz).max() <= 1e-5 * max(1.0, np.abs(r.logz).max())
+    assert np.array_equal(o["logz"], lz_f.double().cpu().numpy())
+    errs = {}
+    for name, ref in (("grad_emis", r.grad_emis), ("pos_marg", r.pos_marg), ("grad_proj_start", r.grad_proj_start),
+                      ("grad_proj_end", r.grad_proj_end), ("bdy_post", r.bdy_post)):
+        errs[name] = np.abs(o[name] - ref).max()
+        assert errs[name] <= 1e-4 * wmax, (name, errs[name])
+    for name, ref in (("grad_trans", r.grad_trans), ("grad_dur", r.grad_dur), ("grad_pi_start", r.grad_pi_start),
+                      ("grad_pi_end", r.grad_pi_end)):
+        errs[name] = np.abs(o[name] - ref).max()
+        assert errs[name] <= 1e-4 * max(1.0, np.abs(ref).max()), (name, errs[name])
+    print("       max err: " + " ".join(f"{k} {v:.1e}" for k, v in errs.items()), flush=True)
+    return o, r
+
+
+@pytest.mark.parametrize("seed,B,T,K,C", [
+    (1, 3, 40, 5, 3), (2, 4, 300, 8, 6), (3, 2, 700, 33, 24), (4, 5, 130, 1, 7),
+    (5, 3, 90, 2, 5), (6, 2, 50, 80, 4), (7, 3, 257, 16, 64), (8, 6, 33, 7, 1), (9, 1, 1, 1, 1),
+])
+def test_random_ragged_cases_with_all_boundary_terms(seed, B, T, K, C):
+    w = synth.small_random(seed, B, T, K, C, ragged=True)
+    if seed == 2:
+        w.lengths[0] = 0
+        w.lengths[1] = T
+    rng = np.random.default_rng(seed)
+    check(w, *make_terms(100 + seed, w), grad_logz=rng.standard_normal(B))
+
+
+def test_each_term_alone_and_none():
+    w = synth.small_random(21, 3, 260, 12, 10, ragged=True)
+    ps, pe, pis, pie = make_terms(121, w)
+    check(w, ps, None, None, None, label="start projections only")
+    check(w, None, pe, None, None, label="end projections only")
+    check(w, None, None, pis, pie, label="scalar boundaries only")
+    o, _ = check(w, None, None, None, None, label="no boundary term")
+    # with no term the plain entry point must give the same bits
+    emis = dev(nan_pad(w.emis, w.lengths))
+    plain = sb.semicrf_fwd_bwd(emis, dev(w.lengths, np.int32), dev(w.trans), dev(w.dur))
+    torch.cuda.synchronize()
+    for name, t in zip(("logz", "grad_emis", "grad_trans", "grad_dur", "pos_marg"), plain):
+        assert np.array_equal(o[name], t.double().cpu().numpy()), name
+
+
+def test_many_chunks_no_centering_and_sequential_fallback():
+    w = synth.small_random(22, 2, 1500, 12, 10, ragged=True)
+    w.lengths[:] = [1500, 1203]
+    terms = make_terms(122, w)
+    check(w, *terms, ckpt_interval=64, label="many chunks")
+    check(w, *terms, ckpt_interval=64, flags=0, label="no centring")
+    check(w, *terms, ckpt_interval=64, flags=sb.SEMICRF_CENTER | sb.SEMICRF_SEQUENTIAL_SCAN,
+          label="sequential scans")
+
+
+def test_generic_kernels_with_boundary_terms():
+    w = synth.small_random(23, 2, 300, 200, 24, ragged=True)       # K beyond the one-wave kernels
+    check(w, *make_terms(123, w), label="generic kernels")
+
+
+def test_large_boundary_scores_shorten_the_scaling_block():
+    w = synth.small_random(24, 2, 400, 12, 5, ragged=False)
+    check(w, *make_terms(124, w, scale=10.0), label="large projections")
+
+
+def test_workload_shapes_with_boundary_terms():
+    w = synth.make("genomic", T=6000, B=2)
+    check(w, *make_terms(125, w), label="genomic shape")
+    w = synth.make("speech", B=4, T=600)
+    check(w, *make_terms(126, w), label="speech shape")
