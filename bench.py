@@ -51,6 +51,9 @@ def main():
     ap.add_argument("--ckpt-interval", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-T", type=int, default=0)
+    ap.add_argument("--boundary-terms", action="store_true",
+                    help="time semicrf_fwd_bwd_boundary with start/end projections, scalar boundaries and all "
+                         "their outputs instead (whole-call time only; prints its own JSON line)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy so that a rocprofv3 --pmc run of this "
                          "command holds a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
@@ -79,6 +82,33 @@ def main():
            torch.empty((C, C), dtype=torch.float32, device=dev),
            torch.empty((K, C), dtype=torch.float32, device=dev),
            torch.empty((B, T, C), dtype=torch.float32, device=dev))
+    if args.boundary_terms:
+        import numpy as np
+        rng = np.random.default_rng(12345)
+        f32 = lambda a: torch.from_numpy(a.astype(np.float32)).to(dev)
+        ps, pe = f32(0.5 * rng.standard_normal((B, T, C))), f32(0.5 * rng.standard_normal((B, T, C)))
+        pis, pie = f32(rng.standard_normal(C)), f32(rng.standard_normal(C))
+        call = lambda: sb.semicrf_fwd_bwd_boundary(emis, lengths, trans, dur, None, ps, pe, pis, pie,
+                                                   args.ckpt_interval, workspace=ws)
+        for _ in range(args.warmup):
+            o = call()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            o = call()
+        torch.cuda.synchronize()
+        ms = 1e3 * (time.perf_counter() - t0) / args.steps
+        print(json.dumps({
+            "metric": "semi-CRF fwd+bwd with boundary projections, edge evals/sec (B*T*K*C^2/s)",
+            "value": w.nominal_edges / (ms * 1e-3), "unit": "edge evals/s",
+            "positions_per_s": w.positions / (ms * 1e-3), "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+            "config": {"workload": f"{w.name}: B={B} T={T} K={K} C={C} with proj_start, proj_end ~ N(0, 0.5^2), "
+                                   f"pi_start, pi_end ~ N(0,1); all gradients and the boundary posterior "
+                                   f"(output tensors allocated inside the timed calls)"},
+            "logz_mean": float(o["logz"].double().mean().item())}))
+        return
     events = [sb.StageEvents() for _ in range(args.steps)]
 
     if args.calibrate_copy:
