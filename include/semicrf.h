@@ -170,6 +170,18 @@ int semicrf_fwd_bwd_boundary(const float *emis, const int32_t *lengths, const fl
                              float *grad_pi_start, float *grad_pi_end, float *bdy_post, void *stream);
 
 /*
+ * The two entropies of the paper's boundary-entropy paragraph, from outputs of the calls above
+ * (device pointers; needs no workspace):
+ *   h_pos [B] float or NULL: mean over the L_b tokens of -sum_c pos_marg[b,u,c] ln pos_marg[b,u,c]
+ *   h_bdy [B] float or NULL: -sum_{u<L_b} ph_u ln ph_u with ph_u = bdy_post[b,u] / sum_{u'<L_b} bdy_post[b,u']
+ *                            (a segment starts at token u iff a boundary falls at position u); ln L_b at K = 1
+ * pos_marg [B,T,C] is needed for h_pos, bdy_post [B,T+1] for h_bdy; at least one output must be
+ * given.  Empty sequences give 0.
+ */
+int semicrf_entropies(const float *pos_marg, const float *bdy_post, const int32_t *lengths, int B, int T,
+                      int C, float *h_pos, float *h_bdy, void *stream);
+
+/*
  * Measurement aid: semicrf_fwd_bwd with five caller-owned HIP events recorded on
  * `stream`: stage_events[0] before the first kernel and stage_events[1..4] after
  * each of the four stages

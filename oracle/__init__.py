@@ -178,3 +178,27 @@ def logz(emis, lengths, trans, dur, center=True, threads=0, proj_start=None, pro
     if rc < 0:
         raise ValueError("semicrf_oracle_logz: bad arguments")
     return out
+
+
+def entropies(pos_marg, bdy_post, lengths):
+    """The two entropies of the paper's boundary-entropy paragraph, written out per sequence:
+    h_pos = mean over the L tokens of the label entropy of pos_marg[u,:];
+    h_bdy = Shannon entropy of bdy_post[0:L] normalised to sum 1 (a segment starts at token u
+    iff a boundary falls at position u).  Plain loops over sequences, fp64."""
+    pos_marg = _as_f64(pos_marg)
+    bdy_post = _as_f64(bdy_post)
+    B, T, C = pos_marg.shape
+    h_pos = np.zeros(B)
+    h_bdy = np.zeros(B)
+    for b in range(B):
+        L = T if lengths is None else int(lengths[b])
+        if L < 1:
+            continue
+        pm = pos_marg[b, :L]
+        safe = np.where(pm > 0, pm, 1.0)
+        h_pos[b] = -(pm * np.log(safe)).sum() / L
+        ph = bdy_post[b, :L] / bdy_post[b, :L].sum()
+        safe = np.where(ph > 0, ph, 1.0)
+        h_bdy[b] = -(ph * np.log(safe)).sum()
+    return h_pos, h_bdy
+

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libsemicrf.so")
 EXPORTS = ("semicrf_version", "semicrf_strerror", "semicrf_workspace_bytes",
            "semicrf_cum_scores", "semicrf_logz_fwd", "semicrf_fwd_bwd", "semicrf_fwd_bwd_profiled",
            "semicrf_scan_report", "semicrf_ckpt_interval", "semicrf_logz_fwd_boundary",
-           "semicrf_fwd_bwd_boundary")
+           "semicrf_fwd_bwd_boundary", "semicrf_entropies")
 SEMICRF_CENTER = 1
 SEMICRF_SEQUENTIAL_SCAN = 2
 _lib = None
@@ -62,6 +62,8 @@ def load():
     lib.semicrf_logz_fwd_boundary.argtypes = [vp] * 8 + [ci, ci, ci, ci, ci, cu, vp, sz, vp, vp]
     lib.semicrf_fwd_bwd_boundary.restype = ci
     lib.semicrf_fwd_bwd_boundary.argtypes = [vp] * 9 + [ci, ci, ci, ci, ci, cu, vp, sz] + [vp] * 11
+    lib.semicrf_entropies.restype = ci
+    lib.semicrf_entropies.argtypes = [vp, vp, vp, ci, ci, ci, vp, vp, vp]
     lib.semicrf_scan_report.restype = ci
     lib.semicrf_scan_report.argtypes = [vp, sz, ci, ci, ci, ci, ci, ci, vp, vp, vp]
     _lib = lib
@@ -206,6 +208,17 @@ def semicrf_fwd_bwd_boundary(emis, lengths, trans, dur, grad_logz=None, proj_sta
                                                                  "grad_pi_start", "grad_pi_end", "bdy_post")],
                                            _stream()))
     return o
+
+
+def semicrf_entropies(pos_marg, bdy_post, lengths):
+    """Returns (h_pos [B], h_bdy [B]) from the outputs of semicrf_fwd_bwd_boundary."""
+    B, T, C = pos_marg.shape
+    h_pos = torch.empty(B, dtype=torch.float32, device=pos_marg.device)
+    h_bdy = torch.empty(B, dtype=torch.float32, device=pos_marg.device)
+    _check(load().semicrf_entropies(_ptr(pos_marg, torch.float32), _ptr(bdy_post, torch.float32),
+                                    _ptr(lengths, torch.int32), B, T, C, h_pos.data_ptr(), h_bdy.data_ptr(),
+                                    _stream()))
+    return h_pos, h_bdy
 
 
 def semicrf_scan_report(workspace, B, T, K, C, ckpt_interval=0, want_grad=True):

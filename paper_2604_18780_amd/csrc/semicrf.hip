@@ -2366,6 +2366,57 @@ __global__ __launch_bounds__(NT) void k_fin_seq(Params p)
     else fin_pi_body(p);
 }
 
+// Entropies of the posteriors (the paper's boundary-entropy paragraph): per sequence,
+//   h_pos = (1/L) sum_{u<L} -sum_c pm[u,c] ln pm[u,c]          (mean per-position label entropy)
+//   h_bdy = -sum_{u<L} ph_u ln ph_u,  ph_u = bdy[u] / sum_{u'<L} bdy[u']   (entropy of the normalised
+//           segment-start distribution; a segment starts at token u iff a boundary falls at position u)
+// One workgroup per sequence; thread partial sums are combined in thread order.
+__global__ __launch_bounds__(NT) void k_entropies(const float *pos_marg, const float *bdy_post,
+                                                  const int32_t *lengths, int T, int C, float *h_pos,
+                                                  float *h_bdy)
+{
+    __shared__ double red[NT];
+    const int b = blockIdx.x, tid = threadIdx.x;
+    int L = lengths ? lengths[b] : T;
+    L = L < 0 ? 0 : (L > T ? T : L);
+    auto block_sum = [&](double v) {
+        red[tid] = v;
+        __syncthreads();
+        double s = 0.0;
+        if (tid == 0)
+            for (int i = 0; i < NT; ++i) s += red[i];
+        __syncthreads();
+        if (tid == 0) red[0] = s;
+        __syncthreads();
+        s = red[0];
+        __syncthreads();
+        return s;
+    };
+    if (h_pos) {
+        const float *pm = pos_marg + (size_t)b * T * C;
+        double acc = 0.0;
+        for (size_t i = tid; i < (size_t)L * C; i += NT) {
+            const double x = (double)pm[i];
+            if (x > 0.0) acc -= x * log(x);
+        }
+        const double tot = block_sum(acc);
+        if (tid == 0) h_pos[b] = L > 0 ? (float)(tot / (double)L) : 0.f;
+    }
+    if (h_bdy) {
+        const float *bd = bdy_post + (size_t)b * (T + 1);
+        double acc = 0.0;
+        for (int u = tid; u < L; u += NT) acc += (double)bd[u];
+        const double norm = block_sum(acc);
+        acc = 0.0;
+        for (int u = tid; u < L; u += NT) {
+            const double x = (double)bd[u] / norm;
+            if (x > 0.0) acc -= x * log(x);
+        }
+        const double tot = block_sum(acc);
+        if (tid == 0) h_bdy[b] = L > 0 ? (float)tot : 0.f;
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Host side: sizing, workspace carving, launches.
 // ---------------------------------------------------------------------------
@@ -2918,6 +2969,16 @@ int semicrf_fwd_bwd_boundary(const float *emis, const int32_t *lengths, const fl
     p.g_proj_start = grad_proj_start; p.g_proj_end = grad_proj_end;
     p.g_pi_start = grad_pi_start; p.g_pi_end = grad_pi_end; p.bdy_post = bdy_post;
     return run(p, ckpt_interval, workspace, workspace_bytes, (hipStream_t)stream, 2);
+}
+
+int semicrf_entropies(const float *pos_marg, const float *bdy_post, const int32_t *lengths, int B, int T,
+                      int C, float *h_pos, float *h_bdy, void *stream)
+{
+    if (B < 1 || T < 1 || C < 1) return SEMICRF_EINVAL;
+    if ((!h_pos && !h_bdy) || (h_pos && !pos_marg) || (h_bdy && !bdy_post)) return SEMICRF_EINVAL;
+    hipLaunchKernelGGL(k_entropies, dim3(B), dim3(NT), 0, (hipStream_t)stream, pos_marg, bdy_post, lengths, T,
+                       C, h_pos, h_bdy);
+    return check_launch();
 }
 
 int semicrf_scan_report(const void *workspace, size_t workspace_bytes, int B, int T, int K, int C,

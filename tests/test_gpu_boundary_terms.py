@@ -123,3 +123,24 @@ def test_workload_shapes_with_boundary_terms():
     check(w, *make_terms(125, w), label="genomic shape")
     w = synth.make("speech", B=4, T=600)
     check(w, *make_terms(126, w), label="speech shape")
+
+
+def test_entropies_of_the_posteriors():
+    w = synth.small_random(31, 4, 300, 9, 7, ragged=True)
+    w.lengths[3] = 0
+    ps, pe, pis, pie = make_terms(131, w)
+    emis = dev(nan_pad(w.emis, w.lengths))
+    out = sb.semicrf_fwd_bwd_boundary(emis, dev(w.lengths, np.int32), dev(w.trans), dev(w.dur), None,
+                                      dev(nan_pad(ps, w.lengths)), dev(nan_pad(pe, w.lengths)), dev(pis), dev(pie))
+    h_pos, h_bdy = sb.semicrf_entropies(out["pos_marg"], out["bdy_post"], dev(w.lengths, np.int32))
+    torch.cuda.synchronize()
+    r = oracle.fwd_bwd(w.emis, w.lengths, w.trans, w.dur, proj_start=ps, proj_end=pe, pi_start=pis, pi_end=pie)
+    rp, rb = oracle.entropies(r.pos_marg, r.bdy_post, w.lengths)
+    assert np.abs(h_pos.double().cpu().numpy() - rp).max() <= 1e-5 * max(1.0, np.abs(rp).max())
+    assert np.abs(h_bdy.double().cpu().numpy() - rb).max() <= 1e-5 * max(1.0, np.abs(rb).max())
+    # K = 1: ln L, whatever the parameters
+    w1 = synth.small_random(32, 2, 200, 1, 5, ragged=True)
+    o1 = sb.semicrf_fwd_bwd_boundary(dev(nan_pad(w1.emis, w1.lengths)), dev(w1.lengths, np.int32), dev(w1.trans),
+                                     dev(w1.dur))
+    _, hb = sb.semicrf_entropies(o1["pos_marg"], o1["bdy_post"], dev(w1.lengths, np.int32))
+    assert np.abs(hb.double().cpu().numpy() - np.log(w1.lengths)).max() <= 1e-5

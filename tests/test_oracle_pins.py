@@ -559,3 +559,25 @@ def test_boundary_posterior_invariants():
         assert np.all(p[:L + 1] > 0) and np.all(p[:L + 1] <= 1 + 1e-12)
         # expected number of boundaries = expected number of segments + 1
         assert abs(p.sum() - (r.grad_dur_b[b].sum() + 1)) < 1e-9
+
+
+def test_entropies_closed_forms():
+    """K = 1: every token starts a segment, so the boundary entropy is ln L whatever the
+    parameters (stated in the boundary-entropy paragraph).  All-zero potentials: the label
+    posterior is uniform, so the position entropy is ln C; with K >= 1 and zero potentials the
+    boundary posterior is the same at every interior position by symmetry only for K = 1, so
+    the general case is checked against the definition written out on a tiny example."""
+    emis, lengths, trans, dur = rand_case(18, 3, 30, 1, 4, ragged=True)
+    r = oracle.fwd_bwd(emis, lengths, trans, dur, boundary=True)
+    h_pos, h_bdy = oracle.entropies(r.pos_marg, r.bdy_post, lengths)
+    assert np.allclose(h_bdy, np.log(lengths), atol=1e-12)
+    z = oracle.fwd_bwd(np.zeros((1, 12, 5)), None, np.zeros((5, 5)), np.zeros((3, 5)), boundary=True)
+    h_pos, h_bdy = oracle.entropies(z.pos_marg, z.bdy_post, None)
+    assert abs(h_pos[0] - math.log(5)) < 1e-12
+    # definition by hand on a 3-token example
+    pm = np.array([[[0.5, 0.5], [1.0, 0.0], [0.25, 0.75]]])
+    bd = np.array([[1.0, 0.5, 0.5, 1.0]])
+    h_pos, h_bdy = oracle.entropies(pm, bd, None)
+    hp = (math.log(2) + 0.0 - 0.25 * math.log(0.25) - 0.75 * math.log(0.75)) / 3
+    ph = np.array([0.5, 0.25, 0.25])
+    assert abs(h_pos[0] - hp) < 1e-12 and abs(h_bdy[0] + (ph * np.log(ph)).sum()) < 1e-12
