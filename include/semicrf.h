@@ -68,6 +68,12 @@ typedef enum {
  * results are those of the sequential scan either way; only the time differs.
  * semicrf_scan_report tells which happened. */
 #define SEMICRF_SEQUENTIAL_SCAN 2u
+/* flags bits 2, 3: storage type of `emis`.  With one of them set the `emis` argument of every
+ * entry point addresses 2-byte elements, IEEE half precision or bfloat16, in the same [B,T,C]
+ * layout (pass the pointer cast to const float*); they are widened exactly on load and
+ * everything downstream is unchanged (all outputs stay float).  Setting both is invalid. */
+#define SEMICRF_EMIS_F16 4u
+#define SEMICRF_EMIS_BF16 8u
 
 int semicrf_version(void);
 

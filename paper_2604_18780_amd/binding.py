@@ -21,6 +21,8 @@ EXPORTS = ("semicrf_version", "semicrf_strerror", "semicrf_workspace_bytes",
            "semicrf_fwd_bwd_boundary", "semicrf_entropies")
 SEMICRF_CENTER = 1
 SEMICRF_SEQUENTIAL_SCAN = 2
+SEMICRF_EMIS_F16 = 4
+SEMICRF_EMIS_BF16 = 8
 _lib = None
 
 
@@ -104,6 +106,14 @@ def _ptr(t, dtype):
     return t.data_ptr()
 
 
+def _emis(t, flags):
+    """Pointer of the emission tensor and the flags with its storage type (float32, float16 or bfloat16)."""
+    bits = {torch.float32: 0, torch.float16: SEMICRF_EMIS_F16, torch.bfloat16: SEMICRF_EMIS_BF16}
+    if t.dtype not in bits:
+        raise ValueError("emissions must be float32, float16 or bfloat16")
+    return _ptr(t, t.dtype), (flags & ~(SEMICRF_EMIS_F16 | SEMICRF_EMIS_BF16)) | bits[t.dtype]
+
+
 def _stream():
     return torch.cuda.current_stream().cuda_stream
 
@@ -120,7 +130,8 @@ def semicrf_cum_scores(emis, lengths, flags=SEMICRF_CENTER, workspace=None):
     if workspace is None:
         workspace = alloc_workspace(B, T, 1, C, 0, False, emis.device)
     cum = torch.empty((B, T + 1, C), dtype=torch.float64, device=emis.device)
-    _check(load().semicrf_cum_scores(_ptr(emis, torch.float32), _ptr(lengths, torch.int32),
+    ep, flags = _emis(emis, flags)
+    _check(load().semicrf_cum_scores(ep, _ptr(lengths, torch.int32),
                                      B, T, C, flags, workspace.data_ptr(), workspace.numel(),
                                      cum.data_ptr(), _stream()))
     return cum
@@ -134,7 +145,8 @@ def semicrf_logz_fwd(emis, lengths, trans, dur, ckpt_interval=0, flags=SEMICRF_C
         workspace = alloc_workspace(B, T, K, C, ckpt_interval, False, emis.device)
     if logz is None:
         logz = torch.empty(B, dtype=torch.float32, device=emis.device)
-    _check(load().semicrf_logz_fwd(_ptr(emis, torch.float32), _ptr(lengths, torch.int32),
+    ep, flags = _emis(emis, flags)
+    _check(load().semicrf_logz_fwd(ep, _ptr(lengths, torch.int32),
                                    _ptr(trans, torch.float32), _ptr(dur, torch.float32),
                                    B, T, K, C, ckpt_interval, flags,
                                    workspace.data_ptr(), workspace.numel(),
@@ -158,7 +170,8 @@ def semicrf_fwd_bwd(emis, lengths, trans, dur, grad_logz=None, ckpt_interval=0,
         pm = torch.empty((B, T, C), dtype=torch.float32, device=dev) if want_pos_marg else None
     else:
         logz, g_e, g_t, g_d, pm = out
-    _check(load().semicrf_fwd_bwd(_ptr(emis, torch.float32), _ptr(lengths, torch.int32),
+    ep, flags = _emis(emis, flags)
+    _check(load().semicrf_fwd_bwd(ep, _ptr(lengths, torch.int32),
                                   _ptr(trans, torch.float32), _ptr(dur, torch.float32),
                                   _ptr(grad_logz, torch.float32), B, T, K, C, ckpt_interval, flags,
                                   workspace.data_ptr(), workspace.numel(),
@@ -176,7 +189,8 @@ def semicrf_logz_fwd_boundary(emis, lengths, trans, dur, proj_start=None, proj_e
         workspace = alloc_workspace(B, T, K, C, ckpt_interval, False, emis.device)
     logz = torch.empty(B, dtype=torch.float32, device=emis.device)
     f32 = torch.float32
-    _check(load().semicrf_logz_fwd_boundary(_ptr(emis, f32), _ptr(lengths, torch.int32), _ptr(trans, f32),
+    ep, flags = _emis(emis, flags)
+    _check(load().semicrf_logz_fwd_boundary(ep, _ptr(lengths, torch.int32), _ptr(trans, f32),
                                             _ptr(dur, f32), _ptr(proj_start, f32), _ptr(proj_end, f32),
                                             _ptr(pi_start, f32), _ptr(pi_end, f32), B, T, K, C, ckpt_interval,
                                             flags, workspace.data_ptr(), workspace.numel(), _ptr(logz, f32),
@@ -198,7 +212,8 @@ def semicrf_fwd_bwd_boundary(emis, lengths, trans, dur, grad_logz=None, proj_sta
     o = dict(logz=new(B), grad_emis=new(B, T, C), grad_trans=new(C, C), grad_dur=new(K, C), pos_marg=new(B, T, C),
              grad_proj_start=new(B, T, C), grad_proj_end=new(B, T, C), grad_pi_start=new(C), grad_pi_end=new(C),
              bdy_post=new(B, T + 1))
-    _check(load().semicrf_fwd_bwd_boundary(_ptr(emis, f32), _ptr(lengths, torch.int32), _ptr(trans, f32),
+    ep, flags = _emis(emis, flags)
+    _check(load().semicrf_fwd_bwd_boundary(ep, _ptr(lengths, torch.int32), _ptr(trans, f32),
                                            _ptr(dur, f32), _ptr(grad_logz, f32), _ptr(proj_start, f32),
                                            _ptr(proj_end, f32), _ptr(pi_start, f32), _ptr(pi_end, f32),
                                            B, T, K, C, ckpt_interval, flags, workspace.data_ptr(),
@@ -290,8 +305,9 @@ def semicrf_fwd_bwd_profiled(emis, lengths, trans, dur, events, grad_logz=None, 
                torch.empty((K, C), dtype=torch.float32, device=dev),
                torch.empty((B, T, C), dtype=torch.float32, device=dev))
     logz, g_e, g_t, g_d, pm = out
+    ep, flags = _emis(emis, flags)
     _check(load().semicrf_fwd_bwd_profiled(
-        _ptr(emis, torch.float32), _ptr(lengths, torch.int32), _ptr(trans, torch.float32),
+        ep, _ptr(lengths, torch.int32), _ptr(trans, torch.float32),
         _ptr(dur, torch.float32), _ptr(grad_logz, torch.float32), B, T, K, C, ckpt_interval, flags,
         workspace.data_ptr(), workspace.numel(), _ptr(logz, torch.float32),
         _ptr(g_e, torch.float32), _ptr(g_t, torch.float32), _ptr(g_d, torch.float32),

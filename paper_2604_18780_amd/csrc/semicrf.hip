@@ -65,7 +65,8 @@ struct SeqHdr {
 
 struct Params {
     // problem
-    const float *emis;
+    const void *emis;   // [B][T][C] float, or 2-byte IEEE half / bfloat16 (emis_type 1 / 2)
+    int emis_type;
     const int32_t *lengths;
     const float *trans;
     const float *dur;
@@ -130,6 +131,15 @@ struct Params {
     float *bdy_post;      // optional [B][T+1]
 };
 
+// emission i of the [B][T][C] array; ET = storage type (0 float, 1 IEEE half, 2 bfloat16)
+template <int ET>
+__device__ __forceinline__ double emis_at(const Params &p, size_t i)
+{
+    if (ET == 0) return (double)((const float *)p.emis)[i];
+    if (ET == 1) return (double)(float)((const _Float16 *)p.emis)[i];
+    return (double)__uint_as_float((uint32_t)((const uint16_t *)p.emis)[i] << 16);  // bfloat16: upper half of a float
+}
+
 __device__ __forceinline__ int seq_len(const Params &p, int b)
 {
     int L = p.lengths ? p.lengths[b] : p.T;
@@ -180,6 +190,7 @@ __device__ __forceinline__ void tables_body(const Params &p)
 // ---------------------------------------------------------------------------
 // Eq. 1, stage 1: per-chunk column sums (fp64) and |f| maxima.  grid (NCH, B).
 // ---------------------------------------------------------------------------
+template <int ET>
 __device__ __forceinline__ void colsum_body(const Params &p, const int b, const int ch)
 {
     __shared__ double red[NT];
@@ -192,10 +203,10 @@ __device__ __forceinline__ void colsum_body(const Params &p, const int b, const 
     const int r = tid / C, c = tid % C;
     double acc = 0.0, mx = 0.0;
     if (r < R) {
-        const float *f = p.emis + ((size_t)b * p.T) * C;
+        const size_t f0 = ((size_t)b * p.T) * C;
 #pragma unroll 8
         for (int u = u0 + r; u < u1; u += R) {
-            double v = (double)f[(size_t)u * C + c];
+            double v = emis_at<ET>(p, f0 + (size_t)u * C + c);
             acc += v;
             mx = fmax(mx, fabs(v));
         }
@@ -229,6 +240,7 @@ __device__ __forceinline__ void colsum_body(const Params &p, const int b, const 
 }
 
 // One launch for both: workgroup 0 builds the tables, workgroup 1 + b*NCH + ch sums a chunk.
+template <int ET>
 __global__ __launch_bounds__(NT) void k_colsum(Params p)
 {
     if (blockIdx.x == 0) {
@@ -236,7 +248,7 @@ __global__ __launch_bounds__(NT) void k_colsum(Params p)
         return;
     }
     const int id = blockIdx.x - 1;
-    colsum_body(p, id / p.NCH, id % p.NCH);
+    colsum_body<ET>(p, id / p.NCH, id % p.NCH);
 }
 
 // ---------------------------------------------------------------------------
@@ -324,7 +336,7 @@ __global__ __launch_bounds__(NT) void k_prep_seq(Params p)
 constexpr int PREP_SEG = 32;
 static_assert(PREP_CH == 8 * PREP_SEG && JMAX <= PREP_SEG && NT == 256, "k_prefix geometry");
 
-template <bool BTERMS>  // any boundary term of Eq. 4 present
+template <bool BTERMS, int ET>  // any boundary term of Eq. 4 present; emission storage type
 __global__ __launch_bounds__(NT) void k_prefix(Params p)
 {
     __shared__ double segsum[8][PREP_SEG + 1];
@@ -339,11 +351,11 @@ __global__ __launch_bounds__(NT) void k_prefix(Params p)
     for (int cb = 0; cb < C; cb += 32) {
         const int c = cb + cl;
         const bool valid = c < C;
-        const float *f = p.emis + ((size_t)b * p.T) * C + (valid ? c : 0);
+        const size_t f0 = ((size_t)b * p.T) * C + (valid ? c : 0);
         const double nu = valid ? p.nu[(size_t)b * C + c] : 0.0;
         double sum = 0.0;
         if (valid)
-            for (int t = t0; t < min(tend, L); ++t) sum += (double)f[(size_t)t * C] - nu;
+            for (int t = t0; t < min(tend, L); ++t) sum += emis_at<ET>(p, f0 + (size_t)t * C) - nu;
         segsum[seg][cl] = sum;
         __syncthreads();
         double S = valid ? p.chsum[((size_t)b * p.NCH + ch) * C + c] : 0.0;
@@ -379,7 +391,7 @@ __global__ __launch_bounds__(NT) void k_prefix(Params p)
                 }
                 p.EI[(row0 + t) * C + c] = pr;
                 if (p.cum) p.cum[(row0 + t) * C + c] = S;
-                if (t < L) S += (double)f[(size_t)t * C] - nu;
+                if (t < L) S += emis_at<ET>(p, f0 + (size_t)t * C) - nu;
             } else if (p.cum) {
                 p.cum[(row0 + t) * C + c] = 0.0;
             }
@@ -2595,15 +2607,23 @@ int check_launch()
 }
 
 // prefix stage shared by all entry points
-int launch_prep(const Params &p, hipStream_t st)
+template <int ET>
+int launch_prep_et(const Params &p, hipStream_t st)
 {
-    hipLaunchKernelGGL(k_colsum, dim3(1 + p.NCH * p.B), dim3(NT), 0, st, p);
+    hipLaunchKernelGGL(k_colsum<ET>, dim3(1 + p.NCH * p.B), dim3(NT), 0, st, p);
     hipLaunchKernelGGL(k_prep_seq, dim3(p.B), dim3(NT), 0, st, p);
     if (p.proj_start || p.proj_end || p.pi_start || p.pi_end)
-        hipLaunchKernelGGL(k_prefix<true>, dim3(p.NCH, p.B), dim3(NT), 0, st, p);
+        hipLaunchKernelGGL((k_prefix<true, ET>), dim3(p.NCH, p.B), dim3(NT), 0, st, p);
     else
-        hipLaunchKernelGGL(k_prefix<false>, dim3(p.NCH, p.B), dim3(NT), 0, st, p);
+        hipLaunchKernelGGL((k_prefix<false, ET>), dim3(p.NCH, p.B), dim3(NT), 0, st, p);
     return check_launch();
+}
+
+int launch_prep(const Params &p, hipStream_t st)
+{
+    if (p.emis_type == 1) return launch_prep_et<1>(p, st);
+    if (p.emis_type == 2) return launch_prep_et<2>(p, st);
+    return launch_prep_et<0>(p, st);
 }
 
 // Chooses the latency-oriented scan when the helper lanes can cover the durations,
@@ -2868,6 +2888,8 @@ int semicrf_cum_scores(const float *emis, const int32_t *lengths, int B, int T, 
     p.emis = emis; p.lengths = lengths;
     p.B = B; p.T = T; p.K = 1; p.C = C;
     p.center = (flags & SEMICRF_CENTER) ? 1 : 0;
+    p.emis_type = (flags & SEMICRF_EMIS_F16) ? 1 : ((flags & SEMICRF_EMIS_BF16) ? 2 : 0);
+    if ((flags & SEMICRF_EMIS_F16) && (flags & SEMICRF_EMIS_BF16)) return SEMICRF_EINVAL;
     p.cum = cum;
     return run(p, 0, workspace, workspace_bytes, (hipStream_t)stream, 0);
 }
@@ -2882,6 +2904,8 @@ int semicrf_logz_fwd(const float *emis, const int32_t *lengths, const float *tra
     p.emis = emis; p.lengths = lengths; p.trans = trans; p.dur = dur;
     p.B = B; p.T = T; p.K = K; p.C = C;
     p.center = (flags & SEMICRF_CENTER) ? 1 : 0;
+    p.emis_type = (flags & SEMICRF_EMIS_F16) ? 1 : ((flags & SEMICRF_EMIS_BF16) ? 2 : 0);
+    if ((flags & SEMICRF_EMIS_F16) && (flags & SEMICRF_EMIS_BF16)) return SEMICRF_EINVAL;
     p.spec = (flags & SEMICRF_SEQUENTIAL_SCAN) ? 0 : 1;
     p.logz = logz;
     return run(p, ckpt_interval, workspace, workspace_bytes, (hipStream_t)stream, 1);
@@ -2899,6 +2923,8 @@ int semicrf_fwd_bwd(const float *emis, const int32_t *lengths, const float *tran
     p.emis = emis; p.lengths = lengths; p.trans = trans; p.dur = dur; p.grad_logz = grad_logz;
     p.B = B; p.T = T; p.K = K; p.C = C;
     p.center = (flags & SEMICRF_CENTER) ? 1 : 0;
+    p.emis_type = (flags & SEMICRF_EMIS_F16) ? 1 : ((flags & SEMICRF_EMIS_BF16) ? 2 : 0);
+    if ((flags & SEMICRF_EMIS_F16) && (flags & SEMICRF_EMIS_BF16)) return SEMICRF_EINVAL;
     p.spec = (flags & SEMICRF_SEQUENTIAL_SCAN) ? 0 : 1;
     p.logz = logz; p.grad_emis = grad_emis; p.grad_trans = grad_trans; p.grad_dur = grad_dur;
     p.pos_marg = pos_marg;
@@ -2918,6 +2944,8 @@ int semicrf_fwd_bwd_profiled(const float *emis, const int32_t *lengths, const fl
     p.emis = emis; p.lengths = lengths; p.trans = trans; p.dur = dur; p.grad_logz = grad_logz;
     p.B = B; p.T = T; p.K = K; p.C = C;
     p.center = (flags & SEMICRF_CENTER) ? 1 : 0;
+    p.emis_type = (flags & SEMICRF_EMIS_F16) ? 1 : ((flags & SEMICRF_EMIS_BF16) ? 2 : 0);
+    if ((flags & SEMICRF_EMIS_F16) && (flags & SEMICRF_EMIS_BF16)) return SEMICRF_EINVAL;
     p.spec = (flags & SEMICRF_SEQUENTIAL_SCAN) ? 0 : 1;
     p.logz = logz; p.grad_emis = grad_emis; p.grad_trans = grad_trans; p.grad_dur = grad_dur;
     p.pos_marg = pos_marg;
@@ -2943,6 +2971,8 @@ int semicrf_logz_fwd_boundary(const float *emis, const int32_t *lengths, const f
     p.proj_start = proj_start; p.proj_end = proj_end; p.pi_start = pi_start; p.pi_end = pi_end;
     p.B = B; p.T = T; p.K = K; p.C = C;
     p.center = (flags & SEMICRF_CENTER) ? 1 : 0;
+    p.emis_type = (flags & SEMICRF_EMIS_F16) ? 1 : ((flags & SEMICRF_EMIS_BF16) ? 2 : 0);
+    if ((flags & SEMICRF_EMIS_F16) && (flags & SEMICRF_EMIS_BF16)) return SEMICRF_EINVAL;
     p.spec = (flags & SEMICRF_SEQUENTIAL_SCAN) ? 0 : 1;
     p.logz = logz;
     return run(p, ckpt_interval, workspace, workspace_bytes, (hipStream_t)stream, 1);
@@ -2963,6 +2993,8 @@ int semicrf_fwd_bwd_boundary(const float *emis, const int32_t *lengths, const fl
     p.proj_start = proj_start; p.proj_end = proj_end; p.pi_start = pi_start; p.pi_end = pi_end;
     p.B = B; p.T = T; p.K = K; p.C = C;
     p.center = (flags & SEMICRF_CENTER) ? 1 : 0;
+    p.emis_type = (flags & SEMICRF_EMIS_F16) ? 1 : ((flags & SEMICRF_EMIS_BF16) ? 2 : 0);
+    if ((flags & SEMICRF_EMIS_F16) && (flags & SEMICRF_EMIS_BF16)) return SEMICRF_EINVAL;
     p.spec = (flags & SEMICRF_SEQUENTIAL_SCAN) ? 0 : 1;
     p.logz = logz; p.grad_emis = grad_emis; p.grad_trans = grad_trans; p.grad_dur = grad_dur;
     p.pos_marg = pos_marg;

@@ -315,3 +315,36 @@ def test_full_size_workload_against_stored_oracle_values(name):
     assert pm.min().item() >= -1e-6 and pm.max().item() <= 1.0 + 1e-6
     # expected segment count from both accumulated gradients agrees
     assert abs(g_t.double().sum().item() - g_d.double().sum().item()) <= 1e-5 * g_d.double().sum().item()
+
+
+# --------------------------------------------------------------------------
+# Half-precision emissions (IEEE half, bfloat16): widened exactly on load
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
+def test_half_precision_emissions(dtype):
+    w = synth.small_random(95, 3, 500, 10, 12, ragged=True)
+    e_half = torch.from_numpy(w.emis).to(dtype)                 # round once, on the host
+    w.emis = e_half.to(torch.float32).numpy().copy()            # the oracle sees exactly those values
+    r = oracle.fwd_bwd(w.emis, w.lengths, w.trans, w.dur)
+    _, lengths, trans, dur = to_dev(w)
+    e_dev = e_half.to(DEV)
+    for b in range(w.B):
+        e_dev[b, int(w.lengths[b]):] = float("nan")
+    out = sb.semicrf_fwd_bwd(e_dev, lengths, trans, dur)
+    ref = sb.semicrf_fwd_bwd(e_dev.to(torch.float32), lengths, trans, dur)
+    lz = sb.semicrf_logz_fwd(e_dev, lengths, trans, dur)
+    cum = sb.semicrf_cum_scores(e_dev, lengths)
+    torch.cuda.synchronize()
+    assert_outputs_match_oracle([o.double().cpu().numpy() for o in out], r)
+    for a, b_ in zip(out, ref):
+        assert torch.equal(a, b_)                                # same values in, same bits out
+    assert torch.equal(lz, out[0])
+    rt = oracle.fwd_bwd(w.emis, w.lengths, w.trans, w.dur, tables=True)
+    assert np.abs(cum.cpu().numpy() - rt.S).max() <= 1e-9
+    # both storage flags at once are refused
+    with pytest.raises(sb.SemiCRFError) as ei:
+        lib = sb.load()
+        rc = lib.semicrf_logz_fwd(e_dev.data_ptr(), None, trans.data_ptr(), dur.data_ptr(), w.B, w.T, w.K, w.C, 0,
+                                  sb.SEMICRF_EMIS_F16 | sb.SEMICRF_EMIS_BF16, 4096, 1 << 30, lz.data_ptr(), None)
+        sb._check(rc)
+    assert ei.value.status == -1
