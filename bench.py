@@ -83,11 +83,7 @@ def main():
            torch.empty((K, C), dtype=torch.float32, device=dev),
            torch.empty((B, T, C), dtype=torch.float32, device=dev))
     if args.boundary_terms:
-        import numpy as np
-        rng = np.random.default_rng(12345)
-        f32 = lambda a: torch.from_numpy(a.astype(np.float32)).to(dev)
-        ps, pe = f32(0.5 * rng.standard_normal((B, T, C))), f32(0.5 * rng.standard_normal((B, T, C)))
-        pis, pie = f32(rng.standard_normal(C)), f32(rng.standard_normal(C))
+        ps, pe, pis, pie = (torch.from_numpy(a).to(dev) for a in synth.boundary_terms(w))
         call = lambda: sb.semicrf_fwd_bwd_boundary(emis, lengths, trans, dur, None, ps, pe, pis, pie,
                                                    args.ckpt_interval, workspace=ws)
         for _ in range(args.warmup):

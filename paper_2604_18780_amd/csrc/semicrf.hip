@@ -1,8 +1,8 @@
 // Streaming semi-Markov CRF forward-backward for gfx950 (MI355X).
 //
 // Numerical design.  The paper runs the recurrences of Algorithm 1 / Algorithm 3
-// in the log domain in fp32 and renormalises at checkpoints.  CDNA issues fp64
-// FMA at the same rate as unpacked fp32 FMA, so here the recurrences run in the
+// in the log domain in fp32 and renormalises at checkpoints.  CDNA has a full
+// fp64 vector pipeline (half the fp32 FMA rate), so here the recurrences run in the
 // LINEAR (probability) domain in fp64 with explicit power-of-two scaling; there
 // is no exp/log inside any scan.  With a = exp(alpha), the factorised form of
 // Eq. 4 (the transition does not depend on k, the rest not on the source label)

@@ -137,3 +137,15 @@ def small_random(seed: int, B: int, T: int, K: int, C: int, ragged: bool = True,
     dur = (0.3 * rng.standard_normal((K, C))).astype(np.float32)
     emis = (scale * rng.standard_normal((B, T, C))).astype(np.float32)
     return Workload(f"rand{seed}", emis, lengths, trans, dur, B, T, K, C)
+
+
+def boundary_terms(w: Workload, seed: int = 12345, scale: float = 0.5):
+    """Seeded stand-ins for the optional boundary terms of Eq. 4: start / end projections
+    ~ N(0, scale^2) of shape [B,T,C] and scalar sequence boundaries ~ N(0, 1) of shape [C]
+    (float32; draw order: proj_start, proj_end, pi_start, pi_end)."""
+    rng = np.random.default_rng(seed)
+    ps = (scale * rng.standard_normal((w.B, w.T, w.C))).astype(np.float32)
+    pe = (scale * rng.standard_normal((w.B, w.T, w.C))).astype(np.float32)
+    pis = rng.standard_normal(w.C).astype(np.float32)
+    pie = rng.standard_normal(w.C).astype(np.float32)
+    return ps, pe, pis, pie

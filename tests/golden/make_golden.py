@@ -8,6 +8,10 @@ per-position outputs at a fixed random sample of (sequence, position) rows:
 
     python tests/golden/make_golden.py speech genomic longgen
 
+With ``--boundary`` after a name (``genomic --boundary``) the same is done with the seeded
+boundary terms of ``synth.boundary_terms`` and the file is full_<name>_boundary.npz, which also
+holds the gradients of those terms and the boundary posterior at the sampled rows.
+
 Output: tests/golden/full_<name>.npz (float64 arrays, a few hundred KB each).
 """
 import os
@@ -22,7 +26,7 @@ sys.path.insert(0, ROOT)
 import oracle  # noqa: E402
 from paper_2604_18780_amd import synth  # noqa: E402
 
-NSAMPLE = 4096
+NSAMPLE = 1024
 
 
 def sample_rows(w, seed=12345):
@@ -39,20 +43,35 @@ def sample_rows(w, seed=12345):
     return np.concatenate(rows, 0)
 
 
-def main(names):
+def main(args):
+    names = [a for a in args if not a.startswith("--")]
+    boundary = "--boundary" in args
     for name in names:
         w = synth.make(name)
         t0 = time.time()
-        r = oracle.fwd_bwd(w.emis, w.lengths, w.trans, w.dur)
+        extra = {}
+        if boundary:
+            ps, pe, pis, pie = synth.boundary_terms(w)
+            r = oracle.fwd_bwd(w.emis, w.lengths, w.trans, w.dur, proj_start=ps, proj_end=pe, pi_start=pis,
+                               pi_end=pie)
+        else:
+            r = oracle.fwd_bwd(w.emis, w.lengths, w.trans, w.dur)
         dt = time.time() - t0
         rows = sample_rows(w)
-        out = os.path.join(os.path.dirname(os.path.abspath(__file__)), f"full_{name}.npz")
+        if boundary:
+            extra = dict(grad_proj_start_rows=r.grad_proj_start[rows[:, 0], rows[:, 1]],
+                         grad_proj_end_rows=r.grad_proj_end[rows[:, 0], rows[:, 1]],
+                         bdy_post_rows=r.bdy_post[rows[:, 0], rows[:, 1]],
+                         grad_pi_start=r.grad_pi_start, grad_pi_end=r.grad_pi_end,
+                         bdy_post_total=np.array([r.bdy_post.sum()]))
+        out = os.path.join(os.path.dirname(os.path.abspath(__file__)),
+                           f"full_{name}{'_boundary' if boundary else ''}.npz")
         np.savez_compressed(
             out, logz=r.logz, grad_trans=r.grad_trans, grad_dur=r.grad_dur, rows=rows,
             pos_marg_rows=r.pos_marg[rows[:, 0], rows[:, 1]],
             grad_emis_rows=r.grad_emis[rows[:, 0], rows[:, 1]],
             pos_marg_total=np.array([r.pos_marg.sum()]),
-            oracle_seconds=np.array([dt]), oracle_threads=np.array([r.threads]))
+            oracle_seconds=np.array([dt]), oracle_threads=np.array([r.threads]), **extra)
         print(f"{name}: oracle {dt:.1f}s on {r.threads} threads -> {out}", flush=True)
 
 

@@ -144,3 +144,39 @@ def test_entropies_of_the_posteriors():
                                      dev(w1.dur))
     _, hb = sb.semicrf_entropies(o1["pos_marg"], o1["bdy_post"], dev(w1.lengths, np.int32))
     assert np.abs(hb.double().cpu().numpy() - np.log(w1.lengths)).max() <= 1e-5
+
+
+def test_full_size_genomic_with_boundary_terms_against_stored_oracle_values():
+    """The genomic workload at full size with the seeded boundary terms of synth.boundary_terms,
+    as `bench.py --boundary-terms` runs it, against oracle values stored by
+    tests/golden/make_golden.py (which calls only oracle/): everything accumulated in full,
+    per-position outputs at the sampled rows, and properties over all rows."""
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "full_genomic_boundary.npz")
+    if not os.path.exists(path):
+        pytest.skip(f"{path} not generated")
+    g = np.load(path)
+    w = synth.make("genomic")
+    ps, pe, pis, pie = synth.boundary_terms(w)
+    lengths = dev(w.lengths, np.int32)
+    out = sb.semicrf_fwd_bwd_boundary(dev(w.emis), lengths, dev(w.trans), dev(w.dur), None,
+                                      dev(ps), dev(pe), dev(pis), dev(pie))
+    torch.cuda.synchronize()
+    lz = out["logz"].double().cpu().numpy()
+    assert (np.abs(lz - g["logz"]) / np.abs(g["logz"])).max() <= 1e-5
+    rows = g["rows"]
+    rb, ru = torch.from_numpy(rows[:, 0]).to(DEV), torch.from_numpy(rows[:, 1]).to(DEV)
+    for name in ("pos_marg", "grad_emis", "grad_proj_start", "grad_proj_end", "bdy_post"):
+        err = np.abs(out[name][rb, ru].double().cpu().numpy() - g[name + "_rows"]).max()
+        print(f"       {name} max err at {len(rows)} sampled rows {err:.2e}", flush=True)
+        assert err <= 1e-4, (name, err)
+    for name in ("grad_trans", "grad_dur", "grad_pi_start", "grad_pi_end"):
+        err = np.abs(out[name].double().cpu().numpy() - g[name]).max()
+        assert err <= 1e-4 * max(1.0, np.abs(g[name]).max()), (name, err)
+    # over all rows: one start and one end per segment; boundary mass = segments + sequences
+    nseg = out["grad_dur"].double().sum().item()
+    assert abs(out["grad_proj_start"].double().sum().item() - nseg) <= 1e-5 * nseg
+    assert abs(out["grad_proj_end"].double().sum().item() - nseg) <= 1e-5 * nseg
+    assert abs(out["bdy_post"].double().sum().item() - float(g["bdy_post_total"][0])) <= 1e-5 * nseg
+    assert abs(out["bdy_post"].double().sum().item() - (nseg + w.B)) <= 1e-5 * nseg
+    assert out["bdy_post"].min().item() >= 0.0 and out["bdy_post"].max().item() <= 1.0 + 1e-6

@@ -220,7 +220,7 @@ def test_more_than_64_labels_forward_only():
 
 def test_more_tasks_than_buffer_slots():
     """An explicit interval of 2 positions gives 2250 (sequence, interval) tasks, more than the
-    2048 task buffers: the interval kernel then loops over tasks and recomputes its forward rows
+    1024 task buffers: the interval kernel then loops over tasks and recomputes its forward rows
     instead of taking them from the chunk-parallel scan."""
     w = synth.small_random(91, 3, 1500, 6, 5, ragged=True)
     w.lengths[:] = [1500, 1500, 1497]
