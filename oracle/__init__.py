@@ -51,6 +51,8 @@ def _load():
         lib.semicrf_oracle_fwd_bwd_boundary.restype = ctypes.c_int
         lib.semicrf_oracle_fwd_bwd_boundary.argtypes = ([dp, ip, dp, dp, dp] + [dp] * 4 + [ctypes.c_int] * 6
                                                         + [dp] * 16)
+        lib.semicrf_oracle_viterbi.restype = ctypes.c_int
+        lib.semicrf_oracle_viterbi.argtypes = [dp, ip, dp, dp] + [dp] * 4 + [ctypes.c_int] * 6 + [dp, ip, ip, ip]
         lib.semicrf_oracle_logz_boundary.restype = ctypes.c_int
         lib.semicrf_oracle_logz_boundary.argtypes = [dp, ip, dp, dp] + [dp] * 4 + [ctypes.c_int] * 6 + [dp]
         _lib = lib
@@ -201,4 +203,67 @@ def entropies(pos_marg, bdy_post, lengths):
         safe = np.where(ph > 0, ph, 1.0)
         h_bdy[b] = -(ph * np.log(safe)).sum()
     return h_pos, h_bdy
+
+
+def viterbi(emis, lengths, trans, dur, center=True, threads=0, proj_start=None, proj_end=None,
+            pi_start=None, pi_end=None):
+    """Best segmentation (max semiring).  Returns (score [B], labels [B,T] int32 with -1 beyond
+    the sequence, starts [B,T] int32: 1 on the first token of every segment, nseg [B])."""
+    lib = _load()
+    emis = _as_f64(emis)
+    B, T, C = emis.shape
+    trans = _as_f64(trans)
+    dur = _as_f64(dur)
+    K = dur.shape[0]
+    lp = None
+    if lengths is not None:
+        lengths = np.ascontiguousarray(np.asarray(lengths), dtype=np.int32)
+        lp = lengths.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    opt = [None if a is None else _as_f64(a) for a in (proj_start, proj_end, pi_start, pi_end)]
+    score = np.zeros(B)
+    labels = np.zeros((B, T), dtype=np.int32)
+    starts = np.zeros((B, T), dtype=np.int32)
+    nseg = np.zeros(B, dtype=np.int32)
+    i32 = lambda a: a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    rc = lib.semicrf_oracle_viterbi(_dptr(emis), lp, _dptr(trans), _dptr(dur), *[_dptr(a) for a in opt],
+                                    B, T, K, C, int(bool(center)), int(threads), _dptr(score), i32(labels),
+                                    i32(starts), i32(nseg))
+    if rc < 0:
+        raise ValueError("semicrf_oracle_viterbi: bad arguments")
+    return score, labels, starts, nseg
+
+
+def path_score(emis, L, trans, dur, labels, starts, center=True, proj_start=None, proj_end=None,
+               pi_start=None, pi_end=None):
+    """Score of ONE given segmentation of one sequence (emis [T,C], first L tokens), written out
+    from the definition of the edge potential: the sum over its segments [s, s+k) with label c of
+    the centred content, the duration bias, the transition from the previous segment's label (for
+    the first segment: the best source label, since every initial label has score 0), and the
+    boundary terms.  Independent of the dynamic programme; used to validate decoded paths."""
+    emis = _as_f64(emis)
+    T, C = emis.shape
+    trans = _as_f64(trans)
+    dur = _as_f64(dur)
+    nu = emis[:L].mean(0) if (center and L > 0) else np.zeros(C)
+    bounds = [u for u in range(L) if starts[u]] + [L]
+    if L > 0:
+        assert bounds[0] == 0, "the first token must start a segment"
+    total = 0.0
+    prev = None
+    for s, e in zip(bounds[:-1], bounds[1:]):
+        c = int(labels[s])
+        k = e - s
+        assert 1 <= k <= dur.shape[0] and all(int(labels[u]) == c for u in range(s, e))
+        total += (emis[s:e, c] - nu[c]).sum() + dur[k - 1, c]
+        total += trans[:, c].max() if prev is None else trans[prev, c]
+        if proj_start is not None:
+            total += proj_start[s, c]
+        if proj_end is not None:
+            total += proj_end[e - 1, c]
+        if pi_start is not None and s == 0:
+            total += pi_start[c]
+        if pi_end is not None and e == L:
+            total += pi_end[c]
+        prev = c
+    return total
 

@@ -417,3 +417,81 @@ int semicrf_oracle_logz(const double *emis, const int32_t *lengths,
     return semicrf_oracle_logz_boundary(emis, lengths, trans, dur, NULL, NULL, NULL, NULL,
                                         B, T, K, C, center, threads, logz);
 }
+
+/*
+ * Viterbi decode (max semiring): the best-scoring segmentation under the same edge
+ * potential psi of Eq. 4, with the same conventions as the sum recurrence (V[0,c] = 0 for
+ * every label, so the first segment pays max_c' trans[c',c]; no end term).
+ *     V[t,c] = max_{k <= min(K,t)} max_{c'} ( V[t-k,c'] + psi(t,k,c,c') ),   score = max_c V[L,c]
+ * Full tables, (duration, source label) back-pointers, ties broken towards the smallest k, then
+ * the smallest c' (strict ">" in scan order), final label = smallest argmax.  Outputs per
+ * sequence: score; per token its segment's label and a flag that is 1 on the first token of a
+ * segment (tokens beyond L: label -1, flag 0); the number of segments.
+ */
+int semicrf_oracle_viterbi(const double *emis, const int32_t *lengths,
+                           const double *trans, const double *dur,
+                           const double *proj_start, const double *proj_end,
+                           const double *pi_start, const double *pi_end,
+                           int B, int T, int K, int C, int center, int threads,
+                           double *score, int32_t *labels, int32_t *starts, int32_t *nseg)
+{
+    if (B < 1 || T < 1 || K < 1 || C < 1) return -1;
+    int nthreads = 1;
+#ifdef _OPENMP
+    nthreads = threads > 0 ? threads : omp_get_max_threads();
+#endif
+    int outer = B < nthreads ? B : nthreads;
+#pragma omp parallel for num_threads(outer) schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        int L = lengths ? lengths[b] : T;
+        if (L < 0) L = 0;
+        if (L > T) L = T;
+        const double *f = emis + (size_t)T * C * b;
+        size_t n1 = (size_t)(L + 1) * C;
+        double *nu = (double *)calloc((size_t)C, sizeof(double));
+        double *S = (double *)calloc(n1, sizeof(double));
+        double *V = (double *)malloc(n1 * sizeof(double));
+        int32_t *bk = (int32_t *)calloc(n1, sizeof(int32_t));   /* best duration */
+        int32_t *bc = (int32_t *)calloc(n1, sizeof(int32_t));   /* best source label */
+        double *bs, *be;
+        oracle_boundary_scores(proj_start ? proj_start + (size_t)T * C * b : NULL,
+                               proj_end ? proj_end + (size_t)T * C * b : NULL, pi_start, pi_end, L, C, &bs, &be);
+        oracle_prefix_sums(f, L, C, center, nu, S);
+        for (int c = 0; c < C; ++c) V[c] = 0.0;
+        for (int t = 1; t <= L; ++t) {
+            int kmax = K < t ? K : t;
+            for (int c = 0; c < C; ++c) {
+                double best = -INFINITY;
+                int kb = 0, cb = 0;
+                for (int k = 1; k <= kmax; ++k)
+                    for (int cp = 0; cp < C; ++cp) {
+                        double x = V[(size_t)(t - k) * C + cp] + PSI(t, k, c, cp);
+                        if (x > best) { best = x; kb = k; cb = cp; }
+                    }
+                V[(size_t)t * C + c] = best;
+                bk[(size_t)t * C + c] = kb;
+                bc[(size_t)t * C + c] = cb;
+            }
+        }
+        int32_t *lab = labels + (size_t)T * b, *st = starts + (size_t)T * b;
+        for (int u = 0; u < T; ++u) { lab[u] = -1; st[u] = 0; }
+        int c = 0;
+        double best = -INFINITY;
+        for (int cc = 0; cc < C; ++cc)
+            if (V[(size_t)L * C + cc] > best) { best = V[(size_t)L * C + cc]; c = cc; }
+        score[b] = L > 0 ? best : 0.0;
+        int ns = 0, t = L;
+        while (t > 0) {
+            int k = bk[(size_t)t * C + c], cp = bc[(size_t)t * C + c];
+            for (int u = t - k; u < t; ++u) lab[u] = c;
+            st[t - k] = 1;
+            ++ns;
+            t -= k;
+            c = cp;
+        }
+        nseg[b] = ns;
+        free(nu); free(S); free(V); free(bk); free(bc); free(bs); free(be);
+    }
+    return outer;
+}
+

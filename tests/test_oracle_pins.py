@@ -581,3 +581,88 @@ def test_entropies_closed_forms():
     hp = (math.log(2) + 0.0 - 0.25 * math.log(0.25) - 0.75 * math.log(0.75)) / 3
     ph = np.array([0.5, 0.25, 0.25])
     assert abs(h_pos[0] - hp) < 1e-12 and abs(h_bdy[0] + (ph * np.log(ph)).sum()) < 1e-12
+
+
+# --------------------------------------------------------------------------
+# P12  Viterbi decode (max semiring)
+# --------------------------------------------------------------------------
+def brute_force_best(emis, L, trans, dur, ps, pe, pis, pie, center):
+    """Maximum over every segmentation and labelling, by enumeration (scores as in P11)."""
+    T, C = emis.shape
+    K = dur.shape[0]
+    nu = emis[:L].mean(0) if (center and L > 0) else np.zeros(C)
+    fbar = emis - nu
+    best = -np.inf
+    for comp in compositions(L, K):
+        for c0 in range(C):
+            for labs in itertools.product(range(C), repeat=len(comp)):
+                score, prev, s = 0.0, c0, 0
+                for k, c in zip(comp, labs):
+                    score += trans[prev, c] + dur[k - 1, c] + fbar[s:s + k, c].sum() + ps[s, c] + pe[s + k - 1, c]
+                    if s == 0:
+                        score += pis[c]
+                    if s + k == L:
+                        score += pie[c]
+                    prev, s = c, s + k
+                best = max(best, score)
+    return best
+
+
+@pytest.mark.parametrize("T,K,C,center,bt", [(5, 3, 2, True, True), (6, 4, 2, False, False), (4, 2, 3, True, True),
+                                             (7, 7, 2, True, False), (5, 1, 3, True, True)])
+def test_viterbi_against_enumeration(T, K, C, center, bt):
+    rng = np.random.default_rng(900 + T * 10 + K)
+    emis, _, trans, dur = rand_case(700 + T * 10 + K, 1, T, K, C)
+    z = np.zeros((1, T, C))
+    ps, pe = (rng.standard_normal((1, T, C)), rng.standard_normal((1, T, C))) if bt else (z, z)
+    pis, pie = (rng.standard_normal(C), rng.standard_normal(C)) if bt else (np.zeros(C), np.zeros(C))
+    score, labels, starts, nseg = oracle.viterbi(emis, None, trans, dur, center=center, proj_start=ps, proj_end=pe,
+                                                 pi_start=pis, pi_end=pie)
+    best = brute_force_best(emis[0], T, trans, dur, ps[0], pe[0], pis, pie, center)
+    assert abs(score[0] - best) < 1e-12 * max(1, abs(best))
+    # the decoded path is a valid segmentation and achieves the reported score
+    got = oracle.path_score(emis[0], T, trans, dur, labels[0], starts[0], center=center, proj_start=ps[0],
+                            proj_end=pe[0], pi_start=pis, pi_end=pie)
+    assert abs(got - score[0]) < 1e-10
+    assert nseg[0] == starts[0].sum()
+
+
+def test_viterbi_k1_is_the_textbook_chain_decoder():
+    T, C = 150, 5
+    emis, _, trans, dur = rand_case(19, 1, T, 1, C)
+    score, labels, starts, nseg = oracle.viterbi(emis, None, trans, dur, center=True)
+    fbar = emis[0] - emis[0].mean(0)
+    v = np.zeros(C)
+    back = np.zeros((T, C), dtype=int)
+    for t in range(T):
+        cand = v[:, None] + trans                      # [source, destination]
+        back[t] = cand.argmax(0)
+        v = cand.max(0) + fbar[t] + dur[0]
+    assert abs(score[0] - v.max()) < 1e-9
+    path = np.zeros(T, dtype=int)
+    c = int(v.argmax())
+    for t in range(T - 1, -1, -1):
+        path[t] = c
+        c = back[t, c]
+    assert np.array_equal(labels[0], path) and np.all(starts[0] == 1) and nseg[0] == T
+
+
+def test_viterbi_ragged_bounds_and_zero_temperature_limit():
+    emis, lengths, trans, dur = rand_case(20, 3, 25, 5, 3, ragged=True)
+    lengths[2] = 0
+    score, labels, starts, nseg = oracle.viterbi(emis, lengths, trans, dur)
+    lz = oracle.logz(emis, lengths, trans, dur)
+    for b in range(3):
+        L = int(lengths[b])
+        assert np.all(labels[b, L:] == -1) and np.all(starts[b, L:] == 0)
+        if L == 0:
+            assert score[b] == 0.0 and nseg[b] == 0
+            continue
+        assert score[b] <= lz[b] + 1e-12                               # one path among those summed
+        got = oracle.path_score(emis[b], L, trans, dur, labels[b], starts[b])
+        assert abs(got - score[b]) < 1e-10
+    # potentials scaled by a large factor: logZ / factor tends to the best score (centring is linear in emis)
+    fac = 200.0
+    lz_hot = oracle.logz(fac * emis, lengths, fac * trans, fac * dur)
+    for b in range(2):
+        assert abs(lz_hot[b] / fac - score[b]) < 0.2
