@@ -54,6 +54,8 @@ def main():
     ap.add_argument("--boundary-terms", action="store_true",
                     help="time semicrf_fwd_bwd_boundary with start/end projections, scalar boundaries and all "
                          "their outputs instead (whole-call time only; prints its own JSON line)")
+    ap.add_argument("--viterbi", action="store_true",
+                    help="time semicrf_viterbi (max-semiring decode + trace-back) instead; prints its own JSON line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy so that a rocprofv3 --pmc run of this "
                          "command holds a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
@@ -82,6 +84,26 @@ def main():
            torch.empty((C, C), dtype=torch.float32, device=dev),
            torch.empty((K, C), dtype=torch.float32, device=dev),
            torch.empty((B, T, C), dtype=torch.float32, device=dev))
+    if args.viterbi:
+        call = lambda: sb.semicrf_viterbi(emis, lengths, trans, dur)
+        for _ in range(args.warmup):
+            o = call()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            o = call()
+        torch.cuda.synchronize()
+        ms = 1e3 * (time.perf_counter() - t0) / args.steps
+        print(json.dumps({
+            "metric": "semi-CRF Viterbi decode, edge evals/sec (B*T*K*C^2/s)",
+            "value": w.nominal_edges / (ms * 1e-3), "unit": "edge evals/s",
+            "positions_per_s": w.positions / (ms * 1e-3), "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+            "config": {"workload": f"{w.name}: B={B} T={T} K={K} C={C} (workspace and outputs allocated inside "
+                                   f"the timed calls)"},
+            "score_mean": float(o[0].double().mean().item()), "segments": int(o[3].sum().item())}))
+        return
     if args.boundary_terms:
         ps, pe, pis, pie = (torch.from_numpy(a).to(dev) for a in synth.boundary_terms(w))
         call = lambda: sb.semicrf_fwd_bwd_boundary(emis, lengths, trans, dur, None, ps, pe, pis, pie,

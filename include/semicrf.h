@@ -176,6 +176,29 @@ int semicrf_fwd_bwd_boundary(const float *emis, const int32_t *lengths, const fl
                              float *grad_pi_start, float *grad_pi_end, float *bdy_post, void *stream);
 
 /*
+ * Viterbi decode (the max-semiring counterpart of Algorithm 1; the paper's inference path):
+ * the best-scoring segmentation under the edge potential of Eq. 4, boundary terms included
+ * (each of the four may be NULL).  Same conventions as the sum: every initial label has score
+ * 0, so the first segment pays max_c' trans[c',c]; no end term.
+ *   score  [B]   float  score of the best segmentation (0 for an empty sequence)
+ *   labels [B,T] int32  label of the segment that covers token u; -1 for u >= L_b
+ *   starts [B,T] int32  1 on the first token of every segment, else 0 (0 for u >= L_b)
+ *   nseg   [B]   int32  number of segments
+ * Among equally good segmentations the last segment's label is the smallest, and going
+ * backwards each segment takes the smallest duration, then the smallest predecessor label,
+ * among the maximisers; since sums are rounded, "equally good" means equal in fp64.
+ * Supported sizes: C <= 64 and K <= 64 * (64 / (C rounded up to 8/16/32/64)).  Workspace:
+ * semicrf_viterbi_workspace_bytes (O(T*C): prefix arrays plus two doubles per position and label).
+ */
+int semicrf_viterbi_workspace_bytes(int B, int T, int K, int C, size_t *bytes);
+
+int semicrf_viterbi(const float *emis, const int32_t *lengths, const float *trans, const float *dur,
+                    const float *proj_start, const float *proj_end, const float *pi_start,
+                    const float *pi_end, int B, int T, int K, int C, unsigned flags, void *workspace,
+                    size_t workspace_bytes, float *score, int32_t *labels, int32_t *starts, int32_t *nseg,
+                    void *stream);
+
+/*
  * The two entropies of the paper's boundary-entropy paragraph, from outputs of the calls above
  * (device pointers; needs no workspace):
  *   h_pos [B] float or NULL: mean over the L_b tokens of -sum_c pos_marg[b,u,c] ln pos_marg[b,u,c]

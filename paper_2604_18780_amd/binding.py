@@ -18,7 +18,8 @@ LIB_PATH = os.path.join(_HERE, "libsemicrf.so")
 EXPORTS = ("semicrf_version", "semicrf_strerror", "semicrf_workspace_bytes",
            "semicrf_cum_scores", "semicrf_logz_fwd", "semicrf_fwd_bwd", "semicrf_fwd_bwd_profiled",
            "semicrf_scan_report", "semicrf_ckpt_interval", "semicrf_logz_fwd_boundary",
-           "semicrf_fwd_bwd_boundary", "semicrf_entropies")
+           "semicrf_fwd_bwd_boundary", "semicrf_entropies", "semicrf_viterbi_workspace_bytes",
+           "semicrf_viterbi")
 SEMICRF_CENTER = 1
 SEMICRF_SEQUENTIAL_SCAN = 2
 SEMICRF_EMIS_F16 = 4
@@ -64,6 +65,10 @@ def load():
     lib.semicrf_logz_fwd_boundary.argtypes = [vp] * 8 + [ci, ci, ci, ci, ci, cu, vp, sz, vp, vp]
     lib.semicrf_fwd_bwd_boundary.restype = ci
     lib.semicrf_fwd_bwd_boundary.argtypes = [vp] * 9 + [ci, ci, ci, ci, ci, cu, vp, sz] + [vp] * 11
+    lib.semicrf_viterbi_workspace_bytes.restype = ci
+    lib.semicrf_viterbi_workspace_bytes.argtypes = [ci, ci, ci, ci, ctypes.POINTER(sz)]
+    lib.semicrf_viterbi.restype = ci
+    lib.semicrf_viterbi.argtypes = [vp] * 8 + [ci, ci, ci, ci, cu, vp, sz] + [vp] * 5
     lib.semicrf_entropies.restype = ci
     lib.semicrf_entropies.argtypes = [vp, vp, vp, ci, ci, ci, vp, vp, vp]
     lib.semicrf_scan_report.restype = ci
@@ -223,6 +228,36 @@ def semicrf_fwd_bwd_boundary(emis, lengths, trans, dur, grad_logz=None, proj_sta
                                                                  "grad_pi_start", "grad_pi_end", "bdy_post")],
                                            _stream()))
     return o
+
+
+def semicrf_viterbi_workspace_bytes(B, T, K, C) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().semicrf_viterbi_workspace_bytes(B, T, K, C, ctypes.byref(out)))
+    return out.value
+
+
+def semicrf_viterbi(emis, lengths, trans, dur, proj_start=None, proj_end=None, pi_start=None, pi_end=None,
+                    flags=SEMICRF_CENTER, workspace=None):
+    """Returns (score [B] float32, labels [B,T] int32, starts [B,T] int32, nseg [B] int32)."""
+    B, T, C = emis.shape
+    K = dur.shape[0]
+    dev = emis.device
+    if workspace is None:
+        n = semicrf_viterbi_workspace_bytes(B, T, K, C)
+        ws = torch.empty(n + 256, dtype=torch.uint8, device=dev)
+        off = (-ws.data_ptr()) % 256
+        workspace = ws[off:off + n]
+    f32 = torch.float32
+    score = torch.empty(B, dtype=f32, device=dev)
+    labels = torch.empty((B, T), dtype=torch.int32, device=dev)
+    starts = torch.empty((B, T), dtype=torch.int32, device=dev)
+    nseg = torch.empty(B, dtype=torch.int32, device=dev)
+    ep, flags = _emis(emis, flags)
+    _check(load().semicrf_viterbi(ep, _ptr(lengths, torch.int32), _ptr(trans, f32), _ptr(dur, f32),
+                                  _ptr(proj_start, f32), _ptr(proj_end, f32), _ptr(pi_start, f32), _ptr(pi_end, f32),
+                                  B, T, K, C, flags, workspace.data_ptr(), workspace.numel(), score.data_ptr(),
+                                  labels.data_ptr(), starts.data_ptr(), nseg.data_ptr(), _stream()))
+    return score, labels, starts, nseg
 
 
 def semicrf_entropies(pos_marg, bdy_post, lengths):

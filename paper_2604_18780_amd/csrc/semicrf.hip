@@ -105,6 +105,11 @@ struct Params {
     double *spec_lr;    // [B][2][N+1]
     double *spec_err;   // [B][2][N+1]
     int *spec_ok;       // [B][2]  1: the chunk-parallel scan of (sequence, direction) was accepted
+    int logpair;        // k_prefix stores the log-domain pair (S + end score, start score - S): Viterbi
+    double2 *vr;        // [B][T+1][C] Viterbi: (V_t(c), r_t(c)) = best score arriving at / leaving position t
+    int *vbest;         // [B] Viterbi: label of the last segment
+    float *vscore;      // Viterbi outputs
+    int32_t *vlabels, *vstarts, *vnseg;
     int spec;           // chunk-parallel scan enabled for this call
     int fuse;           // its forward tasks also store the interval stage's forward rows (one slot per task)
     double *aloc;       // [nslot][Delta][2C]
@@ -387,7 +392,8 @@ __global__ __launch_bounds__(NT) void k_prefix(Params p)
                         if (p.proj_end) xe = (double)p.proj_end[((size_t)b * p.T + t - 1) * C + c];
                         if (t == L && p.pi_end) xe += (double)p.pi_end[c];
                     }
-                    pr = make_double2(exp(x + xe), exp(xs - x));
+                    // max semiring: the same pair in the log domain, (S + end score, start score - S)
+                    pr = p.logpair ? make_double2(S + xe, xs - S) : make_double2(exp(x + xe), exp(xs - x));
                 }
                 p.EI[(row0 + t) * C + c] = pr;
                 if (p.cum) p.cum[(row0 + t) * C + c] = S;
@@ -2220,6 +2226,250 @@ __global__ void k_spec_report(Params p, int32_t *accepted, double *mismatch)
 }
 
 // ---------------------------------------------------------------------------
+// Viterbi decode (max semiring) with the window / time-block organisation of the one-wave
+// kernels, in the log domain (fp64 additions and maxima only; nothing needs rescaling):
+//     r_s(c) = max_c' (V_s(c') + trans[c',c]) + (start score of token s) - S[s,c]        (leaves s)
+//     V_t(c) = S[t,c] + (end score of token t-1) + max_k (dur[k,c] + r_{t-k}(c))          (arrives at t)
+// V_0 = 0 for every label.  One wave per sequence walks the positions in order and stores
+// (V_t, r_t) for every position and label; no back-pointers are kept.  The trace-back
+// (k_vit_trace) finds each segment's duration and predecessor label by recomputing the
+// candidates from the stored values: the same additions as in the scan, so the maxima are
+// bit-identical.  Ties go to the smallest duration, then the smallest label.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ double max_across_32(double v)
+{
+    const unsigned lo = (unsigned)__double2loint(v), hi = (unsigned)__double2hiint(v);
+    const auto a = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
+    const auto b = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
+    return fmax(__hiloint2double((int)b[0], (int)a[0]), __hiloint2double((int)b[1], (int)a[1]));
+}
+
+__device__ __forceinline__ double max_across_16(double v)
+{
+    const unsigned lo = (unsigned)__double2loint(v), hi = (unsigned)__double2hiint(v);
+    const auto a = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
+    const auto b = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
+    return fmax(__hiloint2double((int)b[0], (int)a[0]), __hiloint2double((int)b[1], (int)a[1]));
+}
+
+__device__ __forceinline__ double max_across_8(double v)
+{
+    const int lo = __double2loint(v), hi = __double2hiint(v);
+    const int lo2 = __builtin_amdgcn_update_dpp(0, lo, 0x128, 0xf, 0xf, false);
+    const int hi2 = __builtin_amdgcn_update_dpp(0, hi, 0x128, 0xf, 0xf, false);
+    return fmax(v, __hiloint2double(hi2, lo2));
+}
+
+// max over the 64/CTP lanes of a wave that share lane % CTP; every lane gets the result
+template <int CTP>
+__device__ __forceinline__ double group_max(double v)
+{
+    if (CTP <= 8) v = max_across_8(v);
+    if (CTP <= 16) v = max_across_16(v);
+    if (CTP <= 32) v = max_across_32(v);
+    return v;
+}
+
+template <int CT, int NKW>
+__global__ __launch_bounds__(64) void k_viterbi(Params p)
+{
+    using G = WaveWin<CT, NKW>;
+    constexpr int CTP = G::CTP, RS = G::RS, NK = G::NK, KW = G::KW, ROWS = G::ROWS;
+    constexpr int RTOT = G::RTOT, H = G::H, HC = G::HC;
+    extern __shared__ double lds_raw[];
+    const int lane = threadIdx.x, b = blockIdx.x;
+    const int K = p.K, C = p.C;
+    double *ring = lds_raw;          // [ROWS][RS] (+ pad): r of the last KW positions
+    double *yv = ring + RTOT;        // [CTP]: V of the current position
+    const int c = lane % CTP, g = lane / CTP;
+    const int hh = H == 2 ? (lane >> 5) : 0;
+    const bool cval = c < C;
+    const int cc = cval ? c : 0;
+    const bool writer = cval && g == 0;
+    const int L = p.hdr[b].L;
+    const size_t row0 = (size_t)b * (p.T + 1);
+    const double2 *LPc = p.EI + row0 * C + cc;  // (S + end score, start score - S)
+    double2 *VR = p.vr + row0 * C;
+    const double NINF = -INFINITY;
+
+    double wd[NK + MB - 1];  // dur[g*NK + jj, c] (duration g*NK + jj + 1)
+#pragma unroll
+    for (int jj = 0; jj < NK + MB - 1; ++jj) {
+        const int k = g * NK + jj + 1;
+        wd[jj] = (cval && k <= K) ? (double)p.dur[(size_t)(k - 1) * C + c] : NINF;
+    }
+    double wn[MB - 1];
+#pragma unroll
+    for (int jj = 0; jj < MB - 1; ++jj) wn[jj] = (cval && jj + 1 <= K) ? (double)p.dur[(size_t)jj * C + c] : NINF;
+    double Treg[HC];         // trans[o, c] for the lane's half of the source labels
+#pragma unroll
+    for (int i = 0; i < HC; ++i) {
+        const int o = hh * HC + i;
+        Treg[i] = (cval && o < C) ? (double)p.trans[(size_t)o * C + c] : NINF;
+    }
+    const double2 *ys = (const double2 *)__builtin_assume_aligned(yv + hh * HC, 16);
+
+    for (int i = lane; i < RTOT; i += 64) ring[i] = NINF;
+    if (lane < CTP) yv[lane] = lane < C ? 0.0 : NINF;  // V_0 = 0 for every label
+    lds_wave_fence();
+    int r = KW - 1;
+    auto leave = [&]() {  // max_o (V(o) + trans[o,c]) from the V vector in yv
+        double m0 = NINF, m1 = NINF;
+#pragma unroll
+        for (int o = 0; o < HC; o += 2) {
+            const double2 vv = ys[o >> 1];
+            m0 = fmax(m0, vv.x + Treg[o]);
+            m1 = fmax(m1, vv.y + Treg[o + 1]);
+        }
+        double m = fmax(m0, m1);
+        if (H == 2) m = max_across_32(m);
+        return m;
+    };
+    {
+        const double q = leave() + LPc[0].y;
+        if (writer) {
+            ring[r * RS + c] = q;
+            VR[c] = make_double2(0.0, q);
+        }
+    }
+    lds_wave_fence();
+    const int rdoff = -(g * NK + NK - 1) * RS + c;
+    int t = 0;
+    auto load_rows = [&](double2 (&e)[MB], const int tfrom) {
+#pragma unroll
+        for (int i = 0; i < MB; ++i) e[i] = LPc[(size_t)min(tfrom + 1 + i, L) * C];
+    };
+    double2 e[MB];
+    load_rows(e, t);
+    while (t < L) {
+        const int nb = min(L - t, MB);
+        double2 en[MB];
+        load_rows(en, t + nb);
+        if (__builtin_expect(r + MB > ROWS - 1, 0)) r = G::template move<false>(ring, lane, r);
+        const double *base = ring + r * RS + rdoff;
+        double acc[MB];
+#pragma unroll
+        for (int i = 0; i < MB; ++i) acc[i] = NINF;
+#pragma unroll
+        for (int jj = 0; jj < NK; ++jj) {
+            const double v = base[(NK - 1 - jj) * RS];  // r of the position g*NK + jj before the newest
+#pragma unroll
+            for (int i = 0; i < MB; ++i) acc[i] = fmax(acc[i], wd[jj + i] + v);
+        }
+#pragma unroll
+        for (int i = 0; i < MB; ++i) acc[i] = group_max<CTP>(acc[i]);
+        double qn[MB];
+#pragma unroll
+        for (int i = 0; i < MB; ++i) {
+            if (i < nb) {
+                double x = acc[i];
+#pragma unroll
+                for (int jn = 0; jn < i; ++jn) x = fmax(x, wn[i - 1 - jn] + qn[jn]);
+                const double y = x + e[i].x;  // V_t(c)
+                if (cval) yv[c] = y;
+                lds_wave_fence();
+                const double q = leave() + e[i].y;
+                qn[i] = q;
+                ++r;
+                if (writer) {
+                    ring[r * RS + c] = q;
+                    VR[(size_t)(t + 1 + i) * C + c] = make_double2(y, q);
+                }
+                lds_wave_fence();
+            } else {
+                qn[i] = NINF;
+            }
+        }
+        t += nb;
+#pragma unroll
+        for (int i = 0; i < MB; ++i) e[i] = en[i];
+    }
+    // best final label (smallest on ties) and score
+    double best = cval ? yv[c] : NINF;
+    int bl = cval ? c : 0x7fffffff;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const double ov = __shfl_xor(best, off);
+        const int ol = __shfl_xor(bl, off);
+        if (ov > best || (ov == best && ol < bl)) {
+            best = ov;
+            bl = ol;
+        }
+    }
+    if (lane == 0) {
+        p.vscore[b] = L > 0 ? (float)best : 0.f;
+        p.vbest[b] = bl;
+    }
+}
+
+// Trace-back: one wave per sequence.  At (t, c): the duration is the smallest k that maximises
+// dur[k,c] + r_{t-k}(c) (lanes take k = lane+1, lane+65, ...), then the predecessor label is the
+// smallest c' that maximises V_{t-k}(c') + trans[c',c].  Writes the label of every token, a flag
+// on the first token of every segment, and the number of segments.
+__global__ __launch_bounds__(64) void k_vit_trace(Params p)
+{
+    const int lane = threadIdx.x, b = blockIdx.x;
+    const int K = p.K, C = p.C, T = p.T;
+    const int L = p.hdr[b].L;
+    const double2 *VR = p.vr + (size_t)b * (T + 1) * C;
+    int32_t *lab = p.vlabels + (size_t)b * T, *st = p.vstarts + (size_t)b * T;
+    for (int u = L + lane; u < T; u += 64) {  // beyond the sequence; every token before L is written once below
+        lab[u] = -1;
+        st[u] = 0;
+    }
+    auto wave_argmax = [&](double v, int idx, double &bv, int &bi) {
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const double ov = __shfl_xor(v, off);
+            const int oi = __shfl_xor(idx, off);
+            if (ov > v || (ov == v && oi < idx)) {
+                v = ov;
+                idx = oi;
+            }
+        }
+        bv = v;
+        bi = idx;
+    };
+    int t = L, c = p.vbest[b], nseg = 0;
+    while (t > 0) {
+        const int kmax = min(K, t);
+        double v = -INFINITY;
+        int kb = 0x7fffffff;
+        for (int k = lane + 1; k <= kmax; k += 64) {
+            const double cand = (double)p.dur[(size_t)(k - 1) * C + c] + VR[(size_t)(t - k) * C + c].y;
+            if (cand > v) {  // ascending k per lane: strict ">" keeps the smallest
+                v = cand;
+                kb = k;
+            }
+        }
+        double bv;
+        int k;
+        wave_argmax(v, kb, bv, k);
+        if (k < 1 || k > kmax) break;  // only if the scores were not finite
+        const int s = t - k;
+        double v2 = -INFINITY;
+        int cb = 0x7fffffff;
+        for (int o = lane; o < C; o += 64) {
+            const double cand = VR[(size_t)s * C + o].x + (double)p.trans[(size_t)o * C + c];
+            if (cand > v2) {
+                v2 = cand;
+                cb = o;
+            }
+        }
+        int cp;
+        wave_argmax(v2, cb, bv, cp);
+        for (int u = s + lane; u < t; u += 64) {
+            lab[u] = c;
+            st[u] = u == s ? 1 : 0;
+        }
+        ++nseg;
+        t = s;
+        c = cp;
+    }
+    if (lane == 0) p.vnseg[b] = nseg;
+}
+
+// ---------------------------------------------------------------------------
 // Finalisation (fixed-order reductions).
 // ---------------------------------------------------------------------------
 // carry[b,i,c] = sum_{i'<=i} tot[b,i',c];  mean[b,c] = (1/L) sum_u pm[b,u,c].  grid B, NT threads:
@@ -2612,7 +2862,7 @@ int launch_prep_et(const Params &p, hipStream_t st)
 {
     hipLaunchKernelGGL(k_colsum<ET>, dim3(1 + p.NCH * p.B), dim3(NT), 0, st, p);
     hipLaunchKernelGGL(k_prep_seq, dim3(p.B), dim3(NT), 0, st, p);
-    if (p.proj_start || p.proj_end || p.pi_start || p.pi_end)
+    if (p.logpair || p.proj_start || p.proj_end || p.pi_start || p.pi_end)
         hipLaunchKernelGGL((k_prefix<true, ET>), dim3(p.NCH, p.B), dim3(NT), 0, st, p);
     else
         hipLaunchKernelGGL((k_prefix<false, ET>), dim3(p.NCH, p.B), dim3(NT), 0, st, p);
@@ -2840,6 +3090,65 @@ int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hi
     return check_launch();
 }
 
+size_t viterbi_extra_bytes(int B, int T, int C)
+{
+    return align_up((size_t)B * ((size_t)T + 1) * C * sizeof(double2)) + align_up((size_t)B * sizeof(int));
+}
+
+template <int CT, int NKW>
+int launch_viterbi_k(const Params &p, hipStream_t st)
+{
+    const size_t lds = wave_lds_doubles(CT, NKW) * sizeof(double);
+    if (lds > LDS_LIMIT) return SEMICRF_EUNSUPPORTED;
+    if (hipFuncSetAttribute((const void *)k_viterbi<CT, NKW>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds) != hipSuccess)
+        return SEMICRF_ELAUNCH;
+    hipLaunchKernelGGL((k_viterbi<CT, NKW>), dim3(p.B), dim3(64), lds, st, p);
+    return check_launch();
+}
+
+template <int CT>
+int launch_viterbi_ct(const Params &p, hipStream_t st)
+{
+    constexpr int GW = 64 / pow2_ge8(CT);
+    const int per_lane = (p.K + GW - 1) / GW;
+    if (per_lane <= 16) return launch_viterbi_k<CT, 16>(p, st);
+    if (per_lane <= 32) return launch_viterbi_k<CT, 32>(p, st);
+    if (per_lane <= 64) return launch_viterbi_k<CT, 64>(p, st);
+    return SEMICRF_EUNSUPPORTED;
+}
+
+// Viterbi: prefix stage with the log-domain pair, one scan wave per sequence, trace-back.
+int run_viterbi(Params p, void *workspace, size_t workspace_bytes, hipStream_t st)
+{
+    Plan pl;
+    int rc = make_plan(p.B, p.T, p.K, p.C, 0, 0, &pl);
+    if (rc != SEMICRF_OK) return rc;
+    if (p.C > 64 || !spec_applies(p.K, p.C)) return SEMICRF_EUNSUPPORTED;
+    const size_t total = pl.total + viterbi_extra_bytes(p.B, p.T, p.C);
+    if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < total) return SEMICRF_EWORKSPACE;
+    p.Delta = pl.Delta;
+    p.N = pl.N;
+    p.NCH = pl.NCH;
+    p.nslot = pl.nslot;
+    bind_workspace(p, pl, workspace);
+    p.vr = (double2 *)((char *)workspace + pl.total);
+    p.vbest = (int *)((char *)workspace + pl.total +
+                      align_up((size_t)p.B * ((size_t)p.T + 1) * p.C * sizeof(double2)));
+    p.logpair = 1;
+    rc = launch_prep(p, st);
+    if (rc != SEMICRF_OK) return rc;
+    const int C = p.C;
+    if (C <= 8) rc = launch_viterbi_ct<8>(p, st);
+    else if (C <= 16) rc = launch_viterbi_ct<16>(p, st);
+    else if (C <= 24) rc = launch_viterbi_ct<24>(p, st);
+    else if (C <= 32) rc = launch_viterbi_ct<32>(p, st);
+    else rc = launch_viterbi_ct<64>(p, st);
+    if (rc != SEMICRF_OK) return rc;
+    hipLaunchKernelGGL(k_vit_trace, dim3(p.B), dim3(64), 0, st, p);
+    return check_launch();
+}
+
 }  // namespace
 
 extern "C" {
@@ -3011,6 +3320,35 @@ int semicrf_entropies(const float *pos_marg, const float *bdy_post, const int32_
     hipLaunchKernelGGL(k_entropies, dim3(B), dim3(NT), 0, (hipStream_t)stream, pos_marg, bdy_post, lengths, T,
                        C, h_pos, h_bdy);
     return check_launch();
+}
+
+int semicrf_viterbi_workspace_bytes(int B, int T, int K, int C, size_t *bytes)
+{
+    if (!bytes) return SEMICRF_EINVAL;
+    Plan pl;
+    int rc = make_plan(B, T, K, C, 0, 0, &pl);
+    if (rc != SEMICRF_OK) return rc;
+    if (C > 64 || !spec_applies(K, C)) return SEMICRF_EUNSUPPORTED;
+    *bytes = pl.total + viterbi_extra_bytes(B, T, C);
+    return SEMICRF_OK;
+}
+
+int semicrf_viterbi(const float *emis, const int32_t *lengths, const float *trans, const float *dur,
+                    const float *proj_start, const float *proj_end, const float *pi_start,
+                    const float *pi_end, int B, int T, int K, int C, unsigned flags, void *workspace,
+                    size_t workspace_bytes, float *score, int32_t *labels, int32_t *starts, int32_t *nseg,
+                    void *stream)
+{
+    if (!emis || !trans || !dur || !score || !labels || !starts || !nseg) return SEMICRF_EINVAL;
+    Params p = {};
+    p.emis = emis; p.lengths = lengths; p.trans = trans; p.dur = dur;
+    p.proj_start = proj_start; p.proj_end = proj_end; p.pi_start = pi_start; p.pi_end = pi_end;
+    p.B = B; p.T = T; p.K = K; p.C = C;
+    p.center = (flags & SEMICRF_CENTER) ? 1 : 0;
+    p.emis_type = (flags & SEMICRF_EMIS_F16) ? 1 : ((flags & SEMICRF_EMIS_BF16) ? 2 : 0);
+    if ((flags & SEMICRF_EMIS_F16) && (flags & SEMICRF_EMIS_BF16)) return SEMICRF_EINVAL;
+    p.vscore = score; p.vlabels = labels; p.vstarts = starts; p.vnseg = nseg;
+    return run_viterbi(p, workspace, workspace_bytes, (hipStream_t)stream);
 }
 
 int semicrf_scan_report(const void *workspace, size_t workspace_bytes, int B, int T, int K, int C,

@@ -12,6 +12,9 @@ With ``--boundary`` after a name (``genomic --boundary``) the same is done with 
 boundary terms of ``synth.boundary_terms`` and the file is full_<name>_boundary.npz, which also
 holds the gradients of those terms and the boundary posterior at the sampled rows.
 
+With ``--viterbi`` the oracle's Viterbi decode is run instead and its best scores and segment
+counts are stored in full_<name>_viterbi.npz.
+
 Output: tests/golden/full_<name>.npz (float64 arrays, a few hundred KB each).
 """
 import os
@@ -49,6 +52,13 @@ def main(args):
     for name in names:
         w = synth.make(name)
         t0 = time.time()
+        if "--viterbi" in args:   # best score and segment count of the Viterbi decode -> full_<name>_viterbi.npz
+            score, labels, starts, nseg = oracle.viterbi(w.emis, w.lengths, w.trans, w.dur)
+            dt = time.time() - t0
+            out = os.path.join(os.path.dirname(os.path.abspath(__file__)), f"full_{name}_viterbi.npz")
+            np.savez_compressed(out, score=score, nseg=nseg, oracle_seconds=np.array([dt]))
+            print(f"{name}: oracle viterbi {dt:.1f}s -> {out}", flush=True)
+            continue
         extra = {}
         if boundary:
             ps, pe, pis, pie = synth.boundary_terms(w)

@@ -1,0 +1,118 @@
+"""GPU parity of the Viterbi decode against the fp64 CPU oracle.
+
+The best score is unique: it must match the oracle's (relative 1e-6: the score is returned in
+fp32).  The best PATH need not be unique, so the decoded segmentation is checked for validity
+(segments tile the sequence, one label each, no segment longer than K, flags and counts agree,
+nothing beyond the sequence) and for optimality: its score, recomputed by the oracle's independent
+path scorer, must equal the best score.  Ties are structural, not accidental (a run of one label
+cut as 1+2 or as 2+1 tokens scores the same), and rounding decides them, so the paths themselves
+are not compared; the fraction of tokens on which both decoders agree is printed.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2604_18780_amd import binding as sb
+from paper_2604_18780_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def dev(a, dtype=np.float32):
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a, dtype=dtype)).to(DEV)
+
+
+def nan_pad(a, lengths):
+    a = a.copy()
+    for b in range(a.shape[0]):
+        a[b, int(lengths[b]):] = np.nan
+    return a
+
+
+def check(w, terms=(None, None, None, None), center=True, label=""):
+    print(f"[case] viterbi {label} B={w.B} T={w.T} K={w.K} C={w.C}", flush=True)
+    ps, pe, pis, pie = terms
+    flags = sb.SEMICRF_CENTER if center else 0
+    score, labels, starts, nseg = sb.semicrf_viterbi(
+        dev(nan_pad(w.emis, w.lengths)), dev(w.lengths, np.int32), dev(w.trans), dev(w.dur),
+        dev(None if ps is None else nan_pad(ps, w.lengths)), dev(None if pe is None else nan_pad(pe, w.lengths)),
+        dev(pis), dev(pie), flags)
+    torch.cuda.synchronize()
+    score = score.double().cpu().numpy()
+    labels, starts, nseg = labels.cpu().numpy(), starts.cpu().numpy(), nseg.cpu().numpy()
+    r_score, r_labels, r_starts, r_nseg = oracle.viterbi(w.emis, w.lengths, w.trans, w.dur, center=center,
+                                                         proj_start=ps, proj_end=pe, pi_start=pis, pi_end=pie)
+    assert np.all(np.isfinite(score))
+    assert np.abs(score - r_score).max() <= 1e-6 * max(1.0, np.abs(r_score).max()), (score, r_score)
+    for b in range(w.B):
+        L = int(w.lengths[b])
+        assert np.all(labels[b, L:] == -1) and np.all(starts[b, L:] == 0)
+        assert nseg[b] == starts[b].sum()
+        if L == 0:
+            continue
+        assert starts[b, 0] == 1 and labels[b, :L].min() >= 0 and labels[b, :L].max() < w.C
+        got = oracle.path_score(w.emis[b], L, w.trans, w.dur, labels[b], starts[b], center=center,
+                                proj_start=None if ps is None else ps[b], proj_end=None if pe is None else pe[b],
+                                pi_start=pis, pi_end=pie)                 # also asserts the structure
+        assert abs(got - r_score[b]) <= 1e-9 * max(1.0, abs(r_score[b])), (b, got, r_score[b])
+    valid = np.arange(w.T)[None, :] < w.lengths[:, None]
+    if valid.any():
+        print(f"       same label on {np.mean(labels[valid] == r_labels[valid]):.4f} of the tokens, same start flag on "
+              f"{np.mean(starts[valid] == r_starts[valid]):.4f}", flush=True)
+
+
+@pytest.mark.parametrize("seed,B,T,K,C", [
+    (1, 3, 40, 5, 3), (2, 4, 300, 8, 6), (3, 2, 700, 33, 24), (4, 5, 130, 1, 7),
+    (5, 3, 90, 2, 5), (6, 2, 50, 80, 4), (7, 3, 257, 16, 64), (8, 6, 33, 7, 1), (9, 1, 1, 1, 1),
+])
+def test_random_ragged_cases(seed, B, T, K, C):
+    w = synth.small_random(seed, B, T, K, C, ragged=True)
+    if seed == 2:
+        w.lengths[0] = 0
+        w.lengths[1] = T
+    check(w)
+    rng = np.random.default_rng(200 + seed)
+    terms = ((0.5 * rng.standard_normal((B, T, C))).astype(np.float32),
+             (0.5 * rng.standard_normal((B, T, C))).astype(np.float32),
+             rng.standard_normal(C).astype(np.float32), rng.standard_normal(C).astype(np.float32))
+    check(w, terms, center=(seed % 2 == 0), label="with boundary terms")
+
+
+def test_workload_shapes():
+    check(synth.make("nlp"), label="nlp")
+    check(synth.make("speech", B=4, T=600), label="speech shape")
+    check(synth.make("genomic", T=6000, B=2), label="genomic shape")
+    check(synth.make("longgen", T=3000), label="longgen shape")
+
+
+def test_unsupported_sizes_are_refused():
+    w = synth.small_random(61, 1, 8, 2, 70, ragged=False)
+    with pytest.raises(sb.SemiCRFError) as ei:
+        sb.semicrf_viterbi(dev(w.emis), dev(w.lengths, np.int32), dev(w.trans), dev(w.dur))
+    assert ei.value.status == -3
+
+
+def test_full_size_genomic_decode():
+    """The genomic workload at full size, as `bench.py --viterbi` runs it: best score against the
+    stored oracle value (tests/golden/make_golden.py, oracle only), and the decoded segmentation
+    validated and re-scored by the oracle's independent path scorer."""
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "full_genomic_viterbi.npz")
+    if not os.path.exists(path):
+        pytest.skip(f"{path} not generated")
+    g = np.load(path)
+    w = synth.make("genomic")
+    score, labels, starts, nseg = sb.semicrf_viterbi(dev(w.emis), dev(w.lengths, np.int32), dev(w.trans), dev(w.dur))
+    torch.cuda.synchronize()
+    score = score.double().cpu().numpy()
+    labels, starts, nseg = labels.cpu().numpy(), starts.cpu().numpy(), nseg.cpu().numpy()
+    assert np.abs(score - g["score"]).max() <= 1e-6 * np.abs(g["score"]).max()
+    for b in range(w.B):
+        L = int(w.lengths[b])
+        got = oracle.path_score(w.emis[b], L, w.trans, w.dur, labels[b], starts[b])
+        assert abs(got - g["score"][b]) <= 1e-9 * abs(g["score"][b]), (b, got, g["score"][b])
+        assert nseg[b] == starts[b].sum()
+    print(f"       segments per sequence {nseg} (oracle {g['nseg']})", flush=True)
