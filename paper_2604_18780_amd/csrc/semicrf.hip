@@ -108,6 +108,9 @@ struct Params {
     int logpair;        // k_prefix stores the log-domain pair (S + end score, start score - S): Viterbi
     double2 *vr;        // [B][T+1][C] Viterbi: (V_t(c), r_t(c)) = best score arriving at / leaving position t
     int *vbest;         // [B] Viterbi: label of the last segment
+    int *vbp;           // [B][T+1][C] Viterbi back-pointers: (duration << 8) | predecessor label
+    int *vpar[2];       // [B][T+1][C] parent node (position * C + label) and its doublings (ping-pong)
+    unsigned char *vmark;  // [B][T+1][C] 1: the node lies on the best path
     float *vscore;      // Viterbi outputs
     int32_t *vlabels, *vstarts, *vnseg;
     int spec;           // chunk-parallel scan enabled for this call
@@ -2402,71 +2405,114 @@ __global__ __launch_bounds__(64) void k_viterbi(Params p)
     }
 }
 
-// Trace-back: one wave per sequence.  At (t, c): the duration is the smallest k that maximises
-// dur[k,c] + r_{t-k}(c) (lanes take k = lane+1, lane+65, ...), then the predecessor label is the
-// smallest c' that maximises V_{t-k}(c') + trans[c',c].  Writes the label of every token, a flag
-// on the first token of every segment, and the number of segments.
-__global__ __launch_bounds__(64) void k_vit_trace(Params p)
+// Trace-back, in parallel.  Node (t, c) = "a segment with label c ends at position t".
+// 1. k_vit_bp: for every node the duration is the smallest k that maximises
+//    dur[k,c] + r_{t-k}(c), then the predecessor label the smallest c' that maximises
+//    V_{t-k}(c') + trans[c',c]: the same additions as in the scan, so the maxima are the scan's,
+//    bit for bit.  A tile of 32 positions per workgroup with the K + 32 rows of (V, r) it can
+//    reach staged in LDS.  parent(t, c) = (t - k, c'); nodes at position 0 are their own parent.
+// 2. k_vit_round, ceil(log2(T+1)) times: every marked node marks the node its current
+//    pointer leads to, then every pointer is replaced by the pointer's pointer.  After round i
+//    the marked nodes are the root's ancestors at distances < 2^(i+1): the best path.
+// 3. k_vit_emit: every marked node writes its segment's tokens.
+constexpr int VBP_TILE = 32;
+
+__global__ __launch_bounds__(NT) void k_vit_bp(Params p)
 {
-    const int lane = threadIdx.x, b = blockIdx.x;
+    extern __shared__ double lds_raw[];
+    const int b = blockIdx.y, tid = threadIdx.x;
     const int K = p.K, C = p.C, T = p.T;
     const int L = p.hdr[b].L;
-    const double2 *VR = p.vr + (size_t)b * (T + 1) * C;
-    int32_t *lab = p.vlabels + (size_t)b * T, *st = p.vstarts + (size_t)b * T;
-    for (int u = L + lane; u < T; u += 64) {  // beyond the sequence; every token before L is written once below
-        lab[u] = -1;
-        st[u] = 0;
+    const int t0 = blockIdx.x * VBP_TILE;
+    const int rows = K + VBP_TILE, sbase = t0 - K;  // LDS row i holds position sbase + i
+    double *vv = lds_raw;                            // [rows][C]  V
+    double *rr = lds_raw + (size_t)rows * C;         // [rows][C]  r
+    const size_t nn = (size_t)(T + 1) * C;
+    const double2 *VR = p.vr + (size_t)b * nn;
+    for (int i = tid; i < rows * C; i += NT) {
+        const int sp = sbase + i / C;
+        double2 x = make_double2(-INFINITY, -INFINITY);
+        if (sp >= 0 && sp <= L) x = VR[(size_t)sp * C + i % C];
+        vv[i] = x.x;
+        rr[i] = x.y;
     }
-    auto wave_argmax = [&](double v, int idx, double &bv, int &bi) {
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const double ov = __shfl_xor(v, off);
-            const int oi = __shfl_xor(idx, off);
-            if (ov > v || (ov == v && oi < idx)) {
-                v = ov;
-                idx = oi;
-            }
+    if (blockIdx.x == 0 && tid == 0) p.vnseg[b] = 0;
+    __syncthreads();
+    int *bp = p.vbp + (size_t)b * nn, *par = p.vpar[0] + (size_t)b * nn;
+    unsigned char *mark = p.vmark + (size_t)b * nn;
+    for (int j = tid; j < VBP_TILE * C; j += NT) {
+        const int t = t0 + j / C, c = j % C;
+        if (t > T) continue;
+        const size_t n = (size_t)t * C + c;
+        mark[n] = 0;
+        if (t < 1 || t > L) {
+            bp[n] = 0;
+            par[n] = (int)n;
+            continue;
         }
-        bv = v;
-        bi = idx;
-    };
-    int t = L, c = p.vbest[b], nseg = 0;
-    while (t > 0) {
         const int kmax = min(K, t);
-        double v = -INFINITY;
-        int kb = 0x7fffffff;
-        for (int k = lane + 1; k <= kmax; k += 64) {
-            const double cand = (double)p.dur[(size_t)(k - 1) * C + c] + VR[(size_t)(t - k) * C + c].y;
-            if (cand > v) {  // ascending k per lane: strict ">" keeps the smallest
-                v = cand;
+        double best = -INFINITY;
+        int kb = 1;
+        const double *rcol = rr + (size_t)(t - sbase) * C + c;  // r_{t-k}(c) at rcol[-k*C]
+        for (int k = 1; k <= kmax; ++k) {
+            const double cand = (double)p.dur[(size_t)(k - 1) * C + c] + rcol[-(k * C)];
+            if (cand > best) {
+                best = cand;
                 kb = k;
             }
         }
-        double bv;
-        int k;
-        wave_argmax(v, kb, bv, k);
-        if (k < 1 || k > kmax) break;  // only if the scores were not finite
-        const int s = t - k;
-        double v2 = -INFINITY;
-        int cb = 0x7fffffff;
-        for (int o = lane; o < C; o += 64) {
-            const double cand = VR[(size_t)s * C + o].x + (double)p.trans[(size_t)o * C + c];
-            if (cand > v2) {
-                v2 = cand;
+        const int sp = t - kb;
+        const double *vrow = vv + (size_t)(sp - sbase) * C;
+        double best2 = -INFINITY;
+        int cb = 0;
+        for (int o = 0; o < C; ++o) {
+            const double cand = vrow[o] + (double)p.trans[(size_t)o * C + c];
+            if (cand > best2) {
+                best2 = cand;
                 cb = o;
             }
         }
-        int cp;
-        wave_argmax(v2, cb, bv, cp);
-        for (int u = s + lane; u < t; u += 64) {
-            lab[u] = c;
-            st[u] = u == s ? 1 : 0;
-        }
-        ++nseg;
-        t = s;
-        c = cp;
+        bp[n] = (kb << 8) | cb;
+        par[n] = sp * C + cb;
     }
-    if (lane == 0) p.vnseg[b] = nseg;
+}
+
+__global__ __launch_bounds__(NT) void k_vit_round(Params p, int src, int first)
+{
+    const int b = blockIdx.y;
+    const size_t nn = (size_t)(p.T + 1) * p.C;
+    const size_t n = (size_t)blockIdx.x * NT + threadIdx.x;
+    if (n >= nn) return;
+    const int *pin = p.vpar[src] + (size_t)b * nn;
+    int *pout = p.vpar[src ^ 1] + (size_t)b * nn;
+    unsigned char *mark = p.vmark + (size_t)b * nn;
+    const int par = pin[n];
+    const bool root = first && n == (size_t)p.hdr[b].L * p.C + p.vbest[b];
+    if (root) mark[n] = 1;
+    if (root || mark[n]) mark[par] = 1;  // a mark set earlier in this launch only arrives sooner
+    pout[n] = pin[par];
+}
+
+__global__ __launch_bounds__(NT) void k_vit_emit(Params p)
+{
+    const int b = blockIdx.y, C = p.C, T = p.T;
+    const int L = p.hdr[b].L;
+    const size_t nn = (size_t)(T + 1) * C;
+    const size_t n = (size_t)blockIdx.x * NT + threadIdx.x;
+    if (n >= nn) return;
+    const int t = (int)(n / (unsigned)C), c = (int)(n - (size_t)t * C);
+    int32_t *lab = p.vlabels + (size_t)b * T, *st = p.vstarts + (size_t)b * T;
+    if (c == 0 && t >= 1 && t - 1 >= L) {  // token t-1 lies beyond the sequence
+        lab[t - 1] = -1;
+        st[t - 1] = 0;
+    }
+    if (t < 1 || t > L || !p.vmark[(size_t)b * nn + n]) return;
+    const int k = p.vbp[(size_t)b * nn + n] >> 8;
+    for (int u = t - k; u < t; ++u) {
+        lab[u] = c;
+        st[u] = u == t - k ? 1 : 0;
+    }
+    atomicAdd(&p.vnseg[b], 1);
 }
 
 // ---------------------------------------------------------------------------
@@ -3090,9 +3136,25 @@ int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hi
     return check_launch();
 }
 
-size_t viterbi_extra_bytes(int B, int T, int C)
+// Viterbi workspace beyond the prefix-stage plan: (V, r) pairs, best final labels, back-pointers,
+// two pointer arrays and the path marks.
+struct VitLayout {
+    size_t vr, vbest, vbp, vpar0, vpar1, vmark, total;
+};
+
+VitLayout viterbi_layout(int B, int T, int C)
 {
-    return align_up((size_t)B * ((size_t)T + 1) * C * sizeof(double2)) + align_up((size_t)B * sizeof(int));
+    const size_t nodes = (size_t)B * ((size_t)T + 1) * C;
+    VitLayout l;
+    size_t off = 0;
+    l.vr = off; off += align_up(nodes * sizeof(double2));
+    l.vbest = off; off += align_up((size_t)B * sizeof(int));
+    l.vbp = off; off += align_up(nodes * sizeof(int));
+    l.vpar0 = off; off += align_up(nodes * sizeof(int));
+    l.vpar1 = off; off += align_up(nodes * sizeof(int));
+    l.vmark = off; off += align_up(nodes);
+    l.total = off;
+    return l;
 }
 
 template <int CT, int NKW>
@@ -3125,16 +3187,22 @@ int run_viterbi(Params p, void *workspace, size_t workspace_bytes, hipStream_t s
     int rc = make_plan(p.B, p.T, p.K, p.C, 0, 0, &pl);
     if (rc != SEMICRF_OK) return rc;
     if (p.C > 64 || !spec_applies(p.K, p.C)) return SEMICRF_EUNSUPPORTED;
-    const size_t total = pl.total + viterbi_extra_bytes(p.B, p.T, p.C);
+    if (((size_t)p.T + 1) * p.C >= ((size_t)1 << 31)) return SEMICRF_EUNSUPPORTED;  // node ids are 32-bit
+    const VitLayout vl = viterbi_layout(p.B, p.T, p.C);
+    const size_t total = pl.total + vl.total;
     if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < total) return SEMICRF_EWORKSPACE;
     p.Delta = pl.Delta;
     p.N = pl.N;
     p.NCH = pl.NCH;
     p.nslot = pl.nslot;
     bind_workspace(p, pl, workspace);
-    p.vr = (double2 *)((char *)workspace + pl.total);
-    p.vbest = (int *)((char *)workspace + pl.total +
-                      align_up((size_t)p.B * ((size_t)p.T + 1) * p.C * sizeof(double2)));
+    char *vw = (char *)workspace + pl.total;
+    p.vr = (double2 *)(vw + vl.vr);
+    p.vbest = (int *)(vw + vl.vbest);
+    p.vbp = (int *)(vw + vl.vbp);
+    p.vpar[0] = (int *)(vw + vl.vpar0);
+    p.vpar[1] = (int *)(vw + vl.vpar1);
+    p.vmark = (unsigned char *)(vw + vl.vmark);
     p.logpair = 1;
     rc = launch_prep(p, st);
     if (rc != SEMICRF_OK) return rc;
@@ -3145,7 +3213,21 @@ int run_viterbi(Params p, void *workspace, size_t workspace_bytes, hipStream_t s
     else if (C <= 32) rc = launch_viterbi_ct<32>(p, st);
     else rc = launch_viterbi_ct<64>(p, st);
     if (rc != SEMICRF_OK) return rc;
-    hipLaunchKernelGGL(k_vit_trace, dim3(p.B), dim3(64), 0, st, p);
+    {
+        const size_t lds = 2 * (size_t)(p.K + VBP_TILE) * p.C * sizeof(double);
+        if (lds > LDS_LIMIT) return SEMICRF_EUNSUPPORTED;
+        if (hipFuncSetAttribute((const void *)k_vit_bp, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) !=
+            hipSuccess)
+            return SEMICRF_ELAUNCH;
+        hipLaunchKernelGGL(k_vit_bp, dim3(p.T / VBP_TILE + 1, p.B), dim3(NT), lds, st, p);
+    }
+    const size_t nn = ((size_t)p.T + 1) * p.C;
+    const unsigned nblk = (unsigned)((nn + NT - 1) / NT);
+    int rounds = 1;
+    while (((size_t)1 << rounds) < (size_t)p.T + 1) ++rounds;
+    for (int i = 0; i < rounds; ++i)
+        hipLaunchKernelGGL(k_vit_round, dim3(nblk, p.B), dim3(NT), 0, st, p, i & 1, i == 0 ? 1 : 0);
+    hipLaunchKernelGGL(k_vit_emit, dim3(nblk, p.B), dim3(NT), 0, st, p);
     return check_launch();
 }
 
@@ -3329,7 +3411,8 @@ int semicrf_viterbi_workspace_bytes(int B, int T, int K, int C, size_t *bytes)
     int rc = make_plan(B, T, K, C, 0, 0, &pl);
     if (rc != SEMICRF_OK) return rc;
     if (C > 64 || !spec_applies(K, C)) return SEMICRF_EUNSUPPORTED;
-    *bytes = pl.total + viterbi_extra_bytes(B, T, C);
+    if (((size_t)T + 1) * C >= ((size_t)1 << 31)) return SEMICRF_EUNSUPPORTED;
+    *bytes = pl.total + viterbi_layout(B, T, C).total;
     return SEMICRF_OK;
 }
 
