@@ -2273,15 +2273,22 @@ __device__ __forceinline__ double group_max(double v)
     return v;
 }
 
+// One scan task: the whole sequence (chunk < 0: the sequential scan) or one checkpoint interval
+// (lo, hi] after a warm-up over the `warm` positions before it, started as a sequence that
+// begins there.  A chunk task records its window and V vector at lo (-> ckA[chunk]) and at hi
+// (-> ckA2[chunk+1]) for the verification, and stores (V_t, r_t) for lo < t <= hi (and for
+// position 0 if lo = 0) in ITS OWN additive unit: max-plus recurrences are invariant under adding
+// a constant to every message, and a warmed-up chunk differs from the true values by exactly such
+// a constant once all best paths through the warm-up have merged.
 template <int CT, int NKW>
-__global__ __launch_bounds__(64) void k_viterbi(Params p)
+__device__ __forceinline__ void vit_task(const Params &p, double *lds_raw, const int b, const int chunk,
+                                         const int warm)
 {
     using G = WaveWin<CT, NKW>;
     constexpr int CTP = G::CTP, RS = G::RS, NK = G::NK, KW = G::KW, ROWS = G::ROWS;
     constexpr int RTOT = G::RTOT, H = G::H, HC = G::HC;
-    extern __shared__ double lds_raw[];
-    const int lane = threadIdx.x, b = blockIdx.x;
-    const int K = p.K, C = p.C;
+    const int lane = threadIdx.x;
+    const int K = p.K, C = p.C, KC = K * C;
     double *ring = lds_raw;          // [ROWS][RS] (+ pad): r of the last KW positions
     double *yv = ring + RTOT;        // [CTP]: V of the current position
     const int c = lane % CTP, g = lane / CTP;
@@ -2290,6 +2297,11 @@ __global__ __launch_bounds__(64) void k_viterbi(Params p)
     const int cc = cval ? c : 0;
     const bool writer = cval && g == 0;
     const int L = p.hdr[b].L;
+    const bool whole = chunk < 0;
+    const int lo = whole ? 0 : chunk * p.Delta;
+    if (!whole && lo >= L && !(lo == 0 && L == 0)) return;
+    const int hi = whole ? L : min(lo + p.Delta, L);
+    const int s0 = whole ? 0 : max(lo - warm, 0);
     const size_t row0 = (size_t)b * (p.T + 1);
     const double2 *LPc = p.EI + row0 * C + cc;  // (S + end score, start score - S)
     double2 *VR = p.vr + row0 * C;
@@ -2313,7 +2325,7 @@ __global__ __launch_bounds__(64) void k_viterbi(Params p)
     const double2 *ys = (const double2 *)__builtin_assume_aligned(yv + hh * HC, 16);
 
     for (int i = lane; i < RTOT; i += 64) ring[i] = NINF;
-    if (lane < CTP) yv[lane] = lane < C ? 0.0 : NINF;  // V_0 = 0 for every label
+    if (lane < CTP) yv[lane] = lane < C ? 0.0 : NINF;  // V = 0 for every label where the (sub)sequence begins
     lds_wave_fence();
     int r = KW - 1;
     auto leave = [&]() {  // max_o (V(o) + trans[o,c]) from the V vector in yv
@@ -2328,24 +2340,33 @@ __global__ __launch_bounds__(64) void k_viterbi(Params p)
         if (H == 2) m = max_across_32(m);
         return m;
     };
+    // state for the verification: r of the K positions up to t (by distance), then V_t
+    const size_t ckstride = (size_t)KC + C;
+    auto record = [&](double *ck) {
+        for (int i = lane; i < KC; i += 64) ck[i] = ring[(r - i / C) * RS + i % C];
+        if (lane < C) ck[KC + lane] = yv[lane];
+    };
     {
-        const double q = leave() + LPc[0].y;
+        const double q = leave() + LPc[(size_t)s0 * C].y;
         if (writer) {
             ring[r * RS + c] = q;
-            VR[c] = make_double2(0.0, q);
+            if (s0 == lo) VR[(size_t)s0 * C + c] = make_double2(0.0, q);
         }
     }
     lds_wave_fence();
+    if (!whole && s0 == lo) record(p.ckA + ((size_t)b * (p.N + 1) + chunk) * ckstride);
     const int rdoff = -(g * NK + NK - 1) * RS + c;
-    int t = 0;
+    int t = s0;
     auto load_rows = [&](double2 (&e)[MB], const int tfrom) {
 #pragma unroll
-        for (int i = 0; i < MB; ++i) e[i] = LPc[(size_t)min(tfrom + 1 + i, L) * C];
+        for (int i = 0; i < MB; ++i) e[i] = LPc[(size_t)min(tfrom + 1 + i, hi) * C];
     };
     double2 e[MB];
     load_rows(e, t);
-    while (t < L) {
-        const int nb = min(L - t, MB);
+    while (t < hi) {
+        int nb = min(hi - t, MB);
+        if (t < lo) nb = min(nb, lo - t);  // the position where the chunk proper starts ends its block
+        const bool keep = t >= lo;
         double2 en[MB];
         load_rows(en, t + nb);
         if (__builtin_expect(r + MB > ROWS - 1, 0)) r = G::template move<false>(ring, lane, r);
@@ -2376,7 +2397,7 @@ __global__ __launch_bounds__(64) void k_viterbi(Params p)
                 ++r;
                 if (writer) {
                     ring[r * RS + c] = q;
-                    VR[(size_t)(t + 1 + i) * C + c] = make_double2(y, q);
+                    if (keep) VR[(size_t)(t + 1 + i) * C + c] = make_double2(y, q);
                 }
                 lds_wave_fence();
             } else {
@@ -2386,6 +2407,11 @@ __global__ __launch_bounds__(64) void k_viterbi(Params p)
         t += nb;
 #pragma unroll
         for (int i = 0; i < MB; ++i) e[i] = en[i];
+        if (!whole && t == lo) record(p.ckA + ((size_t)b * (p.N + 1) + chunk) * ckstride);
+    }
+    if (!whole) {
+        record(p.ckA2 + ((size_t)b * (p.N + 1) + chunk + 1) * ckstride);
+        return;
     }
     // best final label (smallest on ties) and score
     double best = cval ? yv[c] : NINF;
@@ -2402,6 +2428,131 @@ __global__ __launch_bounds__(64) void k_viterbi(Params p)
     if (lane == 0) {
         p.vscore[b] = L > 0 ? (float)best : 0.f;
         p.vbest[b] = bl;
+    }
+}
+
+// The sequential scan: one wave per sequence (skips sequences whose chunk-parallel scan was accepted).
+template <int CT, int NKW>
+__global__ __launch_bounds__(64) void k_viterbi(Params p)
+{
+    extern __shared__ double lds_raw[];
+    if (p.spec && p.spec_ok[blockIdx.x * 2]) return;
+    vit_task<CT, NKW>(p, lds_raw, blockIdx.x, -1, 0);
+}
+
+// The chunk-parallel scan: one wave per (sequence, checkpoint interval).
+template <int CT, int NKW>
+__global__ __launch_bounds__(64) void k_vit_spec(Params p, int warm, int tier)
+{
+    extern __shared__ double lds_raw[];
+    const int b = blockIdx.x / p.N, chunk = blockIdx.x % p.N;
+    if (tier > 0 && p.spec_ok[b * 2]) return;
+    vit_task<CT, NKW>(p, lds_raw, b, chunk, warm);
+}
+
+// Per chunk boundary j (position j*Delta): the state chunk j-1 reached against the warmed-up
+// state chunk j started from.  They must agree entry by entry up to ONE additive constant
+// (taken from the largest V entry); -inf entries must coincide.
+__global__ __launch_bounds__(64) void k_vit_cmp(Params p, int tier)
+{
+    const int j = blockIdx.x, b = blockIdx.y, lane = threadIdx.x;
+    if (tier > 0 && p.spec_ok[b * 2]) return;
+    const int L = p.hdr[b].L;
+    const int nint = (L + p.Delta - 1) / p.Delta;
+    if (j < 1 || j >= nint) return;
+    const int KC = p.K * p.C, C = p.C, N = p.N;
+    const size_t ckstride = (size_t)KC + C;
+    const double *A = p.ckA + ((size_t)b * (N + 1) + j) * ckstride;    // warm-up state
+    const double *A2 = p.ckA2 + ((size_t)b * (N + 1) + j) * ckstride;  // reached state
+    // additive constant: at the largest reached V entry (smallest label on ties)
+    double v = lane < C ? A2[KC + lane] : -INFINITY;
+    int idx = lane < C ? lane : 0x7fffffff;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const double ov = __shfl_xor(v, off);
+        const int oi = __shfl_xor(idx, off);
+        if (ov > v || (ov == v && oi < idx)) {
+            v = ov;
+            idx = oi;
+        }
+    }
+    const double delta = v - A[KC + idx];
+    double err = (v > -INFINITY && delta == delta && fabs(delta) < DBL_MAX) ? 0.0 : DBL_MAX;
+#pragma unroll 4
+    for (int i = lane; i < KC + C; i += 64) {
+        const double x = A2[i], y = A[i];
+        if (x == -INFINITY || y == -INFINITY) {
+            if (x != y) err = DBL_MAX;
+        } else {
+            err = fmax(err, fabs(x - (y + delta)) / fmax(1.0, fmax(fabs(x), fabs(y + delta))));
+        }
+    }
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) err = fmax(err, __shfl_xor(err, off));
+    if (lane == 0) {
+        const size_t o = ((size_t)b * 2) * (N + 1) + j;
+        p.spec_err[o] = err;
+        p.spec_lr[o] = delta;
+    }
+}
+
+// Accept or reject each sequence; chain the additive constants (ckYA[b][j] = what must be added
+// to the values stored by chunk j to get the true ones); best final label and score.
+constexpr double VIT_TOL = 1e-12;
+
+__global__ __launch_bounds__(64) void k_vit_fix(Params p, int tier)
+{
+    const int b = blockIdx.x, lane = threadIdx.x;
+    if (tier > 0 && p.spec_ok[b * 2]) return;
+    const int L = p.hdr[b].L, N = p.N, C = p.C, KC = p.K * C;
+    const int nint = (L + p.Delta - 1) / p.Delta;
+    const size_t so = ((size_t)b * 2) * (N + 1);
+    double *off = p.ckYA + (size_t)b * (N + 1);
+    double worst = 0.0;
+    for (int j = 1 + lane; j < nint; j += 64) worst = fmax(worst, p.spec_err[so + j]);
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) worst = fmax(worst, __shfl_xor(worst, o));
+    // prefix sums of the constants, in boundary order (lane 0; a few hundred terms)
+    double total = 0.0;
+    if (lane == 0) {
+        off[0] = 0.0;
+        for (int j = 1; j < nint; ++j) {
+            total += p.spec_lr[so + j];
+            off[j] = total;
+        }
+    }
+    total = __shfl(total, 0);
+    const bool ok = worst <= VIT_TOL;
+    if (ok) {
+        double best = -INFINITY;
+        int bl = 0x7fffffff;
+        if (nint > 0) {
+            const double *e = p.ckA2 + ((size_t)b * (N + 1) + nint) * ((size_t)KC + C);
+            if (lane < C) {
+                best = e[KC + lane];
+                bl = lane;
+            }
+        } else if (lane == 0) {
+            best = 0.0;
+            bl = 0;
+        }
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const double ov = __shfl_xor(best, o);
+            const int ol = __shfl_xor(bl, o);
+            if (ov > best || (ov == best && ol < bl)) {
+                best = ov;
+                bl = ol;
+            }
+        }
+        if (lane == 0) {
+            p.vscore[b] = L > 0 ? (float)(best + total) : 0.f;
+            p.vbest[b] = bl;
+        }
+    }
+    if (lane == 0) {
+        p.spec_ok[b * 2] = ok ? 1 : 0;
+        p.spec_err[so] = worst;
     }
 }
 
@@ -2429,10 +2580,20 @@ __global__ __launch_bounds__(NT) void k_vit_bp(Params p)
     double *rr = lds_raw + (size_t)rows * C;         // [rows][C]  r
     const size_t nn = (size_t)(T + 1) * C;
     const double2 *VR = p.vr + (size_t)b * nn;
+    // values stored by an accepted chunk-parallel scan are in their chunk's additive unit
+    const bool chunked = p.spec && p.spec_ok[b * 2];
+    const double *unit = p.ckYA + (size_t)b * (p.N + 1);
     for (int i = tid; i < rows * C; i += NT) {
         const int sp = sbase + i / C;
         double2 x = make_double2(-INFINITY, -INFINITY);
-        if (sp >= 0 && sp <= L) x = VR[(size_t)sp * C + i % C];
+        if (sp >= 0 && sp <= L) {
+            x = VR[(size_t)sp * C + i % C];
+            if (chunked) {
+                const double u = unit[sp == 0 ? 0 : (sp - 1) / p.Delta];
+                x.x += u;
+                x.y += u;
+            }
+        }
         vv[i] = x.x;
         rr[i] = x.y;
     }
@@ -3163,8 +3324,22 @@ int launch_viterbi_k(const Params &p, hipStream_t st)
     const size_t lds = wave_lds_doubles(CT, NKW) * sizeof(double);
     if (lds > LDS_LIMIT) return SEMICRF_EUNSUPPORTED;
     if (hipFuncSetAttribute((const void *)k_viterbi<CT, NKW>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds) != hipSuccess ||
+        hipFuncSetAttribute((const void *)k_vit_spec<CT, NKW>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)lds) != hipSuccess)
         return SEMICRF_ELAUNCH;
+    if (p.spec) {
+        // chunk-parallel scan with two warm-up lengths, as for the sum recurrences
+        const int warm[2] = {2 * p.K < 32 ? 32 : 2 * p.K, 8 * p.K < 64 ? 64 : 8 * p.K};
+        for (int tier = 0; tier < 2; ++tier) {
+            hipLaunchKernelGGL((k_vit_spec<CT, NKW>), dim3(p.B * p.N), dim3(64), lds, st, p, warm[tier], tier);
+            hipLaunchKernelGGL(k_vit_cmp, dim3(p.N, p.B), dim3(64), 0, st, p, tier);
+            hipLaunchKernelGGL(k_vit_fix, dim3(p.B), dim3(64), 0, st, p, tier);
+        }
+    } else {
+        hipLaunchKernelGGL(k_spec_clear, dim3((2 * p.B + 63) / 64), dim3(64), 0, st, p);
+    }
+    // sequential scan for what the verification rejected (returns at once otherwise)
     hipLaunchKernelGGL((k_viterbi<CT, NKW>), dim3(p.B), dim3(64), lds, st, p);
     return check_launch();
 }
@@ -3204,6 +3379,7 @@ int run_viterbi(Params p, void *workspace, size_t workspace_bytes, hipStream_t s
     p.vpar[1] = (int *)(vw + vl.vpar1);
     p.vmark = (unsigned char *)(vw + vl.vmark);
     p.logpair = 1;
+    p.spec = p.spec ? 1 : 0;
     rc = launch_prep(p, st);
     if (rc != SEMICRF_OK) return rc;
     const int C = p.C;
@@ -3431,6 +3607,7 @@ int semicrf_viterbi(const float *emis, const int32_t *lengths, const float *tran
     p.emis_type = (flags & SEMICRF_EMIS_F16) ? 1 : ((flags & SEMICRF_EMIS_BF16) ? 2 : 0);
     if ((flags & SEMICRF_EMIS_F16) && (flags & SEMICRF_EMIS_BF16)) return SEMICRF_EINVAL;
     p.vscore = score; p.vlabels = labels; p.vstarts = starts; p.vnseg = nseg;
+    p.spec = (flags & SEMICRF_SEQUENTIAL_SCAN) ? 0 : 1;
     return run_viterbi(p, workspace, workspace_bytes, (hipStream_t)stream);
 }
 

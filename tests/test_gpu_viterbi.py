@@ -32,15 +32,25 @@ def nan_pad(a, lengths):
     return a
 
 
-def check(w, terms=(None, None, None, None), center=True, label=""):
+def check(w, terms=(None, None, None, None), center=True, label="", extra_flags=0, expect_chunked=None):
     print(f"[case] viterbi {label} B={w.B} T={w.T} K={w.K} C={w.C}", flush=True)
     ps, pe, pis, pie = terms
-    flags = sb.SEMICRF_CENTER if center else 0
+    flags = (sb.SEMICRF_CENTER if center else 0) | extra_flags
+    n = sb.semicrf_viterbi_workspace_bytes(w.B, w.T, w.K, w.C)
+    raw = torch.empty(n + 256, dtype=torch.uint8, device=DEV)
+    off = (-raw.data_ptr()) % 256
+    ws = raw[off:off + n]
     score, labels, starts, nseg = sb.semicrf_viterbi(
         dev(nan_pad(w.emis, w.lengths)), dev(w.lengths, np.int32), dev(w.trans), dev(w.dur),
         dev(None if ps is None else nan_pad(ps, w.lengths)), dev(None if pe is None else nan_pad(pe, w.lengths)),
-        dev(pis), dev(pie), flags)
+        dev(pis), dev(pie), flags, workspace=ws)
+    acc, mis = sb.semicrf_scan_report(ws, w.B, w.T, w.K, w.C, 0, False)
     torch.cuda.synchronize()
+    acc = acc.cpu().numpy()[:, 0]
+    print(f"       chunk-parallel scan accepted for {int(acc.sum())} of {w.B} sequences, largest mismatch "
+          f"{mis[:, 0].max().item():.2e}", flush=True)
+    if expect_chunked is not None:
+        assert np.all(acc == (1 if expect_chunked else 0))
     score = score.double().cpu().numpy()
     labels, starts, nseg = labels.cpu().numpy(), starts.cpu().numpy(), nseg.cpu().numpy()
     r_score, r_labels, r_starts, r_nseg = oracle.viterbi(w.emis, w.lengths, w.trans, w.dur, center=center,
@@ -116,3 +126,25 @@ def test_full_size_genomic_decode():
         assert abs(got - g["score"][b]) <= 1e-9 * abs(g["score"][b]), (b, got, g["score"][b])
         assert nseg[b] == starts[b].sum()
     print(f"       segments per sequence {nseg} (oracle {g['nseg']})", flush=True)
+
+
+def test_chunk_parallel_and_sequential_scans_give_the_same_score():
+    w = synth.small_random(41, 3, 1500, 12, 10, ragged=True)
+    w.lengths[:] = [1500, 1499, 64]
+    check(w, label="default (chunk-parallel, verified)", expect_chunked=True)
+    check(w, label="sequential", extra_flags=sb.SEMICRF_SEQUENTIAL_SCAN, expect_chunked=False)
+
+
+def test_paths_that_do_not_merge_fall_back_to_the_sequential_scan():
+    """A nearly deterministic two-label chain with weak emissions: the best path into a position
+    depends on how the sequence started for thousands of positions, so the warmed-up chunk states
+    differ from the true ones by more than one constant; the boundary check must fail and the
+    sequential scan must deliver the result."""
+    rng = np.random.default_rng(42)
+    B, T, K, C = 2, 2000, 2, 2
+    w = synth.small_random(42, B, T, K, C, ragged=False)
+    w.emis[:] = (0.05 * rng.standard_normal((B, T, C))).astype(np.float32)
+    w.trans[:] = np.array([[0.0, -40.0], [-40.0, 0.0]], dtype=np.float32)
+    w.dur[:] = 0.0
+    check(w, label="no merging", expect_chunked=False)
+
