@@ -188,7 +188,18 @@ int semicrf_fwd_bwd_boundary(const float *emis, const int32_t *lengths, const fl
  * backwards each segment takes the smallest duration, then the smallest predecessor label,
  * among the maximisers; since sums are rounded, "equally good" means equal in fp64.
  * Supported sizes: C <= 64 and K <= 64 * (64 / (C rounded up to 8/16/32/64)).  Workspace:
- * semicrf_viterbi_workspace_bytes (O(T*C): prefix arrays plus two doubles per position and label).
+ * semicrf_viterbi_workspace_bytes (O(T*C): prefix arrays plus two doubles and three
+ * integers per position and label).
+ * The forward recurrence runs chunk-parallel like the sums: every checkpoint interval is
+ * scanned on its own after a warm-up from the state of a sequence that begins there.  Best
+ * paths that have merged give states equal up to one additive constant, so each interval
+ * boundary is checked entry by entry (-inf entries must coincide) after removing that
+ * constant, to 1e-12 relative to the entries' size; the constants are chained in a fixed
+ * order.  A sequence with a boundary that does not agree after the second, longer warm-up
+ * is rescanned sequentially inside the same call, and SEMICRF_SEQUENTIAL_SCAN forces that.
+ * semicrf_scan_report with ckpt_interval = 0 and want_grad = 0 on this workspace reports
+ * the outcome in column 0.  The trace-back (back-pointers of every node, pointer doubling,
+ * one store per token) is parallel either way.
  */
 int semicrf_viterbi_workspace_bytes(int B, int T, int K, int C, size_t *bytes);
 

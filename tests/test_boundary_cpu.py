@@ -145,6 +145,35 @@ def test_calls_reject_null_pointers_and_bad_workspace_before_any_launch():
     assert rc == -1
 
 
+def test_viterbi_and_entropy_entries_check_their_arguments_on_the_host():
+    lib = sb.load()
+    out = ctypes.c_size_t(0)
+    fake = ctypes.c_void_p(4096)
+    assert lib.semicrf_viterbi_workspace_bytes(1, 8, 2, 3, None) == -1
+    assert lib.semicrf_viterbi_workspace_bytes(0, 8, 2, 3, ctypes.byref(out)) == -1
+    # label counts and windows beyond the one-wave decoder
+    assert lib.semicrf_viterbi_workspace_bytes(1, 8, 2, 65, ctypes.byref(out)) == -3
+    assert lib.semicrf_viterbi_workspace_bytes(1, 1000, 65, 64, ctypes.byref(out)) == -3
+    assert lib.semicrf_viterbi_workspace_bytes(1, 1000, 512, 8, ctypes.byref(out)) == 0
+    # O(T*C): the prefix arrays (20 B) plus a double pair, three ints and a byte per node
+    n = sb.semicrf_viterbi_workspace_bytes(4, 100000, 64, 24)
+    nodes = 4 * 100001 * 24
+    assert n % 256 == 0 and nodes * (20 + 16 + 12 + 1) < n < nodes * 64
+    rc = lib.semicrf_viterbi(None, None, None, None, None, None, None, None, 1, 8, 2, 3, 0, None, 0,
+                             None, None, None, None, None)
+    assert rc == -1
+    rc = lib.semicrf_viterbi(fake, None, fake, fake, None, None, None, None, 1, 8, 2, 3, 0, None, 0,
+                             fake, fake, fake, fake, None)
+    assert rc == -2
+    rc = lib.semicrf_viterbi(fake, None, fake, fake, None, None, None, None, 1, 8, 2, 3, 4 | 8, fake, 1 << 30,
+                             fake, fake, fake, fake, None)
+    assert rc == -1                                  # both storage types at once
+    assert lib.semicrf_entropies(None, None, None, 1, 8, 3, None, None, None) == -1
+    assert lib.semicrf_entropies(None, fake, None, 1, 8, 3, fake, None, None) == -1   # h_pos needs pos_marg
+    assert lib.semicrf_entropies(fake, None, None, 1, 8, 3, None, fake, None) == -1   # h_bdy needs bdy_post
+    assert lib.semicrf_entropies(fake, fake, None, 1, 0, 3, fake, fake, None) == -1
+
+
 def test_binding_requires_the_built_library(monkeypatch, tmp_path):
     import importlib
     mod = importlib.reload(sb)
