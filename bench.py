@@ -85,7 +85,11 @@ def main():
            torch.empty((K, C), dtype=torch.float32, device=dev),
            torch.empty((B, T, C), dtype=torch.float32, device=dev))
     if args.viterbi:
-        call = lambda: sb.semicrf_viterbi(emis, lengths, trans, dur)
+        nv = sb.semicrf_viterbi_workspace_bytes(B, T, K, C)
+        raw = torch.empty(nv + 256, dtype=torch.uint8, device=dev)
+        off = (-raw.data_ptr()) % 256
+        vws = raw[off:off + nv]
+        call = lambda: sb.semicrf_viterbi(emis, lengths, trans, dur, workspace=vws)
         for _ in range(args.warmup):
             o = call()
         torch.cuda.synchronize()
@@ -100,8 +104,10 @@ def main():
             "positions_per_s": w.positions / (ms * 1e-3), "n_gpus": 1, "steps": args.steps,
             "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
             "vs_baseline": None, "dtype": "f64", "data": "synthetic",
-            "config": {"workload": f"{w.name}: B={B} T={T} K={K} C={C} (workspace and outputs allocated inside "
-                                   f"the timed calls)"},
+            "config": {"workload": f"{w.name}: B={B} T={T} K={K} C={C} (output tensors allocated inside the "
+                                   f"timed calls)", "workspace_bytes": nv},
+            "scans_accepted_chunk_parallel": int(sb.semicrf_scan_report(vws, B, T, K, C, 0, False)[0][:, 0].sum().item()),
+            "scans_total": B,
             "score_mean": float(o[0].double().mean().item()), "segments": int(o[3].sum().item())}))
         return
     if args.boundary_terms:

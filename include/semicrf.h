@@ -194,8 +194,10 @@ int semicrf_fwd_bwd_boundary(const float *emis, const int32_t *lengths, const fl
  * scanned on its own after a warm-up from the state of a sequence that begins there.  Best
  * paths that have merged give states equal up to one additive constant, so each interval
  * boundary is checked entry by entry (-inf entries must coincide) after removing that
- * constant, to 1e-12 relative to the entries' size; the constants are chained in a fixed
- * order.  A sequence with a boundary that does not agree after the second, longer warm-up
+ * constant, to 1e-12 relative to the larger of the entry and the prefix sums of Eq. 2 there
+ * (the entries are differences of prefix sums, so that is the scale of their rounding); the
+ * constants are chained in a fixed order.  Intervals whose start did not agree are scanned
+ * once more after a longer warm-up; a sequence with a boundary that still does not agree
  * is rescanned sequentially inside the same call, and SEMICRF_SEQUENTIAL_SCAN forces that.
  * semicrf_scan_report with ckpt_interval = 0 and want_grad = 0 on this workspace reports
  * the outcome in column 0.  The trace-back (back-pointers of every node, pointer doubling,

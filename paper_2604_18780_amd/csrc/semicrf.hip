@@ -2440,13 +2440,23 @@ __global__ __launch_bounds__(64) void k_viterbi(Params p)
     vit_task<CT, NKW>(p, lds_raw, blockIdx.x, -1, 0);
 }
 
+// Largest disagreement at a chunk boundary that is accepted, relative to the larger of the entry
+// and the prefix sums at the boundary.
+constexpr double VIT_TOL = 1e-12;
+
 // The chunk-parallel scan: one wave per (sequence, checkpoint interval).
 template <int CT, int NKW>
 __global__ __launch_bounds__(64) void k_vit_spec(Params p, int warm, int tier)
 {
     extern __shared__ double lds_raw[];
     const int b = blockIdx.x / p.N, chunk = blockIdx.x % p.N;
-    if (tier > 0 && p.spec_ok[b * 2]) return;
+    if (tier > 0) {
+        // second pass: only the chunks whose warmed-up start disagreed with what the chunk before
+        // reached (chunk 0 starts exactly; by induction over the boundaries a chunk whose left
+        // boundary agrees is right up to its constant, so only these can be wrong)
+        if (p.spec_ok[b * 2] || chunk == 0) return;
+        if (p.spec_err[((size_t)b * 2) * (p.N + 1) + chunk] <= VIT_TOL) return;
+    }
     vit_task<CT, NKW>(p, lds_raw, b, chunk, warm);
 }
 
@@ -2478,13 +2488,23 @@ __global__ __launch_bounds__(64) void k_vit_cmp(Params p, int tier)
     }
     const double delta = v - A[KC + idx];
     double err = (v > -INFINITY && delta == delta && fabs(delta) < DBL_MAX) ? 0.0 : DBL_MAX;
+    // Every entry is a difference of prefix sums (r carries -S, V carries +S), so its rounding
+    // error scales with |S| here, not with the entry: measure relative to the larger of the two.
+    double smag = 1.0;
+    if (lane < C) {
+        const double2 lp = p.EI[((size_t)b * (p.T + 1) + (size_t)j * p.Delta) * C + lane];
+        if (fabs(lp.x) < DBL_MAX) smag = fmax(smag, fabs(lp.x));
+        if (fabs(lp.y) < DBL_MAX) smag = fmax(smag, fabs(lp.y));
+    }
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) smag = fmax(smag, __shfl_xor(smag, off));
 #pragma unroll 4
     for (int i = lane; i < KC + C; i += 64) {
         const double x = A2[i], y = A[i];
         if (x == -INFINITY || y == -INFINITY) {
             if (x != y) err = DBL_MAX;
         } else {
-            err = fmax(err, fabs(x - (y + delta)) / fmax(1.0, fmax(fabs(x), fabs(y + delta))));
+            err = fmax(err, fabs(x - (y + delta)) / fmax(smag, fmax(fabs(x), fabs(y + delta))));
         }
     }
 #pragma unroll
@@ -2498,7 +2518,6 @@ __global__ __launch_bounds__(64) void k_vit_cmp(Params p, int tier)
 
 // Accept or reject each sequence; chain the additive constants (ckYA[b][j] = what must be added
 // to the values stored by chunk j to get the true ones); best final label and score.
-constexpr double VIT_TOL = 1e-12;
 
 __global__ __launch_bounds__(64) void k_vit_fix(Params p, int tier)
 {
@@ -2673,7 +2692,23 @@ __global__ __launch_bounds__(NT) void k_vit_emit(Params p)
         lab[u] = c;
         st[u] = u == t - k ? 1 : 0;
     }
-    atomicAdd(&p.vnseg[b], 1);
+}
+
+// nseg[b] = number of start flags (zeroed by k_vit_bp): one integer atomic per 8192 tokens, not
+// one per segment, which would serialise on one address.
+constexpr int VCNT_TOK = 8192;
+
+__global__ __launch_bounds__(NT) void k_vit_count(Params p)
+{
+    const int b = blockIdx.y;
+    const int L = p.hdr[b].L;
+    const int32_t *st = p.vstarts + (size_t)b * p.T;
+    const int lo = blockIdx.x * VCNT_TOK, hi = min(L, lo + VCNT_TOK);
+    int cnt = 0;
+    for (int u = lo + threadIdx.x; u < hi; u += NT) cnt += st[u];
+#pragma unroll
+    for (int off = 32; off; off >>= 1) cnt += __shfl_xor(cnt, off);
+    if ((threadIdx.x & 63) == 0 && cnt) atomicAdd(&p.vnseg[b], cnt);
 }
 
 // ---------------------------------------------------------------------------
@@ -3330,7 +3365,11 @@ int launch_viterbi_k(const Params &p, hipStream_t st)
         return SEMICRF_ELAUNCH;
     if (p.spec) {
         // chunk-parallel scan with two warm-up lengths, as for the sum recurrences
-        const int warm[2] = {2 * p.K < 32 ? 32 : 2 * p.K, 8 * p.K < 64 ? 64 : 8 * p.K};
+        int warm[2] = {2 * p.K < 32 ? 32 : 2 * p.K, 8 * p.K < 64 ? 64 : 8 * p.K};
+        if (const char *e = getenv("SEMICRF_VITERBI_WARMUP")) {  // tuning knob: first warm-up length
+            const int w = atoi(e);
+            if (w > 0) warm[0] = w, warm[1] = 4 * w;
+        }
         for (int tier = 0; tier < 2; ++tier) {
             hipLaunchKernelGGL((k_vit_spec<CT, NKW>), dim3(p.B * p.N), dim3(64), lds, st, p, warm[tier], tier);
             hipLaunchKernelGGL(k_vit_cmp, dim3(p.N, p.B), dim3(64), 0, st, p, tier);
@@ -3404,6 +3443,7 @@ int run_viterbi(Params p, void *workspace, size_t workspace_bytes, hipStream_t s
     for (int i = 0; i < rounds; ++i)
         hipLaunchKernelGGL(k_vit_round, dim3(nblk, p.B), dim3(NT), 0, st, p, i & 1, i == 0 ? 1 : 0);
     hipLaunchKernelGGL(k_vit_emit, dim3(nblk, p.B), dim3(NT), 0, st, p);
+    hipLaunchKernelGGL(k_vit_count, dim3((p.T + VCNT_TOK - 1) / VCNT_TOK, p.B), dim3(NT), 0, st, p);
     return check_launch();
 }
 
