@@ -58,8 +58,9 @@ typedef enum {
 #define SEMICRF_CENTER 1u
 /* flags bit 1: run the forward scan of Algorithm 1 and the backward scan of Algorithm 3
  * strictly sequentially.  By default both are run chunk-parallel: every checkpoint interval
- * is scanned as an independent task that first warms its ring up over the max(4K,32)
- * positions before the interval, starting from the state of a sequence that begins there.
+ * is scanned as an independent task that first warms its ring up over the max(2K,32)
+ * positions before the interval (max(8K,64) in a second attempt for what the first did not
+ * verify), starting from the state of a sequence that begins there.
  * The state each task reaches at its end is then compared, entry by entry and up to the
  * common scale factor, with the warmed-up state its neighbour started from; a (sequence,
  * direction) is accepted only if every one of its boundaries agrees to 1e-10 (relative),

@@ -13,7 +13,9 @@ enumeration, the K=1 linear-chain CRF, closed forms, finite differences,
 marginal invariants, the centring/duration-prior identity of Eq. 5, the toy
 baseline table; the boundary terms of Eq. 4 by enumeration with those terms, by
 finite differences, by the K=1 chain with start/end scores and by the identity
-between scalar boundaries and projections at the first/last token).
+between scalar boundaries and projections at the first/last token; the
+duration-dependent transitions by enumeration, by the reduction to one shared
+matrix, by finite differences and by the identity with the duration bias).
 """
 from __future__ import annotations
 
@@ -51,6 +53,10 @@ def _load():
         lib.semicrf_oracle_fwd_bwd_boundary.restype = ctypes.c_int
         lib.semicrf_oracle_fwd_bwd_boundary.argtypes = ([dp, ip, dp, dp, dp] + [dp] * 4 + [ctypes.c_int] * 6
                                                         + [dp] * 16)
+        lib.semicrf_oracle_fwd_bwd_durtrans.restype = ctypes.c_int
+        lib.semicrf_oracle_fwd_bwd_durtrans.argtypes = [dp, ip, dp, dp, dp] + [ctypes.c_int] * 6 + [dp] * 5
+        lib.semicrf_oracle_logz_durtrans.restype = ctypes.c_int
+        lib.semicrf_oracle_logz_durtrans.argtypes = [dp, ip, dp, dp] + [ctypes.c_int] * 6 + [dp]
         lib.semicrf_oracle_viterbi.restype = ctypes.c_int
         lib.semicrf_oracle_viterbi.argtypes = [dp, ip, dp, dp] + [dp] * 4 + [ctypes.c_int] * 6 + [dp, ip, ip, ip]
         lib.semicrf_oracle_logz_boundary.restype = ctypes.c_int
@@ -267,3 +273,54 @@ def path_score(emis, L, trans, dur, labels, starts, center=True, proj_start=None
         prev = c
     return total
 
+
+
+def _lengths_ptr(lengths, B):
+    if lengths is None:
+        return None, None
+    lengths = np.ascontiguousarray(np.asarray(lengths), dtype=np.int32)
+    assert lengths.shape == (B,)
+    return lengths, lengths.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def fwd_bwd_durtrans(emis, lengths, trans, dur, grad_logz=None, center=True, threads=0) -> OracleResult:
+    """Duration-dependent transitions: trans [K,C,C] (row k-1, source label, destination label)
+    replaces trans[c',c] in the potential.  grad_trans of the result is [K,C,C]."""
+    lib = _load()
+    emis = _as_f64(emis)
+    B, T, C = emis.shape
+    trans = _as_f64(trans)
+    dur = _as_f64(dur)
+    K = dur.shape[0]
+    assert trans.shape == (K, C, C) and dur.shape == (K, C)
+    keep, lp = _lengths_ptr(lengths, B)
+    w = None if grad_logz is None else _as_f64(grad_logz)
+    logz = np.zeros(B)
+    gE = np.zeros((B, T, C))
+    pm = np.zeros((B, T, C))
+    gTr = np.zeros((K, C, C))
+    gD = np.zeros((K, C))
+    rc = lib.semicrf_oracle_fwd_bwd_durtrans(_dptr(emis), lp, _dptr(trans), _dptr(dur), _dptr(w), B, T, K, C,
+                                             int(bool(center)), int(threads), _dptr(logz), _dptr(gE), _dptr(pm),
+                                             _dptr(gTr), _dptr(gD))
+    if rc < 0:
+        raise ValueError("semicrf_oracle_fwd_bwd_durtrans: bad arguments")
+    return OracleResult(logz, gE, pm, gTr, gD, None, None, rc)
+
+
+def logz_durtrans(emis, lengths, trans, dur, center=True, threads=0) -> np.ndarray:
+    """Forward only with trans [K,C,C]."""
+    lib = _load()
+    emis = _as_f64(emis)
+    B, T, C = emis.shape
+    trans = _as_f64(trans)
+    dur = _as_f64(dur)
+    K = dur.shape[0]
+    assert trans.shape == (K, C, C) and dur.shape == (K, C)
+    keep, lp = _lengths_ptr(lengths, B)
+    logz = np.zeros(B)
+    rc = lib.semicrf_oracle_logz_durtrans(_dptr(emis), lp, _dptr(trans), _dptr(dur), B, T, K, C,
+                                          int(bool(center)), int(threads), _dptr(logz))
+    if rc < 0:
+        raise ValueError("semicrf_oracle_logz_durtrans: bad arguments")
+    return logz

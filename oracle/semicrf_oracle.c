@@ -15,7 +15,9 @@
  *     Projections" section (start score of the segment's first token, end score of
  *     its last token; zero when absent), to which the optional scalar sequence
  *     boundaries pi_start[c] / pi_end[c] are added at token 0 / token L-1
- *     (appendix on boundary handling, composition rule);
+ *     (appendix on boundary handling, composition rule); optionally trans carries a
+ *     duration index, trans[k-1,c',c] (the [K,C,C] transition whose gradient the
+ *     gradient-workspace section allocates), and so does its gradient;
  *   - log-forward messages alpha[t,c] by the recurrence of Algorithm 1
  *     (alpha[0,:] = 0, k <= min(K,t)) but with the FULL table kept: no ring
  *     buffer, no checkpoints, no normalisation;
@@ -58,8 +60,11 @@ static double lse_pair_guard(double m, double s) {
     return m + log(s);
 }
 
+/* tks = 0: trans is [C,C] as in Eq. 4; tks = C*C: trans is [K,C,C], one matrix per duration
+ * (the duration-indexed transition of the gradient-workspace section). */
 #define PSI(t, k, c, cp) (S[(size_t)(t) * C + (c)] - S[(size_t)((t) - (k)) * C + (c)] \
-                          + dur[(size_t)((k) - 1) * C + (c)] + trans[(size_t)(cp) * C + (c)] \
+                          + dur[(size_t)((k) - 1) * C + (c)] \
+                          + trans[(size_t)((k) - 1) * tks + (size_t)(cp) * C + (c)] \
                           + bs[(size_t)((t) - (k)) * C + (c)] + be[(size_t)((t) - 1) * C + (c)])
 
 /* Eq. 1 (masked mean over the L valid positions) and Eq. 2 (S[0,c] = 0,
@@ -81,7 +86,7 @@ static void oracle_prefix_sums(const double *f, int L, int C, int center, double
 
 /* Algorithm 1 with the whole table kept (alpha[0,:] = 0); returns
  * logZ = LSE_c alpha[L,c]. */
-static double oracle_forward(const double *S, const double *trans, const double *dur,
+static double oracle_forward(const double *S, const double *trans, size_t tks, const double *dur,
                              const double *bs, const double *be,
                              int L, int K, int C, int inner_threads, double *alpha)
 {
@@ -139,7 +144,8 @@ static void oracle_boundary_scores(const double *ps, const double *pe, const dou
 /* One sequence.  All arrays are fp64.  Optional inputs and outputs may be NULL. */
 static void oracle_sequence(const double *f,      /* [T,C] emissions of this sequence */
                             int L, int T, int K, int C, int center, double w,
-                            const double *trans,  /* [C,C] source-major: trans[c'*C+c] */
+                            const double *trans,  /* [C,C] source-major: trans[c'*C+c]; or [K,C,C] */
+                            size_t tks,           /* 0, or C*C when trans has one matrix per duration */
                             const double *dur,    /* [K,C] row k-1 */
                             const double *ps,     /* [T,C] start projections or NULL */
                             const double *pe,     /* [T,C] end projections or NULL */
@@ -149,7 +155,7 @@ static void oracle_sequence(const double *f,      /* [T,C] emissions of this seq
                             double *logz_out,
                             double *gE,           /* [T,C] */
                             double *pm,           /* [T,C] */
-                            double *gTr,          /* [C,C]   this sequence only, weighted by w */
+                            double *gTr,          /* [C,C] or [K,C,C], this sequence only, weighted by w */
                             double *gD,           /* [K,C]   this sequence only, weighted by w */
                             double *S_out,        /* [T+1,C] or NULL */
                             double *alpha_out,    /* [T+1,C] or NULL */
@@ -171,7 +177,7 @@ static void oracle_sequence(const double *f,      /* [T,C] emissions of this seq
     oracle_boundary_scores(ps, pe, pis, pie, L, C, &bs, &be);
 
     oracle_prefix_sums(f, L, C, center, nu, S);
-    double logz = oracle_forward(S, trans, dur, bs, be, L, K, C, inner_threads, alpha);
+    double logz = oracle_forward(S, trans, tks, dur, bs, be, L, K, C, inner_threads, alpha);
     *logz_out = logz;
 
     /* Algorithm 3 recurrence with the whole table kept: beta[L,:] = 0. */
@@ -197,7 +203,7 @@ static void oracle_sequence(const double *f,      /* [T,C] emissions of this seq
 
     /* Marginals and expected sufficient statistics.  The destination label c
      * is the outer loop so that every accumulator element is owned by one c. */
-    memset(gTr, 0, sizeof(double) * (size_t)C * C);
+    memset(gTr, 0, sizeof(double) * (tks ? (size_t)K * C * C : (size_t)C * C));
     memset(gD, 0, sizeof(double) * (size_t)K * C);
     if (gPs) memset(gPs, 0, sizeof(double) * (size_t)T * C);
     if (gPe) memset(gPe, 0, sizeof(double) * (size_t)T * C);
@@ -210,7 +216,7 @@ static void oracle_sequence(const double *f,      /* [T,C] emissions of this seq
                     double lm = alpha[(size_t)t * C + cp] + PSI(t + k, k, c, cp)
                                 + beta[(size_t)(t + k) * C + c] - logz;
                     double mu = exp(lm);
-                    gTr[(size_t)cp * C + c] += w * mu;
+                    gTr[(size_t)(k - 1) * tks + (size_t)cp * C + c] += w * mu;
                     gD[(size_t)(k - 1) * C + c] += w * mu;
                     gS[(size_t)(t + k) * C + c] += mu;
                     gS[(size_t)t * C + c] -= mu;
@@ -279,8 +285,8 @@ static void oracle_sequence(const double *f,      /* [T,C] emissions of this seq
  *   grad_dur [K,C]; optional per-sequence grad_trans_b [B,C,C], grad_dur_b
  *   [B,K,C]; optional tables S, alpha, beta, gS each [B,T+1,C].
  */
-int semicrf_oracle_fwd_bwd_boundary(const double *emis, const int32_t *lengths,
-                                    const double *trans, const double *dur, const double *grad_logz,
+static int oracle_batch(const double *emis, const int32_t *lengths,
+                                    const double *trans, int per_duration, const double *dur, const double *grad_logz,
                                     const double *proj_start, const double *proj_end,
                                     const double *pi_start, const double *pi_end,
                                     int B, int T, int K, int C, int center, int threads,
@@ -303,7 +309,9 @@ int semicrf_oracle_fwd_bwd_boundary(const double *emis, const int32_t *lengths,
 #ifdef _OPENMP
     omp_set_max_active_levels(2);
 #endif
-    size_t cc = (size_t)C * C, kc = (size_t)K * C, tc = (size_t)T * C, t1c = (size_t)(T + 1) * C;
+    size_t tks = per_duration ? (size_t)C * C : 0;
+    size_t cc = per_duration ? (size_t)K * C * C : (size_t)C * C;
+    size_t kc = (size_t)K * C, tc = (size_t)T * C, t1c = (size_t)(T + 1) * C;
     double *gTr_b = grad_trans_b ? grad_trans_b : (double *)malloc(sizeof(double) * cc * B);
     double *gD_b = grad_dur_b ? grad_dur_b : (double *)malloc(sizeof(double) * kc * B);
     /* the scalar-boundary gradients are read off the projection gradients */
@@ -317,7 +325,7 @@ int semicrf_oracle_fwd_bwd_boundary(const double *emis, const int32_t *lengths,
         if (L < 0) L = 0;
         if (L > T) L = T;
         double w = grad_logz ? grad_logz[b] : 1.0;
-        oracle_sequence(emis + tc * b, L, T, K, C, center, w, trans, dur,
+        oracle_sequence(emis + tc * b, L, T, K, C, center, w, trans, tks, dur,
                         proj_start ? proj_start + tc * b : NULL, proj_end ? proj_end + tc * b : NULL,
                         pi_start, pi_end, inner,
                         logz + b, grad_emis + tc * b, pos_marg + tc * b,
@@ -359,6 +367,42 @@ int semicrf_oracle_fwd_bwd_boundary(const double *emis, const int32_t *lengths,
     return outer * inner;
 }
 
+int semicrf_oracle_fwd_bwd_boundary(const double *emis, const int32_t *lengths,
+                                    const double *trans, const double *dur, const double *grad_logz,
+                                    const double *proj_start, const double *proj_end,
+                                    const double *pi_start, const double *pi_end,
+                                    int B, int T, int K, int C, int center, int threads,
+                                    double *logz, double *grad_emis, double *pos_marg,
+                                    double *grad_trans, double *grad_dur,
+                                    double *grad_trans_b, double *grad_dur_b,
+                                    double *S_out, double *alpha_out, double *beta_out, double *gS_out,
+                                    double *grad_proj_start, double *grad_proj_end,
+                                    double *grad_pi_start, double *grad_pi_end, double *bdy_post)
+{
+    return oracle_batch(emis, lengths, trans, 0, dur, grad_logz, proj_start, proj_end, pi_start, pi_end,
+                        B, T, K, C, center, threads, logz, grad_emis, pos_marg, grad_trans, grad_dur,
+                        grad_trans_b, grad_dur_b, S_out, alpha_out, beta_out, gS_out,
+                        grad_proj_start, grad_proj_end, grad_pi_start, grad_pi_end, bdy_post);
+}
+
+/*
+ * Duration-dependent transitions: trans [K,C,C], trans[((k-1)*C + c')*C + c] replaces
+ * trans[c',c] in the potential, i.e. psi(t,k,c,c') = S[t,c] - S[t-k,c] + dur[k-1,c] + trans[k-1,c',c];
+ * grad_trans [K,C,C] is then the duration-indexed expected count sum_b w_b sum_t mu_b(t,k,c,c')
+ * (the transition gradient with a duration index of the gradient-workspace section).  No
+ * boundary terms.  Everything else as above.
+ */
+int semicrf_oracle_fwd_bwd_durtrans(const double *emis, const int32_t *lengths,
+                                    const double *trans, const double *dur, const double *grad_logz,
+                                    int B, int T, int K, int C, int center, int threads,
+                                    double *logz, double *grad_emis, double *pos_marg,
+                                    double *grad_trans, double *grad_dur)
+{
+    return oracle_batch(emis, lengths, trans, 1, dur, grad_logz, NULL, NULL, NULL, NULL,
+                        B, T, K, C, center, threads, logz, grad_emis, pos_marg, grad_trans, grad_dur,
+                        NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL);
+}
+
 /* The three-term form of Eq. 4 (no boundary terms). */
 int semicrf_oracle_fwd_bwd(const double *emis, const int32_t *lengths,
                            const double *trans, const double *dur, const double *grad_logz,
@@ -378,8 +422,8 @@ int semicrf_oracle_fwd_bwd(const double *emis, const int32_t *lengths,
  * Forward only: logZ per sequence (same recurrence, same arithmetic).
  * Used for finite-difference checks, where the backward pass is not wanted.
  */
-int semicrf_oracle_logz_boundary(const double *emis, const int32_t *lengths,
-                                 const double *trans, const double *dur,
+static int oracle_logz_batch(const double *emis, const int32_t *lengths,
+                                 const double *trans, int per_duration, const double *dur,
                                  const double *proj_start, const double *proj_end,
                                  const double *pi_start, const double *pi_end,
                                  int B, int T, int K, int C, int center, int threads, double *logz)
@@ -404,10 +448,29 @@ int semicrf_oracle_logz_boundary(const double *emis, const int32_t *lengths,
         oracle_boundary_scores(proj_start ? proj_start + (size_t)T * C * b : NULL,
                                proj_end ? proj_end + (size_t)T * C * b : NULL, pi_start, pi_end, L, C, &bs, &be);
         oracle_prefix_sums(f, L, C, center, nu, S);
-        logz[b] = oracle_forward(S, trans, dur, bs, be, L, K, C, 1, alpha);
+        logz[b] = oracle_forward(S, trans, per_duration ? (size_t)C * C : 0, dur, bs, be, L, K, C, 1, alpha);
         free(nu); free(S); free(alpha); free(bs); free(be);
     }
     return outer;
+}
+
+int semicrf_oracle_logz_boundary(const double *emis, const int32_t *lengths,
+                                 const double *trans, const double *dur,
+                                 const double *proj_start, const double *proj_end,
+                                 const double *pi_start, const double *pi_end,
+                                 int B, int T, int K, int C, int center, int threads, double *logz)
+{
+    return oracle_logz_batch(emis, lengths, trans, 0, dur, proj_start, proj_end, pi_start, pi_end,
+                             B, T, K, C, center, threads, logz);
+}
+
+/* Forward only with duration-dependent transitions trans [K,C,C]. */
+int semicrf_oracle_logz_durtrans(const double *emis, const int32_t *lengths,
+                                 const double *trans, const double *dur,
+                                 int B, int T, int K, int C, int center, int threads, double *logz)
+{
+    return oracle_logz_batch(emis, lengths, trans, 1, dur, NULL, NULL, NULL, NULL,
+                             B, T, K, C, center, threads, logz);
 }
 
 int semicrf_oracle_logz(const double *emis, const int32_t *lengths,
@@ -435,6 +498,7 @@ int semicrf_oracle_viterbi(const double *emis, const int32_t *lengths,
                            int B, int T, int K, int C, int center, int threads,
                            double *score, int32_t *labels, int32_t *starts, int32_t *nseg)
 {
+    const size_t tks = 0; /* one transition matrix for every duration */
     if (B < 1 || T < 1 || K < 1 || C < 1) return -1;
     int nthreads = 1;
 #ifdef _OPENMP

@@ -2531,16 +2531,28 @@ __global__ __launch_bounds__(64) void k_vit_fix(Params p, int tier)
     for (int j = 1 + lane; j < nint; j += 64) worst = fmax(worst, p.spec_err[so + j]);
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) worst = fmax(worst, __shfl_xor(worst, o));
-    // prefix sums of the constants, in boundary order (lane 0; a few hundred terms)
+    // prefix sums of the constants in a fixed order: lane l owns boundaries 1 + l*per .. l*per + per,
+    // sums them in order, the lane totals are scanned across the wave, then every lane walks its own
     double total = 0.0;
-    if (lane == 0) {
-        off[0] = 0.0;
-        for (int j = 1; j < nint; ++j) {
-            total += p.spec_lr[so + j];
-            off[j] = total;
+    {
+        const int per = (max(nint - 1, 0) + 63) / 64;
+        const int j0 = 1 + lane * per, j1 = min(j0 + per, nint);
+        double mine = 0.0;
+        for (int j = j0; j < j1; ++j) mine += p.spec_lr[so + j];
+        double incl = mine;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const double up = __shfl_up(incl, o);
+            if (lane >= o) incl += up;
         }
+        double run = incl - mine;
+        for (int j = j0; j < j1; ++j) {
+            run += p.spec_lr[so + j];
+            off[j] = run;
+        }
+        if (lane == 0) off[0] = 0.0;
+        total = __shfl(incl, 63);
     }
-    total = __shfl(total, 0);
     const bool ok = worst <= VIT_TOL;
     if (ok) {
         double best = -INFINITY;

@@ -666,3 +666,145 @@ def test_viterbi_ragged_bounds_and_zero_temperature_limit():
     lz_hot = oracle.logz(fac * emis, lengths, fac * trans, fac * dur)
     for b in range(2):
         assert abs(lz_hot[b] / fac - score[b]) < 0.2
+
+
+# --------------------------------------------------------------------------
+# P13  duration-dependent transitions trans[k-1,c',c] (the transition gradient with a
+#      duration index of the gradient-workspace section)
+# --------------------------------------------------------------------------
+def brute_force_durtrans(emis, L, trans3, dur, center):
+    """Explicit enumeration with one transition matrix per duration."""
+    T, C = emis.shape
+    K = dur.shape[0]
+    nu = emis[:L].mean(0) if (center and L > 0) else np.zeros(C)
+    fbar = emis - nu
+    Z = 0.0
+    gTr = np.zeros((K, C, C))
+    gD = np.zeros((K, C))
+    pm = np.zeros((T, C))
+    for comp in compositions(L, K):
+        n = len(comp)
+        for c0 in range(C):
+            for labs in itertools.product(range(C), repeat=n):
+                score, prev, s = 0.0, c0, 0
+                for k, c in zip(comp, labs):
+                    score += trans3[k - 1, prev, c] + dur[k - 1, c] + fbar[s:s + k, c].sum()
+                    prev = c
+                    s += k
+                wgt = math.exp(score)
+                Z += wgt
+                prev, s = c0, 0
+                for k, c in zip(comp, labs):
+                    gTr[k - 1, prev, c] += wgt
+                    gD[k - 1, c] += wgt
+                    pm[s:s + k, c] += wgt
+                    prev = c
+                    s += k
+    return math.log(Z), gTr / Z, gD / Z, pm / Z
+
+
+def rand_trans3(seed, K, C):
+    return 0.7 * np.random.default_rng(seed).standard_normal((K, C, C))
+
+
+@pytest.mark.parametrize("T,K,C,center", [(5, 3, 2, True), (6, 4, 2, False), (4, 2, 3, True),
+                                          (6, 6, 2, True), (5, 1, 3, True), (3, 5, 2, False)])
+def test_durtrans_brute_force_enumeration(T, K, C, center):
+    emis, _, _, dur = rand_case(300 + T * 10 + K, 1, T, K, C)
+    trans3 = rand_trans3(301 + T, K, C)
+    r = oracle.fwd_bwd_durtrans(emis, None, trans3, dur, center=center)
+    lz, gTr, gD, pm = brute_force_durtrans(emis[0], T, trans3, dur, center)
+    assert abs(r.logz[0] - lz) < 1e-12 * max(1, abs(lz))
+    assert np.allclose(r.grad_trans, gTr, atol=1e-10)
+    assert np.allclose(r.grad_dur, gD, atol=1e-10)
+    assert np.allclose(r.pos_marg[0], pm, atol=1e-10)
+    gE = pm - (pm.mean(0) if center else 0.0)
+    assert np.allclose(r.grad_emis[0], gE, atol=1e-10)
+    assert abs(oracle.logz_durtrans(emis, None, trans3, dur, center=center)[0] - lz) < 1e-12 * max(1, abs(lz))
+
+
+def test_durtrans_ragged_and_weighted():
+    T, K, C = 6, 3, 2
+    emis, _, _, dur = rand_case(17, 3, T, K, C)
+    trans3 = rand_trans3(18, K, C)
+    lengths = np.array([6, 3, 1], np.int32)
+    w = np.array([0.5, -2.0, 3.0])
+    r = oracle.fwd_bwd_durtrans(emis, lengths, trans3, dur, grad_logz=w)
+    gTr = np.zeros((K, C, C))
+    gD = np.zeros((K, C))
+    for b in range(3):
+        L = int(lengths[b])
+        lz, tr_b, d_b, pm = brute_force_durtrans(emis[b], L, trans3, dur, True)
+        assert abs(r.logz[b] - lz) < 1e-12
+        assert np.allclose(r.pos_marg[b], pm, atol=1e-10)
+        assert np.all(r.pos_marg[b, L:] == 0) and np.all(r.grad_emis[b, L:] == 0)
+        assert np.allclose(r.grad_emis[b, :L], w[b] * (pm[:L] - pm[:L].mean(0)), atol=1e-10)
+        gTr += w[b] * tr_b
+        gD += w[b] * d_b
+    assert np.allclose(r.grad_trans, gTr, atol=1e-10)
+    assert np.allclose(r.grad_dur, gD, atol=1e-10)
+
+
+def test_durtrans_reduces_to_one_shared_matrix_and_absorbs_the_duration_bias():
+    B, T, K, C = 3, 11, 4, 3
+    emis, lengths, trans, dur = rand_case(41, B, T, K, C, ragged=True)
+    w = np.array([1.0, 0.3, -1.2])
+    ref = oracle.fwd_bwd(emis, lengths, trans, dur, grad_logz=w)
+    # the same matrix for every duration is the potential of Eq. 4
+    r = oracle.fwd_bwd_durtrans(emis, lengths, np.broadcast_to(trans, (K, C, C)).copy(), dur, grad_logz=w)
+    assert np.allclose(r.logz, ref.logz, rtol=1e-13)
+    assert np.allclose(r.grad_trans.sum(0), ref.grad_trans, atol=1e-11)
+    assert np.allclose(r.grad_dur, ref.grad_dur, atol=1e-11)
+    assert np.allclose(r.pos_marg, ref.pos_marg, atol=1e-12)
+    assert np.allclose(r.grad_emis, ref.grad_emis, atol=1e-12)
+    # dur[k,c] and trans[k,c',c] enter the potential together: moving the bias into the
+    # transitions changes nothing, and the bias gradient is the transition gradient summed
+    # over the source label
+    trans3 = rand_trans3(42, K, C)
+    a = oracle.fwd_bwd_durtrans(emis, lengths, trans3, dur, grad_logz=w)
+    b = oracle.fwd_bwd_durtrans(emis, lengths, trans3 + dur[:, None, :], np.zeros_like(dur), grad_logz=w)
+    assert np.allclose(a.logz, b.logz, rtol=1e-13)
+    assert np.allclose(a.grad_trans, b.grad_trans, atol=1e-11)
+    assert np.allclose(a.grad_dur, a.grad_trans.sum(1), atol=1e-11)
+    # every segment has exactly one (duration, source, destination):
+    # with unit weights the transition gradient sums to the expected number of segments,
+    # which is what the duration gradient sums to as well
+    u = oracle.fwd_bwd_durtrans(emis, lengths, trans3, dur)
+    assert abs(u.grad_trans.sum() - u.grad_dur.sum()) < 1e-10
+    durw = (u.grad_dur * np.arange(1, K + 1)[:, None]).sum()
+    assert abs(durw - lengths.sum()) < 1e-9          # durations tile the sequences
+
+
+def test_durtrans_finite_differences():
+    B, T, K, C = 2, 8, 3, 3
+    emis, _, _, dur = rand_case(51, B, T, K, C)
+    trans3 = rand_trans3(52, K, C)
+    lengths = np.array([8, 5], np.int32)
+    w = np.array([1.3, -0.7])
+    r = oracle.fwd_bwd_durtrans(emis, lengths, trans3, dur, grad_logz=w)
+
+    def loss(e, tr, d):
+        return float((w * oracle.logz_durtrans(e, lengths, tr, d)).sum())
+
+    eps = 1e-6
+    for arr, grad, which in ((emis, r.grad_emis, 0), (trans3, r.grad_trans, 1), (dur, r.grad_dur, 2)):
+        g = np.zeros_like(arr)
+        for idx in np.ndindex(*arr.shape):
+            p, m = arr.copy(), arr.copy()
+            p[idx] += eps
+            m[idx] -= eps
+            args_p = [emis, trans3, dur]
+            args_m = [emis, trans3, dur]
+            args_p[which], args_m[which] = p, m
+            g[idx] = (loss(*args_p) - loss(*args_m)) / (2 * eps)
+        assert np.allclose(grad, g, atol=2e-8), which
+
+
+def test_durtrans_pins_can_see_a_transposed_matrix_or_a_shifted_duration_index():
+    T, K, C = 5, 3, 2
+    emis, _, _, dur = rand_case(61, 1, T, K, C)
+    trans3 = rand_trans3(62, K, C)
+    lz, *_ = brute_force_durtrans(emis[0], T, trans3, dur, True)
+    wrong_t = oracle.logz_durtrans(emis, None, trans3.transpose(0, 2, 1).copy(), dur)[0]
+    wrong_k = oracle.logz_durtrans(emis, None, np.roll(trans3, 1, axis=0).copy(), dur)[0]
+    assert abs(wrong_t - lz) > 1e-4 and abs(wrong_k - lz) > 1e-4
