@@ -213,6 +213,38 @@ int semicrf_viterbi(const float *emis, const int32_t *lengths, const float *tran
                     void *stream);
 
 /*
+ * Duration-dependent transitions: one transition matrix per duration, the generality whose
+ * gradient the paper's gradient-workspace section allocates (a transition gradient with a
+ * duration index).  The edge potential is that of Eq. 4 with trans3[k-1,c',c] in place of
+ * trans[c',c]:
+ *     psi(t,k,c,c') = S[t,c] - S[t-k,c] + dur[k-1,c] + trans3[k-1,c',c]      (no boundary terms)
+ *   trans3      [K,C,C] float  trans3[((k-1)*C + c_src)*C + c_dst]
+ *   grad_trans3 [K,C,C] float  sum_b w_b * sum_t mu_b(t,k,c,c')  at [((k-1)*C + c')*C + c]
+ *   grad_dur    [K,C]   float  its sum over the source label (dur and trans3 enter together)
+ * Everything else (emis, lengths, dur, grad_logz, flags, logz, grad_emis, pos_marg, stream,
+ * errors) as for semicrf_logz_fwd / semicrf_fwd_bwd.  The transition no longer factors out
+ * of the sum over durations, so a position costs K*C*C multiply-adds per recurrence.
+ * Supported sizes: C <= 64, K <= 8 * floor(1024 / C), and C*C * ceil(K/64) <= 640 or
+ * C*C * ceil(K/32) <= 1024 (one label pair per thread, at most 64 durations of it in
+ * registers); SEMICRF_EUNSUPPORTED otherwise.  Workspace: semicrf_durtrans_workspace_bytes
+ * (that of semicrf_workspace_bytes plus the K*C*C table, the forward messages, O(T*C), and
+ * up to 512 partial gradient tables).  semicrf_scan_report applies to this workspace too.
+ */
+int semicrf_durtrans_workspace_bytes(int B, int T, int K, int C, int ckpt_interval, int want_grad,
+                                     size_t *bytes);
+
+int semicrf_logz_fwd_durtrans(const float *emis, const int32_t *lengths, const float *trans3,
+                              const float *dur, int B, int T, int K, int C, int ckpt_interval,
+                              unsigned flags, void *workspace, size_t workspace_bytes, float *logz,
+                              void *stream);
+
+int semicrf_fwd_bwd_durtrans(const float *emis, const int32_t *lengths, const float *trans3,
+                             const float *dur, const float *grad_logz, int B, int T, int K, int C,
+                             int ckpt_interval, unsigned flags, void *workspace, size_t workspace_bytes,
+                             float *logz, float *grad_emis, float *grad_trans3, float *grad_dur,
+                             float *pos_marg, void *stream);
+
+/*
  * The two entropies of the paper's boundary-entropy paragraph, from outputs of the calls above
  * (device pointers; needs no workspace):
  *   h_pos [B] float or NULL: mean over the L_b tokens of -sum_c pos_marg[b,u,c] ln pos_marg[b,u,c]

@@ -19,7 +19,8 @@ EXPORTS = ("semicrf_version", "semicrf_strerror", "semicrf_workspace_bytes",
            "semicrf_cum_scores", "semicrf_logz_fwd", "semicrf_fwd_bwd", "semicrf_fwd_bwd_profiled",
            "semicrf_scan_report", "semicrf_ckpt_interval", "semicrf_logz_fwd_boundary",
            "semicrf_fwd_bwd_boundary", "semicrf_entropies", "semicrf_viterbi_workspace_bytes",
-           "semicrf_viterbi")
+           "semicrf_viterbi", "semicrf_durtrans_workspace_bytes", "semicrf_logz_fwd_durtrans",
+           "semicrf_fwd_bwd_durtrans")
 SEMICRF_CENTER = 1
 SEMICRF_SEQUENTIAL_SCAN = 2
 SEMICRF_EMIS_F16 = 4
@@ -71,6 +72,12 @@ def load():
     lib.semicrf_viterbi.argtypes = [vp] * 8 + [ci, ci, ci, ci, cu, vp, sz] + [vp] * 5
     lib.semicrf_entropies.restype = ci
     lib.semicrf_entropies.argtypes = [vp, vp, vp, ci, ci, ci, vp, vp, vp]
+    lib.semicrf_durtrans_workspace_bytes.restype = ci
+    lib.semicrf_durtrans_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci, ctypes.POINTER(sz)]
+    lib.semicrf_logz_fwd_durtrans.restype = ci
+    lib.semicrf_logz_fwd_durtrans.argtypes = lib.semicrf_logz_fwd.argtypes
+    lib.semicrf_fwd_bwd_durtrans.restype = ci
+    lib.semicrf_fwd_bwd_durtrans.argtypes = lib.semicrf_fwd_bwd.argtypes
     lib.semicrf_scan_report.restype = ci
     lib.semicrf_scan_report.argtypes = [vp, sz, ci, ci, ci, ci, ci, ci, vp, vp, vp]
     _lib = lib
@@ -258,6 +265,58 @@ def semicrf_viterbi(emis, lengths, trans, dur, proj_start=None, proj_end=None, p
                                   B, T, K, C, flags, workspace.data_ptr(), workspace.numel(), score.data_ptr(),
                                   labels.data_ptr(), starts.data_ptr(), nseg.data_ptr(), _stream()))
     return score, labels, starts, nseg
+
+
+def semicrf_durtrans_workspace_bytes(B, T, K, C, ckpt_interval=0, want_grad=True) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().semicrf_durtrans_workspace_bytes(B, T, K, C, ckpt_interval, int(bool(want_grad)),
+                                                   ctypes.byref(out)))
+    return out.value
+
+
+def alloc_durtrans_workspace(B, T, K, C, ckpt_interval, want_grad, device):
+    n = semicrf_durtrans_workspace_bytes(B, T, K, C, ckpt_interval, want_grad)
+    ws = torch.empty(n + 256, dtype=torch.uint8, device=device)
+    off = (-ws.data_ptr()) % 256
+    return ws[off:off + n]
+
+
+def semicrf_logz_fwd_durtrans(emis, lengths, trans3, dur, ckpt_interval=0, flags=SEMICRF_CENTER, workspace=None):
+    """trans3 [K,C,C]: one transition matrix per duration.  Returns logz [B]."""
+    B, T, C = emis.shape
+    K = dur.shape[0]
+    if workspace is None:
+        workspace = alloc_durtrans_workspace(B, T, K, C, ckpt_interval, False, emis.device)
+    logz = torch.empty(B, dtype=torch.float32, device=emis.device)
+    ep, flags = _emis(emis, flags)
+    _check(load().semicrf_logz_fwd_durtrans(ep, _ptr(lengths, torch.int32), _ptr(trans3, torch.float32),
+                                            _ptr(dur, torch.float32), B, T, K, C, ckpt_interval, flags,
+                                            workspace.data_ptr(), workspace.numel(), _ptr(logz, torch.float32),
+                                            _stream()))
+    return logz
+
+
+def semicrf_fwd_bwd_durtrans(emis, lengths, trans3, dur, grad_logz=None, ckpt_interval=0,
+                             flags=SEMICRF_CENTER, workspace=None, want_pos_marg=True):
+    """trans3 [K,C,C].  Returns (logz, grad_emis, grad_trans3 [K,C,C], grad_dur, pos_marg or None)."""
+    B, T, C = emis.shape
+    K = dur.shape[0]
+    dev = emis.device
+    if workspace is None:
+        workspace = alloc_durtrans_workspace(B, T, K, C, ckpt_interval, True, dev)
+    f32 = torch.float32
+    logz = torch.empty(B, dtype=f32, device=dev)
+    g_e = torch.empty((B, T, C), dtype=f32, device=dev)
+    g_t = torch.empty((K, C, C), dtype=f32, device=dev)
+    g_d = torch.empty((K, C), dtype=f32, device=dev)
+    pm = torch.empty((B, T, C), dtype=f32, device=dev) if want_pos_marg else None
+    ep, flags = _emis(emis, flags)
+    _check(load().semicrf_fwd_bwd_durtrans(ep, _ptr(lengths, torch.int32), _ptr(trans3, f32), _ptr(dur, f32),
+                                           _ptr(grad_logz, f32), B, T, K, C, ckpt_interval, flags,
+                                           workspace.data_ptr(), workspace.numel(), _ptr(logz, f32),
+                                           _ptr(g_e, f32), _ptr(g_t, f32), _ptr(g_d, f32), _ptr(pm, f32),
+                                           _stream()))
+    return logz, g_e, g_t, g_d, pm
 
 
 def semicrf_entropies(pos_marg, bdy_post, lengths):

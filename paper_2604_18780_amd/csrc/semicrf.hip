@@ -137,6 +137,15 @@ struct Params {
     float *g_pi_start;    // optional [C]
     float *g_pi_end;      // optional [C]
     float *bdy_post;      // optional [B][T+1]
+    // duration-dependent transitions (null / unused otherwise)
+    const float *trans3;  // [K][C][C] trans3[k-1][c'][c] in place of trans[c'][c]
+    double *G3;           // [K][C][C] exp(dur[k-1,c] + trans3[k-1,c',c])
+    double *dtA;          // [B][T+1][C] forward messages a_t(c), scaled
+    double *dtY;          // [B][T+1]    log2 scale of that row relative to its interval's first position
+    double *partG;        // [dt_nwg][K][C][C] per-workgroup sums of the weighted segment marginals
+    double *sumG;         // [K][C][C] their fixed-order total
+    int dt_nwg;
+    float *grad_trans3;   // output [K][C][C]
 };
 
 // emission i of the [B][T][C] array; ET = storage type (0 float, 1 IEEE half, 2 bfloat16)
@@ -163,20 +172,25 @@ __device__ __forceinline__ void tables_body(const Params &p)
     __shared__ double red[NT];
     const int tid = threadIdx.x;
     const int KC = p.K * p.C, CC = p.C * p.C;
-    if (!p.dur || !p.trans) {  // prefix sums only: growth is bounded by the emissions alone
+    if (!p.dur || (!p.trans && !p.trans3)) {  // prefix sums only: growth is bounded by the emissions alone
         if (tid < 2) p.tabmax[tid] = 0.0;
         return;
     }
     double mxd = -DBL_MAX, mxt = -DBL_MAX;
-    for (int i = tid; i < KC; i += NT) {
-        double v = (double)p.dur[i];
-        p.W[i] = exp(v);
-        mxd = fmax(mxd, v);
-    }
-    for (int i = tid; i < CC; i += NT) {
-        double v = (double)p.trans[i];
-        p.Etr[i] = exp(v);
-        mxt = fmax(mxt, v);
+    if (p.trans3) {  // one transition matrix per duration: only the maxima are needed here
+        for (int i = tid; i < KC; i += NT) mxd = fmax(mxd, (double)p.dur[i]);
+        for (int i = tid; i < p.K * CC; i += NT) mxt = fmax(mxt, (double)p.trans3[i]);
+    } else {
+        for (int i = tid; i < KC; i += NT) {
+            double v = (double)p.dur[i];
+            p.W[i] = exp(v);
+            mxd = fmax(mxd, v);
+        }
+        for (int i = tid; i < CC; i += NT) {
+            double v = (double)p.trans[i];
+            p.Etr[i] = exp(v);
+            mxt = fmax(mxt, v);
+        }
     }
     red[tid] = mxd;
     __syncthreads();
@@ -2936,6 +2950,8 @@ __global__ __launch_bounds__(NT) void k_entropies(const float *pos_marg, const f
 // ---------------------------------------------------------------------------
 // Host side: sizing, workspace carving, launches.
 // ---------------------------------------------------------------------------
+#include "durtrans.inl"
+
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // Single-wave tasks a compute unit holds at once for these sizes (scan kernel, interval
@@ -3459,6 +3475,178 @@ int run_viterbi(Params p, void *workspace, size_t workspace_bytes, hipStream_t s
     return check_launch();
 }
 
+
+// ---------------------------------------------------------------------------
+// Duration-dependent transitions: launch geometry, workspace and driver.
+// ---------------------------------------------------------------------------
+struct DtGeom {
+    int kptf, ntf;        // forward kernel: durations per thread, threads
+    int kpt, ntb;         // backward kernels: durations per thread, threads
+    size_t lds_f, lds_b;  // dynamic LDS bytes
+    int mbi;              // time-block length of the marginal kernel
+};
+
+// False when the sizes do not fit the kernels: the backward kernels hold one label pair per
+// thread and at most 64 durations of it in registers.
+bool dt_geometry(int K, int C, DtGeom *g)
+{
+    if (C > 64) return false;
+    const int nksf = K < 1024 / C ? K : 1024 / C;
+    const int kptf = (K + nksf - 1) / nksf;
+    if (kptf > 8) return false;
+    g->kptf = kptf <= 1 ? 1 : (kptf <= 2 ? 2 : (kptf <= 4 ? 4 : 8));
+    g->ntf = (C * nksf + 63) / 64 * 64;
+    g->lds_f = ((size_t)K * C + (size_t)(DT_MB + 2) * C) * sizeof(double);
+    const int CC = C * C;
+    g->kpt = 0;
+    for (int kpt = 8; kpt <= 64; kpt *= 2) {
+        const int nks = (K + kpt - 1) / kpt;
+        if ((size_t)CC * nks <= (size_t)(kpt == 64 ? 640 : 1024)) {
+            g->kpt = kpt;
+            g->ntb = (CC * nks + 63) / 64 * 64;
+            g->lds_b = ((size_t)K * C + (size_t)nks * CC + (size_t)(DT_MB + 2) * C) * sizeof(double);
+            break;
+        }
+    }
+    if (!g->kpt) return false;
+    g->mbi = g->kpt == 64 ? 2 : DT_MB;
+    return g->lds_f <= LDS_LIMIT && g->lds_b <= LDS_LIMIT;
+}
+
+constexpr int DT_NWG = 512;  // most persistent workgroups of the marginal kernel
+
+struct DtLayout {
+    size_t g3, dta, dty, partg, sumg, total;
+    int nwg;
+};
+
+DtLayout dt_layout(int B, int T, int K, int C, int N, int want_grad)
+{
+    DtLayout l;
+    const size_t kcc = (size_t)K * C * C, t1 = (size_t)T + 1;
+    const size_t ntask = (size_t)B * N;
+    l.nwg = (int)(ntask < (size_t)DT_NWG ? ntask : (size_t)DT_NWG);
+    size_t off = 0;
+    l.g3 = off; off += align_up(kcc * 8);
+    l.dta = off; off += align_up((size_t)B * t1 * C * 8);
+    l.dty = off; off += align_up((size_t)B * t1 * 8);
+    l.partg = off; off += want_grad ? align_up((size_t)l.nwg * kcc * 8) : 0;
+    l.sumg = off; off += want_grad ? align_up(kcc * 8) : 0;
+    l.total = off;
+    return l;
+}
+
+template <int KPTF>
+int launch_dt_fwd(const Params &p, const DtGeom &g, hipStream_t st, int grid, int warm, int tier, int whole)
+{
+    if (hipFuncSetAttribute((const void *)k_dt_fwd<KPTF>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)g.lds_f) != hipSuccess)
+        return SEMICRF_ELAUNCH;
+    hipLaunchKernelGGL((k_dt_fwd<KPTF>), dim3(grid), dim3(g.ntf), g.lds_f, st, p, warm, tier, whole);
+    return SEMICRF_OK;
+}
+
+int launch_dt_fwd_any(const Params &p, const DtGeom &g, hipStream_t st, int grid, int warm, int tier, int whole)
+{
+    switch (g.kptf) {
+    case 1: return launch_dt_fwd<1>(p, g, st, grid, warm, tier, whole);
+    case 2: return launch_dt_fwd<2>(p, g, st, grid, warm, tier, whole);
+    case 4: return launch_dt_fwd<4>(p, g, st, grid, warm, tier, whole);
+    default: return launch_dt_fwd<8>(p, g, st, grid, warm, tier, whole);
+    }
+}
+
+template <int KPT, bool ACC, int MBT, int NTMAX>
+int launch_dt_bwd(const Params &p, const DtGeom &g, hipStream_t st, int grid, int warm, int tier, int mode)
+{
+    if (hipFuncSetAttribute((const void *)k_dt_bwd<KPT, ACC, MBT, NTMAX>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_b) != hipSuccess)
+        return SEMICRF_ELAUNCH;
+    hipLaunchKernelGGL((k_dt_bwd<KPT, ACC, MBT, NTMAX>), dim3(grid), dim3(g.ntb), g.lds_b, st, p, warm, tier, mode);
+    return SEMICRF_OK;
+}
+
+// mode 0 / 1: the scan; mode 2: the marginals
+int launch_dt_bwd_any(const Params &p, const DtGeom &g, hipStream_t st, int grid, int warm, int tier, int mode)
+{
+    if (mode == 2) {
+        switch (g.kpt) {
+        case 8: return launch_dt_bwd<8, true, DT_MB, 1024>(p, g, st, grid, warm, tier, mode);
+        case 16: return launch_dt_bwd<16, true, DT_MB, 1024>(p, g, st, grid, warm, tier, mode);
+        case 32: return launch_dt_bwd<32, true, DT_MB, 1024>(p, g, st, grid, warm, tier, mode);
+        default: return launch_dt_bwd<64, true, 2, 640>(p, g, st, grid, warm, tier, mode);
+        }
+    }
+    switch (g.kpt) {
+    case 8: return launch_dt_bwd<8, false, DT_MB, 1024>(p, g, st, grid, warm, tier, mode);
+    case 16: return launch_dt_bwd<16, false, DT_MB, 1024>(p, g, st, grid, warm, tier, mode);
+    case 32: return launch_dt_bwd<32, false, DT_MB, 1024>(p, g, st, grid, warm, tier, mode);
+    default: return launch_dt_bwd<64, false, DT_MB, 640>(p, g, st, grid, warm, tier, mode);
+    }
+}
+
+int run_durtrans(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hipStream_t st, bool grad)
+{
+    Plan pl;
+    int rc = make_plan(p.B, p.T, p.K, p.C, ckpt_interval, grad ? 1 : 0, &pl);
+    if (rc != SEMICRF_OK) return rc;
+    DtGeom g;
+    if (!dt_geometry(p.K, p.C, &g)) return SEMICRF_EUNSUPPORTED;
+    const DtLayout dl = dt_layout(p.B, p.T, p.K, p.C, pl.N, grad ? 1 : 0);
+    if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < pl.total + dl.total)
+        return SEMICRF_EWORKSPACE;
+    p.Delta = pl.Delta;
+    p.N = pl.N;
+    p.NCH = pl.NCH;
+    p.nslot = pl.nslot;
+    p.want_grad = grad ? 1 : 0;
+    bind_workspace(p, pl, workspace);
+    char *dw = (char *)workspace + pl.total;
+    p.G3 = (double *)(dw + dl.g3);
+    p.dtA = (double *)(dw + dl.dta);
+    p.dtY = (double *)(dw + dl.dty);
+    p.partG = (double *)(dw + dl.partg);
+    p.sumG = (double *)(dw + dl.sumg);
+    p.dt_nwg = dl.nwg;
+    rc = launch_prep(p, st);
+    if (rc != SEMICRF_OK) return rc;
+    const size_t kcc = (size_t)p.K * p.C * p.C;
+    hipLaunchKernelGGL(k_dt_tables, dim3((unsigned)((kcc + NT - 1) / NT)), dim3(NT), 0, st, p);
+    const int ndir = grad ? 2 : 1;
+    if (p.spec) {
+        const int warm[2] = {2 * p.K < 32 ? 32 : 2 * p.K, 8 * p.K < 64 ? 64 : 8 * p.K};
+        for (int tier = 0; tier < 2; ++tier) {
+            rc = launch_dt_fwd_any(p, g, st, p.B * p.N, warm[tier], tier, 0);
+            if (rc != SEMICRF_OK) return rc;
+            if (grad) {
+                rc = launch_dt_bwd_any(p, g, st, p.B * p.N, warm[tier], tier, 0);
+                if (rc != SEMICRF_OK) return rc;
+            }
+            hipLaunchKernelGGL(k_spec_cmp, dim3(p.N, p.B, ndir), dim3(64), 0, st, p, tier);
+            hipLaunchKernelGGL(k_spec_fix, dim3(p.B, 2), dim3(64), 0, st, p, ndir, tier);
+        }
+    } else {
+        hipLaunchKernelGGL(k_spec_clear, dim3((2 * p.B + 63) / 64), dim3(64), 0, st, p);
+    }
+    // whole-sequence scans for what the verification rejected (return at once otherwise)
+    rc = launch_dt_fwd_any(p, g, st, p.B, 0, 0, 1);
+    if (rc != SEMICRF_OK) return rc;
+    if (!grad) return check_launch();
+    rc = launch_dt_bwd_any(p, g, st, p.B, 0, 0, 1);
+    if (rc != SEMICRF_OK) return rc;
+    rc = launch_dt_bwd_any(p, g, st, dl.nwg, 0, 0, 2);
+    if (rc != SEMICRF_OK) return rc;
+    hipLaunchKernelGGL(k_dt_fin, dim3(p.B + (unsigned)((kcc + NT - 1) / NT)), dim3(NT), 0, st, p);
+    hipLaunchKernelGGL(k_dt_fin_dur, dim3((p.K * p.C + NT - 1) / NT), dim3(NT), 0, st, p);
+    {
+        size_t n = (size_t)p.T * p.C;
+        size_t blocks = (n + NT - 1) / NT;
+        if (blocks > 16384) blocks = 16384;
+        hipLaunchKernelGGL(k_fin_emis, dim3((unsigned)blocks, p.B), dim3(NT), 0, st, p);
+    }
+    return check_launch();
+}
+
 }  // namespace
 
 extern "C" {
@@ -3661,6 +3849,55 @@ int semicrf_viterbi(const float *emis, const int32_t *lengths, const float *tran
     p.vscore = score; p.vlabels = labels; p.vstarts = starts; p.vnseg = nseg;
     p.spec = (flags & SEMICRF_SEQUENTIAL_SCAN) ? 0 : 1;
     return run_viterbi(p, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+int semicrf_durtrans_workspace_bytes(int B, int T, int K, int C, int ckpt_interval, int want_grad,
+                                     size_t *bytes)
+{
+    if (!bytes) return SEMICRF_EINVAL;
+    Plan pl;
+    int rc = make_plan(B, T, K, C, ckpt_interval, want_grad ? 1 : 0, &pl);
+    if (rc != SEMICRF_OK) return rc;
+    DtGeom g;
+    if (!dt_geometry(K, C, &g)) return SEMICRF_EUNSUPPORTED;
+    *bytes = pl.total + dt_layout(B, T, K, C, pl.N, want_grad ? 1 : 0).total;
+    return SEMICRF_OK;
+}
+
+int semicrf_logz_fwd_durtrans(const float *emis, const int32_t *lengths, const float *trans3,
+                              const float *dur, int B, int T, int K, int C, int ckpt_interval,
+                              unsigned flags, void *workspace, size_t workspace_bytes, float *logz,
+                              void *stream)
+{
+    if (!emis || !trans3 || !dur || !logz) return SEMICRF_EINVAL;
+    if ((flags & SEMICRF_EMIS_F16) && (flags & SEMICRF_EMIS_BF16)) return SEMICRF_EINVAL;
+    Params p = {};
+    p.emis = emis; p.lengths = lengths; p.trans3 = trans3; p.dur = dur;
+    p.B = B; p.T = T; p.K = K; p.C = C;
+    p.center = (flags & SEMICRF_CENTER) ? 1 : 0;
+    p.emis_type = (flags & SEMICRF_EMIS_F16) ? 1 : ((flags & SEMICRF_EMIS_BF16) ? 2 : 0);
+    p.spec = (flags & SEMICRF_SEQUENTIAL_SCAN) ? 0 : 1;
+    p.logz = logz;
+    return run_durtrans(p, ckpt_interval, workspace, workspace_bytes, (hipStream_t)stream, false);
+}
+
+int semicrf_fwd_bwd_durtrans(const float *emis, const int32_t *lengths, const float *trans3,
+                             const float *dur, const float *grad_logz, int B, int T, int K, int C,
+                             int ckpt_interval, unsigned flags, void *workspace, size_t workspace_bytes,
+                             float *logz, float *grad_emis, float *grad_trans3, float *grad_dur,
+                             float *pos_marg, void *stream)
+{
+    if (!emis || !trans3 || !dur || !logz || !grad_emis || !grad_trans3 || !grad_dur) return SEMICRF_EINVAL;
+    if ((flags & SEMICRF_EMIS_F16) && (flags & SEMICRF_EMIS_BF16)) return SEMICRF_EINVAL;
+    Params p = {};
+    p.emis = emis; p.lengths = lengths; p.trans3 = trans3; p.dur = dur; p.grad_logz = grad_logz;
+    p.B = B; p.T = T; p.K = K; p.C = C;
+    p.center = (flags & SEMICRF_CENTER) ? 1 : 0;
+    p.emis_type = (flags & SEMICRF_EMIS_F16) ? 1 : ((flags & SEMICRF_EMIS_BF16) ? 2 : 0);
+    p.spec = (flags & SEMICRF_SEQUENTIAL_SCAN) ? 0 : 1;
+    p.logz = logz; p.grad_emis = grad_emis; p.grad_trans3 = grad_trans3; p.grad_dur = grad_dur;
+    p.pos_marg = pos_marg;
+    return run_durtrans(p, ckpt_interval, workspace, workspace_bytes, (hipStream_t)stream, true);
 }
 
 int semicrf_scan_report(const void *workspace, size_t workspace_bytes, int B, int T, int K, int C,
