@@ -56,6 +56,9 @@ def main():
                          "their outputs instead (whole-call time only; prints its own JSON line)")
     ap.add_argument("--viterbi", action="store_true",
                     help="time semicrf_viterbi (max-semiring decode + trace-back) instead; prints its own JSON line")
+    ap.add_argument("--durtrans", action="store_true",
+                    help="time semicrf_fwd_bwd_durtrans (one transition matrix per duration: K*C*C multiply-adds "
+                         "per position and recurrence) instead; prints its own JSON line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy so that a rocprofv3 --pmc run of this "
                          "command holds a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
@@ -109,6 +112,38 @@ def main():
             "scans_accepted_chunk_parallel": int(sb.semicrf_scan_report(vws, B, T, K, C, 0, False)[0][:, 0].sum().item()),
             "scans_total": B,
             "score_mean": float(o[0].double().mean().item()), "segments": int(o[3].sum().item())}))
+        return
+    if args.durtrans:
+        t3 = torch.from_numpy(synth.duration_transitions(w)).to(dev)
+        dws = sb.alloc_durtrans_workspace(B, T, K, C, args.ckpt_interval, True, dev)
+        call = lambda: sb.semicrf_fwd_bwd_durtrans(emis, lengths, t3, dur, None, args.ckpt_interval, workspace=dws)
+        for _ in range(args.warmup):
+            o = call()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            o = call()
+        torch.cuda.synchronize()
+        ms = 1e3 * (time.perf_counter() - t0) / args.steps
+        acc, mis = sb.semicrf_scan_report(dws, B, T, K, C, args.ckpt_interval, True)
+        # forward + backward recurrence + marginals: 3 * K*C*C multiply-adds per position (the
+        # backward recurrence runs twice: once as a scan, once inside the intervals)
+        flop = 2.0 * 4.0 * K * C * C * w.positions
+        print(json.dumps({
+            "metric": "semi-CRF fwd+bwd with duration-dependent transitions, edge evals/sec (B*T*K*C^2/s)",
+            "value": w.nominal_edges / (ms * 1e-3), "unit": "edge evals/s",
+            "positions_per_s": w.positions / (ms * 1e-3), "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "f64", "data": "synthetic",
+            "config": {"workload": f"{w.name}: B={B} T={T} K={K} C={C}, trans3 [K,C,C] = trans + N(0, 0.1^2) "
+                                   f"(output tensors allocated inside the timed calls)",
+                       "ckpt_interval": sb.semicrf_ckpt_interval(B, T, K, C, args.ckpt_interval),
+                       "workspace_bytes": int(dws.numel())},
+            "roofline": {"bound": "alu", "achieved": flop / (ms * 1e-3) / 1e12, "peak": FP64_VECTOR_PEAK_TFLOPS,
+                         "unit": "TFLOP/s", "frac": flop / (ms * 1e-3) / 1e12 / FP64_VECTOR_PEAK_TFLOPS,
+                         "traffic": None, "flop_per_call": flop},
+            "scans_accepted_chunk_parallel": int(acc.sum().item()), "scans_total": 2 * B,
+            "logz_mean": float(o[0].double().mean().item())}))
         return
     if args.boundary_terms:
         ps, pe, pis, pie = (torch.from_numpy(a).to(dev) for a in synth.boundary_terms(w))

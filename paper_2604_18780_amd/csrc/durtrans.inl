@@ -212,231 +212,341 @@ __global__ __launch_bounds__(1024) void k_dt_fwd(Params p, int warm, int tier, i
 }
 
 // ---------------------------------------------------------------------------
-// Backward recurrence and, with ACC, the marginals.  Thread (ks, c', c): one label pair and the
-// KPT consecutive durations ks*KPT + 1 .. ks*KPT + KPT; its sum over those durations goes
-// through a [NKS][C][C] table in LDS from which threads 0..C-1 form b_t (row sums) and, with
-// ACC, the mass of the segments that start at t (column sums weighted by a_t).
-// mode 0: grid B*N chunk tasks with warm-up (scan; checkpoint states at both ends)
+// Backward recurrence.  Thread (ks, c', c): one label pair and the KPT consecutive durations
+// ks*KPT + 1 .. ks*KPT + KPT; its sum over those durations goes through a [NKS][C][C] table in
+// LDS from which threads 0..C-1 form b_t (row sums) and the mass of the segments that start
+// at t (column sums weighted by a_t, which the forward scan has stored).
+// mode 0: grid B*N chunk tasks with warm-up (checkpoint states at both ends)
 // mode 1: grid B whole sequences whose chunk-parallel backward scan was not accepted
-// mode 2: persistent workgroups over the (sequence, interval) tasks, restoring the state at
-//         the interval's upper end from the backward checkpoints; accumulates, per thread,
-//         sum_t w_b mu(t -> t+k, c', c) for its pair and durations (registers, all tasks of
-//         the workgroup), and writes the running emission-gradient sums like k_interval.
+// For the positions of its interval a task stores, in its own power-of-two scale,
+//   dtV  v_t(c)                         (read by the marginal kernel)
+//   dtD  out_t(c) - in_t(c), out = sum_c' a_t(c') IE_t(c) sum_k G v_{t+k}(c): segments that start at t,
+//        in = a_t(c) b_t(c): segments that end at t   (times exp(scales - logZ) later)
+//   dtYb the log2 scale of both relative to the interval's upper end.
 // ---------------------------------------------------------------------------
-template <int KPT, bool ACC, int MBT, int NTMAX>
-__global__ __launch_bounds__(NTMAX) void k_dt_bwd(Params p, int warm, int tier, int mode)
+template <int KPT, int MBT>
+__global__ __launch_bounds__(1024) void k_dt_bwd(Params p, int warm, int tier, int mode)
 {
     extern __shared__ double lds_raw[];
     const int tid = threadIdx.x;
     const int K = p.K, C = p.C, CC = C * C, KC = K * C, N = p.N, Delta = p.Delta;
     const int NKS = (K + KPT - 1) / KPT;
     const int ks = tid / CC, pair = tid % CC;
-    const int cp = pair / C, c = pair % C;
+    const int c = pair % C;
     const bool active = ks < NKS;
     const int k0 = ks * KPT;  // the thread's durations are k0 + 1 .. k0 + KPT
     double *ring = lds_raw;           // [K][C]   v_u(c) at slot u mod K
     double *red = ring + KC;          // [NKS][C][C]
-    double *av = red + NKS * CC;      // [MBT][C] a_t of the block's positions (ACC)
+    double *av = red + NKS * CC;      // [MBT][C] a_t of the block's positions
     double *yv = av + MBT * C;        // [C]      b_t: scale reference
     int *sc = (int *)(yv + C);        // [C]
     const size_t ckstride = (size_t)KC + C;
 
-    double acc[ACC ? KPT : 1];
-    if (ACC) {
-#pragma unroll
-        for (int kk = 0; kk < KPT; ++kk) acc[kk] = 0.0;
-    }
+    const int b = mode == 1 ? (int)blockIdx.x : (int)blockIdx.x / N;
+    const int chunk = mode == 1 ? -1 : (int)blockIdx.x % N;
+    if (mode == 0 && tier > 0 && p.spec_ok[b * 2 + 1]) return;
+    if (mode == 1 && p.spec && p.spec_ok[b * 2 + 1]) return;
+    const SeqHdr h = p.hdr[b];
+    const int L = h.L, J = h.J;
+    const int lo = mode == 1 ? 0 : chunk * Delta;
+    if (mode != 1 && lo >= L) return;
+    const int hi = mode == 1 ? L : min(lo + Delta, L);
+    const int s1 = mode == 0 ? min(hi + warm, L) : hi;  // where this task's recurrence starts
+    const size_t row0 = (size_t)b * (p.T + 1);
+    const double2 *EI = p.EI + row0 * C;
+    const int *nb = p.nbase + row0 * C;
+    const double *rowA = p.dtA + row0 * C;
+    double *rowV = p.dtV + row0 * C;
+    double *rowD = p.dtD + row0 * C;
+    double *rowYb = p.dtYb + row0;
 
-    const int ntask = mode == 1 ? p.B : p.B * N;
+    // a sequence that ends at s1 (exactly so when s1 = L): b = 1, v = ES
+    for (int i = tid; i < KC; i += blockDim.x) ring[i] = 0.0;
+    __syncthreads();
+    if (tid < C) {
+        yv[tid] = tid == 0 ? 1.0 : 0.0;
+        const double v = EI[(size_t)s1 * C + tid].x;
+        ring[(s1 % K) * C + tid] = v;
+        if (s1 == L) rowV[(size_t)L * C + tid] = v;
+    }
+    if (s1 == L && tid == 0) rowYb[L] = 0.0;
+    double Yb = 0.0, Ytop = 0.0;
+    __syncthreads();
+    auto record = [&](double *ck) {
+        for (int i = tid; i < KC; i += blockDim.x) ck[i] = ring[i];
+        if (tid < C) ck[KC + tid] = yv[tid];
+    };
+
+    int t0 = s1 - 1;
+    while (t0 >= lo) {
+        int nbk = min(MBT, t0 - lo + 1);
+        if (t0 >= hi) nbk = min(nbk, t0 - hi + 1);         // the interval's upper end ends its block
+        nbk = min(nbk, (t0 % J) + 1);                       // no scaling-block boundary inside a block
+        if (mode == 1) nbk = min(nbk, (t0 % Delta) + 1);    // checkpoints are recorded at block ends
+        if (((t0 + 1) % J) == 0) Yb += (double)dt_rebase(ring, yv, sc, nb, KC, C, t0 / J, t0 / J + 1, -1);
+        double ie[MBT];
+#pragma unroll
+        for (int i = 0; i < MBT; ++i) {
+            ie[i] = 0.0;
+            if (i < nbk) {
+                const int tt = t0 - i;
+                if (active) ie[i] = EI[(size_t)tt * C + c].y;
+                if (tid < C) av[i * C + tid] = rowA[(size_t)tt * C + tid];
+            }
+        }
+        // ---- durations that reach beyond the block: every table entry once for all positions
+        double bs[MBT];
+#pragma unroll
+        for (int i = 0; i < MBT; ++i) bs[i] = 0.0;
+        if (active) {
+            // position t0 - i with duration k reads v of position t0 + k - i: one new ring row per
+            // duration (w[0]); the rows of the later positions are the earlier durations' rows
+            const double *gp = p.G3 + (size_t)k0 * CC + pair;
+            int sl = (t0 + k0 + 1) % K;  // slot of position t0 + k0 + 1
+            double w[MBT];
+#pragma unroll
+            for (int i = 1; i < MBT; ++i) w[i] = ring[dt_wrap(sl - i, K) * C + c];
+#pragma unroll 16
+            for (int kk = 0; kk < KPT; ++kk) {
+                const int k = k0 + kk + 1;
+                if (k <= K) {
+                    w[0] = ring[sl * C + c];
+                    const double gv = *gp;
+#pragma unroll
+                    for (int i = 0; i < MBT; ++i)
+                        if (i < nbk && k > i) bs[i] = fma(gv, w[i], bs[i]);
+#pragma unroll
+                    for (int i = MBT - 1; i > 0; --i) w[i] = w[i - 1];
+                    sl = sl + 1 == K ? 0 : sl + 1;
+                    gp += CC;
+                }
+            }
+        }
+        // ---- finish the positions one after the other
+#pragma unroll
+        for (int i = 0; i < MBT; ++i) {
+            if (i < nbk) {  // uniform
+                const int tt = t0 - i;
+                if (active) {
+                    // durations 1 .. i end inside the block, at positions finished just before
+                    for (int k = 1; k <= i && k <= K; ++k)
+                        if (k > k0 && k <= k0 + KPT)
+                            bs[i] = fma(p.G3[(size_t)(k - 1) * CC + pair], ring[((tt + k) % K) * C + c], bs[i]);
+                    red[ks * CC + pair] = bs[i] * ie[i];
+                }
+                __syncthreads();
+                if (tid < C) {
+                    double bsum = 0.0, osum = 0.0;
+                    for (int q = 0; q < NKS; ++q) {
+                        const double *rq = red + q * CC;
+                        for (int o = 0; o < C; ++o) {
+                            bsum += rq[tid * C + o];
+                            osum = fma(av[i * C + o], rq[o * C + tid], osum);
+                        }
+                    }
+                    yv[tid] = bsum;
+                    const double v = bsum * EI[(size_t)tt * C + tid].x;
+                    ring[(tt % K) * C + tid] = v;
+                    if (tt < hi) {
+                        rowV[(size_t)tt * C + tid] = v;
+                        rowD[(size_t)tt * C + tid] = osum - (tt >= 1 ? av[i * C + tid] * bsum : 0.0);
+                    }
+                }
+                if (tid == 0 && tt < hi) rowYb[tt] = Yb - Ytop;
+                __syncthreads();
+            }
+        }
+        const int tlast = t0 - nbk + 1;
+        if (mode == 0 && tlast == hi && hi < L) {
+            record(p.ckB + ((size_t)b * (N + 1) + hi / Delta) * ckstride);
+            if (tid == 0) p.ckYB[(size_t)b * (N + 1) + hi / Delta] = Yb;
+            Ytop = Yb;
+        }
+        if (mode == 1 && tlast > 0 && (tlast % Delta) == 0) {
+            record(p.ckB + ((size_t)b * (N + 1) + tlast / Delta) * ckstride);
+            if (tid == 0) p.ckYB[(size_t)b * (N + 1) + tlast / Delta] = Yb;
+            Ytop = Yb;
+        }
+        t0 -= nbk;
+    }
+    if (mode == 0 && lo > 0) {
+        record(p.ckB2 + ((size_t)b * (N + 1) + lo / Delta) * ckstride);
+        if (tid == 0) p.ckYB2[(size_t)b * (N + 1) + lo / Delta] = Yb;
+    }
+    if (mode == 1 && tid == 0) {
+        double s = 0.0;
+        for (int i = 0; i < C; ++i) s += yv[i];
+        p.hdr[b].logZb = Yb * LN2 + log(s);
+    }
+}
+
+// Absolute log2 scale of the backward rows of interval j at its upper end (0 at the sequence end).
+__device__ __forceinline__ double dt_ytop(const Params &p, int b, int j, int L)
+{
+    const int hi = min((j + 1) * p.Delta, L);
+    return hi == L ? 0.0 : p.ckYB[(size_t)b * (p.N + 1) + j + 1];
+}
+
+// Running emission-gradient sums per interval, in the form k_fin_seq / k_fin_emis expect from the
+// interval kernels: grad_emis[t] = sum of (out - in) over the interval's positions above t, tot and
+// sumR per interval.  One wave per (sequence, interval), lane = label; rows are fetched eight
+// positions at a time.
+__global__ __launch_bounds__(64) void k_dt_emis(Params p)
+{
+    const int b = blockIdx.x / p.N, j = blockIdx.x % p.N, lane = threadIdx.x;
+    const int C = p.C, Delta = p.Delta, N = p.N;
+    const int L = p.hdr[b].L;
+    const int lo = j * Delta;
+    if (lo >= L) return;
+    const int hi = min(lo + Delta, L);
+    const size_t row0 = (size_t)b * (p.T + 1);
+    const double *rowD = p.dtD + row0 * C;
+    const double *rowY = p.dtY + row0, *rowYb = p.dtYb + row0;
+    const double *ckYA = p.ckYA + (size_t)b * (N + 1);
+    const double logZ = p.hdr[b].logZ;
+    const double ytop = dt_ytop(p, b, j, L);
+    const bool act = lane < C;
+    double R = 0.0, sR = 0.0, kappa = 0.0, kY = -1.0e300;
+    for (int t1 = hi; t1 > lo; t1 -= 8) {
+        double d[8], y[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int tt = t1 - 1 - i;
+            d[i] = 0.0;
+            y[i] = 0.0;
+            if (tt >= lo) {
+                if (act) d[i] = rowD[(size_t)tt * C + lane];
+                y[i] = ckYA[tt == 0 ? 0 : (tt - 1) / Delta] + rowY[tt] + ytop + rowYb[tt];
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int tt = t1 - 1 - i;
+            if (tt >= lo) {
+                if (y[i] != kY) {  // uniform
+                    kY = y[i];
+                    kappa = exp(kY * LN2 - logZ);
+                }
+                if (act) {
+                    p.grad_emis[((size_t)b * p.T + tt) * C + lane] = (float)R;
+                    sR += R;
+                    R = fma(d[i], kappa, R);
+                }
+            }
+        }
+    }
+    if (act) {
+        p.tot[((size_t)b * N + j) * C + lane] = R;
+        p.sumR[((size_t)b * N + j) * C + lane] = sR;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Marginals: sum_t w_b mu_b(t -> t+k, c', c) for every (k, c', c), from the stored rows.
+//   mu = a_t(c') IE_t(c) G[k][c'][c] v_{t+k}(c) 2^(n_blk(t+k)(c) - n_blk(t)(c)) exp((YA(t) + YB(t+k)) ln2 - logZ)
+// (the power of two is what the backward recurrence applies to its ring when it crosses the
+// scaling blocks between t+k and t).  Thread = label pair; workgroup (x, y) = persistent over
+// the (sequence, interval) tasks x, x + gridDim.x, ... for the KS durations y*KS + 1 .. y*KS + KS,
+// one accumulator per duration in registers, multiplied by G once at the end.  Positions are
+// taken in groups that lie in one scaling block (at most DT_TG): the group's a and IE rows and
+// the v rows it can reach are staged in LDS, the latter converted to the group's frame; four
+// positions share every LDS read.
+// ---------------------------------------------------------------------------
+constexpr int DT_TG = 32;
+
+template <int KS>
+__global__ __launch_bounds__(1024) void k_dt_acc(Params p)
+{
+    extern __shared__ double lds_raw[];
+    const int tid = threadIdx.x;
+    const int K = p.K, C = p.C, CC = C * C, N = p.N, Delta = p.Delta;
+    const bool active = tid < CC;
+    const int pair = active ? tid : 0;
+    const int cp = pair / C, c = pair % C;
+    const int kA = blockIdx.y * KS;
+    constexpr int VR = DT_TG + KS + 3;   // rows of v a group can reach (+3: blocks of four positions)
+    double *Arow = lds_raw;              // [DT_TG][C]  a_t(c') w_b 2^(YA(t) - YA(group))
+    double *IErow = Arow + DT_TG * C;    // [DT_TG][C]
+    double *Vp = IErow + DT_TG * C;      // [VR][C]
+    double acc[KS];
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) acc[kk] = 0.0;
+
+    const int ntask = p.B * N;
     for (int task = blockIdx.x; task < ntask; task += gridDim.x) {
-        const int b = mode == 1 ? task : task / N;
-        const int chunk = mode == 1 ? -1 : task % N;
-        if (mode == 0 && tier > 0 && p.spec_ok[b * 2 + 1]) continue;
-        if (mode == 1 && p.spec && p.spec_ok[b * 2 + 1]) continue;
+        const int b = task / N, chunk = task % N;
         const SeqHdr h = p.hdr[b];
         const int L = h.L, J = h.J;
-        const int lo = mode == 1 ? 0 : chunk * Delta;
-        if (mode != 1 && lo >= L) continue;
-        const int hi = mode == 1 ? L : min(lo + Delta, L);
-        const int s1 = mode == 0 ? min(hi + warm, L) : hi;  // where this task's recurrence starts
+        const int lo = chunk * Delta;
+        if (lo >= L) continue;
+        const int hi = min(lo + Delta, L);
         const size_t row0 = (size_t)b * (p.T + 1);
         const double2 *EI = p.EI + row0 * C;
         const int *nb = p.nbase + row0 * C;
-        const double *rowA = p.dtA + row0 * C;
-        const double *rowY = p.dtY + row0;
+        const double *rowA = p.dtA + row0 * C, *rowV = p.dtV + row0 * C;
+        const double *rowY = p.dtY + row0, *rowYb = p.dtYb + row0;
         const double *ckYA = p.ckYA + (size_t)b * (N + 1);
         const double logZ = h.logZ;
-        const double wb = (ACC && p.grad_logz) ? (double)p.grad_logz[b] : 1.0;
-
-        __syncthreads();  // the previous task is done with the LDS arrays
-        double Yb = 0.0;
-        if (s1 == L) {  // exact: b_L = 1, v_L = ES_L
-            for (int i = tid; i < KC; i += blockDim.x) ring[i] = 0.0;
-            __syncthreads();
-            if (tid < C) {
-                yv[tid] = tid == 0 ? 1.0 : 0.0;
-                ring[(L % K) * C + tid] = EI[(size_t)L * C + tid].x;
-            }
-        } else if (mode == 0) {  // a sequence that ends at s1
-            for (int i = tid; i < KC; i += blockDim.x) ring[i] = 0.0;
-            __syncthreads();
-            if (tid < C) {
-                yv[tid] = tid == 0 ? 1.0 : 0.0;
-                ring[(s1 % K) * C + tid] = EI[(size_t)s1 * C + tid].x;
-            }
-        } else {  // the checkpoint at the interval's upper end
-            const int ci = s1 / Delta;
-            const double *ck = p.ckB + ((size_t)b * (N + 1) + ci) * ckstride;
-            for (int i = tid; i < KC; i += blockDim.x) ring[i] = ck[i];
-            if (tid < C) yv[tid] = ck[KC + tid];
-            Yb = p.ckYB[(size_t)b * (N + 1) + ci];
-        }
-        double R = 0.0, sR = 0.0;  // running suffix sum of (out - in) and its sum: threads < C
-        double kappa = 0.0, kY = -1.0e300;  // exp((Y_alpha + Y_beta) ln2 - logZ), recomputed when the scales move
-        __syncthreads();
-        auto record = [&](double *ck) {
-            for (int i = tid; i < KC; i += blockDim.x) ck[i] = ring[i];
-            if (tid < C) ck[KC + tid] = yv[tid];
-        };
-
-        int t0 = s1 - 1;
-        while (t0 >= lo) {
-            int nbk = min(MBT, t0 - lo + 1);
-            if (t0 >= hi) nbk = min(nbk, t0 - hi + 1);         // the interval's upper end ends its block
-            nbk = min(nbk, (t0 % J) + 1);                       // no scaling-block boundary inside a block
-            if (mode == 1) nbk = min(nbk, (t0 % Delta) + 1);    // checkpoints are recorded at block ends
-            if (((t0 + 1) % J) == 0) Yb += (double)dt_rebase(ring, yv, sc, nb, KC, C, t0 / J, t0 / J + 1, -1);
-            // ---- per-position factors of this thread
-            double ie[MBT], coef[MBT], kap[MBT];
-#pragma unroll
-            for (int i = 0; i < MBT; ++i) {
-                ie[i] = 0.0;
-                coef[i] = 0.0;
-                kap[i] = 0.0;
-                if (i < nbk) {
-                    const int tt = t0 - i;
-                    if (active) ie[i] = EI[(size_t)tt * C + c].y;
-                    if (ACC) {
-                        const int jr = tt == 0 ? 0 : (tt - 1) / Delta;
-                        const double ysum = ckYA[jr] + rowY[tt] + Yb;
-                        if (ysum != kY) {  // uniform
-                            kY = ysum;
-                            kappa = exp(ysum * LN2 - logZ);
-                        }
-                        kap[i] = kappa;
-                        if (active) coef[i] = rowA[(size_t)tt * C + cp] * kap[i] * wb * ie[i];
-                        if (tid < C) av[i * C + tid] = rowA[(size_t)tt * C + tid];
-                    }
+        const double wb = p.grad_logz ? (double)p.grad_logz[b] : 1.0;
+        for (int tg0 = lo; tg0 < hi;) {
+            const int tg1 = min(min(hi, (tg0 / J + 1) * J), tg0 + DT_TG);
+            const int ng = tg1 - tg0, jt = tg0 / J;
+            const double yA0 = ckYA[tg0 == 0 ? 0 : (tg0 - 1) / Delta] + rowY[tg0];
+            __syncthreads();  // the previous group is done with the staged rows
+            for (int i = tid; i < DT_TG * C; i += blockDim.x) {
+                const int r = i / C, o = i % C, tt = tg0 + r;
+                double a = 0.0, e = 0.0;
+                if (r < ng) {
+                    const double yA = ckYA[tt == 0 ? 0 : (tt - 1) / Delta] + rowY[tt];
+                    a = rowA[(size_t)tt * C + o] * wb * exp2(yA - yA0);
+                    e = EI[(size_t)tt * C + o].y;
                 }
+                Arow[i] = a;
+                IErow[i] = e;
             }
-            // ---- durations that reach beyond the block: every table entry once for all positions
-            double bs[MBT];
-#pragma unroll
-            for (int i = 0; i < MBT; ++i) bs[i] = 0.0;
+            for (int i = tid; i < VR * C; i += blockDim.x) {
+                const int r = i / C, o = i % C, s = tg0 + kA + 1 + r;
+                double v = 0.0;
+                if (s <= L && r < ng + KS) {
+                    const int js = s / J;
+                    const int jc = s == L ? -1 : s / Delta;  // interval whose backward task stored the row
+                    const double yB = jc < 0 ? 0.0 : dt_ytop(p, b, jc, L) + rowYb[s];
+                    // all exponents are combined before anything is formed, so that an empty row
+                    // stays zero and nothing passes through infinity
+                    const double lf = (yA0 + yB) - logZ * LOG2E;
+                    const double fl = floor(lf);
+                    const int sh = nb[(size_t)js * C + o] - nb[(size_t)jt * C + o];
+                    const double ef = fmin(fmax(fl, -100000.0), 100000.0);
+                    v = fmin(ldexp(rowV[(size_t)s * C + o] * exp2(lf - fl), sh + (int)ef), DBL_MAX);
+                }
+                Vp[i] = v;
+            }
+            __syncthreads();
             if (active) {
-                // position t0 - i with duration k reads v of position t0 + k - i: one new ring row per
-                // duration (w[0]); the rows of the later positions are the earlier durations' rows
-                const double *gp = p.G3 + (size_t)k0 * CC + pair;
-                int sl = (t0 + k0 + 1) % K;  // slot of position t0 + k0 + 1
-                double w[MBT];
+                for (int i0 = 0; i0 < ng; i0 += 4) {
+                    double ca[4];
 #pragma unroll
-                for (int i = 1; i < MBT; ++i) w[i] = ring[dt_wrap(sl - i, K) * C + c];
-#pragma unroll  // fully: the accumulators must stay in registers
-                for (int kk = 0; kk < KPT; ++kk) {
-                    const int k = k0 + kk + 1;
-                    if (k <= K) {
-                        w[0] = ring[sl * C + c];
-                        const double gv = *gp;
+                    for (int i = 0; i < 4; ++i)
+                        ca[i] = i0 + i < ng ? Arow[(i0 + i) * C + cp] * IErow[(i0 + i) * C + c] : 0.0;
+                    double w[KS + 3];
 #pragma unroll
-                        for (int i = 0; i < MBT; ++i) {
-                            if (i < nbk && k > i) {
-                                const double gu = gv * w[i];
-                                bs[i] += gu;
-                                if (ACC) acc[kk] = fma(coef[i], gu, acc[kk]);
-                            }
-                        }
+                    for (int q = 0; q < KS + 3; ++q) w[q] = Vp[(i0 + q) * C + c];
 #pragma unroll
-                        for (int i = MBT - 1; i > 0; --i) w[i] = w[i - 1];
-                        sl = sl + 1 == K ? 0 : sl + 1;
-                        gp += CC;
+                    for (int kk = 0; kk < KS; ++kk) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) acc[kk] = fma(ca[i], w[kk + i], acc[kk]);
                     }
                 }
             }
-            // ---- finish the positions one after the other
-#pragma unroll
-            for (int i = 0; i < MBT; ++i) {
-                if (i < nbk) {  // uniform
-                    const int tt = t0 - i;
-                    if (active) {
-                        // durations 1 .. i end inside the block, at positions finished just before
-                        for (int k = 1; k <= i && k <= K; ++k) {
-                            if (k > k0 && k <= k0 + KPT) {
-                                const double gu = p.G3[(size_t)(k - 1) * CC + pair] * ring[((tt + k) % K) * C + c];
-                                bs[i] += gu;
-                                if (ACC) {
-#pragma unroll
-                                    for (int kk = 0; kk < (KPT < MBT ? KPT : MBT - 1); ++kk)
-                                        if (kk == k - 1 - k0) acc[kk] = fma(coef[i], gu, acc[kk]);
-                                }
-                            }
-                        }
-                        red[ks * CC + pair] = bs[i] * ie[i];
-                    }
-                    __syncthreads();
-                    if (tid < C) {
-                        double bsum = 0.0, osum = 0.0;
-                        for (int q = 0; q < NKS; ++q) {
-                            const double *rq = red + q * CC;
-                            for (int o = 0; o < C; ++o) {
-                                bsum += rq[tid * C + o];
-                                if (ACC) osum = fma(av[i * C + o], rq[o * C + tid], osum);
-                            }
-                        }
-                        yv[tid] = bsum;
-                        ring[(tt % K) * C + tid] = bsum * EI[(size_t)tt * C + tid].x;
-                        if (ACC) {
-                            const double outv = osum * kap[i];
-                            const double inv = tt >= 1 ? av[i * C + tid] * bsum * kap[i] : 0.0;
-                            p.grad_emis[((size_t)b * p.T + tt) * C + tid] = (float)R;
-                            sR += R;
-                            R += outv - inv;
-                            if (tt == 0) p.out0[(size_t)b * C + tid] = outv;
-                        }
-                    }
-                    __syncthreads();
-                }
-            }
-            const int tlast = t0 - nbk + 1;
-            if (mode == 0 && tlast == hi && hi < L) {
-                record(p.ckB + ((size_t)b * (N + 1) + hi / Delta) * ckstride);
-                if (tid == 0) p.ckYB[(size_t)b * (N + 1) + hi / Delta] = Yb;
-            }
-            if (mode == 1 && tlast > 0 && (tlast % Delta) == 0) {
-                record(p.ckB + ((size_t)b * (N + 1) + tlast / Delta) * ckstride);
-                if (tid == 0) p.ckYB[(size_t)b * (N + 1) + tlast / Delta] = Yb;
-            }
-            t0 -= nbk;
-        }
-        if (mode == 0 && lo > 0) {
-            record(p.ckB2 + ((size_t)b * (N + 1) + lo / Delta) * ckstride);
-            if (tid == 0) p.ckYB2[(size_t)b * (N + 1) + lo / Delta] = Yb;
-        }
-        if (mode == 1 && tid == 0) {
-            double s = 0.0;
-            for (int i = 0; i < C; ++i) s += yv[i];
-            p.hdr[b].logZb = Yb * LN2 + log(s);
-        }
-        if (ACC && tid < C) {
-            p.tot[((size_t)b * N + chunk) * C + tid] = R;
-            p.sumR[((size_t)b * N + chunk) * C + tid] = sR;
+            tg0 = tg1;
         }
     }
-    if (ACC && active) {
+    if (active) {
         double *pg = p.partG + (size_t)blockIdx.x * K * CC;
 #pragma unroll
-        for (int kk = 0; kk < KPT; ++kk) {
-            const int k = k0 + kk + 1;
-            if (k <= K) pg[(size_t)(k - 1) * CC + pair] = acc[kk];
+        for (int kk = 0; kk < KS; ++kk) {
+            const int k = kA + kk + 1;
+            if (k <= K) pg[(size_t)(k - 1) * CC + pair] = acc[kk] * p.G3[(size_t)(k - 1) * CC + pair];
         }
     }
 }

@@ -142,6 +142,9 @@ struct Params {
     double *G3;           // [K][C][C] exp(dur[k-1,c] + trans3[k-1,c',c])
     double *dtA;          // [B][T+1][C] forward messages a_t(c), scaled
     double *dtY;          // [B][T+1]    log2 scale of that row relative to its interval's first position
+    double *dtV;          // [B][T+1][C] backward messages v_t(c) = b_t(c) ES_t(c), scaled
+    double *dtD;          // [B][T+1][C] (mass of the segments that start at t) - (that end at t), scaled
+    double *dtYb;         // [B][T+1]    log2 scale of those two rows relative to the interval's upper end
     double *partG;        // [dt_nwg][K][C][C] per-workgroup sums of the weighted segment marginals
     double *sumG;         // [K][C][C] their fixed-order total
     int dt_nwg;
@@ -3481,16 +3484,16 @@ int run_viterbi(Params p, void *workspace, size_t workspace_bytes, hipStream_t s
 // ---------------------------------------------------------------------------
 struct DtGeom {
     int kptf, ntf;        // forward kernel: durations per thread, threads
-    int kpt, ntb;         // backward kernels: durations per thread, threads
-    size_t lds_f, lds_b;  // dynamic LDS bytes
-    int mbi;              // time-block length of the marginal kernel
+    int kpt, ntb;         // backward kernel: durations per thread, threads
+    int ks, nta;          // marginal kernel: durations per workgroup, threads
+    size_t lds_f, lds_b, lds_a;  // dynamic LDS bytes
 };
 
-// False when the sizes do not fit the kernels: the backward kernels hold one label pair per
-// thread and at most 64 durations of it in registers.
+// False when the sizes do not fit the kernels: the backward and marginal kernels hold one
+// label pair per thread.
 bool dt_geometry(int K, int C, DtGeom *g)
 {
-    if (C > 64) return false;
+    if (C > 32) return false;
     const int nksf = K < 1024 / C ? K : 1024 / C;
     const int kptf = (K + nksf - 1) / nksf;
     if (kptf > 8) return false;
@@ -3501,7 +3504,7 @@ bool dt_geometry(int K, int C, DtGeom *g)
     g->kpt = 0;
     for (int kpt = 8; kpt <= 64; kpt *= 2) {
         const int nks = (K + kpt - 1) / kpt;
-        if ((size_t)CC * nks <= (size_t)(kpt == 64 ? 640 : 1024)) {
+        if ((size_t)CC * nks <= 1024) {
             g->kpt = kpt;
             g->ntb = (CC * nks + 63) / 64 * 64;
             g->lds_b = ((size_t)K * C + (size_t)nks * CC + (size_t)(DT_MB + 2) * C) * sizeof(double);
@@ -3509,14 +3512,16 @@ bool dt_geometry(int K, int C, DtGeom *g)
         }
     }
     if (!g->kpt) return false;
-    g->mbi = g->kpt == 64 ? 2 : DT_MB;
+    g->ks = 16;
+    g->nta = (CC + 63) / 64 * 64;
+    g->lds_a = (size_t)(2 * DT_TG + DT_TG + g->ks + 3) * C * sizeof(double);
     return g->lds_f <= LDS_LIMIT && g->lds_b <= LDS_LIMIT;
 }
 
-constexpr int DT_NWG = 512;  // most persistent workgroups of the marginal kernel
+constexpr int DT_NWG = 256;  // most persistent workgroups (per group of 16 durations) of the marginal kernel
 
 struct DtLayout {
-    size_t g3, dta, dty, partg, sumg, total;
+    size_t g3, dta, dty, dtv, dtd, dtyb, partg, sumg, total;
     int nwg;
 };
 
@@ -3530,6 +3535,9 @@ DtLayout dt_layout(int B, int T, int K, int C, int N, int want_grad)
     l.g3 = off; off += align_up(kcc * 8);
     l.dta = off; off += align_up((size_t)B * t1 * C * 8);
     l.dty = off; off += align_up((size_t)B * t1 * 8);
+    l.dtv = off; off += want_grad ? align_up((size_t)B * t1 * C * 8) : 0;
+    l.dtd = off; off += want_grad ? align_up((size_t)B * t1 * C * 8) : 0;
+    l.dtyb = off; off += want_grad ? align_up((size_t)B * t1 * 8) : 0;
     l.partg = off; off += want_grad ? align_up((size_t)l.nwg * kcc * 8) : 0;
     l.sumg = off; off += want_grad ? align_up(kcc * 8) : 0;
     l.total = off;
@@ -3556,32 +3564,23 @@ int launch_dt_fwd_any(const Params &p, const DtGeom &g, hipStream_t st, int grid
     }
 }
 
-template <int KPT, bool ACC, int MBT, int NTMAX>
+template <int KPT>
 int launch_dt_bwd(const Params &p, const DtGeom &g, hipStream_t st, int grid, int warm, int tier, int mode)
 {
-    if (hipFuncSetAttribute((const void *)k_dt_bwd<KPT, ACC, MBT, NTMAX>,
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_b) != hipSuccess)
+    if (hipFuncSetAttribute((const void *)k_dt_bwd<KPT, DT_MB>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)g.lds_b) != hipSuccess)
         return SEMICRF_ELAUNCH;
-    hipLaunchKernelGGL((k_dt_bwd<KPT, ACC, MBT, NTMAX>), dim3(grid), dim3(g.ntb), g.lds_b, st, p, warm, tier, mode);
+    hipLaunchKernelGGL((k_dt_bwd<KPT, DT_MB>), dim3(grid), dim3(g.ntb), g.lds_b, st, p, warm, tier, mode);
     return SEMICRF_OK;
 }
 
-// mode 0 / 1: the scan; mode 2: the marginals
 int launch_dt_bwd_any(const Params &p, const DtGeom &g, hipStream_t st, int grid, int warm, int tier, int mode)
 {
-    if (mode == 2) {
-        switch (g.kpt) {
-        case 8: return launch_dt_bwd<8, true, DT_MB, 1024>(p, g, st, grid, warm, tier, mode);
-        case 16: return launch_dt_bwd<16, true, DT_MB, 1024>(p, g, st, grid, warm, tier, mode);
-        case 32: return launch_dt_bwd<32, true, DT_MB, 1024>(p, g, st, grid, warm, tier, mode);
-        default: return launch_dt_bwd<64, true, 2, 640>(p, g, st, grid, warm, tier, mode);
-        }
-    }
     switch (g.kpt) {
-    case 8: return launch_dt_bwd<8, false, DT_MB, 1024>(p, g, st, grid, warm, tier, mode);
-    case 16: return launch_dt_bwd<16, false, DT_MB, 1024>(p, g, st, grid, warm, tier, mode);
-    case 32: return launch_dt_bwd<32, false, DT_MB, 1024>(p, g, st, grid, warm, tier, mode);
-    default: return launch_dt_bwd<64, false, DT_MB, 640>(p, g, st, grid, warm, tier, mode);
+    case 8: return launch_dt_bwd<8>(p, g, st, grid, warm, tier, mode);
+    case 16: return launch_dt_bwd<16>(p, g, st, grid, warm, tier, mode);
+    case 32: return launch_dt_bwd<32>(p, g, st, grid, warm, tier, mode);
+    default: return launch_dt_bwd<64>(p, g, st, grid, warm, tier, mode);
     }
 }
 
@@ -3605,6 +3604,9 @@ int run_durtrans(Params p, int ckpt_interval, void *workspace, size_t workspace_
     p.G3 = (double *)(dw + dl.g3);
     p.dtA = (double *)(dw + dl.dta);
     p.dtY = (double *)(dw + dl.dty);
+    p.dtV = (double *)(dw + dl.dtv);
+    p.dtD = (double *)(dw + dl.dtd);
+    p.dtYb = (double *)(dw + dl.dtyb);
     p.partG = (double *)(dw + dl.partg);
     p.sumG = (double *)(dw + dl.sumg);
     p.dt_nwg = dl.nwg;
@@ -3634,8 +3636,8 @@ int run_durtrans(Params p, int ckpt_interval, void *workspace, size_t workspace_
     if (!grad) return check_launch();
     rc = launch_dt_bwd_any(p, g, st, p.B, 0, 0, 1);
     if (rc != SEMICRF_OK) return rc;
-    rc = launch_dt_bwd_any(p, g, st, dl.nwg, 0, 0, 2);
-    if (rc != SEMICRF_OK) return rc;
+    hipLaunchKernelGGL(k_dt_emis, dim3(p.B * p.N), dim3(64), 0, st, p);
+    hipLaunchKernelGGL((k_dt_acc<16>), dim3(dl.nwg, (p.K + 15) / 16), dim3(g.nta), g.lds_a, st, p);
     hipLaunchKernelGGL(k_dt_fin, dim3(p.B + (unsigned)((kcc + NT - 1) / NT)), dim3(NT), 0, st, p);
     hipLaunchKernelGGL(k_dt_fin_dur, dim3((p.K * p.C + NT - 1) / NT), dim3(NT), 0, st, p);
     {

@@ -149,3 +149,10 @@ def boundary_terms(w: Workload, seed: int = 12345, scale: float = 0.5):
     pis = rng.standard_normal(w.C).astype(np.float32)
     pie = rng.standard_normal(w.C).astype(np.float32)
     return ps, pe, pis, pie
+
+
+def duration_transitions(w: Workload, seed: int = 777, sd: float = 0.1):
+    """Seeded stand-in for duration-dependent transitions: one [C,C] matrix per duration, the
+    workload's matrix plus N(0, sd^2) noise per (duration, source, destination); float32 [K,C,C]."""
+    rng = np.random.default_rng(seed)
+    return (w.trans[None] + sd * rng.standard_normal((w.K, w.C, w.C))).astype(np.float32)

@@ -18,8 +18,7 @@ DEV = "cuda:0"
 
 def trans3_of(w, seed, sd=0.3):
     """One matrix per duration: the workload's matrix plus duration-dependent noise."""
-    rng = np.random.default_rng(seed)
-    return (w.trans[None] + sd * rng.standard_normal((w.K, w.C, w.C))).astype(np.float32)
+    return synth.duration_transitions(w, seed, sd)
 
 
 def run(w, trans3, center=True, grad_logz=None, ckpt_interval=0, extra_flags=0):
