@@ -95,6 +95,8 @@ __global__ __launch_bounds__(1024) void k_dt_fwd(Params p, int warm, int tier, i
     double *av = X + KC;             // [DT_MB][C]
     double *yv = av + DT_MB * C;     // [C]
     int *sc = (int *)(yv + C);       // [C]
+    double *Gs = yv + 2 * C;         // [DT_MB-1][C][C] table rows of the durations below DT_MB
+    const int KIN = min(K, DT_MB - 1);
     const SeqHdr h = p.hdr[b];
     const int L = h.L, J = h.J;
     const int lo = whole ? 0 : chunk * Delta;
@@ -109,6 +111,7 @@ __global__ __launch_bounds__(1024) void k_dt_fwd(Params p, int warm, int tier, i
     double *rowY = p.dtY + row0;
 
     for (int i = tid; i < KC; i += blockDim.x) X[i] = 0.0;
+    for (int i = tid; i < KIN * CC; i += blockDim.x) Gs[i] = p.G3[i];
     if (tid < C) yv[tid] = 1.0;
     __syncthreads();
     double Y = 0.0, Ybase = 0.0;
@@ -123,11 +126,24 @@ __global__ __launch_bounds__(1024) void k_dt_fwd(Params p, int warm, int tier, i
         if (t0 <= lo) nbk = min(nbk, lo - t0 + 1);  // the interval's first position ends its block
         nbk = min(nbk, J - (t0 % J));               // no scaling-block boundary inside a block
         if (t0 > s0 && (t0 % J) == 0) Y += (double)dt_rebase(X, yv, sc, nb, KC, C, t0 / J, t0 / J - 1, +1);
+        // emission factors of the block's positions: fetched before the dependent chain starts
+        double es[DT_MB], ie[DT_MB];
+#pragma unroll
+        for (int i = 0; i < DT_MB; ++i) {
+            es[i] = 0.0;
+            ie[i] = 0.0;
+            if (i < nbk) {
+                if (tid < C) es[i] = EI[(size_t)(t0 + i) * C + tid].x;
+                if (active) ie[i] = EI[(size_t)(t0 + i) * C + c].y;
+            }
+        }
         // ---- the block's positions, one after the other
-        for (int i = 0; i < nbk; ++i) {
+#pragma unroll
+        for (int i = 0; i < DT_MB; ++i) {
+            if (i >= nbk) break;
             const int tt = t0 + i;
             if (tid < C) {
-                const double a = tt == s0 ? 1.0 : EI[(size_t)tt * C + tid].x * X[(tt % K) * C + tid];
+                const double a = tt == s0 ? 1.0 : es[i] * X[(tt % K) * C + tid];
                 av[i * C + tid] = a;
                 if (tt > lo || tt == 0) rowA[(size_t)tt * C + tid] = a;
             }
@@ -141,11 +157,12 @@ __global__ __launch_bounds__(1024) void k_dt_fwd(Params p, int warm, int tier, i
             if (kin > 0) {
                 const int k = ks + 1;
                 if (active && k <= kin && k <= K) {
-                    const double *g = p.G3 + (size_t)(k - 1) * CC + c;
+                    const double *g = Gs + (size_t)(k - 1) * CC + c;
                     double m = 0.0;
-                    for (int o = 0; o < C; ++o) m = fma(av[i * C + o], g[(size_t)o * C], m);
+#pragma unroll 8
+                    for (int o = 0; o < C; ++o) m = fma(av[i * C + o], g[o * C], m);
                     const int slot = ((tt + k) % K) * C + c;
-                    const double val = EI[(size_t)tt * C + c].y * m;
+                    const double val = ie[i] * m;
                     X[slot] = k == K ? val : X[slot] + val;
                 }
                 __syncthreads();
@@ -160,8 +177,18 @@ __global__ __launch_bounds__(1024) void k_dt_fwd(Params p, int warm, int tier, i
             const int k = ks + 1 + kk * NKS;
             if (active && k <= K) {
                 const double *g = p.G3 + (size_t)(k - 1) * CC + c;
-#pragma unroll 4
-                for (int o = 0; o < C; ++o) {
+                int o = 0;
+                for (; o + 8 <= C; o += 8) {  // eight table loads in flight, then their products
+                    double gv[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) gv[u] = g[(size_t)(o + u) * C];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+#pragma unroll
+                        for (int i = 0; i < DT_MB; ++i) m[kk][i] = fma(av[i * C + o + u], gv[u], m[kk][i]);
+                    }
+                }
+                for (; o < C; ++o) {
                     const double gv = g[(size_t)o * C];
 #pragma unroll
                     for (int i = 0; i < DT_MB; ++i) m[kk][i] = fma(av[i * C + o], gv, m[kk][i]);
@@ -173,13 +200,12 @@ __global__ __launch_bounds__(1024) void k_dt_fwd(Params p, int warm, int tier, i
             if (i < nbk) {  // uniform
                 const int tt = t0 + i;
                 if (active) {
-                    const double ie = EI[(size_t)tt * C + c].y;
 #pragma unroll
                     for (int kk = 0; kk < KPTF; ++kk) {
                         const int k = ks + 1 + kk * NKS;
                         if (k <= K && i + k >= nbk) {
                             const int slot = ((tt + k) % K) * C + c;
-                            const double val = ie * m[kk][i];
+                            const double val = ie[i] * m[kk][i];
                             X[slot] = k == K ? val : X[slot] + val;
                         }
                     }
@@ -240,6 +266,8 @@ __global__ __launch_bounds__(1024) void k_dt_bwd(Params p, int warm, int tier, i
     double *av = red + NKS * CC;      // [MBT][C] a_t of the block's positions
     double *yv = av + MBT * C;        // [C]      b_t: scale reference
     int *sc = (int *)(yv + C);        // [C]
+    double *Gs = yv + 2 * C;          // [MBT-1][C][C] table rows of the durations below MBT
+    const int KIN = min(K, MBT - 1);
     const size_t ckstride = (size_t)KC + C;
 
     const int b = mode == 1 ? (int)blockIdx.x : (int)blockIdx.x / N;
@@ -262,6 +290,7 @@ __global__ __launch_bounds__(1024) void k_dt_bwd(Params p, int warm, int tier, i
 
     // a sequence that ends at s1 (exactly so when s1 = L): b = 1, v = ES
     for (int i = tid; i < KC; i += blockDim.x) ring[i] = 0.0;
+    for (int i = tid; i < KIN * CC; i += blockDim.x) Gs[i] = p.G3[i];
     __syncthreads();
     if (tid < C) {
         yv[tid] = tid == 0 ? 1.0 : 0.0;
@@ -284,14 +313,18 @@ __global__ __launch_bounds__(1024) void k_dt_bwd(Params p, int warm, int tier, i
         nbk = min(nbk, (t0 % J) + 1);                       // no scaling-block boundary inside a block
         if (mode == 1) nbk = min(nbk, (t0 % Delta) + 1);    // checkpoints are recorded at block ends
         if (((t0 + 1) % J) == 0) Yb += (double)dt_rebase(ring, yv, sc, nb, KC, C, t0 / J, t0 / J + 1, -1);
-        double ie[MBT];
+        double ie[MBT], es[MBT];
 #pragma unroll
         for (int i = 0; i < MBT; ++i) {
             ie[i] = 0.0;
+            es[i] = 0.0;
             if (i < nbk) {
                 const int tt = t0 - i;
                 if (active) ie[i] = EI[(size_t)tt * C + c].y;
-                if (tid < C) av[i * C + tid] = rowA[(size_t)tt * C + tid];
+                if (tid < C) {
+                    es[i] = EI[(size_t)tt * C + tid].x;
+                    av[i * C + tid] = rowA[(size_t)tt * C + tid];
+                }
             }
         }
         // ---- durations that reach beyond the block: every table entry once for all positions
@@ -303,23 +336,39 @@ __global__ __launch_bounds__(1024) void k_dt_bwd(Params p, int warm, int tier, i
             // duration (w[0]); the rows of the later positions are the earlier durations' rows
             const double *gp = p.G3 + (size_t)k0 * CC + pair;
             int sl = (t0 + k0 + 1) % K;  // slot of position t0 + k0 + 1
+            const int nk = min(KPT, K - k0);  // this thread's durations (at least one: ks < NKS)
             double w[MBT];
 #pragma unroll
             for (int i = 1; i < MBT; ++i) w[i] = ring[dt_wrap(sl - i, K) * C + c];
-#pragma unroll 16
-            for (int kk = 0; kk < KPT; ++kk) {
-                const int k = k0 + kk + 1;
-                if (k <= K) {
-                    w[0] = ring[sl * C + c];
-                    const double gv = *gp;
+            // A duration k <= i would end inside the block, at a position not finished yet: those
+            // terms are left out here (a select, no branch: the loads of a batch must all be in
+            // flight together) and added from the fresh values below.
+            auto one = [&](const double gv, const double wv, const int k) {
+                w[0] = wv;
 #pragma unroll
-                    for (int i = 0; i < MBT; ++i)
-                        if (i < nbk && k > i) bs[i] = fma(gv, w[i], bs[i]);
+                for (int i = 0; i < MBT; ++i) bs[i] = fma(gv, k > i ? w[i] : 0.0, bs[i]);
 #pragma unroll
-                    for (int i = MBT - 1; i > 0; --i) w[i] = w[i - 1];
-                    sl = sl + 1 == K ? 0 : sl + 1;
-                    gp += CC;
+                for (int i = MBT - 1; i > 0; --i) w[i] = w[i - 1];
+            };
+            int kk = 0;
+            for (; kk + 8 <= nk; kk += 8) {
+                double gv[8], wv[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    gv[u] = gp[(size_t)u * CC];
+                    int su = sl + u;
+                    su = su >= K ? su - K : su;
+                    wv[u] = ring[su * C + c];
                 }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) one(gv[u], wv[u], k0 + kk + u + 1);
+                gp += (size_t)8 * CC;
+                sl = dt_wrap(sl + 8, K);
+            }
+            for (; kk < nk; ++kk) {
+                one(*gp, ring[sl * C + c], k0 + kk + 1);
+                gp += CC;
+                sl = sl + 1 == K ? 0 : sl + 1;
             }
         }
         // ---- finish the positions one after the other
@@ -331,7 +380,7 @@ __global__ __launch_bounds__(1024) void k_dt_bwd(Params p, int warm, int tier, i
                     // durations 1 .. i end inside the block, at positions finished just before
                     for (int k = 1; k <= i && k <= K; ++k)
                         if (k > k0 && k <= k0 + KPT)
-                            bs[i] = fma(p.G3[(size_t)(k - 1) * CC + pair], ring[((tt + k) % K) * C + c], bs[i]);
+                            bs[i] = fma(Gs[(k - 1) * CC + pair], ring[((tt + k) % K) * C + c], bs[i]);
                     red[ks * CC + pair] = bs[i] * ie[i];
                 }
                 __syncthreads();
@@ -339,13 +388,14 @@ __global__ __launch_bounds__(1024) void k_dt_bwd(Params p, int warm, int tier, i
                     double bsum = 0.0, osum = 0.0;
                     for (int q = 0; q < NKS; ++q) {
                         const double *rq = red + q * CC;
+#pragma unroll 8
                         for (int o = 0; o < C; ++o) {
                             bsum += rq[tid * C + o];
                             osum = fma(av[i * C + o], rq[o * C + tid], osum);
                         }
                     }
                     yv[tid] = bsum;
-                    const double v = bsum * EI[(size_t)tt * C + tid].x;
+                    const double v = bsum * es[i];
                     ring[(tt % K) * C + tid] = v;
                     if (tt < hi) {
                         rowV[(size_t)tt * C + tid] = v;

@@ -3499,7 +3499,7 @@ bool dt_geometry(int K, int C, DtGeom *g)
     if (kptf > 8) return false;
     g->kptf = kptf <= 1 ? 1 : (kptf <= 2 ? 2 : (kptf <= 4 ? 4 : 8));
     g->ntf = (C * nksf + 63) / 64 * 64;
-    g->lds_f = ((size_t)K * C + (size_t)(DT_MB + 2) * C) * sizeof(double);
+    g->lds_f = ((size_t)K * C + (size_t)(DT_MB + 2) * C + (size_t)(DT_MB - 1) * C * C) * sizeof(double);
     const int CC = C * C;
     g->kpt = 0;
     for (int kpt = 8; kpt <= 64; kpt *= 2) {
@@ -3507,7 +3507,7 @@ bool dt_geometry(int K, int C, DtGeom *g)
         if ((size_t)CC * nks <= 1024) {
             g->kpt = kpt;
             g->ntb = (CC * nks + 63) / 64 * 64;
-            g->lds_b = ((size_t)K * C + (size_t)nks * CC + (size_t)(DT_MB + 2) * C) * sizeof(double);
+            g->lds_b = ((size_t)K * C + (size_t)nks * CC + (size_t)(DT_MB + 2) * C + (size_t)(DT_MB - 1) * CC) * sizeof(double);
             break;
         }
     }
