@@ -224,14 +224,20 @@ int semicrf_viterbi(const float *emis, const int32_t *lengths, const float *tran
  * Everything else (emis, lengths, dur, grad_logz, flags, logz, grad_emis, pos_marg, stream,
  * errors) as for semicrf_logz_fwd / semicrf_fwd_bwd.  The transition no longer factors out
  * of the sum over durations, so a position costs K*C*C multiply-adds per recurrence.
- * Supported sizes: C <= 64, K <= 8 * floor(1024 / C), and C*C * ceil(K/64) <= 640 or
- * C*C * ceil(K/32) <= 1024 (one label pair per thread, at most 64 durations of it in
- * registers); SEMICRF_EUNSUPPORTED otherwise.  Workspace: semicrf_durtrans_workspace_bytes
- * (that of semicrf_workspace_bytes plus the K*C*C table, the forward messages, O(T*C), and
- * up to 512 partial gradient tables).  semicrf_scan_report applies to this workspace too.
+ * Supported sizes: C <= 32, K <= 8 * floor(1024 / C) and C*C * ceil(K/64) <= 1024 (one label
+ * pair per thread, at most 64 durations per thread in the backward recurrence);
+ * SEMICRF_EUNSUPPORTED otherwise.  Workspace: semicrf_durtrans_workspace_bytes (that of
+ * semicrf_workspace_bytes plus the K*C*C table, four O(T*C) arrays of stored messages and up
+ * to 256 partial gradient tables).  semicrf_scan_report applies to this workspace too.
  */
 int semicrf_durtrans_workspace_bytes(int B, int T, int K, int C, int ckpt_interval, int want_grad,
                                      size_t *bytes);
+
+/* Host only, pure.  The checkpoint interval these calls use: ckpt_interval (clamped to T) when
+ * positive, else their own automatic choice (tasks here are workgroups, not single waves: the
+ * multiple of 8, at least max(8, K/2), that minimises rounds * (warm-up + interval)).  Pass it
+ * as ckpt_interval to semicrf_scan_report. */
+int semicrf_durtrans_ckpt_interval(int B, int T, int K, int C, int ckpt_interval, int *interval);
 
 int semicrf_logz_fwd_durtrans(const float *emis, const int32_t *lengths, const float *trans3,
                               const float *dur, int B, int T, int K, int C, int ckpt_interval,

@@ -19,7 +19,7 @@ EXPORTS = ("semicrf_version", "semicrf_strerror", "semicrf_workspace_bytes",
            "semicrf_cum_scores", "semicrf_logz_fwd", "semicrf_fwd_bwd", "semicrf_fwd_bwd_profiled",
            "semicrf_scan_report", "semicrf_ckpt_interval", "semicrf_logz_fwd_boundary",
            "semicrf_fwd_bwd_boundary", "semicrf_entropies", "semicrf_viterbi_workspace_bytes",
-           "semicrf_viterbi", "semicrf_durtrans_workspace_bytes", "semicrf_logz_fwd_durtrans",
+           "semicrf_viterbi", "semicrf_durtrans_workspace_bytes", "semicrf_durtrans_ckpt_interval", "semicrf_logz_fwd_durtrans",
            "semicrf_fwd_bwd_durtrans")
 SEMICRF_CENTER = 1
 SEMICRF_SEQUENTIAL_SCAN = 2
@@ -74,6 +74,8 @@ def load():
     lib.semicrf_entropies.argtypes = [vp, vp, vp, ci, ci, ci, vp, vp, vp]
     lib.semicrf_durtrans_workspace_bytes.restype = ci
     lib.semicrf_durtrans_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci, ctypes.POINTER(sz)]
+    lib.semicrf_durtrans_ckpt_interval.restype = ci
+    lib.semicrf_durtrans_ckpt_interval.argtypes = [ci, ci, ci, ci, ci, ctypes.POINTER(ci)]
     lib.semicrf_logz_fwd_durtrans.restype = ci
     lib.semicrf_logz_fwd_durtrans.argtypes = lib.semicrf_logz_fwd.argtypes
     lib.semicrf_fwd_bwd_durtrans.restype = ci
@@ -271,6 +273,12 @@ def semicrf_durtrans_workspace_bytes(B, T, K, C, ckpt_interval=0, want_grad=True
     out = ctypes.c_size_t(0)
     _check(load().semicrf_durtrans_workspace_bytes(B, T, K, C, ckpt_interval, int(bool(want_grad)),
                                                    ctypes.byref(out)))
+    return out.value
+
+
+def semicrf_durtrans_ckpt_interval(B, T, K, C, ckpt_interval=0) -> int:
+    out = ctypes.c_int(0)
+    _check(load().semicrf_durtrans_ckpt_interval(B, T, K, C, ckpt_interval, ctypes.byref(out)))
     return out.value
 
 

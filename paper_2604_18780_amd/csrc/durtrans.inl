@@ -384,15 +384,20 @@ __global__ __launch_bounds__(1024) void k_dt_bwd(Params p, int warm, int tier, i
                     red[ks * CC + pair] = bs[i] * ie[i];
                 }
                 __syncthreads();
+                if (NKS > 1) {  // uniform: sum the duration groups per label pair first, in group order
+                    if (tid < CC) {
+                        double sq = red[tid];
+                        for (int q = 1; q < NKS; ++q) sq += red[q * CC + tid];
+                        red[tid] = sq;
+                    }
+                    __syncthreads();
+                }
                 if (tid < C) {
                     double bsum = 0.0, osum = 0.0;
-                    for (int q = 0; q < NKS; ++q) {
-                        const double *rq = red + q * CC;
 #pragma unroll 8
-                        for (int o = 0; o < C; ++o) {
-                            bsum += rq[tid * C + o];
-                            osum = fma(av[i * C + o], rq[o * C + tid], osum);
-                        }
+                    for (int o = 0; o < C; ++o) {
+                        bsum += red[tid * C + o];
+                        osum = fma(av[i * C + o], red[o * C + tid], osum);
                     }
                     yv[tid] = bsum;
                     const double v = bsum * es[i];

@@ -3518,6 +3518,36 @@ bool dt_geometry(int K, int C, DtGeom *g)
     return g->lds_f <= LDS_LIMIT && g->lds_b <= LDS_LIMIT;
 }
 
+// Automatic checkpoint interval of the duration-dependent path: every (sequence, interval) is one
+// workgroup-sized task of the forward and of the backward scan (interval + warm-up positions
+// each); tasks run in rounds of as many workgroups as the chip holds (by threads, and about five
+// waves per SIMD by registers) and a partly filled round costs a full one.  The multiple of 8
+// that minimises rounds * (warm-up + interval), at least max(8, K/2).
+int dt_auto_interval(int B, int T, int K, const DtGeom &g)
+{
+    const int waves = g.ntb / 64;
+    int per_cu = 2048 / g.ntb < 20 / waves ? 2048 / g.ntb : 20 / waves;
+    if (per_cu < 1) per_cu = 1;
+    const double slots = 256.0 * per_cu;
+    const double warm = 2 * K < 32 ? 32.0 : 2.0 * K;
+    const int dlo = K / 2 < 8 ? 8 : K / 2;
+    int best = 0;
+    double best_cost = 0.0;
+    for (int n = 1; n <= 8192; ++n) {
+        int d = ((T + n - 1) / n + 7) & ~7;
+        if (d > T) d = T;
+        if (d < dlo && best) break;
+        const double tasks = (double)B * (double)((T + d - 1) / d);
+        const double cost = ceil(tasks / slots) * (warm + d);
+        if (!best || cost < best_cost) {
+            best = d;
+            best_cost = cost;
+        }
+        if (d <= dlo) break;
+    }
+    return best;
+}
+
 constexpr int DT_NWG = 256;  // most persistent workgroups (per group of 16 durations) of the marginal kernel
 
 struct DtLayout {
@@ -3586,11 +3616,13 @@ int launch_dt_bwd_any(const Params &p, const DtGeom &g, hipStream_t st, int grid
 
 int run_durtrans(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hipStream_t st, bool grad)
 {
+    if (p.B < 1 || p.T < 1 || p.K < 1 || p.C < 1 || ckpt_interval < 0) return SEMICRF_EINVAL;
+    DtGeom g;
+    if (!dt_geometry(p.K, p.C, &g)) return SEMICRF_EUNSUPPORTED;
+    if (ckpt_interval == 0) ckpt_interval = dt_auto_interval(p.B, p.T, p.K, g);
     Plan pl;
     int rc = make_plan(p.B, p.T, p.K, p.C, ckpt_interval, grad ? 1 : 0, &pl);
     if (rc != SEMICRF_OK) return rc;
-    DtGeom g;
-    if (!dt_geometry(p.K, p.C, &g)) return SEMICRF_EUNSUPPORTED;
     const DtLayout dl = dt_layout(p.B, p.T, p.K, p.C, pl.N, grad ? 1 : 0);
     if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < pl.total + dl.total)
         return SEMICRF_EWORKSPACE;
@@ -3857,12 +3889,24 @@ int semicrf_durtrans_workspace_bytes(int B, int T, int K, int C, int ckpt_interv
                                      size_t *bytes)
 {
     if (!bytes) return SEMICRF_EINVAL;
+    if (B < 1 || T < 1 || K < 1 || C < 1 || ckpt_interval < 0) return SEMICRF_EINVAL;
+    DtGeom g;
+    if (!dt_geometry(K, C, &g)) return SEMICRF_EUNSUPPORTED;
+    if (ckpt_interval == 0) ckpt_interval = dt_auto_interval(B, T, K, g);
     Plan pl;
     int rc = make_plan(B, T, K, C, ckpt_interval, want_grad ? 1 : 0, &pl);
     if (rc != SEMICRF_OK) return rc;
+    *bytes = pl.total + dt_layout(B, T, K, C, pl.N, want_grad ? 1 : 0).total;
+    return SEMICRF_OK;
+}
+
+int semicrf_durtrans_ckpt_interval(int B, int T, int K, int C, int ckpt_interval, int *interval)
+{
+    if (!interval) return SEMICRF_EINVAL;
+    if (B < 1 || T < 1 || K < 1 || C < 1 || ckpt_interval < 0) return SEMICRF_EINVAL;
     DtGeom g;
     if (!dt_geometry(K, C, &g)) return SEMICRF_EUNSUPPORTED;
-    *bytes = pl.total + dt_layout(B, T, K, C, pl.N, want_grad ? 1 : 0).total;
+    *interval = ckpt_interval == 0 ? dt_auto_interval(B, T, K, g) : (ckpt_interval > T ? T : ckpt_interval);
     return SEMICRF_OK;
 }
 

@@ -174,6 +174,39 @@ def test_viterbi_and_entropy_entries_check_their_arguments_on_the_host():
     assert lib.semicrf_entropies(fake, fake, None, 1, 0, 3, fake, fake, None) == -1
 
 
+def test_duration_dependent_transition_entries_check_their_arguments_on_the_host():
+    lib = sb.load()
+    out = ctypes.c_size_t(0)
+    iv = ctypes.c_int(0)
+    fake = ctypes.c_void_p(4096)
+    assert lib.semicrf_durtrans_workspace_bytes(1, 8, 2, 3, 0, 1, None) == -1
+    assert lib.semicrf_durtrans_workspace_bytes(0, 8, 2, 3, 0, 1, ctypes.byref(out)) == -1
+    assert lib.semicrf_durtrans_workspace_bytes(1, 8, 2, 3, -1, 1, ctypes.byref(out)) == -1
+    # one label pair per thread: 33 labels and more do not fit a workgroup, nor 32 labels with K > 64
+    assert lib.semicrf_durtrans_workspace_bytes(1, 100, 4, 33, 0, 1, ctypes.byref(out)) == -3
+    assert lib.semicrf_durtrans_workspace_bytes(1, 100, 65, 32, 0, 1, ctypes.byref(out)) == -3
+    assert lib.semicrf_durtrans_workspace_bytes(1, 100, 64, 32, 0, 1, ctypes.byref(out)) == 0
+    # the gradient path needs the stored messages and the partial gradient tables on top
+    assert (sb.semicrf_durtrans_workspace_bytes(4, 100000, 64, 24, 0, True)
+            > sb.semicrf_durtrans_workspace_bytes(4, 100000, 64, 24, 0, False)
+            > sb.semicrf_workspace_bytes(4, 100000, 64, 24, 0, False))
+    # automatic interval: a multiple of 8 (or T), at least max(8, K/2); explicit ones are clamped to T
+    for (B, T, K, C) in [(64, 256, 16, 24), (4, 100000, 64, 24), (1, 400000, 512, 8), (1, 1, 1, 1), (2, 50, 80, 4)]:
+        d = sb.semicrf_durtrans_ckpt_interval(B, T, K, C)
+        assert 1 <= d <= T and (d == T or (d % 8 == 0 and d >= max(8, K // 2)))
+    assert sb.semicrf_durtrans_ckpt_interval(2, 100, 4, 3, 1000) == 100
+    assert lib.semicrf_durtrans_ckpt_interval(2, 100, 4, 3, 0, None) == -1
+    assert lib.semicrf_durtrans_ckpt_interval(2, 100, 4, 64, 0, ctypes.byref(iv)) == -3
+    rc = lib.semicrf_logz_fwd_durtrans(None, None, None, None, 1, 8, 2, 3, 0, 1, None, 0, None, None)
+    assert rc == -1
+    rc = lib.semicrf_fwd_bwd_durtrans(fake, None, fake, fake, None, 1, 8, 2, 3, 0, 1, None, 0,
+                                      fake, fake, fake, fake, None, None)
+    assert rc == -2
+    rc = lib.semicrf_fwd_bwd_durtrans(fake, None, fake, fake, None, 1, 8, 2, 3, 0, 1, fake, 1 << 30,
+                                      fake, fake, None, fake, None, None)
+    assert rc == -1                                  # grad_trans3 is required
+
+
 def test_binding_requires_the_built_library(monkeypatch, tmp_path):
     import importlib
     mod = importlib.reload(sb)

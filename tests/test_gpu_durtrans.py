@@ -31,7 +31,8 @@ def run(w, trans3, center=True, grad_logz=None, ckpt_interval=0, extra_flags=0):
             torch.from_numpy(trans3).to(DEV), torch.from_numpy(w.dur).to(DEV))
     ws = sb.alloc_durtrans_workspace(w.B, w.T, w.K, w.C, ckpt_interval, True, DEV)
     out = sb.semicrf_fwd_bwd_durtrans(*args, gl, ckpt_interval, flags, workspace=ws)
-    acc, mis = sb.semicrf_scan_report(ws, w.B, w.T, w.K, w.C, ckpt_interval, True)
+    acc, mis = sb.semicrf_scan_report(ws, w.B, w.T, w.K, w.C,
+                                      sb.semicrf_durtrans_ckpt_interval(w.B, w.T, w.K, w.C, ckpt_interval), True)
     lz_f = sb.semicrf_logz_fwd_durtrans(*args, ckpt_interval, flags)
     torch.cuda.synchronize()
     res = [None if o is None else o.double().cpu().numpy() for o in out]
