@@ -174,22 +174,45 @@ __global__ __launch_bounds__(1024) void k_dt_fwd(Params p, int warm, int tier, i
         for (int kk = 0; kk < KPTF; ++kk) {
 #pragma unroll
             for (int i = 0; i < DT_MB; ++i) m[kk][i] = 0.0;
-            const int k = ks + 1 + kk * NKS;
-            if (active && k <= K) {
-                const double *g = p.G3 + (size_t)(k - 1) * CC + c;
-                int o = 0;
-                for (; o + 8 <= C; o += 8) {  // eight table loads in flight, then their products
-                    double gv[8];
+        }
+        if (active) {
+            // source labels in chunks of four: the chunk's a values are read once (broadcast) for all
+            // the thread's durations; 4 * KPTF table loads are in flight together
+            unsigned gi[KPTF];
+            bool kok[KPTF];
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) gv[u] = g[(size_t)(o + u) * C];
+            for (int kk = 0; kk < KPTF; ++kk) {
+                const int k = ks + 1 + kk * NKS;
+                kok[kk] = k <= K;
+                gi[kk] = (unsigned)((kok[kk] ? k - 1 : 0) * CC + c);
+            }
+            const double *G3 = p.G3;
+            int o = 0;
+            for (; o + 4 <= C; o += 4) {
+                double a4[DT_MB][4], gv[KPTF][4];
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) {
+                for (int kk = 0; kk < KPTF; ++kk) {
 #pragma unroll
-                        for (int i = 0; i < DT_MB; ++i) m[kk][i] = fma(av[i * C + o + u], gv[u], m[kk][i]);
+                    for (int u = 0; u < 4; ++u) gv[kk][u] = G3[gi[kk] + (unsigned)((o + u) * C)];
+                }
+#pragma unroll
+                for (int i = 0; i < DT_MB; ++i) {
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) a4[i][u] = av[i * C + o + u];
+                }
+#pragma unroll
+                for (int kk = 0; kk < KPTF; ++kk) {
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+#pragma unroll
+                        for (int i = 0; i < DT_MB; ++i) m[kk][i] = fma(a4[i][u], gv[kk][u], m[kk][i]);
                     }
                 }
-                for (; o < C; ++o) {
-                    const double gv = g[(size_t)o * C];
+            }
+            for (; o < C; ++o) {
+#pragma unroll
+                for (int kk = 0; kk < KPTF; ++kk) {
+                    const double gv = G3[gi[kk] + (unsigned)(o * C)];
 #pragma unroll
                     for (int i = 0; i < DT_MB; ++i) m[kk][i] = fma(av[i * C + o], gv, m[kk][i]);
                 }
@@ -334,40 +357,59 @@ __global__ __launch_bounds__(1024) void k_dt_bwd(Params p, int warm, int tier, i
         if (active) {
             // position t0 - i with duration k reads v of position t0 + k - i: one new ring row per
             // duration (w[0]); the rows of the later positions are the earlier durations' rows
-            const double *gp = p.G3 + (size_t)k0 * CC + pair;
-            int sl = (t0 + k0 + 1) % K;  // slot of position t0 + k0 + 1
-            const int nk = min(KPT, K - k0);  // this thread's durations (at least one: ks < NKS)
+            const double *G3 = p.G3;
+            unsigned gi = (unsigned)(k0 * CC + pair);  // index of G[k0 + 1][c'][c] (the table is < 4 GB)
+            int sl = (t0 + k0 + 1) % K;                // slot of position t0 + k0 + 1
+            const int nk = min(KPT, K - k0);           // this thread's durations (at least one: ks < NKS)
             double w[MBT];
 #pragma unroll
             for (int i = 1; i < MBT; ++i) w[i] = ring[dt_wrap(sl - i, K) * C + c];
-            // A duration k <= i would end inside the block, at a position not finished yet: those
-            // terms are left out here (a select, no branch: the loads of a batch must all be in
-            // flight together) and added from the fresh values below.
-            auto one = [&](const double gv, const double wv, const int k) {
-                w[0] = wv;
-#pragma unroll
-                for (int i = 0; i < MBT; ++i) bs[i] = fma(gv, k > i ? w[i] : 0.0, bs[i]);
-#pragma unroll
-                for (int i = MBT - 1; i > 0; --i) w[i] = w[i - 1];
-            };
             int kk = 0;
+            // A duration k <= i would end inside the block, at a position not finished yet: those
+            // terms are left out here and added from the fresh values below.  Only the durations
+            // below MBT are affected; they are taken first, one by one.
+            if (k0 == 0) {
+                for (; kk < MBT - 1 && kk < nk; ++kk) {
+                    const double gv = G3[gi];
+                    w[0] = ring[sl * C + c];
+#pragma unroll
+                    for (int i = 0; i < MBT; ++i) bs[i] = fma(gv, kk + 1 > i ? w[i] : 0.0, bs[i]);
+#pragma unroll
+                    for (int i = MBT - 1; i > 0; --i) w[i] = w[i - 1];
+                    gi += CC;
+                    sl = sl + 1 == K ? 0 : sl + 1;
+                }
+            }
+            // the rest in batches of eight table loads in flight together (no branch between them)
             for (; kk + 8 <= nk; kk += 8) {
                 double gv[8], wv[8];
+                const bool nowrap = sl + 8 <= K;
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
-                    gv[u] = gp[(size_t)u * CC];
+                    gv[u] = G3[gi + (unsigned)(u * CC)];
                     int su = sl + u;
-                    su = su >= K ? su - K : su;
+                    if (!nowrap) su = su >= K ? su - K : su;
                     wv[u] = ring[su * C + c];
                 }
 #pragma unroll
-                for (int u = 0; u < 8; ++u) one(gv[u], wv[u], k0 + kk + u + 1);
-                gp += (size_t)8 * CC;
+                for (int u = 0; u < 8; ++u) {
+                    w[0] = wv[u];
+#pragma unroll
+                    for (int i = 0; i < MBT; ++i) bs[i] = fma(gv[u], w[i], bs[i]);
+#pragma unroll
+                    for (int i = MBT - 1; i > 0; --i) w[i] = w[i - 1];
+                }
+                gi += (unsigned)(8 * CC);
                 sl = dt_wrap(sl + 8, K);
             }
             for (; kk < nk; ++kk) {
-                one(*gp, ring[sl * C + c], k0 + kk + 1);
-                gp += CC;
+                const double gv = G3[gi];
+                w[0] = ring[sl * C + c];
+#pragma unroll
+                for (int i = 0; i < MBT; ++i) bs[i] = fma(gv, w[i], bs[i]);
+#pragma unroll
+                for (int i = MBT - 1; i > 0; --i) w[i] = w[i - 1];
+                gi += CC;
                 sl = sl + 1 == K ? 0 : sl + 1;
             }
         }

@@ -15,6 +15,10 @@ holds the gradients of those terms and the boundary posterior at the sampled row
 With ``--viterbi`` the oracle's Viterbi decode is run instead and its best scores and segment
 counts are stored in full_<name>_viterbi.npz.
 
+With ``--durtrans`` the oracle runs with the seeded duration-dependent transitions of
+``synth.duration_transitions`` (one matrix per duration) and the file is full_<name>_durtrans.npz
+(grad_trans is then [K,C,C]).
+
 Output: tests/golden/full_<name>.npz (float64 arrays, a few hundred KB each).
 """
 import os
@@ -49,6 +53,7 @@ def sample_rows(w, seed=12345):
 def main(args):
     names = [a for a in args if not a.startswith("--")]
     boundary = "--boundary" in args
+    durtrans = "--durtrans" in args
     for name in names:
         w = synth.make(name)
         t0 = time.time()
@@ -60,7 +65,9 @@ def main(args):
             print(f"{name}: oracle viterbi {dt:.1f}s -> {out}", flush=True)
             continue
         extra = {}
-        if boundary:
+        if durtrans:
+            r = oracle.fwd_bwd_durtrans(w.emis, w.lengths, synth.duration_transitions(w), w.dur)
+        elif boundary:
             ps, pe, pis, pie = synth.boundary_terms(w)
             r = oracle.fwd_bwd(w.emis, w.lengths, w.trans, w.dur, proj_start=ps, proj_end=pe, pi_start=pis,
                                pi_end=pie)
@@ -75,7 +82,7 @@ def main(args):
                          grad_pi_start=r.grad_pi_start, grad_pi_end=r.grad_pi_end,
                          bdy_post_total=np.array([r.bdy_post.sum()]))
         out = os.path.join(os.path.dirname(os.path.abspath(__file__)),
-                           f"full_{name}{'_boundary' if boundary else ''}.npz")
+                           f"full_{name}{'_durtrans' if durtrans else ('_boundary' if boundary else '')}.npz")
         np.savez_compressed(
             out, logz=r.logz, grad_trans=r.grad_trans, grad_dur=r.grad_dur, rows=rows,
             pos_marg_rows=r.pos_marg[rows[:, 0], rows[:, 1]],

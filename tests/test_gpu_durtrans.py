@@ -157,3 +157,37 @@ def test_unsupported_sizes_are_reported():
     with pytest.raises(sb.SemiCRFError) as e:
         sb.semicrf_durtrans_workspace_bytes(2, 100, 128, 32)         # 1024 pairs x 2 duration groups
     assert e.value.status == -3
+
+
+def test_full_size_genomic_against_stored_oracle_values():
+    """The genomic shape at full size, in the launch configuration bench.py --durtrans times,
+    against oracle values stored by tests/golden/make_golden.py genomic --durtrans."""
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "full_genomic_durtrans.npz")
+    if not os.path.exists(path):
+        pytest.skip(f"{path} not generated")
+    g = np.load(path)
+    w = synth.make("genomic")
+    t3 = synth.duration_transitions(w)
+    print(f"[case] full genomic, duration-dependent transitions B={w.B} T={w.T} K={w.K} C={w.C}", flush=True)
+    dev = [torch.from_numpy(a).to(DEV) for a in (w.emis, w.lengths, t3, w.dur)]
+    logz, g_e, g_t, g_d, pm = sb.semicrf_fwd_bwd_durtrans(*dev)
+    torch.cuda.synchronize()
+    rel = np.abs(logz.double().cpu().numpy() - g["logz"]) / np.abs(g["logz"])
+    rows = g["rows"]
+    rb = torch.from_numpy(rows[:, 0]).to(DEV)
+    ru = torch.from_numpy(rows[:, 1]).to(DEV)
+    e_pm = np.abs(pm[rb, ru].double().cpu().numpy() - g["pos_marg_rows"]).max()
+    e_ge = np.abs(g_e[rb, ru].double().cpu().numpy() - g["grad_emis_rows"]).max()
+    e_t = np.abs(g_t.double().cpu().numpy() - g["grad_trans"]).max()
+    e_d = np.abs(g_d.double().cpu().numpy() - g["grad_dur"]).max()
+    print(f"       max err: logz rel {rel.max():.2e} pos_marg {e_pm:.2e} grad_emis {e_ge:.2e} "
+          f"grad_trans3 {e_t:.2e} (max|g| {np.abs(g['grad_trans']).max():.3g}) "
+          f"grad_dur {e_d:.2e} (max|g| {np.abs(g['grad_dur']).max():.3g})", flush=True)
+    assert rel.max() <= 1e-5
+    assert e_pm <= 1e-4 and e_ge <= 1e-4
+    assert e_t <= 1e-4 * max(1.0, np.abs(g["grad_trans"]).max())
+    assert e_d <= 1e-4 * max(1.0, np.abs(g["grad_dur"]).max())
+    row_sum = pm.double().sum(-1)
+    assert (row_sum - 1.0).abs().max().item() <= 1e-5              # every token of this workload is valid
+    assert abs(g_t.double().sum().item() - g_d.double().sum().item()) <= 1e-5 * g_d.double().sum().item()
