@@ -25,6 +25,8 @@
 // every table entry is loaded once per block.  Terms between positions of the same block
 // (durations < DT_MB) are added while the block's positions are finished one after the other.
 // Only the first position of a block may cross a scaling-block boundary.
+// The barriers inside the scans order LDS traffic only (lds_barrier): a full barrier would
+// also wait for the global stores of the rows just written, a round trip per position.
 // ---------------------------------------------------------------------------
 constexpr int DT_MB = 4;
 
@@ -52,15 +54,15 @@ __device__ __forceinline__ int dt_wrap(int i, const int K)
 __device__ __forceinline__ int dt_rebase(double *ring, const double *yv, int *sc, const int *nb, int KC,
                                          int C, int jnew, int jold, int sgn)
 {
-    __syncthreads();  // yv and the ring are complete
+    lds_barrier();  // yv and the ring are complete
     double pm = 0.0;
     for (int i = 0; i < C; ++i) pm += yv[i];
     const int e = safe_exponent(pm);
     const int tid = threadIdx.x;
     if (tid < C) sc[tid] = sgn * (nb[(size_t)jnew * C + tid] - nb[(size_t)jold * C + tid]) - e;
-    __syncthreads();
+    lds_barrier();
     for (int i = tid; i < KC; i += blockDim.x) ring[i] = fmin(ldexp(ring[i], sc[i % C]), DBL_MAX);
-    __syncthreads();
+    lds_barrier();
     return e;
 }
 
@@ -113,7 +115,7 @@ __global__ __launch_bounds__(1024) void k_dt_fwd(Params p, int warm, int tier, i
     for (int i = tid; i < KC; i += blockDim.x) X[i] = 0.0;
     for (int i = tid; i < KIN * CC; i += blockDim.x) Gs[i] = p.G3[i];
     if (tid < C) yv[tid] = 1.0;
-    __syncthreads();
+    lds_barrier();
     double Y = 0.0, Ybase = 0.0;
     auto record = [&](double *ck) {
         for (int i = tid; i < KC; i += blockDim.x) ck[i] = X[i];
@@ -152,7 +154,7 @@ __global__ __launch_bounds__(1024) void k_dt_fwd(Params p, int warm, int tier, i
                 if (whole && (tt % Delta) == 0) p.ckYA[(size_t)b * (N + 1) + tt / Delta] = Y;
             }
             if ((whole && (tt % Delta) == 0) || tt == lo) Ybase = Y;  // uniform
-            __syncthreads();
+            lds_barrier();
             const int kin = nbk - 1 - i;  // durations that stay inside the block
             if (kin > 0) {
                 const int k = ks + 1;
@@ -165,7 +167,7 @@ __global__ __launch_bounds__(1024) void k_dt_fwd(Params p, int warm, int tier, i
                     const double val = ie[i] * m;
                     X[slot] = k == K ? val : X[slot] + val;
                 }
-                __syncthreads();
+                lds_barrier();
             }
         }
         // ---- durations that leave the block: every table entry once for all its positions
@@ -233,7 +235,7 @@ __global__ __launch_bounds__(1024) void k_dt_fwd(Params p, int warm, int tier, i
                         }
                     }
                 }
-                __syncthreads();
+                lds_barrier();
             }
         }
         if (tid < C) yv[tid] = av[(nbk - 1) * C + tid];
@@ -249,7 +251,7 @@ __global__ __launch_bounds__(1024) void k_dt_fwd(Params p, int warm, int tier, i
         if (tid == 0) p.ckYA2[(size_t)b * (N + 1) + chunk + 1] = Y;
         return;
     }
-    __syncthreads();
+    lds_barrier();
     if (tid == 0) {
         double s = 0.0;
         for (int i = 0; i < C; ++i) s += yv[i];
@@ -282,11 +284,14 @@ __global__ __launch_bounds__(1024) void k_dt_bwd(Params p, int warm, int tier, i
     const int NKS = (K + KPT - 1) / KPT;
     const int ks = tid / CC, pair = tid % CC;
     const int c = pair % C;
+    const int CP1 = C | 1, CCP = C * CP1;         // odd row stride of the pair table: rows and columns
+    const int ppair = (pair / C) * CP1 + c;       // are both read without bank conflicts
     const bool active = ks < NKS;
     const int k0 = ks * KPT;  // the thread's durations are k0 + 1 .. k0 + KPT
-    double *ring = lds_raw;           // [K][C]   v_u(c) at slot u mod K
-    double *red = ring + KC;          // [NKS][C][C]
-    double *av = red + NKS * CC;      // [MBT][C] a_t of the block's positions
+    double *ring = lds_raw;           // [2K][C]  v_u(c) at slots u mod K and u mod K + K: K consecutive
+                                      //          positions are K consecutive rows wherever they start
+    double *red = ring + 2 * KC;      // [NKS][C][C|1]
+    double *av = red + NKS * CCP;     // [MBT][C] a_t of the block's positions
     double *yv = av + MBT * C;        // [C]      b_t: scale reference
     int *sc = (int *)(yv + C);        // [C]
     double *Gs = yv + 2 * C;          // [MBT-1][C][C] table rows of the durations below MBT
@@ -312,20 +317,21 @@ __global__ __launch_bounds__(1024) void k_dt_bwd(Params p, int warm, int tier, i
     double *rowYb = p.dtYb + row0;
 
     // a sequence that ends at s1 (exactly so when s1 = L): b = 1, v = ES
-    for (int i = tid; i < KC; i += blockDim.x) ring[i] = 0.0;
+    for (int i = tid; i < 2 * KC; i += blockDim.x) ring[i] = 0.0;
     for (int i = tid; i < KIN * CC; i += blockDim.x) Gs[i] = p.G3[i];
-    __syncthreads();
+    lds_barrier();
     if (tid < C) {
         yv[tid] = tid == 0 ? 1.0 : 0.0;
         const double v = EI[(size_t)s1 * C + tid].x;
         ring[(s1 % K) * C + tid] = v;
+        ring[(s1 % K + K) * C + tid] = v;
         if (s1 == L) rowV[(size_t)L * C + tid] = v;
     }
     if (s1 == L && tid == 0) rowYb[L] = 0.0;
     double Yb = 0.0, Ytop = 0.0;
-    __syncthreads();
+    lds_barrier();
     auto record = [&](double *ck) {
-        for (int i = tid; i < KC; i += blockDim.x) ck[i] = ring[i];
+        for (int i = tid; i < KC; i += blockDim.x) ck[i] = ring[i];  // first copy of the ring
         if (tid < C) ck[KC + tid] = yv[tid];
     };
 
@@ -335,7 +341,7 @@ __global__ __launch_bounds__(1024) void k_dt_bwd(Params p, int warm, int tier, i
         if (t0 >= hi) nbk = min(nbk, t0 - hi + 1);         // the interval's upper end ends its block
         nbk = min(nbk, (t0 % J) + 1);                       // no scaling-block boundary inside a block
         if (mode == 1) nbk = min(nbk, (t0 % Delta) + 1);    // checkpoints are recorded at block ends
-        if (((t0 + 1) % J) == 0) Yb += (double)dt_rebase(ring, yv, sc, nb, KC, C, t0 / J, t0 / J + 1, -1);
+        if (((t0 + 1) % J) == 0) Yb += (double)dt_rebase(ring, yv, sc, nb, 2 * KC, C, t0 / J, t0 / J + 1, -1);
         double ie[MBT], es[MBT];
 #pragma unroll
         for (int i = 0; i < MBT; ++i) {
@@ -359,8 +365,9 @@ __global__ __launch_bounds__(1024) void k_dt_bwd(Params p, int warm, int tier, i
             // duration (w[0]); the rows of the later positions are the earlier durations' rows
             const double *G3 = p.G3;
             unsigned gi = (unsigned)(k0 * CC + pair);  // index of G[k0 + 1][c'][c] (the table is < 4 GB)
-            int sl = (t0 + k0 + 1) % K;                // slot of position t0 + k0 + 1
+            const int sl = (t0 + k0 + 1) % K;          // slot of position t0 + k0 + 1
             const int nk = min(KPT, K - k0);           // this thread's durations (at least one: ks < NKS)
+            const double *rp = ring + sl * C + c;      // rows sl, sl + 1, ... of the doubled ring: no wrap
             double w[MBT];
 #pragma unroll
             for (int i = 1; i < MBT; ++i) w[i] = ring[dt_wrap(sl - i, K) * C + c];
@@ -370,26 +377,23 @@ __global__ __launch_bounds__(1024) void k_dt_bwd(Params p, int warm, int tier, i
             // below MBT are affected; they are taken first, one by one.
             if (k0 == 0) {
                 for (; kk < MBT - 1 && kk < nk; ++kk) {
-                    const double gv = G3[gi];
-                    w[0] = ring[sl * C + c];
+                    const double gv = Gs[kk * CC + pair];  // the short durations' rows are in LDS
+                    w[0] = *rp;
 #pragma unroll
                     for (int i = 0; i < MBT; ++i) bs[i] = fma(gv, kk + 1 > i ? w[i] : 0.0, bs[i]);
 #pragma unroll
                     for (int i = MBT - 1; i > 0; --i) w[i] = w[i - 1];
                     gi += CC;
-                    sl = sl + 1 == K ? 0 : sl + 1;
+                    rp += C;
                 }
             }
             // the rest in batches of eight table loads in flight together (no branch between them)
             for (; kk + 8 <= nk; kk += 8) {
                 double gv[8], wv[8];
-                const bool nowrap = sl + 8 <= K;
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
                     gv[u] = G3[gi + (unsigned)(u * CC)];
-                    int su = sl + u;
-                    if (!nowrap) su = su >= K ? su - K : su;
-                    wv[u] = ring[su * C + c];
+                    wv[u] = rp[u * C];
                 }
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
@@ -400,17 +404,26 @@ __global__ __launch_bounds__(1024) void k_dt_bwd(Params p, int warm, int tier, i
                     for (int i = MBT - 1; i > 0; --i) w[i] = w[i - 1];
                 }
                 gi += (unsigned)(8 * CC);
-                sl = dt_wrap(sl + 8, K);
+                rp += 8 * C;
             }
-            for (; kk < nk; ++kk) {
-                const double gv = G3[gi];
-                w[0] = ring[sl * C + c];
+            if (kk < nk) {  // the last, partial batch: indices clamped, surplus terms times zero (no serial loads)
+                double gv[8], wv[8];
+                const int left = nk - kk;
 #pragma unroll
-                for (int i = 0; i < MBT; ++i) bs[i] = fma(gv, w[i], bs[i]);
+                for (int u = 0; u < 8; ++u) {
+                    const int uu = u < left ? u : left - 1;
+                    gv[u] = G3[gi + (unsigned)(uu * CC)];
+                    wv[u] = rp[uu * C];
+                }
 #pragma unroll
-                for (int i = MBT - 1; i > 0; --i) w[i] = w[i - 1];
-                gi += CC;
-                sl = sl + 1 == K ? 0 : sl + 1;
+                for (int u = 0; u < 8; ++u) {
+                    w[0] = wv[u];
+                    const double g = u < left ? gv[u] : 0.0;
+#pragma unroll
+                    for (int i = 0; i < MBT; ++i) bs[i] = fma(g, w[i], bs[i]);
+#pragma unroll
+                    for (int i = MBT - 1; i > 0; --i) w[i] = w[i - 1];
+                }
             }
         }
         // ---- finish the positions one after the other
@@ -423,34 +436,35 @@ __global__ __launch_bounds__(1024) void k_dt_bwd(Params p, int warm, int tier, i
                     for (int k = 1; k <= i && k <= K; ++k)
                         if (k > k0 && k <= k0 + KPT)
                             bs[i] = fma(Gs[(k - 1) * CC + pair], ring[((tt + k) % K) * C + c], bs[i]);
-                    red[ks * CC + pair] = bs[i] * ie[i];
+                    red[ks * CCP + ppair] = bs[i] * ie[i];
                 }
-                __syncthreads();
+                lds_barrier();
                 if (NKS > 1) {  // uniform: sum the duration groups per label pair first, in group order
                     if (tid < CC) {
-                        double sq = red[tid];
-                        for (int q = 1; q < NKS; ++q) sq += red[q * CC + tid];
-                        red[tid] = sq;
+                        double sq = red[ppair];
+                        for (int q = 1; q < NKS; ++q) sq += red[q * CCP + ppair];
+                        red[ppair] = sq;
                     }
-                    __syncthreads();
+                    lds_barrier();
                 }
                 if (tid < C) {
                     double bsum = 0.0, osum = 0.0;
 #pragma unroll 8
                     for (int o = 0; o < C; ++o) {
-                        bsum += red[tid * C + o];
-                        osum = fma(av[i * C + o], red[o * C + tid], osum);
+                        bsum += red[tid * CP1 + o];
+                        osum = fma(av[i * C + o], red[o * CP1 + tid], osum);
                     }
                     yv[tid] = bsum;
                     const double v = bsum * es[i];
                     ring[(tt % K) * C + tid] = v;
+                    ring[(tt % K + K) * C + tid] = v;
                     if (tt < hi) {
                         rowV[(size_t)tt * C + tid] = v;
                         rowD[(size_t)tt * C + tid] = osum - (tt >= 1 ? av[i * C + tid] * bsum : 0.0);
                     }
                 }
                 if (tid == 0 && tt < hi) rowYb[tt] = Yb - Ytop;
-                __syncthreads();
+                lds_barrier();
             }
         }
         const int tlast = t0 - nbk + 1;

@@ -3507,7 +3507,7 @@ bool dt_geometry(int K, int C, DtGeom *g)
         if ((size_t)CC * nks <= 1024) {
             g->kpt = kpt;
             g->ntb = (CC * nks + 63) / 64 * 64;
-            g->lds_b = ((size_t)K * C + (size_t)nks * CC + (size_t)(DT_MB + 2) * C + (size_t)(DT_MB - 1) * CC) * sizeof(double);
+            g->lds_b = ((size_t)2 * K * C + (size_t)nks * C * (C | 1) + (size_t)(DT_MB + 2) * C + (size_t)(DT_MB - 1) * CC) * sizeof(double);
             break;
         }
     }
