@@ -29,6 +29,7 @@
 // also wait for the global stores of the rows just written, a round trip per position.
 // ---------------------------------------------------------------------------
 constexpr int DT_MB = 4;
+constexpr int DT_NB = 8;  // table loads a thread of the backward scan keeps in flight
 
 // G[k][c'][c] = exp(dur[k,c] + trans3[k,c',c])
 __global__ __launch_bounds__(NT) void k_dt_tables(Params p)
@@ -387,36 +388,36 @@ __global__ __launch_bounds__(1024) void k_dt_bwd(Params p, int warm, int tier, i
                     rp += C;
                 }
             }
-            // the rest in batches of eight table loads in flight together (no branch between them)
-            for (; kk + 8 <= nk; kk += 8) {
-                double gv[8], wv[8];
+            // the rest in batches of DT_NB table loads in flight together (no branch between them)
+            for (; kk + DT_NB <= nk; kk += DT_NB) {
+                double gv[DT_NB], wv[DT_NB];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
+                for (int u = 0; u < DT_NB; ++u) {
                     gv[u] = G3[gi + (unsigned)(u * CC)];
                     wv[u] = rp[u * C];
                 }
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
+                for (int u = 0; u < DT_NB; ++u) {
                     w[0] = wv[u];
 #pragma unroll
                     for (int i = 0; i < MBT; ++i) bs[i] = fma(gv[u], w[i], bs[i]);
 #pragma unroll
                     for (int i = MBT - 1; i > 0; --i) w[i] = w[i - 1];
                 }
-                gi += (unsigned)(8 * CC);
-                rp += 8 * C;
+                gi += (unsigned)(DT_NB * CC);
+                rp += DT_NB * C;
             }
             if (kk < nk) {  // the last, partial batch: indices clamped, surplus terms times zero (no serial loads)
-                double gv[8], wv[8];
+                double gv[DT_NB], wv[DT_NB];
                 const int left = nk - kk;
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
+                for (int u = 0; u < DT_NB; ++u) {
                     const int uu = u < left ? u : left - 1;
                     gv[u] = G3[gi + (unsigned)(uu * CC)];
                     wv[u] = rp[uu * C];
                 }
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
+                for (int u = 0; u < DT_NB; ++u) {
                     w[0] = wv[u];
                     const double g = u < left ? gv[u] : 0.0;
 #pragma unroll
