@@ -2112,12 +2112,14 @@ __global__ __launch_bounds__(64) void k_spec(Params p, int both, int warm, int t
     else spec_task<CT, NKW, true>(p, lds_raw, b, j, warm);
 }
 
-// One wave per (chunk boundary j, sequence, direction): compare the state chunk j-1
+// One workgroup per (chunk boundary j, sequence, direction): compare the state chunk j-1
 // (forward) / chunk j (backward) reached at position j*Delta with the warm-up state the
 // neighbouring chunk started from.
-__global__ __launch_bounds__(64) void k_spec_cmp(Params p, int tier)
+__global__ __launch_bounds__(NT) void k_spec_cmp(Params p, int tier)
 {
-    const int j = blockIdx.x, b = blockIdx.y, dir = blockIdx.z, lane = threadIdx.x;
+    __shared__ double part[NT / 64];
+    const int j = blockIdx.x, b = blockIdx.y, dir = blockIdx.z, tid = threadIdx.x;
+    const int lane = tid & 63, wv = tid >> 6;
     if (tier > 0 && p.spec_ok[b * 2 + dir]) return;
     const int L = p.hdr[b].L;
     const int nint = (L + p.Delta - 1) / p.Delta;
@@ -2128,7 +2130,8 @@ __global__ __launch_bounds__(64) void k_spec_cmp(Params p, int tier)
     const double *A2 = (dir ? p.ckB2 : p.ckA2) + ((size_t)b * (N + 1) + j) * ckstride;  // reached state
     const double Y = (dir ? p.ckYB : p.ckYA)[(size_t)b * (N + 1) + j];
     const double Y2 = (dir ? p.ckYB2 : p.ckYA2)[(size_t)b * (N + 1) + j];
-    // sums of the two message vectors (their ratio is the common scale factor); C <= 64 here
+    // sums of the two message vectors (their ratio is the common scale factor); C <= 64 here:
+    // every wave forms them, in lane order
     double s1 = lane < C ? A[KC + lane] : 0.0, s2 = lane < C ? A2[KC + lane] : 0.0;
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
@@ -2138,8 +2141,8 @@ __global__ __launch_bounds__(64) void k_spec_cmp(Params p, int tier)
     const double f = s2 / s1;  // reached = f * 2^(Y2-Y) * warm-up, entry by entry, if they agree
     double err = 0.0;
     if (!(s1 > 0.0) || !(s2 > 0.0) || !(f > 0.0) || !(f < DBL_MAX)) err = DBL_MAX;
-#pragma unroll 4
-    for (int i = lane; i < KC + C; i += 64) {
+#pragma unroll 8
+    for (int i = tid; i < KC + C; i += NT) {
         const double x = A2[i], y = A[i] * f;
         const double m = fmax(fabs(x), fabs(y));
         if (m > 1e-290) err = fmax(err, fabs(x - y) / m);
@@ -2147,7 +2150,10 @@ __global__ __launch_bounds__(64) void k_spec_cmp(Params p, int tier)
     }
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) err = fmax(err, __shfl_xor(err, off));
-    if (lane == 0) {
+    if (lane == 0) part[wv] = err;
+    __syncthreads();
+    if (tid == 0) {
+        for (int i = 1; i < NT / 64; ++i) err = fmax(err, part[i]);
         const size_t o = ((size_t)b * 2 + dir) * (N + 1) + j;
         p.spec_err[o] = err;
         p.spec_lr[o] = (Y2 - Y) + log2(f);
@@ -3248,7 +3254,7 @@ int launch_spec_k(const Params &p, hipStream_t st, bool both, int warm, int tier
     const int ndir = both ? 2 : 1;
     hipLaunchKernelGGL((k_spec<CT, NKW>), dim3(p.B * p.N * ndir), dim3(64), lds, st, p, both ? 1 : 0,
                        warm, tier);
-    hipLaunchKernelGGL(k_spec_cmp, dim3(p.N, p.B, ndir), dim3(64), 0, st, p, tier);
+    hipLaunchKernelGGL(k_spec_cmp, dim3(p.N, p.B, ndir), dim3(NT), 0, st, p, tier);
     hipLaunchKernelGGL(k_spec_fix, dim3(p.B, 2), dim3(64), 0, st, p, ndir, tier);
     return check_launch();
 }
@@ -3656,7 +3662,7 @@ int run_durtrans(Params p, int ckpt_interval, void *workspace, size_t workspace_
                 rc = launch_dt_bwd_any(p, g, st, p.B * p.N, warm[tier], tier, 0);
                 if (rc != SEMICRF_OK) return rc;
             }
-            hipLaunchKernelGGL(k_spec_cmp, dim3(p.N, p.B, ndir), dim3(64), 0, st, p, tier);
+            hipLaunchKernelGGL(k_spec_cmp, dim3(p.N, p.B, ndir), dim3(NT), 0, st, p, tier);
             hipLaunchKernelGGL(k_spec_fix, dim3(p.B, 2), dim3(64), 0, st, p, ndir, tier);
         }
     } else {
