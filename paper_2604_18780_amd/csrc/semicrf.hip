@@ -110,6 +110,7 @@ struct Params {
     int *vbest;         // [B] Viterbi: label of the last segment
     int *vbp;           // [B][T+1][C] Viterbi back-pointers: (duration << 8) | predecessor label
     int *vpar[2];       // [B][T+1][C] parent node (position * C + label) and its doublings (ping-pong)
+    int *vexit;         // [B][T+1][C] second buffer of the interval-exit pointers (the first is vpar[1])
     unsigned char *vmark;  // [B][T+1][C] 1: the node lies on the best path
     float *vscore;      // Viterbi outputs
     int32_t *vlabels, *vstarts, *vnseg;
@@ -2747,6 +2748,145 @@ __global__ __launch_bounds__(NT) void k_vit_count(Params p)
 }
 
 // ---------------------------------------------------------------------------
+// Trace-back by checkpoint interval (used when an interval's nodes fit in LDS): pointer doubling
+// over all nodes touches every node ceil(log2 T) times in HBM; here
+//   k_vit_local  one workgroup per (sequence, interval): the parents of the interval's nodes
+//                (positions lo < t <= hi) are loaded into LDS and jumped until every node points
+//                at its EXIT node, the first node of its path at a position <= lo;
+//   k_vit_hop    ceil(log2 N) + 1 launches over the window nodes only (the at most K positions
+//                below each interval's upper end, where exit nodes lie): marks the path's exit
+//                nodes by pointer doubling over the exit pointers, as k_vit_round does over all;
+//   k_vit_walk   one workgroup per (sequence, interval): from the interval's marked entry node
+//                one thread follows the parents in LDS and marks the path; all threads then
+//                write the marked nodes' segments and count them.
+// ---------------------------------------------------------------------------
+// local parent of the interval's node i (global id n): index inside the interval, or -(id) - 1 of
+// a parent at a position <= lo
+__device__ __forceinline__ int vit_local_parent(const int *par, const size_t n, const int lo, const int C)
+{
+    const int gp = par[n];
+    const int tp = gp / C;
+    return tp > lo ? (tp - lo - 1) * C + (gp - tp * C) : -gp - 1;
+}
+
+__global__ __launch_bounds__(NT) void k_vit_local(Params p)
+{
+    extern __shared__ int lds_int[];
+    const int j = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const int C = p.C, L = p.hdr[b].L;
+    const size_t nn = (size_t)(p.T + 1) * C;
+    const int *par = p.vpar[0] + (size_t)b * nn;
+    int *e0 = p.vpar[1] + (size_t)b * nn, *e1 = p.vexit + (size_t)b * nn;
+    if (j == 0 && tid < C) {  // the nodes at position 0 are where every path ends
+        e0[tid] = tid;
+        e1[tid] = tid;
+    }
+    const int lo = j * p.Delta;
+    if (lo >= L) return;
+    const int hi = min(lo + p.Delta, L);
+    const int nloc = (hi - lo) * C;
+    int *lp = lds_int;
+    for (int i = tid; i < nloc; i += NT) lp[i] = vit_local_parent(par, (size_t)(lo + 1) * C + i, lo, C);
+    __syncthreads();
+    for (;;) {  // jump until every pointer has left the interval (at most ceil(log2(hi - lo)) + 1 rounds)
+        int pending = 0;
+        for (int i = tid; i < nloc; i += NT) {
+            const int v = lp[i];
+            if (v >= 0) {
+                const int w = lp[v];  // an older or a newer pointer of v: both lie on i's path
+                lp[i] = w;
+                pending |= w >= 0;
+            }
+        }
+        if (!__syncthreads_or(pending)) break;
+    }
+    for (int i = tid; i < nloc; i += NT) {
+        const int e = -lp[i] - 1;
+        e0[(size_t)(lo + 1) * C + i] = e;
+        e1[(size_t)(lo + 1) * C + i] = e;
+    }
+}
+
+// One doubling round over the window nodes (interval j, distance d below its upper end, label c).
+__global__ __launch_bounds__(NT) void k_vit_hop(Params p, int src, int first)
+{
+    const int b = blockIdx.y, C = p.C, K = p.K;
+    const int L = p.hdr[b].L;
+    const size_t nn = (size_t)(p.T + 1) * C;
+    const unsigned idx = blockIdx.x * NT + threadIdx.x;
+    const unsigned kc = (unsigned)K * C;
+    const int j = (int)(idx / kc);
+    if (j >= p.N) return;
+    const int lo = j * p.Delta;
+    if (lo >= L) return;
+    const int hi = min(lo + p.Delta, L);
+    const int r = (int)(idx - (unsigned)j * kc);
+    const int t = hi - r / C;
+    if (t <= lo) return;  // that position belongs to an earlier interval's window
+    const size_t n = (size_t)t * C + r % C;
+    const int *ein = (src ? p.vexit : p.vpar[1]) + (size_t)b * nn;
+    int *eout = (src ? p.vpar[1] : p.vexit) + (size_t)b * nn;
+    unsigned char *mark = p.vmark + (size_t)b * nn;
+    const int e = ein[n];
+    const bool root = first && n == (size_t)L * C + p.vbest[b];
+    if (root) mark[n] = 1;
+    if (root || mark[n]) mark[e] = 1;  // a mark set earlier in this launch only arrives sooner
+    eout[n] = ein[e];
+}
+
+__global__ __launch_bounds__(NT) void k_vit_walk(Params p)
+{
+    extern __shared__ int lds_int[];
+    __shared__ int entry, cnt;
+    const int j = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const int C = p.C, T = p.T, L = p.hdr[b].L;
+    const size_t nn = (size_t)(T + 1) * C;
+    int32_t *lab = p.vlabels + (size_t)b * T, *st = p.vstarts + (size_t)b * T;
+    const int lo = j * p.Delta;
+    // tokens beyond the sequence
+    for (int u = max(lo, L) + tid; u < min(lo + p.Delta, T); u += NT) {
+        lab[u] = -1;
+        st[u] = 0;
+    }
+    if (lo >= L) return;
+    const int hi = min(lo + p.Delta, L);
+    const int nloc = (hi - lo) * C;
+    const int *par = p.vpar[0] + (size_t)b * nn;
+    const unsigned char *mark = p.vmark + (size_t)b * nn;
+    int *lp = lds_int;
+    unsigned char *lm = (unsigned char *)(lds_int + nloc);
+    if (tid == 0) {
+        entry = -1;
+        cnt = 0;
+    }
+    __syncthreads();
+    for (int i = tid; i < nloc; i += NT) {
+        lp[i] = vit_local_parent(par, (size_t)(lo + 1) * C + i, lo, C);
+        lm[i] = 0;
+        if (mark[(size_t)(lo + 1) * C + i]) entry = i;  // at most one: where the best path enters the interval
+    }
+    __syncthreads();
+    if (tid == 0) {
+        for (int cur = entry; cur >= 0; cur = lp[cur]) lm[cur] = 1;
+    }
+    __syncthreads();
+    int mine = 0;
+    for (int i = tid; i < nloc; i += NT) {
+        if (!lm[i]) continue;
+        const int t = lo + 1 + i / C, c = i % C;
+        const int k = p.vbp[(size_t)b * nn + (size_t)t * C + c] >> 8;
+        for (int u = t - k; u < t; ++u) {
+            lab[u] = c;
+            st[u] = u == t - k ? 1 : 0;
+        }
+        ++mine;
+    }
+    if (mine) atomicAdd(&cnt, mine);
+    __syncthreads();
+    if (tid == 0 && cnt) atomicAdd(&p.vnseg[b], cnt);
+}
+
+// ---------------------------------------------------------------------------
 // Finalisation (fixed-order reductions).
 // ---------------------------------------------------------------------------
 // carry[b,i,c] = sum_{i'<=i} tot[b,i',c];  mean[b,c] = (1/L) sum_u pm[b,u,c].  grid B, NT threads:
@@ -3372,7 +3512,7 @@ int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hi
 // Viterbi workspace beyond the prefix-stage plan: (V, r) pairs, best final labels, back-pointers,
 // two pointer arrays and the path marks.
 struct VitLayout {
-    size_t vr, vbest, vbp, vpar0, vpar1, vmark, total;
+    size_t vr, vbest, vbp, vpar0, vpar1, vexit, vmark, total;
 };
 
 VitLayout viterbi_layout(int B, int T, int C)
@@ -3385,6 +3525,7 @@ VitLayout viterbi_layout(int B, int T, int C)
     l.vbp = off; off += align_up(nodes * sizeof(int));
     l.vpar0 = off; off += align_up(nodes * sizeof(int));
     l.vpar1 = off; off += align_up(nodes * sizeof(int));
+    l.vexit = off; off += align_up(nodes * sizeof(int));
     l.vmark = off; off += align_up(nodes);
     l.total = off;
     return l;
@@ -3453,6 +3594,7 @@ int run_viterbi(Params p, void *workspace, size_t workspace_bytes, hipStream_t s
     p.vbp = (int *)(vw + vl.vbp);
     p.vpar[0] = (int *)(vw + vl.vpar0);
     p.vpar[1] = (int *)(vw + vl.vpar1);
+    p.vexit = (int *)(vw + vl.vexit);
     p.vmark = (unsigned char *)(vw + vl.vmark);
     p.logpair = 1;
     p.spec = p.spec ? 1 : 0;
@@ -3472,6 +3614,24 @@ int run_viterbi(Params p, void *workspace, size_t workspace_bytes, hipStream_t s
             hipSuccess)
             return SEMICRF_ELAUNCH;
         hipLaunchKernelGGL(k_vit_bp, dim3(p.T / VBP_TILE + 1, p.B), dim3(NT), lds, st, p);
+    }
+    const size_t lds_iv = (size_t)p.Delta * p.C * 5 + 16;  // parents (int) and path marks (byte) of one interval
+    if (lds_iv <= LDS_LIMIT) {
+        // trace-back by interval: local pointer jumping in LDS, doubling over the window nodes only
+        if (hipFuncSetAttribute((const void *)k_vit_local, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds_iv) != hipSuccess ||
+            hipFuncSetAttribute((const void *)k_vit_walk, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds_iv) != hipSuccess)
+            return SEMICRF_ELAUNCH;
+        hipLaunchKernelGGL(k_vit_local, dim3(p.N, p.B), dim3(NT), lds_iv, st, p);
+        int hops = 1;
+        while ((1 << hops) < p.N + 1) ++hops;
+        ++hops;
+        const unsigned wblk = (unsigned)(((size_t)p.N * p.K * p.C + NT - 1) / NT);
+        for (int i = 0; i < hops; ++i)
+            hipLaunchKernelGGL(k_vit_hop, dim3(wblk, p.B), dim3(NT), 0, st, p, i & 1, i == 0 ? 1 : 0);
+        hipLaunchKernelGGL(k_vit_walk, dim3(p.N, p.B), dim3(NT), lds_iv, st, p);
+        return check_launch();
     }
     const size_t nn = ((size_t)p.T + 1) * p.C;
     const unsigned nblk = (unsigned)((nn + NT - 1) / NT);
