@@ -3624,9 +3624,8 @@ int run_viterbi(Params p, void *workspace, size_t workspace_bytes, hipStream_t s
                                 (int)lds_iv) != hipSuccess)
             return SEMICRF_ELAUNCH;
         hipLaunchKernelGGL(k_vit_local, dim3(p.N, p.B), dim3(NT), lds_iv, st, p);
-        int hops = 1;
+        int hops = 1;  // after round i the marks reach the exit nodes fewer than 2^(i+1) intervals down
         while ((1 << hops) < p.N + 1) ++hops;
-        ++hops;
         const unsigned wblk = (unsigned)(((size_t)p.N * p.K * p.C + NT - 1) / NT);
         for (int i = 0; i < hops; ++i)
             hipLaunchKernelGGL(k_vit_hop, dim3(wblk, p.B), dim3(NT), 0, st, p, i & 1, i == 0 ? 1 : 0);
