@@ -189,7 +189,7 @@ int semicrf_fwd_bwd_boundary(const float *emis, const int32_t *lengths, const fl
  * backwards each segment takes the smallest duration, then the smallest predecessor label,
  * among the maximisers; since sums are rounded, "equally good" means equal in fp64.
  * Supported sizes: C <= 64 and K <= 64 * (64 / (C rounded up to 8/16/32/64)).  Workspace:
- * semicrf_viterbi_workspace_bytes (O(T*C): prefix arrays plus two doubles and three
+ * semicrf_viterbi_workspace_bytes (O(T*C): prefix arrays plus two doubles and four
  * integers per position and label).
  * The forward recurrence runs chunk-parallel like the sums: every checkpoint interval is
  * scanned on its own after a warm-up from the state of a sequence that begins there.  Best
@@ -201,8 +201,9 @@ int semicrf_fwd_bwd_boundary(const float *emis, const int32_t *lengths, const fl
  * once more after a longer warm-up; a sequence with a boundary that still does not agree
  * is rescanned sequentially inside the same call, and SEMICRF_SEQUENTIAL_SCAN forces that.
  * semicrf_scan_report with ckpt_interval = 0 and want_grad = 0 on this workspace reports
- * the outcome in column 0.  The trace-back (back-pointers of every node, pointer doubling,
- * one store per token) is parallel either way.
+ * the outcome in column 0.  The trace-back (back-pointers of every node, pointer jumping
+ * inside each interval, pointer doubling across intervals, one store per token) is parallel
+ * either way.
  */
 int semicrf_viterbi_workspace_bytes(int B, int T, int K, int C, size_t *bytes);
 

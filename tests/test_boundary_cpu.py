@@ -155,10 +155,10 @@ def test_viterbi_and_entropy_entries_check_their_arguments_on_the_host():
     assert lib.semicrf_viterbi_workspace_bytes(1, 8, 2, 65, ctypes.byref(out)) == -3
     assert lib.semicrf_viterbi_workspace_bytes(1, 1000, 65, 64, ctypes.byref(out)) == -3
     assert lib.semicrf_viterbi_workspace_bytes(1, 1000, 512, 8, ctypes.byref(out)) == 0
-    # O(T*C): the prefix arrays (20 B) plus a double pair, three ints and a byte per node
+    # O(T*C): the prefix arrays (20 B) plus a double pair, four ints and a byte per node
     n = sb.semicrf_viterbi_workspace_bytes(4, 100000, 64, 24)
     nodes = 4 * 100001 * 24
-    assert n % 256 == 0 and nodes * (20 + 16 + 12 + 1) < n < nodes * 64
+    assert n % 256 == 0 and nodes * (20 + 16 + 16 + 1) < n < nodes * 64
     rc = lib.semicrf_viterbi(None, None, None, None, None, None, None, None, 1, 8, 2, 3, 0, None, 0,
                              None, None, None, None, None)
     assert rc == -1
