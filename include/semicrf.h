@@ -58,7 +58,7 @@ typedef enum {
 #define SEMICRF_CENTER 1u
 /* flags bit 1: run the forward scan of Algorithm 1 and the backward scan of Algorithm 3
  * strictly sequentially.  By default both are run chunk-parallel: every checkpoint interval
- * is scanned as an independent task that first warms its ring up over the max(2K,32)
+ * is scanned as an independent task that first warms its ring up over the max(1.5K,32)
  * positions before the interval (max(8K,64) in a second attempt for what the first did not
  * verify), starting from the state of a sequence that begins there.
  * The state each task reaches at its end is then compared, entry by entry and up to the

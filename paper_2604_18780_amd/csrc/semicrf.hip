@@ -3103,6 +3103,11 @@ __global__ __launch_bounds__(NT) void k_entropies(const float *pos_marg, const f
 
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// First warm-up length of the chunk-parallel sum scans: one and a half maximal segment lengths.
+// The products of positive maps forget their start fast enough that the boundary mismatch is at the
+// rounding floor there on all workloads (it reaches 1e-11 at 1.25 K; the acceptance bound is 1e-10).
+inline int sum_warmup(int K) { return 3 * K / 2 < 32 ? 32 : (3 * K + 1) / 2; }
+
 // Single-wave tasks a compute unit holds at once for these sizes (scan kernel, interval
 // kernel): bounded by the LDS windows and by registers (two scan waves per SIMD, one where
 // the kernel needs more than 256 registers; one interval wave per SIMD).  False when the
@@ -3147,7 +3152,7 @@ int auto_interval(int B, int T, int K, int C)
     }
     const double slots_scan = 256.0 * per_scan;
     const double slots_int = 256.0 * per_int;
-    const double warm = 2 * K < 32 ? 32.0 : 2.0 * K;
+    const double warm = (double)sum_warmup(K);
     const int dlo = K / 2 < 8 ? 8 : K / 2;
     int dhi = (int)ceil(sqrt((double)T * (double)K));
     if (dhi < dlo) dhi = dlo;
@@ -3466,9 +3471,9 @@ int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hi
     p.nslot = pl.nslot;
     p.want_grad = mode == 2;
     bind_workspace(p, pl, workspace);
-    // warm-up lengths of the chunk-parallel scan: two maximal segment lengths first, eight
-    // for the (sequence, direction) pairs that fails for, the sequential scan for the rest
-    int warm[2] = {2 * p.K < 32 ? 32 : 2 * p.K, 8 * p.K < 64 ? 64 : 8 * p.K};
+    // warm-up lengths of the chunk-parallel scan: one and a half maximal segment lengths first,
+    // eight for the (sequence, direction) pairs that fails for, the sequential scan for the rest
+    int warm[2] = {sum_warmup(p.K), 8 * p.K < 64 ? 64 : 8 * p.K};
     if (const char *e = getenv("SEMICRF_WARMUP")) {  // tuning knob: first warm-up length
         const int w = atoi(e);
         if (w > 0) warm[0] = w, warm[1] = 4 * w;
@@ -3694,7 +3699,7 @@ int dt_auto_interval(int B, int T, int K, const DtGeom &g)
     int per_cu = 2048 / g.ntb < 20 / waves ? 2048 / g.ntb : 20 / waves;
     if (per_cu < 1) per_cu = 1;
     const double slots = 256.0 * per_cu;
-    const double warm = 2 * K < 32 ? 32.0 : 2.0 * K;
+    const double warm = (double)sum_warmup(K);
     const int dlo = K / 2 < 8 ? 8 : K / 2;
     int best = 0;
     double best_cost = 0.0;
@@ -3813,7 +3818,7 @@ int run_durtrans(Params p, int ckpt_interval, void *workspace, size_t workspace_
     hipLaunchKernelGGL(k_dt_tables, dim3((unsigned)((kcc + NT - 1) / NT)), dim3(NT), 0, st, p);
     const int ndir = grad ? 2 : 1;
     if (p.spec) {
-        const int warm[2] = {2 * p.K < 32 ? 32 : 2 * p.K, 8 * p.K < 64 ? 64 : 8 * p.K};
+        const int warm[2] = {sum_warmup(p.K), 8 * p.K < 64 ? 64 : 8 * p.K};
         for (int tier = 0; tier < 2; ++tier) {
             rc = launch_dt_fwd_any(p, g, st, p.B * p.N, warm[tier], tier, 0);
             if (rc != SEMICRF_OK) return rc;
