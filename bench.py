@@ -209,7 +209,7 @@ def main():
     # HBM bytes per launch of the two big kernels at the genomic workload with the automatic
     # interval, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by a 1 GiB copy
     # (profiles/hot_path_genomic_hbm_traffic_pmc.txt); unknown for other workloads.
-    measured_traffic = {("genomic", "intervals"): 384.4e6, ("genomic", "scans"): 624.5e6 + 52.9e6}
+    measured_traffic = {("genomic", "intervals"): 384.4e6, ("genomic", "scans"): 599.0e6 + 52.8e6}
     dom = "scans" if stage[1] >= stage[2] else "intervals"
     dom_s = (stage[1] if dom == "scans" else stage[2]) * 1e-3
     achieved = stage_flop[dom] / dom_s / 1e12

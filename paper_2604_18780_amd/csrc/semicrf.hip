@@ -3621,7 +3621,8 @@ int run_viterbi(Params p, void *workspace, size_t workspace_bytes, hipStream_t s
         hipLaunchKernelGGL(k_vit_bp, dim3(p.T / VBP_TILE + 1, p.B), dim3(NT), lds, st, p);
     }
     const size_t lds_iv = (size_t)p.Delta * p.C * 5 + 16;  // parents (int) and path marks (byte) of one interval
-    if (lds_iv <= LDS_LIMIT) {
+    const char *force = getenv("SEMICRF_VITERBI_TRACE");    // test knob: "global" = doubling over all nodes
+    if (lds_iv <= LDS_LIMIT && !(force && force[0] == 'g')) {
         // trace-back by interval: local pointer jumping in LDS, doubling over the window nodes only
         if (hipFuncSetAttribute((const void *)k_vit_local, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)lds_iv) != hipSuccess ||
