@@ -118,6 +118,9 @@ struct Params {
     int fuse;           // its forward tasks also store the interval stage's forward rows (one slot per task)
     double *aloc;       // [nslot][Delta][2C]
     double *alocY;      // [nslot][Delta]
+    double *bloc;       // [nslot][Delta][2C] backward rows (p_t, v_t) of the chunk-parallel backward tasks
+    double *blocY;      // [nslot][Delta]     their scale relative to the interval's upper end
+    int marg;           // marginals from the stored rows of both scans (no recurrence in the interval stage)
     double *partD;      // [B][N][K][C]
     double *partTr;     // [B][N][C][C]
     double *tot;        // [B][N][C]
@@ -1146,6 +1149,7 @@ __global__ __launch_bounds__(NT) void k_interval(Params p)
         const int L = h.L, J = h.J;
         const int t0 = iv * Delta;
         if (t0 >= L) continue;  // uniform
+        if (p.marg && p.spec_ok[b * 2] && p.spec_ok[b * 2 + 1]) continue;  // uniform: done from the stored rows
         const int t1 = min(t0 + Delta, L);
         const size_t row0 = (size_t)b * (p.T + 1);
         const double2 *EI = p.EI + row0 * C;
@@ -1505,6 +1509,7 @@ __global__ __launch_bounds__(64 * interval_waves(CT, NKW)) void k_interval_wave(
         const int L = h.L, J = h.J, Jm = J - 1;
         const int t0 = iv * Delta;
         if (t0 >= L) continue;
+        if (p.marg && p.spec_ok[b * 2] && p.spec_ok[b * 2 + 1]) continue;  // done from the stored rows of both scans
         const int t1 = min(t0 + Delta, L);
         const size_t row0 = (size_t)b * (p.T + 1);
         const double2 *EIc = p.EI + row0 * C + cc;
@@ -1980,13 +1985,16 @@ __device__ __forceinline__ void spec_task(const Params &p, double *lds_raw, cons
     // Forward tasks also leave the rows the interval stage needs, (a_t, q_t) and the scale relative
     // to the chunk's first position, for t = lo .. hi-1, in the task's own slot (the interval
     // stage then skips its forward recompute for accepted sequences).
-    const bool keep = !BWD && p.fuse;
+    // Backward tasks do the same with (p_t, v_t) and the scale relative to the chunk's upper end,
+    // for t = hi-1 .. lo, when the marginals are formed from the stored rows of both scans.
+    const bool keep = BWD ? p.marg != 0 : p.fuse != 0;
     const bool writer = cval && g == 0;
-    double2 *aloc = (double2 *)p.aloc + ((size_t)b * N + j) * Delta * C;
-    double *alocY = p.alocY + ((size_t)b * N + j) * Delta;
-    double Yrec = 0.0;  // scale at the chunk's first position
+    double2 *aloc = (double2 *)(BWD ? p.bloc : p.aloc) + ((size_t)b * N + j) * Delta * C;
+    double *alocY = (BWD ? p.blocY : p.alocY) + ((size_t)b * N + j) * Delta;
+    double Yrec = 0.0;  // scale at the chunk's first position (forward) / upper end (backward)
     auto start_rows = [&]() {
         Yrec = Y;
+        if (BWD) return;
         if (keep && writer) aloc[c] = make_double2(yv[c], ring[r * RS + c]);
         if (keep && lane == 0) alocY[0] = 0.0;
     };
@@ -2031,7 +2039,7 @@ __device__ __forceinline__ void spec_task(const Params &p, double *lds_raw, cons
         double2 en[MB];
         load_rows(en, tn);
         const int t1 = BWD ? t - 1 : t + 1;
-        const bool inchunk = keep && t >= tstart;  // blocks end at tstart, so this holds for the whole block
+        const bool inchunk = keep && (BWD ? t <= tstart : t >= tstart);  // blocks end at tstart: holds for the whole block
         const bool boundary = BWD ? (t & Jm) == 0 : (t1 & Jm) == 0;
         if (__builtin_expect(boundary, 0)) {
             double prevsum = 0.0;
@@ -2083,6 +2091,10 @@ __device__ __forceinline__ void spec_task(const Params &p, double *lds_raw, cons
                 if (!BWD && inchunk && t + 1 + i < hi) {
                     if (writer) aloc[(size_t)(t + 1 + i - lo) * C + c] = make_double2(y, q);
                     if (lane == 0) alocY[t + 1 + i - lo] = Y - Yrec;
+                }
+                if (BWD && inchunk) {  // position t - 1 - i of [lo, hi)
+                    if (writer) aloc[(size_t)(t - 1 - i - lo) * C + c] = make_double2(y, q);
+                    if (lane == 0) alocY[t - 1 - i - lo] = Y - Yrec;
                 }
                 lds_wave_fence();
             } else {
@@ -3100,6 +3112,7 @@ __global__ __launch_bounds__(NT) void k_entropies(const float *pos_marg, const f
 // Host side: sizing, workspace carving, launches.
 // ---------------------------------------------------------------------------
 #include "durtrans.inl"
+#include "marg.inl"
 
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -3231,6 +3244,8 @@ int make_plan(int B, int T, int K, int C, int ckpt_interval, int want_grad, Plan
     sz[i++] = g * b * (n + 1) * 8;                // 25 ckYB2
     sz[i++] = b * c * 8;                          // 26 out0
     sz[i++] = b * c * 8;                          // 27 inL
+    sz[i++] = g * (size_t)pl->nslot * pl->Delta * 2 * c * 8;  // 28 bloc
+    sz[i++] = g * (size_t)pl->nslot * pl->Delta * 8;          // 29 blocY
     size_t off = 0;
     for (int j = 0; j < i; ++j) {
         pl->off[j] = off;
@@ -3270,6 +3285,8 @@ void bind_workspace(Params &p, const Plan &pl, void *ws)
     p.ckYB2 = (double *)(w + pl.off[25]);
     p.out0 = (double *)(w + pl.off[26]);
     p.inL = (double *)(w + pl.off[27]);
+    p.bloc = (double *)(w + pl.off[28]);
+    p.blocY = (double *)(w + pl.off[29]);
     p.spec_lr = (double *)(w + pl.off[8]);
     p.spec_err = p.spec_lr + (size_t)p.B * 2 * (pl.N + 1);
     p.spec_ok = (int *)(p.spec_err + (size_t)p.B * 2 * (pl.N + 1));
@@ -3480,6 +3497,16 @@ int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hi
     }
     p.spec = p.spec && mode != 0 && spec_applies(p.K, p.C);
     p.fuse = p.spec && mode == 2 && (size_t)p.B * pl.N <= (size_t)pl.nslot;  // one slot per task
+    // Marginals from the stored rows of both scans: when every task has its slot, no boundary-term
+    // output is asked for (those come from the interval kernels) and the sizes fit its kernels.
+    const int mg_nsl = (p.K + MG_KS - 1) / MG_KS;
+    const size_t mg_lds_d = (size_t)(2 * MG_TG + MG_KS * mg_nsl + 3) * p.C * sizeof(double);
+    const size_t mg_lds_t = (size_t)3 * MG_TG * p.C * sizeof(double);
+    p.marg = p.fuse && !p.g_proj_start && !p.g_proj_end && !p.g_pi_start && !p.g_pi_end && !p.bdy_post &&
+             p.C * mg_nsl <= 1024 && mg_lds_d <= LDS_LIMIT;
+    if (const char *e = getenv("SEMICRF_MARGINALS")) {  // tuning knob: "interval" = always the interval kernels
+        if (e[0] == 'i') p.marg = 0;
+    }
     T.mark();
     rc = launch_prep(p, st);
     T.mark();
@@ -3499,6 +3526,17 @@ int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hi
     T.mark();
     rc = check_launch();
     if (rc != SEMICRF_OK || mode == 1) return rc;
+    if (p.marg) {
+        if (hipFuncSetAttribute((const void *)k_mg_dur, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)mg_lds_d) != hipSuccess)
+            return SEMICRF_ELAUNCH;
+        const int ntd = (p.C * mg_nsl + 63) / 64 * 64;
+        const int cc = p.C * p.C;
+        const int ntt = cc >= 1024 ? 1024 : (cc + 63) / 64 * 64;
+        hipLaunchKernelGGL(k_mg_dur, dim3(p.B * p.N), dim3(ntd), mg_lds_d, st, p);
+        hipLaunchKernelGGL(k_mg_te, dim3(p.B * p.N), dim3(ntt), mg_lds_t, st, p);
+    }
+    // the interval kernels: everything without the stored rows, else only what those kernels left
     rc = launch_interval(p, pl, st);
     if (rc != SEMICRF_OK) return rc;
     T.mark();
