@@ -16,7 +16,7 @@
 // partTr, the running emission sums, tot, sumR), which skip the sequences handled here.
 // ---------------------------------------------------------------------------
 constexpr int MG_TG = 32;  // positions staged at a time
-constexpr int MG_KS = 16;  // durations per thread of the duration kernel
+constexpr int MG_KS = 8;   // durations per thread of the duration kernel
 
 // absolute log2 scale of the forward / backward row i of interval j
 __device__ __forceinline__ double mg_ya(const Params &p, const int b, const int j, const int i)
@@ -31,10 +31,11 @@ __device__ __forceinline__ double mg_yb(const Params &p, const int b, const int 
     return top + p.blocY[((size_t)b * p.N + j) * p.Delta + i];
 }
 
-// Duration-bias statistics.  Thread (ks, c): label c, durations ks*16 + 1 .. ks*16 + 16, one
+// Duration-bias statistics.  Thread (ks, c): label c, durations ks*MG_KS + 1 .. ks*MG_KS + MG_KS, one
 // accumulator each.  Positions are taken in groups inside one scaling block: the group's q rows
 // and the v rows it can reach are staged in LDS, the latter converted to the group's frame with
-// all exponents combined before anything is formed; four positions share every LDS read.
+// all exponents combined before anything is formed; four positions share every LDS read.  The
+// absolute scales of all rows the interval can touch are fetched into LDS once, at the start.
 __global__ __launch_bounds__(1024) void k_mg_dur(Params p)
 {
     extern __shared__ double lds_raw[];
@@ -53,6 +54,12 @@ __global__ __launch_bounds__(1024) void k_mg_dur(Params p)
     const int VR = MG_TG + MG_KS * nsl + 3;
     double *Qrow = lds_raw;            // [MG_TG][C]
     double *Vp = Qrow + MG_TG * C;     // [VR][C]
+    double *qf = Vp + VR * C;          // [MG_TG] per-row factors of the group
+    double *vf = qf + MG_TG;           // [VR]
+    int *ve = (int *)(vf + VR);        // [VR]
+    int *vj = ve + VR;                 // [VR]
+    double *yAs = vf + 2 * VR;         // [Delta]      absolute scale of the forward row lo + i
+    double *yBs = yAs + Delta;         // [Delta + K]  absolute scale of the backward row lo + 1 + i
     const size_t row0 = (size_t)b * (p.T + 1);
     const double2 *EI = p.EI + row0 * C;
     const int *nb = p.nbase + row0 * C;
@@ -62,37 +69,80 @@ __global__ __launch_bounds__(1024) void k_mg_dur(Params p)
     double acc[MG_KS];
 #pragma unroll
     for (int kk = 0; kk < MG_KS; ++kk) acc[kk] = 0.0;
+    for (int i = tid; i < hi - lo; i += blockDim.x) yAs[i] = mg_ya(p, b, iv, i);
+    for (int i = tid; i < hi - lo + K; i += blockDim.x) {
+        const int s = lo + 1 + i;
+        yBs[i] = s < L ? mg_yb(p, b, s / Delta, s % Delta, L) : 0.0;  // b_L = 1: scale 0
+    }
 
     for (int tg0 = lo; tg0 < hi;) {
         const int tg1 = min(min(hi, (tg0 / J + 1) * J), tg0 + MG_TG);
         const int ng = tg1 - tg0, jt = tg0 / J;
-        const double yA0 = mg_ya(p, b, iv, tg0 - lo);
-        __syncthreads();  // the previous group is done with the staged rows
-        for (int i = tid; i < MG_TG * C; i += blockDim.x) {
-            const int r = i / C, o = i % C;
-            double q = 0.0;
-            if (r < ng) q = frow[(size_t)(tg0 + r) * C + o].y * exp2(mg_ya(p, b, iv, tg0 + r - lo) - yA0);
-            Qrow[i] = q;
-        }
-        for (int i = tid; i < VR * C; i += blockDim.x) {
-            const int r = i / C, o = i % C, s = tg0 + 1 + r;
-            double v = 0.0;
-            if (s <= L && r < ng + K) {
-                double vs, yB;
-                if (s == L) {  // b_L = 1: v_L = ES_L, scale 0
-                    vs = EI[(size_t)L * C + o].x;
-                    yB = 0.0;
-                } else {
-                    vs = brow[(size_t)s * C + o].y;
-                    yB = mg_yb(p, b, s / Delta, s % Delta, L);
+        __syncthreads();  // the previous group is done with the staged rows (first: the scales are there)
+        const double yA0 = yAs[tg0 - lo];
+        // per row first (uniform over the labels): the scale factor of a q row; for a v row the
+        // fractional factor, the integer exponent and the scaling block it was stored in
+        for (int r = tid; r < MG_TG + VR; r += blockDim.x) {
+            if (r < MG_TG) {
+                qf[r] = r < ng ? exp2(yAs[tg0 + r - lo] - yA0) : 0.0;
+            } else {
+                const int rr = r - MG_TG, s = tg0 + 1 + rr;
+                double f = 0.0;
+                int e = 0, js = jt;
+                if (s <= L && rr < ng + K) {
+                    const double lf = (yA0 + yBs[s - lo - 1]) - logZ * LOG2E;
+                    const double fl = floor(lf);
+                    f = exp2(lf - fl);
+                    e = (int)fmin(fmax(fl, -100000.0), 100000.0);
+                    js = s / J;
                 }
-                const double lf = (yA0 + yB) - logZ * LOG2E;
-                const double fl = floor(lf);
-                const int sh = nb[(size_t)(s / J) * C + o] - nb[(size_t)jt * C + o];
-                const double ef = fmin(fmax(fl, -100000.0), 100000.0);
-                v = fmin(ldexp(vs * exp2(lf - fl), sh + (int)ef), DBL_MAX);
+                vf[rr] = f;
+                ve[rr] = e;
+                vj[rr] = js;
             }
-            Vp[i] = v;
+        }
+        __syncthreads();
+        // v_L = ES_L; all exponents are combined before anything is formed, so that an empty row stays
+        // zero and nothing passes through infinity.  The loads of several elements per thread are
+        // issued together (indices of empty rows are clamped, their factor is zero).
+        {
+            constexpr int UQ = 4, UV = 6;
+            for (int i0 = tid; i0 < MG_TG * C; i0 += UQ * (int)blockDim.x) {
+                double qv[UQ];
+#pragma unroll
+                for (int u = 0; u < UQ; ++u) {
+                    const int i = min(i0 + u * (int)blockDim.x, MG_TG * C - 1);
+                    const int r = min(i / C, ng - 1);
+                    qv[u] = frow[(size_t)(tg0 + r) * C + i % C].y;
+                }
+#pragma unroll
+                for (int u = 0; u < UQ; ++u) {
+                    const int i = i0 + u * (int)blockDim.x;
+                    if (i < MG_TG * C) Qrow[i] = qv[u] * qf[i / C];  // qf is zero beyond the group
+                }
+            }
+            for (int i0 = tid; i0 < VR * C; i0 += UV * (int)blockDim.x) {
+                double vs[UV];
+                int n1[UV], n0[UV], rr[UV];
+#pragma unroll
+                for (int u = 0; u < UV; ++u) {
+                    const int i = min(i0 + u * (int)blockDim.x, VR * C - 1);
+                    const int r = i / C, o = i % C;
+                    const int s = min(tg0 + 1 + r, L);
+                    rr[u] = r;
+                    vs[u] = s == L ? EI[(size_t)L * C + o].x : brow[(size_t)s * C + o].y;
+                    n1[u] = nb[(size_t)vj[r] * C + o];
+                    n0[u] = nb[(size_t)jt * C + o];
+                }
+#pragma unroll
+                for (int u = 0; u < UV; ++u) {
+                    const int i = i0 + u * (int)blockDim.x;
+                    if (i < VR * C) {
+                        const double f = vf[rr[u]];
+                        Vp[i] = f != 0.0 ? fmin(ldexp(vs[u] * f, n1[u] - n0[u] + ve[rr[u]]), DBL_MAX) : 0.0;
+                    }
+                }
+            }
         }
         __syncthreads();
         if (active) {
@@ -122,11 +172,13 @@ __global__ __launch_bounds__(1024) void k_mg_dur(Params p)
     }
 }
 
-// Transition statistics and the running emission sums.  Groups of positions from the interval's
-// upper end downwards (the emission sums are suffix sums); per group all threads stage
-// a_t kappa, p_t and (out - in) kappa, then every thread adds the group's products for its label
-// pairs while threads 0..C-1 walk the group for the running sums.
-__global__ __launch_bounds__(1024) void k_mg_te(Params p)
+// Transition statistics and the running emission sums.  Groups of MG_TE positions from the
+// interval's upper end downwards (the emission sums are suffix sums); per group all threads stage
+// a_t kappa, p_t and (out - in) kappa (rows beyond the group are zero), then every thread adds the
+// group's products for its label pairs while threads 0..C-1 walk the group for the running sums.
+constexpr int MG_TE = 64;
+
+__global__ __launch_bounds__(NT) void k_mg_te(Params p)
 {
     extern __shared__ double lds_raw[];
     const int tid = threadIdx.x;
@@ -138,39 +190,57 @@ __global__ __launch_bounds__(1024) void k_mg_te(Params p)
     if (lo >= L) return;
     if (!(p.spec_ok[b * 2] && p.spec_ok[b * 2 + 1])) return;
     const int hi = min(lo + Delta, L);
-    double *AK = lds_raw;            // [MG_TG][C] a_t(c') kappa(t,t)
-    double *P = AK + MG_TG * C;      // [MG_TG][C] p_t(c)
-    double *D = P + MG_TG * C;       // [MG_TG][C] (out_t - in_t)(c)
+    double *AK = lds_raw;            // [MG_TE][C] a_t(c') kappa(t,t)
+    double *P = AK + MG_TE * C;      // [MG_TE][C] p_t(c)
+    double *D = P + MG_TE * C;       // [MG_TE][C] (out_t - in_t)(c)
+    double *kp = D + MG_TE * C;      // [Delta]    kappa(t,t) of every position of the interval
     const size_t row0 = (size_t)b * (p.T + 1);
     const double2 *EI = p.EI + row0 * C;
     const double2 *frow = (const double2 *)p.aloc + ((size_t)b * N) * Delta * C;
     const double2 *brow = (const double2 *)p.bloc + ((size_t)b * N) * Delta * C;
     const double logZ = h.logZ;
-    double acc[4] = {0.0, 0.0, 0.0, 0.0};  // label pairs tid, tid + blockDim, ... (C <= 64, >= 1024 threads then)
+    constexpr int NPAIR = GRAD_CMAX * GRAD_CMAX / NT;  // label pairs tid, tid + NT, ...
+    double acc[NPAIR];
+#pragma unroll
+    for (int n = 0; n < NPAIR; ++n) acc[n] = 0.0;
     double R = 0.0, sR = 0.0;
+    for (int i = tid; i < hi - lo; i += NT)
+        kp[i] = exp((mg_ya(p, b, iv, i) + mg_yb(p, b, iv, i, L)) * LN2 - logZ);
 
     for (int tg1 = hi; tg1 > lo;) {
-        const int tg0 = max(lo, tg1 - MG_TG);
+        const int tg0 = max(lo, tg1 - MG_TE);
         const int ng = tg1 - tg0;
         __syncthreads();
-        for (int i = tid; i < ng * C; i += blockDim.x) {
+        for (int i = tid; i < MG_TE * C; i += NT) {
             const int r = i / C, o = i % C, t = tg0 + r;
-            const double2 fa = frow[(size_t)t * C + o], fb = brow[(size_t)t * C + o], e = EI[(size_t)t * C + o];
-            const double kap = exp((mg_ya(p, b, iv, t - lo) + mg_yb(p, b, iv, t - lo, L)) * LN2 - logZ);
-            AK[i] = fa.x * kap;
-            P[i] = fb.x;
-            // a segment of label o starts at t (z_t p_t, z = q ES) / ends at t (a_t b_t, b = v IE; none ends at 0)
-            D[i] = (fa.y * e.x * fb.x - (t >= 1 ? fa.x * fb.y * e.y : 0.0)) * kap;
+            double ak = 0.0, pp = 0.0, d = 0.0;
+            if (r < ng) {
+                const double2 fa = frow[(size_t)t * C + o], fb = brow[(size_t)t * C + o], e = EI[(size_t)t * C + o];
+                const double kap = kp[t - lo];
+                ak = fa.x * kap;
+                pp = fb.x;
+                // a segment of label o starts at t (z_t p_t, z = q ES) / ends at t (a_t b_t, b = v IE; none ends at 0)
+                d = (fa.y * e.x * fb.x - (t >= 1 ? fa.x * fb.y * e.y : 0.0)) * kap;
+            }
+            AK[i] = ak;
+            P[i] = pp;
+            D[i] = d;
         }
         __syncthreads();
 #pragma unroll
-        for (int n = 0; n < 4; ++n) {
-            const int pair = tid + n * (int)blockDim.x;
+        for (int n = 0; n < NPAIR; ++n) {
+            const int pair = tid + n * NT;
             if (pair < CC) {
                 const int cp = pair / C, c = pair % C;
-                double a = acc[n];
-                for (int r = 0; r < ng; ++r) a = fma(AK[r * C + cp], P[r * C + c], a);
-                acc[n] = a;
+                double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+#pragma unroll 4
+                for (int r = 0; r < MG_TE; r += 4) {
+                    a0 = fma(AK[r * C + cp], P[r * C + c], a0);
+                    a1 = fma(AK[(r + 1) * C + cp], P[(r + 1) * C + c], a1);
+                    a2 = fma(AK[(r + 2) * C + cp], P[(r + 2) * C + c], a2);
+                    a3 = fma(AK[(r + 3) * C + cp], P[(r + 3) * C + c], a3);
+                }
+                acc[n] += (a0 + a1) + (a2 + a3);
             }
         }
         if (tid < C) {
@@ -184,8 +254,8 @@ __global__ __launch_bounds__(1024) void k_mg_te(Params p)
     }
     double *pT = p.partTr + ((size_t)b * N + iv) * CC;
 #pragma unroll
-    for (int n = 0; n < 4; ++n) {
-        const int pair = tid + n * (int)blockDim.x;
+    for (int n = 0; n < NPAIR; ++n) {
+        const int pair = tid + n * NT;
         if (pair < CC) pT[pair] = acc[n];
     }
     if (tid < C) {

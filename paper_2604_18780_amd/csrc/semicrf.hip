@@ -3500,12 +3500,17 @@ int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hi
     // Marginals from the stored rows of both scans: when every task has its slot, no boundary-term
     // output is asked for (those come from the interval kernels) and the sizes fit its kernels.
     const int mg_nsl = (p.K + MG_KS - 1) / MG_KS;
-    const size_t mg_lds_d = (size_t)(2 * MG_TG + MG_KS * mg_nsl + 3) * p.C * sizeof(double);
-    const size_t mg_lds_t = (size_t)3 * MG_TG * p.C * sizeof(double);
-    p.marg = p.fuse && !p.g_proj_start && !p.g_proj_end && !p.g_pi_start && !p.g_pi_end && !p.bdy_post &&
-             p.C * mg_nsl <= 1024 && mg_lds_d <= LDS_LIMIT;
-    if (const char *e = getenv("SEMICRF_MARGINALS")) {  // tuning knob: "interval" = always the interval kernels
+    const size_t mg_vr = (size_t)MG_TG + MG_KS * mg_nsl + 3;
+    const size_t mg_lds_d = ((MG_TG + mg_vr) * p.C + MG_TG + 2 * mg_vr + 2 * (size_t)pl.Delta + p.K) * sizeof(double);
+    const size_t mg_lds_t = ((size_t)3 * MG_TE * p.C + pl.Delta) * sizeof(double);
+    // Measured: it wins where the K-deep window makes the interval kernel's recurrence long (K = 512:
+    // 0.62 ms against 1.08 ms) and is level with it at K = 64, so it is taken for K >= 128.
+    const bool mg_fits = p.fuse && !p.g_proj_start && !p.g_proj_end && !p.g_pi_start && !p.g_pi_end &&
+                         !p.bdy_post && p.C * mg_nsl <= 1024 && mg_lds_d <= LDS_LIMIT && mg_lds_t <= LDS_LIMIT;
+    p.marg = mg_fits && p.K >= 128;
+    if (const char *e = getenv("SEMICRF_MARGINALS")) {  // tuning knob: "interval" / "rows" force one route
         if (e[0] == 'i') p.marg = 0;
+        if (e[0] == 'r') p.marg = mg_fits;
     }
     T.mark();
     rc = launch_prep(p, st);
@@ -3530,11 +3535,13 @@ int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hi
         if (hipFuncSetAttribute((const void *)k_mg_dur, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)mg_lds_d) != hipSuccess)
             return SEMICRF_ELAUNCH;
-        const int ntd = (p.C * mg_nsl + 63) / 64 * 64;
-        const int cc = p.C * p.C;
-        const int ntt = cc >= 1024 ? 1024 : (cc + 63) / 64 * 64;
+        int ntd = (p.C * mg_nsl + 63) / 64 * 64;
+        if (ntd < NT) ntd = NT;  // the extra threads help staging the rows
+        if (hipFuncSetAttribute((const void *)k_mg_te, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)mg_lds_t) != hipSuccess)
+            return SEMICRF_ELAUNCH;
         hipLaunchKernelGGL(k_mg_dur, dim3(p.B * p.N), dim3(ntd), mg_lds_d, st, p);
-        hipLaunchKernelGGL(k_mg_te, dim3(p.B * p.N), dim3(ntt), mg_lds_t, st, p);
+        hipLaunchKernelGGL(k_mg_te, dim3(p.B * p.N), dim3(NT), mg_lds_t, st, p);
     }
     // the interval kernels: everything without the stored rows, else only what those kernels left
     rc = launch_interval(p, pl, st);

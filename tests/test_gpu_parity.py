@@ -348,3 +348,52 @@ def test_half_precision_emissions(dtype):
                                   sb.SEMICRF_EMIS_F16 | sb.SEMICRF_EMIS_BF16, 4096, 1 << 30, lz.data_ptr(), None)
         sb._check(rc)
     assert ei.value.status == -1
+
+
+# --------------------------------------------------------------------------
+# Marginals from the stored rows of both scans (the route taken for K >= 128), forced on
+# small shapes so that every case above also covers it
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("seed,B,T,K,C", [
+    (1, 3, 40, 5, 3), (2, 4, 300, 8, 6), (3, 2, 700, 33, 24), (4, 5, 130, 1, 7),
+    (6, 2, 50, 80, 4), (7, 3, 257, 16, 64), (8, 6, 33, 7, 1), (11, 2, 900, 130, 8),
+])
+def test_marginals_from_stored_rows(monkeypatch, seed, B, T, K, C):
+    monkeypatch.setenv("SEMICRF_MARGINALS", "rows")
+    w = synth.small_random(seed, B, T, K, C, ragged=True)
+    if seed == 2:
+        w.lengths[0] = 0
+        w.lengths[1] = T
+    rng = np.random.default_rng(seed)
+    check_against_oracle(w, grad_logz=rng.standard_normal(B), label=f"stored rows, rand{seed}")
+    check_against_oracle(w, ckpt_interval=max(8, K // 2 + 3), label=f"stored rows, rand{seed}, short intervals")
+
+
+def test_marginals_from_stored_rows_large_scale_and_mixed_acceptance(monkeypatch):
+    monkeypatch.setenv("SEMICRF_MARGINALS", "rows")
+    # scaling blocks of a few positions
+    check_against_oracle(synth.small_random(21, 2, 400, 12, 5, ragged=False, scale=8.0), label="stored rows, scale 8")
+    # both routes agree with each other to rounding
+    w = synth.small_random(96, 3, 600, 20, 6, ragged=True)
+    dev = to_dev(w)
+    rows = [o.double().cpu().numpy() for o in sb.semicrf_fwd_bwd(*dev)]
+    monkeypatch.setenv("SEMICRF_MARGINALS", "interval")
+    itv = [o.double().cpu().numpy() for o in sb.semicrf_fwd_bwd(*dev)]
+    torch.cuda.synchronize()
+    assert np.array_equal(rows[0], itv[0])
+    for a, b in zip(rows[1:], itv[1:]):
+        assert np.abs(a - b).max() <= 2e-6 * max(1.0, np.abs(b).max())
+    # a slow-mixing input whose scans are rejected falls back to the interval kernels
+    monkeypatch.setenv("SEMICRF_MARGINALS", "rows")
+    B, T, K, C = 2, 600, 4, 3
+    w = synth.small_random(51, B, T, K, C, ragged=False, scale=0.05)
+    w.trans[:] = -14.0
+    np.fill_diagonal(w.trans, 0.0)
+    check_against_oracle(w, ckpt_interval=40, label="stored rows requested, scans rejected")
+
+
+def test_longgen_shape_reduced_takes_the_stored_rows_route():
+    w0 = synth.make("longgen")
+    w = synth.small_random(97, 1, 6000, w0.K, w0.C, ragged=False)
+    w.dur[:] = w0.dur
+    check_against_oracle(w, label="longgen reduced (K = 512)")
