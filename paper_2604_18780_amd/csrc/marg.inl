@@ -39,7 +39,7 @@ __device__ __forceinline__ double mg_yb(const Params &p, const int b, const int 
 __global__ __launch_bounds__(1024) void k_mg_dur(Params p)
 {
     extern __shared__ double lds_raw[];
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, nth = blockDim.x;
     const int K = p.K, C = p.C, N = p.N, Delta = p.Delta;
     const int b = blockIdx.x / N, iv = blockIdx.x % N;
     const SeqHdr h = p.hdr[b];
@@ -103,43 +103,46 @@ __global__ __launch_bounds__(1024) void k_mg_dur(Params p)
         }
         __syncthreads();
         // v_L = ES_L; all exponents are combined before anything is formed, so that an empty row stays
-        // zero and nothing passes through infinity.  The loads of several elements per thread are
-        // issued together (indices of empty rows are clamped, their factor is zero).
+        // zero and nothing passes through infinity.  Thread (row offset, label): no index divisions in
+        // the loops; the loads of several rows per thread are issued together (rows beyond the
+        // sequence are clamped, their factor is zero).
         {
-            constexpr int UQ = 4, UV = 6;
-            for (int i0 = tid; i0 < MG_TG * C; i0 += UQ * (int)blockDim.x) {
-                double qv[UQ];
+            const int rstep = nth / C;               // rows per sweep of the workgroup
+            const int o = tid % C, r0 = tid / C;     // threads with r0 >= rstep idle here
+            if (r0 < rstep) {
+                {
+                    constexpr int UQ = 4;  // the q rows of a thread are fetched together
+                    for (int rb = r0; rb < MG_TG; rb += UQ * rstep) {
+                        double qv[UQ];
 #pragma unroll
-                for (int u = 0; u < UQ; ++u) {
-                    const int i = min(i0 + u * (int)blockDim.x, MG_TG * C - 1);
-                    const int r = min(i / C, ng - 1);
-                    qv[u] = frow[(size_t)(tg0 + r) * C + i % C].y;
+                        for (int u = 0; u < UQ; ++u)
+                            qv[u] = frow[(size_t)(tg0 + min(rb + u * rstep, ng - 1)) * C + o].y;
+#pragma unroll
+                        for (int u = 0; u < UQ; ++u) {
+                            const int r = rb + u * rstep;
+                            if (r < MG_TG) Qrow[r * C + o] = qv[u] * qf[r];  // qf is zero beyond the group
+                        }
+                    }
                 }
+                const int nbt = nb[(size_t)jt * C + o];
+                constexpr int UV = 4;
+                for (int rb = r0; rb < VR; rb += UV * rstep) {
+                    double vs[UV];
+                    int n1[UV];
 #pragma unroll
-                for (int u = 0; u < UQ; ++u) {
-                    const int i = i0 + u * (int)blockDim.x;
-                    if (i < MG_TG * C) Qrow[i] = qv[u] * qf[i / C];  // qf is zero beyond the group
-                }
-            }
-            for (int i0 = tid; i0 < VR * C; i0 += UV * (int)blockDim.x) {
-                double vs[UV];
-                int n1[UV], n0[UV], rr[UV];
+                    for (int u = 0; u < UV; ++u) {
+                        const int r = min(rb + u * rstep, VR - 1);
+                        const int s = min(tg0 + 1 + r, L);
+                        vs[u] = s == L ? EI[(size_t)L * C + o].x : brow[(size_t)s * C + o].y;
+                        n1[u] = nb[(size_t)vj[r] * C + o];
+                    }
 #pragma unroll
-                for (int u = 0; u < UV; ++u) {
-                    const int i = min(i0 + u * (int)blockDim.x, VR * C - 1);
-                    const int r = i / C, o = i % C;
-                    const int s = min(tg0 + 1 + r, L);
-                    rr[u] = r;
-                    vs[u] = s == L ? EI[(size_t)L * C + o].x : brow[(size_t)s * C + o].y;
-                    n1[u] = nb[(size_t)vj[r] * C + o];
-                    n0[u] = nb[(size_t)jt * C + o];
-                }
-#pragma unroll
-                for (int u = 0; u < UV; ++u) {
-                    const int i = i0 + u * (int)blockDim.x;
-                    if (i < VR * C) {
-                        const double f = vf[rr[u]];
-                        Vp[i] = f != 0.0 ? fmin(ldexp(vs[u] * f, n1[u] - n0[u] + ve[rr[u]]), DBL_MAX) : 0.0;
+                    for (int u = 0; u < UV; ++u) {
+                        const int r = rb + u * rstep;
+                        if (r < VR) {
+                            const double f = vf[r];
+                            Vp[r * C + o] = f != 0.0 ? fmin(ldexp(vs[u] * f, n1[u] - nbt + ve[r]), DBL_MAX) : 0.0;
+                        }
                     }
                 }
             }
@@ -211,20 +214,25 @@ __global__ __launch_bounds__(NT) void k_mg_te(Params p)
         const int tg0 = max(lo, tg1 - MG_TE);
         const int ng = tg1 - tg0;
         __syncthreads();
-        for (int i = tid; i < MG_TE * C; i += NT) {
-            const int r = i / C, o = i % C, t = tg0 + r;
-            double ak = 0.0, pp = 0.0, d = 0.0;
-            if (r < ng) {
-                const double2 fa = frow[(size_t)t * C + o], fb = brow[(size_t)t * C + o], e = EI[(size_t)t * C + o];
-                const double kap = kp[t - lo];
-                ak = fa.x * kap;
-                pp = fb.x;
-                // a segment of label o starts at t (z_t p_t, z = q ES) / ends at t (a_t b_t, b = v IE; none ends at 0)
-                d = (fa.y * e.x * fb.x - (t >= 1 ? fa.x * fb.y * e.y : 0.0)) * kap;
+        {
+            const int rstep = NT / C, o = tid % C, r0 = tid / C;  // thread (row offset, label): no index divisions below
+            if (r0 < rstep) {
+                for (int r = r0; r < MG_TE; r += rstep) {
+                    const int t = tg0 + r;
+                    double ak = 0.0, pp = 0.0, d = 0.0;
+                    if (r < ng) {
+                        const double2 fa = frow[(size_t)t * C + o], fb = brow[(size_t)t * C + o], e = EI[(size_t)t * C + o];
+                        const double kap = kp[t - lo];
+                        ak = fa.x * kap;
+                        pp = fb.x;
+                        // a segment of label o starts at t (z_t p_t, z = q ES) / ends at t (a_t b_t, b = v IE; none ends at 0)
+                        d = (fa.y * e.x * fb.x - (t >= 1 ? fa.x * fb.y * e.y : 0.0)) * kap;
+                    }
+                    AK[r * C + o] = ak;
+                    P[r * C + o] = pp;
+                    D[r * C + o] = d;
+                }
             }
-            AK[i] = ak;
-            P[i] = pp;
-            D[i] = d;
         }
         __syncthreads();
 #pragma unroll
