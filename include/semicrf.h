@@ -33,7 +33,7 @@
  *   - Supported sizes: 1 <= C <= 256, and K*C small enough for the ring, the
  *     duration table and the per-interval accumulators to fit the 160 KB LDS of
  *     one compute unit (see semicrf_workspace_bytes, which reports
- *     SEMICRF_EUNSUPPORTED otherwise).
+ *     SEMICRF_EUNSUPPORTED otherwise); T <= 2^30 and B*(T+1)*C <= 2e10.
  */
 #ifndef SEMICRF_H
 #define SEMICRF_H
@@ -49,7 +49,7 @@ typedef enum {
     SEMICRF_OK = 0,
     SEMICRF_EINVAL = -1,       /* bad size, null required pointer, negative interval */
     SEMICRF_EWORKSPACE = -2,   /* workspace_bytes too small or workspace misaligned (256 B) */
-    SEMICRF_EUNSUPPORTED = -3, /* (K,C) does not fit the LDS budget of the kernels */
+    SEMICRF_EUNSUPPORTED = -3, /* (K,C) does not fit the LDS budget of the kernels, or T / B*T*C beyond the stated limits */
     SEMICRF_ELAUNCH = -4       /* a HIP call or kernel launch reported an error */
 } semicrf_status;
 

@@ -3177,7 +3177,7 @@ int auto_interval(int B, int T, int K, int C)
         if (d > dhi && d != T) continue;
         if (d > dhi && n > 1) continue;
         if (d < dlo && best) break;
-        const double tasks = (double)B * (double)((T + d - 1) / d);
+        const double tasks = (double)B * (double)(((long long)T + d - 1) / d);
         const double cost = ceil(2.0 * tasks / slots_scan) * (warm + d) + 1.2 * ceil(tasks / slots_int) * d;
         if (!best || cost < best_cost) {
             best = d;
@@ -3188,8 +3188,12 @@ int auto_interval(int B, int T, int K, int C)
     return best;
 }
 
+bool spec_applies(int K, int C);
+
 struct Plan {
     int Delta, N, NCH, nslot, G;
+    int rows;  // the backward scan tasks have row storage (stored-row marginals possible)
+    size_t lds_mg_dur, lds_mg_te;
     size_t lds_scan, lds_interval;
     size_t total;
     size_t off[32];
@@ -3199,7 +3203,7 @@ int make_plan(int B, int T, int K, int C, int ckpt_interval, int want_grad, Plan
 {
     if (B < 1 || T < 1 || K < 1 || C < 1 || ckpt_interval < 0) return SEMICRF_EINVAL;
     if (C > 256) return SEMICRF_EUNSUPPORTED;
-    if ((double)B * ((double)T + 1.0) * (double)C > 2.0e10) return SEMICRF_EUNSUPPORTED;
+    if (T > (1 << 30) || (double)B * ((double)T + 1.0) * (double)C > 2.0e10) return SEMICRF_EUNSUPPORTED;
     pl->Delta = ckpt_interval > 0 ? (ckpt_interval > T ? T : ckpt_interval) : auto_interval(B, T, K, C);
     pl->N = (T + pl->Delta - 1) / pl->Delta;
     pl->NCH = T / PREP_CH + 1;
@@ -3244,8 +3248,24 @@ int make_plan(int B, int T, int K, int C, int ckpt_interval, int want_grad, Plan
     sz[i++] = g * b * (n + 1) * 8;                // 25 ckYB2
     sz[i++] = b * c * 8;                          // 26 out0
     sz[i++] = b * c * 8;                          // 27 inL
-    sz[i++] = g * (size_t)pl->nslot * pl->Delta * 2 * c * 8;  // 28 bloc
-    sz[i++] = g * (size_t)pl->nslot * pl->Delta * 8;          // 29 blocY
+    // Marginals from the stored rows of both scans need a second set of row slots.  Measured: the
+    // route wins where the K-deep window makes the interval kernel's recurrence long (K = 512:
+    // 0.52 ms against 1.08 ms) and is level with it at K = 64, so it is planned for K >= 128,
+    // when every task has its slot and the sizes fit its kernels.
+    const int mg_nsl = (K + MG_KS - 1) / MG_KS;
+    const size_t mg_vr = (size_t)MG_TG + MG_KS * mg_nsl + 3;
+    pl->lds_mg_dur = ((MG_TG + mg_vr) * c + MG_TG + 2 * mg_vr + 2 * (size_t)pl->Delta + k) * sizeof(double);
+    pl->lds_mg_te = ((size_t)3 * MG_TE * c + pl->Delta) * sizeof(double);
+    bool rows = K >= 128;
+    if (const char *e = getenv("SEMICRF_MARGINALS")) {  // tuning knob: "interval" / "rows" force one route
+        if (e[0] == 'i') rows = false;
+        if (e[0] == 'r') rows = true;
+    }
+    pl->rows = rows && want_grad && spec_applies(K, C) && ntask <= (size_t)pl->nslot && c * mg_nsl <= 1024 &&
+               pl->lds_mg_dur <= LDS_LIMIT && pl->lds_mg_te <= LDS_LIMIT;
+    const size_t gr = pl->rows ? 1 : 0;
+    sz[i++] = gr * (size_t)pl->nslot * pl->Delta * 2 * c * 8;  // 28 bloc
+    sz[i++] = gr * (size_t)pl->nslot * pl->Delta * 8;          // 29 blocY
     size_t off = 0;
     for (int j = 0; j < i; ++j) {
         pl->off[j] = off;
@@ -3497,21 +3517,11 @@ int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hi
     }
     p.spec = p.spec && mode != 0 && spec_applies(p.K, p.C);
     p.fuse = p.spec && mode == 2 && (size_t)p.B * pl.N <= (size_t)pl.nslot;  // one slot per task
-    // Marginals from the stored rows of both scans: when every task has its slot, no boundary-term
-    // output is asked for (those come from the interval kernels) and the sizes fit its kernels.
+    // Marginals from the stored rows of both scans: where the plan has the row slots and no
+    // boundary-term output is asked for (those come from the interval kernels).
+    p.marg = pl.rows && p.fuse && !p.g_proj_start && !p.g_proj_end && !p.g_pi_start && !p.g_pi_end && !p.bdy_post;
+    const size_t mg_lds_d = pl.lds_mg_dur, mg_lds_t = pl.lds_mg_te;
     const int mg_nsl = (p.K + MG_KS - 1) / MG_KS;
-    const size_t mg_vr = (size_t)MG_TG + MG_KS * mg_nsl + 3;
-    const size_t mg_lds_d = ((MG_TG + mg_vr) * p.C + MG_TG + 2 * mg_vr + 2 * (size_t)pl.Delta + p.K) * sizeof(double);
-    const size_t mg_lds_t = ((size_t)3 * MG_TE * p.C + pl.Delta) * sizeof(double);
-    // Measured: it wins where the K-deep window makes the interval kernel's recurrence long (K = 512:
-    // 0.62 ms against 1.08 ms) and is level with it at K = 64, so it is taken for K >= 128.
-    const bool mg_fits = p.fuse && !p.g_proj_start && !p.g_proj_end && !p.g_pi_start && !p.g_pi_end &&
-                         !p.bdy_post && p.C * mg_nsl <= 1024 && mg_lds_d <= LDS_LIMIT && mg_lds_t <= LDS_LIMIT;
-    p.marg = mg_fits && p.K >= 128;
-    if (const char *e = getenv("SEMICRF_MARGINALS")) {  // tuning knob: "interval" / "rows" force one route
-        if (e[0] == 'i') p.marg = 0;
-        if (e[0] == 'r') p.marg = mg_fits;
-    }
     T.mark();
     rc = launch_prep(p, st);
     T.mark();
@@ -3753,7 +3763,7 @@ int dt_auto_interval(int B, int T, int K, const DtGeom &g)
         int d = ((T + n - 1) / n + 7) & ~7;
         if (d > T) d = T;
         if (d < dlo && best) break;
-        const double tasks = (double)B * (double)((T + d - 1) / d);
+        const double tasks = (double)B * (double)(((long long)T + d - 1) / d);
         const double cost = ceil(tasks / slots) * (warm + d);
         if (!best || cost < best_cost) {
             best = d;

@@ -75,6 +75,16 @@ def test_working_memory_beyond_prefix_arrays_is_bounded_then_sublinear_in_T():
         assert extra(T) < 1.5 * B * (T + 1) * C * 20
     # 16x longer sequences: sqrt growth is 4x (the number of rounds is an integer, hence the slack), linear 16x
     assert extra(204800000) / extra(12800000) < 6.0
+    # long maximal durations (K >= 128): the backward scan tasks keep their rows too, one more
+    # O(T*C) array while every task has a slot, and nothing more once they do not
+    extra512 = lambda T: (sb.semicrf_workspace_bytes(2, T, 512, 8, 0, True)
+                          - sb.semicrf_workspace_bytes(2, T, 512, 8, 0, False))
+    for T in (400000, 1600000):
+        assert extra512(T) < 2.5 * 2 * (T + 1) * 8 * 20
+    assert extra512(1000000000) / extra512(62500000) < 6.0
+    # sequences beyond 2^30 positions are refused (positions are 32-bit in the kernels)
+    with pytest.raises(Exception, match="-3"):
+        sb.semicrf_workspace_bytes(1, (1 << 30) + 1, 4, 2, 0, True)
     # and it is of the order of what the paper's own per-interval layout (full K x C x C
     # gradient workspace per checkpoint) would need, without the K*C*C blow-up per interval
     T = 100000
