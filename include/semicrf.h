@@ -134,6 +134,14 @@ int semicrf_logz_fwd(const float *emis, const int32_t *lengths, const float *tra
  *   pos_marg   [B,T,C] float or NULL: posterior P(token u has label c), which is the
  *                             gradient of logZ_b w.r.t. the centred emission; rows
  *                             u >= L_b are 0.
+ * For K >= 128 (when every checkpoint interval has a buffer slot of its own) the chunk-parallel
+ * backward scan keeps its per-position rows as the forward scan does, and the expected
+ * statistics of the "Gradient Formulas" section are formed as position-local products of the
+ * two sets of rows instead of by a third recurrence per interval; sequences whose scans were
+ * not both accepted take Algorithm 3's per-interval pass.  The results are the same to the
+ * rounding of the outputs.  The environment variable SEMICRF_MARGINALS ("rows" / "interval") is a
+ * tuning knob that forces one route; it is read by semicrf_workspace_bytes too (the rows
+ * need workspace), so it must not change between sizing the workspace and the call.
  */
 int semicrf_fwd_bwd(const float *emis, const int32_t *lengths, const float *trans,
                     const float *dur, const float *grad_logz, int B, int T, int K, int C,

@@ -31,8 +31,9 @@
 // positions); k_scan_fast / k_scan (the same scans sequentially, for what the verification
 // rejects); k_interval_wave / k_interval (per checkpoint interval: recompute the forward
 // messages unless the scan stored them, run beta across the interval, accumulate the
-// expected sufficient statistics in registers/LDS, no global atomics); k_fin_seq (+ the
-// parameter gradients), k_fin_emis (fixed-order reductions).
+// expected sufficient statistics in registers/LDS, no global atomics); k_mg_dur / k_mg_te
+// (the same statistics as position-local products of the rows both scans stored, for long
+// maximal durations); k_fin_seq (+ the parameter gradients), k_fin_emis (fixed-order reductions).
 #include <hip/hip_runtime.h>
 #include <float.h>
 #include <math.h>
