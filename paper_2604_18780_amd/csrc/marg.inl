@@ -53,8 +53,12 @@ __global__ __launch_bounds__(1024) void k_mg_dur(Params p)
     const int c = tid % C, kA = (tid / C) * MG_KS;
     const int VR = MG_TG + MG_KS * nsl + 3;
     double *Qrow = lds_raw;            // [MG_TG][C]
-    double *Vp = Qrow + MG_TG * C;     // [VR][C]
-    double *qf = Vp + VR * C;          // [MG_TG] per-row factors of the group
+    // rows of CP = C|3 doubles: the threads of a wave read rows MG_KS apart (one per duration strip),
+    // and MG_KS*C is a multiple of the 32 banks (of 8 bytes) for every C that is a multiple of 4;
+    // with CP = 3 mod 4 the strips of a half-wave fall 24 banks apart instead of on top of each other
+    const int CP = C | 3;
+    double *Vp = Qrow + MG_TG * C;     // [VR][CP]
+    double *qf = Vp + VR * CP;         // [MG_TG] per-row factors of the group
     double *vf = qf + MG_TG;           // [VR]
     int *ve = (int *)(vf + VR);        // [VR]
     int *vj = ve + VR;                 // [VR]
@@ -141,7 +145,7 @@ __global__ __launch_bounds__(1024) void k_mg_dur(Params p)
                         const int r = rb + u * rstep;
                         if (r < VR) {
                             const double f = vf[r];
-                            Vp[r * C + o] = f != 0.0 ? fmin(ldexp(vs[u] * f, n1[u] - nbt + ve[r]), DBL_MAX) : 0.0;
+                            Vp[r * CP + o] = f != 0.0 ? fmin(ldexp(vs[u] * f, n1[u] - nbt + ve[r]), DBL_MAX) : 0.0;
                         }
                     }
                 }
@@ -155,7 +159,7 @@ __global__ __launch_bounds__(1024) void k_mg_dur(Params p)
                 for (int i = 0; i < 4; ++i) ca[i] = i0 + i < ng ? Qrow[(i0 + i) * C + c] : 0.0;
                 double w[MG_KS + 3];
 #pragma unroll
-                for (int q = 0; q < MG_KS + 3; ++q) w[q] = Vp[(i0 + kA + q) * C + c];
+                for (int q = 0; q < MG_KS + 3; ++q) w[q] = Vp[(i0 + kA + q) * CP + c];
 #pragma unroll
                 for (int kk = 0; kk < MG_KS; ++kk) {
 #pragma unroll

@@ -3255,7 +3255,7 @@ int make_plan(int B, int T, int K, int C, int ckpt_interval, int want_grad, Plan
     // when every task has its slot and the sizes fit its kernels.
     const int mg_nsl = (K + MG_KS - 1) / MG_KS;
     const size_t mg_vr = (size_t)MG_TG + MG_KS * mg_nsl + 3;
-    pl->lds_mg_dur = ((MG_TG + mg_vr) * c + MG_TG + 2 * mg_vr + 2 * (size_t)pl->Delta + k) * sizeof(double);
+    pl->lds_mg_dur = (MG_TG * c + mg_vr * (c | 3) + MG_TG + 2 * mg_vr + 2 * (size_t)pl->Delta + k) * sizeof(double);
     pl->lds_mg_te = ((size_t)3 * MG_TE * c + pl->Delta) * sizeof(double);
     bool rows = K >= 128;
     if (const char *e = getenv("SEMICRF_MARGINALS")) {  // tuning knob: "interval" / "rows" force one route
