@@ -202,10 +202,17 @@ def main():
     # interval and accumulates the marginals (2 units).  Warm-up positions of the chunk-parallel
     # scans are overhead and are not counted.
     unit = 2.0 * (K * C + C * C) * positions
-    stage_flop = {"scans": 2 * unit, "intervals": 2 * unit}
+    # For K >= 128 the library takes the marginals from the rows both scans stored (position-local
+    # products: 1 unit, no third recurrence), unless SEMICRF_MARGINALS forces a route; counting 1 unit
+    # there can only understate the rate if the library fell back to the interval kernel.
+    knob = os.environ.get("SEMICRF_MARGINALS", "")[:1]
+    rows_route = knob == "r" or (K >= 128 and knob != "i")
+    stage_flop = {"scans": 2 * unit, "intervals": (1 if rows_route else 2) * unit}
     kernels = {"scans": "k_spec (chunk-parallel forward + backward scans, one launch; stage time "
                         "includes its two small verification kernels)",
-               "intervals": "k_interval_wave / k_interval (per-interval recompute + marginals, one launch)"}
+               "intervals": ("k_mg_dur + k_mg_te (marginals from the stored rows of both scans, two launches)"
+                             if rows_route else
+                             "k_interval_wave / k_interval (per-interval recompute + marginals, one launch)")}
     # HBM bytes per launch of the two big kernels at the genomic workload with the automatic
     # interval, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by a 1 GiB copy
     # (profiles/hot_path_genomic_hbm_traffic_pmc.txt); unknown for other workloads.
@@ -213,7 +220,7 @@ def main():
     dom = "scans" if stage[1] >= stage[2] else "intervals"
     dom_s = (stage[1] if dom == "scans" else stage[2]) * 1e-3
     achieved = stage_flop[dom] / dom_s / 1e12
-    whole = 4 * unit / (ms_step * 1e-3) / 1e12
+    whole = (stage_flop["scans"] + stage_flop["intervals"]) / (ms_step * 1e-3) / 1e12
     logz = out[0].double().cpu().numpy()
     acc, mis = sb.semicrf_scan_report(ws, B, T, K, C, args.ckpt_interval, True)
     torch.cuda.synchronize()
