@@ -392,6 +392,19 @@ def test_marginals_from_stored_rows_large_scale_and_mixed_acceptance(monkeypatch
     check_against_oracle(w, ckpt_interval=40, label="stored rows requested, scans rejected")
 
 
+@pytest.mark.parametrize("seed,B,T,K,C,scale", [
+    (31, 2, 1500, 160, 24, 1.0),   # three duration strips per label row of a wave
+    (32, 1, 600, 128, 32, 1.0),    # K*C at the limit of the gradient kernels
+    (35, 1, 2500, 1024, 4, 1.0),   # the longest durations they take
+    (33, 2, 900, 130, 5, 30.0),    # scaling blocks of one or two positions: a frame per one or two positions
+    (34, 3, 700, 200, 12, 8.0),
+])
+def test_long_durations_take_the_stored_rows_route_by_default(seed, B, T, K, C, scale):
+    w = synth.small_random(seed, B, T, K, C, ragged=True, scale=scale)
+    rng = np.random.default_rng(seed)
+    check_against_oracle(w, grad_logz=rng.standard_normal(B), label=f"K >= 128, rand{seed}")
+
+
 def test_longgen_shape_reduced_takes_the_stored_rows_route():
     w0 = synth.make("longgen")
     w = synth.small_random(97, 1, 6000, w0.K, w0.C, ragged=False)
