@@ -3200,6 +3200,7 @@ struct Plan {
     size_t off[32];
 };
 
+// want_grad: 0 forward only, 1 gradients, 2 gradients of a caller that never takes the stored-row marginals
 int make_plan(int B, int T, int K, int C, int ckpt_interval, int want_grad, Plan *pl)
 {
     if (B < 1 || T < 1 || K < 1 || C < 1 || ckpt_interval < 0) return SEMICRF_EINVAL;
@@ -3262,7 +3263,7 @@ int make_plan(int B, int T, int K, int C, int ckpt_interval, int want_grad, Plan
         if (e[0] == 'i') rows = false;
         if (e[0] == 'r') rows = true;
     }
-    pl->rows = rows && want_grad && spec_applies(K, C) && ntask <= (size_t)pl->nslot && c * mg_nsl <= 1024 &&
+    pl->rows = rows && want_grad == 1 && spec_applies(K, C) && ntask <= (size_t)pl->nslot && c * mg_nsl <= 1024 &&
                pl->lds_mg_dur <= LDS_LIMIT && pl->lds_mg_te <= LDS_LIMIT;
     const size_t gr = pl->rows ? 1 : 0;
     sz[i++] = gr * (size_t)pl->nslot * pl->Delta * 2 * c * 8;  // 28 bloc
@@ -3848,7 +3849,7 @@ int run_durtrans(Params p, int ckpt_interval, void *workspace, size_t workspace_
     if (!dt_geometry(p.K, p.C, &g)) return SEMICRF_EUNSUPPORTED;
     if (ckpt_interval == 0) ckpt_interval = dt_auto_interval(p.B, p.T, p.K, g);
     Plan pl;
-    int rc = make_plan(p.B, p.T, p.K, p.C, ckpt_interval, grad ? 1 : 0, &pl);
+    int rc = make_plan(p.B, p.T, p.K, p.C, ckpt_interval, grad ? 2 : 0, &pl);
     if (rc != SEMICRF_OK) return rc;
     const DtLayout dl = dt_layout(p.B, p.T, p.K, p.C, pl.N, grad ? 1 : 0);
     if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < pl.total + dl.total)
@@ -4121,7 +4122,7 @@ int semicrf_durtrans_workspace_bytes(int B, int T, int K, int C, int ckpt_interv
     if (!dt_geometry(K, C, &g)) return SEMICRF_EUNSUPPORTED;
     if (ckpt_interval == 0) ckpt_interval = dt_auto_interval(B, T, K, g);
     Plan pl;
-    int rc = make_plan(B, T, K, C, ckpt_interval, want_grad ? 1 : 0, &pl);
+    int rc = make_plan(B, T, K, C, ckpt_interval, want_grad ? 2 : 0, &pl);
     if (rc != SEMICRF_OK) return rc;
     *bytes = pl.total + dt_layout(B, T, K, C, pl.N, want_grad ? 1 : 0).total;
     return SEMICRF_OK;
