@@ -1323,10 +1323,12 @@ __host__ __device__ constexpr int wave_nk(int CT, int NKW)
     return NKW + ((64 / pow2_ge8(CT)) > 2 ? 1 : 0);
 }
 
-// Rows of slack behind the sliding window.
+// Rows of slack behind the sliding window: a quarter of the window (the window is moved back once
+// per that many positions), an eighth for the deepest window, where the quarter would cost the
+// fourth resident task of a compute unit its LDS.
 __host__ __device__ constexpr int lin_slack(int KW)
 {
-    return KW / 4 < 8 ? 8 : ((KW / 4 + 3) & ~3);
+    return KW / 4 < 8 ? 8 : (KW >= 512 ? ((KW / 8 + 3) & ~3) : ((KW / 4 + 3) & ~3));
 }
 
 __host__ __device__ constexpr size_t wave_lds_doubles(int CT, int NKW)
