@@ -226,3 +226,18 @@ def test_binding_requires_the_built_library(monkeypatch, tmp_path):
     with pytest.raises(FileNotFoundError):
         mod.load()
     importlib.reload(sb)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU only: `bench.py --gpus N` with N > 1 (or under a multi-rank launcher) exits with a
+    message that says so, before anything touches a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "one GPU only" in r.stderr and r.stdout.strip() == ""
+    env = dict(os.environ, WORLD_SIZE="2")
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py")], capture_output=True, text=True,
+                       timeout=120, env=env)
+    assert r.returncode != 0 and "one GPU only" in r.stderr
