@@ -150,6 +150,26 @@ int semicrf_fwd_bwd(const float *emis, const int32_t *lengths, const float *tran
                     float *pos_marg, void *stream);
 
 /*
+ * For callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  semicrf_fwd_bwd with the
+ * workspace taken from a static array in the library's device image instead of an argument:
+ * SEMICRF_STATIC_WORKSPACE_BYTES per GPU, held by every GPU the library runs on until the process
+ * ends.  The call allocates and frees nothing (no hipMalloc, hipFree or allocating library
+ * routine); the first call on a device looks the array's address up once.  Inputs, outputs,
+ * results and errors are those of semicrf_fwd_bwd; sizes whose semicrf_workspace_bytes(B, T, K, C,
+ * ckpt_interval, 1) exceeds the limit return SEMICRF_EWORKSPACE before anything is launched.
+ * All calls on one GPU share that GPU's array: calls that may overlap in time on one GPU (two
+ * streams, two host threads) race on it and must be serialised by the caller.  Nothing in the
+ * array has to survive between calls and nothing in it is assumed zero: every call writes what
+ * it later reads.  The device that is current when the call is made must be the stream's.
+ */
+#define SEMICRF_STATIC_WORKSPACE_BYTES (64u << 20)
+int semicrf_fwd_bwd_static(const float *emis, const int32_t *lengths, const float *trans,
+                           const float *dur, const float *grad_logz, int B, int T, int K, int C,
+                           int ckpt_interval, unsigned flags, float *logz, float *grad_emis,
+                           float *grad_trans, float *grad_dur, float *pos_marg, void *stream);
+
+/*
  * The full edge potential of Eq. 4: the three terms above plus the optional boundary terms
  * of the "Boundary Projections" section and the scalar sequence boundaries of the appendix on
  * boundary handling.  A segment [s, s+k) with label c additionally scores

@@ -20,7 +20,8 @@ EXPORTS = ("semicrf_version", "semicrf_strerror", "semicrf_workspace_bytes",
            "semicrf_scan_report", "semicrf_ckpt_interval", "semicrf_logz_fwd_boundary",
            "semicrf_fwd_bwd_boundary", "semicrf_entropies", "semicrf_viterbi_workspace_bytes",
            "semicrf_viterbi", "semicrf_durtrans_workspace_bytes", "semicrf_durtrans_ckpt_interval", "semicrf_logz_fwd_durtrans",
-           "semicrf_fwd_bwd_durtrans")
+           "semicrf_fwd_bwd_durtrans", "semicrf_fwd_bwd_static")
+SEMICRF_STATIC_WORKSPACE_BYTES = 64 << 20
 SEMICRF_CENTER = 1
 SEMICRF_SEQUENTIAL_SCAN = 2
 SEMICRF_EMIS_F16 = 4
@@ -58,6 +59,8 @@ def load():
     lib.semicrf_fwd_bwd.restype = ci
     lib.semicrf_fwd_bwd.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, cu, vp, sz,
                                     vp, vp, vp, vp, vp, vp]
+    lib.semicrf_fwd_bwd_static.restype = ci
+    lib.semicrf_fwd_bwd_static.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, cu, vp, vp, vp, vp, vp, vp]
     lib.semicrf_fwd_bwd_profiled.restype = ci
     lib.semicrf_fwd_bwd_profiled.argtypes = lib.semicrf_fwd_bwd.argtypes + [ctypes.POINTER(vp)]
     lib.semicrf_ckpt_interval.restype = ci
@@ -193,6 +196,22 @@ def semicrf_fwd_bwd(emis, lengths, trans, dur, grad_logz=None, ckpt_interval=0,
                                   _ptr(g_t, torch.float32), _ptr(g_d, torch.float32),
                                   _ptr(pm, torch.float32), _stream()))
     return logz, g_e, g_t, g_d, pm
+
+
+def semicrf_fwd_bwd_static(emis, lengths, trans, dur, out, grad_logz=None, ckpt_interval=0,
+                           flags=SEMICRF_CENTER):
+    """semicrf_fwd_bwd on the library's static workspace.  `out` = (logz, grad_emis, grad_trans,
+    grad_dur, pos_marg or None), preallocated by the caller: nothing is allocated here."""
+    B, T, C = emis.shape
+    K = dur.shape[0]
+    logz, g_e, g_t, g_d, pm = out
+    ep, flags = _emis(emis, flags)
+    _check(load().semicrf_fwd_bwd_static(ep, _ptr(lengths, torch.int32), _ptr(trans, torch.float32),
+                                         _ptr(dur, torch.float32), _ptr(grad_logz, torch.float32), B, T, K, C,
+                                         ckpt_interval, flags, _ptr(logz, torch.float32),
+                                         _ptr(g_e, torch.float32), _ptr(g_t, torch.float32),
+                                         _ptr(g_d, torch.float32), _ptr(pm, torch.float32), _stream()))
+    return out
 
 
 def semicrf_logz_fwd_boundary(emis, lengths, trans, dur, proj_start=None, proj_end=None, pi_start=None,

@@ -39,9 +39,16 @@
 #include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
+#include <mutex>
 #include <type_traits>
 
 #include "semicrf.h"
+
+// Workspace of semicrf_fwd_bwd_static: callers that cannot allocate (HIP graph capture, serving
+// loops) get the library's scratch memory from this array instead of a workspace argument.  Every
+// GPU the library runs on holds its own copy until the process ends.  In host code the name is only
+// a handle for hipGetSymbolAddress; kernels receive the device address obtained there.
+static __device__ __align__(256) unsigned char scratch[SEMICRF_STATIC_WORKSPACE_BYTES];
 
 namespace {
 
@@ -3911,6 +3918,27 @@ int run_durtrans(Params p, int ckpt_interval, void *workspace, size_t workspace_
     return check_launch();
 }
 
+// Device address of this GPU's copy of the static scratch array, looked up once per device with
+// that device current and kept for the life of the process.
+constexpr int STATIC_MAX_DEVICES = 64;
+std::mutex static_mu;
+void *static_ptr[STATIC_MAX_DEVICES] = {};
+
+int static_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= STATIC_MAX_DEVICES) return SEMICRF_ELAUNCH;
+    std::lock_guard<std::mutex> lock(static_mu);
+    if (!static_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return SEMICRF_ELAUNCH;
+        if (((uintptr_t)p & 255) != 0) return SEMICRF_ELAUNCH;
+        static_ptr[dev] = p;
+    }
+    *out = static_ptr[dev];
+    return SEMICRF_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -4000,6 +4028,24 @@ int semicrf_fwd_bwd(const float *emis, const int32_t *lengths, const float *tran
     p.logz = logz; p.grad_emis = grad_emis; p.grad_trans = grad_trans; p.grad_dur = grad_dur;
     p.pos_marg = pos_marg;
     return run(p, ckpt_interval, workspace, workspace_bytes, (hipStream_t)stream, 2);
+}
+
+int semicrf_fwd_bwd_static(const float *emis, const int32_t *lengths, const float *trans, const float *dur,
+                           const float *grad_logz, int B, int T, int K, int C, int ckpt_interval,
+                           unsigned flags, float *logz, float *grad_emis, float *grad_trans,
+                           float *grad_dur, float *pos_marg, void *stream)
+{
+    // sizes first: nothing is touched when the plan does not fit the static array
+    size_t need = 0;
+    int rc = semicrf_workspace_bytes(B, T, K, C, ckpt_interval, 1, &need);
+    if (rc != SEMICRF_OK) return rc;
+    if (need > (size_t)SEMICRF_STATIC_WORKSPACE_BYTES) return SEMICRF_EWORKSPACE;
+    void *ws = nullptr;
+    rc = static_scratch(&ws);
+    if (rc != SEMICRF_OK) return rc;
+    return semicrf_fwd_bwd(emis, lengths, trans, dur, grad_logz, B, T, K, C, ckpt_interval, flags, ws,
+                           (size_t)SEMICRF_STATIC_WORKSPACE_BYTES, logz, grad_emis, grad_trans, grad_dur,
+                           pos_marg, stream);
 }
 
 int semicrf_fwd_bwd_profiled(const float *emis, const int32_t *lengths, const float *trans,
