@@ -75,6 +75,15 @@ typedef enum {
  * everything downstream is unchanged (all outputs stay float).  Setting both is invalid. */
 #define SEMICRF_EMIS_F16 4u
 #define SEMICRF_EMIS_BF16 8u
+/* flags bit 4: run the chunk-parallel scans of semicrf_logz_fwd / semicrf_fwd_bwd (and their _boundary forms)
+ * on the matrix cores where the sizes allow (17 <= C <= 24, K <= 64, checkpoint interval a multiple of 32,
+ * B*(T+1)*C < 2^27): sixteen checkpoint intervals advance in lock step as the columns of
+ * v_mfma_f64_16x16x4_f64 products (window: [16 positions] x [4 source positions] x [16 intervals] per label,
+ * transition: [16 labels] x [4 labels] x [16 intervals] per position).  Checkpoints, verification and results
+ * are those of the default one-wave-per-interval kernel (the acceptance test is the same); only the time
+ * differs.  Off by default: measured slower than the default kernel on MI355X (a lone wave per SIMD issues its
+ * per-position bookkeeping too slowly); kept as the measured alternative.  Ignored where the sizes do not allow it. */
+#define SEMICRF_MATRIX_SCAN 16u
 
 int semicrf_version(void);
 

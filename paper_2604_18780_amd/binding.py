@@ -26,6 +26,7 @@ SEMICRF_CENTER = 1
 SEMICRF_SEQUENTIAL_SCAN = 2
 SEMICRF_EMIS_F16 = 4
 SEMICRF_EMIS_BF16 = 8
+SEMICRF_MATRIX_SCAN = 16
 _lib = None
 
 

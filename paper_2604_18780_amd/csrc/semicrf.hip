@@ -41,8 +41,10 @@
 #include <stdlib.h>
 #include <mutex>
 #include <type_traits>
+#include <utility>
 
 #include "semicrf.h"
+#include "common.h"
 
 // Workspace of semicrf_fwd_bwd_static: callers that cannot allocate (HIP graph capture, serving
 // loops) get the library's scratch memory from this array instead of a workspace argument.  Every
@@ -52,132 +54,7 @@ static __device__ __align__(256) unsigned char scratch[SEMICRF_STATIC_WORKSPACE_
 
 namespace {
 
-constexpr int NT = 256;          // threads per workgroup in the scan kernels
-constexpr int PREP_CH = 256;     // positions per prefix-sum chunk (multiple of JMAX)
-constexpr int JMAX = 32;         // largest scaling block
-constexpr int NSLOT_MAX = 1024;  // resident tasks of the interval kernel (one wave per SIMD)
-constexpr int GRAD_CMAX = 64;    // most labels the gradient path holds transition accumulators for
-constexpr double LN2 = 0.6931471805599453094;
-constexpr double LOG2E = 1.4426950408889634074;
-constexpr double RANGE_NATS = 300.0;  // growth allowed inside one scaling block (2x this < ln DBL_MAX)
-constexpr size_t LDS_LIMIT = 160 * 1024;
-
-struct SeqHdr {
-    int L;          // clamped length
-    int J;          // scaling block length (power of two <= JMAX)
-    int flags;      // bit 0: scores exceed the supported per-position range
-    int pad;
-    double logZ;    // from the forward scan
-    double logZb;   // from the backward scan (diagnostic: must equal logZ)
-};
-
-struct Params {
-    // problem
-    const void *emis;   // [B][T][C] float, or 2-byte IEEE half / bfloat16 (emis_type 1 / 2)
-    int emis_type;
-    const int32_t *lengths;
-    const float *trans;
-    const float *dur;
-    const float *grad_logz;
-    // optional boundary terms of Eq. 4 (any of them may be null)
-    const float *proj_start;  // [B][T][C]  start score of a segment whose first token is t
-    const float *proj_end;    // [B][T][C]  end score of a segment whose last token is t
-    const float *pi_start;    // [C]        scalar boundary of the sequence's first segment
-    const float *pi_end;      // [C]        scalar boundary of the sequence's last segment
-    int B, T, K, C;
-    int Delta, N;       // checkpoint interval and intervals per padded sequence
-    int NCH;            // prefix-sum chunks per sequence (covers t = 0..T)
-    int center;
-    int want_grad;
-    int nslot;
-    // workspace
-    SeqHdr *hdr;        // [B]
-    double *nu;         // [B][C]
-    double *chsum;      // [B][NCH][C] chunk sums, then exclusive chunk offsets
-    double *chmax;      // [B][NCH]
-    double *tabmax;     // [2]: max dur, max trans
-    double *W;          // [K][C]
-    double *Etr;        // [C][C]
-    double2 *EI;        // [B][T+1][C]  .x = ES = exp(S - n ln2), .y = 1/ES
-    int *nbase;         // [B][T+1][C] (row j = scaling block j)
-    double *ckA;        // [B][N+1][K*C + C]
-    double *ckB;        // [B][N+1][K*C + C]
-    double *ckYA;       // [B][N+1]
-    double *ckYB;       // [B][N+1]
-    // chunk-parallel scan: states reached at the END of a chunk (compared with the next
-    // chunk's warm-up state), their scales, per-boundary log2 scale ratios and mismatches
-    double *ckA2;       // [B][N+1][K*C + C]
-    double *ckB2;       // [B][N+1][K*C + C]
-    double *ckYA2;      // [B][N+1]
-    double *ckYB2;      // [B][N+1]
-    double *spec_lr;    // [B][2][N+1]
-    double *spec_err;   // [B][2][N+1]
-    int *spec_ok;       // [B][2]  1: the chunk-parallel scan of (sequence, direction) was accepted
-    int logpair;        // k_prefix stores the log-domain pair (S + end score, start score - S): Viterbi
-    double2 *vr;        // [B][T+1][C] Viterbi: (V_t(c), r_t(c)) = best score arriving at / leaving position t
-    int *vbest;         // [B] Viterbi: label of the last segment
-    int *vbp;           // [B][T+1][C] Viterbi back-pointers: (duration << 8) | predecessor label
-    int *vpar[2];       // [B][T+1][C] parent node (position * C + label) and its doublings (ping-pong)
-    int *vexit;         // [B][T+1][C] second buffer of the interval-exit pointers (the first is vpar[1])
-    unsigned char *vmark;  // [B][T+1][C] 1: the node lies on the best path
-    float *vscore;      // Viterbi outputs
-    int32_t *vlabels, *vstarts, *vnseg;
-    int spec;           // chunk-parallel scan enabled for this call
-    int fuse;           // its forward tasks also store the interval stage's forward rows (one slot per task)
-    double *aloc;       // [nslot][Delta][2C]
-    double *alocY;      // [nslot][Delta]
-    double *bloc;       // [nslot][Delta][2C] backward rows (p_t, v_t) of the chunk-parallel backward tasks
-    double *blocY;      // [nslot][Delta]     their scale relative to the interval's upper end
-    int marg;           // marginals from the stored rows of both scans (no recurrence in the interval stage)
-    double *partD;      // [B][N][K][C]
-    double *partTr;     // [B][N][C][C]
-    double *tot;        // [B][N][C]
-    double *sumR;       // [B][N][C]
-    double *carry;      // [B][N][C]
-    double *mean;       // [B][C]
-    double *out0;       // [B][C]  mass of the segments that start at position 0, per label
-    double *inL;        // [B][C]  mass of the segments that end at position L, per label
-    // outputs
-    double *cum;        // optional [B][T+1][C]
-    float *logz;
-    float *grad_emis;
-    float *grad_trans;
-    float *grad_dur;
-    float *pos_marg;
-    float *g_proj_start;  // optional [B][T][C]
-    float *g_proj_end;    // optional [B][T][C]
-    float *g_pi_start;    // optional [C]
-    float *g_pi_end;      // optional [C]
-    float *bdy_post;      // optional [B][T+1]
-    // duration-dependent transitions (null / unused otherwise)
-    const float *trans3;  // [K][C][C] trans3[k-1][c'][c] in place of trans[c'][c]
-    double *G3;           // [K][C][C] exp(dur[k-1,c] + trans3[k-1,c',c])
-    double *dtA;          // [B][T+1][C] forward messages a_t(c), scaled
-    double *dtY;          // [B][T+1]    log2 scale of that row relative to its interval's first position
-    double *dtV;          // [B][T+1][C] backward messages v_t(c) = b_t(c) ES_t(c), scaled
-    double *dtD;          // [B][T+1][C] (mass of the segments that start at t) - (that end at t), scaled
-    double *dtYb;         // [B][T+1]    log2 scale of those two rows relative to the interval's upper end
-    double *partG;        // [dt_nwg][K][C][C] per-workgroup sums of the weighted segment marginals
-    double *sumG;         // [K][C][C] their fixed-order total
-    int dt_nwg;
-    float *grad_trans3;   // output [K][C][C]
-};
-
-// emission i of the [B][T][C] array; ET = storage type (0 float, 1 IEEE half, 2 bfloat16)
-template <int ET>
-__device__ __forceinline__ double emis_at(const Params &p, size_t i)
-{
-    if (ET == 0) return (double)((const float *)p.emis)[i];
-    if (ET == 1) return (double)(float)((const _Float16 *)p.emis)[i];
-    return (double)__uint_as_float((uint32_t)((const uint16_t *)p.emis)[i] << 16);  // bfloat16: upper half of a float
-}
-
-__device__ __forceinline__ int seq_len(const Params &p, int b)
-{
-    int L = p.lengths ? p.lengths[b] : p.T;
-    L = L < 0 ? 0 : L;
-    return L > p.T ? p.T : L;
-}
+using namespace semicrf_impl;
 
 // ---------------------------------------------------------------------------
 // exp(dur), exp(trans) in fp64 and the maxima that bound per-step growth.
@@ -490,13 +367,6 @@ __device__ __forceinline__ double vec_sum(const double *v, int C)
     return m;
 }
 
-__device__ __forceinline__ int safe_exponent(double m)
-{
-    if (!(m > 0.0) || !(m < DBL_MAX)) return 0;
-    int e;
-    (void)frexp(m, &e);
-    return e;
-}
 
 // Rescale the ring when the scan enters scaling block jnew from block jold:
 // every entry of label c is multiplied by 2^(sgn*(n_new-n_old) - e), e being the
@@ -688,72 +558,6 @@ __global__ __launch_bounds__(NT) void k_scan(Params p, int both)
 constexpr int PF = 8;        // prefetch distance of the emission factors, in steps
 constexpr int NH_MAX = 4;    // most helper waves
 constexpr int NKL = 16;      // consecutive durations per helper lane
-
-__host__ __device__ constexpr int pow2_ge8(int x)
-{
-    int r = 8;
-    while (r < x) r <<= 1;
-    return r;
-}
-
-__device__ __forceinline__ void lds_barrier()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
-
-// The tip's end-of-step barrier: no s_waitcnt.  The only LDS write of the step that
-// other waves read (the ring entry) is not read by them before the NEXT barrier.
-__device__ __forceinline__ void tip_step_barrier()
-{
-    asm volatile("s_barrier" ::: "memory");
-}
-
-// orders LDS accesses of one wave (LDS executes a wave's instructions in order)
-__device__ __forceinline__ void lds_wave_fence()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
-}
-
-// v + (v of the lane 32 away), in every lane: rows 2,3 of one copy are swapped with
-// rows 0,1 of the other (a row is 16 lanes), then the copies are added.
-__device__ __forceinline__ double add_across_32(double v)
-{
-    const unsigned lo = (unsigned)__double2loint(v), hi = (unsigned)__double2hiint(v);
-    const auto a = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
-    const auto b = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
-    return __hiloint2double((int)b[0], (int)a[0]) + __hiloint2double((int)b[1], (int)a[1]);
-}
-
-// v + (v of the lane 16 away): odd rows of one copy are swapped with even rows of the other
-__device__ __forceinline__ double add_across_16(double v)
-{
-    const unsigned lo = (unsigned)__double2loint(v), hi = (unsigned)__double2hiint(v);
-    const auto a = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
-    const auto b = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
-    return __hiloint2double((int)b[0], (int)a[0]) + __hiloint2double((int)b[1], (int)a[1]);
-}
-
-// v + (v of the lane 8 away inside a row of 16): DPP row rotate by 8
-__device__ __forceinline__ double add_across_8(double v)
-{
-    const int lo = __double2loint(v), hi = __double2hiint(v);
-    const int lo2 = __builtin_amdgcn_update_dpp(0, lo, 0x128, 0xf, 0xf, false);
-    const int hi2 = __builtin_amdgcn_update_dpp(0, hi, 0x128, 0xf, 0xf, false);
-    return v + __hiloint2double(hi2, lo2);
-}
-
-// sum over the 64/CTP lanes of a wave that share lane % CTP; every lane gets the total
-template <int CTP>
-__device__ __forceinline__ double group_sum(double v)
-{
-    if (CTP <= 8) v = add_across_8(v);
-    if (CTP <= 16) v = add_across_16(v);
-    if (CTP <= 32) v = add_across_32(v);
-    return v;
-}
 
 struct FastGeom {
     int RSLOTS;  // ring slots: both copies plus front padding
@@ -2122,8 +1926,9 @@ __device__ __forceinline__ void spec_task(const Params &p, double *lds_raw, cons
     record(tend, ck2 + (size_t)iend * ckstride, ckY2 + iend);
 }
 
+// rest: only the sequences the lock-step kernel (k_mscan, launched before) leaves out
 template <int CT, int NKW>
-__global__ __launch_bounds__(64) void k_spec(Params p, int both, int warm, int tier)
+__global__ __launch_bounds__(64) void k_spec(Params p, int both, int warm, int tier, int rest)
 {
     extern __shared__ double lds_raw[];
     const int ndir = both ? 2 : 1;
@@ -2131,6 +1936,7 @@ __global__ __launch_bounds__(64) void k_spec(Params p, int both, int warm, int t
     const int task = blockIdx.x / ndir;
     const int b = task / p.N, j = task % p.N;
     if (tier > 0 && p.spec_ok[b * 2 + dir]) return;  // accepted with the shorter warm-up
+    if (rest && p.hdr[b].J >= MS_JMIN) return;
     if (dir == 0) spec_task<CT, NKW, false>(p, lds_raw, b, j, warm);
     else spec_task<CT, NKW, true>(p, lds_raw, b, j, warm);
 }
@@ -3277,6 +3083,7 @@ int make_plan(int B, int T, int K, int C, int ckpt_interval, int want_grad, Plan
     const size_t gr = pl->rows ? 1 : 0;
     sz[i++] = gr * (size_t)pl->nslot * pl->Delta * 2 * c * 8;  // 28 bloc
     sz[i++] = gr * (size_t)pl->nslot * pl->Delta * 8;          // 29 blocY
+    sz[i++] = 1536 * 8;                                        // 30 sink
     size_t off = 0;
     for (int j = 0; j < i; ++j) {
         pl->off[j] = off;
@@ -3318,6 +3125,7 @@ void bind_workspace(Params &p, const Plan &pl, void *ws)
     p.inL = (double *)(w + pl.off[27]);
     p.bloc = (double *)(w + pl.off[28]);
     p.blocY = (double *)(w + pl.off[29]);
+    p.sink = (double *)(w + pl.off[30]);
     p.spec_lr = (double *)(w + pl.off[8]);
     p.spec_err = p.spec_lr + (size_t)p.B * 2 * (pl.N + 1);
     p.spec_ok = (int *)(p.spec_err + (size_t)p.B * 2 * (pl.N + 1));
@@ -3445,8 +3253,14 @@ int launch_spec_k(const Params &p, hipStream_t st, bool both, int warm, int tier
                             (int)lds) != hipSuccess)
         return SEMICRF_ELAUNCH;
     const int ndir = both ? 2 : 1;
+    int rest = 0;
+    if (p.mscan && mscan_applies(p.K, p.C, p.Delta) && (double)p.B * ((double)p.T + 1.0) * (double)p.C < 134217728.0) {
+        const int rc = launch_mscan(p, st, both, warm, tier);
+        if (rc != SEMICRF_OK) return rc;
+        rest = 1;
+    }
     hipLaunchKernelGGL((k_spec<CT, NKW>), dim3(p.B * p.N * ndir), dim3(64), lds, st, p, both ? 1 : 0,
-                       warm, tier);
+                       warm, tier, rest);
     hipLaunchKernelGGL(k_spec_cmp, dim3(p.N, p.B, ndir), dim3(NT), 0, st, p, tier);
     hipLaunchKernelGGL(k_spec_fix, dim3(p.B, 2), dim3(64), 0, st, p, ndir, tier);
     return check_launch();
@@ -3527,6 +3341,7 @@ int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hi
         if (w > 0) warm[0] = w, warm[1] = 4 * w;
     }
     p.spec = p.spec && mode != 0 && spec_applies(p.K, p.C);
+    p.mscan = p.mscan && p.spec;
     p.fuse = p.spec && mode == 2 && (size_t)p.B * pl.N <= (size_t)pl.nslot;  // one slot per task
     // Marginals from the stored rows of both scans: where the plan has the row slots and no
     // boundary-term output is asked for (those come from the interval kernels).
@@ -3918,6 +3733,22 @@ int run_durtrans(Params p, int ckpt_interval, void *workspace, size_t workspace_
     return check_launch();
 }
 
+// Fields every entry point fills the same way.  SEMICRF_EINVAL for flag combinations that make no sense.
+int common_params(Params &p, const float *emis, const int32_t *lengths, const float *dur, int B, int T, int K, int C,
+                  unsigned flags)
+{
+    if ((flags & SEMICRF_EMIS_F16) && (flags & SEMICRF_EMIS_BF16)) return SEMICRF_EINVAL;
+    p.emis = emis;
+    p.lengths = lengths;
+    p.dur = dur;
+    p.B = B; p.T = T; p.K = K; p.C = C;
+    p.center = (flags & SEMICRF_CENTER) ? 1 : 0;
+    p.emis_type = (flags & SEMICRF_EMIS_F16) ? 1 : ((flags & SEMICRF_EMIS_BF16) ? 2 : 0);
+    p.spec = (flags & SEMICRF_SEQUENTIAL_SCAN) ? 0 : 1;
+    p.mscan = (flags & SEMICRF_MATRIX_SCAN) ? 1 : 0;
+    return SEMICRF_OK;
+}
+
 // Device address of this GPU's copy of the static scratch array, looked up once per device with
 // that device current and kept for the life of the process.
 constexpr int STATIC_MAX_DEVICES = 64;
@@ -3984,11 +3815,7 @@ int semicrf_cum_scores(const float *emis, const int32_t *lengths, int B, int T, 
 {
     if (!emis || !cum) return SEMICRF_EINVAL;
     Params p = {};
-    p.emis = emis; p.lengths = lengths;
-    p.B = B; p.T = T; p.K = 1; p.C = C;
-    p.center = (flags & SEMICRF_CENTER) ? 1 : 0;
-    p.emis_type = (flags & SEMICRF_EMIS_F16) ? 1 : ((flags & SEMICRF_EMIS_BF16) ? 2 : 0);
-    if ((flags & SEMICRF_EMIS_F16) && (flags & SEMICRF_EMIS_BF16)) return SEMICRF_EINVAL;
+    if (int rc = common_params(p, emis, lengths, nullptr, B, T, 1, C, flags)) return rc;
     p.cum = cum;
     return run(p, 0, workspace, workspace_bytes, (hipStream_t)stream, 0);
 }
@@ -4000,12 +3827,8 @@ int semicrf_logz_fwd(const float *emis, const int32_t *lengths, const float *tra
 {
     if (!emis || !trans || !dur || !logz) return SEMICRF_EINVAL;
     Params p = {};
-    p.emis = emis; p.lengths = lengths; p.trans = trans; p.dur = dur;
-    p.B = B; p.T = T; p.K = K; p.C = C;
-    p.center = (flags & SEMICRF_CENTER) ? 1 : 0;
-    p.emis_type = (flags & SEMICRF_EMIS_F16) ? 1 : ((flags & SEMICRF_EMIS_BF16) ? 2 : 0);
-    if ((flags & SEMICRF_EMIS_F16) && (flags & SEMICRF_EMIS_BF16)) return SEMICRF_EINVAL;
-    p.spec = (flags & SEMICRF_SEQUENTIAL_SCAN) ? 0 : 1;
+    if (int rc = common_params(p, emis, lengths, dur, B, T, K, C, flags)) return rc;
+    p.trans = trans;
     p.logz = logz;
     return run(p, ckpt_interval, workspace, workspace_bytes, (hipStream_t)stream, 1);
 }
@@ -4019,12 +3842,8 @@ int semicrf_fwd_bwd(const float *emis, const int32_t *lengths, const float *tran
     if (!emis || !trans || !dur || !logz || !grad_emis || !grad_trans || !grad_dur)
         return SEMICRF_EINVAL;
     Params p = {};
-    p.emis = emis; p.lengths = lengths; p.trans = trans; p.dur = dur; p.grad_logz = grad_logz;
-    p.B = B; p.T = T; p.K = K; p.C = C;
-    p.center = (flags & SEMICRF_CENTER) ? 1 : 0;
-    p.emis_type = (flags & SEMICRF_EMIS_F16) ? 1 : ((flags & SEMICRF_EMIS_BF16) ? 2 : 0);
-    if ((flags & SEMICRF_EMIS_F16) && (flags & SEMICRF_EMIS_BF16)) return SEMICRF_EINVAL;
-    p.spec = (flags & SEMICRF_SEQUENTIAL_SCAN) ? 0 : 1;
+    if (int rc = common_params(p, emis, lengths, dur, B, T, K, C, flags)) return rc;
+    p.trans = trans; p.grad_logz = grad_logz;
     p.logz = logz; p.grad_emis = grad_emis; p.grad_trans = grad_trans; p.grad_dur = grad_dur;
     p.pos_marg = pos_marg;
     return run(p, ckpt_interval, workspace, workspace_bytes, (hipStream_t)stream, 2);
@@ -4058,12 +3877,8 @@ int semicrf_fwd_bwd_profiled(const float *emis, const int32_t *lengths, const fl
     if (!emis || !trans || !dur || !logz || !grad_emis || !grad_trans || !grad_dur || !stage_events)
         return SEMICRF_EINVAL;
     Params p = {};
-    p.emis = emis; p.lengths = lengths; p.trans = trans; p.dur = dur; p.grad_logz = grad_logz;
-    p.B = B; p.T = T; p.K = K; p.C = C;
-    p.center = (flags & SEMICRF_CENTER) ? 1 : 0;
-    p.emis_type = (flags & SEMICRF_EMIS_F16) ? 1 : ((flags & SEMICRF_EMIS_BF16) ? 2 : 0);
-    if ((flags & SEMICRF_EMIS_F16) && (flags & SEMICRF_EMIS_BF16)) return SEMICRF_EINVAL;
-    p.spec = (flags & SEMICRF_SEQUENTIAL_SCAN) ? 0 : 1;
+    if (int rc = common_params(p, emis, lengths, dur, B, T, K, C, flags)) return rc;
+    p.trans = trans; p.grad_logz = grad_logz;
     p.logz = logz; p.grad_emis = grad_emis; p.grad_trans = grad_trans; p.grad_dur = grad_dur;
     p.pos_marg = pos_marg;
     StageTimer tm;
@@ -4084,13 +3899,9 @@ int semicrf_logz_fwd_boundary(const float *emis, const int32_t *lengths, const f
 {
     if (!emis || !trans || !dur || !logz) return SEMICRF_EINVAL;
     Params p = {};
-    p.emis = emis; p.lengths = lengths; p.trans = trans; p.dur = dur;
+    if (int rc = common_params(p, emis, lengths, dur, B, T, K, C, flags)) return rc;
+    p.trans = trans;
     p.proj_start = proj_start; p.proj_end = proj_end; p.pi_start = pi_start; p.pi_end = pi_end;
-    p.B = B; p.T = T; p.K = K; p.C = C;
-    p.center = (flags & SEMICRF_CENTER) ? 1 : 0;
-    p.emis_type = (flags & SEMICRF_EMIS_F16) ? 1 : ((flags & SEMICRF_EMIS_BF16) ? 2 : 0);
-    if ((flags & SEMICRF_EMIS_F16) && (flags & SEMICRF_EMIS_BF16)) return SEMICRF_EINVAL;
-    p.spec = (flags & SEMICRF_SEQUENTIAL_SCAN) ? 0 : 1;
     p.logz = logz;
     return run(p, ckpt_interval, workspace, workspace_bytes, (hipStream_t)stream, 1);
 }
@@ -4106,13 +3917,9 @@ int semicrf_fwd_bwd_boundary(const float *emis, const int32_t *lengths, const fl
     if (!emis || !trans || !dur || !logz || !grad_emis || !grad_trans || !grad_dur)
         return SEMICRF_EINVAL;
     Params p = {};
-    p.emis = emis; p.lengths = lengths; p.trans = trans; p.dur = dur; p.grad_logz = grad_logz;
+    if (int rc = common_params(p, emis, lengths, dur, B, T, K, C, flags)) return rc;
+    p.trans = trans; p.grad_logz = grad_logz;
     p.proj_start = proj_start; p.proj_end = proj_end; p.pi_start = pi_start; p.pi_end = pi_end;
-    p.B = B; p.T = T; p.K = K; p.C = C;
-    p.center = (flags & SEMICRF_CENTER) ? 1 : 0;
-    p.emis_type = (flags & SEMICRF_EMIS_F16) ? 1 : ((flags & SEMICRF_EMIS_BF16) ? 2 : 0);
-    if ((flags & SEMICRF_EMIS_F16) && (flags & SEMICRF_EMIS_BF16)) return SEMICRF_EINVAL;
-    p.spec = (flags & SEMICRF_SEQUENTIAL_SCAN) ? 0 : 1;
     p.logz = logz; p.grad_emis = grad_emis; p.grad_trans = grad_trans; p.grad_dur = grad_dur;
     p.pos_marg = pos_marg;
     p.g_proj_start = grad_proj_start; p.g_proj_end = grad_proj_end;
@@ -4150,14 +3957,10 @@ int semicrf_viterbi(const float *emis, const int32_t *lengths, const float *tran
 {
     if (!emis || !trans || !dur || !score || !labels || !starts || !nseg) return SEMICRF_EINVAL;
     Params p = {};
-    p.emis = emis; p.lengths = lengths; p.trans = trans; p.dur = dur;
+    if (int rc = common_params(p, emis, lengths, dur, B, T, K, C, flags)) return rc;
+    p.trans = trans;
     p.proj_start = proj_start; p.proj_end = proj_end; p.pi_start = pi_start; p.pi_end = pi_end;
-    p.B = B; p.T = T; p.K = K; p.C = C;
-    p.center = (flags & SEMICRF_CENTER) ? 1 : 0;
-    p.emis_type = (flags & SEMICRF_EMIS_F16) ? 1 : ((flags & SEMICRF_EMIS_BF16) ? 2 : 0);
-    if ((flags & SEMICRF_EMIS_F16) && (flags & SEMICRF_EMIS_BF16)) return SEMICRF_EINVAL;
     p.vscore = score; p.vlabels = labels; p.vstarts = starts; p.vnseg = nseg;
-    p.spec = (flags & SEMICRF_SEQUENTIAL_SCAN) ? 0 : 1;
     return run_viterbi(p, workspace, workspace_bytes, (hipStream_t)stream);
 }
 
@@ -4192,13 +3995,9 @@ int semicrf_logz_fwd_durtrans(const float *emis, const int32_t *lengths, const f
                               void *stream)
 {
     if (!emis || !trans3 || !dur || !logz) return SEMICRF_EINVAL;
-    if ((flags & SEMICRF_EMIS_F16) && (flags & SEMICRF_EMIS_BF16)) return SEMICRF_EINVAL;
     Params p = {};
-    p.emis = emis; p.lengths = lengths; p.trans3 = trans3; p.dur = dur;
-    p.B = B; p.T = T; p.K = K; p.C = C;
-    p.center = (flags & SEMICRF_CENTER) ? 1 : 0;
-    p.emis_type = (flags & SEMICRF_EMIS_F16) ? 1 : ((flags & SEMICRF_EMIS_BF16) ? 2 : 0);
-    p.spec = (flags & SEMICRF_SEQUENTIAL_SCAN) ? 0 : 1;
+    if (int rc = common_params(p, emis, lengths, dur, B, T, K, C, flags)) return rc;
+    p.trans3 = trans3;
     p.logz = logz;
     return run_durtrans(p, ckpt_interval, workspace, workspace_bytes, (hipStream_t)stream, false);
 }
@@ -4210,13 +4009,9 @@ int semicrf_fwd_bwd_durtrans(const float *emis, const int32_t *lengths, const fl
                              float *pos_marg, void *stream)
 {
     if (!emis || !trans3 || !dur || !logz || !grad_emis || !grad_trans3 || !grad_dur) return SEMICRF_EINVAL;
-    if ((flags & SEMICRF_EMIS_F16) && (flags & SEMICRF_EMIS_BF16)) return SEMICRF_EINVAL;
     Params p = {};
-    p.emis = emis; p.lengths = lengths; p.trans3 = trans3; p.dur = dur; p.grad_logz = grad_logz;
-    p.B = B; p.T = T; p.K = K; p.C = C;
-    p.center = (flags & SEMICRF_CENTER) ? 1 : 0;
-    p.emis_type = (flags & SEMICRF_EMIS_F16) ? 1 : ((flags & SEMICRF_EMIS_BF16) ? 2 : 0);
-    p.spec = (flags & SEMICRF_SEQUENTIAL_SCAN) ? 0 : 1;
+    if (int rc = common_params(p, emis, lengths, dur, B, T, K, C, flags)) return rc;
+    p.trans3 = trans3; p.grad_logz = grad_logz;
     p.logz = logz; p.grad_emis = grad_emis; p.grad_trans3 = grad_trans3; p.grad_dur = grad_dur;
     p.pos_marg = pos_marg;
     return run_durtrans(p, ckpt_interval, workspace, workspace_bytes, (hipStream_t)stream, true);
