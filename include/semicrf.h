@@ -84,6 +84,20 @@ typedef enum {
  * differs.  Off by default: measured slower than the default kernel on MI355X (a lone wave per SIMD issues its
  * per-position bookkeeping too slowly); kept as the measured alternative.  Ignored where the sizes do not allow it. */
 #define SEMICRF_MATRIX_SCAN 16u
+/* flags bits 5, 6: where semicrf_fwd_bwd takes the expected statistics of the "Gradient Formulas" section from.
+ * Default (neither bit): from the stored rows of both scans for K >= 128, from Algorithm 3's per-interval
+ * recurrence below that.  SEMICRF_MARGINALS_ROWS asks for the stored rows whatever K is (the workspace must
+ * have been sized with want_grad = 3), SEMICRF_MARGINALS_INTERVAL for the per-interval recurrence (want_grad = 2
+ * suffices).  Setting both is invalid.  The results agree to the rounding of the outputs. */
+#define SEMICRF_MARGINALS_ROWS 32u
+#define SEMICRF_MARGINALS_INTERVAL 64u
+/* flags bit 7 (semicrf_viterbi only): trace back by pointer doubling over all nodes, the route otherwise taken
+ * only when an interval's nodes do not fit in LDS.  Same back-pointers, same path; for tests of that route. */
+#define SEMICRF_VITERBI_GLOBAL_TRACE 128u
+/* flags bits 16..31: first warm-up length of the chunk-parallel scans, in positions (0 = the default, max(1.5K, 32);
+ * the long second warm-up is four times this).  A length too short for the input costs time, never accuracy:
+ * what does not verify is repaired or rescanned.  Tests use it to force those routes. */
+#define SEMICRF_WARMUP(n) ((unsigned)(n) << 16)
 
 int semicrf_version(void);
 
@@ -96,7 +110,10 @@ const char *semicrf_strerror(int status);
  * [max(8, K/2), sqrt(T*K)] (the upper end is the spacing of Algorithm 1) that minimises
  * the modelled time of the (sequence, interval) tasks, which run in rounds of about one
  * task per SIMD of the chip; roughly ceil(B*T/1024) when the K-deep window is small.
- * want_grad = 0 sizes for semicrf_logz_fwd / semicrf_cum_scores only.
+ * want_grad = 0 sizes for semicrf_logz_fwd / semicrf_cum_scores only; 1 for semicrf_fwd_bwd with the default
+ * choice of marginal route; 2 for semicrf_fwd_bwd with SEMICRF_MARGINALS_INTERVAL (the smallest);
+ * 3 for semicrf_fwd_bwd with SEMICRF_MARGINALS_ROWS (adds the row slots of the backward scan).  A workspace
+ * sized with 3 serves every gradient call, one sized with 1 every call without SEMICRF_MARGINALS_ROWS.
  * `bytes` is a host pointer.
  */
 int semicrf_workspace_bytes(int B, int T, int K, int C, int ckpt_interval, int want_grad,
@@ -148,9 +165,7 @@ int semicrf_logz_fwd(const float *emis, const int32_t *lengths, const float *tra
  * statistics of the "Gradient Formulas" section are formed as position-local products of the
  * two sets of rows instead of by a third recurrence per interval; sequences whose scans were
  * not both accepted take Algorithm 3's per-interval pass.  The results are the same to the
- * rounding of the outputs.  The environment variable SEMICRF_MARGINALS ("rows" / "interval") is a
- * tuning knob that forces one route; it is read by semicrf_workspace_bytes too (the rows
- * need workspace), so it must not change between sizing the workspace and the call.
+ * rounding of the outputs.  SEMICRF_MARGINALS_ROWS / SEMICRF_MARGINALS_INTERVAL select one route.
  */
 int semicrf_fwd_bwd(const float *emis, const int32_t *lengths, const float *trans,
                     const float *dur, const float *grad_logz, int B, int T, int K, int C,
@@ -305,7 +320,8 @@ int semicrf_entropies(const float *pos_marg, const float *bdy_post, const int32_
  * `stream`: stage_events[0] before the first kernel and stage_events[1..4] after
  * each of the four stages
  *   1 prefix sums (Eq. 1-2 kernels),
- *   2 the two sequential scans (Algorithm 1 and the beta recurrence of Algorithm 3),
+ *   2 the two scans (Algorithm 1 and the beta recurrence of Algorithm 3; chunk-parallel with verification,
+ *     repair and the sequential fallback),
  *   3 per-interval recompute + marginals (Algorithm 3 body),
  *   4 fixed-order reductions of the gradient formulas.
  * stage_events is a HOST array of 5 hipEvent_t handles created by the caller
@@ -325,7 +341,9 @@ int semicrf_fwd_bwd_profiled(const float *emis, const int32_t *lengths, const fl
  * this workspace with these sizes (same B, T, K, C, ckpt_interval and want_grad: they
  * locate the fields in the workspace).  Enqueued on `stream` after that call.
  *   accepted [B,2] int32 device, or NULL: [b,0] forward scan (Algorithm 1), [b,1] backward
- *             scan (Algorithm 3): 1 = the chunk-parallel result was verified and used,
+ *             scan (Algorithm 3): > 0 = the chunk-parallel result was verified and used:
+ *             1 at the first attempt, 2 after the intervals whose start had disagreed were
+ *             rerun from the state their neighbour reached, 3 after the long warm-up;
  *             0 = the sequential scan computed it (flag SEMICRF_SEQUENTIAL_SCAN, sizes the
  *             chunk-parallel kernels do not cover, a direction that call did not run, or
  *             a boundary that did not agree).

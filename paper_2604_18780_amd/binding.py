@@ -27,6 +27,19 @@ SEMICRF_SEQUENTIAL_SCAN = 2
 SEMICRF_EMIS_F16 = 4
 SEMICRF_EMIS_BF16 = 8
 SEMICRF_MATRIX_SCAN = 16
+SEMICRF_MARGINALS_ROWS = 32
+SEMICRF_MARGINALS_INTERVAL = 64
+SEMICRF_VITERBI_GLOBAL_TRACE = 128
+
+
+def SEMICRF_WARMUP(n: int) -> int:
+    """flags bits 16..31: first warm-up length of the chunk-parallel scans."""
+    return int(n) << 16
+
+
+def grad_workspace_kind(flags: int) -> int:
+    """The want_grad value of semicrf_workspace_bytes that fits a gradient call with these flags."""
+    return 3 if flags & SEMICRF_MARGINALS_ROWS else (2 if flags & SEMICRF_MARGINALS_INTERVAL else 1)
 _lib = None
 
 
@@ -105,7 +118,7 @@ def semicrf_strerror(status: int) -> str:
 
 def semicrf_workspace_bytes(B, T, K, C, ckpt_interval=0, want_grad=True) -> int:
     out = ctypes.c_size_t(0)
-    _check(load().semicrf_workspace_bytes(B, T, K, C, ckpt_interval, int(bool(want_grad)),
+    _check(load().semicrf_workspace_bytes(B, T, K, C, ckpt_interval, int(want_grad),
                                           ctypes.byref(out)))
     return out.value
 
@@ -179,7 +192,7 @@ def semicrf_fwd_bwd(emis, lengths, trans, dur, grad_logz=None, ckpt_interval=0,
     K = dur.shape[0]
     dev = emis.device
     if workspace is None:
-        workspace = alloc_workspace(B, T, K, C, ckpt_interval, True, dev)
+        workspace = alloc_workspace(B, T, K, C, ckpt_interval, grad_workspace_kind(flags), dev)
     if out is None:
         logz = torch.empty(B, dtype=torch.float32, device=dev)
         g_e = torch.empty((B, T, C), dtype=torch.float32, device=dev)
@@ -240,7 +253,7 @@ def semicrf_fwd_bwd_boundary(emis, lengths, trans, dur, grad_logz=None, proj_sta
     K = dur.shape[0]
     dev = emis.device
     if workspace is None:
-        workspace = alloc_workspace(B, T, K, C, ckpt_interval, True, dev)
+        workspace = alloc_workspace(B, T, K, C, ckpt_interval, grad_workspace_kind(flags), dev)
     f32 = torch.float32
     new = lambda *shape: torch.empty(shape, dtype=f32, device=dev)
     o = dict(logz=new(B), grad_emis=new(B, T, C), grad_trans=new(C, C), grad_dur=new(K, C), pos_marg=new(B, T, C),
@@ -419,7 +432,7 @@ def semicrf_fwd_bwd_profiled(emis, lengths, trans, dur, events, grad_logz=None, 
     K = dur.shape[0]
     dev = emis.device
     if workspace is None:
-        workspace = alloc_workspace(B, T, K, C, ckpt_interval, True, dev)
+        workspace = alloc_workspace(B, T, K, C, ckpt_interval, grad_workspace_kind(flags), dev)
     if out is None:
         out = (torch.empty(B, dtype=torch.float32, device=dev),
                torch.empty((B, T, C), dtype=torch.float32, device=dev),

@@ -88,6 +88,9 @@ struct Params {
     int spec;           // chunk-parallel scan enabled for this call
     int mscan;          // its tasks may run sixteen at a time in lock step on the matrix cores
     double *sink;       // [1536] target of stores that must be issued but whose value nobody wants
+    int warm0;          // first warm-up length of the chunk-parallel scans asked for by the caller (0 = default)
+    int marg_route;     // 0 automatic, 1 marginals from the stored rows of both scans, 2 per-interval recurrence
+    int vit_global;     // Viterbi trace-back by pointer doubling over all nodes (test of the fallback route)
     int fuse;           // its forward tasks also store the interval stage's forward rows (one slot per task)
     double *aloc;       // [nslot][Delta][2C]
     double *alocY;      // [nslot][Delta]

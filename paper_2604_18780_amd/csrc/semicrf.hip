@@ -1711,9 +1711,12 @@ __global__ __launch_bounds__(64 * interval_waves(CT, NKW)) void k_interval_wave(
 constexpr double SPEC_TOL = 1e-10;
 
 // One scan task of the chunk-parallel scan, one wave (window and time blocking as above).
+// repair: the task restarts from the state its neighbour in scan order REACHED at their common boundary (no
+// warm-up, exact), but only when that boundary disagreed and the neighbour itself started from a verified or
+// exact state; every other task returns at once and keeps what it has.
 template <int CT, int NKW, bool BWD>
 __device__ __forceinline__ void spec_task(const Params &p, double *lds_raw, const int b, const int j,
-                                          const int warm)
+                                          const int warm, const bool repair)
 {
     using G = WaveWin<CT, NKW>;
     constexpr int CTP = G::CTP, RS = G::RS, NK = G::NK, KW = G::KW, M = G::M, ROWS = G::ROWS;
@@ -1755,14 +1758,36 @@ __device__ __forceinline__ void spec_task(const Params &p, double *lds_raw, cons
     }
     const double2 *ys = (const double2 *)__builtin_assume_aligned(yv + hh * HC, 16);
 
+    if (repair) {
+        const int nint = (L + Delta - 1) / Delta;
+        const size_t so = ((size_t)b * 2 + (BWD ? 1 : 0)) * (N + 1);
+        const int bs = BWD ? j + 1 : j;        // boundary this task starts from
+        const int bp = BWD ? j + 2 : j - 1;    // boundary its neighbour in scan order started from
+        if (bs < 1 || bs > nint - 1) return;   // the first task in scan order starts from the exact state
+        if (p.spec_err[so + bs] <= SPEC_TOL) return;  // agreed: nothing to repair here
+        const bool nb_exact = BWD ? bp >= nint : bp <= 0;
+        if (!nb_exact && !(p.spec_err[so + bp] <= SPEC_TOL)) return;  // the neighbour is wrong itself: a later attempt
+    }
     // ---- start: the state of a sequence that begins (forward) / ends (backward) at s0
-    const int s0 = BWD ? min(hi + warm, L) : max(lo - warm, 0);
+    const int s0 = repair ? (BWD ? hi : lo) : (BWD ? min(hi + warm, L) : max(lo - warm, 0));
     for (int i = lane; i < RTOT; i += 64) ring[i] = 0.0;
     if (lane < CTP) yv[lane] = 0.0;
     lds_wave_fence();
     int r = BWD ? M : KW - 1;  // row of the newest message
     double Y = 0.0;
-    {
+    if (repair) {
+        // the reached state at the boundary: K-deep window in slot order, message vector, scale
+        const int bs = BWD ? j + 1 : j;
+        const double *src = (BWD ? p.ckB2 : p.ckA2) + ((size_t)b * (N + 1) + bs) * ((size_t)KC + C);
+        const int tm = s0 % K;
+        for (int i = lane; i < KC; i += 64) {
+            const int sl = i / C, col = i % C;
+            const int d = G::template slot_dist<BWD>(sl, tm, K);
+            ring[(BWD ? r + d : r - d) * RS + col] = src[i];
+        }
+        if (lane < C) yv[lane] = src[KC + lane];
+        Y = ((BWD ? p.ckYB2 : p.ckYA2) + (size_t)b * (N + 1))[bs];
+    } else {
         double q;
         if (!BWD) {
             double z = 0.0;
@@ -1935,10 +1960,11 @@ __global__ __launch_bounds__(64) void k_spec(Params p, int both, int warm, int t
     const int dir = blockIdx.x % ndir;
     const int task = blockIdx.x / ndir;
     const int b = task / p.N, j = task % p.N;
-    if (tier > 0 && p.spec_ok[b * 2 + dir]) return;  // accepted with the shorter warm-up
+    if (tier > 0 && p.spec_ok[b * 2 + dir]) return;  // accepted by an earlier attempt
     if (rest && p.hdr[b].J >= MS_JMIN) return;
-    if (dir == 0) spec_task<CT, NKW, false>(p, lds_raw, b, j, warm);
-    else spec_task<CT, NKW, true>(p, lds_raw, b, j, warm);
+    const bool repair = warm == 0;  // the attempt that restarts single intervals from reached states
+    if (dir == 0) spec_task<CT, NKW, false>(p, lds_raw, b, j, warm, repair);
+    else spec_task<CT, NKW, true>(p, lds_raw, b, j, warm, repair);
 }
 
 // One workgroup per (chunk boundary j, sequence, direction): compare the state chunk j-1
@@ -1992,7 +2018,7 @@ __global__ __launch_bounds__(NT) void k_spec_cmp(Params p, int tier)
 // Accept or reject each (sequence, direction); chain the scale factors.  grid (B, 2), one
 // wave: lane l owns a contiguous run of boundaries in scan order, the running log2 factor
 // is a fixed-order prefix sum (per lane, then across lanes).
-__global__ __launch_bounds__(64) void k_spec_fix(Params p, int ndir, int tier)
+__global__ __launch_bounds__(64) void k_spec_fix(Params p, int ndir, int tier, int code)
 {
     const int b = blockIdx.x, dir = blockIdx.y, lane = threadIdx.x;
     if (tier > 0 && p.spec_ok[b * 2 + dir]) return;
@@ -2025,42 +2051,41 @@ __global__ __launch_bounds__(64) void k_spec_fix(Params p, int ndir, int tier)
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) worst = fmax(worst, __shfl_xor(worst, off));
     const double total = __shfl(inc, 63);
-    double *ckY = (dir ? p.ckYB : p.ckYA) + (size_t)b * (N + 1);
-    double acc = inc - s;  // log2 of the factor between the true state and the warm-up state
-    for (int i = i0; i < i1; ++i) {
-        acc += p.spec_lr[so + jof(i)];
-        ckY[jof(i)] += acc;
-    }
-    if (dir == 0 && nint > 0) {
-        // a_L(c) / Z: mass of the segments that end at L with label c (the sequential scan
-        // overwrites it if this scan is rejected)
-        const double *e = p.ckA2 + ((size_t)b * (N + 1) + nint) * ((size_t)KC + C);
-        const double v = lane < C ? e[KC + lane] : 0.0;
-        double sum = v;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) sum += __shfl_xor(sum, off);
-        if (lane < C) p.inL[(size_t)b * C + lane] = v / sum;
-    }
-    if (lane != 0) return;
+    // accepted or not (the same in every lane): every boundary within the bound, and a finite logZ
     bool ok = worst <= SPEC_TOL;
-    p.spec_err[so] = worst;  // entry 0 is no boundary: it carries the report value
+    double lz = 0.0, sumL = 1.0, vL = 0.0;
     if (dir == 0) {
-        double lz;
         if (nint == 0) {
             lz = log((double)C);
         } else {
+            // a_L(c) / Z: mass of the segments that end at L with label c
             const double *e = p.ckA2 + ((size_t)b * (N + 1) + nint) * ((size_t)KC + C);
-            double sum = 0.0;
-            for (int i = 0; i < C; ++i) sum += e[KC + i];
-            lz = (p.ckYA2[(size_t)b * (N + 1) + nint] + total) * LN2 + log(sum);
-            ok = ok && sum > 0.0 && lz == lz;
-        }
-        if (ok) {
-            p.hdr[b].logZ = lz;
-            p.logz[b] = (float)lz;
+            vL = lane < C ? e[KC + lane] : 0.0;
+            sumL = vL;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) sumL += __shfl_xor(sumL, off);
+            lz = (p.ckYA2[(size_t)b * (N + 1) + nint] + total) * LN2 + log(sumL);
+            ok = ok && sumL > 0.0 && lz == lz;
         }
     }
-    p.spec_ok[b * 2 + dir] = ok ? 1 : 0;
+    if (ok) {
+        // Chain the scale factors into the checkpoint scales.  Only on acceptance: a later attempt that rewrites
+        // some of the checkpoints must find the others as their tasks left them.
+        double *ckY = (dir ? p.ckYB : p.ckYA) + (size_t)b * (N + 1);
+        double acc = inc - s;  // log2 of the factor between the true state and the warm-up state
+        for (int i = i0; i < i1; ++i) {
+            acc += p.spec_lr[so + jof(i)];
+            ckY[jof(i)] += acc;
+        }
+        if (dir == 0 && nint > 0 && lane < C) p.inL[(size_t)b * C + lane] = vL / sumL;
+    }
+    if (lane != 0) return;
+    p.spec_err[so] = worst;  // entry 0 is no boundary: it carries the report value
+    if (dir == 0 && ok) {
+        p.hdr[b].logZ = lz;
+        p.logz[b] = (float)lz;
+    }
+    p.spec_ok[b * 2 + dir] = ok ? code : 0;  // which attempt verified it (1 first, 2 after repairs, 3 long warm-up)
 }
 
 // The chunk-parallel scan was not attempted: say so in the report fields.
@@ -3015,7 +3040,8 @@ struct Plan {
     size_t off[32];
 };
 
-// want_grad: 0 forward only, 1 gradients, 2 gradients of a caller that never takes the stored-row marginals
+// want_grad: 0 forward only, 1 gradients (stored-row marginals where they pay: K >= 128), 2 gradients of a caller
+// that never takes the stored-row marginals, 3 gradients with the row slots of the stored-row marginals planned
 int make_plan(int B, int T, int K, int C, int ckpt_interval, int want_grad, Plan *pl)
 {
     if (B < 1 || T < 1 || K < 1 || C < 1 || ckpt_interval < 0) return SEMICRF_EINVAL;
@@ -3073,12 +3099,8 @@ int make_plan(int B, int T, int K, int C, int ckpt_interval, int want_grad, Plan
     const size_t mg_vr = (size_t)MG_TG + MG_KS * mg_nsl + 3;
     pl->lds_mg_dur = (MG_TG * c + mg_vr * (c | 3) + MG_TG + 2 * mg_vr + 2 * (size_t)pl->Delta + k) * sizeof(double);
     pl->lds_mg_te = ((size_t)3 * MG_TE * c + pl->Delta) * sizeof(double);
-    bool rows = K >= 128;
-    if (const char *e = getenv("SEMICRF_MARGINALS")) {  // tuning knob: "interval" / "rows" force one route
-        if (e[0] == 'i') rows = false;
-        if (e[0] == 'r') rows = true;
-    }
-    pl->rows = rows && want_grad == 1 && spec_applies(K, C) && ntask <= (size_t)pl->nslot && c * mg_nsl <= 1024 &&
+    const bool rows = want_grad == 3 || (want_grad == 1 && K >= 128);
+    pl->rows = rows && spec_applies(K, C) && ntask <= (size_t)pl->nslot && c * mg_nsl <= 1024 &&
                pl->lds_mg_dur <= LDS_LIMIT && pl->lds_mg_te <= LDS_LIMIT;
     const size_t gr = pl->rows ? 1 : 0;
     sz[i++] = gr * (size_t)pl->nslot * pl->Delta * 2 * c * 8;  // 28 bloc
@@ -3254,7 +3276,7 @@ int launch_spec_k(const Params &p, hipStream_t st, bool both, int warm, int tier
         return SEMICRF_ELAUNCH;
     const int ndir = both ? 2 : 1;
     int rest = 0;
-    if (p.mscan && mscan_applies(p.K, p.C, p.Delta) && (double)p.B * ((double)p.T + 1.0) * (double)p.C < 134217728.0) {
+    if (warm > 0 && p.mscan && mscan_applies(p.K, p.C, p.Delta) && (double)p.B * ((double)p.T + 1.0) * (double)p.C < 134217728.0) {
         const int rc = launch_mscan(p, st, both, warm, tier);
         if (rc != SEMICRF_OK) return rc;
         rest = 1;
@@ -3262,7 +3284,7 @@ int launch_spec_k(const Params &p, hipStream_t st, bool both, int warm, int tier
     hipLaunchKernelGGL((k_spec<CT, NKW>), dim3(p.B * p.N * ndir), dim3(64), lds, st, p, both ? 1 : 0,
                        warm, tier, rest);
     hipLaunchKernelGGL(k_spec_cmp, dim3(p.N, p.B, ndir), dim3(NT), 0, st, p, tier);
-    hipLaunchKernelGGL(k_spec_fix, dim3(p.B, 2), dim3(64), 0, st, p, ndir, tier);
+    hipLaunchKernelGGL(k_spec_fix, dim3(p.B, 2), dim3(64), 0, st, p, ndir, tier, tier == 0 ? 1 : (warm == 0 ? 2 : 3));
     return check_launch();
 }
 
@@ -3323,7 +3345,7 @@ int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hi
     StageTimer none;
     StageTimer &T = tm ? *tm : none;
     Plan pl;
-    int rc = make_plan(p.B, p.T, p.K, p.C, ckpt_interval, mode == 2, &pl);
+    int rc = make_plan(p.B, p.T, p.K, p.C, ckpt_interval, mode != 2 ? 0 : (p.marg_route == 1 ? 3 : (p.marg_route == 2 ? 2 : 1)), &pl);
     if (rc != SEMICRF_OK) return rc;
     if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < pl.total)
         return SEMICRF_EWORKSPACE;
@@ -3336,10 +3358,7 @@ int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hi
     // warm-up lengths of the chunk-parallel scan: one and a half maximal segment lengths first,
     // eight for the (sequence, direction) pairs that fails for, the sequential scan for the rest
     int warm[2] = {sum_warmup(p.K), 8 * p.K < 64 ? 64 : 8 * p.K};
-    if (const char *e = getenv("SEMICRF_WARMUP")) {  // tuning knob: first warm-up length
-        const int w = atoi(e);
-        if (w > 0) warm[0] = w, warm[1] = 4 * w;
-    }
+    if (p.warm0 > 0) warm[0] = p.warm0, warm[1] = 4 * p.warm0;  // the caller's first warm-up length (flags bits 16..31)
     p.spec = p.spec && mode != 0 && spec_applies(p.K, p.C);
     p.mscan = p.mscan && p.spec;
     p.fuse = p.spec && mode == 2 && (size_t)p.B * pl.N <= (size_t)pl.nslot;  // one slot per task
@@ -3353,8 +3372,13 @@ int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hi
     T.mark();
     if (rc != SEMICRF_OK || mode == 0) return rc;
     if (p.spec) {
-        for (int tier = 0; tier < 2; ++tier) {
-            rc = launch_spec(p, st, mode == 2, warm[tier], tier);
+        // Every interval after a short warm-up; then, for what did not verify, the intervals whose start disagreed
+        // restart from the state their neighbour reached (exact; warm-up 0 selects that; each such attempt mends
+        // the first of a run of adjacent disagreeing boundaries, so there are two); then everything that is still
+        // open once more after a long warm-up.  The sequential scan takes the rest.
+        const int attempt[4] = {warm[0], 0, 0, warm[1]};
+        for (int tier = 0; tier < 4; ++tier) {
+            rc = launch_spec(p, st, mode == 2, attempt[tier], tier);
             if (rc != SEMICRF_OK) return rc;
         }
     } else {
@@ -3430,10 +3454,7 @@ int launch_viterbi_k(const Params &p, hipStream_t st)
     if (p.spec) {
         // chunk-parallel scan with two warm-up lengths, as for the sum recurrences
         int warm[2] = {2 * p.K < 32 ? 32 : 2 * p.K, 8 * p.K < 64 ? 64 : 8 * p.K};
-        if (const char *e = getenv("SEMICRF_VITERBI_WARMUP")) {  // tuning knob: first warm-up length
-            const int w = atoi(e);
-            if (w > 0) warm[0] = w, warm[1] = 4 * w;
-        }
+        if (p.warm0 > 0) warm[0] = p.warm0, warm[1] = 4 * p.warm0;  // the caller's first warm-up length
         for (int tier = 0; tier < 2; ++tier) {
             hipLaunchKernelGGL((k_vit_spec<CT, NKW>), dim3(p.B * p.N), dim3(64), lds, st, p, warm[tier], tier);
             hipLaunchKernelGGL(k_vit_cmp, dim3(p.N, p.B), dim3(64), 0, st, p, tier);
@@ -3466,6 +3487,7 @@ int run_viterbi(Params p, void *workspace, size_t workspace_bytes, hipStream_t s
     if (rc != SEMICRF_OK) return rc;
     if (p.C > 64 || !spec_applies(p.K, p.C)) return SEMICRF_EUNSUPPORTED;
     if (((size_t)p.T + 1) * p.C >= ((size_t)1 << 31)) return SEMICRF_EUNSUPPORTED;  // node ids are 32-bit
+    if (2 * (size_t)(p.K + VBP_TILE) * p.C * sizeof(double) > LDS_LIMIT) return SEMICRF_EUNSUPPORTED;  // back-pointer tiles
     const VitLayout vl = viterbi_layout(p.B, p.T, p.C);
     const size_t total = pl.total + vl.total;
     if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < total) return SEMICRF_EWORKSPACE;
@@ -3494,16 +3516,14 @@ int run_viterbi(Params p, void *workspace, size_t workspace_bytes, hipStream_t s
     else rc = launch_viterbi_ct<64>(p, st);
     if (rc != SEMICRF_OK) return rc;
     {
-        const size_t lds = 2 * (size_t)(p.K + VBP_TILE) * p.C * sizeof(double);
-        if (lds > LDS_LIMIT) return SEMICRF_EUNSUPPORTED;
+        const size_t lds = 2 * (size_t)(p.K + VBP_TILE) * p.C * sizeof(double);  // checked before the first launch
         if (hipFuncSetAttribute((const void *)k_vit_bp, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) !=
             hipSuccess)
             return SEMICRF_ELAUNCH;
         hipLaunchKernelGGL(k_vit_bp, dim3(p.T / VBP_TILE + 1, p.B), dim3(NT), lds, st, p);
     }
     const size_t lds_iv = (size_t)p.Delta * p.C * 5 + 16;  // parents (int) and path marks (byte) of one interval
-    const char *force = getenv("SEMICRF_VITERBI_TRACE");    // test knob: "global" = doubling over all nodes
-    if (lds_iv <= LDS_LIMIT && !(force && force[0] == 'g')) {
+    if (lds_iv <= LDS_LIMIT && !p.vit_global) {
         // trace-back by interval: local pointer jumping in LDS, doubling over the window nodes only
         if (hipFuncSetAttribute((const void *)k_vit_local, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)lds_iv) != hipSuccess ||
@@ -3709,7 +3729,7 @@ int run_durtrans(Params p, int ckpt_interval, void *workspace, size_t workspace_
                 if (rc != SEMICRF_OK) return rc;
             }
             hipLaunchKernelGGL(k_spec_cmp, dim3(p.N, p.B, ndir), dim3(NT), 0, st, p, tier);
-            hipLaunchKernelGGL(k_spec_fix, dim3(p.B, 2), dim3(64), 0, st, p, ndir, tier);
+            hipLaunchKernelGGL(k_spec_fix, dim3(p.B, 2), dim3(64), 0, st, p, ndir, tier, tier == 0 ? 1 : 3);
         }
     } else {
         hipLaunchKernelGGL(k_spec_clear, dim3((2 * p.B + 63) / 64), dim3(64), 0, st, p);
@@ -3746,6 +3766,10 @@ int common_params(Params &p, const float *emis, const int32_t *lengths, const fl
     p.emis_type = (flags & SEMICRF_EMIS_F16) ? 1 : ((flags & SEMICRF_EMIS_BF16) ? 2 : 0);
     p.spec = (flags & SEMICRF_SEQUENTIAL_SCAN) ? 0 : 1;
     p.mscan = (flags & SEMICRF_MATRIX_SCAN) ? 1 : 0;
+    if ((flags & SEMICRF_MARGINALS_ROWS) && (flags & SEMICRF_MARGINALS_INTERVAL)) return SEMICRF_EINVAL;
+    p.marg_route = (flags & SEMICRF_MARGINALS_ROWS) ? 1 : ((flags & SEMICRF_MARGINALS_INTERVAL) ? 2 : 0);
+    p.vit_global = (flags & SEMICRF_VITERBI_GLOBAL_TRACE) ? 1 : 0;
+    p.warm0 = (int)(flags >> 16);
     return SEMICRF_OK;
 }
 
@@ -4022,7 +4046,8 @@ int semicrf_scan_report(const void *workspace, size_t workspace_bytes, int B, in
                         void *stream)
 {
     Plan pl;
-    int rc = make_plan(B, T, K, C, ckpt_interval, want_grad, &pl);
+    // the report fields sit in front of everything that differs between the gradient plans: the smallest one locates them
+    int rc = make_plan(B, T, K, C, ckpt_interval, want_grad ? 2 : 0, &pl);
     if (rc != SEMICRF_OK) return rc;
     if (!accepted && !mismatch) return SEMICRF_EINVAL;
     if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < pl.total)
