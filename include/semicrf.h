@@ -91,6 +91,15 @@ typedef enum {
  * suffices).  Setting both is invalid.  The results agree to the rounding of the outputs. */
 #define SEMICRF_MARGINALS_ROWS 32u
 #define SEMICRF_MARGINALS_INTERVAL 64u
+/* flags bit 8 (semicrf_logz_fwd, semicrf_fwd_bwd and their _boundary / _profiled / _static forms): the
+ * low-memory plan.  With ckpt_interval = 0 the interval is the spacing of Algorithm 1, ceil(sqrt(T*K)) rounded
+ * up to a multiple of 8, instead of the one that fills the chip, and the interval stage keeps 8 row buffers of
+ * ckpt_interval positions per sequence instead of one per interval: it recomputes each interval's forward rows
+ * from the checkpoint (the body of Algorithm 3) instead of taking them from the forward scan.  Everything
+ * beyond the O(T*C) prefix arrays then grows like sqrt(T*K)*C per sequence: the paper's memory bound.  The
+ * results are the same up to rounding; the call is several times slower.  The workspace must have been sized
+ * with want_grad + 8 (8 forward only, 9 gradients); not combinable with SEMICRF_MARGINALS_ROWS. */
+#define SEMICRF_LOW_MEMORY 256u
 /* flags bit 7 (semicrf_viterbi only): trace back by pointer doubling over all nodes, the route otherwise taken
  * only when an interval's nodes do not fit in LDS.  Same back-pointers, same path; for tests of that route. */
 #define SEMICRF_VITERBI_GLOBAL_TRACE 128u
@@ -114,7 +123,8 @@ const char *semicrf_strerror(int status);
  * choice of marginal route; 2 for semicrf_fwd_bwd with SEMICRF_MARGINALS_INTERVAL (the smallest);
  * 3 for semicrf_fwd_bwd with SEMICRF_MARGINALS_ROWS (adds the row slots of the backward scan).  A workspace
  * sized with 3 serves every gradient call, one sized with 1 every call without SEMICRF_MARGINALS_ROWS.
- * `bytes` is a host pointer.
+ * Add 8 for calls with SEMICRF_LOW_MEMORY (8 forward only, 9 or 10 gradients): another layout, for those
+ * calls only.  `bytes` is a host pointer.
  */
 int semicrf_workspace_bytes(int B, int T, int K, int C, int ckpt_interval, int want_grad,
                             size_t *bytes);
@@ -123,8 +133,10 @@ int semicrf_workspace_bytes(int B, int T, int K, int C, int ckpt_interval, int w
  * Host only, pure.  The checkpoint interval (the Delta of Algorithm 1) the calls below
  * use for these sizes: ckpt_interval itself (clamped to T) when positive, else the
  * automatic choice described above.  `interval` is a host pointer.
+ * semicrf_ckpt_interval_low_memory: the same for calls with SEMICRF_LOW_MEMORY.
  */
 int semicrf_ckpt_interval(int B, int T, int K, int C, int ckpt_interval, int *interval);
+int semicrf_ckpt_interval_low_memory(int B, int T, int K, int C, int ckpt_interval, int *interval);
 
 /*
  * Eq. 1 and Eq. 2: per-sequence baseline and centred prefix sums.
@@ -354,6 +366,22 @@ int semicrf_fwd_bwd_profiled(const float *emis, const int32_t *lengths, const fl
 int semicrf_scan_report(const void *workspace, size_t workspace_bytes, int B, int T, int K, int C,
                         int ckpt_interval, int want_grad, int32_t *accepted, double *mismatch,
                         void *stream);
+
+/*
+ * Per-sequence results the LAST semicrf_logz_fwd / semicrf_fwd_bwd call (or their _boundary forms) left in
+ * this workspace; sizes and want_grad as for semicrf_scan_report.  Enqueued on `stream` after that call.
+ *   range_exceeded [B] int32 device, or NULL: 1 if the scores of sequence b exceed the range the scaled
+ *             recurrences are built for: with r = max|f - nu| + max(0, max dur) + max(0, max trans) + ln(K*C)
+ *             (or the same with the minima; boundary terms added), one position may change the messages by
+ *             e^r, and r must stay below 300 nats so that a product of two scaled factors stays inside the
+ *             double range (Eq. 2 is what keeps f - nu small).  logZ and the gradients of such a sequence may
+ *             be inf or NaN; nothing else is affected.  0 otherwise.
+ *   logz64 [B] double device, or NULL: logZ_b as the forward scan computed it, before rounding to float
+ *             (at T = 100 000 a float holds logZ to about 0.03 absolute).
+ * At least one of the two must be given.
+ */
+int semicrf_seq_report(const void *workspace, size_t workspace_bytes, int B, int T, int K, int C,
+                       int ckpt_interval, int want_grad, int32_t *range_exceeded, double *logz64, void *stream);
 
 #ifdef __cplusplus
 }

@@ -20,7 +20,8 @@ EXPORTS = ("semicrf_version", "semicrf_strerror", "semicrf_workspace_bytes",
            "semicrf_scan_report", "semicrf_ckpt_interval", "semicrf_logz_fwd_boundary",
            "semicrf_fwd_bwd_boundary", "semicrf_entropies", "semicrf_viterbi_workspace_bytes",
            "semicrf_viterbi", "semicrf_durtrans_workspace_bytes", "semicrf_durtrans_ckpt_interval", "semicrf_logz_fwd_durtrans",
-           "semicrf_fwd_bwd_durtrans", "semicrf_fwd_bwd_static")
+           "semicrf_fwd_bwd_durtrans", "semicrf_fwd_bwd_static", "semicrf_seq_report",
+           "semicrf_ckpt_interval_low_memory")
 SEMICRF_STATIC_WORKSPACE_BYTES = 64 << 20
 SEMICRF_CENTER = 1
 SEMICRF_SEQUENTIAL_SCAN = 2
@@ -30,6 +31,8 @@ SEMICRF_MATRIX_SCAN = 16
 SEMICRF_MARGINALS_ROWS = 32
 SEMICRF_MARGINALS_INTERVAL = 64
 SEMICRF_VITERBI_GLOBAL_TRACE = 128
+SEMICRF_LOW_MEMORY = 256
+PLAN_LOW_MEMORY = 8   # added to want_grad for the workspace of SEMICRF_LOW_MEMORY calls
 
 
 def SEMICRF_WARMUP(n: int) -> int:
@@ -39,7 +42,14 @@ def SEMICRF_WARMUP(n: int) -> int:
 
 def grad_workspace_kind(flags: int) -> int:
     """The want_grad value of semicrf_workspace_bytes that fits a gradient call with these flags."""
-    return 3 if flags & SEMICRF_MARGINALS_ROWS else (2 if flags & SEMICRF_MARGINALS_INTERVAL else 1)
+    kind = 3 if flags & SEMICRF_MARGINALS_ROWS else (2 if flags & SEMICRF_MARGINALS_INTERVAL else 1)
+    return kind | (PLAN_LOW_MEMORY if flags & SEMICRF_LOW_MEMORY else 0)
+
+
+def fwd_workspace_kind(flags: int) -> int:
+    """The want_grad value of semicrf_workspace_bytes that fits a forward-only call with these flags."""
+    return PLAN_LOW_MEMORY if flags & SEMICRF_LOW_MEMORY else 0
+
 _lib = None
 
 
@@ -99,6 +109,10 @@ def load():
     lib.semicrf_fwd_bwd_durtrans.argtypes = lib.semicrf_fwd_bwd.argtypes
     lib.semicrf_scan_report.restype = ci
     lib.semicrf_scan_report.argtypes = [vp, sz, ci, ci, ci, ci, ci, ci, vp, vp, vp]
+    lib.semicrf_seq_report.restype = ci
+    lib.semicrf_seq_report.argtypes = [vp, sz, ci, ci, ci, ci, ci, ci, vp, vp, vp]
+    lib.semicrf_ckpt_interval_low_memory.restype = ci
+    lib.semicrf_ckpt_interval_low_memory.argtypes = [ci, ci, ci, ci, ci, ctypes.POINTER(ci)]
     _lib = lib
     return lib
 
@@ -121,6 +135,12 @@ def semicrf_workspace_bytes(B, T, K, C, ckpt_interval=0, want_grad=True) -> int:
     _check(load().semicrf_workspace_bytes(B, T, K, C, ckpt_interval, int(want_grad),
                                           ctypes.byref(out)))
     return out.value
+
+
+def semicrf_ckpt_interval_low_memory(B, T, K, C, ckpt_interval=0) -> int:
+    d = ctypes.c_int(0)
+    _check(load().semicrf_ckpt_interval_low_memory(B, T, K, C, ckpt_interval, ctypes.byref(d)))
+    return d.value
 
 
 def semicrf_ckpt_interval(B, T, K, C, ckpt_interval=0) -> int:
@@ -173,7 +193,7 @@ def semicrf_logz_fwd(emis, lengths, trans, dur, ckpt_interval=0, flags=SEMICRF_C
     B, T, C = emis.shape
     K = dur.shape[0]
     if workspace is None:
-        workspace = alloc_workspace(B, T, K, C, ckpt_interval, False, emis.device)
+        workspace = alloc_workspace(B, T, K, C, ckpt_interval, fwd_workspace_kind(flags), emis.device)
     if logz is None:
         logz = torch.empty(B, dtype=torch.float32, device=emis.device)
     ep, flags = _emis(emis, flags)
@@ -233,7 +253,7 @@ def semicrf_logz_fwd_boundary(emis, lengths, trans, dur, proj_start=None, proj_e
     B, T, C = emis.shape
     K = dur.shape[0]
     if workspace is None:
-        workspace = alloc_workspace(B, T, K, C, ckpt_interval, False, emis.device)
+        workspace = alloc_workspace(B, T, K, C, ckpt_interval, fwd_workspace_kind(flags), emis.device)
     logz = torch.empty(B, dtype=torch.float32, device=emis.device)
     f32 = torch.float32
     ep, flags = _emis(emis, flags)
@@ -376,9 +396,18 @@ def semicrf_scan_report(workspace, B, T, K, C, ckpt_interval=0, want_grad=True):
     acc = torch.empty((B, 2), dtype=torch.int32, device=workspace.device)
     mis = torch.empty((B, 2), dtype=torch.float64, device=workspace.device)
     _check(load().semicrf_scan_report(workspace.data_ptr(), workspace.numel(), B, T, K, C,
-                                      ckpt_interval, int(bool(want_grad)), acc.data_ptr(),
+                                      ckpt_interval, int(want_grad), acc.data_ptr(),
                                       mis.data_ptr(), _stream()))
     return acc, mis
+
+
+def semicrf_seq_report(workspace, B, T, K, C, ckpt_interval=0, want_grad=True):
+    """Returns (range_exceeded [B] int32, logz64 [B] float64) of the last call on `workspace`."""
+    rng = torch.empty(B, dtype=torch.int32, device=workspace.device)
+    lz = torch.empty(B, dtype=torch.float64, device=workspace.device)
+    _check(load().semicrf_seq_report(workspace.data_ptr(), workspace.numel(), B, T, K, C,
+                                     ckpt_interval, int(want_grad), rng.data_ptr(), lz.data_ptr(), _stream()))
+    return rng, lz
 
 
 _hip = None

@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libsemicrf.so")
-SOURCES = [os.path.join(HERE, "csrc", n) for n in ("semicrf.hip", "mscan.hip")]
+SOURCES = [os.path.join(HERE, "csrc", n) for n in ("semicrf.hip", "mscan.hip", "plan.cpp")]
 OBJDIR = os.path.join(HERE, "_build")
 FLAGS = [
     "-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17",
@@ -29,7 +29,9 @@ def build_library(verbose: bool = False, only=None) -> str:
         objs.append(obj)
         if only is not None and os.path.basename(src) not in only and os.path.exists(obj):
             continue
-        jobs.append((src, subprocess.Popen([hipcc] + FLAGS + ["-c", "-o", obj, src], cwd=HERE,
+        # plan.cpp is host-only C++: no offload flags
+        flags = FLAGS if src.endswith(".hip") else [f for f in FLAGS if not f.startswith("--offload-arch")][:3] + [FLAGS[-1]]
+        jobs.append((src, subprocess.Popen([hipcc] + flags + ["-c", "-o", obj, src], cwd=HERE,
                                            stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
     failed = False
     for src, proc in jobs:

@@ -12,18 +12,14 @@
 #include <utility>
 
 #include "semicrf.h"
+#include "geometry.h"
+#include "plan.h"
 
 namespace semicrf_impl {
 
-constexpr int NT = 256;          // threads per workgroup in the scan kernels
-constexpr int PREP_CH = 256;     // positions per prefix-sum chunk (multiple of JMAX)
-constexpr int JMAX = 32;         // largest scaling block
-constexpr int NSLOT_MAX = 1024;  // resident tasks of the interval kernel (one wave per SIMD)
-constexpr int GRAD_CMAX = 64;    // most labels the gradient path holds transition accumulators for
 constexpr double LN2 = 0.6931471805599453094;
 constexpr double LOG2E = 1.4426950408889634074;
 constexpr double RANGE_NATS = 300.0;  // growth allowed inside one scaling block (2x this < ln DBL_MAX)
-constexpr size_t LDS_LIMIT = 160 * 1024;
 
 struct SeqHdr {
     int L;          // clamped length
@@ -33,6 +29,7 @@ struct SeqHdr {
     double logZ;    // from the forward scan
     double logZb;   // from the backward scan (diagnostic: must equal logZ)
 };
+static_assert(sizeof(SeqHdr) == SEQ_HDR_BYTES, "the plan sizes the header array with SEQ_HDR_BYTES");
 
 struct Params {
     // problem
@@ -88,6 +85,7 @@ struct Params {
     int spec;           // chunk-parallel scan enabled for this call
     int mscan;          // its tasks may run sixteen at a time in lock step on the matrix cores
     double *sink;       // [1536] target of stores that must be issued but whose value nobody wants
+    int lowmem;         // low-memory plan: interval at the spacing of Algorithm 1, a few row slots per sequence
     int warm0;          // first warm-up length of the chunk-parallel scans asked for by the caller (0 = default)
     int marg_route;     // 0 automatic, 1 marginals from the stored rows of both scans, 2 per-interval recurrence
     int vit_global;     // Viterbi trace-back by pointer doubling over all nodes (test of the fallback route)
@@ -153,13 +151,6 @@ __device__ __forceinline__ int safe_exponent(double m)
     int e;
     (void)frexp(m, &e);
     return e;
-}
-
-__host__ __device__ constexpr int pow2_ge8(int x)
-{
-    int r = 8;
-    while (r < x) r <<= 1;
-    return r;
 }
 
 __device__ __forceinline__ void lds_barrier()

@@ -15,8 +15,6 @@
 // (sequence, interval) each; they write the same partials as the interval kernels (partD,
 // partTr, the running emission sums, tot, sumR), which skip the sequences handled here.
 // ---------------------------------------------------------------------------
-constexpr int MG_TG = 32;  // positions staged at a time
-constexpr int MG_KS = 8;   // durations per thread of the duration kernel
 
 // absolute log2 scale of the forward / backward row i of interval j
 __device__ __forceinline__ double mg_ya(const Params &p, const int b, const int j, const int i)
@@ -183,7 +181,6 @@ __global__ __launch_bounds__(1024) void k_mg_dur(Params p)
 // interval's upper end downwards (the emission sums are suffix sums); per group all threads stage
 // a_t kappa, p_t and (out - in) kappa (rows beyond the group are zero), then every thread adds the
 // group's products for its label pairs while threads 0..C-1 walk the group for the running sums.
-constexpr int MG_TE = 64;
 
 __global__ __launch_bounds__(NT) void k_mg_te(Params p)
 {

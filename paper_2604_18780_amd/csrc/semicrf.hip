@@ -325,14 +325,6 @@ struct Lds {
     int *sc;
 };
 
-__host__ __device__ inline size_t lds_doubles(int K, int C, int G, bool interval)
-{
-    size_t CP1 = (size_t)(C | 1);
-    size_t n = 2 * (size_t)K * C + (size_t)C * CP1 + (size_t)G * C + 5 * (size_t)C;
-    if (interval) n += (size_t)K * C;
-    return n;
-}
-
 __device__ __forceinline__ Lds carve(double *base, int K, int C, int G, bool interval)
 {
     Lds l;
@@ -1125,30 +1117,7 @@ __global__ __launch_bounds__(NT) void k_interval(Params p)
 // block's own new messages contribute to its later positions (durations 1..MB-1) is added
 // from registers while the positions are finished one after the other.
 // ---------------------------------------------------------------------------
-constexpr int MB = 4;  // positions per time block
-
-// Window entries per lane: NKW, plus one when a half-wave holds several lane groups, so
-// that the groups' rows fall into different LDS banks.
-__host__ __device__ constexpr int wave_nk(int CT, int NKW)
-{
-    return NKW + ((64 / pow2_ge8(CT)) > 2 ? 1 : 0);
-}
-
-// Rows of slack behind the sliding window: a quarter of the window (the window is moved back once
-// per that many positions), an eighth for the deepest window, where the quarter would cost the
-// fourth resident task of a compute unit its LDS.
-__host__ __device__ constexpr int lin_slack(int KW)
-{
-    return KW / 4 < 8 ? 8 : (KW >= 512 ? ((KW / 8 + 3) & ~3) : ((KW / 4 + 3) & ~3));
-}
-
-__host__ __device__ constexpr size_t wave_lds_doubles(int CT, int NKW)
-{
-    const int CTP = pow2_ge8(CT);
-    const int KW = wave_nk(CT, NKW) * (64 / CTP);
-    const int YS = CTP < 16 ? 16 : CTP;
-    return (size_t)(KW + lin_slack(KW)) * CT + (size_t)(CTP - CT) + (size_t)MB * YS;
-}
+// MB positions per time block; wave_nk, lin_slack and wave_lds_doubles give the window's size (geometry.h).
 
 // Geometry and the window operations shared by the one-wave kernels.
 template <int CT, int NKW>
@@ -1223,18 +1192,7 @@ struct WaveWin {
 // With the longest duration strips (NKW = 64) the strip of weights and the strip of grad_dur
 // accumulators do not both fit the registers; the weights then live in LDS as well, W[m+1, c]
 // at [m*CT + c] (zero beyond K), and are read once per block like the window.
-__host__ __device__ constexpr int interval_waves(int CT, int NKW) { return CT == 64 ? 4 : (NKW == 64 ? 3 : 1); }
-
-__host__ __device__ constexpr size_t interval_wtab_doubles(int CT, int NKW)
-{
-    return NKW == 64 ? (size_t)(wave_nk(CT, NKW) * (64 / pow2_ge8(CT)) + MB) * CT + (size_t)(pow2_ge8(CT) - CT) : 0;
-}
-
-__host__ __device__ constexpr size_t interval_lds_doubles(int CT, int NKW)
-{
-    return (CT == 64 ? 2 * (size_t)CT * CT : 0) + interval_wtab_doubles(CT, NKW) +
-           (size_t)interval_waves(CT, NKW) * wave_lds_doubles(CT, NKW);
-}
+// (interval_waves, interval_wtab_doubles, interval_lds_doubles: geometry.h)
 
 template <int CT, int NKW>
 __global__ __launch_bounds__(64 * interval_waves(CT, NKW)) void k_interval_wave(Params p)
@@ -1709,14 +1667,14 @@ __global__ __launch_bounds__(64 * interval_waves(CT, NKW)) void k_interval_wave(
 // One wave per task, no barriers, same register/LDS organisation as k_interval_wave.
 // ---------------------------------------------------------------------------
 constexpr double SPEC_TOL = 1e-10;
+constexpr int SPEC_RUN_MAX = 8;  // intervals one wave mends in a row in the repair attempt
 
 // One scan task of the chunk-parallel scan, one wave (window and time blocking as above).
 // repair: the task restarts from the state its neighbour in scan order REACHED at their common boundary (no
-// warm-up, exact), but only when that boundary disagreed and the neighbour itself started from a verified or
-// exact state; every other task returns at once and keeps what it has.
-template <int CT, int NKW, bool BWD>
+// warm-up: exact if the neighbour's own start was); k_spec decides which tasks do that.
+template <int CT, int NKW, bool BWD, bool repair>
 __device__ __forceinline__ void spec_task(const Params &p, double *lds_raw, const int b, const int j,
-                                          const int warm, const bool repair)
+                                          const int warm)
 {
     using G = WaveWin<CT, NKW>;
     constexpr int CTP = G::CTP, RS = G::RS, NK = G::NK, KW = G::KW, M = G::M, ROWS = G::ROWS;
@@ -1758,16 +1716,6 @@ __device__ __forceinline__ void spec_task(const Params &p, double *lds_raw, cons
     }
     const double2 *ys = (const double2 *)__builtin_assume_aligned(yv + hh * HC, 16);
 
-    if (repair) {
-        const int nint = (L + Delta - 1) / Delta;
-        const size_t so = ((size_t)b * 2 + (BWD ? 1 : 0)) * (N + 1);
-        const int bs = BWD ? j + 1 : j;        // boundary this task starts from
-        const int bp = BWD ? j + 2 : j - 1;    // boundary its neighbour in scan order started from
-        if (bs < 1 || bs > nint - 1) return;   // the first task in scan order starts from the exact state
-        if (p.spec_err[so + bs] <= SPEC_TOL) return;  // agreed: nothing to repair here
-        const bool nb_exact = BWD ? bp >= nint : bp <= 0;
-        if (!nb_exact && !(p.spec_err[so + bp] <= SPEC_TOL)) return;  // the neighbour is wrong itself: a later attempt
-    }
     // ---- start: the state of a sequence that begins (forward) / ends (backward) at s0
     const int s0 = repair ? (BWD ? hi : lo) : (BWD ? min(hi + warm, L) : max(lo - warm, 0));
     for (int i = lane; i < RTOT; i += 64) ring[i] = 0.0;
@@ -1962,9 +1910,38 @@ __global__ __launch_bounds__(64) void k_spec(Params p, int both, int warm, int t
     const int b = task / p.N, j = task % p.N;
     if (tier > 0 && p.spec_ok[b * 2 + dir]) return;  // accepted by an earlier attempt
     if (rest && p.hdr[b].J >= MS_JMIN) return;
-    const bool repair = warm == 0;  // the attempt that restarts single intervals from reached states
-    if (dir == 0) spec_task<CT, NKW, false>(p, lds_raw, b, j, warm, repair);
-    else spec_task<CT, NKW, true>(p, lds_raw, b, j, warm, repair);
+    if (dir == 0) spec_task<CT, NKW, false, false>(p, lds_raw, b, j, warm);
+    else spec_task<CT, NKW, true, false>(p, lds_raw, b, j, warm);
+}
+
+// The repair attempt of the chunk-parallel scans, for the (sequence, direction) pairs that are still open.
+template <int CT, int NKW>
+__global__ __launch_bounds__(64) void k_spec_repair(Params p, int both)
+{
+    extern __shared__ double lds_raw[];
+    const int ndir = both ? 2 : 1;
+    const int dir = blockIdx.x % ndir;
+    const int task = blockIdx.x / ndir;
+    const int b = task / p.N, j = task % p.N;
+    if (p.spec_ok[b * 2 + dir]) return;
+    // A run of adjacent boundaries that disagreed is taken by ONE wave, the task that starts at the first of them
+    // in scan order (its neighbour started from a verified or exact state, so what that neighbour reached is
+    // right): it restarts from the reached state and goes on through the run's intervals one after the other,
+    // at most SPEC_RUN_MAX of them; a longer run stays open for the next attempt.  Every other task returns at once and keeps what it has.  Nothing in this kernel writes spec_err.
+    const int L = p.hdr[b].L;
+    const int nint = (L + p.Delta - 1) / p.Delta;
+    const double *err = p.spec_err + ((size_t)b * 2 + dir) * (p.N + 1);
+    auto bad = [&](const int m) { return m >= 1 && m <= nint - 1 && !(err[m] <= SPEC_TOL); };
+    if (!bad(dir ? j + 1 : j) || bad(dir ? j + 2 : j - 1)) return;
+    int jj = j;
+    for (int n = 0; n < SPEC_RUN_MAX; ++n) {
+        if (dir == 0) spec_task<CT, NKW, false, true>(p, lds_raw, b, jj, 0);
+        else spec_task<CT, NKW, true, true>(p, lds_raw, b, jj, 0);
+        const int nx = dir ? jj - 1 : jj + 1;              // the next task in scan order ...
+        if (nx < 0 || nx >= nint || !bad(dir ? nx + 1 : nx)) break;  // ... starts where this one ended
+        __threadfence();  // the reached state this wave has just written is what it restarts from
+        jj = nx;
+    }
 }
 
 // One workgroup per (chunk boundary j, sequence, direction): compare the state chunk j-1
@@ -2103,6 +2080,23 @@ __global__ void k_spec_report(Params p, int32_t *accepted, double *mismatch)
     if (i >= 2 * p.B) return;
     if (accepted) accepted[i] = p.spec_ok[i];
     if (mismatch) mismatch[i] = p.spec_err[(size_t)i * (p.N + 1)];
+}
+
+__global__ void k_seq_report(Params p, int32_t *range_exceeded, double *logz64)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= p.B) return;
+    const SeqHdr h = p.hdr[b];
+    if (range_exceeded) range_exceeded[b] = h.flags & 1;
+    if (logz64) logz64[b] = h.logZ;
+}
+
+// The report fields sit in front of everything that differs between the gradient plans: the smallest plan of the
+// caller's kind (forward only or gradients, default or low memory) locates them.
+inline int report_plan_kind(int want_grad)
+{
+    if (want_grad < 0) return -1;
+    return (want_grad & PLAN_LOW_MEMORY) | ((want_grad & 7) ? 2 : 0);
 }
 
 // ---------------------------------------------------------------------------
@@ -2955,166 +2949,6 @@ __global__ __launch_bounds__(NT) void k_entropies(const float *pos_marg, const f
 #include "durtrans.inl"
 #include "marg.inl"
 
-inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
-
-// First warm-up length of the chunk-parallel sum scans: one and a half maximal segment lengths.
-// The products of positive maps forget their start fast enough that the boundary mismatch is at the
-// rounding floor there on all workloads (it reaches 1e-11 at 1.25 K; the acceptance bound is 1e-10).
-inline int sum_warmup(int K) { return 3 * K / 2 < 32 ? 32 : (3 * K + 1) / 2; }
-
-// Single-wave tasks a compute unit holds at once for these sizes (scan kernel, interval
-// kernel): bounded by the LDS windows and by registers (two scan waves per SIMD, one where
-// the kernel needs more than 256 registers; one interval wave per SIMD).  False when the
-// one-wave kernels do not apply.
-bool wave_tasks_per_cu(int K, int C, int *scan, int *interval)
-{
-    if (C > 64) return false;
-    const int CT = C <= 8 ? 8 : (C <= 16 ? 16 : (C <= 24 ? 24 : (C <= 32 ? 32 : 64)));
-    const int GW = 64 / pow2_ge8(CT);
-    const int per_lane = (K + GW - 1) / GW;
-    if (per_lane > 64) return false;
-    const int NKW = per_lane <= 16 ? 16 : (per_lane <= 32 ? 32 : 64);
-    const size_t lds = wave_lds_doubles(CT, NKW) * sizeof(double);
-    if (lds > LDS_LIMIT) return false;
-    const int fit = (int)(LDS_LIMIT / lds);
-    const int scan_regs = (CT == 64 || (CT == 32 && NKW == 64)) ? 4 : 8;
-    *scan = fit < scan_regs ? fit : scan_regs;
-    const size_t ilds = interval_lds_doubles(CT, NKW) * sizeof(double);
-    int iw = ilds <= LDS_LIMIT ? (int)(LDS_LIMIT / ilds) * interval_waves(CT, NKW) : 1;  // else the generic kernel
-    *interval = iw < 4 ? iw : 4;
-    return true;
-}
-
-// Automatic checkpoint interval.  Every (sequence, interval) is one single-wave task of the
-// chunk-parallel scans (both directions, interval + warm-up positions each) and of the
-// interval stage (interval positions, about 1.2x the cost per position and round).  Tasks run in
-// rounds of as many as fit the chip at once (256 compute units; per compute unit 8 scan
-// waves or 4 interval waves by registers, fewer when the K-deep LDS window is large), and
-// a partly filled round costs a full one.  The interval is the multiple of 8 that
-// minimises that cost, within [max(8, K/2), sqrt(T*K)]: below the lower end warm-ups and
-// K-deep checkpoints dominate work and memory; the upper end is the spacing of Algorithm 1,
-// so checkpoints and per-task buffers still grow like sqrt(T) for very long sequences.
-int auto_interval(int B, int T, int K, int C)
-{
-    int per_scan = 0, per_int = 0;
-    if (!wave_tasks_per_cu(K, C, &per_scan, &per_int)) {
-        // generic kernels: sqrt(T*K) spacing scaled to spread B*T/interval tasks over 256 units
-        double d = ceil(sqrt((double)T * (double)K * (double)B / 256.0));
-        int di = d < 1.0 ? 1 : (int)d;
-        if (di >= 8) di = (di + 7) & ~7;
-        return di > T ? T : di;
-    }
-    const double slots_scan = 256.0 * per_scan;
-    const double slots_int = 256.0 * per_int;
-    const double warm = (double)sum_warmup(K);
-    const int dlo = K / 2 < 8 ? 8 : K / 2;
-    int dhi = (int)ceil(sqrt((double)T * (double)K));
-    if (dhi < dlo) dhi = dlo;
-    int best = 0;
-    double best_cost = 0.0;
-    for (int n = 1; n <= 8192; ++n) {
-        int d = ((T + n - 1) / n + 7) & ~7;
-        if (d > T) d = T;
-        if (d > dhi && d != T) continue;
-        if (d > dhi && n > 1) continue;
-        if (d < dlo && best) break;
-        const double tasks = (double)B * (double)(((long long)T + d - 1) / d);
-        const double cost = ceil(2.0 * tasks / slots_scan) * (warm + d) + 1.2 * ceil(tasks / slots_int) * d;
-        if (!best || cost < best_cost) {
-            best = d;
-            best_cost = cost;
-        }
-        if (d <= dlo) break;
-    }
-    return best;
-}
-
-bool spec_applies(int K, int C);
-
-struct Plan {
-    int Delta, N, NCH, nslot, G;
-    int rows;  // the backward scan tasks have row storage (stored-row marginals possible)
-    size_t lds_mg_dur, lds_mg_te;
-    size_t lds_scan, lds_interval;
-    size_t total;
-    size_t off[32];
-};
-
-// want_grad: 0 forward only, 1 gradients (stored-row marginals where they pay: K >= 128), 2 gradients of a caller
-// that never takes the stored-row marginals, 3 gradients with the row slots of the stored-row marginals planned
-int make_plan(int B, int T, int K, int C, int ckpt_interval, int want_grad, Plan *pl)
-{
-    if (B < 1 || T < 1 || K < 1 || C < 1 || ckpt_interval < 0) return SEMICRF_EINVAL;
-    if (C > 256) return SEMICRF_EUNSUPPORTED;
-    if (T > (1 << 30) || (double)B * ((double)T + 1.0) * (double)C > 2.0e10) return SEMICRF_EUNSUPPORTED;
-    pl->Delta = ckpt_interval > 0 ? (ckpt_interval > T ? T : ckpt_interval) : auto_interval(B, T, K, C);
-    pl->N = (T + pl->Delta - 1) / pl->Delta;
-    pl->NCH = T / PREP_CH + 1;
-    pl->G = (NT / C) < K ? (NT / C) : K;
-    pl->lds_scan = lds_doubles(K, C, pl->G, false) * sizeof(double);
-    pl->lds_interval = lds_doubles(K, C, pl->G, true) * sizeof(double);
-    if (pl->lds_scan > LDS_LIMIT) return SEMICRF_EUNSUPPORTED;
-    if (want_grad && (pl->lds_interval > LDS_LIMIT || C > GRAD_CMAX)) return SEMICRF_EUNSUPPORTED;
-    size_t ntask = (size_t)B * pl->N;
-    pl->nslot = (int)(ntask < (size_t)NSLOT_MAX ? ntask : (size_t)NSLOT_MAX);
-    pl->nslot = (pl->nslot + 11) / 12 * 12;  // whole workgroups of three or four single-wave tasks
-    const size_t b = (size_t)B, t1 = (size_t)T + 1, c = (size_t)C, k = (size_t)K, n = (size_t)pl->N;
-    const size_t n1 = n;
-    size_t sz[32];
-    int i = 0;
-    sz[i++] = b * sizeof(SeqHdr);                 // 0 hdr
-    sz[i++] = b * c * 8;                          // 1 nu
-    sz[i++] = b * pl->NCH * c * 8;                // 2 chsum
-    sz[i++] = b * pl->NCH * 8;                    // 3 chmax
-    sz[i++] = 2 * 8;                              // 4 tabmax
-    sz[i++] = k * c * 8;                          // 5 W
-    sz[i++] = c * c * 8;                          // 6 Etr
-    sz[i++] = b * t1 * c * 16;                    // 7 EI
-    sz[i++] = 2 * b * 2 * (n1 + 1) * 8 + b * 2 * 4 + 256;  // 8 spec_lr, spec_err, spec_ok
-    sz[i++] = b * t1 * c * 4;                     // 9 nbase
-    const size_t g = want_grad ? 1 : 0;
-    sz[i++] = b * (n + 1) * (k * c + c) * 8;      // 10 ckA
-    sz[i++] = g * b * (n + 1) * (k * c + c) * 8;  // 11 ckB
-    sz[i++] = b * (n + 1) * 8;                    // 12 ckYA
-    sz[i++] = g * b * (n + 1) * 8;                // 13 ckYB
-    sz[i++] = g * (size_t)pl->nslot * pl->Delta * 2 * c * 8;  // 14 aloc
-    sz[i++] = g * (size_t)pl->nslot * pl->Delta * 8;          // 15 alocY
-    sz[i++] = g * b * n * k * c * 8;              // 16 partD
-    sz[i++] = g * b * n * c * c * 8;              // 17 partTr
-    sz[i++] = g * b * n * c * 8;                  // 18 tot
-    sz[i++] = g * b * n * c * 8;                  // 19 sumR
-    sz[i++] = g * b * n * c * 8;                  // 20 carry
-    sz[i++] = g * b * c * 8;                      // 21 mean
-    sz[i++] = b * (n + 1) * (k * c + c) * 8;      // 22 ckA2
-    sz[i++] = g * b * (n + 1) * (k * c + c) * 8;  // 23 ckB2
-    sz[i++] = b * (n + 1) * 8;                    // 24 ckYA2
-    sz[i++] = g * b * (n + 1) * 8;                // 25 ckYB2
-    sz[i++] = b * c * 8;                          // 26 out0
-    sz[i++] = b * c * 8;                          // 27 inL
-    // Marginals from the stored rows of both scans need a second set of row slots.  Measured: the
-    // route wins where the K-deep window makes the interval kernel's recurrence long (K = 512:
-    // 0.52 ms against 1.08 ms) and is level with it at K = 64, so it is planned for K >= 128,
-    // when every task has its slot and the sizes fit its kernels.
-    const int mg_nsl = (K + MG_KS - 1) / MG_KS;
-    const size_t mg_vr = (size_t)MG_TG + MG_KS * mg_nsl + 3;
-    pl->lds_mg_dur = (MG_TG * c + mg_vr * (c | 3) + MG_TG + 2 * mg_vr + 2 * (size_t)pl->Delta + k) * sizeof(double);
-    pl->lds_mg_te = ((size_t)3 * MG_TE * c + pl->Delta) * sizeof(double);
-    const bool rows = want_grad == 3 || (want_grad == 1 && K >= 128);
-    pl->rows = rows && spec_applies(K, C) && ntask <= (size_t)pl->nslot && c * mg_nsl <= 1024 &&
-               pl->lds_mg_dur <= LDS_LIMIT && pl->lds_mg_te <= LDS_LIMIT;
-    const size_t gr = pl->rows ? 1 : 0;
-    sz[i++] = gr * (size_t)pl->nslot * pl->Delta * 2 * c * 8;  // 28 bloc
-    sz[i++] = gr * (size_t)pl->nslot * pl->Delta * 8;          // 29 blocY
-    sz[i++] = 1536 * 8;                                        // 30 sink
-    size_t off = 0;
-    for (int j = 0; j < i; ++j) {
-        pl->off[j] = off;
-        off += align_up(sz[j]);
-    }
-    pl->total = off;
-    return SEMICRF_OK;
-}
-
 void bind_workspace(Params &p, const Plan &pl, void *ws)
 {
     char *w = (char *)ws;
@@ -3272,6 +3106,8 @@ int launch_spec_k(const Params &p, hipStream_t st, bool both, int warm, int tier
     const size_t lds = wave_lds_doubles(CT, NKW) * sizeof(double);
     if (lds > LDS_LIMIT) return 1;
     if (hipFuncSetAttribute((const void *)k_spec<CT, NKW>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds) != hipSuccess ||
+        hipFuncSetAttribute((const void *)k_spec_repair<CT, NKW>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)lds) != hipSuccess)
         return SEMICRF_ELAUNCH;
     const int ndir = both ? 2 : 1;
@@ -3281,8 +3117,11 @@ int launch_spec_k(const Params &p, hipStream_t st, bool both, int warm, int tier
         if (rc != SEMICRF_OK) return rc;
         rest = 1;
     }
-    hipLaunchKernelGGL((k_spec<CT, NKW>), dim3(p.B * p.N * ndir), dim3(64), lds, st, p, both ? 1 : 0,
-                       warm, tier, rest);
+    if (warm > 0)
+        hipLaunchKernelGGL((k_spec<CT, NKW>), dim3(p.B * p.N * ndir), dim3(64), lds, st, p, both ? 1 : 0,
+                           warm, tier, rest);
+    else
+        hipLaunchKernelGGL((k_spec_repair<CT, NKW>), dim3(p.B * p.N * ndir), dim3(64), lds, st, p, both ? 1 : 0);
     hipLaunchKernelGGL(k_spec_cmp, dim3(p.N, p.B, ndir), dim3(NT), 0, st, p, tier);
     hipLaunchKernelGGL(k_spec_fix, dim3(p.B, 2), dim3(64), 0, st, p, ndir, tier, tier == 0 ? 1 : (warm == 0 ? 2 : 3));
     return check_launch();
@@ -3297,22 +3136,6 @@ int launch_spec_ct(const Params &p, hipStream_t st, bool both, int warm, int tie
     if (per_lane <= 32) return launch_spec_k<CT, 32>(p, st, both, warm, tier);
     if (per_lane <= 64) return launch_spec_k<CT, 64>(p, st, both, warm, tier);
     return 1;
-}
-
-constexpr int spec_ct_of(int C)
-{
-    return C <= 8 ? 8 : (C <= 16 ? 16 : (C <= 24 ? 24 : (C <= 32 ? 32 : 64)));
-}
-
-bool spec_applies(int K, int C)
-{
-    if (C > 64) return false;
-    const int CT = spec_ct_of(C);
-    const int GW = 64 / pow2_ge8(CT);
-    const int per_lane = (K + GW - 1) / GW;
-    if (per_lane > 64) return false;
-    const int NKW = per_lane <= 16 ? 16 : (per_lane <= 32 ? 32 : 64);
-    return wave_lds_doubles(CT, NKW) * sizeof(double) <= LDS_LIMIT;
 }
 
 int launch_spec(const Params &p, hipStream_t st, bool both, int warm, int tier)
@@ -3335,7 +3158,7 @@ struct StageTimer {
     hipStream_t st = nullptr;
     void mark()
     {
-        if (on && n < 5) hipEventRecord(ev[n++], st);
+        if (on && n < 5) (void)hipEventRecord(ev[n++], st);
     }
 };
 
@@ -3345,7 +3168,8 @@ int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hi
     StageTimer none;
     StageTimer &T = tm ? *tm : none;
     Plan pl;
-    int rc = make_plan(p.B, p.T, p.K, p.C, ckpt_interval, mode != 2 ? 0 : (p.marg_route == 1 ? 3 : (p.marg_route == 2 ? 2 : 1)), &pl);
+    const int kind = mode != 2 ? 0 : (p.marg_route == 1 ? 3 : (p.marg_route == 2 ? 2 : 1));
+    int rc = make_plan(p.B, p.T, p.K, p.C, ckpt_interval, kind | (p.lowmem ? PLAN_LOW_MEMORY : 0), &pl);
     if (rc != SEMICRF_OK) return rc;
     if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < pl.total)
         return SEMICRF_EWORKSPACE;
@@ -3373,11 +3197,10 @@ int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hi
     if (rc != SEMICRF_OK || mode == 0) return rc;
     if (p.spec) {
         // Every interval after a short warm-up; then, for what did not verify, the intervals whose start disagreed
-        // restart from the state their neighbour reached (exact; warm-up 0 selects that; each such attempt mends
-        // the first of a run of adjacent disagreeing boundaries, so there are two); then everything that is still
+        // restart from the state their neighbour reached (warm-up 0 selects that); then everything that is still
         // open once more after a long warm-up.  The sequential scan takes the rest.
-        const int attempt[4] = {warm[0], 0, 0, warm[1]};
-        for (int tier = 0; tier < 4; ++tier) {
+        const int attempt[3] = {warm[0], 0, warm[1]};
+        for (int tier = 0; tier < 3; ++tier) {
             rc = launch_spec(p, st, mode == 2, attempt[tier], tier);
             if (rc != SEMICRF_OK) return rc;
         }
@@ -3757,7 +3580,7 @@ int run_durtrans(Params p, int ckpt_interval, void *workspace, size_t workspace_
 int common_params(Params &p, const float *emis, const int32_t *lengths, const float *dur, int B, int T, int K, int C,
                   unsigned flags)
 {
-    if ((flags & SEMICRF_EMIS_F16) && (flags & SEMICRF_EMIS_BF16)) return SEMICRF_EINVAL;
+    if (int rc = check_flags(flags)) return rc;
     p.emis = emis;
     p.lengths = lengths;
     p.dur = dur;
@@ -3766,7 +3589,7 @@ int common_params(Params &p, const float *emis, const int32_t *lengths, const fl
     p.emis_type = (flags & SEMICRF_EMIS_F16) ? 1 : ((flags & SEMICRF_EMIS_BF16) ? 2 : 0);
     p.spec = (flags & SEMICRF_SEQUENTIAL_SCAN) ? 0 : 1;
     p.mscan = (flags & SEMICRF_MATRIX_SCAN) ? 1 : 0;
-    if ((flags & SEMICRF_MARGINALS_ROWS) && (flags & SEMICRF_MARGINALS_INTERVAL)) return SEMICRF_EINVAL;
+    p.lowmem = (flags & SEMICRF_LOW_MEMORY) ? 1 : 0;
     p.marg_route = (flags & SEMICRF_MARGINALS_ROWS) ? 1 : ((flags & SEMICRF_MARGINALS_INTERVAL) ? 2 : 0);
     p.vit_global = (flags & SEMICRF_VITERBI_GLOBAL_TRACE) ? 1 : 0;
     p.warm0 = (int)(flags >> 16);
@@ -3828,6 +3651,16 @@ int semicrf_ckpt_interval(int B, int T, int K, int C, int ckpt_interval, int *in
     if (!interval) return SEMICRF_EINVAL;
     Plan pl;
     int rc = make_plan(B, T, K, C, ckpt_interval, 0, &pl);
+    if (rc != SEMICRF_OK) return rc;
+    *interval = pl.Delta;
+    return SEMICRF_OK;
+}
+
+int semicrf_ckpt_interval_low_memory(int B, int T, int K, int C, int ckpt_interval, int *interval)
+{
+    if (!interval) return SEMICRF_EINVAL;
+    Plan pl;
+    int rc = make_plan(B, T, K, C, ckpt_interval, PLAN_LOW_MEMORY, &pl);
     if (rc != SEMICRF_OK) return rc;
     *interval = pl.Delta;
     return SEMICRF_OK;
@@ -3981,6 +3814,7 @@ int semicrf_viterbi(const float *emis, const int32_t *lengths, const float *tran
 {
     if (!emis || !trans || !dur || !score || !labels || !starts || !nseg) return SEMICRF_EINVAL;
     Params p = {};
+    if (flags & SEMICRF_LOW_MEMORY) return SEMICRF_EINVAL;  // the low-memory plan exists for the factorised sums only
     if (int rc = common_params(p, emis, lengths, dur, B, T, K, C, flags)) return rc;
     p.trans = trans;
     p.proj_start = proj_start; p.proj_end = proj_end; p.pi_start = pi_start; p.pi_end = pi_end;
@@ -4020,6 +3854,7 @@ int semicrf_logz_fwd_durtrans(const float *emis, const int32_t *lengths, const f
 {
     if (!emis || !trans3 || !dur || !logz) return SEMICRF_EINVAL;
     Params p = {};
+    if (flags & SEMICRF_LOW_MEMORY) return SEMICRF_EINVAL;  // the low-memory plan exists for the factorised sums only
     if (int rc = common_params(p, emis, lengths, dur, B, T, K, C, flags)) return rc;
     p.trans3 = trans3;
     p.logz = logz;
@@ -4034,6 +3869,7 @@ int semicrf_fwd_bwd_durtrans(const float *emis, const int32_t *lengths, const fl
 {
     if (!emis || !trans3 || !dur || !logz || !grad_emis || !grad_trans3 || !grad_dur) return SEMICRF_EINVAL;
     Params p = {};
+    if (flags & SEMICRF_LOW_MEMORY) return SEMICRF_EINVAL;  // the low-memory plan exists for the factorised sums only
     if (int rc = common_params(p, emis, lengths, dur, B, T, K, C, flags)) return rc;
     p.trans3 = trans3; p.grad_logz = grad_logz;
     p.logz = logz; p.grad_emis = grad_emis; p.grad_trans3 = grad_trans3; p.grad_dur = grad_dur;
@@ -4041,13 +3877,30 @@ int semicrf_fwd_bwd_durtrans(const float *emis, const int32_t *lengths, const fl
     return run_durtrans(p, ckpt_interval, workspace, workspace_bytes, (hipStream_t)stream, true);
 }
 
+int semicrf_seq_report(const void *workspace, size_t workspace_bytes, int B, int T, int K, int C,
+                       int ckpt_interval, int want_grad, int32_t *range_exceeded, double *logz64, void *stream)
+{
+    Plan pl;
+    int rc = make_plan(B, T, K, C, ckpt_interval, report_plan_kind(want_grad), &pl);
+    if (rc != SEMICRF_OK) return rc;
+    if (!range_exceeded && !logz64) return SEMICRF_EINVAL;
+    if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < pl.total)
+        return SEMICRF_EWORKSPACE;
+    Params p = {};
+    p.B = B; p.T = T; p.K = K; p.C = C;
+    p.N = pl.N;
+    bind_workspace(p, pl, const_cast<void *>(workspace));
+    hipLaunchKernelGGL(k_seq_report, dim3((B + 63) / 64), dim3(64), 0, (hipStream_t)stream, p, range_exceeded,
+                       logz64);
+    return check_launch();
+}
+
 int semicrf_scan_report(const void *workspace, size_t workspace_bytes, int B, int T, int K, int C,
                         int ckpt_interval, int want_grad, int32_t *accepted, double *mismatch,
                         void *stream)
 {
     Plan pl;
-    // the report fields sit in front of everything that differs between the gradient plans: the smallest one locates them
-    int rc = make_plan(B, T, K, C, ckpt_interval, want_grad ? 2 : 0, &pl);
+    int rc = make_plan(B, T, K, C, ckpt_interval, report_plan_kind(want_grad), &pl);
     if (rc != SEMICRF_OK) return rc;
     if (!accepted && !mismatch) return SEMICRF_EINVAL;
     if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < pl.total)

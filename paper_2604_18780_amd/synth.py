@@ -156,3 +156,20 @@ def duration_transitions(w: Workload, seed: int = 777, sd: float = 0.1):
     workload's matrix plus N(0, sd^2) noise per (duration, source, destination); float32 [K,C,C]."""
     rng = np.random.default_rng(seed)
     return (w.trans[None] + sd * rng.standard_normal((w.K, w.C, w.C))).astype(np.float32)
+
+
+def reshape_transitions(trans: np.ndarray, sd: float | None = None, band: int | None = None,
+                        forbidden: float = -30.0) -> np.ndarray:
+    """Other transition models on the same draw: scores rescaled from the recipe's N(0, 0.1^2) to
+    N(0, sd^2), and / or every transition between labels further apart than `band` (cyclically)
+    set to `forbidden`.  A banded matrix with a large forbidden score mixes slowly: the case the
+    chunk-parallel scans' verification is there for."""
+    out = trans.astype(np.float64)
+    if sd is not None:
+        out = out * (sd / 0.1)
+    if band is not None:
+        C = out.shape[0]
+        d = np.abs(np.arange(C)[:, None] - np.arange(C)[None, :])
+        d = np.minimum(d, C - d)
+        out = np.where(d <= band, out, forbidden)
+    return out.astype(np.float32)

@@ -94,6 +94,33 @@ def test_working_memory_beyond_prefix_arrays_is_bounded_then_sublinear_in_T():
     assert extra(T) < 40 * paper_ws
 
 
+def test_working_memory_beyond_prefix_arrays_is_sublinear_in_T():
+    """The low-memory plan (flag SEMICRF_LOW_MEMORY, workspace kinds 8 / 9): checkpoints every ceil(sqrt(T*K))
+    positions and a fixed number of row buffers of one interval each per sequence.  The part of the workspace
+    that is not the O(T*C) prefix arrays, measured as (gradient workspace - forward-only workspace), must grow
+    like sqrt(T): at most 2.3x when T grows fourfold (it would quadruple if it were linear), from T = 100 000
+    on, at the genomic and the long-duration shapes (the paper's "Complexity" section and memory table:
+    O(KC) ring + O(sqrt(T/K) KC) checkpoints beyond the prefix sums)."""
+    for (B, K, C) in ((4, 64, 24), (1, 512, 8)):
+        extra = lambda T: (sb.semicrf_workspace_bytes(B, T, K, C, 0, 9) - sb.semicrf_workspace_bytes(B, T, K, C, 0, 8))
+        e = [extra(T) for T in (100000, 400000, 1600000, 6400000)]
+        for a, b in zip(e, e[1:]):
+            assert 1.0 < b / a < 2.3, (B, K, C, e)
+        # and it is small beside the emission array itself
+        assert e[0] < 1.5 * B * 100000 * C * 4 * max(1.0, math.sqrt(K / 64.0))
+        # the interval is the spacing of Algorithm 1
+        for T in (100000, 400000):
+            d = sb.semicrf_ckpt_interval_low_memory(B, T, K, C)
+            assert d % 8 == 0 and math.ceil(math.sqrt(T * K)) <= d < math.ceil(math.sqrt(T * K)) + 8
+    # the default plan needs more: it is the faster one, not the smaller one
+    assert sb.semicrf_workspace_bytes(4, 100000, 64, 24, 0, 9) < 0.75 * sb.semicrf_workspace_bytes(4, 100000, 64, 24, 0, 1)
+    # an explicit interval is taken as given, and kinds that do not exist are refused
+    assert sb.semicrf_ckpt_interval_low_memory(4, 100000, 64, 24, 500) == 500
+    for bad in (4, 7, 11, 16, -1):
+        with pytest.raises(Exception, match="-1"):
+            sb.semicrf_workspace_bytes(4, 1000, 8, 4, 0, bad)
+
+
 def test_checkpoint_interval_choice():
     """Explicit intervals are clamped to T; the automatic one is a multiple of 8 (or T),
     at least max(8, K/2) and at most the sqrt(T*K) spacing of Algorithm 1 rounded up."""

@@ -438,3 +438,70 @@ def test_longgen_shape_reduced_takes_the_stored_rows_route():
     w = synth.small_random(97, 1, 6000, w0.K, w0.C, ragged=False)
     w.dur[:] = w0.dur
     check_against_oracle(w, label="longgen reduced (K = 512)")
+
+
+@pytest.mark.parametrize("seed,B,T,K,C", [(81, 2, 3000, 8, 6), (82, 3, 1500, 40, 24), (83, 1, 5000, 130, 5),
+                                          (84, 2, 90, 4, 3)])
+def test_low_memory_plan_matches_oracle(seed, B, T, K, C):
+    """SEMICRF_LOW_MEMORY: checkpoints every ceil(sqrt(T*K)) positions, eight row buffers per sequence, the
+    forward rows of an interval recomputed from its checkpoint (Algorithm 3's body).  Same results."""
+    w = synth.small_random(seed, B, T, K, C, ragged=True)
+    w.lengths[0] = T
+    delta = sb.semicrf_ckpt_interval_low_memory(B, T, K, C)
+    assert delta == min(T, (int(np.ceil(np.sqrt(T * K))) + 7) // 8 * 8)
+    check_against_oracle(w, label="low-memory plan", extra_flags=sb.SEMICRF_LOW_MEMORY,
+                         grad_logz=np.random.default_rng(seed).standard_normal(B))
+    # the workspace of the default plan has another layout: one that is too small for this call is refused
+    emis, lengths, trans, dur = to_dev(w)
+    small = sb.alloc_workspace(B, T, K, C, 0, sb.PLAN_LOW_MEMORY, DEV)      # forward-only size
+    with pytest.raises(sb.SemiCRFError, match="-2"):
+        sb.semicrf_fwd_bwd(emis, lengths, trans, dur, flags=sb.SEMICRF_CENTER | sb.SEMICRF_LOW_MEMORY, workspace=small)
+    with pytest.raises(sb.SemiCRFError, match="-1"):
+        sb.semicrf_fwd_bwd(emis, lengths, trans, dur,
+                           flags=sb.SEMICRF_CENTER | sb.SEMICRF_LOW_MEMORY | sb.SEMICRF_MARGINALS_ROWS)
+
+
+def test_low_memory_plan_more_tasks_than_row_buffers_genomic_shape():
+    """Genomic shape cut to T = 20 000: 4 x 18 intervals of 1136 positions share 36 row buffers."""
+    w = synth.make("genomic", T=20000)
+    flags = sb.SEMICRF_CENTER | sb.SEMICRF_LOW_MEMORY
+    kind = sb.grad_workspace_kind(flags)
+    assert kind == 9
+    emis, lengths, trans, dur = to_dev(w)
+    ws = sb.alloc_workspace(w.B, w.T, w.K, w.C, 0, kind, DEV)
+    out = sb.semicrf_fwd_bwd(emis, lengths, trans, dur, None, 0, flags, workspace=ws)
+    acc, mis = sb.semicrf_scan_report(ws, w.B, w.T, w.K, w.C, 0, kind)
+    ref = sb.semicrf_fwd_bwd(emis, lengths, trans, dur)
+    torch.cuda.synchronize()
+    assert np.all(acc.cpu().numpy() == 1) and float(mis.max()) <= 1e-10
+    r = oracle.fwd_bwd(w.emis, w.lengths, w.trans, w.dur)
+    assert_outputs_match_oracle([o.double().cpu().numpy() for o in out], r)
+    for a, b in zip(out, ref):
+        assert (a.double() - b.double()).abs().max().item() <= 2e-6 * max(1.0, b.double().abs().max().item())
+    assert ws.numel() < 0.7 * sb.semicrf_workspace_bytes(w.B, w.T, w.K, w.C, 0, 1)
+
+
+def test_sequence_report_range_flag_and_double_logz():
+    """semicrf_seq_report: logZ in fp64 as the forward scan computed it, and the flag of sequences whose scores
+    exceed the range the scaled recurrences are built for (300 nats per position)."""
+    B, T, K, C = 3, 400, 6, 5
+    w = synth.small_random(91, B, T, K, C, ragged=False)
+    w.emis[1, 100, 2] = 5000.0            # one position that no scaling block can hold
+    emis, lengths, trans, dur = to_dev(w)
+    ws = sb.alloc_workspace(B, T, K, C, 0, 1, DEV)
+    out = sb.semicrf_fwd_bwd(emis, lengths, trans, dur, workspace=ws)
+    rng, lz64 = sb.semicrf_seq_report(ws, B, T, K, C, 0, 1)
+    torch.cuda.synchronize()
+    assert rng.cpu().numpy().tolist() == [0, 1, 0]
+    r = oracle.fwd_bwd(w.emis, w.lengths, w.trans, w.dur)
+    lz = lz64.cpu().numpy()
+    for b in (0, 2):
+        assert abs(lz[b] - r.logz[b]) <= 1e-9 * max(1.0, abs(r.logz[b]))
+        assert np.float32(lz[b]) == out[0].cpu().numpy()[b]
+    # forward-only calls leave the same fields
+    fws = sb.alloc_workspace(B, T, K, C, 0, 0, DEV)
+    sb.semicrf_logz_fwd(emis, lengths, trans, dur, workspace=fws)
+    rng2, lz2 = sb.semicrf_seq_report(fws, B, T, K, C, 0, 0)
+    torch.cuda.synchronize()
+    assert rng2.cpu().numpy().tolist() == [0, 1, 0]
+    assert np.array_equal(lz2.cpu().numpy()[[0, 2]], lz[[0, 2]])
