@@ -364,6 +364,20 @@ def main():
                          "accepted_by": accepted_summary(a), "boundary_mismatch_max": e})
         pb.set_transitions(w.trans)
         rec["transition_model_sensitivity"] = sens
+        # the low-memory plan on the same workload: milliseconds and bytes of both plans side by side
+        pl = Problem(w, 0, sb.SEMICRF_CENTER | sb.SEMICRF_LOW_MEMORY, dev)
+        m, st, a, e = pl.time_fwd_bwd(3, 1)
+        rec["memory_plans"] = {
+            "default": {"ms_per_step": ms_step, "workspace_bytes": pb.ws_bytes,
+                        "forward_only_workspace_bytes": sb.semicrf_workspace_bytes(B, T, K, C, args.ckpt_interval, 0),
+                        "ckpt_interval": sb.semicrf_ckpt_interval(B, T, K, C, args.ckpt_interval)},
+            "low_memory": {"ms_per_step": m, "workspace_bytes": pl.ws_bytes,
+                           "forward_only_workspace_bytes": sb.semicrf_workspace_bytes(B, T, K, C, 0, sb.PLAN_LOW_MEMORY),
+                           "ckpt_interval": sb.semicrf_ckpt_interval_low_memory(B, T, K, C, 0),
+                           "stage_ms": {"prefix": st[0], "scans": st[1], "intervals": st[2], "finalise": st[3]},
+                           "accepted_by": accepted_summary(a)},
+            "emission_bytes": B * T * C * 4}
+        del pl
         del pb, emis, lengths, trans, dur, ws
         torch.cuda.empty_cache()
         # the other configurations, each whole

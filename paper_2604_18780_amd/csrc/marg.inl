@@ -272,3 +272,228 @@ __global__ __launch_bounds__(NT) void k_mg_te(Params p)
         p.sumR[((size_t)b * N + iv) * C + tid] = sR;
     }
 }
+
+// ---------------------------------------------------------------------------
+// The same statistics for short maximal durations (K < 128), where a whole interval's work fits one wave:
+// One wave per (sequence, interval), the lane organisation of the interval kernel (lane (g, c): label c,
+// durations g*NK + 1 ..): the wave walks the interval from its upper end downwards, as the backward scan did,
+// but takes p_t and v_t from that scan's stored rows instead of running the recurrence.  The K-deep window of
+// v rows slides through LDS in the frame of the current scaling block (rescaled by the same powers of two at the
+// same positions as in the scan, read off the stored scales), so the duration statistics are NK multiply-adds
+// per position and lane with every window entry read once per block of MB positions; the transition statistics
+// run on the matrix cores, four positions per v_mfma_f64_16x16x4; the emission sums are running sums.  Nothing
+// in the loop depends on the previous position: the rows of the next block are requested before the current one is worked on.  Partials go where the interval kernels put theirs (partD, partTr, grad_emis, tot, sumR).
+template <int CT, int NKW>
+__global__ __launch_bounds__(64) void k_mg_wave(Params p)
+{
+    using G = WaveWin<CT, NKW>;
+    constexpr int CTP = G::CTP, RS = G::RS, NK = G::NK, KW = G::KW, M = G::M, RTOT = G::RTOT, TRN = G::TRN;
+    typedef double double4_t __attribute__((ext_vector_type(4)));
+    extern __shared__ double lds_raw[];
+    double *ring = lds_raw;  // [ROWS][RS] (+ pad), then 64 doubles nobody reads
+    const int lane = threadIdx.x;
+    const int K = p.K, C = p.C, KC = K * C, CC = C * C, N = p.N, Delta = p.Delta;
+    const int b = blockIdx.x / N, iv = blockIdx.x % N;
+    const SeqHdr h = p.hdr[b];
+    const int L = h.L, J = h.J, Jm = J - 1;
+    const int t0 = iv * Delta;
+    if (t0 >= L) return;
+    if (!(p.spec_ok[b * 2] && p.spec_ok[b * 2 + 1])) return;  // the interval kernel takes this sequence
+    const int t1 = min(t0 + Delta, L);
+    const int c = lane % CTP, g = lane / CTP;
+    const bool cval = c < C;
+    const int cc = cval ? c : 0;
+    const bool writer = cval && g == 0;  // one lane per label
+    const int pj = lane >> 4, pl = lane & 15;  // matrix-core operands: position pj of the block, label pl of the tile
+    const size_t row0 = (size_t)b * (p.T + 1);
+    const double2 *EIc = p.EI + row0 * C + cc;
+    const int *nbc = p.nbase + row0 * C + cc;
+    const size_t slot = (size_t)b * N + iv;
+    const double2 *arow = (const double2 *)p.aloc + slot * Delta * C;  // (a_t, q_t) of position t0 + i at i*C
+    const double2 *brow = (const double2 *)p.bloc + slot * Delta * C;  // (p_t, v_t)
+    const double *arowY = p.alocY + slot * Delta;
+    const double *browY = p.blocY + slot * Delta;
+    const double logZ = h.logZ;
+    const double Y0 = p.ckYA[(size_t)b * (N + 1) + iv];
+    const double Ytop = t1 == L ? 0.0 : p.ckYB[(size_t)b * (N + 1) + iv + 1];
+
+    // ---- the window above the interval: the state the backward task started from
+    for (int i = lane; i < RTOT; i += 64) ring[i] = 0.0;
+    lds_wave_fence();
+    int r = M;  // row of the newest (lowest) position
+    if (t1 == L) {  // v_L = E_L
+        if (writer) ring[r * RS + c] = EIc[(size_t)L * C].x;
+    } else {
+        const double *ck = p.ckB + ((size_t)b * (N + 1) + iv + 1) * ((size_t)KC + C);
+        const int tm = t1 % K;
+        for (int i = lane; i < KC; i += 64) {
+            const int sl = i / C, col = i % C;
+            ring[(r + G::template slot_dist<true>(sl, tm, K)) * RS + col] = ck[i];
+        }
+    }
+    lds_wave_fence();
+
+    double dx[NK + MB - 1];  // sum_t q_t(c) kappa_t v_{t+k}(c), k = g*NK + jj + 1 (times W[k,c] at the end)
+    double dn[MB - 1];       // the same for k = 1..MB-1 from inside the blocks (lanes g == 0)
+    double4_t accT[TRN][TRN];
+#pragma unroll
+    for (int jj = 0; jj < NK + MB - 1; ++jj) dx[jj] = 0.0;
+#pragma unroll
+    for (int jj = 0; jj < MB - 1; ++jj) dn[jj] = 0.0;
+#pragma unroll
+    for (int i = 0; i < TRN; ++i)
+#pragma unroll
+        for (int o = 0; o < TRN; ++o) accT[i][o] = double4_t{0.0, 0.0, 0.0, 0.0};
+    double R = 0.0, sR = 0.0;
+    float *const sink = (float *)p.sink + lane;
+    float *const gout = p.grad_emis + ((size_t)b * p.T) * C + cc;
+
+    struct Rows {
+        double2 aq[MB], pv[MB], e[MB];  // this lane's label, the MB positions below tfrom
+        double aA[TRN], bB[TRN];        // operand elements: position pj of the block, label pl of tile tr
+        double ya, yb;                  // stored scales of the position just below tfrom (forward, backward)
+        int nd;                         // exponent step of this lane's label at the scaling-block boundary tfrom
+    };
+    // element offsets fit 32 bits: a slot has Delta*C < 2^27 elements (the plan's limits), a sequence (T+1)*C < 2^31
+    const double2 *const arc = arow + cc, *const brc = brow + cc, *const eic = EIc + (size_t)t0 * C;
+    int cpo[TRN];
+#pragma unroll
+    for (int tr = 0; tr < TRN; ++tr) cpo[tr] = min(tr * 16 + pl, C - 1);
+    auto request = [&](Rows &w, const int tfrom) {
+#pragma unroll
+        for (int i = 0; i < MB; ++i) {
+            const unsigned o = (unsigned)(max(tfrom - 1 - i, t0) - t0) * (unsigned)C;
+            w.aq[i] = arc[o];
+            w.pv[i] = brc[o];
+            w.e[i] = eic[o];
+        }
+        const unsigned o = (unsigned)(max(tfrom - 1 - pj, t0) - t0) * (unsigned)C;
+#pragma unroll
+        for (int tr = 0; tr < TRN; ++tr) {
+            w.aA[tr] = arow[o + cpo[tr]].x;
+            w.bB[tr] = brow[o + cpo[tr]].x;
+        }
+        // what a scaling-block boundary at tfrom needs, fetched with every block: a load inside the (rare)
+        // boundary branch would make the wave wait there for everything in flight
+        const int i0 = max(tfrom - 1 - t0, 0);
+        w.ya = arowY[i0];
+        w.yb = browY[i0];
+        const int jb = max(tfrom / J, 1);
+        const int hiE = nbc[(size_t)min(jb, L / J) * C], loE = nbc[(size_t)(jb - 1) * C];
+        w.nd = (tfrom / J >= 1 && (long)jb * J <= (long)L) ? hiE - loE : 0;
+    };
+    auto block_len = [&](const int t) { return min(min(t - t0, MB), ((t - 1) & Jm) + 1); };
+    // kappa(t,t) of the positions of a scaling block (they share both scales)
+    auto kappa_of = [&](const Rows &w) { return exp((Y0 + w.ya + Ytop + w.yb) * LN2 - logZ); };
+
+    int t = t1;
+    double kappa = 0.0;
+    double ybPrev = 0.0;  // stored scale (relative to the upper end) of the frame the window is in
+    const int rdoff = g * NK * RS + c;
+    // one block of positions from the rows in `w`; the next block's rows are requested into `wn` first
+    auto step = [&](const Rows &w, Rows &wn) {
+        const int nb = block_len(t);
+        request(wn, t - nb);
+        if (__builtin_expect((t & Jm) == 0, 0)) {
+            // the scan stepped into a new scaling block here: same shift of the window, read off its scales
+            G::rescale(ring, g, c, cval, w.nd - (int)(w.yb - ybPrev));
+            ybPrev = w.yb;
+            kappa = kappa_of(w);
+        }
+        if (__builtin_expect(r < MB, 0)) r = G::template move<true>(ring, lane, r);
+        double coef[MB];
+#pragma unroll
+        for (int i = 0; i < MB; ++i) coef[i] = (cval && i < nb) ? w.aq[i].y * kappa : 0.0;  // q_t(c) kappa
+        const double *base = ring + r * RS + rdoff;
+#pragma unroll
+        for (int jj = 0; jj < NK; ++jj) {
+            const double v = base[jj * RS];  // distance g*NK + jj from the newest
+#pragma unroll
+            for (int i = 0; i < MB; ++i) dx[jj + i] = fma(coef[i], v, dx[jj + i]);
+        }
+#pragma unroll
+        for (int i = 0; i < MB; ++i) {
+            const bool on = i < nb;
+            const int tt = t - 1 - i;
+            const double cg = g == 0 ? coef[i] : 0.0;
+#pragma unroll
+            for (int jn = 0; jn < i; ++jn) dn[i - 1 - jn] = fma(cg, w.pv[jn].y, dn[i - 1 - jn]);
+            // a segment of this label starts at tt (z p, z = q ES) / ends at tt (a b, b = v IE; none ends at 0)
+            const double d = on ? (w.aq[i].y * w.e[i].x * w.pv[i].x -
+                                   (tt >= 1 ? w.aq[i].x * w.pv[i].y * w.e[i].y : 0.0)) * kappa : 0.0;
+            float *dst = (on && writer) ? gout + (unsigned)tt * (unsigned)C : sink;
+            *dst = (float)R;
+            sR += on ? R : 0.0;
+            R += d;
+            // v_t(c) enters the window; beyond the block's end the store goes to the pad behind the buffer
+            double *rdst = (on && writer) ? ring + (r - 1 - i) * RS + c : ring + RTOT + lane;
+            *rdst = w.pv[i].y;
+        }
+        r -= nb;
+        lds_wave_fence();
+        {
+            const bool on = pj < nb;
+#pragma unroll
+            for (int tr = 0; tr < TRN; ++tr) {
+                const double a = (on && tr * 16 + pl < C) ? w.aA[tr] * kappa : 0.0;
+#pragma unroll
+                for (int tc = 0; tc < TRN; ++tc) {
+                    const double bb = (on && tc * 16 + pl < C) ? w.bB[tc] : 0.0;
+                    accT[tr][tc] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, bb, accT[tr][tc], 0, 0, 0);
+                }
+            }
+        }
+        t -= nb;
+    };
+    Rows ra, rb;
+    request(ra, t);
+    kappa = kappa_of(ra);
+    while (t > t0) {
+        step(ra, rb);
+        if (t <= t0) break;
+        step(rb, ra);
+    }
+    // ---- partials of this task.  Duration sums: the strips of neighbouring lane groups overlap by MB-1
+    // durations; they are combined through LDS in a fixed order (own strip, then the neighbour's overlap, then
+    // the in-block terms) and scaled by W[k,c].
+    lds_wave_fence();
+    double *tmp = ring;  // [KW + MB - 1][CT], row m = duration m + 1
+    {
+        double *tl = tmp + g * NK * CT + c;
+        if (cval) {
+#pragma unroll
+            for (int jj = 0; jj < NK; ++jj) tl[jj * CT] = dx[jj];
+        }
+        if (cval && g == G::GW - 1) {
+#pragma unroll
+            for (int jj = NK; jj < NK + MB - 1; ++jj) tl[jj * CT] = 0.0;
+        }
+        lds_wave_fence();
+        if (cval) {
+#pragma unroll
+            for (int jj = NK; jj < NK + MB - 1; ++jj) tl[jj * CT] += dx[jj];
+        }
+        lds_wave_fence();
+        if (writer) {
+#pragma unroll
+            for (int jj = 0; jj < MB - 1; ++jj) tl[jj * CT] += dn[jj];
+        }
+        lds_wave_fence();
+    }
+    double *pD = p.partD + slot * KC;
+    for (int i = lane; i < KC; i += 64) pD[i] = p.W[i] * tmp[(i / C) * CT + i % C];
+    double *pT = p.partTr + slot * CC;
+#pragma unroll
+    for (int tr = 0; tr < TRN; ++tr)
+#pragma unroll
+        for (int tc = 0; tc < TRN; ++tc)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {  // tile element (4v + lane/16, lane%16)
+                const int src = tr * 16 + 4 * v + pj, dst = tc * 16 + pl;
+                if (src < C && dst < C) pT[(size_t)src * C + dst] = accT[tr][tc][v];
+            }
+    if (lane < C) {
+        p.tot[slot * C + lane] = R;
+        p.sumR[slot * C + lane] = sR;
+    }
+}

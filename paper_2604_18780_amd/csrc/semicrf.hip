@@ -1667,7 +1667,7 @@ __global__ __launch_bounds__(64 * interval_waves(CT, NKW)) void k_interval_wave(
 // One wave per task, no barriers, same register/LDS organisation as k_interval_wave.
 // ---------------------------------------------------------------------------
 constexpr double SPEC_TOL = 1e-10;
-constexpr int SPEC_RUN_MAX = 8;  // intervals one wave mends in a row in the repair attempt
+constexpr int SPEC_RUN_MAX = 2;  // intervals one wave mends in a row in the repair attempt
 
 // One scan task of the chunk-parallel scan, one wave (window and time blocking as above).
 // repair: the task restarts from the state its neighbour in scan order REACHED at their common boundary (no
@@ -1927,10 +1927,14 @@ __global__ __launch_bounds__(64) void k_spec_repair(Params p, int both)
     // A run of adjacent boundaries that disagreed is taken by ONE wave, the task that starts at the first of them
     // in scan order (its neighbour started from a verified or exact state, so what that neighbour reached is
     // right): it restarts from the reached state and goes on through the run's intervals one after the other,
-    // at most SPEC_RUN_MAX of them; a longer run stays open for the next attempt.  Every other task returns at once and keeps what it has.  Nothing in this kernel writes spec_err.
+    // at most SPEC_RUN_MAX of them; a longer run stays open for the next attempt.  Every other task returns at
+    // once and keeps what it has.  Nothing in this kernel writes spec_err.
     const int L = p.hdr[b].L;
     const int nint = (L + p.Delta - 1) / p.Delta;
     const double *err = p.spec_err + ((size_t)b * 2 + dir) * (p.N + 1);
+    // Mending is sequential work, one wave per run: it pays for a few isolated disagreements (a stretch of
+    // uninformative input), not for a model that forgets slowly everywhere; that goes to the long warm-up.
+    if (p.spec_lr[((size_t)b * 2 + dir) * (p.N + 1)] > (double)max(2, nint / 16)) return;
     auto bad = [&](const int m) { return m >= 1 && m <= nint - 1 && !(err[m] <= SPEC_TOL); };
     if (!bad(dir ? j + 1 : j) || bad(dir ? j + 2 : j - 1)) return;
     int jj = j;
@@ -2015,9 +2019,12 @@ __global__ __launch_bounds__(64) void k_spec_fix(Params p, int ndir, int tier, i
     // i-th boundary in scan order: ascending for the forward scan, descending for the backward one
     auto jof = [&](int i) { return dir == 0 ? 1 + i : nint - 1 - i; };
     double s = 0.0, worst = 0.0;
+    int nbad = 0;  // boundaries that disagreed
     for (int i = i0; i < i1; ++i) {
         s += p.spec_lr[so + jof(i)];
-        worst = fmax(worst, p.spec_err[so + jof(i)]);
+        const double e = p.spec_err[so + jof(i)];
+        worst = fmax(worst, e);
+        nbad += !(e <= SPEC_TOL);
     }
     double inc = s;
 #pragma unroll
@@ -2026,7 +2033,10 @@ __global__ __launch_bounds__(64) void k_spec_fix(Params p, int ndir, int tier, i
         if (lane >= off) inc += v;
     }
 #pragma unroll
-    for (int off = 1; off < 64; off <<= 1) worst = fmax(worst, __shfl_xor(worst, off));
+    for (int off = 1; off < 64; off <<= 1) {
+        worst = fmax(worst, __shfl_xor(worst, off));
+        nbad += __shfl_xor(nbad, off);
+    }
     const double total = __shfl(inc, 63);
     // accepted or not (the same in every lane): every boundary within the bound, and a finite logZ
     bool ok = worst <= SPEC_TOL;
@@ -2057,7 +2067,8 @@ __global__ __launch_bounds__(64) void k_spec_fix(Params p, int ndir, int tier, i
         if (dir == 0 && nint > 0 && lane < C) p.inL[(size_t)b * C + lane] = vL / sumL;
     }
     if (lane != 0) return;
-    p.spec_err[so] = worst;  // entry 0 is no boundary: it carries the report value
+    p.spec_err[so] = worst;  // entry 0 is no boundary: it carries the report value,
+    p.spec_lr[so] = (double)nbad;  // and this one the number of boundaries that disagreed (read by the repair attempt)
     if (dir == 0 && ok) {
         p.hdr[b].logZ = lz;
         p.logz[b] = (float)lz;
@@ -3162,6 +3173,41 @@ struct StageTimer {
     }
 };
 
+// Marginals from the stored rows of both scans: one wave per (sequence, interval).
+template <int CT, int NKW>
+int launch_mg_k(const Params &p, hipStream_t st)
+{
+    const size_t lds = (wave_lds_doubles(CT, NKW) + 64) * sizeof(double);
+    if (lds > LDS_LIMIT) return SEMICRF_EUNSUPPORTED;
+    if (hipFuncSetAttribute((const void *)k_mg_wave<CT, NKW>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds) != hipSuccess)
+        return SEMICRF_ELAUNCH;
+    hipLaunchKernelGGL((k_mg_wave<CT, NKW>), dim3(p.B * p.N), dim3(64), lds, st, p);
+    return SEMICRF_OK;
+}
+
+template <int CT>
+int launch_mg_ct(const Params &p, hipStream_t st)
+{
+    const int GW = 64 / pow2_ge8(CT);
+    const int per_lane = (p.K + GW - 1) / GW;
+    if (per_lane <= 16) return launch_mg_k<CT, 16>(p, st);
+    if (per_lane <= 32) return launch_mg_k<CT, 32>(p, st);
+    if (per_lane <= 64) return launch_mg_k<CT, 64>(p, st);
+    return SEMICRF_EUNSUPPORTED;  // the plan has row slots only where the chunk-parallel scans apply
+}
+
+int launch_mg(const Params &p, hipStream_t st)
+{
+    const int C = p.C;
+    if (C <= 8) return launch_mg_ct<8>(p, st);
+    if (C <= 16) return launch_mg_ct<16>(p, st);
+    if (C <= 24) return launch_mg_ct<24>(p, st);
+    if (C <= 32) return launch_mg_ct<32>(p, st);
+    if (C <= 64) return launch_mg_ct<64>(p, st);
+    return SEMICRF_EUNSUPPORTED;
+}
+
 int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hipStream_t st,
         int mode /*0 cum, 1 logz, 2 fwd_bwd*/, StageTimer *tm = nullptr)
 {
@@ -3189,8 +3235,8 @@ int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hi
     // Marginals from the stored rows of both scans: where the plan has the row slots and no
     // boundary-term output is asked for (those come from the interval kernels).
     p.marg = pl.rows && p.fuse && !p.g_proj_start && !p.g_proj_end && !p.g_pi_start && !p.g_pi_end && !p.bdy_post;
-    const size_t mg_lds_d = pl.lds_mg_dur, mg_lds_t = pl.lds_mg_te;
-    const int mg_nsl = (p.K + MG_KS - 1) / MG_KS;
+    if (p.K < 128 && ((double)p.T + 1.0) * (double)p.C >= 2147483648.0)
+        p.marg = 0;  // the one-wave kernel indexes a sequence's rows with 32 bits
     T.mark();
     rc = launch_prep(p, st);
     T.mark();
@@ -3214,17 +3260,23 @@ int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hi
     T.mark();
     rc = check_launch();
     if (rc != SEMICRF_OK || mode == 1) return rc;
-    if (p.marg) {
+    if (p.marg && p.K < 128) {
+        // one wave per (sequence, interval): measured 0.29 ms against 0.31 ms for the two kernels below at
+        // K = 64, C = 24 (1024 tasks), 0.65 ms against 0.39 ms at K = 512, C = 8 (511 tasks: half the chip idle)
+        rc = launch_mg(p, st);
+        if (rc != SEMICRF_OK) return rc;
+    } else if (p.marg) {
+        const int mg_nsl = (p.K + MG_KS - 1) / MG_KS;
         if (hipFuncSetAttribute((const void *)k_mg_dur, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)mg_lds_d) != hipSuccess)
+                                (int)pl.lds_mg_dur) != hipSuccess)
             return SEMICRF_ELAUNCH;
         int ntd = (p.C * mg_nsl + 63) / 64 * 64;
         if (ntd < NT) ntd = NT;  // the extra threads help staging the rows
         if (hipFuncSetAttribute((const void *)k_mg_te, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)mg_lds_t) != hipSuccess)
+                                (int)pl.lds_mg_te) != hipSuccess)
             return SEMICRF_ELAUNCH;
-        hipLaunchKernelGGL(k_mg_dur, dim3(p.B * p.N), dim3(ntd), mg_lds_d, st, p);
-        hipLaunchKernelGGL(k_mg_te, dim3(p.B * p.N), dim3(NT), mg_lds_t, st, p);
+        hipLaunchKernelGGL(k_mg_dur, dim3(p.B * p.N), dim3(ntd), pl.lds_mg_dur, st, p);
+        hipLaunchKernelGGL(k_mg_te, dim3(p.B * p.N), dim3(NT), pl.lds_mg_te, st, p);
     }
     // the interval kernels: everything without the stored rows, else only what those kernels left
     rc = launch_interval(p, pl, st);

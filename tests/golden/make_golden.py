@@ -19,6 +19,13 @@ With ``--durtrans`` the oracle runs with the seeded duration-dependent transitio
 ``synth.duration_transitions`` (one matrix per duration) and the file is full_<name>_durtrans.npz
 (grad_trans is then [K,C,C]).
 
+Besides the random rows every file holds contiguous WINDOWS of rows (float32): around eight
+boundaries of the checkpoint intervals (j*interval - K .. j*interval + K, where the chunk-parallel
+scans hand over from one task to the next) and around four multiples of 32 that are no interval
+boundary (where the scaling blocks of every length end).  The interval lengths are those the
+library's planner reports for these shapes (INTERVALS below; the GPU tests check that they still
+are, and fail if this file has to be run again).
+
 Output: tests/golden/full_<name>.npz (float64 arrays, a few hundred KB each).
 """
 import os
@@ -34,6 +41,38 @@ import oracle  # noqa: E402
 from paper_2604_18780_amd import synth  # noqa: E402
 
 NSAMPLE = 1024
+# checkpoint interval of the default plan per workload (semicrf_ckpt_interval / semicrf_durtrans_ckpt_interval)
+INTERVALS = {"speech": 64, "genomic": 392, "longgen": 784, "genomic--durtrans": 784}
+
+
+def windows(w, interval):
+    """(b, first token, length) of the stored windows: 8 interval boundaries +- K and 4 multiples of 32
+    +- 8 that are no interval boundary, spread over the sequences and along them."""
+    out = []
+    seqs = [b for b in range(w.B) if int(w.lengths[b]) > 2 * interval]
+    for i in range(8):
+        b = seqs[i % len(seqs)]
+        L = int(w.lengths[b])
+        nint = (L + interval - 1) // interval
+        j = 1 + (i * 7919 + 3 * b) % (nint - 1)                 # boundaries 1 .. nint-1
+        lo = max(0, j * interval - w.K)
+        hi = min(L, j * interval + w.K)
+        out.append((b, lo, hi - lo))
+    for i in range(4):
+        b = seqs[(i + 1) % len(seqs)]
+        L = int(w.lengths[b])
+        m = 32 * (1 + (i * 104729 + 17) % (L // 32 - 1))
+        while m % interval == 0:
+            m += 32
+        lo = max(0, m - 8)
+        hi = min(L, m + 8)
+        out.append((b, lo, hi - lo))
+    return np.array(out, dtype=np.int64)
+
+
+def window_values(a, win):
+    """Rows of `a` [B,T,C] inside the windows, concatenated, as float32."""
+    return np.concatenate([a[b, lo:lo + n] for b, lo, n in win], 0).astype(np.float32)
 
 
 def sample_rows(w, seed=12345):
@@ -83,6 +122,10 @@ def main(args):
                          bdy_post_total=np.array([r.bdy_post.sum()]))
         out = os.path.join(os.path.dirname(os.path.abspath(__file__)),
                            f"full_{name}{'_durtrans' if durtrans else ('_boundary' if boundary else '')}.npz")
+        interval = INTERVALS[name + ("--durtrans" if durtrans else "")]
+        win = windows(w, interval)
+        extra.update(interval=np.array([interval]), windows=win, pos_marg_windows=window_values(r.pos_marg, win),
+                     grad_emis_windows=window_values(r.grad_emis, win))
         np.savez_compressed(
             out, logz=r.logz, grad_trans=r.grad_trans, grad_dur=r.grad_dur, rows=rows,
             pos_marg_rows=r.pos_marg[rows[:, 0], rows[:, 1]],

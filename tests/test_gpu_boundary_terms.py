@@ -173,6 +173,8 @@ def test_full_size_genomic_with_boundary_terms_against_stored_oracle_values():
     for name in ("grad_trans", "grad_dur", "grad_pi_start", "grad_pi_end"):
         err = np.abs(out[name].double().cpu().numpy() - g[name]).max()
         assert err <= 1e-4 * max(1.0, np.abs(g[name]).max()), (name, err)
+    from golden_windows import check_windows
+    check_windows(g, sb.semicrf_ckpt_interval(w.B, w.T, w.K, w.C), out["pos_marg"], out["grad_emis"])
     # over all rows: one start and one end per segment; boundary mass = segments + sequences
     nseg = out["grad_dur"].double().sum().item()
     assert abs(out["grad_proj_start"].double().sum().item() - nseg) <= 1e-5 * nseg

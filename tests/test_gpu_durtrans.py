@@ -188,6 +188,8 @@ def test_full_size_genomic_against_stored_oracle_values():
     assert e_pm <= 1e-4 and e_ge <= 1e-4
     assert e_t <= 1e-4 * max(1.0, np.abs(g["grad_trans"]).max())
     assert e_d <= 1e-4 * max(1.0, np.abs(g["grad_dur"]).max())
+    from golden_windows import check_windows
+    check_windows(g, sb.semicrf_durtrans_ckpt_interval(w.B, w.T, w.K, w.C), pm, g_e)
     row_sum = pm.double().sum(-1)
     assert (row_sum - 1.0).abs().max().item() <= 1e-5              # every token of this workload is valid
     assert abs(g_t.double().sum().item() - g_d.double().sum().item()) <= 1e-5 * g_d.double().sum().item()

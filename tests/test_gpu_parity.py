@@ -306,6 +306,9 @@ import os
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
 
+from golden_windows import check_windows  # noqa: E402
+
+
 @pytest.mark.parametrize("name", ["speech", "genomic", "longgen"])
 def test_full_size_workload_against_stored_oracle_values(name):
     path = os.path.join(GOLDEN, f"full_{name}.npz")
@@ -333,6 +336,7 @@ def test_full_size_workload_against_stored_oracle_values(name):
     assert e_pm <= 1e-4 and e_ge <= 1e-4
     assert e_t <= 1e-4 * max(1.0, np.abs(g["grad_trans"]).max())
     assert e_d <= 1e-4 * max(1.0, np.abs(g["grad_dur"]).max())
+    check_windows(g, sb.semicrf_ckpt_interval(w.B, w.T, w.K, w.C), pm, g_e)
     # properties over ALL rows: each valid token's label posterior sums to one,
     # padding carries no mass, total mass = number of valid tokens
     row_sum = pm.double().sum(-1)
