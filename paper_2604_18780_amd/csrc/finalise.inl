@@ -1,0 +1,213 @@
+// Fixed-order reductions of the gradient formulas: per-sequence sums, the emission gradient and the position marginals.
+// Included by semicrf.hip inside its anonymous namespace (after common.h); not a translation unit of its own.
+
+// ---------------------------------------------------------------------------
+// Finalisation (fixed-order reductions).
+// ---------------------------------------------------------------------------
+// carry[b,i,c] = sum_{i'<=i} tot[b,i',c];  mean[b,c] = (1/L) sum_u pm[b,u,c].  grid B, NT threads:
+// the intervals are split into G = NT/C contiguous chunks, one per thread group; chunk sums are
+// combined in chunk order, so the result does not depend on the launch shape.
+__device__ __forceinline__ void fin_seq_body(const Params &p, const int b)
+{
+    __shared__ double gsum[NT];
+    __shared__ double gtot[NT];
+    const int C = p.C, N = p.N, tid = threadIdx.x;
+    const int L = p.hdr[b].L;
+    const int nint = (L + p.Delta - 1) / p.Delta;
+    const int G = NT / C;
+    const int g = tid / C, c = tid % C;
+    const int per = (nint + G - 1) / G;
+    const int i0 = min(g * per, nint), i1 = min(i0 + per, nint);
+    const bool act = g < G;
+    double loc = 0.0;
+    if (act) {
+#pragma unroll 8
+        for (int i = i0; i < i1; ++i) loc += p.tot[((size_t)b * N + i) * C + c];
+    }
+    gsum[tid] = loc;
+    __syncthreads();
+    double run = 0.0, total = 0.0;
+    if (act) {
+        for (int gg = 0; gg < g; ++gg) run += gsum[gg * C + c];
+#pragma unroll 8
+        for (int i = i0; i < i1; ++i) {
+            const size_t o = ((size_t)b * N + i) * C + c;
+            run += p.tot[o];
+            p.carry[o] = run;
+            const int n = min(p.Delta, L - i * p.Delta);
+            total += (double)n * run - p.sumR[o];
+        }
+    }
+    gtot[tid] = total;
+    __syncthreads();
+    if (tid < C) {
+        double t = 0.0;
+        for (int gg = 0; gg < G; ++gg) t += gtot[gg * C + tid];
+        p.mean[(size_t)b * C + tid] = (p.center && L > 0) ? t / (double)L : 0.0;
+    }
+    // boundary posterior: certain at both ends of the sequence, nothing beyond it (the interval
+    // kernels wrote positions 1 .. L-1)
+    if (p.bdy_post) {
+        float *bd = p.bdy_post + (size_t)b * (p.T + 1);
+        for (int t = tid; t <= p.T; t += NT)
+            if (t == 0 || t >= L) bd[t] = (t == 0 || t == L) ? 1.f : 0.f;
+    }
+}
+
+// Gradients of the scalar sequence boundaries: sums over sequences, in sequence order, of the
+// mass of the segments that start at position 0 / end at position L.  One workgroup.
+__device__ __forceinline__ void fin_pi_body(const Params &p)
+{
+    const int c = threadIdx.x;
+    if (c >= p.C) return;
+    double gs = 0.0, ge = 0.0;
+    for (int b = 0; b < p.B; ++b) {
+        if (p.hdr[b].L < 1) continue;
+        const double w = p.grad_logz ? (double)p.grad_logz[b] : 1.0;
+        gs = fma(w, p.out0[(size_t)b * p.C + c], gs);
+        ge = fma(w, p.inL[(size_t)b * p.C + c], ge);
+    }
+    if (p.g_pi_start) p.g_pi_start[c] = (float)gs;
+    if (p.g_pi_end) p.g_pi_end[c] = (float)ge;
+}
+
+// grad_emis / pos_marg, elementwise over (u,c) of one sequence.  grid (blocks, B).
+__global__ __launch_bounds__(NT) void k_fin_emis(Params p)
+{
+    const int b = blockIdx.y, C = p.C;
+    const int L = p.hdr[b].L;
+    const double w = p.grad_logz ? (double)p.grad_logz[b] : 1.0;
+    const size_t n = (size_t)p.T * C;  // elements of one sequence
+    const size_t base = (size_t)b * n;
+    const double *carry = p.carry + ((size_t)b * p.N) * C;
+    const double *mean = p.mean + (size_t)b * C;
+    auto one = [&](const size_t idx, const int u, const int c) {
+        float ge = 0.f, pmv = 0.f;
+        if (u < L) {
+            const int i = u / p.Delta;
+            const double pm = carry[(size_t)i * C + c] - (double)p.grad_emis[base + idx];
+            ge = (float)(w * (pm - mean[c]));
+            pmv = (float)pm;
+        }
+        p.grad_emis[base + idx] = ge;
+        if (p.pos_marg) p.pos_marg[base + idx] = pmv;
+        // boundary projections: rows beyond the sequence are zero; the last token's end score
+        // belongs to the segments that end at position L
+        if (p.g_proj_start && u >= L) p.g_proj_start[base + idx] = 0.f;
+        if (p.g_proj_end && u >= L - 1)
+            p.g_proj_end[base + idx] = u == L - 1 ? (float)(w * p.inL[(size_t)b * C + c]) : 0.f;
+    };
+    if (n < ((size_t)1 << 31)) {  // 32-bit index arithmetic
+        const unsigned n32 = (unsigned)n, step = gridDim.x * NT;
+        for (unsigned idx = blockIdx.x * NT + threadIdx.x; idx < n32; idx += step) {
+            const unsigned u = idx / (unsigned)C;
+            one(idx, (int)u, (int)(idx - u * (unsigned)C));
+        }
+    } else {
+        for (size_t idx = (size_t)blockIdx.x * NT + threadIdx.x; idx < n; idx += (size_t)gridDim.x * NT)
+            one(idx, (int)(idx / C), (int)(idx % C));
+    }
+}
+
+// grad_trans[c',c] = Etr[c',c] * sum_b w_b sum_i partTr;  grad_dur[k,c] = sum_b w_b sum_i partD.
+// One workgroup per 32 outputs; 8 thread groups take the intervals i = g, g+8, ... and their
+// sums are combined in group order (fixed order for a given problem).
+__device__ __forceinline__ void fin_params_body(const Params &p, const int blk)
+{
+    __shared__ double red[NT];
+    const int C = p.C, CC = C * C, KC = p.K * C, N = p.N, tid = threadIdx.x;
+    const int o = tid & 31, g = tid >> 5;
+    const int idx = blk * 32 + o;
+    const bool ok = idx < CC + KC;
+    double acc = 0.0;
+    if (ok) {
+        for (int b = 0; b < p.B; ++b) {
+            const int L = p.hdr[b].L;
+            const int nint = (L + p.Delta - 1) / p.Delta;
+            const double w = p.grad_logz ? (double)p.grad_logz[b] : 1.0;
+            const size_t stride = idx < CC ? (size_t)CC : (size_t)KC;
+            const double *q = idx < CC ? p.partTr + ((size_t)b * N) * CC + idx
+                                       : p.partD + ((size_t)b * N) * KC + (idx - CC);
+            double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+            int i = g;
+            for (; i + 24 < nint; i += 32) {
+                s0 += q[(size_t)i * stride];
+                s1 += q[(size_t)(i + 8) * stride];
+                s2 += q[(size_t)(i + 16) * stride];
+                s3 += q[(size_t)(i + 24) * stride];
+            }
+            for (; i < nint; i += 8) s0 += q[(size_t)i * stride];
+            acc = fma(w, (s0 + s1) + (s2 + s3), acc);
+        }
+    }
+    red[tid] = acc;
+    __syncthreads();
+    if (ok && g == 0) {
+        double t = 0.0;
+        for (int gg = 0; gg < 8; ++gg) t += red[gg * 32 + o];
+        if (idx < CC) p.grad_trans[idx] = (float)(t * p.Etr[idx]);
+        else p.grad_dur[idx - CC] = (float)t;
+    }
+}
+
+// One launch for the two independent reductions: workgroups 0..B-1 per sequence, the rest
+// per 32 parameter gradients.
+__global__ __launch_bounds__(NT) void k_fin_seq(Params p)
+{
+    const int nparam = (p.C * p.C + p.K * p.C + 31) / 32;
+    if ((int)blockIdx.x < p.B) fin_seq_body(p, blockIdx.x);
+    else if ((int)blockIdx.x < p.B + nparam) fin_params_body(p, blockIdx.x - p.B);
+    else fin_pi_body(p);
+}
+
+// Entropies of the posteriors (the paper's boundary-entropy paragraph): per sequence,
+//   h_pos = (1/L) sum_{u<L} -sum_c pm[u,c] ln pm[u,c]          (mean per-position label entropy)
+//   h_bdy = -sum_{u<L} ph_u ln ph_u,  ph_u = bdy[u] / sum_{u'<L} bdy[u']   (entropy of the normalised
+//           segment-start distribution; a segment starts at token u iff a boundary falls at position u)
+// One workgroup per sequence; thread partial sums are combined in thread order.
+__global__ __launch_bounds__(NT) void k_entropies(const float *pos_marg, const float *bdy_post,
+                                                  const int32_t *lengths, int T, int C, float *h_pos,
+                                                  float *h_bdy)
+{
+    __shared__ double red[NT];
+    const int b = blockIdx.x, tid = threadIdx.x;
+    int L = lengths ? lengths[b] : T;
+    L = L < 0 ? 0 : (L > T ? T : L);
+    auto block_sum = [&](double v) {
+        red[tid] = v;
+        __syncthreads();
+        double s = 0.0;
+        if (tid == 0)
+            for (int i = 0; i < NT; ++i) s += red[i];
+        __syncthreads();
+        if (tid == 0) red[0] = s;
+        __syncthreads();
+        s = red[0];
+        __syncthreads();
+        return s;
+    };
+    if (h_pos) {
+        const float *pm = pos_marg + (size_t)b * T * C;
+        double acc = 0.0;
+        for (size_t i = tid; i < (size_t)L * C; i += NT) {
+            const double x = (double)pm[i];
+            if (x > 0.0) acc -= x * log(x);
+        }
+        const double tot = block_sum(acc);
+        if (tid == 0) h_pos[b] = L > 0 ? (float)(tot / (double)L) : 0.f;
+    }
+    if (h_bdy) {
+        const float *bd = bdy_post + (size_t)b * (T + 1);
+        double acc = 0.0;
+        for (int u = tid; u < L; u += NT) acc += (double)bd[u];
+        const double norm = block_sum(acc);
+        acc = 0.0;
+        for (int u = tid; u < L; u += NT) {
+            const double x = (double)bd[u] / norm;
+            if (x > 0.0) acc -= x * log(x);
+        }
+        const double tot = block_sum(acc);
+        if (tid == 0) h_bdy[b] = L > 0 ? (float)tot : 0.f;
+    }
+}
+
