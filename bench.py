@@ -186,7 +186,7 @@ def main():
     ap.add_argument("--trans-scale", type=float, default=0.0,
                     help="standard deviation of the transition scores (the recipe's is 0.1)")
     ap.add_argument("--trans-band", type=int, default=-1,
-                    help="forbid (score -30) transitions between labels further apart than this, cyclically")
+                    help="forbid (score -1e4) transitions between labels further apart than this, cyclically")
     ap.add_argument("--brief", action="store_true", help="only the headline workload: no other configurations, "
                                                         "entry points, model variants")
     ap.add_argument("--no-cpu-baseline", action="store_true")

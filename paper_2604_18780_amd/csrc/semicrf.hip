@@ -25,15 +25,17 @@
 // multiplications by powers of two at block boundaries.  logZ = Y ln 2 +
 // log(sum_c a_L(c)).
 //
-// Kernels: k_colsum (+ the exp tables), k_prep_seq, k_prefix (Eq. 1-2); k_spec, k_spec_cmp,
-// k_spec_fix (Algorithm 1 and the beta recurrence of Algorithm 3 as chunk-parallel scans
-// that are verified at every chunk boundary and write ring checkpoints every Delta
-// positions); k_scan_fast / k_scan (the same scans sequentially, for what the verification
-// rejects); k_interval_wave / k_interval (per checkpoint interval: recompute the forward
-// messages unless the scan stored them, run beta across the interval, accumulate the
-// expected sufficient statistics in registers/LDS, no global atomics); k_mg_dur / k_mg_te
-// (the same statistics as position-local products of the rows both scans stored, for long
-// maximal durations); k_fin_seq (+ the parameter gradients), k_fin_emis (fixed-order reductions).
+// Kernels (each group in its own include file, see below): k_colsum (+ the exp tables), k_prep_seq,
+// k_prefix (Eq. 1-2); k_spec, k_spec_repair, k_spec_cmp, k_spec_fix (Algorithm 1 and the beta
+// recurrence of Algorithm 3 as chunk-parallel scans that are verified at every chunk boundary and
+// write ring checkpoints every Delta positions; k_mscan in mscan.hip runs the same tasks sixteen at
+// a time on the matrix cores); k_scan_fast / k_scan (the same scans sequentially, for what the
+// verification rejects); k_interval_wave / k_interval (per checkpoint interval: recompute the forward
+// messages unless the scan stored them, run beta across the interval, accumulate the expected
+// sufficient statistics in registers/LDS, no global atomics); k_mg_dur / k_mg_te / k_mg_wave (the
+// same statistics from the rows both scans stored, without a third recurrence); k_fin_seq (+ the
+// parameter gradients), k_fin_emis (fixed-order reductions).  Interval choice and workspace layout:
+// plan.cpp (host only).
 #include <hip/hip_runtime.h>
 #include <float.h>
 #include <math.h>

@@ -159,11 +159,11 @@ def duration_transitions(w: Workload, seed: int = 777, sd: float = 0.1):
 
 
 def reshape_transitions(trans: np.ndarray, sd: float | None = None, band: int | None = None,
-                        forbidden: float = -30.0) -> np.ndarray:
+                        forbidden: float = -1.0e4) -> np.ndarray:
     """Other transition models on the same draw: scores rescaled from the recipe's N(0, 0.1^2) to
     N(0, sd^2), and / or every transition between labels further apart than `band` (cyclically)
-    set to `forbidden`.  A banded matrix with a large forbidden score mixes slowly: the case the
-    chunk-parallel scans' verification is there for."""
+    set to `forbidden` (an exact zero of exp(trans) in fp64).  A banded matrix mixes slowly: the case
+    the chunk-parallel scans' verification is there for."""
     out = trans.astype(np.float64)
     if sd is not None:
         out = out * (sd / 0.1)
