@@ -100,6 +100,12 @@ typedef enum {
  * results are the same up to rounding; the call is several times slower.  The workspace must have been sized
  * with want_grad + 8 (8 forward only, 9 gradients); not combinable with SEMICRF_MARGINALS_ROWS. */
 #define SEMICRF_LOW_MEMORY 256u
+/* flags bits 9 and 10: the chunk-parallel scan tasks run with two waves each (one runs the positions' dependent
+ * chains, one adds up the older window entries a block ahead) / with one wave each.  By default the library takes
+ * two waves where the window is deep or the label set large (more than 32 durations per lane, or C > 32), where
+ * that is the faster form.  Same results up to rounding; both at once are refused. */
+#define SEMICRF_TWO_WAVE_SCAN 512u
+#define SEMICRF_ONE_WAVE_SCAN 1024u
 /* flags bit 7 (semicrf_viterbi only): trace back by pointer doubling over all nodes, the route otherwise taken
  * only when an interval's nodes do not fit in LDS.  Same back-pointers, same path; for tests of that route. */
 #define SEMICRF_VITERBI_GLOBAL_TRACE 128u

@@ -32,6 +32,8 @@ SEMICRF_MARGINALS_ROWS = 32
 SEMICRF_MARGINALS_INTERVAL = 64
 SEMICRF_VITERBI_GLOBAL_TRACE = 128
 SEMICRF_LOW_MEMORY = 256
+SEMICRF_TWO_WAVE_SCAN = 512
+SEMICRF_ONE_WAVE_SCAN = 1024
 PLAN_LOW_MEMORY = 8   # added to want_grad for the workspace of SEMICRF_LOW_MEMORY calls
 
 

@@ -85,6 +85,7 @@ struct Params {
     int spec;           // chunk-parallel scan enabled for this call
     int mscan;          // its tasks may run sixteen at a time in lock step on the matrix cores
     double *sink;       // [1536] target of stores that must be issued but whose value nobody wants
+    int spec2;          // chunk-parallel scan tasks with two waves each (tip + helper): 0 where it pays, 1 always, 2 never
     int lowmem;         // low-memory plan: interval at the spacing of Algorithm 1, a few row slots per sequence
     int warm0;          // first warm-up length of the chunk-parallel scans asked for by the caller (0 = default)
     int marg_route;     // 0 automatic, 1 marginals from the stored rows of both scans, 2 per-interval recurrence

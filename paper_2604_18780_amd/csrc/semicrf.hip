@@ -63,6 +63,7 @@ using namespace semicrf_impl;
 #include "scan_seq.inl"   // sequential scans (fallback of the chunk-parallel ones)
 #include "interval.inl"   // Algorithm 3 body: per-interval recompute + marginals; one-wave window geometry
 #include "spec.inl"       // chunk-parallel scans with warm-up, repair and verification
+#include "spec2.inl"      // the same scan tasks with two waves per task (tip + helper)
 #include "viterbi.inl"    // max-semiring decode and trace-back
 #include "finalise.inl"   // fixed-order reductions of the gradient formulas
 #include "durtrans.inl"   // duration-dependent transitions
@@ -240,7 +241,17 @@ int launch_spec_k(const Params &p, hipStream_t st, bool both, int warm, int tier
         if (rc != SEMICRF_OK) return rc;
         rest = 1;
     }
-    if (warm > 0)
+    const size_t lds2 = spec2_lds_doubles<CT, NKW>() * sizeof(double);
+    // two waves per task where the window or the transition product is long next to a position's dependent chain
+    // (measured: longgen scans 1.27 -> 0.85 ms, speech 0.30 -> 0.25 ms; genomic 0.37 -> 0.41 ms, so not there)
+    const bool two = p.spec2 == 1 || (p.spec2 == 0 && (NKW == 64 || CT == 64));
+    if (warm > 0 && two && lds2 <= LDS_LIMIT) {
+        if (hipFuncSetAttribute((const void *)k_spec2<CT, NKW>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds2) != hipSuccess)
+            return SEMICRF_ELAUNCH;
+        hipLaunchKernelGGL((k_spec2<CT, NKW>), dim3(p.B * p.N * ndir), dim3(128), lds2, st, p, both ? 1 : 0,
+                           warm, tier, rest);
+    } else if (warm > 0)
         hipLaunchKernelGGL((k_spec<CT, NKW>), dim3(p.B * p.N * ndir), dim3(64), lds, st, p, both ? 1 : 0,
                            warm, tier, rest);
     else
@@ -754,6 +765,8 @@ int common_params(Params &p, const float *emis, const int32_t *lengths, const fl
     p.spec = (flags & SEMICRF_SEQUENTIAL_SCAN) ? 0 : 1;
     p.mscan = (flags & SEMICRF_MATRIX_SCAN) ? 1 : 0;
     p.lowmem = (flags & SEMICRF_LOW_MEMORY) ? 1 : 0;
+    if ((flags & SEMICRF_TWO_WAVE_SCAN) && (flags & SEMICRF_ONE_WAVE_SCAN)) return SEMICRF_EINVAL;
+    p.spec2 = (flags & SEMICRF_TWO_WAVE_SCAN) ? 1 : ((flags & SEMICRF_ONE_WAVE_SCAN) ? 2 : 0);
     p.marg_route = (flags & SEMICRF_MARGINALS_ROWS) ? 1 : ((flags & SEMICRF_MARGINALS_INTERVAL) ? 2 : 0);
     p.vit_global = (flags & SEMICRF_VITERBI_GLOBAL_TRACE) ? 1 : 0;
     p.warm0 = (int)(flags >> 16);
@@ -877,7 +890,11 @@ int semicrf_fwd_bwd_static(const float *emis, const int32_t *lengths, const floa
 {
     // sizes first: nothing is touched when the plan does not fit the static array
     size_t need = 0;
-    int rc = semicrf_workspace_bytes(B, T, K, C, ckpt_interval, 1, &need);
+    int rc = check_flags(flags);
+    if (rc != SEMICRF_OK) return rc;
+    const int kind = ((flags & SEMICRF_MARGINALS_ROWS) ? 3 : ((flags & SEMICRF_MARGINALS_INTERVAL) ? 2 : 1)) |
+                     ((flags & SEMICRF_LOW_MEMORY) ? PLAN_LOW_MEMORY : 0);
+    rc = semicrf_workspace_bytes(B, T, K, C, ckpt_interval, kind, &need);
     if (rc != SEMICRF_OK) return rc;
     if (need > (size_t)SEMICRF_STATIC_WORKSPACE_BYTES) return SEMICRF_EWORKSPACE;
     void *ws = nullptr;

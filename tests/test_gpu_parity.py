@@ -509,3 +509,28 @@ def test_sequence_report_range_flag_and_double_logz():
     torch.cuda.synchronize()
     assert rng2.cpu().numpy().tolist() == [0, 1, 0]
     assert np.array_equal(lz2.cpu().numpy()[[0, 2]], lz[[0, 2]])
+
+
+@pytest.mark.parametrize("waves", ["one", "two"])
+@pytest.mark.parametrize("seed,B,T,K,C,delta,scale", [
+    (101, 3, 300, 8, 6, 0, 1.0), (102, 2, 700, 33, 24, 64, 1.0), (103, 3, 257, 16, 64, 32, 1.0), (104, 2, 513, 3, 17, 40, 8.0),
+    (105, 2, 1500, 64, 24, 96, 8.0), (106, 2, 900, 130, 8, 0, 1.0), (107, 1, 1100, 512, 8, 0, 1.0), (108, 2, 50, 80, 4, 0, 30.0),
+    (109, 4, 130, 1, 7, 16, 1.0), (110, 2, 600, 40, 32, 0, 1.0),
+])
+def test_scan_tasks_with_one_and_with_two_waves(waves, seed, B, T, K, C, delta, scale):
+    """The chunk-parallel scan tasks in both forms (one wave; tip + helper) on shapes of every kernel variant:
+    verified at the first attempt, results as the oracle's, and the two forms agree to rounding."""
+    w = synth.small_random(seed, B, T, K, C, ragged=True, scale=scale)
+    w.lengths[0] = T
+    flag = sb.SEMICRF_ONE_WAVE_SCAN if waves == "one" else sb.SEMICRF_TWO_WAVE_SCAN
+    out, acc, mis = run_with_report(w, sb.SEMICRF_CENTER | flag, delta)
+    print(f"       accepted {acc.ravel()} boundary mismatch {mis.max():.1e}", flush=True)
+    assert np.all(acc == 1) and np.all(mis <= 1e-10)
+    r = oracle.fwd_bwd(w.emis, w.lengths, w.trans, w.dur)
+    assert_outputs_match_oracle(out, r)
+    other, _, _ = run_with_report(w, sb.SEMICRF_CENTER | (sb.SEMICRF_ONE_WAVE_SCAN | sb.SEMICRF_TWO_WAVE_SCAN) ^ flag, delta)
+    for a, b_ in zip(out, other):
+        assert np.abs(a - b_).max() <= 2e-6 * max(1.0, np.abs(b_).max())
+    emis, lengths, trans, dur = to_dev(w)
+    with pytest.raises(sb.SemiCRFError, match="-1"):
+        sb.semicrf_logz_fwd(emis, lengths, trans, dur, flags=sb.SEMICRF_ONE_WAVE_SCAN | sb.SEMICRF_TWO_WAVE_SCAN)
