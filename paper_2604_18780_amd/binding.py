@@ -268,9 +268,11 @@ def semicrf_logz_fwd_boundary(emis, lengths, trans, dur, proj_start=None, proj_e
 
 
 def semicrf_fwd_bwd_boundary(emis, lengths, trans, dur, grad_logz=None, proj_start=None, proj_end=None,
-                             pi_start=None, pi_end=None, ckpt_interval=0, flags=SEMICRF_CENTER, workspace=None):
+                             pi_start=None, pi_end=None, ckpt_interval=0, flags=SEMICRF_CENTER, workspace=None,
+                             boundary_outputs=True):
     """Returns a dict with logz, grad_emis, grad_trans, grad_dur, pos_marg, grad_proj_start,
-    grad_proj_end, grad_pi_start, grad_pi_end, bdy_post."""
+    grad_proj_end, grad_pi_start, grad_pi_end, bdy_post (the last five only with boundary_outputs:
+    the C entry point takes NULL for each output that is not wanted)."""
     B, T, C = emis.shape
     K = dur.shape[0]
     dev = emis.device
@@ -281,6 +283,9 @@ def semicrf_fwd_bwd_boundary(emis, lengths, trans, dur, grad_logz=None, proj_sta
     o = dict(logz=new(B), grad_emis=new(B, T, C), grad_trans=new(C, C), grad_dur=new(K, C), pos_marg=new(B, T, C),
              grad_proj_start=new(B, T, C), grad_proj_end=new(B, T, C), grad_pi_start=new(C), grad_pi_end=new(C),
              bdy_post=new(B, T + 1))
+    if not boundary_outputs:
+        for k in ("grad_proj_start", "grad_proj_end", "grad_pi_start", "grad_pi_end", "bdy_post"):
+            o[k] = None
     ep, flags = _emis(emis, flags)
     _check(load().semicrf_fwd_bwd_boundary(ep, _ptr(lengths, torch.int32), _ptr(trans, f32),
                                            _ptr(dur, f32), _ptr(grad_logz, f32), _ptr(proj_start, f32),
@@ -291,7 +296,7 @@ def semicrf_fwd_bwd_boundary(emis, lengths, trans, dur, grad_logz=None, proj_sta
                                                                  "pos_marg", "grad_proj_start", "grad_proj_end",
                                                                  "grad_pi_start", "grad_pi_end", "bdy_post")],
                                            _stream()))
-    return o
+    return {k: v for k, v in o.items() if v is not None}
 
 
 def semicrf_viterbi_workspace_bytes(B, T, K, C) -> int:

@@ -357,7 +357,11 @@ int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hi
     p.fuse = p.spec && mode == 2 && (size_t)p.B * pl.N <= (size_t)pl.nslot;  // one slot per task
     // Marginals from the stored rows of both scans: where the plan has the row slots and no
     // boundary-term output is asked for (those come from the interval kernels).
-    p.marg = pl.rows && p.fuse && !p.g_proj_start && !p.g_proj_end && !p.g_pi_start && !p.g_pi_end && !p.bdy_post;
+    // Their emission sums are formed from the stored pairs with ES * (1/ES) = 1, which start / end projections
+    // break; calls with boundary inputs or outputs go through the one-wave interval kernel.
+    const bool bterms = p.proj_start || p.proj_end || p.pi_start || p.pi_end || p.g_proj_start || p.g_proj_end ||
+                        p.g_pi_start || p.g_pi_end || p.bdy_post;
+    p.marg = pl.rows && p.fuse && !bterms;
     if (p.K < 128 && ((double)p.T + 1.0) * (double)p.C >= 2147483648.0)
         p.marg = 0;  // the one-wave kernel indexes a sequence's rows with 32 bits
     T.mark();

@@ -98,6 +98,30 @@ def test_each_term_alone_and_none():
         assert np.array_equal(o[name], t.double().cpu().numpy()), name
 
 
+@pytest.mark.parametrize("K,C,flags", [(130, 8, 0), (160, 5, 0), (12, 10, sb.SEMICRF_MARGINALS_ROWS)])
+def test_boundary_inputs_without_boundary_outputs_where_the_stored_row_marginals_would_apply(K, C, flags):
+    """Start / end projections as INPUTS only, at sizes where the marginals are otherwise formed from the stored
+    rows of both scans (K >= 128, or on request): those kernels rebuild the emission sums from the stored
+    (ES, 1/ES) pairs, which the projections change, so such calls must go through the interval kernel."""
+    w = synth.small_random(61, 2, 900, K, C, ragged=True)
+    w.lengths[0] = 900
+    ps, pe, pis, pie = make_terms(62, w)
+    flags |= sb.SEMICRF_CENTER
+    emis, lengths = dev(nan_pad(w.emis, w.lengths)), dev(w.lengths, np.int32)
+    o = sb.semicrf_fwd_bwd_boundary(emis, lengths, dev(w.trans), dev(w.dur), None, dev(nan_pad(ps, w.lengths)),
+                                    dev(nan_pad(pe, w.lengths)), dev(pis), dev(pie), 0, flags, boundary_outputs=False)
+    torch.cuda.synchronize()
+    assert set(o) == {"logz", "grad_emis", "grad_trans", "grad_dur", "pos_marg"}
+    r = oracle.fwd_bwd(w.emis, w.lengths, w.trans, w.dur, proj_start=ps, proj_end=pe, pi_start=pis, pi_end=pie,
+                       boundary=True)
+    g = {k: v.double().cpu().numpy() for k, v in o.items()}
+    assert np.abs(g["logz"] - r.logz).max() <= 1e-5 * max(1.0, np.abs(r.logz).max())
+    assert np.abs(g["pos_marg"] - r.pos_marg).max() <= 1e-4
+    assert np.abs(g["grad_emis"] - r.grad_emis).max() <= 1e-4
+    assert np.abs(g["grad_trans"] - r.grad_trans).max() <= 1e-4 * max(1.0, np.abs(r.grad_trans).max())
+    assert np.abs(g["grad_dur"] - r.grad_dur).max() <= 1e-4 * max(1.0, np.abs(r.grad_dur).max())
+
+
 def test_many_chunks_no_centering_and_sequential_fallback():
     w = synth.small_random(22, 2, 1500, 12, 10, ragged=True)
     w.lengths[:] = [1500, 1203]
