@@ -185,6 +185,7 @@ def main():
     ap.add_argument("--matrix-scan", action="store_true", help="chunk-parallel scans on the matrix cores")
     ap.add_argument("--scan-waves", type=int, default=0, choices=[0, 1, 2],
                     help="waves per chunk-parallel scan task (0: the library's choice)")
+    ap.add_argument("--extra-flags", type=lambda x: int(x, 0), default=0, help="further flag bits, as a number")
     ap.add_argument("--trans-scale", type=float, default=0.0,
                     help="standard deviation of the transition scores (the recipe's is 0.1)")
     ap.add_argument("--trans-band", type=int, default=-1,
@@ -221,7 +222,7 @@ def main():
     flags |= {"auto": 0, "rows": sb.SEMICRF_MARGINALS_ROWS, "interval": sb.SEMICRF_MARGINALS_INTERVAL}[args.marginals]
     if args.matrix_scan:
         flags |= sb.SEMICRF_MATRIX_SCAN
-    flags |= {0: 0, 1: sb.SEMICRF_ONE_WAVE_SCAN, 2: sb.SEMICRF_TWO_WAVE_SCAN}[args.scan_waves]
+    flags |= {0: 0, 1: sb.SEMICRF_ONE_WAVE_SCAN, 2: sb.SEMICRF_TWO_WAVE_SCAN}[args.scan_waves] | args.extra_flags
     w = synth.make(args.workload)
     if args.trans_scale > 0.0 or args.trans_band >= 0:
         w.trans = synth.reshape_transitions(w.trans, args.trans_scale or None,

@@ -96,11 +96,14 @@ struct Params {
     double *bloc;       // [nslot][Delta][2C] backward rows (p_t, v_t) of the chunk-parallel backward tasks
     double *blocY;      // [nslot][Delta]     their scale relative to the interval's upper end
     int marg;           // marginals from the stored rows of both scans (no recurrence in the interval stage)
-    double *partD;      // [B][N][K][C]
-    double *partTr;     // [B][N][C][C]
-    double *tot;        // [B][N][C]
-    double *sumR;       // [B][N][C]
-    double *carry;      // [B][N][C]
+    int msplit;         // parts per interval of the one-wave stored-row marginals; a sequence they handle has its partial
+                        // sums per part (index interval*msplit + part), any other per interval (index interval)
+    int NP;             // N * msplit: partial sums of a sequence in partD, partTr, tot, sumR, carry
+    double *partD;      // [B][NP][K][C]
+    double *partTr;     // [B][NP][C][C]
+    double *tot;        // [B][NP][C]
+    double *sumR;       // [B][NP][C]
+    double *carry;      // [B][NP][C]
     double *mean;       // [B][C]
     double *out0;       // [B][C]  mass of the segments that start at position 0, per label
     double *inL;        // [B][C]  mass of the segments that end at position L, per label

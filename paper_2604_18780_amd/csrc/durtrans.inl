@@ -548,8 +548,8 @@ __global__ __launch_bounds__(64) void k_dt_emis(Params p)
         }
     }
     if (act) {
-        p.tot[((size_t)b * N + j) * C + lane] = R;
-        p.sumR[((size_t)b * N + j) * C + lane] = sR;
+        p.tot[((size_t)b * p.NP + j) * C + lane] = R;
+        p.sumR[((size_t)b * p.NP + j) * C + lane] = sR;
     }
 }
 

@@ -4,6 +4,13 @@
 // ---------------------------------------------------------------------------
 // Finalisation (fixed-order reductions).
 // ---------------------------------------------------------------------------
+// Positions per partial sum of sequence b: an interval, or a part of one where the one-wave stored-row marginals
+// took the sequence (the condition under which that kernel works on it).
+__device__ __forceinline__ int stat_delta(const Params &p, const int b)
+{
+    return (p.msplit > 1 && p.spec_ok[b * 2] && p.spec_ok[b * 2 + 1]) ? p.Delta / p.msplit : p.Delta;
+}
+
 // carry[b,i,c] = sum_{i'<=i} tot[b,i',c];  mean[b,c] = (1/L) sum_u pm[b,u,c].  grid B, NT threads:
 // the intervals are split into G = NT/C contiguous chunks, one per thread group; chunk sums are
 // combined in chunk order, so the result does not depend on the launch shape.
@@ -11,9 +18,10 @@ __device__ __forceinline__ void fin_seq_body(const Params &p, const int b)
 {
     __shared__ double gsum[NT];
     __shared__ double gtot[NT];
-    const int C = p.C, N = p.N, tid = threadIdx.x;
+    const int C = p.C, N = p.NP, tid = threadIdx.x;
     const int L = p.hdr[b].L;
-    const int nint = (L + p.Delta - 1) / p.Delta;
+    const int Ds = stat_delta(p, b);
+    const int nint = (L + Ds - 1) / Ds;
     const int G = NT / C;
     const int g = tid / C, c = tid % C;
     const int per = (nint + G - 1) / G;
@@ -34,7 +42,7 @@ __device__ __forceinline__ void fin_seq_body(const Params &p, const int b)
             const size_t o = ((size_t)b * N + i) * C + c;
             run += p.tot[o];
             p.carry[o] = run;
-            const int n = min(p.Delta, L - i * p.Delta);
+            const int n = min(Ds, L - i * Ds);
             total += (double)n * run - p.sumR[o];
         }
     }
@@ -79,12 +87,13 @@ __global__ __launch_bounds__(NT) void k_fin_emis(Params p)
     const double w = p.grad_logz ? (double)p.grad_logz[b] : 1.0;
     const size_t n = (size_t)p.T * C;  // elements of one sequence
     const size_t base = (size_t)b * n;
-    const double *carry = p.carry + ((size_t)b * p.N) * C;
+    const double *carry = p.carry + ((size_t)b * p.NP) * C;
+    const int Ds = stat_delta(p, b);
     const double *mean = p.mean + (size_t)b * C;
     auto one = [&](const size_t idx, const int u, const int c) {
         float ge = 0.f, pmv = 0.f;
         if (u < L) {
-            const int i = u / p.Delta;
+            const int i = u / Ds;
             const double pm = carry[(size_t)i * C + c] - (double)p.grad_emis[base + idx];
             ge = (float)(w * (pm - mean[c]));
             pmv = (float)pm;
@@ -115,7 +124,7 @@ __global__ __launch_bounds__(NT) void k_fin_emis(Params p)
 __device__ __forceinline__ void fin_params_body(const Params &p, const int blk)
 {
     __shared__ double red[NT];
-    const int C = p.C, CC = C * C, KC = p.K * C, N = p.N, tid = threadIdx.x;
+    const int C = p.C, CC = C * C, KC = p.K * C, N = p.NP, tid = threadIdx.x;
     const int o = tid & 31, g = tid >> 5;
     const int idx = blk * 32 + o;
     const bool ok = idx < CC + KC;
@@ -123,7 +132,8 @@ __device__ __forceinline__ void fin_params_body(const Params &p, const int blk)
     if (ok) {
         for (int b = 0; b < p.B; ++b) {
             const int L = p.hdr[b].L;
-            const int nint = (L + p.Delta - 1) / p.Delta;
+            const int Ds = stat_delta(p, b);
+            const int nint = (L + Ds - 1) / Ds;
             const double w = p.grad_logz ? (double)p.grad_logz[b] : 1.0;
             const size_t stride = idx < CC ? (size_t)CC : (size_t)KC;
             const double *q = idx < CC ? p.partTr + ((size_t)b * N) * CC + idx

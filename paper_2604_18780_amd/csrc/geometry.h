@@ -22,6 +22,11 @@ constexpr int MB = 4;      // positions per time block of the one-wave kernels
 constexpr int MG_TG = 32;  // stored-row marginals: positions staged at a time
 constexpr int MG_KS = 8;   // stored-row marginals: durations per thread of the duration kernel
 constexpr int MG_TE = 64;  // stored-row marginals: positions per group of the transition/emission kernel
+constexpr int MG_SIMDS = 1024;  // SIMDs of the chip (256 compute units of four)
+
+// Tasks of the one-wave stored-row marginals a SIMD holds: two where the duration strip of a lane (NKW) and the
+// transition tiles (CT) leave the kernel within half the register file, else one.
+constexpr int mg_waves_per_simd(int CT, int NKW) { return (CT <= 32 && NKW <= 32) ? 2 : 1; }
 
 constexpr size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 

@@ -167,17 +167,17 @@ __global__ __launch_bounds__(NT) void k_interval(Params p)
             __syncthreads();
         }
 
-        double *pD = p.partD + ((size_t)b * N + iv) * KC;
+        double *pD = p.partD + ((size_t)b * p.NP + iv) * KC;
         for (int i = tid; i < KC; i += NT) pD[i] = l.accD[i];
-        double *pT = p.partTr + ((size_t)b * N + iv) * CC;
+        double *pT = p.partTr + ((size_t)b * p.NP + iv) * CC;
 #pragma unroll
         for (int j = 0; j < TRP; ++j) {
             const int idx = tid + j * NT;
             if (idx < CC) pT[idx] = accTr[j];
         }
         if (tid < C) {
-            p.tot[((size_t)b * N + iv) * C + tid] = R;
-            p.sumR[((size_t)b * N + iv) * C + tid] = sR;
+            p.tot[((size_t)b * p.NP + iv) * C + tid] = R;
+            p.sumR[((size_t)b * p.NP + iv) * C + tid] = sR;
         }
         __syncthreads();
     }
@@ -707,10 +707,10 @@ __global__ __launch_bounds__(64 * interval_waves(CT, NKW)) void k_interval_wave(
             }
             lds_wave_fence();
         }
-        double *pD = p.partD + ((size_t)b * N + iv) * KC;
+        double *pD = p.partD + ((size_t)b * p.NP + iv) * KC;
         for (int i = lane; i < KC; i += 64) pD[i] = p.W[i] * tmp[(i / C) * CT + i % C];
         lds_wave_fence();
-        double *pT = p.partTr + ((size_t)b * N + iv) * CC;
+        double *pT = p.partTr + ((size_t)b * p.NP + iv) * CC;
 #pragma unroll
         for (int tr = 0; tr < TRN; ++tr)
 #pragma unroll
@@ -721,8 +721,8 @@ __global__ __launch_bounds__(64 * interval_waves(CT, NKW)) void k_interval_wave(
                     if (src < C && dst < C) pT[(size_t)src * C + dst] = accT[tr][tc][v];
                 }
         if (lane < C) {
-            p.tot[((size_t)b * N + iv) * C + lane] = R;
-            p.sumR[((size_t)b * N + iv) * C + lane] = sR;
+            p.tot[((size_t)b * p.NP + iv) * C + lane] = R;
+            p.sumR[((size_t)b * p.NP + iv) * C + lane] = sR;
         }
     }
 }

@@ -168,7 +168,7 @@ __global__ __launch_bounds__(1024) void k_mg_dur(Params p)
         tg0 = tg1;
     }
     if (active) {
-        double *pD = p.partD + ((size_t)b * N + iv) * K * C;
+        double *pD = p.partD + ((size_t)b * p.NP + iv) * K * C;
 #pragma unroll
         for (int kk = 0; kk < MG_KS; ++kk) {
             const int k = kA + kk + 1;
@@ -261,30 +261,34 @@ __global__ __launch_bounds__(NT) void k_mg_te(Params p)
         }
         tg1 = tg0;
     }
-    double *pT = p.partTr + ((size_t)b * N + iv) * CC;
+    double *pT = p.partTr + ((size_t)b * p.NP + iv) * CC;
 #pragma unroll
     for (int n = 0; n < NPAIR; ++n) {
         const int pair = tid + n * NT;
         if (pair < CC) pT[pair] = acc[n];
     }
     if (tid < C) {
-        p.tot[((size_t)b * N + iv) * C + tid] = R;
-        p.sumR[((size_t)b * N + iv) * C + tid] = sR;
+        p.tot[((size_t)b * p.NP + iv) * C + tid] = R;
+        p.sumR[((size_t)b * p.NP + iv) * C + tid] = sR;
     }
 }
 
 // ---------------------------------------------------------------------------
-// The same statistics for short maximal durations (K < 128), where a whole interval's work fits one wave:
-// One wave per (sequence, interval), the lane organisation of the interval kernel (lane (g, c): label c,
-// durations g*NK + 1 ..): the wave walks the interval from its upper end downwards, as the backward scan did,
-// but takes p_t and v_t from that scan's stored rows instead of running the recurrence.  The K-deep window of
-// v rows slides through LDS in the frame of the current scaling block (rescaled by the same powers of two at the
-// same positions as in the scan, read off the stored scales), so the duration statistics are NK multiply-adds
-// per position and lane with every window entry read once per block of MB positions; the transition statistics
-// run on the matrix cores, four positions per v_mfma_f64_16x16x4; the emission sums are running sums.  Nothing
-// in the loop depends on the previous position: the rows of the next block are requested before the current one is worked on.  Partials go where the interval kernels put theirs (partD, partTr, grad_emis, tot, sumR).
+// The same statistics for short maximal durations (K < 128), where the work of an interval fits single waves.
+// One wave per (sequence, interval, part): an interval is cut into p.msplit parts of equal length, each its own
+// task, so that the chip holds two tasks per SIMD where there are few intervals; nothing in these statistics
+// depends on the position before, only the running emission sums do, and those restart with every part (the
+// partial sums tot, sumR, partD, partTr are per part: index interval*msplit + part).  Lane organisation of the
+// interval kernel (lane (g, c): label c, durations g*NK + 1 ..): the wave walks its part from the upper end
+// downwards, as the backward scan did, but takes p_t and v_t from that scan's stored rows instead of running the
+// recurrence.  The K-deep window of v rows slides through LDS in the frame of the current scaling block (rescaled
+// by the same powers of two at the same positions as in the scan, read off the stored scales), so the duration
+// statistics are NK multiply-adds per position and lane with every window entry read once per block of MB
+// positions; the transition statistics run on the matrix cores, four positions per v_mfma_f64_16x16x4; the
+// emission sums are running sums.  The rows of the next block are requested as soon as the current block's have
+// been turned into the few values the multiply-adds need.
 template <int CT, int NKW>
-__global__ __launch_bounds__(64) void k_mg_wave(Params p)
+__global__ __launch_bounds__(64, mg_waves_per_simd(CT, NKW)) void k_mg_wave(Params p)
 {
     using G = WaveWin<CT, NKW>;
     constexpr int CTP = G::CTP, RS = G::RS, NK = G::NK, KW = G::KW, M = G::M, RTOT = G::RTOT, TRN = G::TRN;
@@ -293,13 +297,16 @@ __global__ __launch_bounds__(64) void k_mg_wave(Params p)
     double *ring = lds_raw;  // [ROWS][RS] (+ pad), then 64 doubles nobody reads
     const int lane = threadIdx.x;
     const int K = p.K, C = p.C, KC = K * C, CC = C * C, N = p.N, Delta = p.Delta;
-    const int b = blockIdx.x / N, iv = blockIdx.x % N;
+    const int S = p.msplit, Dm = Delta / S;
+    const int sub = blockIdx.x % S, b = (blockIdx.x / S) / N, iv = (blockIdx.x / S) % N;
     const SeqHdr h = p.hdr[b];
     const int L = h.L, J = h.J, Jm = J - 1;
-    const int t0 = iv * Delta;
-    if (t0 >= L) return;
+    const int t0 = iv * Delta;      // the interval: its rows are stored relative to t0
+    const int ta = t0 + sub * Dm;   // this task's positions: ta <= t < tb
+    if (ta >= L) return;
     if (!(p.spec_ok[b * 2] && p.spec_ok[b * 2 + 1])) return;  // the interval kernel takes this sequence
     const int t1 = min(t0 + Delta, L);
+    const int tb = min(ta + Dm, L);
     const int c = lane % CTP, g = lane / CTP;
     const bool cval = c < C;
     const int cc = cval ? c : 0;
@@ -309,6 +316,7 @@ __global__ __launch_bounds__(64) void k_mg_wave(Params p)
     const double2 *EIc = p.EI + row0 * C + cc;
     const int *nbc = p.nbase + row0 * C + cc;
     const size_t slot = (size_t)b * N + iv;
+    const size_t part = (size_t)b * p.NP + (size_t)iv * S + sub;
     const double2 *arow = (const double2 *)p.aloc + slot * Delta * C;  // (a_t, q_t) of position t0 + i at i*C
     const double2 *brow = (const double2 *)p.bloc + slot * Delta * C;  // (p_t, v_t)
     const double *arowY = p.alocY + slot * Delta;
@@ -317,19 +325,43 @@ __global__ __launch_bounds__(64) void k_mg_wave(Params p)
     const double Y0 = p.ckYA[(size_t)b * (N + 1) + iv];
     const double Ytop = t1 == L ? 0.0 : p.ckYB[(size_t)b * (N + 1) + iv + 1];
 
-    // ---- the window above the interval: the state the backward task started from
+    // ---- the window above the part
     for (int i = lane; i < RTOT; i += 64) ring[i] = 0.0;
     lds_wave_fence();
     int r = M;  // row of the newest (lowest) position
-    if (t1 == L) {  // v_L = E_L
+    double ybPrev = 0.0;  // stored scale (relative to the interval's upper end) of the frame the window is in
+    if (tb == L) {  // v_L = E_L
         if (writer) ring[r * RS + c] = EIc[(size_t)L * C].x;
-    } else {
+    } else if (tb == t1) {  // the state the backward task started from
         const double *ck = p.ckB + ((size_t)b * (N + 1) + iv + 1) * ((size_t)KC + C);
         const int tm = t1 % K;
         for (int i = lane; i < KC; i += 64) {
             const int sl = i / C, col = i % C;
             ring[(r + G::template slot_dist<true>(sl, tm, K)) * RS + col] = ck[i];
         }
+    } else {
+        // inside the interval: the rows v_tb .. v_{tb+K-1} as the scans of this and the following intervals
+        // stored them, each brought from the frame of its own scaling block into that of position tb (the
+        // powers of two the scan applied on its way down from there, and the difference of the scales)
+        const int jt = tb / J;
+        const double ybt = mg_yb(p, b, iv, tb - t0, L);
+        const int *nb = p.nbase + row0 * C;
+        for (int i = lane; i < KC; i += 64) {
+            const int d = i / C, col = i % C;
+            const int sp = tb + d;
+            double val = 0.0;
+            if (sp <= L) {
+                const int jv = sp / Delta;
+                const double v = sp == L ? p.EI[(row0 + L) * C + col].x
+                                         : ((const double2 *)p.bloc)[(((size_t)b * N + jv) * Delta + (sp - jv * Delta)) * C + col].y;
+                const double lf = (sp == L ? 0.0 : mg_yb(p, b, jv, sp - jv * Delta, L)) - ybt;
+                const double fl = floor(lf);
+                const int e = (int)fmin(fmax(fl, -100000.0), 100000.0) + nb[(size_t)(sp / J) * C + col] - nb[(size_t)jt * C + col];
+                val = fmin(ldexp(v * exp2(lf - fl), e), DBL_MAX);
+            }
+            ring[(r + d) * RS + col] = val;
+        }
+        ybPrev = browY[tb - t0];
     }
     lds_wave_fence();
 
@@ -348,110 +380,125 @@ __global__ __launch_bounds__(64) void k_mg_wave(Params p)
     float *const sink = (float *)p.sink + lane;
     float *const gout = p.grad_emis + ((size_t)b * p.T) * C + cc;
 
-    struct Rows {
-        double2 aq[MB], pv[MB], e[MB];  // this lane's label, the MB positions below tfrom
-        double aA[TRN], bB[TRN];        // operand elements: position pj of the block, label pl of tile tr
-        double ya, yb;                  // stored scales of the position just below tfrom (forward, backward)
-        int nd;                         // exponent step of this lane's label at the scaling-block boundary tfrom
-    };
+    // the rows of one block of positions, as they come from memory
+    double2 aq[MB], pv[MB], e[MB];  // this lane's label, the MB positions below tfrom
+    double aA[TRN], bB[TRN];        // operand elements: position pj of the block, label pl of tile tr
+    double ya, yb;                  // stored scales of the position just below tfrom (forward, backward)
+    int nd;                         // exponent step of this lane's label at the scaling-block boundary tfrom
     // element offsets fit 32 bits: a slot has Delta*C < 2^27 elements (the plan's limits), a sequence (T+1)*C < 2^31
-    const double2 *const arc = arow + cc, *const brc = brow + cc, *const eic = EIc + (size_t)t0 * C;
+    const double2 *const eir = p.EI + (row0 + t0) * C;
     int cpo[TRN];
 #pragma unroll
     for (int tr = 0; tr < TRN; ++tr) cpo[tr] = min(tr * 16 + pl, C - 1);
-    auto request = [&](Rows &w, const int tfrom) {
+    auto request = [&](const int tfrom) {
 #pragma unroll
         for (int i = 0; i < MB; ++i) {
-            const unsigned o = (unsigned)(max(tfrom - 1 - i, t0) - t0) * (unsigned)C;
-            w.aq[i] = arc[o];
-            w.pv[i] = brc[o];
-            w.e[i] = eic[o];
+            const unsigned o = (unsigned)(max(tfrom - 1 - i, ta) - t0) * (unsigned)C + (unsigned)cc;
+            aq[i] = arow[o];
+            pv[i] = brow[o];
+            e[i] = eir[o];
         }
-        const unsigned o = (unsigned)(max(tfrom - 1 - pj, t0) - t0) * (unsigned)C;
+        const unsigned o = (unsigned)(max(tfrom - 1 - pj, ta) - t0) * (unsigned)C;
 #pragma unroll
         for (int tr = 0; tr < TRN; ++tr) {
-            w.aA[tr] = arow[o + cpo[tr]].x;
-            w.bB[tr] = brow[o + cpo[tr]].x;
+            aA[tr] = arow[o + cpo[tr]].x;
+            bB[tr] = brow[o + cpo[tr]].x;
         }
         // what a scaling-block boundary at tfrom needs, fetched with every block: a load inside the (rare)
         // boundary branch would make the wave wait there for everything in flight
         const int i0 = max(tfrom - 1 - t0, 0);
-        w.ya = arowY[i0];
-        w.yb = browY[i0];
+        ya = arowY[i0];
+        yb = browY[i0];
         const int jb = max(tfrom / J, 1);
         const int hiE = nbc[(size_t)min(jb, L / J) * C], loE = nbc[(size_t)(jb - 1) * C];
-        w.nd = (tfrom / J >= 1 && (long)jb * J <= (long)L) ? hiE - loE : 0;
+        nd = (tfrom / J >= 1 && (long)jb * J <= (long)L) ? hiE - loE : 0;
     };
-    auto block_len = [&](const int t) { return min(min(t - t0, MB), ((t - 1) & Jm) + 1); };
+    // The rows of the block after the next are touched one block before they are requested, one 64-byte line
+    // per lane and load (the lines of the forward rows first, then the backward rows, then the (ES, 1/ES) pairs):
+    // the request sits only half a block ahead of its use and then finds them in the cache.  The words that come
+    // back are added up into a word nothing reads, a block later.
+    constexpr int LPA = CT + 1;                       // lines a block of MB rows of one array can touch
+    constexpr int NTCH = (3 * LPA + 63) / 64;
+    const unsigned *tbase[NTCH];
+    unsigned tline[NTCH], tw[NTCH], tsum = 0;
+#pragma unroll
+    for (int u = 0; u < NTCH; ++u) {
+        const int q = lane + 64 * u, arr = min(q / LPA, 2);
+        tbase[u] = (const unsigned *)(arr == 0 ? (const void *)arow : arr == 1 ? (const void *)brow : (const void *)eir);
+        tline[u] = (unsigned)(q - arr * LPA) * 16u;  // in words
+        tw[u] = 0;
+    }
+    const unsigned tlim = (unsigned)(tb - t0) * (unsigned)C * 4u - 1u;  // last word of the rows below tb
+    auto touch = [&](const int tfrom) {  // the block of MB rows below tfrom
+        const unsigned w0 = (unsigned)(max(tfrom - MB, ta) - t0) * (unsigned)C * 4u;
+#pragma unroll
+        for (int u = 0; u < NTCH; ++u) tw[u] = tbase[u][min(w0 + tline[u], tlim)];
+    };
     // kappa(t,t) of the positions of a scaling block (they share both scales)
-    auto kappa_of = [&](const Rows &w) { return exp((Y0 + w.ya + Ytop + w.yb) * LN2 - logZ); };
+    auto kappa_of = [&]() { return exp((Y0 + ya + Ytop + yb) * LN2 - logZ); };
 
-    int t = t1;
-    double kappa = 0.0;
-    double ybPrev = 0.0;  // stored scale (relative to the upper end) of the frame the window is in
+    int t = tb;
     const int rdoff = g * NK * RS + c;
-    // one block of positions from the rows in `w`; the next block's rows are requested into `wn` first
-    auto step = [&](const Rows &w, Rows &wn) {
-        const int nb = block_len(t);
-        request(wn, t - nb);
+    request(t);
+    double kappa = kappa_of();
+    while (t > ta) {
+        const int nb = min(min(t - ta, MB), ((t - 1) & Jm) + 1);
         if (__builtin_expect((t & Jm) == 0, 0)) {
             // the scan stepped into a new scaling block here: same shift of the window, read off its scales
-            G::rescale(ring, g, c, cval, w.nd - (int)(w.yb - ybPrev));
-            ybPrev = w.yb;
-            kappa = kappa_of(w);
+            G::rescale(ring, g, c, cval, nd - (int)(yb - ybPrev));
+            ybPrev = yb;
+            kappa = kappa_of();
         }
         if (__builtin_expect(r < MB, 0)) r = G::template move<true>(ring, lane, r);
+        // ---- everything the block needs from its rows; v_t(c) enters the window at once (the rows below the
+        // newest are not among those the block reads; beyond the block's end the store goes to the pad)
         double coef[MB];
-#pragma unroll
-        for (int i = 0; i < MB; ++i) coef[i] = (cval && i < nb) ? w.aq[i].y * kappa : 0.0;  // q_t(c) kappa
-        const double *base = ring + r * RS + rdoff;
-#pragma unroll
-        for (int jj = 0; jj < NK; ++jj) {
-            const double v = base[jj * RS];  // distance g*NK + jj from the newest
-#pragma unroll
-            for (int i = 0; i < MB; ++i) dx[jj + i] = fma(coef[i], v, dx[jj + i]);
-        }
 #pragma unroll
         for (int i = 0; i < MB; ++i) {
             const bool on = i < nb;
             const int tt = t - 1 - i;
+            coef[i] = (cval && on) ? aq[i].y * kappa : 0.0;  // q_t(c) kappa
             const double cg = g == 0 ? coef[i] : 0.0;
 #pragma unroll
-            for (int jn = 0; jn < i; ++jn) dn[i - 1 - jn] = fma(cg, w.pv[jn].y, dn[i - 1 - jn]);
+            for (int jn = 0; jn < i; ++jn) dn[i - 1 - jn] = fma(cg, pv[jn].y, dn[i - 1 - jn]);
+            double *rdst = (on && writer) ? ring + (r - 1 - i) * RS + c : ring + RTOT + lane;
+            *rdst = pv[i].y;
             // a segment of this label starts at tt (z p, z = q ES) / ends at tt (a b, b = v IE; none ends at 0)
-            const double d = on ? (w.aq[i].y * w.e[i].x * w.pv[i].x -
-                                   (tt >= 1 ? w.aq[i].x * w.pv[i].y * w.e[i].y : 0.0)) * kappa : 0.0;
+            const double d = on ? (aq[i].y * e[i].x * pv[i].x - (tt >= 1 ? aq[i].x * pv[i].y * e[i].y : 0.0)) * kappa : 0.0;
             float *dst = (on && writer) ? gout + (unsigned)tt * (unsigned)C : sink;
             *dst = (float)R;
             sR += on ? R : 0.0;
             R += d;
-            // v_t(c) enters the window; beyond the block's end the store goes to the pad behind the buffer
-            double *rdst = (on && writer) ? ring + (r - 1 - i) * RS + c : ring + RTOT + lane;
-            *rdst = w.pv[i].y;
         }
-        r -= nb;
-        lds_wave_fence();
         {
             const bool on = pj < nb;
 #pragma unroll
             for (int tr = 0; tr < TRN; ++tr) {
-                const double a = (on && tr * 16 + pl < C) ? w.aA[tr] * kappa : 0.0;
+                const double a = (on && tr * 16 + pl < C) ? aA[tr] * kappa : 0.0;
 #pragma unroll
                 for (int tc = 0; tc < TRN; ++tc) {
-                    const double bb = (on && tc * 16 + pl < C) ? w.bB[tc] : 0.0;
+                    const double bb = (on && tc * 16 + pl < C) ? bB[tc] : 0.0;
                     accT[tr][tc] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, bb, accT[tr][tc], 0, 0, 0);
                 }
             }
         }
+        // ---- the next block's rows, and a touch of the one after
+        request(t - nb);
+#pragma unroll
+        for (int u = 0; u < NTCH; ++u) tsum += tw[u];
+        touch(t - nb - MB);
+        const double *base = ring + r * RS + rdoff;
+#pragma unroll
+        for (int jj = 0; jj < NK; ++jj) {
+            if (jj % 8 == 0) __builtin_amdgcn_sched_barrier(0);  // window reads eight at a time: not worth the registers of all NK
+            const double v = base[jj * RS];  // distance g*NK + jj from the newest
+#pragma unroll
+            for (int i = 0; i < MB; ++i) dx[jj + i] = fma(coef[i], v, dx[jj + i]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        r -= nb;
+        lds_wave_fence();
         t -= nb;
-    };
-    Rows ra, rb;
-    request(ra, t);
-    kappa = kappa_of(ra);
-    while (t > t0) {
-        step(ra, rb);
-        if (t <= t0) break;
-        step(rb, ra);
     }
     // ---- partials of this task.  Duration sums: the strips of neighbouring lane groups overlap by MB-1
     // durations; they are combined through LDS in a fixed order (own strip, then the neighbour's overlap, then
@@ -480,9 +527,9 @@ __global__ __launch_bounds__(64) void k_mg_wave(Params p)
         }
         lds_wave_fence();
     }
-    double *pD = p.partD + slot * KC;
+    double *pD = p.partD + part * KC;
     for (int i = lane; i < KC; i += 64) pD[i] = p.W[i] * tmp[(i / C) * CT + i % C];
-    double *pT = p.partTr + slot * CC;
+    double *pT = p.partTr + part * CC;
 #pragma unroll
     for (int tr = 0; tr < TRN; ++tr)
 #pragma unroll
@@ -493,7 +540,8 @@ __global__ __launch_bounds__(64) void k_mg_wave(Params p)
                 if (src < C && dst < C) pT[(size_t)src * C + dst] = accT[tr][tc][v];
             }
     if (lane < C) {
-        p.tot[slot * C + lane] = R;
-        p.sumR[slot * C + lane] = sR;
+        p.tot[part * C + lane] = R;
+        p.sumR[part * C + lane] = sR;
     }
+    ((unsigned *)p.sink)[64 + lane] = tsum;
 }

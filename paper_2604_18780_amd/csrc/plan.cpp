@@ -135,11 +135,6 @@ int make_plan(int B, int T, int K, int C, int ckpt_interval, int want_grad, Plan
     sz[PL_CKYB] = g * b * (n + 1) * 8;
     sz[PL_ALOC] = g * (size_t)pl->nslot * pl->Delta * 2 * c * 8;
     sz[PL_ALOCY] = g * (size_t)pl->nslot * pl->Delta * 8;
-    sz[PL_PARTD] = g * b * n * k * c * 8;
-    sz[PL_PARTTR] = g * b * n * c * c * 8;
-    sz[PL_TOT] = g * b * n * c * 8;
-    sz[PL_SUMR] = g * b * n * c * 8;
-    sz[PL_CARRY] = g * b * n * c * 8;
     sz[PL_MEAN] = g * b * c * 8;
     sz[PL_CKA2] = b * (n + 1) * (k * c + c) * 8;
     sz[PL_CKB2] = g * b * (n + 1) * (k * c + c) * 8;
@@ -149,18 +144,34 @@ int make_plan(int B, int T, int K, int C, int ckpt_interval, int want_grad, Plan
     sz[PL_INL] = b * c * 8;
     // Marginals from the stored rows of both scans need a second set of row slots.  Measured: the
     // route wins where the K-deep window makes the interval kernel's recurrence long (K = 512:
-    // 0.52 ms against 1.08 ms) and is level with it at K = 64, so it is planned for K >= 128,
-    // when every task has its slot and the sizes fit its kernels.
+    // 0.52 ms against 1.08 ms), and for shorter durations where its one-wave kernel holds two tasks per
+    // SIMD (K = 64, C = 24: 0.21 ms against 0.33 ms for the stage; with 64 labels, one task per SIMD, it
+    // loses: 0.34 against 0.19 ms).  It is planned there, when every task has its slot and the sizes fit.
     const int mg_nsl = (K + MG_KS - 1) / MG_KS;
     const size_t mg_vr = (size_t)MG_TG + (size_t)MG_KS * mg_nsl + 3;
     pl->lds_mg_dur = (MG_TG * c + mg_vr * (c | 3) + MG_TG + 2 * mg_vr + 2 * (size_t)pl->Delta + k) * sizeof(double);
     pl->lds_mg_te = ((size_t)3 * MG_TE * c + pl->Delta) * sizeof(double);
-    const bool rows = !lowmem && (kind == 3 || (kind == 1 && K >= 128));
+    const int mg_gw = 64 / pow2_ge8(C > 64 ? 64 : C);
+    const int mg_per_simd = mg_waves_per_simd(C, (K + mg_gw - 1) / mg_gw);  // of the one-wave kernel (K < 128)
+    const bool rows = !lowmem && (kind == 3 || (kind == 1 && (K >= 128 || mg_per_simd == 2)));
     pl->rows = rows && spec_applies(K, C) && ntask <= (size_t)pl->nslot && c * mg_nsl <= 1024 &&
                pl->lds_mg_dur <= LDS_LIMIT && pl->lds_mg_te <= LDS_LIMIT;
     const size_t gr = pl->rows ? 1 : 0;
     sz[PL_BLOC] = gr * (size_t)pl->nslot * pl->Delta * 2 * c * 8;
     sz[PL_BLOCY] = gr * (size_t)pl->nslot * pl->Delta * 8;
+    // With fewer intervals than the chip holds tasks of that kernel, each interval is cut into 2 or 4 equal
+    // parts of at least K positions, each part a task with partial sums of its own.
+    pl->msplit = 1;
+    if (pl->rows && K < 128)
+        while (pl->msplit < 4 && ntask * pl->msplit < (size_t)mg_per_simd * MG_SIMDS && pl->Delta % (2 * pl->msplit) == 0 &&
+               pl->Delta / (2 * pl->msplit) >= (K < 32 ? 32 : K))
+            pl->msplit *= 2;
+    const size_t np = n * (size_t)pl->msplit;
+    sz[PL_PARTD] = g * b * np * k * c * 8;
+    sz[PL_PARTTR] = g * b * np * c * c * 8;
+    sz[PL_TOT] = g * b * np * c * 8;
+    sz[PL_SUMR] = g * b * np * c * 8;
+    sz[PL_CARRY] = g * b * np * c * 8;
     sz[PL_SINK] = (size_t)SINK_DOUBLES * 8;
     pl->narrays = PL_COUNT;
     size_t off = 0;

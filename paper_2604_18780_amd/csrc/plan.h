@@ -13,6 +13,7 @@ namespace semicrf_impl {
 struct Plan {
     int Delta, N, NCH, nslot, G;
     int rows;  // the backward scan tasks have row storage (stored-row marginals possible)
+    int msplit;  // parts an interval is cut into by the one-wave stored-row marginals (per-part partial sums)
     size_t lds_mg_dur, lds_mg_te;
     size_t lds_scan, lds_interval;
     size_t total;

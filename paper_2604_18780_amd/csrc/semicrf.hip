@@ -91,6 +91,8 @@ void bind_workspace(Params &p, const Plan &pl, void *ws)
     p.ckYB = (double *)(w + pl.off[13]);
     p.aloc = (double *)(w + pl.off[14]);
     p.alocY = (double *)(w + pl.off[15]);
+    p.NP = pl.N * pl.msplit;  // partial sums per sequence
+    p.msplit = 1;             // parts per interval: set by the call that takes the one-wave stored-row marginals
     p.partD = (double *)(w + pl.off[16]);
     p.partTr = (double *)(w + pl.off[17]);
     p.tot = (double *)(w + pl.off[18]);
@@ -305,7 +307,7 @@ int launch_mg_k(const Params &p, hipStream_t st)
     if (hipFuncSetAttribute((const void *)k_mg_wave<CT, NKW>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)lds) != hipSuccess)
         return SEMICRF_ELAUNCH;
-    hipLaunchKernelGGL((k_mg_wave<CT, NKW>), dim3(p.B * p.N), dim3(64), lds, st, p);
+    hipLaunchKernelGGL((k_mg_wave<CT, NKW>), dim3(p.B * p.N * p.msplit), dim3(64), lds, st, p);
     return SEMICRF_OK;
 }
 
@@ -364,6 +366,7 @@ int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hi
     p.marg = pl.rows && p.fuse && !bterms;
     if (p.K < 128 && ((double)p.T + 1.0) * (double)p.C >= 2147483648.0)
         p.marg = 0;  // the one-wave kernel indexes a sequence's rows with 32 bits
+    if (p.marg && p.K < 128) p.msplit = pl.msplit;  // the partial-sum arrays are planned for N * pl.msplit either way
     T.mark();
     rc = launch_prep(p, st);
     T.mark();

@@ -66,17 +66,20 @@ def test_workspace_is_aligned_positive_and_monotone():
 def test_working_memory_beyond_prefix_arrays_is_bounded_then_sublinear_in_T():
     """Checkpoints + per-interval recompute buffers (grad workspace - forward-only workspace).
     The automatic interval gives one task per SIMD, so up to T ~ 1024*sqrt(T*K)/B this part
-    is about one more O(T*C) array (never more than 1.5x the prefix arrays); beyond that the
-    interval is capped at sqrt(T*K) and it must grow like sqrt(T)."""
+    is two more O(T*C) arrays, the rows the forward and the backward scan tasks leave for the
+    marginals (never more than 2.5x the prefix arrays); beyond that the interval is capped at
+    sqrt(T*K), the rows go to a fixed number of slots and it must grow like sqrt(T).  A caller that
+    asks for the per-interval recurrence (plan kind 2) has one such array (1.5x)."""
     B, K, C = 4, 64, 24
     extra = lambda T: (sb.semicrf_workspace_bytes(B, T, K, C, 0, True)
                        - sb.semicrf_workspace_bytes(B, T, K, C, 0, False))
     for T in (100000, 400000, 1600000):
-        assert extra(T) < 1.5 * B * (T + 1) * C * 20
+        assert extra(T) < 2.5 * B * (T + 1) * C * 20
+        assert (sb.semicrf_workspace_bytes(B, T, K, C, 0, 2)
+                - sb.semicrf_workspace_bytes(B, T, K, C, 0, False)) < 1.5 * B * (T + 1) * C * 20
     # 16x longer sequences: sqrt growth is 4x (the number of rounds is an integer, hence the slack), linear 16x
     assert extra(204800000) / extra(12800000) < 6.0
-    # long maximal durations (K >= 128): the backward scan tasks keep their rows too, one more
-    # O(T*C) array while every task has a slot, and nothing more once they do not
+    # long maximal durations (K >= 128): the same two row arrays while every task has a slot
     extra512 = lambda T: (sb.semicrf_workspace_bytes(2, T, 512, 8, 0, True)
                           - sb.semicrf_workspace_bytes(2, T, 512, 8, 0, False))
     for T in (400000, 1600000):

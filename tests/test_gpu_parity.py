@@ -31,32 +31,36 @@ def to_dev(w, nan_pad=True):
 
 
 def check_against_oracle(w, center=True, grad_logz=None, ckpt_interval=0, label="", extra_flags=0):
+    """HIP path against the oracle.  Without a route in extra_flags the marginals are checked on both: the default
+    one (stored rows of both scans where the plan has them) and the per-interval recurrence."""
     emis, lengths, trans, dur = to_dev(w)
-    flags = (sb.SEMICRF_CENTER if center else 0) | extra_flags
     gl = None if grad_logz is None else torch.from_numpy(grad_logz.astype(np.float32)).to(DEV)
-    print(f"[case] {label or w.name} B={w.B} T={w.T} K={w.K} C={w.C} center={center} "
-          f"delta={ckpt_interval}", flush=True)
-    logz, g_e, g_t, g_d, pm = sb.semicrf_fwd_bwd(emis, lengths, trans, dur, gl, ckpt_interval, flags)
-    logz_f = sb.semicrf_logz_fwd(emis, lengths, trans, dur, ckpt_interval, flags)
-    torch.cuda.synchronize()
     r = oracle.fwd_bwd(w.emis, w.lengths, w.trans, w.dur, grad_logz=grad_logz, center=center)
-    lz = logz.double().cpu().numpy()
-    assert np.all(np.isfinite(lz))
-    rel = np.abs(lz - r.logz) / np.maximum(1.0, np.abs(r.logz))
-    assert rel.max() <= 1e-5, (rel.max(), lz, r.logz)
-    assert np.array_equal(lz, logz_f.double().cpu().numpy())       # forward-only entry agrees bit for bit
-    e_pm = np.abs(pm.double().cpu().numpy() - r.pos_marg).max()
-    e_ge = np.abs(g_e.double().cpu().numpy() - r.grad_emis).max()
-    wmax = 1.0 if grad_logz is None else max(1.0, float(np.abs(grad_logz).max()))
-    assert e_pm <= 1e-4, e_pm
-    assert e_ge <= 1e-4 * wmax, e_ge
-    e_t = np.abs(g_t.double().cpu().numpy() - r.grad_trans).max()
-    e_d = np.abs(g_d.double().cpu().numpy() - r.grad_dur).max()
-    print(f"       max err: logz rel {rel.max():.2e} pos_marg {e_pm:.2e} grad_emis {e_ge:.2e} "
-          f"grad_trans {e_t:.2e} (max|g| {np.abs(r.grad_trans).max():.3g}) "
-          f"grad_dur {e_d:.2e} (max|g| {np.abs(r.grad_dur).max():.3g})", flush=True)
-    assert e_t <= 1e-4 * max(1.0, np.abs(r.grad_trans).max()), e_t
-    assert e_d <= 1e-4 * max(1.0, np.abs(r.grad_dur).max()), e_d
+    pinned = extra_flags & (sb.SEMICRF_MARGINALS_ROWS | sb.SEMICRF_MARGINALS_INTERVAL)
+    for route in ([0] if pinned else [0, sb.SEMICRF_MARGINALS_INTERVAL]):
+        flags = (sb.SEMICRF_CENTER if center else 0) | extra_flags | route
+        print(f"[case] {label or w.name} B={w.B} T={w.T} K={w.K} C={w.C} center={center} "
+              f"delta={ckpt_interval} flags={flags:#x}", flush=True)
+        logz, g_e, g_t, g_d, pm = sb.semicrf_fwd_bwd(emis, lengths, trans, dur, gl, ckpt_interval, flags)
+        logz_f = sb.semicrf_logz_fwd(emis, lengths, trans, dur, ckpt_interval, flags)
+        torch.cuda.synchronize()
+        lz = logz.double().cpu().numpy()
+        assert np.all(np.isfinite(lz))
+        rel = np.abs(lz - r.logz) / np.maximum(1.0, np.abs(r.logz))
+        assert rel.max() <= 1e-5, (rel.max(), lz, r.logz)
+        assert np.array_equal(lz, logz_f.double().cpu().numpy())       # forward-only entry agrees bit for bit
+        e_pm = np.abs(pm.double().cpu().numpy() - r.pos_marg).max()
+        e_ge = np.abs(g_e.double().cpu().numpy() - r.grad_emis).max()
+        wmax = 1.0 if grad_logz is None else max(1.0, float(np.abs(grad_logz).max()))
+        assert e_pm <= 1e-4, e_pm
+        assert e_ge <= 1e-4 * wmax, e_ge
+        e_t = np.abs(g_t.double().cpu().numpy() - r.grad_trans).max()
+        e_d = np.abs(g_d.double().cpu().numpy() - r.grad_dur).max()
+        print(f"       max err: logz rel {rel.max():.2e} pos_marg {e_pm:.2e} grad_emis {e_ge:.2e} "
+              f"grad_trans {e_t:.2e} (max|g| {np.abs(r.grad_trans).max():.3g}) "
+              f"grad_dur {e_d:.2e} (max|g| {np.abs(r.grad_dur).max():.3g})", flush=True)
+        assert e_t <= 1e-4 * max(1.0, np.abs(r.grad_trans).max()), e_t
+        assert e_d <= 1e-4 * max(1.0, np.abs(r.grad_dur).max()), e_d
     return r
 
 
