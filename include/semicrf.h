@@ -85,10 +85,13 @@ typedef enum {
  * per-position bookkeeping too slowly); kept as the measured alternative.  Ignored where the sizes do not allow it. */
 #define SEMICRF_MATRIX_SCAN 16u
 /* flags bits 5, 6: where semicrf_fwd_bwd takes the expected statistics of the "Gradient Formulas" section from.
- * Default (neither bit): from the stored rows of both scans for K >= 128, from Algorithm 3's per-interval
- * recurrence below that.  SEMICRF_MARGINALS_ROWS asks for the stored rows whatever K is (the workspace must
- * have been sized with want_grad = 3), SEMICRF_MARGINALS_INTERVAL for the per-interval recurrence (want_grad = 2
- * suffices).  Setting both is invalid.  The results agree to the rounding of the outputs. */
+ * Default (neither bit): from the stored rows of both scans (the backward scan tasks keep their rows like the
+ * forward ones, and no recurrence is run a third time) wherever the chunk-parallel scans apply, every interval has
+ * its row slot and no boundary term is an input or output of the call; otherwise, and for the sequences whose
+ * scans were not accepted, from Algorithm 3's per-interval recurrence.  SEMICRF_MARGINALS_ROWS states the default
+ * (want_grad = 1 or 3), SEMICRF_MARGINALS_INTERVAL asks for the per-interval recurrence everywhere (want_grad = 2
+ * suffices: one O(T*C) row array less).  Setting both is invalid.  The results agree to the rounding of the
+ * outputs. */
 #define SEMICRF_MARGINALS_ROWS 32u
 #define SEMICRF_MARGINALS_INTERVAL 64u
 /* flags bit 8 (semicrf_logz_fwd, semicrf_fwd_bwd and their _boundary / _profiled / _static forms): the
@@ -126,9 +129,8 @@ const char *semicrf_strerror(int status);
  * the modelled time of the (sequence, interval) tasks, which run in rounds of about one
  * task per SIMD of the chip; roughly ceil(B*T/1024) when the K-deep window is small.
  * want_grad = 0 sizes for semicrf_logz_fwd / semicrf_cum_scores only; 1 for semicrf_fwd_bwd with the default
- * choice of marginal route; 2 for semicrf_fwd_bwd with SEMICRF_MARGINALS_INTERVAL (the smallest);
- * 3 for semicrf_fwd_bwd with SEMICRF_MARGINALS_ROWS (adds the row slots of the backward scan).  A workspace
- * sized with 3 serves every gradient call, one sized with 1 every call without SEMICRF_MARGINALS_ROWS.
+ * choice of marginal route (row slots for both scans); 2 for semicrf_fwd_bwd with SEMICRF_MARGINALS_INTERVAL
+ * (the smallest); 3 is the same as 1.  A workspace sized with 1 serves every gradient call.
  * Add 8 for calls with SEMICRF_LOW_MEMORY (8 forward only, 9 or 10 gradients): another layout, for those
  * calls only.  `bytes` is a host pointer.
  */

@@ -119,14 +119,16 @@ __global__ __launch_bounds__(NT) void k_fin_emis(Params p)
 }
 
 // grad_trans[c',c] = Etr[c',c] * sum_b w_b sum_i partTr;  grad_dur[k,c] = sum_b w_b sum_i partD.
-// One workgroup per 32 outputs; 8 thread groups take the intervals i = g, g+8, ... and their
-// sums are combined in group order (fixed order for a given problem).
+// One workgroup per FIN_PO outputs; NT / FIN_PO thread groups take the partial sums i = g, g + groups, ... and
+// their sums are combined in group order (fixed order for a given problem).
+constexpr int FIN_PO = 8;  // small: the partial sums of a long sequence are many, the outputs few
 __device__ __forceinline__ void fin_params_body(const Params &p, const int blk)
 {
     __shared__ double red[NT];
+    constexpr int NG = NT / FIN_PO;
     const int C = p.C, CC = C * C, KC = p.K * C, N = p.NP, tid = threadIdx.x;
-    const int o = tid & 31, g = tid >> 5;
-    const int idx = blk * 32 + o;
+    const int o = tid % FIN_PO, g = tid / FIN_PO;
+    const int idx = blk * FIN_PO + o;
     const bool ok = idx < CC + KC;
     double acc = 0.0;
     if (ok) {
@@ -140,13 +142,13 @@ __device__ __forceinline__ void fin_params_body(const Params &p, const int blk)
                                        : p.partD + ((size_t)b * N) * KC + (idx - CC);
             double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
             int i = g;
-            for (; i + 24 < nint; i += 32) {
+            for (; i + 3 * NG < nint; i += 4 * NG) {
                 s0 += q[(size_t)i * stride];
-                s1 += q[(size_t)(i + 8) * stride];
-                s2 += q[(size_t)(i + 16) * stride];
-                s3 += q[(size_t)(i + 24) * stride];
+                s1 += q[(size_t)(i + NG) * stride];
+                s2 += q[(size_t)(i + 2 * NG) * stride];
+                s3 += q[(size_t)(i + 3 * NG) * stride];
             }
-            for (; i < nint; i += 8) s0 += q[(size_t)i * stride];
+            for (; i < nint; i += NG) s0 += q[(size_t)i * stride];
             acc = fma(w, (s0 + s1) + (s2 + s3), acc);
         }
     }
@@ -154,17 +156,17 @@ __device__ __forceinline__ void fin_params_body(const Params &p, const int blk)
     __syncthreads();
     if (ok && g == 0) {
         double t = 0.0;
-        for (int gg = 0; gg < 8; ++gg) t += red[gg * 32 + o];
+        for (int gg = 0; gg < NG; ++gg) t += red[gg * FIN_PO + o];
         if (idx < CC) p.grad_trans[idx] = (float)(t * p.Etr[idx]);
         else p.grad_dur[idx - CC] = (float)t;
     }
 }
 
 // One launch for the two independent reductions: workgroups 0..B-1 per sequence, the rest
-// per 32 parameter gradients.
+// per FIN_PO parameter gradients.
 __global__ __launch_bounds__(NT) void k_fin_seq(Params p)
 {
-    const int nparam = (p.C * p.C + p.K * p.C + 31) / 32;
+    const int nparam = (p.C * p.C + p.K * p.C + FIN_PO - 1) / FIN_PO;
     if ((int)blockIdx.x < p.B) fin_seq_body(p, blockIdx.x);
     else if ((int)blockIdx.x < p.B + nparam) fin_params_body(p, blockIdx.x - p.B);
     else fin_pi_body(p);

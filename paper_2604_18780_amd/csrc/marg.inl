@@ -335,6 +335,8 @@ __global__ __launch_bounds__(64, mg_waves_per_simd(CT, NKW)) void k_mg_wave(Para
     } else if (tb == t1) {  // the state the backward task started from
         const double *ck = p.ckB + ((size_t)b * (N + 1) + iv + 1) * ((size_t)KC + C);
         const int tm = t1 % K;
+        // (the loops below are unrolled so that the loads of several rounds are in flight together)
+#pragma unroll 8
         for (int i = lane; i < KC; i += 64) {
             const int sl = i / C, col = i % C;
             ring[(r + G::template slot_dist<true>(sl, tm, K)) * RS + col] = ck[i];
@@ -343,23 +345,37 @@ __global__ __launch_bounds__(64, mg_waves_per_simd(CT, NKW)) void k_mg_wave(Para
         // inside the interval: the rows v_tb .. v_{tb+K-1} as the scans of this and the following intervals
         // stored them, each brought from the frame of its own scaling block into that of position tb (the
         // powers of two the scan applied on its way down from there, and the difference of the scales)
+        // Lane (g, c) fills its own strip, rows g*NK .. of label c; everything is loaded first, so that the
+        // loads of all rows are in flight together (the rows of a sequence's slots are consecutive).
         const int jt = tb / J;
         const double ybt = mg_yb(p, b, iv, tb - t0, L);
-        const int *nb = p.nbase + row0 * C;
-        for (int i = lane; i < KC; i += 64) {
-            const int d = i / C, col = i % C;
-            const int sp = tb + d;
-            double val = 0.0;
-            if (sp <= L) {
-                const int jv = sp / Delta;
-                const double v = sp == L ? p.EI[(row0 + L) * C + col].x
-                                         : ((const double2 *)p.bloc)[(((size_t)b * N + jv) * Delta + (sp - jv * Delta)) * C + col].y;
-                const double lf = (sp == L ? 0.0 : mg_yb(p, b, jv, sp - jv * Delta, L)) - ybt;
-                const double fl = floor(lf);
-                const int e = (int)fmin(fmax(fl, -100000.0), 100000.0) + nb[(size_t)(sp / J) * C + col] - nb[(size_t)jt * C + col];
-                val = fmin(ldexp(v * exp2(lf - fl), e), DBL_MAX);
-            }
-            ring[(r + d) * RS + col] = val;
+        const double2 *bseq = (const double2 *)p.bloc + ((size_t)b * N) * Delta * C + cc;  // row of position s at s*C
+        const double *bseqY = p.blocY + ((size_t)b * N) * Delta;
+        const double *ckYBb = p.ckYB + (size_t)b * (N + 1);
+        const int nbt = nbc[(size_t)jt * C];
+        double vr[NK], ys[NK], tp[NK];
+        int ns[NK];
+#pragma unroll
+        for (int u = 0; u < NK; ++u) {
+            const int sp = min(tb + g * NK + u, L - 1);  // v_L and what lies beyond are dealt with below
+            const int jv = sp / Delta;
+            vr[u] = bseq[(size_t)sp * C].y;
+            ys[u] = bseqY[sp];
+            tp[u] = min((jv + 1) * Delta, L) == L ? 0.0 : ckYBb[jv + 1];
+            ns[u] = nbc[(size_t)(sp / J) * C];
+        }
+        const double vL = EIc[(size_t)L * C].x;
+        const int nsL = nbc[(size_t)(L / J) * C];
+#pragma unroll
+        for (int u = 0; u < NK; ++u) {
+            const int d = g * NK + u, sp = tb + d;
+            const double lf = (sp == L ? 0.0 : tp[u] + ys[u]) - ybt;
+            const double fl = floor(lf);
+            const int e = (int)fmin(fmax(fl, -100000.0), 100000.0) + (sp == L ? nsL : ns[u]) - nbt;
+            // whole numbers inside an interval: only the rows of the next one carry a fractional factor
+            const double fr = lf - fl;
+            const double val = fmin(ldexp((sp == L ? vL : vr[u]) * (fr == 0.0 ? 1.0 : exp2(fr)), e), DBL_MAX);
+            if (cval && d < K && sp <= L) ring[(r + d) * RS + c] = val;
         }
         ybPrev = browY[tb - t0];
     }
@@ -385,24 +401,30 @@ __global__ __launch_bounds__(64, mg_waves_per_simd(CT, NKW)) void k_mg_wave(Para
     double aA[TRN], bB[TRN];        // operand elements: position pj of the block, label pl of tile tr
     double ya, yb;                  // stored scales of the position just below tfrom (forward, backward)
     int nd;                         // exponent step of this lane's label at the scaling-block boundary tfrom
-    // element offsets fit 32 bits: a slot has Delta*C < 2^27 elements (the plan's limits), a sequence (T+1)*C < 2^31
-    const double2 *const eir = p.EI + (row0 + t0) * C;
-    int cpo[TRN];
+    // Byte offsets from the (wave-uniform) starts of the interval's rows fit 32 bits: a slot has Delta*C < 2^27
+    // pairs (the plan's limits), a sequence fewer than 2^30 position-label pairs (checked by the caller).
+    const char *const arb = (const char *)arow, *const brb = (const char *)brow;
+    const char *const eib = (const char *)(p.EI + (row0 + t0) * C);
+    const unsigned C16 = (unsigned)C * 16u, cc16 = (unsigned)cc * 16u;
+    unsigned cpo16[TRN];  // label pl of tile tr (clamped: what lies beyond C lands in tile rows nobody stores), less pj rows
 #pragma unroll
-    for (int tr = 0; tr < TRN; ++tr) cpo[tr] = min(tr * 16 + pl, C - 1);
+    for (int tr = 0; tr < TRN; ++tr) cpo16[tr] = (unsigned)min(tr * 16 + pl, C - 1) * 16u;
+    auto ld2 = [](const char *base, const unsigned off) { return *(const double2 *)(base + off); };
+    auto ld1 = [](const char *base, const unsigned off) { return *(const double *)(base + off); };
+    // the block below tfrom; rows below the part's first are replaced by that one (nobody uses them)
     auto request = [&](const int tfrom) {
 #pragma unroll
         for (int i = 0; i < MB; ++i) {
-            const unsigned o = (unsigned)(max(tfrom - 1 - i, ta) - t0) * (unsigned)C + (unsigned)cc;
-            aq[i] = arow[o];
-            pv[i] = brow[o];
-            e[i] = eir[o];
+            const unsigned o = (unsigned)(max(tfrom - 1 - i, ta) - t0) * C16 + cc16;  // wave-uniform but for the label
+            aq[i] = ld2(arb, o);
+            pv[i] = ld2(brb, o);
+            e[i] = ld2(eib, o);
         }
-        const unsigned o = (unsigned)(max(tfrom - 1 - pj, ta) - t0) * (unsigned)C;
+        const unsigned om = (unsigned)(max(tfrom - 1 - pj, ta) - t0) * C16;
 #pragma unroll
         for (int tr = 0; tr < TRN; ++tr) {
-            aA[tr] = arow[o + cpo[tr]].x;
-            bB[tr] = brow[o + cpo[tr]].x;
+            aA[tr] = ld1(arb, om + cpo16[tr]);
+            bB[tr] = ld1(brb, om + cpo16[tr]);
         }
         // what a scaling-block boundary at tfrom needs, fetched with every block: a load inside the (rare)
         // boundary branch would make the wave wait there for everything in flight
@@ -413,89 +435,111 @@ __global__ __launch_bounds__(64, mg_waves_per_simd(CT, NKW)) void k_mg_wave(Para
         const int hiE = nbc[(size_t)min(jb, L / J) * C], loE = nbc[(size_t)(jb - 1) * C];
         nd = (tfrom / J >= 1 && (long)jb * J <= (long)L) ? hiE - loE : 0;
     };
-    // The rows of the block after the next are touched one block before they are requested, one 64-byte line
-    // per lane and load (the lines of the forward rows first, then the backward rows, then the (ES, 1/ES) pairs):
-    // the request sits only half a block ahead of its use and then finds them in the cache.  The words that come
-    // back are added up into a word nothing reads, a block later.
-    constexpr int LPA = CT + 1;                       // lines a block of MB rows of one array can touch
-    constexpr int NTCH = (3 * LPA + 63) / 64;
-    const unsigned *tbase[NTCH];
-    unsigned tline[NTCH], tw[NTCH], tsum = 0;
-#pragma unroll
-    for (int u = 0; u < NTCH; ++u) {
-        const int q = lane + 64 * u, arr = min(q / LPA, 2);
-        tbase[u] = (const unsigned *)(arr == 0 ? (const void *)arow : arr == 1 ? (const void *)brow : (const void *)eir);
-        tline[u] = (unsigned)(q - arr * LPA) * 16u;  // in words
-        tw[u] = 0;
-    }
-    const unsigned tlim = (unsigned)(tb - t0) * (unsigned)C * 4u - 1u;  // last word of the rows below tb
-    auto touch = [&](const int tfrom) {  // the block of MB rows below tfrom
-        const unsigned w0 = (unsigned)(max(tfrom - MB, ta) - t0) * (unsigned)C * 4u;
-#pragma unroll
-        for (int u = 0; u < NTCH; ++u) tw[u] = tbase[u][min(w0 + tline[u], tlim)];
-    };
-    // kappa(t,t) of the positions of a scaling block (they share both scales)
-    auto kappa_of = [&]() { return exp((Y0 + ya + Ytop + yb) * LN2 - logZ); };
+    // kappa(t,t) = exp((Y_alpha + Y_beta) ln2 - logZ) of the positions of a scaling block (they share both scales):
+    // the stored scales are whole numbers, so it is one fixed factor in [1, 2) times a power of two
+    const double kx = (Y0 + Ytop) - logZ * LOG2E, kxi = floor(kx);
+    const double kfrac = exp2(kx - kxi);
+    const int kint = (int)fmin(fmax(kxi, -100000.0), 100000.0);
+    auto kappa_of = [&]() { return ldexp(kfrac, kint + (int)(ya + yb)); };
 
     int t = tb;
     const int rdoff = g * NK * RS + c;
     request(t);
     double kappa = kappa_of();
+    float *const gseq = p.grad_emis + ((size_t)b * p.T) * C;
     while (t > ta) {
         const int nb = min(min(t - ta, MB), ((t - 1) & Jm) + 1);
         if (__builtin_expect((t & Jm) == 0, 0)) {
-            // the scan stepped into a new scaling block here: same shift of the window, read off its scales
-            G::rescale(ring, g, c, cval, nd - (int)(yb - ybPrev));
+            // the scan stepped into a new scaling block here: same shift of the live window, read off its scales
+            if (cval) {
+                const int sft = nd - (int)(yb - ybPrev);
+                double *q = ring + (r + g) * RS + c;
+#pragma unroll 8
+                for (int row = g; row < KW; row += G::GW, q += G::GW * RS) *q = fmin(ldexp(*q, sft), DBL_MAX);
+            }
+            lds_wave_fence();
             ybPrev = yb;
             kappa = kappa_of();
         }
         if (__builtin_expect(r < MB, 0)) r = G::template move<true>(ring, lane, r);
         // ---- everything the block needs from its rows; v_t(c) enters the window at once (the rows below the
-        // newest are not among those the block reads; beyond the block's end the store goes to the pad)
+        // newest are not among those the block reads)
         double coef[MB];
+        if (__builtin_expect(nb == MB && t - MB >= 1, 1)) {
+            // a whole block: every lane works on its label cc (the lanes of one label hold the same rows and store the
+            // same values to the same places; what lanes beyond C or the second lane group add up is never stored)
+            float *gp = gseq + ((unsigned)(t - 1) * (unsigned)C + (unsigned)cc);
+            double *rw = ring + (r - 1) * RS + cc;
 #pragma unroll
-        for (int i = 0; i < MB; ++i) {
-            const bool on = i < nb;
-            const int tt = t - 1 - i;
-            coef[i] = (cval && on) ? aq[i].y * kappa : 0.0;  // q_t(c) kappa
-            const double cg = g == 0 ? coef[i] : 0.0;
+            for (int i = 0; i < MB; ++i) {
+                coef[i] = aq[i].y * kappa;  // q_t(c) kappa
 #pragma unroll
-            for (int jn = 0; jn < i; ++jn) dn[i - 1 - jn] = fma(cg, pv[jn].y, dn[i - 1 - jn]);
-            double *rdst = (on && writer) ? ring + (r - 1 - i) * RS + c : ring + RTOT + lane;
-            *rdst = pv[i].y;
-            // a segment of this label starts at tt (z p, z = q ES) / ends at tt (a b, b = v IE; none ends at 0)
-            const double d = on ? (aq[i].y * e[i].x * pv[i].x - (tt >= 1 ? aq[i].x * pv[i].y * e[i].y : 0.0)) * kappa : 0.0;
-            float *dst = (on && writer) ? gout + (unsigned)tt * (unsigned)C : sink;
-            *dst = (float)R;
-            sR += on ? R : 0.0;
-            R += d;
-        }
-        {
+                for (int jn = 0; jn < i; ++jn) dn[i - 1 - jn] = fma(coef[i], pv[jn].y, dn[i - 1 - jn]);
+                rw[-i * RS] = pv[i].y;
+                // a segment of this label starts at the position (z p, z = q ES) / ends at it (a b, b = v IE)
+                const double d = (aq[i].y * e[i].x * pv[i].x - aq[i].x * pv[i].y * e[i].y) * kappa;
+                gp[-i * C] = (float)R;
+                sR += R;
+                R += d;
+            }
+#pragma unroll
+            for (int tr = 0; tr < TRN; ++tr) {
+                const double a = aA[tr] * kappa;
+#pragma unroll
+                for (int tc = 0; tc < TRN; ++tc)
+                    accT[tr][tc] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, bB[tc], accT[tr][tc], 0, 0, 0);
+            }
+        } else {
+            // a short block (at most two at the part's upper end, the last one, the one with position 0):
+            // beyond its end the stores go to the pad and to the sink
+#pragma unroll
+            for (int i = 0; i < MB; ++i) {
+                const bool on = i < nb;
+                const int tt = t - 1 - i;
+                coef[i] = (cval && on) ? aq[i].y * kappa : 0.0;
+                const double cg = g == 0 ? coef[i] : 0.0;
+#pragma unroll
+                for (int jn = 0; jn < i; ++jn) dn[i - 1 - jn] = fma(cg, pv[jn].y, dn[i - 1 - jn]);
+                double *rdst = (on && writer) ? ring + (r - 1 - i) * RS + c : ring + RTOT + lane;
+                *rdst = pv[i].y;
+                // none ends at position 0
+                const double d = on ? (aq[i].y * e[i].x * pv[i].x - (tt >= 1 ? aq[i].x * pv[i].y * e[i].y : 0.0)) * kappa : 0.0;
+                float *dst = (on && writer) ? gout + (unsigned)tt * (unsigned)C : sink;
+                *dst = (float)R;
+                sR += on ? R : 0.0;
+                R += d;
+            }
             const bool on = pj < nb;
 #pragma unroll
             for (int tr = 0; tr < TRN; ++tr) {
-                const double a = (on && tr * 16 + pl < C) ? aA[tr] * kappa : 0.0;
+                const double a = on ? aA[tr] * kappa : 0.0;
 #pragma unroll
-                for (int tc = 0; tc < TRN; ++tc) {
-                    const double bb = (on && tc * 16 + pl < C) ? bB[tc] : 0.0;
-                    accT[tr][tc] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, bb, accT[tr][tc], 0, 0, 0);
-                }
+                for (int tc = 0; tc < TRN; ++tc)
+                    accT[tr][tc] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, on ? bB[tc] : 0.0, accT[tr][tc], 0, 0, 0);
             }
         }
-        // ---- the next block's rows, and a touch of the one after
+        // ---- the next block's rows
         request(t - nb);
-#pragma unroll
-        for (int u = 0; u < NTCH; ++u) tsum += tw[u];
-        touch(t - nb - MB);
+        // window reads in groups of four, each group requested before the multiply-adds of the one before it
+        // (all NK at once would cost their registers, one group at a time would wait for every one)
         const double *base = ring + r * RS + rdoff;
+        double vc[4], vn[4];
 #pragma unroll
-        for (int jj = 0; jj < NK; ++jj) {
-            if (jj % 8 == 0) __builtin_amdgcn_sched_barrier(0);  // window reads eight at a time: not worth the registers of all NK
-            const double v = base[jj * RS];  // distance g*NK + jj from the newest
+        for (int q = 0; q < 4; ++q) vc[q] = base[q * RS];
 #pragma unroll
-            for (int i = 0; i < MB; ++i) dx[jj + i] = fma(coef[i], v, dx[jj + i]);
+        for (int jg = 0; jg < NK; jg += 4) {
+            if (jg + 4 < NK) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) vn[q] = base[(jg + 4 + q) * RS];
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q)  // distance g*NK + jg + q from the newest
+#pragma unroll
+                for (int i = 0; i < MB; ++i) dx[jg + q + i] = fma(coef[i], vc[q], dx[jg + q + i]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) vc[q] = vn[q];
         }
-        __builtin_amdgcn_sched_barrier(0);
         r -= nb;
         lds_wave_fence();
         t -= nb;
@@ -528,6 +572,7 @@ __global__ __launch_bounds__(64, mg_waves_per_simd(CT, NKW)) void k_mg_wave(Para
         lds_wave_fence();
     }
     double *pD = p.partD + part * KC;
+#pragma unroll 8
     for (int i = lane; i < KC; i += 64) pD[i] = p.W[i] * tmp[(i / C) * CT + i % C];
     double *pT = p.partTr + part * CC;
 #pragma unroll
@@ -543,5 +588,4 @@ __global__ __launch_bounds__(64, mg_waves_per_simd(CT, NKW)) void k_mg_wave(Para
         p.tot[part * C + lane] = R;
         p.sumR[part * C + lane] = sR;
     }
-    ((unsigned *)p.sink)[64 + lane] = tsum;
 }

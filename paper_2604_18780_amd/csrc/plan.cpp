@@ -142,18 +142,17 @@ int make_plan(int B, int T, int K, int C, int ckpt_interval, int want_grad, Plan
     sz[PL_CKYB2] = g * b * (n + 1) * 8;
     sz[PL_OUT0] = b * c * 8;
     sz[PL_INL] = b * c * 8;
-    // Marginals from the stored rows of both scans need a second set of row slots.  Measured: the
-    // route wins where the K-deep window makes the interval kernel's recurrence long (K = 512:
-    // 0.52 ms against 1.08 ms), and for shorter durations where its one-wave kernel holds two tasks per
-    // SIMD (K = 64, C = 24: 0.21 ms against 0.33 ms for the stage; with 64 labels, one task per SIMD, it
-    // loses: 0.34 against 0.19 ms).  It is planned there, when every task has its slot and the sizes fit.
+    // Marginals from the stored rows of both scans need a second set of row slots.  Measured, marginal stage
+    // alone, against the interval kernels' own recurrence: K = 512, C = 8: 0.52 against 1.08 ms; K = 64, C = 24:
+    // 0.18 against 0.33 ms; K = 32, C = 64: 0.09 against 0.19 ms; K = 16, C = 24, short sequences: level.  The
+    // route is planned whenever every task has its slot and the sizes fit its kernels.
     const int mg_nsl = (K + MG_KS - 1) / MG_KS;
     const size_t mg_vr = (size_t)MG_TG + (size_t)MG_KS * mg_nsl + 3;
     pl->lds_mg_dur = (MG_TG * c + mg_vr * (c | 3) + MG_TG + 2 * mg_vr + 2 * (size_t)pl->Delta + k) * sizeof(double);
     pl->lds_mg_te = ((size_t)3 * MG_TE * c + pl->Delta) * sizeof(double);
     const int mg_gw = 64 / pow2_ge8(C > 64 ? 64 : C);
     const int mg_per_simd = mg_waves_per_simd(C, (K + mg_gw - 1) / mg_gw);  // of the one-wave kernel (K < 128)
-    const bool rows = !lowmem && (kind == 3 || (kind == 1 && (K >= 128 || mg_per_simd == 2)));
+    const bool rows = !lowmem && (kind == 3 || kind == 1);
     pl->rows = rows && spec_applies(K, C) && ntask <= (size_t)pl->nslot && c * mg_nsl <= 1024 &&
                pl->lds_mg_dur <= LDS_LIMIT && pl->lds_mg_te <= LDS_LIMIT;
     const size_t gr = pl->rows ? 1 : 0;

@@ -29,9 +29,9 @@ enum PlanArray {
     PL_CKB2, PL_CKYA2, PL_CKYB2, PL_OUT0, PL_INL, PL_BLOC, PL_BLOCY, PL_SINK, PL_COUNT
 };
 
-// Kinds of plan (the want_grad argument of semicrf_workspace_bytes): 0 forward only, 1 gradients (stored-row
-// marginals where they pay: K >= 128), 2 gradients of a caller that never takes the stored-row marginals,
-// 3 gradients with the row slots of the stored-row marginals planned; plus PLAN_LOW_MEMORY.
+// Kinds of plan (the want_grad argument of semicrf_workspace_bytes): 0 forward only, 1 gradients (with the row
+// slots of the stored-row marginals where that route applies), 2 gradients of a caller that never takes the
+// stored-row marginals, 3 the same plan as 1 (a caller that asks for that route by flag); plus PLAN_LOW_MEMORY.
 constexpr int PLAN_LOW_MEMORY = 8;
 
 // First warm-up length of the chunk-parallel sum scans: one and a half maximal segment lengths.

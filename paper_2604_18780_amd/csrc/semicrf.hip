@@ -412,7 +412,7 @@ int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hi
     rc = launch_interval(p, pl, st);
     if (rc != SEMICRF_OK) return rc;
     T.mark();
-    hipLaunchKernelGGL(k_fin_seq, dim3(p.B + (p.C * p.C + p.K * p.C + 31) / 32 + ((p.g_pi_start || p.g_pi_end) ? 1 : 0)),
+    hipLaunchKernelGGL(k_fin_seq, dim3(p.B + (p.C * p.C + p.K * p.C + FIN_PO - 1) / FIN_PO + ((p.g_pi_start || p.g_pi_end) ? 1 : 0)),
                        dim3(NT), 0, st, p);
     {
         size_t n = (size_t)p.T * p.C;
