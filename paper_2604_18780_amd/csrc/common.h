@@ -104,7 +104,7 @@ struct Params {
     double *tot;        // [B][NP][C]
     double *sumR;       // [B][NP][C]
     double *carry;      // [B][NP][C]
-    double *mean;       // [B][C]
+    double *mean;       // [B][FIN_SLICES][C]  sums behind the per-label mean of the position marginals
     double *out0;       // [B][C]  mass of the segments that start at position 0, per label
     double *inL;        // [B][C]  mass of the segments that end at position L, per label
     // outputs

@@ -663,16 +663,16 @@ __global__ __launch_bounds__(1024) void k_dt_acc(Params p)
     }
 }
 
-// Finalisation: workgroups 0..B-1 per sequence (interval carries and means, as for the
+// Finalisation: FIN_FS workgroups per sequence (interval carries and means, as for the
 // factorised path), the others sum the per-workgroup marginal sums in workgroup order.
 __global__ __launch_bounds__(NT) void k_dt_fin(Params p)
 {
-    if ((int)blockIdx.x < p.B) {
-        fin_seq_body(p, blockIdx.x);
+    if ((int)blockIdx.x < p.B * FIN_FS) {
+        fin_seq_body(p, blockIdx.x / FIN_FS, blockIdx.x % FIN_FS);
         return;
     }
     const size_t n = (size_t)p.K * p.C * p.C;
-    const size_t i = (size_t)(blockIdx.x - p.B) * NT + threadIdx.x;
+    const size_t i = (size_t)(blockIdx.x - p.B * FIN_FS) * NT + threadIdx.x;
     if (i >= n) return;
     double s = 0.0;
     for (int w = 0; w < p.dt_nwg; ++w) s += p.partG[(size_t)w * n + i];

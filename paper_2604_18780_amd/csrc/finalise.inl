@@ -11,10 +11,13 @@ __device__ __forceinline__ int stat_delta(const Params &p, const int b)
     return (p.msplit > 1 && p.spec_ok[b * 2] && p.spec_ok[b * 2 + 1]) ? p.Delta / p.msplit : p.Delta;
 }
 
-// carry[b,i,c] = sum_{i'<=i} tot[b,i',c];  mean[b,c] = (1/L) sum_u pm[b,u,c].  grid B, NT threads:
-// the intervals are split into G = NT/C contiguous chunks, one per thread group; chunk sums are
-// combined in chunk order, so the result does not depend on the launch shape.
-__device__ __forceinline__ void fin_seq_body(const Params &p, const int b)
+// carry[b,i,c] = sum_{i'<=i} tot[b,i',c] and the sums behind mean[b,c] = (1/L) sum_u pm[b,u,c].  FIN_FS workgroups
+// per sequence, each a contiguous slice of the sequence's partial sums (it first adds up, label by label, what
+// lies before its slice).  Inside a workgroup the partial sums are split into G = NT/C contiguous chunks, one per
+// thread group; chunk sums are combined in chunk order, so the result does not depend on the launch shape.
+// mean is left as FIN_FS sums per label; k_fin_emis adds them and divides.
+constexpr int FIN_FS = FIN_SLICES;
+__device__ __forceinline__ void fin_seq_body(const Params &p, const int b, const int s)
 {
     __shared__ double gsum[NT];
     __shared__ double gtot[NT];
@@ -24,17 +27,37 @@ __device__ __forceinline__ void fin_seq_body(const Params &p, const int b)
     const int nint = (L + Ds - 1) / Ds;
     const int G = NT / C;
     const int g = tid / C, c = tid % C;
-    const int per = (nint + G - 1) / G;
-    const int i0 = min(g * per, nint), i1 = min(i0 + per, nint);
     const bool act = g < G;
+    const int per_s = (nint + FIN_FS - 1) / FIN_FS;
+    const int s0 = min(s * per_s, nint), s1 = min(s0 + per_s, nint);
+    const double *tot = p.tot + ((size_t)b * N) * C + c;
+    // what lies before the slice
+    {
+        const int per = (s0 + G - 1) / G;
+        const int a0 = min(g * per, s0), a1 = min(a0 + per, s0);
+        double pre = 0.0;
+        if (act) {
+#pragma unroll 8
+            for (int i = a0; i < a1; ++i) pre += tot[(size_t)i * C];
+        }
+        gsum[tid] = pre;
+    }
+    __syncthreads();
+    double run = 0.0;
+    if (act)
+        for (int gg = 0; gg < G; ++gg) run += gsum[gg * C + c];
+    __syncthreads();
+    // the slice
+    const int per = (s1 - s0 + G - 1) / G;
+    const int i0 = min(s0 + g * per, s1), i1 = min(i0 + per, s1);
     double loc = 0.0;
     if (act) {
 #pragma unroll 8
-        for (int i = i0; i < i1; ++i) loc += p.tot[((size_t)b * N + i) * C + c];
+        for (int i = i0; i < i1; ++i) loc += tot[(size_t)i * C];
     }
     gsum[tid] = loc;
     __syncthreads();
-    double run = 0.0, total = 0.0;
+    double total = 0.0;
     if (act) {
         for (int gg = 0; gg < g; ++gg) run += gsum[gg * C + c];
 #pragma unroll 8
@@ -51,11 +74,11 @@ __device__ __forceinline__ void fin_seq_body(const Params &p, const int b)
     if (tid < C) {
         double t = 0.0;
         for (int gg = 0; gg < G; ++gg) t += gtot[gg * C + tid];
-        p.mean[(size_t)b * C + tid] = (p.center && L > 0) ? t / (double)L : 0.0;
+        p.mean[((size_t)b * FIN_FS + s) * C + tid] = t;
     }
     // boundary posterior: certain at both ends of the sequence, nothing beyond it (the interval
     // kernels wrote positions 1 .. L-1)
-    if (p.bdy_post) {
+    if (p.bdy_post && s == 0) {
         float *bd = p.bdy_post + (size_t)b * (p.T + 1);
         for (int t = tid; t <= p.T; t += NT)
             if (t == 0 || t >= L) bd[t] = (t == 0 || t == L) ? 1.f : 0.f;
@@ -80,6 +103,9 @@ __device__ __forceinline__ void fin_pi_body(const Params &p)
 }
 
 // grad_emis / pos_marg, elementwise over (u,c) of one sequence.  grid (blocks, B).
+// V = 4: four labels of one position per thread as 16-byte accesses (C a multiple of 4, outputs 16-byte aligned,
+// fewer than 2^31 elements per sequence, no boundary projections among the outputs); V = 1: the general form.
+template <int V>
 __global__ __launch_bounds__(NT) void k_fin_emis(Params p)
 {
     const int b = blockIdx.y, C = p.C;
@@ -89,7 +115,34 @@ __global__ __launch_bounds__(NT) void k_fin_emis(Params p)
     const size_t base = (size_t)b * n;
     const double *carry = p.carry + ((size_t)b * p.NP) * C;
     const int Ds = stat_delta(p, b);
-    const double *mean = p.mean + (size_t)b * C;
+    __shared__ double mean[GRAD_CMAX];
+    if ((int)threadIdx.x < C) {
+        double t = 0.0;
+        for (int s = 0; s < FIN_FS; ++s) t += p.mean[((size_t)b * FIN_FS + s) * C + threadIdx.x];
+        mean[threadIdx.x] = (p.center && L > 0) ? t / (double)L : 0.0;
+    }
+    __syncthreads();
+    if (V == 4) {
+        const unsigned Cq = (unsigned)C / 4u, nq = (unsigned)(n / 4), step = gridDim.x * NT;
+        float4 *ge4 = (float4 *)(p.grad_emis + base);
+        float4 *pm4 = p.pos_marg ? (float4 *)(p.pos_marg + base) : nullptr;
+        for (unsigned q = blockIdx.x * NT + threadIdx.x; q < nq; q += step) {
+            const unsigned u = q / Cq, c = (q - u * Cq) * 4u;
+            float4 ge = make_float4(0.f, 0.f, 0.f, 0.f), pmv = ge;
+            if ((int)u < L) {
+                const double *cr = carry + (size_t)(u / (unsigned)Ds) * C + c;
+                const float4 r = ge4[q];
+                const double pm0 = cr[0] - (double)r.x, pm1 = cr[1] - (double)r.y;
+                const double pm2 = cr[2] - (double)r.z, pm3 = cr[3] - (double)r.w;
+                ge = make_float4((float)(w * (pm0 - mean[c])), (float)(w * (pm1 - mean[c + 1])),
+                                 (float)(w * (pm2 - mean[c + 2])), (float)(w * (pm3 - mean[c + 3])));
+                pmv = make_float4((float)pm0, (float)pm1, (float)pm2, (float)pm3);
+            }
+            ge4[q] = ge;
+            if (pm4) pm4[q] = pmv;
+        }
+        return;
+    }
     auto one = [&](const size_t idx, const int u, const int c) {
         float ge = 0.f, pmv = 0.f;
         if (u < L) {
@@ -116,6 +169,18 @@ __global__ __launch_bounds__(NT) void k_fin_emis(Params p)
         for (size_t idx = (size_t)blockIdx.x * NT + threadIdx.x; idx < n; idx += (size_t)gridDim.x * NT)
             one(idx, (int)(idx / C), (int)(idx % C));
     }
+}
+
+// Launch of k_fin_emis in the form the sizes and outputs allow.
+inline void launch_fin_emis(const Params &p, hipStream_t st)
+{
+    const size_t n = (size_t)p.T * p.C;
+    const bool vec = p.C % 4 == 0 && n < ((size_t)1 << 31) && !p.g_proj_start && !p.g_proj_end &&
+                     ((uintptr_t)p.grad_emis & 15) == 0 && ((uintptr_t)p.pos_marg & 15) == 0;
+    size_t blocks = ((vec ? n / 4 : n) + NT - 1) / NT;
+    if (blocks > 16384) blocks = 16384;
+    if (vec) hipLaunchKernelGGL(k_fin_emis<4>, dim3((unsigned)blocks, p.B), dim3(NT), 0, st, p);
+    else hipLaunchKernelGGL(k_fin_emis<1>, dim3((unsigned)blocks, p.B), dim3(NT), 0, st, p);
 }
 
 // grad_trans[c',c] = Etr[c',c] * sum_b w_b sum_i partTr;  grad_dur[k,c] = sum_b w_b sum_i partD.
@@ -162,13 +227,14 @@ __device__ __forceinline__ void fin_params_body(const Params &p, const int blk)
     }
 }
 
-// One launch for the two independent reductions: workgroups 0..B-1 per sequence, the rest
+// One launch for the two independent reductions: FIN_FS workgroups per sequence, the rest
 // per FIN_PO parameter gradients.
 __global__ __launch_bounds__(NT) void k_fin_seq(Params p)
 {
     const int nparam = (p.C * p.C + p.K * p.C + FIN_PO - 1) / FIN_PO;
-    if ((int)blockIdx.x < p.B) fin_seq_body(p, blockIdx.x);
-    else if ((int)blockIdx.x < p.B + nparam) fin_params_body(p, blockIdx.x - p.B);
+    const int nseq = p.B * FIN_FS;
+    if ((int)blockIdx.x < nseq) fin_seq_body(p, blockIdx.x / FIN_FS, blockIdx.x % FIN_FS);
+    else if ((int)blockIdx.x < nseq + nparam) fin_params_body(p, blockIdx.x - nseq);
     else fin_pi_body(p);
 }
 

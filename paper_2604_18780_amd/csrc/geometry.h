@@ -22,6 +22,7 @@ constexpr int MB = 4;      // positions per time block of the one-wave kernels
 constexpr int MG_TG = 32;  // stored-row marginals: positions staged at a time
 constexpr int MG_KS = 8;   // stored-row marginals: durations per thread of the duration kernel
 constexpr int MG_TE = 64;  // stored-row marginals: positions per group of the transition/emission kernel
+constexpr int FIN_SLICES = 4;    // workgroups per sequence of the carry / mean reduction (sums behind the mean per slice)
 constexpr int MG_SIMDS = 1024;  // SIMDs of the chip (256 compute units of four)
 
 // Tasks of the one-wave stored-row marginals a SIMD holds: two where the duration strip of a lane (NKW) and the

@@ -135,7 +135,7 @@ int make_plan(int B, int T, int K, int C, int ckpt_interval, int want_grad, Plan
     sz[PL_CKYB] = g * b * (n + 1) * 8;
     sz[PL_ALOC] = g * (size_t)pl->nslot * pl->Delta * 2 * c * 8;
     sz[PL_ALOCY] = g * (size_t)pl->nslot * pl->Delta * 8;
-    sz[PL_MEAN] = g * b * c * 8;
+    sz[PL_MEAN] = g * b * FIN_SLICES * c * 8;
     sz[PL_CKA2] = b * (n + 1) * (k * c + c) * 8;
     sz[PL_CKB2] = g * b * (n + 1) * (k * c + c) * 8;
     sz[PL_CKYA2] = b * (n + 1) * 8;

@@ -412,14 +412,9 @@ int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hi
     rc = launch_interval(p, pl, st);
     if (rc != SEMICRF_OK) return rc;
     T.mark();
-    hipLaunchKernelGGL(k_fin_seq, dim3(p.B + (p.C * p.C + p.K * p.C + FIN_PO - 1) / FIN_PO + ((p.g_pi_start || p.g_pi_end) ? 1 : 0)),
+    hipLaunchKernelGGL(k_fin_seq, dim3(p.B * FIN_FS + (p.C * p.C + p.K * p.C + FIN_PO - 1) / FIN_PO + ((p.g_pi_start || p.g_pi_end) ? 1 : 0)),
                        dim3(NT), 0, st, p);
-    {
-        size_t n = (size_t)p.T * p.C;
-        size_t blocks = (n + NT - 1) / NT;
-        if (blocks > 16384) blocks = 16384;
-        hipLaunchKernelGGL(k_fin_emis, dim3((unsigned)blocks, p.B), dim3(NT), 0, st, p);
-    }
+    launch_fin_emis(p, st);
     T.mark();
     return check_launch();
 }
@@ -747,14 +742,9 @@ int run_durtrans(Params p, int ckpt_interval, void *workspace, size_t workspace_
     if (rc != SEMICRF_OK) return rc;
     hipLaunchKernelGGL(k_dt_emis, dim3(p.B * p.N), dim3(64), 0, st, p);
     hipLaunchKernelGGL((k_dt_acc<16>), dim3(dl.nwg, (p.K + 15) / 16), dim3(g.nta), g.lds_a, st, p);
-    hipLaunchKernelGGL(k_dt_fin, dim3(p.B + (unsigned)((kcc + NT - 1) / NT)), dim3(NT), 0, st, p);
+    hipLaunchKernelGGL(k_dt_fin, dim3(p.B * FIN_FS + (unsigned)((kcc + NT - 1) / NT)), dim3(NT), 0, st, p);
     hipLaunchKernelGGL(k_dt_fin_dur, dim3((p.K * p.C + NT - 1) / NT), dim3(NT), 0, st, p);
-    {
-        size_t n = (size_t)p.T * p.C;
-        size_t blocks = (n + NT - 1) / NT;
-        if (blocks > 16384) blocks = 16384;
-        hipLaunchKernelGGL(k_fin_emis, dim3((unsigned)blocks, p.B), dim3(NT), 0, st, p);
-    }
+    launch_fin_emis(p, st);
     return check_launch();
 }
 

@@ -209,14 +209,28 @@ __device__ __forceinline__ void spec_task(const Params &p, double *lds_raw, cons
         for (int i = 0; i < MB; ++i) acc[i] = group_sum<CTP>(acc[i]);
         // ---- the positions one after the other
         double qn[MB];
+        // A whole block (nearly all are): nothing is decided per position.  The rows of a block that lies in the
+        // chunk go out through one pointer per lane (the lanes that own no label store to a sink), its scale once
+        // for the MB positions.  A forward block that reaches the chunk's end takes the general path (the end
+        // position itself has no row).
+        if (__builtin_expect(nb == MB && (BWD || !inchunk || t + MB < hi), 1)) {
+            double2 *rowp = (double2 *)p.sink + lane;
+            int rstep = 0;
+            if (inchunk) {
+                const int p0 = BWD ? t - 1 - lo : t + 1 - lo;  // slot row of the block's first position
+                if (writer) {
+                    rowp = aloc + (size_t)p0 * C + c;
+                    rstep = BWD ? -C : C;
+                }
+                alocY[BWD ? p0 - (lane & (MB - 1)) : p0 + (lane & (MB - 1))] = Y - Yrec;  // every lane, the same value
+            }
 #pragma unroll
-        for (int i = 0; i < MB; ++i) {
-            if (i < nb) {
+            for (int i = 0; i < MB; ++i) {
                 double x = acc[i];
 #pragma unroll
                 for (int jn = 0; jn < i; ++jn) x = fma(wn[i - 1 - jn], qn[jn], x);
                 const double y = x * (BWD ? e[i].y : e[i].x);
-                if (cval) yv[c] = y;
+                yv[c] = y;  // both lane groups the same value; entries beyond C are zero and nobody reads them
                 lds_wave_fence();
                 double z0 = 0.0, z1 = 0.0;
 #pragma unroll
@@ -231,18 +245,46 @@ __device__ __forceinline__ void spec_task(const Params &p, double *lds_raw, cons
                 qn[i] = q;
                 r += BWD ? -1 : 1;
                 if (writer) ring[r * RS + c] = q;
-                if (!BWD && inchunk && t + 1 + i < hi) {
-                    if (writer) aloc[(size_t)(t + 1 + i - lo) * C + c] = make_double2(y, q);
-                    if (lane == 0) alocY[t + 1 + i - lo] = Y - Yrec;
-                }
-                if (BWD && inchunk) {  // position t - 1 - i of [lo, hi)
-                    if (writer) aloc[(size_t)(t - 1 - i - lo) * C + c] = make_double2(y, q);
-                    if (lane == 0) alocY[t - 1 - i - lo] = Y - Yrec;
-                }
+                if (keep) rowp[i * rstep] = make_double2(y, q);
                 lds_wave_fence();
-            } else {
-                qn[i] = 0.0;
             }
+        } else {
+    #pragma unroll
+            for (int i = 0; i < MB; ++i) {
+                if (i < nb) {
+                    double x = acc[i];
+    #pragma unroll
+                    for (int jn = 0; jn < i; ++jn) x = fma(wn[i - 1 - jn], qn[jn], x);
+                    const double y = x * (BWD ? e[i].y : e[i].x);
+                    if (cval) yv[c] = y;
+                    lds_wave_fence();
+                    double z0 = 0.0, z1 = 0.0;
+    #pragma unroll
+                    for (int o = 0; o < HC; o += 2) {
+                        const double2 vv = ys[o >> 1];
+                        z0 = fma(vv.x, Ereg[o], z0);
+                        z1 = fma(vv.y, Ereg[o + 1], z1);
+                    }
+                    double z = z0 + z1;
+                    if (H == 2) z = add_across_32(z);
+                    const double q = z * (BWD ? e[i].x : e[i].y);
+                    qn[i] = q;
+                    r += BWD ? -1 : 1;
+                    if (writer) ring[r * RS + c] = q;
+                    if (!BWD && inchunk && t + 1 + i < hi) {
+                        if (writer) aloc[(size_t)(t + 1 + i - lo) * C + c] = make_double2(y, q);
+                        if (lane == 0) alocY[t + 1 + i - lo] = Y - Yrec;
+                    }
+                    if (BWD && inchunk) {  // position t - 1 - i of [lo, hi)
+                        if (writer) aloc[(size_t)(t - 1 - i - lo) * C + c] = make_double2(y, q);
+                        if (lane == 0) alocY[t - 1 - i - lo] = Y - Yrec;
+                    }
+                    lds_wave_fence();
+                } else {
+                    qn[i] = 0.0;
+                }
+            }
+
         }
         t = tn;
 #pragma unroll
