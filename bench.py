@@ -130,16 +130,21 @@ class Problem:
         recurrence once each (2 units; its forward tasks also leave the rows that Algorithm 3 would recompute
         per interval); the interval stage runs the backward recurrence again inside each interval and
         accumulates the marginals (2 units), or forms the marginals from the rows both scans stored (1 unit;
-        the default for K >= 128).  Warm-up positions of the chunk-parallel scans are overhead, not counted."""
+        the default wherever the plan has a row slot per interval for both scans).  Warm-up positions of the
+        chunk-parallel scans are overhead, not counted."""
         from paper_2604_18780_amd import binding as sb
         w = self.w
         unit = 2.0 * (w.K * w.C + w.C * w.C) * w.positions
-        rows_route = bool(self.flags & sb.SEMICRF_MARGINALS_ROWS) or (
-            w.K >= 128 and not (self.flags & sb.SEMICRF_MARGINALS_INTERVAL))
+        # the plan of a default call holds the backward tasks' row slots exactly where that route is taken
+        planned = (not (self.flags & sb.SEMICRF_LOW_MEMORY) and
+                   sb.semicrf_workspace_bytes(w.B, w.T, w.K, w.C, self.delta, 1) >
+                   sb.semicrf_workspace_bytes(w.B, w.T, w.K, w.C, self.delta, 2))
+        rows_route = planned and not (self.flags & sb.SEMICRF_MARGINALS_INTERVAL)
         stage_flop = {"scans": 2 * unit, "intervals": (1 if rows_route else 2) * unit}
         kernels = {"scans": "k_spec (chunk-parallel forward + backward scans, one launch; stage time "
                             "includes its small verification kernels and the early exits of the retries)",
-                   "intervals": ("k_mg_dur + k_mg_te (marginals from the stored rows of both scans, two launches)"
+                   "intervals": (("k_mg_wave (marginals from the stored rows of both scans, one launch)" if w.K < 128 else
+                                  "k_mg_dur + k_mg_te (marginals from the stored rows of both scans, two launches)")
                                  if rows_route else
                                  "k_interval_wave / k_interval (per-interval recompute + marginals, one launch)")}
         dom = "scans" if stage[1] >= stage[2] else "intervals"
