@@ -342,39 +342,30 @@ __global__ __launch_bounds__(64, mg_waves_per_simd(CT, NKW)) void k_mg_wave(Para
             ring[(r + G::template slot_dist<true>(sl, tm, K)) * RS + col] = ck[i];
         }
     } else {
-        // inside the interval: the rows v_tb .. v_{tb+K-1} as the scans of this and the following intervals
-        // stored them, each brought from the frame of its own scaling block into that of position tb (the
-        // powers of two the scan applied on its way down from there, and the difference of the scales)
-        // Lane (g, c) fills its own strip, rows g*NK .. of label c; everything is loaded first, so that the
-        // loads of all rows are in flight together (the rows of a sequence's slots are consecutive).
-        const int jt = tb / J;
-        const double ybt = mg_yb(p, b, iv, tb - t0, L);
-        const double2 *bseq = (const double2 *)p.bloc + ((size_t)b * N) * Delta * C + cc;  // row of position s at s*C
-        const double *bseqY = p.blocY + ((size_t)b * N) * Delta;
-        const double *ckYBb = p.ckYB + (size_t)b * (N + 1);
-        const int nbt = nbc[(size_t)jt * C];
-        double vr[NK], ys[NK], tp[NK];
+        // inside the interval: the rows v_tb .. v_{tb+K-1} as the backward task stored them (a part is at least
+        // K positions long, so they all belong to this interval, or are v_L), each brought from the frame of its own
+        // scaling block into that of position tb: the powers of two the scan applied on its way down from there
+        // and the difference of the stored scales (whole numbers).  Lane (g, c) fills its own strip, rows g*NK ..
+        // of label c; everything is loaded first, so that the loads of all rows are in flight together.
+        const int nbt = nbc[(size_t)(tb / J) * C];
+        const double ybt = browY[tb - t0];
+        const int top = min(t1 - 1, L - 1) - t0;  // last stored row of the interval
+        double vr[NK], ys[NK];
         int ns[NK];
 #pragma unroll
         for (int u = 0; u < NK; ++u) {
-            const int sp = min(tb + g * NK + u, L - 1);  // v_L and what lies beyond are dealt with below
-            const int jv = sp / Delta;
-            vr[u] = bseq[(size_t)sp * C].y;
-            ys[u] = bseqY[sp];
-            tp[u] = min((jv + 1) * Delta, L) == L ? 0.0 : ckYBb[jv + 1];
-            ns[u] = nbc[(size_t)(sp / J) * C];
+            const int i = min(tb - t0 + g * NK + u, top);  // v_L and what lies beyond are dealt with below
+            vr[u] = brow[(size_t)i * C + cc].y;
+            ys[u] = browY[i];
+            ns[u] = nbc[(size_t)((t0 + i) / J) * C];
         }
-        const double vL = EIc[(size_t)L * C].x;
+        const double vL = EIc[(size_t)L * C].x;  // scale 0 relative to the upper end
         const int nsL = nbc[(size_t)(L / J) * C];
 #pragma unroll
         for (int u = 0; u < NK; ++u) {
             const int d = g * NK + u, sp = tb + d;
-            const double lf = (sp == L ? 0.0 : tp[u] + ys[u]) - ybt;
-            const double fl = floor(lf);
-            const int e = (int)fmin(fmax(fl, -100000.0), 100000.0) + (sp == L ? nsL : ns[u]) - nbt;
-            // whole numbers inside an interval: only the rows of the next one carry a fractional factor
-            const double fr = lf - fl;
-            const double val = fmin(ldexp((sp == L ? vL : vr[u]) * (fr == 0.0 ? 1.0 : exp2(fr)), e), DBL_MAX);
+            const int e = (int)fmin(fmax((sp == L ? 0.0 : ys[u]) - ybt, -100000.0), 100000.0) + (sp == L ? nsL : ns[u]) - nbt;
+            const double val = fmin(ldexp(sp == L ? vL : vr[u], e), DBL_MAX);
             if (cval && d < K && sp <= L) ring[(r + d) * RS + c] = val;
         }
         ybPrev = browY[tb - t0];

@@ -366,7 +366,8 @@ int run(Params p, int ckpt_interval, void *workspace, size_t workspace_bytes, hi
     p.marg = pl.rows && p.fuse && !bterms;
     if (p.K < 128 && ((double)p.T + 1.0) * (double)p.C >= 2147483648.0)
         p.marg = 0;  // the one-wave kernel indexes a sequence's rows with 32 bits
-    if (p.marg && p.K < 128) p.msplit = pl.msplit;  // the partial-sum arrays are planned for N * pl.msplit either way
+    // (the partial-sum arrays are planned for N * pl.msplit either way; a part holds at least K positions)
+    if (p.marg && p.K < 128 && pl.Delta / pl.msplit >= p.K) p.msplit = pl.msplit;
     T.mark();
     rc = launch_prep(p, st);
     T.mark();

@@ -406,6 +406,36 @@ def test_marginals_from_stored_rows(seed, B, T, K, C):
                          extra_flags=ROWS)
 
 
+@pytest.mark.parametrize("seed,B,T,K,C,delta,lengths,scale", [
+    # two intervals of 320 cut into four parts of 80: lengths that end inside a part, on a part boundary, on the
+    # interval boundary, one position into the second interval, and short of one block
+    (81, 6, 600, 20, 5, 320, [600, 81, 160, 320, 321, 3], 1.0),
+    # two label tiles on the matrix cores, parts of 88 >= K = 40; emissions of scale 6 shorten the scaling block,
+    # so that part boundaries fall inside scaling blocks and the window fill crosses several of them
+    (82, 2, 700, 40, 24, 352, [700, 439], 6.0),
+    # 64 labels (one task per SIMD variant), parts of 64 >= K
+    (83, 2, 300, 33, 64, 128, [300, 191], 1.0),
+    # parts as short as the plan allows (K = 32 positions each) and a sequence that ends with position 0's block
+    (84, 3, 256, 32, 8, 128, [256, 4, 97], 1.0),
+])
+def test_stored_row_marginals_in_parts(seed, B, T, K, C, delta, lengths, scale):
+    """The one-wave stored-row kernel with every interval cut into parts (few tasks: the plan cuts into 2 or 4):
+    upper parts start from the checkpoint, inner parts fill their window from the stored rows."""
+    w = synth.small_random(seed, B, T, K, C, ragged=False, scale=scale)
+    w.lengths[:] = lengths
+    rng = np.random.default_rng(seed)
+    check_against_oracle(w, grad_logz=rng.standard_normal(B), ckpt_interval=delta,
+                         label=f"stored rows in parts, rand{seed}", extra_flags=sb.SEMICRF_MARGINALS_ROWS)
+    # the per-part partial sums must give the same outputs as one partial sum per interval
+    emis, lens, trans, dur = to_dev(w)
+    a = sb.semicrf_fwd_bwd(emis, lens, trans, dur, None, delta, sb.SEMICRF_CENTER)
+    b = sb.semicrf_fwd_bwd(emis, lens, trans, dur, None, delta, sb.SEMICRF_CENTER | sb.SEMICRF_MARGINALS_INTERVAL)
+    torch.cuda.synchronize()
+    for x, y in zip(a[1:], b[1:]):
+        d = (x.double() - y.double()).abs().max().item()
+        assert d <= 2e-5 * max(1.0, y.double().abs().max().item()), d
+
+
 def test_marginals_from_stored_rows_large_scale_and_mixed_acceptance():
     ROWS, ITV = sb.SEMICRF_MARGINALS_ROWS, sb.SEMICRF_MARGINALS_INTERVAL
     # scaling blocks of a few positions
