@@ -188,6 +188,17 @@ __device__ __forceinline__ double add_across_32(double v)
     return __hiloint2double((int)b[0], (int)a[0]) + __hiloint2double((int)b[1], (int)a[1]);
 }
 
+// The value lanes 0..31 hold (-> lo_half) and the one lanes 32..63 hold (-> hi_half), lane l paired with lane
+// l + 32, both delivered to both lanes.
+__device__ __forceinline__ void both_halves(const double v, double &lo_half, double &hi_half)
+{
+    const unsigned lo = (unsigned)__double2loint(v), hi = (unsigned)__double2hiint(v);
+    const auto a = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
+    const auto b = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
+    lo_half = __hiloint2double((int)b[0], (int)a[0]);
+    hi_half = __hiloint2double((int)b[1], (int)a[1]);
+}
+
 // v + (v of the lane 16 away): odd rows of one copy are swapped with even rows of the other
 __device__ __forceinline__ double add_across_16(double v)
 {

@@ -387,8 +387,15 @@ __global__ __launch_bounds__(64, mg_waves_per_simd(CT, NKW)) void k_mg_wave(Para
     float *const sink = (float *)p.sink + lane;
     float *const gout = p.grad_emis + ((size_t)b * p.T) * C + cc;
 
-    // the rows of one block of positions, as they come from memory
-    double2 aq[MB], pv[MB], e[MB];  // this lane's label, the MB positions below tfrom
+    // The rows of one block of positions, as they come from memory.  Where a label's lanes come in pairs 32 apart
+    // (CTP <= 32) the lower half of the wave fetches the block's first two positions and the upper half the
+    // other two: half the row loads, which is what this kernel waits for most (the few values the other half
+    // needs travel by v_permlane32_swap).  With 64 labels per lane group every lane fetches all four.
+    static_assert(MB == 4, "the split of a block between the halves of the wave is written for four positions");
+    constexpr bool SPLIT = CTP <= 32;
+    constexpr int NPL = SPLIT ? MB / 2 : MB;  // positions of a block this lane fetches
+    const int pofs = SPLIT ? (lane >> 5) * NPL : 0;  // the first of them
+    double2 aq[NPL], pv[NPL], e[NPL];  // this lane's label, positions pofs .. pofs+NPL-1 below tfrom
     double aA[TRN], bB[TRN];        // operand elements: position pj of the block, label pl of tile tr
     double ya, yb;                  // stored scales of the position just below tfrom (forward, backward)
     int nd;                         // exponent step of this lane's label at the scaling-block boundary tfrom
@@ -405,11 +412,11 @@ __global__ __launch_bounds__(64, mg_waves_per_simd(CT, NKW)) void k_mg_wave(Para
     // the block below tfrom; rows below the part's first are replaced by that one (nobody uses them)
     auto request = [&](const int tfrom) {
 #pragma unroll
-        for (int i = 0; i < MB; ++i) {
-            const unsigned o = (unsigned)(max(tfrom - 1 - i, ta) - t0) * C16 + cc16;  // wave-uniform but for the label
-            aq[i] = ld2(arb, o);
-            pv[i] = ld2(brb, o);
-            e[i] = ld2(eib, o);
+        for (int l = 0; l < NPL; ++l) {
+            const unsigned o = (unsigned)(max(tfrom - 1 - l - pofs, ta) - t0) * C16 + cc16;
+            aq[l] = ld2(arb, o);
+            pv[l] = ld2(brb, o);
+            e[l] = ld2(eib, o);
         }
         const unsigned om = (unsigned)(max(tfrom - 1 - pj, ta) - t0) * C16;
 #pragma unroll
@@ -456,35 +463,92 @@ __global__ __launch_bounds__(64, mg_waves_per_simd(CT, NKW)) void k_mg_wave(Para
         // ---- everything the block needs from its rows; v_t(c) enters the window at once (the rows below the
         // newest are not among those the block reads)
         double coef[MB];
-        if (__builtin_expect(nb == MB && t - MB >= 1, 1)) {
-            // a whole block: every lane works on its label cc (the lanes of one label hold the same rows and store the
-            // same values to the same places; what lanes beyond C or the second lane group add up is never stored)
+        const bool whole = nb == MB && t - MB >= 1;
+        if (SPLIT && whole) {
+            // This lane's positions of the block: pofs + l, rows t-1-pofs-l.  A whole block (nearly all are) decides
+            // nothing per position: every lane works on its label cc (the lanes of one label and half hold the same
+            // rows and store the same values to the same places; what lanes beyond C add up is never stored).
+            double dl[NPL];
+#pragma unroll
+            for (int l = 0; l < NPL; ++l) {
+                both_halves(aq[l].y * kappa, coef[l], coef[NPL + l]);  // q_t(c) kappa of positions l and NPL + l
+                // a segment of this label starts at the position (z p, z = q ES) / ends at it (a b, b = v IE)
+                dl[l] = (aq[l].y * e[l].x * pv[l].x - aq[l].x * pv[l].y * e[l].y) * kappa;
+            }
+            // durations 1..3 inside the block: this lane's v rows with the coefficients of the later positions
+            // (lower half: positions 0, 1; upper half: 2, 3; the two halves are added up at the end)
+            const bool lowh = pofs == 0;
+            const double k13 = lowh ? coef[1] : coef[3], k2 = lowh ? coef[2] : 0.0, k3 = lowh ? coef[3] : 0.0;
+            dn[0] = fma(k13, pv[0].y, dn[0]);
+            dn[1] = fma(k2, pv[0].y, dn[1]);
+            dn[2] = fma(k3, pv[0].y, dn[2]);
+            dn[0] = fma(k2, pv[1].y, dn[0]);
+            dn[1] = fma(k3, pv[1].y, dn[1]);
+            // running emission sums: R before the block, plus what the positions before this lane's add
+            double s01, s23;
+            both_halves(dl[0] + dl[1], s01, s23);
+            const double r0 = lowh ? R : R + s01, r1 = r0 + dl[0];
+            sR += r0 + r1;
+            R = (R + s01) + s23;
+            float *gp = gseq + ((unsigned)(t - 1 - pofs) * (unsigned)C + (unsigned)cc);
+            double *rw = ring + (r - 1 - pofs) * RS + cc;
+            rw[0] = pv[0].y;
+            rw[-RS] = pv[1].y;
+            gp[0] = (float)r0;
+            gp[-C] = (float)r1;
+        } else if (SPLIT) {
+            // A short block (at most two at the part's upper end, the last one, the one with position 0): the
+            // positions beyond its end count nothing and their stores go to the pad and to the sink.  The lanes
+            // beyond C keep label cc's running sums here too: in whole blocks they store them.
+            double dl[NPL];
+            bool act[NPL];
+#pragma unroll
+            for (int l = 0; l < NPL; ++l) {
+                const int tt = t - 1 - pofs - l;
+                act[l] = pofs + l < nb;
+                both_halves((act[l] && cval) ? aq[l].y * kappa : 0.0, coef[l], coef[NPL + l]);
+                // none ends at position 0
+                dl[l] = act[l] ? (aq[l].y * e[l].x * pv[l].x - (tt >= 1 ? aq[l].x * pv[l].y * e[l].y : 0.0)) * kappa : 0.0;
+            }
+            const bool lowh = pofs == 0;
+            const double k13 = lowh ? coef[1] : coef[3], k2 = lowh ? coef[2] : 0.0, k3 = lowh ? coef[3] : 0.0;
+            dn[0] = fma(k13, pv[0].y, dn[0]);
+            dn[1] = fma(k2, pv[0].y, dn[1]);
+            dn[2] = fma(k3, pv[0].y, dn[2]);
+            dn[0] = fma(k2, pv[1].y, dn[0]);
+            dn[1] = fma(k3, pv[1].y, dn[1]);
+            double s01, s23;
+            both_halves(dl[0] + dl[1], s01, s23);
+            const double r0 = lowh ? R : R + s01, r1 = r0 + dl[0];
+            sR += (act[0] ? r0 : 0.0) + (act[1] ? r1 : 0.0);
+            R = (R + s01) + s23;
+#pragma unroll
+            for (int l = 0; l < NPL; ++l) {
+                const int i = pofs + l;
+                const bool on = act[l] && cval;
+                double *rdst = on ? ring + (r - 1 - i) * RS + c : ring + RTOT + lane;
+                *rdst = pv[l].y;
+                float *dst = on ? gout + (unsigned)(t - 1 - i) * (unsigned)C : sink;
+                *dst = (float)(l == 0 ? r0 : r1);
+            }
+        } else if (whole) {
+            // 64 labels per lane group: every lane holds all four positions of its label
             float *gp = gseq + ((unsigned)(t - 1) * (unsigned)C + (unsigned)cc);
             double *rw = ring + (r - 1) * RS + cc;
 #pragma unroll
-            for (int i = 0; i < MB; ++i) {
-                coef[i] = aq[i].y * kappa;  // q_t(c) kappa
+            for (int i = 0; i < NPL; ++i) {
+                coef[i] = aq[i].y * kappa;
 #pragma unroll
                 for (int jn = 0; jn < i; ++jn) dn[i - 1 - jn] = fma(coef[i], pv[jn].y, dn[i - 1 - jn]);
                 rw[-i * RS] = pv[i].y;
-                // a segment of this label starts at the position (z p, z = q ES) / ends at it (a b, b = v IE)
                 const double d = (aq[i].y * e[i].x * pv[i].x - aq[i].x * pv[i].y * e[i].y) * kappa;
                 gp[-i * C] = (float)R;
                 sR += R;
                 R += d;
             }
-#pragma unroll
-            for (int tr = 0; tr < TRN; ++tr) {
-                const double a = aA[tr] * kappa;
-#pragma unroll
-                for (int tc = 0; tc < TRN; ++tc)
-                    accT[tr][tc] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, bB[tc], accT[tr][tc], 0, 0, 0);
-            }
         } else {
-            // a short block (at most two at the part's upper end, the last one, the one with position 0):
-            // beyond its end the stores go to the pad and to the sink
 #pragma unroll
-            for (int i = 0; i < MB; ++i) {
+            for (int i = 0; i < NPL; ++i) {
                 const bool on = i < nb;
                 const int tt = t - 1 - i;
                 coef[i] = (cval && on) ? aq[i].y * kappa : 0.0;
@@ -493,20 +557,23 @@ __global__ __launch_bounds__(64, mg_waves_per_simd(CT, NKW)) void k_mg_wave(Para
                 for (int jn = 0; jn < i; ++jn) dn[i - 1 - jn] = fma(cg, pv[jn].y, dn[i - 1 - jn]);
                 double *rdst = (on && writer) ? ring + (r - 1 - i) * RS + c : ring + RTOT + lane;
                 *rdst = pv[i].y;
-                // none ends at position 0
                 const double d = on ? (aq[i].y * e[i].x * pv[i].x - (tt >= 1 ? aq[i].x * pv[i].y * e[i].y : 0.0)) * kappa : 0.0;
                 float *dst = (on && writer) ? gout + (unsigned)tt * (unsigned)C : sink;
                 *dst = (float)R;
                 sR += on ? R : 0.0;
                 R += d;
             }
-            const bool on = pj < nb;
+        }
+        {
+            // transition statistics on the matrix cores; label rows beyond C are never stored, positions beyond a
+            // short block's end must count nothing
+            const bool on = whole || pj < nb;
 #pragma unroll
             for (int tr = 0; tr < TRN; ++tr) {
                 const double a = on ? aA[tr] * kappa : 0.0;
 #pragma unroll
                 for (int tc = 0; tc < TRN; ++tc)
-                    accT[tr][tc] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, on ? bB[tc] : 0.0, accT[tr][tc], 0, 0, 0);
+                    accT[tr][tc] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, bB[tc], accT[tr][tc], 0, 0, 0);
             }
         }
         // ---- the next block's rows
@@ -519,14 +586,16 @@ __global__ __launch_bounds__(64, mg_waves_per_simd(CT, NKW)) void k_mg_wave(Para
         for (int q = 0; q < 4; ++q) vc[q] = base[q * RS];
 #pragma unroll
         for (int jg = 0; jg < NK; jg += 4) {
-            if (jg + 4 < NK) {
 #pragma unroll
-                for (int q = 0; q < 4; ++q) vn[q] = base[(jg + 4 + q) * RS];
+            for (int q = 0; q < 4; ++q)
+                if (jg + 4 + q < NK) vn[q] = base[(jg + 4 + q) * RS];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {  // distance g*NK + jg + q from the newest (NK need not be a multiple of 4)
+                if (jg + q < NK) {
+#pragma unroll
+                    for (int i = 0; i < MB; ++i) dx[jg + q + i] = fma(coef[i], vc[q], dx[jg + q + i]);
+                }
             }
-#pragma unroll
-            for (int q = 0; q < 4; ++q)  // distance g*NK + jg + q from the newest
-#pragma unroll
-                for (int i = 0; i < MB; ++i) dx[jg + q + i] = fma(coef[i], vc[q], dx[jg + q + i]);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int q = 0; q < 4; ++q) vc[q] = vn[q];
@@ -539,6 +608,11 @@ __global__ __launch_bounds__(64, mg_waves_per_simd(CT, NKW)) void k_mg_wave(Para
     // durations; they are combined through LDS in a fixed order (own strip, then the neighbour's overlap, then
     // the in-block terms) and scaled by W[k,c].
     lds_wave_fence();
+    if (SPLIT) {  // what the two halves of the wave gathered separately
+#pragma unroll
+        for (int jj = 0; jj < MB - 1; ++jj) dn[jj] = add_across_32(dn[jj]);
+        sR = add_across_32(sR);
+    }
     double *tmp = ring;  // [KW + MB - 1][CT], row m = duration m + 1
     {
         double *tl = tmp + g * NK * CT + c;
