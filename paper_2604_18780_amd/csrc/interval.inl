@@ -228,6 +228,19 @@ struct WaveWin {
         lds_wave_fence();
     }
 
+    // The same for the KW live rows only (newest row r; the window lies behind it in a forward scan, above it in a
+    // backward one): the slack rows hold nothing that is read before it is written again.
+    template <bool BWD>
+    static __device__ __forceinline__ void rescale_live(double *ring, int g, int c, bool cval, int r, int sft)
+    {
+        if (cval) {
+            double *q = ring + ((BWD ? r : r - (KW - 1)) + g) * RS + c;
+#pragma unroll 8
+            for (int row = g; row < KW; row += GW, q += GW * RS) *q = fmin(ldexp(*q, sft), DBL_MAX);
+        }
+        lds_wave_fence();
+    }
+
     // Move the live window (newest row r) back to the start of the buffer; returns the new r.
     // Chunk order keeps the sources ahead of the stores.
     template <bool BWD>

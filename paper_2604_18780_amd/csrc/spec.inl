@@ -185,11 +185,20 @@ __device__ __forceinline__ void spec_task(const Params &p, double *lds_raw, cons
         const bool inchunk = keep && (BWD ? t <= tstart : t >= tstart);  // blocks end at tstart: holds for the whole block
         const bool boundary = BWD ? (t & Jm) == 0 : (t1 & Jm) == 0;
         if (__builtin_expect(boundary, 0)) {
-            double prevsum = 0.0;
-            for (int i = 0; i < CT; ++i) prevsum += yv[i];
+            // sum of the newest message vector (each half of the wave its half of the labels, as in the
+            // transition product); only its exponent is used, and any power of two would do: scaling is exact
+            double s0 = 0.0, s1 = 0.0;
+#pragma unroll
+            for (int o = 0; o < HC; o += 2) {
+                const double2 vv = ys[o >> 1];
+                s0 += vv.x;
+                s1 += vv.y;
+            }
+            double prevsum = s0 + s1;
+            if (H == 2) prevsum = add_across_32(prevsum);
             const int ex = safe_exponent(prevsum);
             Y += (double)ex;
-            G::rescale(ring, g, c, cval, dnx - ex);
+            G::template rescale_live<BWD>(ring, g, c, cval, r, dnx - ex);
             jnx += BWD ? -1 : 1;
             dnx = nbdelta(jnx);
         }
