@@ -449,13 +449,7 @@ __global__ __launch_bounds__(64, mg_waves_per_simd(CT, NKW)) void k_mg_wave(Para
         const int nb = min(min(t - ta, MB), ((t - 1) & Jm) + 1);
         if (__builtin_expect((t & Jm) == 0, 0)) {
             // the scan stepped into a new scaling block here: same shift of the live window, read off its scales
-            if (cval) {
-                const int sft = nd - (int)(yb - ybPrev);
-                double *q = ring + (r + g) * RS + c;
-#pragma unroll 8
-                for (int row = g; row < KW; row += G::GW, q += G::GW * RS) *q = fmin(ldexp(*q, sft), DBL_MAX);
-            }
-            lds_wave_fence();
+            G::template rescale_live<true>(ring, g, c, cval, r, nd - (int)(yb - ybPrev));
             ybPrev = yb;
             kappa = kappa_of();
         }
