@@ -201,7 +201,8 @@ int semicrf_fwd_bwd(const float *emis, const int32_t *lengths, const float *tran
  * ends.  The call allocates and frees nothing (no hipMalloc, hipFree or allocating library
  * routine); the first call on a device looks the array's address up once.  Inputs, outputs,
  * results and errors are those of semicrf_fwd_bwd; sizes whose semicrf_workspace_bytes(B, T, K, C,
- * ckpt_interval, 1) exceeds the limit return SEMICRF_EWORKSPACE before anything is launched.
+ * ckpt_interval, want_grad) exceeds the limit return SEMICRF_EWORKSPACE before anything is launched
+ * (want_grad as the flags ask: 1, 2 with SEMICRF_MARGINALS_INTERVAL, plus 8 with SEMICRF_LOW_MEMORY).
  * All calls on one GPU share that GPU's array: calls that may overlap in time on one GPU (two
  * streams, two host threads) race on it and must be serialised by the caller.  Nothing in the
  * array has to survive between calls and nothing in it is assumed zero: every call writes what

@@ -400,7 +400,7 @@ __global__ __launch_bounds__(64, mg_waves_per_simd(CT, NKW)) void k_mg_wave(Para
     double ya, yb;                  // stored scales of the position just below tfrom (forward, backward)
     int nd;                         // exponent step of this lane's label at the scaling-block boundary tfrom
     // Byte offsets from the (wave-uniform) starts of the interval's rows fit 32 bits: a slot has Delta*C < 2^27
-    // pairs (the plan's limits), a sequence fewer than 2^30 position-label pairs (checked by the caller).
+    // pairs (the plan's limits), a sequence fewer than 2^31 position-label pairs (checked by the caller).
     const char *const arb = (const char *)arow, *const brb = (const char *)brow;
     const char *const eib = (const char *)(p.EI + (row0 + t0) * C);
     const unsigned C16 = (unsigned)C * 16u, cc16 = (unsigned)cc * 16u;
