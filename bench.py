@@ -387,6 +387,15 @@ def main():
                            "accepted_by": accepted_summary(a)},
             "emission_bytes": B * T * C * 4}
         del pl
+        # the two routes of the marginals on the same workload (the default takes the stored rows where planned)
+        pi = Problem(w, args.ckpt_interval, sb.SEMICRF_CENTER | sb.SEMICRF_MARGINALS_INTERVAL, dev)
+        m, st, a, e = pi.time_fwd_bwd(few, 2)
+        rec["marginal_routes"] = {
+            "default": {"ms_per_step": ms_step, "marginal_stage_ms": stage[2], "scans_ms": stage[1],
+                        "workspace_bytes": pb.ws_bytes},
+            "per_interval_recurrence": {"ms_per_step": m, "marginal_stage_ms": st[2], "scans_ms": st[1],
+                                        "workspace_bytes": pi.ws_bytes}}
+        del pi
         del pb, emis, lengths, trans, dur, ws
         torch.cuda.empty_cache()
         # the other configurations, each whole
