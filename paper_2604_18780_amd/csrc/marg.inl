@@ -335,7 +335,7 @@ __global__ __launch_bounds__(64, mg_waves_per_simd(CT, NKW)) void k_mg_wave(Para
     } else if (tb == t1) {  // the state the backward task started from
         const double *ck = p.ckB + ((size_t)b * (N + 1) + iv + 1) * ((size_t)KC + C);
         const int tm = t1 % K;
-        // (the loops below are unrolled so that the loads of several rounds are in flight together)
+        // (the loops below are unrolled so that the loads of several iterations are in flight together)
 #pragma unroll 8
         for (int i = lane; i < KC; i += 64) {
             const int sl = i / C, col = i % C;
