@@ -6,7 +6,7 @@
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ void tables_body(const Params &p)
 {
-    __shared__ double red[NT];
+    __shared__ double red[2 * (NT / 64)];
     const int tid = threadIdx.x;
     const int KC = p.K * p.C, CC = p.C * p.C;
     if (!p.dur || (!p.trans && !p.trans3)) {  // prefix sums only: growth is bounded by the emissions alone
@@ -29,20 +29,21 @@ __device__ __forceinline__ void tables_body(const Params &p)
             mxt = fmax(mxt, v);
         }
     }
-    red[tid] = mxd;
-    __syncthreads();
-    if (tid == 0) {
-        double m = red[0];
-        for (int i = 1; i < NT; ++i) m = fmax(m, red[i]);
-        p.tabmax[0] = m;
+    // maxima: inside each wave by shuffles, then over the waves (any order)
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        mxd = fmax(mxd, __shfl_xor(mxd, off));
+        mxt = fmax(mxt, __shfl_xor(mxt, off));
+    }
+    if ((tid & 63) == 0) {
+        red[tid >> 6] = mxd;
+        red[NT / 64 + (tid >> 6)] = mxt;
     }
     __syncthreads();
-    red[tid] = mxt;
-    __syncthreads();
-    if (tid == 0) {
-        double m = red[0];
-        for (int i = 1; i < NT; ++i) m = fmax(m, red[i]);
-        p.tabmax[1] = m;
+    if (tid < 2) {
+        double m = red[tid * (NT / 64)];
+        for (int i = 1; i < NT / 64; ++i) m = fmax(m, red[tid * (NT / 64) + i]);
+        p.tabmax[tid] = m;
     }
 }
 
@@ -53,7 +54,7 @@ template <int ET>
 __device__ __forceinline__ void colsum_body(const Params &p, const int b, const int ch)
 {
     __shared__ double red[NT];
-    __shared__ double redm[NT];
+    __shared__ double redm[2 * (NT / 64)];
     const int tid = threadIdx.x;
     const int C = p.C, L = seq_len(p, b);
     const int u0 = ch * PREP_CH;
@@ -79,10 +80,18 @@ __device__ __forceinline__ void colsum_body(const Params &p, const int b, const 
             if (p.proj_end) mpe = fmax(mpe, fabs((double)p.proj_end[o + (size_t)u * C + c]));
         }
     }
-    __shared__ double redp[NT];
+    // the maxima first inside each wave (threads that took no row hold zeros; a maximum does not care for order)
+    double mp = mps + mpe;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        mx = fmax(mx, __shfl_xor(mx, off));
+        mp = fmax(mp, __shfl_xor(mp, off));
+    }
     red[tid] = acc;
-    redm[tid] = mx;
-    redp[tid] = mps + mpe;
+    if ((tid & 63) == 0) {
+        redm[tid >> 6] = mx;
+        redm[NT / 64 + (tid >> 6)] = mp;
+    }
     __syncthreads();
     if (tid < C) {
         double s = 0.0;
@@ -90,11 +99,12 @@ __device__ __forceinline__ void colsum_body(const Params &p, const int b, const 
         p.chsum[((size_t)b * p.NCH + ch) * C + tid] = s;
     }
     if (tid == 0) {
-        double m = 0.0, mp = 0.0;
-        for (int i = 0; i < R * C; ++i) m = fmax(m, redm[i]);
-        if (p.proj_start || p.proj_end)
-            for (int i = 0; i < R * C; ++i) mp = fmax(mp, redp[i]);
-        p.chmax[(size_t)b * p.NCH + ch] = m + 2.0 * mp;  // |start| + |end| bounded by twice the larger sum
+        double m = 0.0, q = 0.0;
+        for (int i = 0; i < NT / 64; ++i) {
+            m = fmax(m, redm[i]);
+            q = fmax(q, redm[NT / 64 + i]);
+        }
+        p.chmax[(size_t)b * p.NCH + ch] = m + 2.0 * q;  // |start| + |end| bounded by twice the larger sum
     }
 }
 
@@ -114,16 +124,17 @@ __global__ __launch_bounds__(NT) void k_colsum(Params p)
 // Eq. 1, stage 2: nu = mean over valid positions; chunk sums -> exclusive
 // offsets of the centred prefix sum; scaling block length J.  grid B.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(NT) void k_prep_seq(Params p)
+constexpr int PREP_NT = 1024;  // one workgroup per sequence: as many threads as a workgroup may have
+__global__ __launch_bounds__(PREP_NT) void k_prep_seq(Params p)
 {
-    // The chunks are split into G = NT/C contiguous ranges, one per thread group; range sums
+    // The chunks are split into G = PREP_NT/C contiguous ranges, one per thread group; range sums
     // are combined in range order (a fixed order for a given problem).
-    __shared__ double gsum[NT];
-    __shared__ double red[NT];
-    __shared__ double nu_s[NT];
+    __shared__ double gsum[PREP_NT];
+    __shared__ double red[PREP_NT / 64];
+    __shared__ double nu_s[256];  // C <= 256
     const int b = blockIdx.x, tid = threadIdx.x;
     const int C = p.C, L = seq_len(p, b), NCH = p.NCH;
-    const int G = NT / C;
+    const int G = PREP_NT / C;
     const int g = tid / C, c = tid % C;
     const bool act = g < G;
     const int per = (NCH + G - 1) / G;
@@ -159,12 +170,14 @@ __global__ __launch_bounds__(NT) void k_prep_seq(Params p)
     // bound on |f - nu|
     double fm = 0.0;
 #pragma unroll 4
-    for (int ch = tid; ch < NCH; ch += NT) fm = fmax(fm, p.chmax[(size_t)b * NCH + ch]);
-    red[tid] = fm;
+    for (int ch = tid; ch < NCH; ch += PREP_NT) fm = fmax(fm, p.chmax[(size_t)b * NCH + ch]);
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) fm = fmax(fm, __shfl_xor(fm, off));  // a maximum: any order
+    if ((tid & 63) == 0) red[tid >> 6] = fm;
     __syncthreads();
     if (tid == 0) {
         fm = 0.0;
-        for (int i = 0; i < NT; ++i) fm = fmax(fm, red[i]);
+        for (int i = 0; i < PREP_NT / 64; ++i) fm = fmax(fm, red[i]);
         double nm = 0.0, npi = 0.0;
         for (int i = 0; i < C; ++i) {
             nm = fmax(nm, fabs(nu_s[i]));

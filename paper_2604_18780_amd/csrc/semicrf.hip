@@ -123,7 +123,7 @@ template <int ET>
 int launch_prep_et(const Params &p, hipStream_t st)
 {
     hipLaunchKernelGGL(k_colsum<ET>, dim3(1 + p.NCH * p.B), dim3(NT), 0, st, p);
-    hipLaunchKernelGGL(k_prep_seq, dim3(p.B), dim3(NT), 0, st, p);
+    hipLaunchKernelGGL(k_prep_seq, dim3(p.B), dim3(PREP_NT), 0, st, p);
     if (p.logpair || p.proj_start || p.proj_end || p.pi_start || p.pi_end)
         hipLaunchKernelGGL((k_prefix<true, ET>), dim3(p.NCH, p.B), dim3(NT), 0, st, p);
     else
