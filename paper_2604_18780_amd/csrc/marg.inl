@@ -335,11 +335,13 @@ __global__ __launch_bounds__(64, mg_waves_per_simd(CT, NKW)) void k_mg_wave(Para
     } else if (tb == t1) {  // the state the backward task started from
         const double *ck = p.ckB + ((size_t)b * (N + 1) + iv + 1) * ((size_t)KC + C);
         const int tm = t1 % K;
-        // (the loops below are unrolled so that the loads of several iterations are in flight together)
+        if (cval) {  // lane (g, c): the window rows at distances g, g + GW, ... of its label (no index divisions)
 #pragma unroll 8
-        for (int i = lane; i < KC; i += 64) {
-            const int sl = i / C, col = i % C;
-            ring[(r + G::template slot_dist<true>(sl, tm, K)) * RS + col] = ck[i];
+            for (int d = g; d < K; d += G::GW) {
+                int sl = tm + d;  // checkpoint slot of the position at that distance
+                sl -= sl >= K ? K : 0;
+                ring[(r + d) * RS + c] = ck[(size_t)sl * C + c];
+            }
         }
     } else {
         // inside the interval: the rows v_tb .. v_{tb+K-1} as the backward task stored them (a part is at least
@@ -631,8 +633,10 @@ __global__ __launch_bounds__(64, mg_waves_per_simd(CT, NKW)) void k_mg_wave(Para
         lds_wave_fence();
     }
     double *pD = p.partD + part * KC;
+    if (cval) {
 #pragma unroll 8
-    for (int i = lane; i < KC; i += 64) pD[i] = p.W[i] * tmp[(i / C) * CT + i % C];
+        for (int k = g; k < K; k += G::GW) pD[(size_t)k * C + c] = p.W[(size_t)k * C + c] * tmp[k * CT + c];
+    }
     double *pT = p.partTr + part * CC;
 #pragma unroll
     for (int tr = 0; tr < TRN; ++tr)

@@ -110,10 +110,13 @@ __device__ __forceinline__ void spec_task(const Params &p, double *lds_raw, cons
     // checkpoint layout: message of position t' at slot t' mod K
     auto record = [&](const int t, double *ck, double *ckY) {
         const int tm = t % K;
-        for (int i = lane; i < KC; i += 64) {
-            const int sl = i / C, col = i % C;
-            const int d = G::template slot_dist<BWD>(sl, tm, K);
-            ck[i] = ring[(BWD ? r + d : r - d) * RS + col];
+        if (cval) {  // lane (g, c): the window rows at distances g, g + GW, ... of its label (no index divisions)
+#pragma unroll 4
+            for (int d = g; d < K; d += G::GW) {
+                int sl = BWD ? tm + d : tm - d;  // slot of the position at that distance
+                sl += BWD ? (sl >= K ? -K : 0) : (sl < 0 ? K : 0);
+                ck[(size_t)sl * C + c] = ring[(BWD ? r + d : r - d) * RS + c];
+            }
         }
         if (lane < C) ck[KC + lane] = yv[lane];
         if (lane == 0) *ckY = Y;
