@@ -188,6 +188,13 @@ __device__ __forceinline__ double add_across_32(double v)
     return __hiloint2double((int)b[0], (int)a[0]) + __hiloint2double((int)b[1], (int)a[1]);
 }
 
+// A stored row (two doubles) that a later kernel reads once: written past the caches.
+__device__ __forceinline__ void store_row(double2 *dst, const double a, const double b)
+{
+    typedef double d2_t __attribute__((ext_vector_type(2)));
+    __builtin_nontemporal_store(d2_t{a, b}, (d2_t *)dst);
+}
+
 // The value lanes 0..31 hold (-> lo_half) and the one lanes 32..63 hold (-> hi_half), lane l paired with lane
 // l + 32, both delivered to both lanes.
 __device__ __forceinline__ void both_halves(const double v, double &lo_half, double &hi_half)

@@ -257,10 +257,7 @@ __device__ __forceinline__ void spec_task(const Params &p, double *lds_raw, cons
                 qn[i] = q;
                 r += BWD ? -1 : 1;
                 if (writer) ring[r * RS + c] = q;
-                if (keep) {
-                    typedef double d2_t __attribute__((ext_vector_type(2)));
-                    __builtin_nontemporal_store(d2_t{y, q}, (d2_t *)(rowp + i * rstep));
-                }
+                if (keep) store_row(rowp + i * rstep, y, q);
                 lds_wave_fence();
             }
         } else {

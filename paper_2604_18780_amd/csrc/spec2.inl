@@ -123,10 +123,13 @@ __device__ __forceinline__ void spec2_task(const Params &p, double *lds_raw, con
         // checkpoint layout: message of position t' at slot t' mod K
         auto record = [&](const int tt, double *ck, double *ckY) {
             const int tm = tt % K;
-            for (int i = lane; i < KC; i += 64) {
-                const int sl = i / C, col = i % C;
-                const int d = G::template slot_dist<BWD>(sl, tm, K);
-                ck[i] = ring[(BWD ? r + d : r - d) * RS + col];
+            if (cval) {  // lane (g, c): the window rows at distances g, g + GW, ... of its label (no index divisions)
+#pragma unroll 4
+                for (int d = g; d < K; d += G::GW) {
+                    int sl = BWD ? tm + d : tm - d;  // slot of the position at that distance
+                    sl += BWD ? (sl >= K ? -K : 0) : (sl < 0 ? K : 0);
+                    ck[(size_t)sl * C + c] = ring[(BWD ? r + d : r - d) * RS + c];
+                }
             }
             if (lane < C) ck[KC + lane] = yv[lane];
             if (lane == 0) *ckY = Y;
@@ -222,11 +225,11 @@ __device__ __forceinline__ void spec2_task(const Params &p, double *lds_raw, con
                     qn[i] = q;
                     if (writer) ring[(BWD ? r - 1 - i : r + 1 + i) * RS + c] = q;
                     if (!BWD && inchunk && t + 1 + i < hi) {
-                        if (writer) aloc[(size_t)(t + 1 + i - lo) * C + c] = make_double2(y, q);
+                        if (writer) store_row(aloc + (size_t)(t + 1 + i - lo) * C + c, y, q);
                         if (lane == 0) alocY[t + 1 + i - lo] = Y - Yrec;
                     }
                     if (BWD && inchunk) {  // position t - 1 - i of [lo, hi)
-                        if (writer) aloc[(size_t)(t - 1 - i - lo) * C + c] = make_double2(y, q);
+                        if (writer) store_row(aloc + (size_t)(t - 1 - i - lo) * C + c, y, q);
                         if (lane == 0) alocY[t - 1 - i - lo] = Y - Yrec;
                     }
                     lds_wave_fence();
