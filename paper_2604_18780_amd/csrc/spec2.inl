@@ -185,8 +185,17 @@ __device__ __forceinline__ void spec2_task(const Params &p, double *lds_raw, con
                 qp[i] = ring[(BWD ? r + i : r - i) * RS + c];   // message of the position i before this block
             }
             if (__builtin_expect(at_boundary(t), 0)) {
+                // sum of the newest message vector, one entry per lane, added up across the wave (the same value in
+                // every lane; only its exponent is used, and any power of two would do: scaling is exact)
+                // (a short vector is summed faster entry by entry)
                 double prevsum = 0.0;
-                for (int i = 0; i < CT; ++i) prevsum += yv[i];
+                if (CT >= 32) {
+                    prevsum = lane < CT ? yv[lane] : 0.0;
+#pragma unroll
+                    for (int off = 1; off < 64; off <<= 1) prevsum += __shfl_xor(prevsum, off);
+                } else {
+                    for (int i = 0; i < CT; ++i) prevsum += yv[i];
+                }
                 const int ex = safe_exponent(prevsum);
                 Y += (double)ex;
                 if (lane == 0) exv[0] = ex;
