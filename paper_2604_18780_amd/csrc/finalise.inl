@@ -195,26 +195,56 @@ __device__ __forceinline__ void fin_params_body(const Params &p, const int blk)
     const int o = tid % FIN_PO, g = tid / FIN_PO;
     const int idx = blk * FIN_PO + o;
     const bool ok = idx < CC + KC;
+    // The number of partial sums of a sequence is fetched once per sequence by the first threads, and the
+    // sequences are taken four at a time: the first partial sum each thread group takes of each of them is loaded
+    // before any is added (many short sequences would otherwise cost one memory latency each), the rest, for
+    // sequences with more partial sums than thread groups, in four chains as before.  Fixed order throughout.
+    constexpr int UB = 4;
+    __shared__ int npart[NT];
+    if (tid < p.B) {
+        const int Ds = stat_delta(p, tid);
+        npart[tid] = (p.hdr[tid].L + Ds - 1) / Ds;
+    }
+    __syncthreads();
+    auto count = [&](const int b) {
+        if (b < NT) return npart[b];
+        const int Ds = stat_delta(p, b);
+        return (p.hdr[b].L + Ds - 1) / Ds;
+    };
+    const size_t stride = idx < CC ? (size_t)CC : (size_t)KC;
+    const double *q0 = idx < CC ? p.partTr + idx : p.partD + (idx - CC);  // partial sum i of sequence b at (b*N + i)*stride
     double acc = 0.0;
     if (ok) {
-        for (int b = 0; b < p.B; ++b) {
-            const int L = p.hdr[b].L;
-            const int Ds = stat_delta(p, b);
-            const int nint = (L + Ds - 1) / Ds;
-            const double w = p.grad_logz ? (double)p.grad_logz[b] : 1.0;
-            const size_t stride = idx < CC ? (size_t)CC : (size_t)KC;
-            const double *q = idx < CC ? p.partTr + ((size_t)b * N) * CC + idx
-                                       : p.partD + ((size_t)b * N) * KC + (idx - CC);
-            double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
-            int i = g;
-            for (; i + 3 * NG < nint; i += 4 * NG) {
-                s0 += q[(size_t)i * stride];
-                s1 += q[(size_t)(i + NG) * stride];
-                s2 += q[(size_t)(i + 2 * NG) * stride];
-                s3 += q[(size_t)(i + 3 * NG) * stride];
+        for (int b0 = 0; b0 < p.B; b0 += UB) {
+            double v[UB], w[UB];
+            int nint[UB];
+            bool more = false;
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
+                const int b = b0 + u;
+                nint[u] = b < p.B ? count(b) : 0;
+                w[u] = (b < p.B && p.grad_logz) ? (double)p.grad_logz[b] : 1.0;
+                v[u] = g < nint[u] ? q0[((size_t)b * N + g) * stride] : 0.0;
+                more = more || nint[u] > NG;
             }
-            for (; i < nint; i += NG) s0 += q[(size_t)i * stride];
-            acc = fma(w, (s0 + s1) + (s2 + s3), acc);
+            if (more) {
+#pragma unroll
+                for (int u = 0; u < UB; ++u) {
+                    const double *q = q0 + ((size_t)(b0 + u) * N) * stride;
+                    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+                    int i = g + NG;
+                    for (; i + 3 * NG < nint[u]; i += 4 * NG) {
+                        s0 += q[(size_t)i * stride];
+                        s1 += q[(size_t)(i + NG) * stride];
+                        s2 += q[(size_t)(i + 2 * NG) * stride];
+                        s3 += q[(size_t)(i + 3 * NG) * stride];
+                    }
+                    for (; i < nint[u]; i += NG) s0 += q[(size_t)i * stride];
+                    v[u] += (s0 + s1) + (s2 + s3);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < UB; ++u) acc = fma(w[u], v[u], acc);
         }
     }
     red[tid] = acc;
